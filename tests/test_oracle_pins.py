@@ -1,0 +1,333 @@
+"""Pins for the CPU oracle: each test checks it against something other than itself
+(brute force from the edge list, dense-matrix closed forms with a library matmul,
+hand-computed fixtures, algebraic identities and invariants of the method)."""
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+import synth
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def tiny_graph(n, m, seed, int_vals=False, d=5):
+    rng = np.random.default_rng(seed)
+    src = rng.integers(0, n, size=m)
+    dst = rng.integers(0, n, size=m)
+    ok = src != dst
+    src, dst = src[ok].astype(np.int32), dst[ok].astype(np.int32)
+    keys = np.unique(synth.edge_keys(src, dst))
+    src, dst = synth.keys_to_edges(keys)
+    if int_vals:       # few distinct values => many exact ties
+        X = rng.integers(-2, 3, size=(n, d)).astype(np.float32)
+    else:
+        X = rng.standard_normal((n, d)).astype(np.float32)
+    return src, dst, X
+
+
+def brute_select(n, src, dst, X, is_min):
+    """Second, independent implementation straight from the edge list (no CSR)."""
+    d = X.shape[1]
+    alpha = np.zeros((n, d), np.float32)
+    arg = -np.ones((n, d), np.int32)
+    for v in range(n):
+        nb = sorted(int(s) for s, t in zip(src, dst) if t == v)
+        for i in range(d):
+            if not nb:
+                continue
+            vals = [X[u, i] for u in nb]
+            best = min(vals) if is_min else max(vals)
+            alpha[v, i] = best
+            arg[v, i] = min(u for u in nb if X[u, i] == best)
+    return alpha, arg
+
+
+@pytest.mark.parametrize("seed", range(6))
+@pytest.mark.parametrize("is_min", [False, True])
+def test_select_matches_brute_force(seed, is_min):
+    n = 30 + seed
+    src, dst, X = tiny_graph(n, 150, seed, int_vals=(seed % 2 == 0))
+    rp, col = synth.in_csr_from_edges(n, src, dst)
+    a, g = oracle.agg_select(rp, col, X, is_min=is_min)
+    a2, g2 = brute_select(n, src, dst, X, is_min)
+    assert np.array_equal(a, a2)
+    assert np.array_equal(g, g2)
+
+
+def _parse_cases(path):
+    cases, cur = [], None
+    for line in open(path):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        tok = line.split()
+        if tok[0] in ("case", "graph"):
+            cur = dict(name=tok[1], m={})
+            cases.append(cur)
+        elif tok[0] == "m":
+            cur["m"][int(tok[1])] = [float(x) for x in tok[2:]]
+        else:
+            cur[tok[0]] = tok[1:]
+    return cases
+
+
+def test_select_golden_ties():
+    for c in _parse_cases(os.path.join(GOLD, "select_ties.txt")):
+        nb = [int(x) for x in c["in"]]
+        n = 8
+        X = np.full((n, 3), 99.0, np.float32)        # non-neighbours hold values that would win
+        X[:, 2] = -99.0
+        for u, row in c["m"].items():
+            X[u] = row
+        src = np.array(nb, np.int32)
+        dst = np.zeros(len(nb), np.int32)
+        rp, col = synth.in_csr_from_edges(n, src, dst)
+        for is_min, kv, ki in ((False, "max", "argmax"), (True, "min", "argmin")):
+            a, g = oracle.agg_select(rp, col, X, is_min=is_min)
+            assert np.array_equal(a[0], np.array(c[kv], np.float32)), c["name"]
+            assert np.array_equal(g[0], np.array(c[ki], np.int32)), c["name"]
+
+
+def test_min_is_negated_max_of_negation():
+    src, dst, X = tiny_graph(40, 200, 11, int_vals=True)
+    rp, col = synth.in_csr_from_edges(40, src, dst)
+    amin, gmin = oracle.agg_select(rp, col, X, is_min=True)
+    amax, gmax = oracle.agg_select(rp, col, -X, is_min=False)
+    assert np.array_equal(amin, -amax + 0.0)
+    assert np.array_equal(gmin, gmax)
+
+
+def dense_adj(n, src, dst):
+    A = np.zeros((n, n), np.float64)
+    A[dst, src] = 1.0           # row v, column u for edge u -> v
+    return A
+
+
+def test_sum_and_mean_match_dense_matmul():
+    n = 35
+    src, dst, X = tiny_graph(n, 180, 3)
+    rp, col = synth.in_csr_from_edges(n, src, dst)
+    A = dense_adj(n, src, dst)
+    ref = A @ X.astype(np.float64)
+    assert np.allclose(oracle.agg_sum(rp, col, X), ref, rtol=1e-6, atol=1e-6)
+    deg = np.maximum(A.sum(1, keepdims=True), 1.0)
+    assert np.allclose(oracle.agg_sum(rp, col, X, mean=True), ref / deg, rtol=1e-6, atol=1e-6)
+
+
+def test_gcn_sym_matches_dense_normalised_adjacency():
+    n = 35
+    src, dst, X = tiny_graph(n, 180, 4)
+    rp, col = synth.in_csr_from_edges(n, src, dst)
+    A = dense_adj(n, src, dst) + np.eye(n)
+    dinv = 1.0 / np.sqrt(A.sum(1))              # row sums = indeg + 1
+    ref = (dinv[:, None] * A * dinv[None, :]) @ X.astype(np.float64)
+    assert np.allclose(oracle.agg_gcn_sym(rp, col, X), ref, rtol=1e-6, atol=1e-6)
+
+
+def test_gcn_sym_golden_star_and_path():
+    for c in _parse_cases(os.path.join(GOLD, "gcn_star_path.txt")):
+        h = np.array([float(x) for x in c["h"]], np.float32)[:, None]
+        e = [tuple(int(t) for t in p.split(">")) for p in c["edges"]]
+        src = np.array([p[0] for p in e], np.int32)
+        dst = np.array([p[1] for p in e], np.int32)
+        rp, col = synth.in_csr_from_edges(h.shape[0], src, dst)
+        got = oracle.agg_gcn_sym(rp, col, h)[:, 0]
+        want = np.array([float(x) for x in c["a"]])
+        assert np.allclose(got, want, rtol=2e-7, atol=0), c["name"]
+
+
+def test_linear_matches_library_matmul_and_is_not_transposed():
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal((17, 13)).astype(np.float32)
+    W = rng.standard_normal((13, 7)).astype(np.float32)
+    b = rng.standard_normal(7).astype(np.float32)
+    ref = x.astype(np.float64) @ W.astype(np.float64) + b
+    for prec, tol in (("f64", 1e-7), ("f32", 2e-6)):
+        y = oracle.linear(x, W, b, relu=False, precision=prec)
+        assert np.allclose(y, ref, rtol=tol, atol=tol * 10)
+        yr = oracle.linear(x, W, b, relu=True, precision=prec)
+        assert np.allclose(yr, np.maximum(ref, 0), rtol=tol, atol=tol * 10)
+        assert not np.signbit(yr).any()          # ReLU emits +0 only
+
+
+def test_linear_exact_on_small_integers():
+    rng = np.random.default_rng(6)
+    x = rng.integers(-8, 9, size=(9, 20)).astype(np.float32)
+    W = rng.integers(-8, 9, size=(20, 6)).astype(np.float32)
+    ref = (x.astype(np.int64) @ W.astype(np.int64)).astype(np.float32)
+    for prec in ("f64", "f32"):
+        assert np.array_equal(oracle.linear(x, W, None, False, prec), ref)
+
+
+def test_linear_precision_modes_differ_where_rounding_order_says_so():
+    # (1 + 2^-12)^2 = 1 + 2^-11 + 2^-24.  An fp32 chain rounds the first product to 1 + 2^-11
+    # (tie to even) and the second step cancels it exactly; fp64 accumulation keeps 2^-24.
+    a = np.float32(1 + 2.0 ** -12)
+    x = np.array([[a, -1.0]], np.float32)
+    W = np.array([[a], [np.float32(1 + 2.0 ** -11)]], np.float32)
+    assert oracle.linear(x, W, None, False, "f32")[0, 0] == 0.0
+    assert oracle.linear(x, W, None, False, "f64")[0, 0] == np.float32(2.0 ** -24)
+
+
+def small_model(kind, agg, dims, seed, hidden=6, eps=0.0):
+    cfg = synth.WorkloadConfig(9, "t", kind, agg, 1, 1, False, tuple(dims), hidden, 2, False)
+    rng = np.random.default_rng(seed)
+    model = synth.make_model(cfg, bias_scale=0.5)
+    model["gin_eps"] = eps
+    for L in model["layers"]:                  # re-draw from this test's own seed
+        for k in list(L):
+            if isinstance(L[k], np.ndarray):
+                L[k] = rng.standard_normal(L[k].shape).astype(np.float32) * 0.5
+    return model
+
+
+def relu(x):
+    return np.maximum(x, 0.0)
+
+
+def test_full_infer_sage_against_dense_formula():
+    n, dims = 25, (4, 5, 3)
+    src, dst, X = tiny_graph(n, 120, 21, d=4)
+    rp, col = synth.in_csr_from_edges(n, src, dst)
+    model = small_model("sage", "max", dims, 1)
+    out = oracle.full_infer(rp, col, X, model)
+    h = X.astype(np.float64)
+    for l, L in enumerate(model["layers"]):
+        a = np.zeros_like(h)
+        for v in range(n):
+            nb = col[rp[v]:rp[v + 1]]
+            if nb.size:
+                a[v] = h[nb].max(0)
+        z = a @ L["W_neigh"].astype(np.float64) + h @ L["W_self"].astype(np.float64)
+        h = relu(z) if l == 0 else z
+        assert np.allclose(out["h"][l + 1], h, rtol=1e-5, atol=1e-5)
+        h = out["h"][l + 1].astype(np.float64)  # follow the oracle's fp32 tables layer by layer
+
+
+def test_full_infer_gin_against_dense_formula():
+    n, dims = 25, (4, 5, 3)
+    src, dst, X = tiny_graph(n, 120, 22, d=4)
+    rp, col = synth.in_csr_from_edges(n, src, dst)
+    model = small_model("gin", "sum", dims, 2, eps=0.25)
+    out = oracle.full_infer(rp, col, X, model)
+    A = dense_adj(n, src, dst)
+    h = X.astype(np.float64)
+    for l, L in enumerate(model["layers"]):
+        x = 1.25 * h + A @ h
+        z = relu(x @ L["W_neigh"].astype(np.float64) + L["bias"])
+        z = z @ L["W_mlp2"].astype(np.float64) + L["bias_mlp2"]
+        h = relu(z) if l == 0 else z
+        assert np.allclose(out["h"][l + 1], h, rtol=1e-5, atol=1e-5)
+        h = out["h"][l + 1].astype(np.float64)
+
+
+def test_full_infer_gcn_against_dense_formula():
+    n, dims = 25, (4, 5, 3)
+    src, dst, X = tiny_graph(n, 120, 23, d=4)
+    rp, col = synth.in_csr_from_edges(n, src, dst)
+    model = small_model("gcn", "gcn_sym", dims, 3)
+    out = oracle.full_infer(rp, col, X, model)
+    A = dense_adj(n, src, dst) + np.eye(n)
+    dinv = 1.0 / np.sqrt(A.sum(1))
+    Ah = dinv[:, None] * A * dinv[None, :]
+    h = X.astype(np.float64)
+    for l, L in enumerate(model["layers"]):
+        z = (Ah @ h) @ L["W_neigh"].astype(np.float64) + L["bias"]
+        h = relu(z) if l == 0 else z
+        assert np.allclose(out["h"][l + 1], h, rtol=1e-5, atol=1e-5)
+        h = out["h"][l + 1].astype(np.float64)
+
+
+def test_one_layer_model_is_one_aggregation_and_one_linear_map():
+    n = 20
+    src, dst, X = tiny_graph(n, 90, 31, d=4)
+    rp, col = synth.in_csr_from_edges(n, src, dst)
+    model = small_model("sage", "max", (4, 3), 4)
+    out = oracle.full_infer(rp, col, X, model)
+    a, g = oracle.agg_select(rp, col, X)
+    assert np.array_equal(out["alpha"][1], a) and np.array_equal(out["arg"][1], g)
+    L = model["layers"][0]
+    ref = a.astype(np.float64) @ L["W_neigh"].astype(np.float64) + X.astype(np.float64) @ L["W_self"].astype(np.float64)
+    assert np.allclose(out["h"][1], ref, rtol=1e-5, atol=1e-5)     # last layer: no activation
+
+
+def test_edgeless_graph():
+    n = 6
+    X = np.arange(n * 3, dtype=np.float32).reshape(n, 3)
+    rp = np.zeros(n + 1, np.int64)
+    col = np.zeros(0, np.int32)
+    a, g = oracle.agg_select(rp, col, X)
+    assert not a.any() and (g == -1).all()
+    assert not oracle.agg_sum(rp, col, X).any()
+    assert np.allclose(oracle.agg_gcn_sym(rp, col, X), X)       # only the self term, dhat = 1
+
+
+# ---- batch semantics and invariants of the update problem -------------------------------
+
+def test_apply_batch_net_effect():
+    keys = np.array(sorted([(1 << 32) | 0, (2 << 32) | 1]), np.int64)      # 0>1, 1>2
+    op = np.array([0, 0, 1, 1, 0, 1, 0, 0], np.uint8)
+    src = np.array([0, 3, 1, 4, 5, 5, 6, 6], np.int32)
+    dst = np.array([1, 2, 2, 0, 0, 0, 6, 7], np.int32)
+    # insert present 0>1 (noop); insert 3>2; delete 1>2; delete absent 4>0 (noop);
+    # insert then delete 5>0 (cancel, 2 noops); self loop 6>6 (noop); insert 6>7
+    new, n_ins, n_del, n_noop = oracle.apply_batch(keys, op, src, dst)
+    want = sorted([(1 << 32) | 0, (2 << 32) | 3, (7 << 32) | 6])
+    assert new.tolist() == want
+    assert (n_ins, n_del, n_noop) == (2, 1, 5)
+
+
+def khop_out(n, keys, seeds, k):
+    src, dst = synth.keys_to_edges(keys)
+    reach = np.zeros(n, bool)
+    reach[list(seeds)] = True
+    for _ in range(k):
+        nxt = reach.copy()
+        nxt[dst[reach[src]]] = True
+        reach = nxt
+    return reach
+
+
+@pytest.mark.parametrize("kind,agg", [("sage", "max"), ("gin", "sum"), ("gcn", "gcn_sym")])
+def test_update_invariants(kind, agg):
+    """Empty batch changes nothing; changes stay inside the k-hop out-neighbourhood of the
+    changed edges' destinations (Sec. 1: affected area); insert-then-delete restores the
+    selection-based state exactly."""
+    cfg = synth.get_config(1, 40)
+    cfg = synth.WorkloadConfig(1, "t", kind, agg, cfg.n_nodes, cfg.n_edges, True, (6, 5, 4), 5, 10, False)
+    src, dst = synth.make_graph(cfg)
+    n = cfg.n_nodes
+    X = np.random.default_rng(1).standard_normal((n, 6)).astype(np.float32)
+    model = small_model(kind, agg, cfg.dims, 8, hidden=5)
+    keys = np.unique(synth.edge_keys(src, dst))
+    pre = oracle.full_infer(*oracle.csr_from_keys(n, keys), X, model)
+    e = np.zeros(0, np.int32)
+    k0, a0, d0, z0 = oracle.apply_batch(keys, np.zeros(0, np.uint8), e, e)
+    assert np.array_equal(k0, keys) and (a0, d0, z0) == (0, 0, 0)
+    sampler = synth.BatchSampler(cfg, src, dst)
+    op, bs, bd = sampler.next_batch()
+    keys2, n_ins, n_del, n_noop = oracle.apply_batch(keys, op, bs, bd)
+    assert (n_ins, n_del, n_noop) == (5, 5, 0)
+    cs, cd = sampler.current_edges()
+    assert np.array_equal(np.unique(synth.edge_keys(cs, cd)), keys2)     # sampler and oracle agree
+    post = oracle.full_infer(*oracle.csr_from_keys(n, keys2), X, model)
+    ch = oracle.changed_nodes(pre, post)
+    assert ch[0].size == 0
+    both = np.union1d(keys, keys2)
+    # GCN's degree normalisation lets a destination's own degree change reach its out-neighbours
+    # one layer earlier than a plain message change would
+    extra = 1 if kind == "gcn" else 0
+    for l in (1, 2):
+        reach = khop_out(n, both, set(bd.tolist()), l - 1 + extra)
+        assert reach[ch[l]].all(), l
+    assert ch[2].size > 0
+    # reversibility: undo the batch (insert <-> delete, reverse order)
+    keys3, _, _, _ = oracle.apply_batch(keys2, (1 - op)[::-1].copy(), bs[::-1].copy(), bd[::-1].copy())
+    assert np.array_equal(keys3, keys)
+    back = oracle.full_infer(*oracle.csr_from_keys(n, keys3), X, model)
+    for l in (1, 2):
+        assert np.array_equal(back["h"][l], pre["h"][l])
+        if agg == "max":
+            assert np.array_equal(back["arg"][l], pre["arg"][l])
