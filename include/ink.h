@@ -1,0 +1,196 @@
+/*
+ * ink.h -- C ABI of the MI355X (gfx950) incremental GNN-inference library.
+ *
+ * The library keeps, on one GPU, the cached state of a k-layer message-passing GNN
+ * (per layer: the messages m_l, the aggregated neighbourhoods alpha_l and, for min/max,
+ * the per-dimension argmax/argmin neighbour ids) and updates it after a batch of edge
+ * insertions and deletions by the event-driven incremental method of the paper
+ * (Sec. 2.3 workflow; Sec. 2.4 events, grouping and propagation; Sec. 2.5 incremental
+ * update, reset conditions and recompute).  The result equals plain inference on the
+ * post-update snapshot (Abstract; Sec. 1, "No Accuracy Loss").
+ *
+ * Conventions for every entry point
+ *   - Plain C types only.  Pointers are HOST pointers unless `ink_options.mem` says
+ *     INK_MEM_DEVICE, in which case caller arrays (graph, features, weights, update
+ *     batches) are device pointers on the current HIP device.
+ *   - The caller keeps ownership of everything it passes in; the library copies what it
+ *     needs.  Buffers returned by the library are library-owned DEVICE memory, valid until
+ *     the next ink_apply_updates / ink_full_infer / ink_destroy on the same context.
+ *   - Every call returns an ink_status.  On an argument / range / state error nothing in
+ *     the context has been modified.  ink_last_error() gives a readable message.
+ *   - One context = one HIP stream; calls on one context must not overlap.  All calls are
+ *     synchronous: on return the work is complete.
+ *   - Node ids are int32 in [0, n_nodes); the graph is a simple directed graph without self
+ *     loops; n_nodes is fixed for the life of the context (the paper updates edges only,
+ *     Sec. 2.1).  Edge (u -> v) makes u an in-neighbour of v: v aggregates m_u.
+ *   - All matrices are row-major float32.  Aggregated widths (the width of m_l at every
+ *     layer) must be <= INK_MAX_AGG_DIM.
+ */
+#ifndef INK_H
+#define INK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define INK_MAX_AGG_DIM 256
+#define INK_MAX_LAYERS 8
+
+typedef struct ink_ctx ink_ctx; /* opaque; owns all device state */
+
+typedef enum {
+  INK_OK = 0,
+  INK_E_ARG = 1,    /* null pointer, bad dimension, malformed CSR, unsupported combination */
+  INK_E_STATE = 2,  /* ink_apply_updates / ink_get_layer before ink_full_infer */
+  INK_E_OOM = 3,    /* device or host allocation failed */
+  INK_E_DEVICE = 4, /* a HIP call failed; the context must be destroyed */
+  INK_E_RANGE = 5   /* node id or layer index out of range */
+} ink_status;
+
+/* Model families of Sec. 3 (eqs. (1)-(6)). */
+typedef enum { INK_MODEL_SAGE = 0, INK_MODEL_GCN = 1, INK_MODEL_GIN = 2 } ink_model_kind;
+
+/* Aggregation function A of Sec. 2.1.  MAX / MIN are the paper's monotonic selections
+ * (Sec. 2.2 item 1).  SUM / MEAN / GCN_SYM use the delta-accumulative update the paper names
+ * as its extension (Sec. 7).  GCN_SYM = symmetric degree normalisation with self loop:
+ * a_v = sum_{u in N(v)+{v}} h_u / sqrt(dhat_u dhat_v), dhat_x = indeg(x) + 1. */
+typedef enum {
+  INK_AGG_MAX = 0, INK_AGG_MIN = 1, INK_AGG_SUM = 2, INK_AGG_MEAN = 3, INK_AGG_GCN_SYM = 4
+} ink_agg;
+
+typedef enum { INK_ACT_NONE = 0, INK_ACT_RELU = 1 } ink_act;
+typedef enum { INK_MEM_HOST = 0, INK_MEM_DEVICE = 1 } ink_mem;
+
+/* In-neighbour CSR of the initial snapshot: row v lists the sources u of edges u -> v,
+ * strictly ascending within a row (no duplicates), no self loops. */
+typedef struct {
+  int32_t n_nodes;
+  int64_t n_edges;
+  const int64_t *rowptr; /* [n_nodes + 1], rowptr[0] = 0, rowptr[n_nodes] = n_edges */
+  const int32_t *col;    /* [n_edges] */
+} ink_csr;
+
+/* One GNN layer.  Weights are row-major [in][out]; a NULL pointer means "absent".
+ *   SAGE: h' = act(W_neigh^T a + W_self^T h + bias)                          (eq. (4))
+ *   GCN : h' = act(W_neigh^T a + bias)                                       (eq. (2))
+ *   GIN : h' = act(W_mlp2^T relu(W_neigh^T ((1+eps) h + a) + bias) + bias_mlp2)  (eq. (6));
+ *         W_neigh is [in_dim][mlp_hidden], W_mlp2 is [mlp_hidden][out_dim]. */
+typedef struct {
+  int32_t in_dim, out_dim, mlp_hidden;
+  const float *W_neigh, *W_self, *bias;
+  const float *W_mlp2, *bias_mlp2;
+  int32_t act; /* ink_act applied at the end of the layer (Sec. 2.1) */
+} ink_layer;
+
+typedef struct {
+  int32_t kind;    /* ink_model_kind */
+  int32_t agg;     /* ink_agg; SAGE: MAX|MIN|SUM|MEAN, GIN: SUM|MAX|MIN|MEAN, GCN: GCN_SYM */
+  float gin_eps;
+  int32_t n_layers; /* 1 .. INK_MAX_LAYERS */
+  const ink_layer *layers;
+} ink_model;
+
+typedef struct {
+  int32_t mem;        /* ink_mem: where the caller's arrays live, for every call on the context */
+  void *hip_stream;   /* hipStream_t to run on, or NULL for a stream the library creates */
+  float slack_factor; /* extra capacity per edge block, as a fraction of its degree (default 0.25) */
+  int32_t max_batch;  /* hint: largest update batch expected (sizes buffers up front); 0 = default */
+  int32_t profile;    /* non-zero: time each kernel class with HIP events (see ink_stats) */
+} ink_options;
+
+/* One streaming update (Sec. 2.1: Delta E holds inserted and removed edges). */
+typedef struct {
+  uint8_t op; /* 0 = insert, 1 = delete */
+  uint8_t pad_[3];
+  int32_t src, dst;
+} ink_edge_update;
+
+/* Result of one update batch (library-owned device buffers, see top comment). */
+typedef struct {
+  int64_t n_changed;          /* nodes whose final embedding h_k changed bitwise            */
+  const int32_t *changed_ids; /* DEVICE [n_changed], ascending                                */
+  const float *embeddings;    /* DEVICE [n_changed][out_dim of last layer], new h_k rows      */
+  int64_t n_applied_ins, n_applied_del; /* edges whose presence differs between the snapshots */
+  int64_t n_noop; /* list entries without net effect: duplicate insert, delete of an absent
+                     edge, self loop, or an insert/delete pair that cancels within the batch */
+} ink_update_result;
+
+/* Per-layer counters and timings of the LAST ink_apply_updates (or ink_full_infer). */
+typedef struct {
+  int64_t n_sources;     /* |F_l|: nodes whose message m_l changed                         */
+  int64_t n_events;      /* event records created (changed edges + propagated)   Sec. 2.4.2 */
+  int64_t n_targets;     /* unique target nodes after grouping                    Sec. 2.4.1 */
+  int64_t n_exposed;     /* targets recomputed from their whole neighbourhood    Sec. 2.5.1 */
+  int64_t n_regather_nb; /* neighbour rows fetched by those recomputes                       */
+  int64_t n_alpha_changed; /* targets whose alpha changed (not resilient)         Sec. 2.5.2 */
+  int64_t n_transformed; /* rows through the dense combination                              */
+  int64_t n_changed;     /* rows whose layer output changed: next layer's sources           */
+  int32_t dense;         /* 1 if the layer fell back to re-aggregating every node           */
+  int32_t pad_;
+} ink_layer_stats;
+
+enum { INK_T_GRAPH = 0, INK_T_EVENTS, INK_T_GROUP, INK_T_AGG, INK_T_COMPACT, INK_T_TRANSFORM,
+       INK_T_NCLASS };
+
+typedef struct {
+  int32_t n_layers, pad_;
+  ink_layer_stats layer[INK_MAX_LAYERS];
+  float ms[INK_T_NCLASS];       /* GPU time per kernel class, HIP events (profile != 0), else 0 */
+  int32_t launches[INK_T_NCLASS];
+  float ms_total;               /* wall time of the call measured on the host                   */
+  float pad2_;
+} ink_stats;
+
+/* Builds a context: copies graph, features ([n_nodes][feat_dim]) and weights to the device and
+ * builds the device graph store (per-node in- and out-edge blocks with slack).  The paper's
+ * method starts from "the result of an initial full graph inference" (Sec. 2): call
+ * ink_full_infer next.  Errors: INK_E_ARG (malformed input), INK_E_RANGE (column id outside
+ * [0, n)), INK_E_OOM. */
+ink_status ink_create(const ink_csr *graph, const float *features, int32_t feat_dim,
+                      const ink_model *model, const ink_options *opts, ink_ctx **out);
+
+/* Initial full-graph inference with caching (Sec. 2: the embedding before and after the
+ * aggregation is saved for every node in every layer).  May be called again at any time to
+ * rebuild the cache from the current graph. */
+ink_status ink_full_infer(ink_ctx *ctx);
+
+/* Applies an ordered list of n updates and incrementally refreshes every layer (Sec. 2.3).
+ * The post-update snapshot is the net effect of the list on the edge set.  `updates` is a host
+ * or device array according to ink_options.mem.  n = 0 is allowed (empty result).
+ * Errors: INK_E_STATE before ink_full_infer; INK_E_RANGE for an id outside [0, n_nodes);
+ * INK_E_ARG for op > 1 or n < 0.  On error the graph and the cache are unchanged. */
+ink_status ink_apply_updates(ink_ctx *ctx, const ink_edge_update *updates, int64_t n,
+                             ink_update_result *out);
+
+/* Inspection for tests: copies rows [row0, row0 + nrows) of a cached table to dst (host or
+ * device per dst_mem), densely packed [nrows][width].  layer in 0..n_layers.
+ *   which = 0: h_layer, the output of layer `layer` (layer 0 = input features); it is the
+ *              message m_{layer+1} of the aggregate-first models (Sec. 2.1).
+ *   which = 1: alpha_layer, the aggregated neighbourhood of layer `layer` >= 1 (for SUM-type
+ *              aggregators the cached plain sum; for GCN the normalised aggregate of the
+ *              transformed features, a = A_hat (h_{layer-1} W_layer)).
+ *   which = 2: int32 argmax/argmin neighbour ids of layer `layer` >= 1 (MAX / MIN only).
+ * width is returned in *width_out if not NULL. */
+ink_status ink_get_layer(ink_ctx *ctx, int32_t layer, int32_t which, int64_t row0, int64_t nrows,
+                         void *dst, int32_t dst_mem, int32_t *width_out);
+
+/* Copies the current in-neighbour lists into caller HOST arrays: rowptr [n_nodes + 1] and, if
+ * col is not NULL, col [n_edges] (each row ascending).  Pass col = NULL first to size it. */
+ink_status ink_get_graph(ink_ctx *ctx, int64_t *rowptr, int32_t *col);
+
+/* Copies min(bytes, sizeof(ink_stats)) bytes of the last call's statistics. */
+ink_status ink_get_stats(ink_ctx *ctx, void *stats_out, size_t bytes);
+
+/* Message of the last failing call on this context ("" if none).  ctx may be NULL: then the
+ * message of the last failing ink_create on this thread. */
+const char *ink_last_error(const ink_ctx *ctx);
+
+void ink_destroy(ink_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* INK_H */

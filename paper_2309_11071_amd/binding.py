@@ -1,0 +1,230 @@
+"""ctypes binding of include/ink.h: argument marshalling only.
+
+Every step of the path runs inside libink.so; this module converts numpy / torch buffers to
+the C structs and copies results out.  It fails loudly if the library has not been built.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+INK_MAX_LAYERS = 8
+INK_T_NCLASS = 6
+TIME_CLASSES = ["graph", "events", "group", "agg", "compact", "transform"]
+STATUS_NAMES = {0: "INK_OK", 1: "INK_E_ARG", 2: "INK_E_STATE", 3: "INK_E_OOM", 4: "INK_E_DEVICE",
+                5: "INK_E_RANGE"}
+MODEL_KINDS = {"sage": 0, "gcn": 1, "gin": 2}
+AGGS = {"max": 0, "min": 1, "sum": 2, "mean": 3, "gcn_sym": 4}
+
+EDGE_UPDATE_DTYPE = np.dtype([("op", np.uint8), ("pad", np.uint8, (3,)), ("src", np.int32),
+                              ("dst", np.int32)])
+assert EDGE_UPDATE_DTYPE.itemsize == 12
+
+
+class InkError(RuntimeError):
+    def __init__(self, status, msg):
+        super().__init__("%s: %s" % (STATUS_NAMES.get(status, status), msg))
+        self.status = status
+
+
+class _Csr(C.Structure):
+    _fields_ = [("n_nodes", C.c_int32), ("n_edges", C.c_int64), ("rowptr", C.c_void_p),
+                ("col", C.c_void_p)]
+
+
+class _Layer(C.Structure):
+    _fields_ = [("in_dim", C.c_int32), ("out_dim", C.c_int32), ("mlp_hidden", C.c_int32),
+                ("W_neigh", C.c_void_p), ("W_self", C.c_void_p), ("bias", C.c_void_p),
+                ("W_mlp2", C.c_void_p), ("bias_mlp2", C.c_void_p), ("act", C.c_int32)]
+
+
+class _Model(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("agg", C.c_int32), ("gin_eps", C.c_float),
+                ("n_layers", C.c_int32), ("layers", C.POINTER(_Layer))]
+
+
+class _Options(C.Structure):
+    _fields_ = [("mem", C.c_int32), ("hip_stream", C.c_void_p), ("slack_factor", C.c_float),
+                ("max_batch", C.c_int32), ("profile", C.c_int32)]
+
+
+class _Result(C.Structure):
+    _fields_ = [("n_changed", C.c_int64), ("changed_ids", C.c_void_p), ("embeddings", C.c_void_p),
+                ("n_applied_ins", C.c_int64), ("n_applied_del", C.c_int64), ("n_noop", C.c_int64)]
+
+
+class _LayerStats(C.Structure):
+    _fields_ = [(k, C.c_int64) for k in ("n_sources", "n_events", "n_targets", "n_exposed",
+                                         "n_regather_nb", "n_alpha_changed", "n_transformed",
+                                         "n_changed")] + [("dense", C.c_int32), ("pad_", C.c_int32)]
+
+
+class _Stats(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("pad_", C.c_int32), ("layer", _LayerStats * INK_MAX_LAYERS),
+                ("ms", C.c_float * INK_T_NCLASS), ("launches", C.c_int32 * INK_T_NCLASS),
+                ("ms_total", C.c_float), ("pad2_", C.c_float)]
+
+
+_lib = None
+
+
+def lib_path():
+    return os.path.join(HERE, "libink.so")
+
+
+def load_library():
+    """Loads libink.so; raises if it is missing (there is no fallback path)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = lib_path()
+    if not os.path.exists(path):
+        raise RuntimeError("libink.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'`")
+    lib = C.CDLL(path)
+    vp = C.c_void_p
+    lib.ink_create.argtypes = [C.POINTER(_Csr), vp, C.c_int32, C.POINTER(_Model), C.POINTER(_Options),
+                               C.POINTER(vp)]
+    lib.ink_create.restype = C.c_int
+    lib.ink_full_infer.argtypes = [vp]
+    lib.ink_full_infer.restype = C.c_int
+    lib.ink_apply_updates.argtypes = [vp, vp, C.c_int64, C.POINTER(_Result)]
+    lib.ink_apply_updates.restype = C.c_int
+    lib.ink_get_layer.argtypes = [vp, C.c_int32, C.c_int32, C.c_int64, C.c_int64, vp, C.c_int32,
+                                  C.POINTER(C.c_int32)]
+    lib.ink_get_layer.restype = C.c_int
+    lib.ink_get_graph.argtypes = [vp, vp, vp]
+    lib.ink_get_graph.restype = C.c_int
+    lib.ink_get_stats.argtypes = [vp, vp, C.c_size_t]
+    lib.ink_get_stats.restype = C.c_int
+    lib.ink_last_error.argtypes = [vp]
+    lib.ink_last_error.restype = C.c_char_p
+    lib.ink_destroy.argtypes = [vp]
+    lib.ink_destroy.restype = None
+    _lib = lib
+    return lib
+
+
+def _ptr(a):
+    return None if a is None else C.c_void_p(a.ctypes.data)
+
+
+def make_updates(op, src, dst):
+    """Packs three arrays into the ink_edge_update layout."""
+    u = np.zeros(len(op), dtype=EDGE_UPDATE_DTYPE)
+    u["op"], u["src"], u["dst"] = op, src, dst
+    return u
+
+
+class Ink:
+    """One context.  `model` is the dict layout of synth.make_model (host numpy weights)."""
+
+    def __init__(self, rowptr, col, features, model, slack_factor=0.25, profile=False, stream=None):
+        self._lib = load_library()
+        self._h = C.c_void_p()
+        rowptr = np.ascontiguousarray(rowptr, np.int64)
+        col = np.ascontiguousarray(col, np.int32)
+        features = np.ascontiguousarray(features, np.float32)
+        keep = [rowptr, col, features]
+        layers = (_Layer * len(model["layers"]))()
+        for i, L in enumerate(model["layers"]):
+            def w(name):
+                a = L.get(name)
+                if a is None:
+                    return None
+                a = np.ascontiguousarray(a, np.float32)
+                keep.append(a)
+                return C.c_void_p(a.ctypes.data)
+            layers[i] = _Layer(L["in_dim"], L["out_dim"], int(L.get("mlp_hidden", 0) or 0), w("W_neigh"),
+                               w("W_self"), w("bias"), w("W_mlp2"), w("bias_mlp2"),
+                               1 if L.get("act", "none") == "relu" else 0)
+        m = _Model(MODEL_KINDS[model["kind"]], AGGS[model["agg"]], float(model.get("gin_eps", 0.0)),
+                   len(model["layers"]), layers)
+        g = _Csr(rowptr.size - 1, col.size, rowptr.ctypes.data, col.ctypes.data if col.size else None)
+        o = _Options(0, stream, slack_factor, 0, int(bool(profile)))
+        st = self._lib.ink_create(C.byref(g), features.ctypes.data, features.shape[1], C.byref(m), C.byref(o),
+                                  C.byref(self._h))
+        if st != 0:
+            raise InkError(st, self._lib.ink_last_error(None).decode())
+        self.n = rowptr.size - 1
+        self.n_layers = len(model["layers"])
+        self.out_dim = model["layers"][-1]["out_dim"]
+
+    def _check(self, st):
+        if st != 0:
+            raise InkError(st, self._lib.ink_last_error(self._h).decode())
+
+    def full_infer(self):
+        self._check(self._lib.ink_full_infer(self._h))
+
+    def apply_updates(self, updates, fetch=True):
+        """updates: structured array (EDGE_UPDATE_DTYPE).  Returns dict; with fetch the changed ids
+        and embeddings are copied to host numpy arrays."""
+        updates = np.ascontiguousarray(updates, dtype=EDGE_UPDATE_DTYPE)
+        r = _Result()
+        self._check(self._lib.ink_apply_updates(self._h, updates.ctypes.data if updates.size else None,
+                                                updates.size, C.byref(r)))
+        out = dict(n_changed=r.n_changed, n_applied_ins=r.n_applied_ins, n_applied_del=r.n_applied_del,
+                   n_noop=r.n_noop, changed_ids_ptr=r.changed_ids, embeddings_ptr=r.embeddings)
+        if fetch:
+            ids = np.empty(r.n_changed, np.int32)
+            emb = np.empty((r.n_changed, self.out_dim), np.float32)
+            if r.n_changed:
+                _dtoh(ids, r.changed_ids)
+                _dtoh(emb, r.embeddings)
+            out["changed_ids"], out["embeddings"] = ids, emb
+        return out
+
+    def get_layer(self, layer, which, row0=0, nrows=None):
+        nrows = self.n - row0 if nrows is None else nrows
+        w = C.c_int32()
+        self._check(self._lib.ink_get_layer(self._h, layer, which, 0, 0, None, 0, C.byref(w)))
+        out = np.empty((nrows, w.value), np.int32 if which == 2 else np.float32)
+        self._check(self._lib.ink_get_layer(self._h, layer, which, row0, nrows, out.ctypes.data, 0, None))
+        return out
+
+    def get_graph(self):
+        rowptr = np.empty(self.n + 1, np.int64)
+        self._check(self._lib.ink_get_graph(self._h, rowptr.ctypes.data, None))
+        col = np.empty(int(rowptr[-1]), np.int32)
+        self._check(self._lib.ink_get_graph(self._h, rowptr.ctypes.data, col.ctypes.data if col.size else None))
+        return rowptr, col
+
+    def stats(self):
+        s = _Stats()
+        self._check(self._lib.ink_get_stats(self._h, C.byref(s), C.sizeof(s)))
+        layers = [{k: getattr(s.layer[i], k) for k, _ in _LayerStats._fields_ if k != "pad_"}
+                  for i in range(s.n_layers)]
+        return dict(layers=layers, ms={TIME_CLASSES[i]: s.ms[i] for i in range(INK_T_NCLASS)},
+                    launches={TIME_CLASSES[i]: s.launches[i] for i in range(INK_T_NCLASS)},
+                    ms_total=s.ms_total)
+
+    def close(self):
+        if self._h:
+            self._lib.ink_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def _dtoh(dst, dev_ptr):
+    """Device -> host copy through torch (PyTorch is the memory/stream plumbing)."""
+    import torch
+    n = dst.nbytes
+    t = torch.empty(n, dtype=torch.uint8, device="cuda")
+    _hip().hipMemcpy(C.c_void_p(t.data_ptr()), C.c_void_p(dev_ptr), C.c_size_t(n), 3)
+    dst.view(np.uint8).reshape(-1)[:] = t.cpu().numpy()
+
+
+_hiprt = None
+
+
+def _hip():
+    global _hiprt
+    if _hiprt is None:
+        _hiprt = C.CDLL("libamdhip64.so")
+    return _hiprt

@@ -1,0 +1,388 @@
+// Aggregation kernels for the selection aggregators (max / min) with per-dimension argument
+// tracking: full re-aggregation ("recompute", Sec. 2.5.2) and the event-driven incremental
+// update with reset detection (Sec. 2.5.1).  One wave64 owns one target row; a lane holds four
+// consecutive dimensions, so a row of d floats occupies LPR = 16/32/64 lanes and a wave works on
+// 64 / LPR neighbour rows at a time.  Rows are read as coalesced 16-byte lane loads.
+#include "ctx.h"
+
+namespace ink {
+
+
+
+struct F4 { float v[4]; };
+struct I4 { int v[4]; };
+
+template <bool IS_MIN> __device__ __forceinline__ bool better(float x, float y) {
+  return IS_MIN ? (x < y) : (x > y);
+}
+template <bool IS_MIN> __device__ __forceinline__ float worst() {
+  return IS_MIN ? __builtin_huge_valf() : -__builtin_huge_valf();
+}
+// lexicographic: better value first, lower id on equal value
+template <bool IS_MIN> __device__ __forceinline__ void take(float x, int id, float &bv, int &bi) {
+  if (better<IS_MIN>(x, bv) || (x == bv && id < bi)) { bv = x; bi = id; }
+}
+
+__device__ __forceinline__ float4 ld4(const float *p) { return *reinterpret_cast<const float4 *>(p); }
+
+// Reduce (bv, bi) over the lane groups of a wave (groups are LPR lanes wide); every lane ends
+// with the result for its 4 dimensions.
+template <bool IS_MIN, int LPR> __device__ __forceinline__ void reduce_groups(F4 &bv, I4 &bi) {
+#pragma unroll
+  for (int off = LPR; off < kWave; off <<= 1) {
+#pragma unroll
+    for (int c = 0; c < 4; c++) {
+      float ov = __shfl_xor(bv.v[c], off, kWave);
+      int oi = __shfl_xor(bi.v[c], off, kWave);
+      take<IS_MIN>(ov, oi, bv.v[c], bi.v[c]);
+    }
+  }
+}
+
+// Selection over neighbours ids[j0 .. j1) of one row, by the whole wave.  On return every lane
+// holds the best (value, id) of its 4 dimensions over the range; (worst, INT_MAX) if empty.
+template <bool IS_MIN, int LPR>
+__device__ __forceinline__ void gather_range(const int32_t *ids, int64_t j0, int64_t j1, const float *M,
+                                             int ldm, bool lane_on, int q, F4 &bv, I4 &bi) {
+  constexpr int G = kWave / LPR;
+  const int l = lane_id();
+  const int g = l / LPR;
+#pragma unroll
+  for (int c = 0; c < 4; c++) { bv.v[c] = worst<IS_MIN>(); bi.v[c] = 0x7fffffff; }
+  for (int64_t jb = j0; jb < j1; jb += kWave) {
+    int64_t jj = jb + l;
+    int myid = jj < j1 ? ids[jj] : -1;
+    int cnt = (int)((j1 - jb) < kWave ? (j1 - jb) : kWave);
+    constexpr int U = 4;
+    for (int it = 0; it < cnt; it += G * U) {
+      int id[U];
+      float4 row[U];
+#pragma unroll
+      for (int u = 0; u < U; u++) {
+        int k = it + u * G + g;
+        id[u] = __shfl(myid, k < kWave ? k : 0, kWave);
+        if (k >= cnt) id[u] = -1;
+        if (id[u] >= 0 && lane_on) row[u] = ld4(M + (int64_t)id[u] * ldm + 4 * q);
+      }
+#pragma unroll
+      for (int u = 0; u < U; u++) {
+        if (id[u] >= 0 && lane_on) {
+          take<IS_MIN>(row[u].x, id[u], bv.v[0], bi.v[0]);
+          take<IS_MIN>(row[u].y, id[u], bv.v[1], bi.v[1]);
+          take<IS_MIN>(row[u].z, id[u], bv.v[2], bi.v[2]);
+          take<IS_MIN>(row[u].w, id[u], bv.v[3], bi.v[3]);
+        }
+      }
+    }
+  }
+  reduce_groups<IS_MIN, LPR>(bv, bi);
+}
+
+struct RowOut {
+  float *A; int32_t *ARG; int ld; int d;
+};
+
+// Writes (bv, bi) as the new aggregated row of v if it differs from what is stored; returns
+// (wave-uniform) whether any VALUE of the first d dimensions changed bitwise.
+template <int LPR>
+__device__ __forceinline__ bool store_row(const RowOut &o, int v, bool lane_on, int q, const F4 &bv,
+                                          const I4 &bi, bool have_old, const F4 &ov, const I4 &oi) {
+  const int l = lane_id();
+  bool writer = lane_on && l < LPR;
+  bool vchg = false, ichg = false;
+  if (writer) {
+    F4 cv = ov; I4 ci = oi;
+    if (!have_old) {
+      float4 a = ld4(o.A + (int64_t)v * o.ld + 4 * q);
+      int4 b = *reinterpret_cast<const int4 *>(o.ARG + (int64_t)v * o.ld + 4 * q);
+      cv.v[0] = a.x; cv.v[1] = a.y; cv.v[2] = a.z; cv.v[3] = a.w;
+      ci.v[0] = b.x; ci.v[1] = b.y; ci.v[2] = b.z; ci.v[3] = b.w;
+    }
+#pragma unroll
+    for (int c = 0; c < 4; c++) {
+      if (4 * q + c < o.d) vchg |= __float_as_uint(cv.v[c]) != __float_as_uint(bv.v[c]);
+      ichg |= ci.v[c] != bi.v[c];
+    }
+    if (vchg || ichg) {
+      *reinterpret_cast<float4 *>(o.A + (int64_t)v * o.ld + 4 * q) = make_float4(bv.v[0], bv.v[1], bv.v[2], bv.v[3]);
+      *reinterpret_cast<int4 *>(o.ARG + (int64_t)v * o.ld + 4 * q) = make_int4(bi.v[0], bi.v[1], bi.v[2], bi.v[3]);
+    }
+  }
+  return __ballot(vchg) != 0ull;
+}
+
+__device__ __forceinline__ void finish_empty(F4 &bv, I4 &bi) {   // no in-neighbours: alpha = 0, arg = -1
+#pragma unroll
+  for (int c = 0; c < 4; c++) if (bi.v[c] == 0x7fffffff) { bv.v[c] = 0.f; bi.v[c] = -1; }
+}
+
+__device__ __forceinline__ void mark_bit(uint64_t *bm, int v) {
+  atomicOr((unsigned long long *)&bm[v >> 6], 1ull << (v & 63));
+}
+
+// ------------------------------------------------------------------ full re-aggregation
+template <bool IS_MIN, int LPR>
+__global__ __launch_bounds__(256) void k_agg_full(AggArgs a, const int32_t *targets, int64_t n_targets,
+                                                  uint64_t *chg, int32_t *big_list, int32_t *n_big, int compare) {
+  const int l = lane_id();
+  const int q = l % LPR;
+  const bool lane_on = 4 * q < a.ld;
+  int64_t wid = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kWave;
+  if (wid >= n_targets) return;
+  int v = targets ? targets[wid] : (int)wid;
+  int deg = a.in_deg[v];
+  if (deg > kBigDeg) {
+    if (l == 0) big_list[atomicAdd(n_big, 1)] = v;
+    return;
+  }
+  int64_t off = a.in_off[v];
+  F4 bv; I4 bi;
+  gather_range<IS_MIN, LPR>(a.in_ids + off, 0, deg, a.M, a.ldm, lane_on, q, bv, bi);
+  finish_empty(bv, bi);
+  RowOut o{a.A, a.ARG, a.ld, a.d};
+  F4 dum; I4 dumi;
+  bool ch;
+  if (compare) ch = store_row<LPR>(o, v, lane_on, q, bv, bi, false, dum, dumi);
+  else {
+    if (lane_on && l < LPR) {
+      *reinterpret_cast<float4 *>(a.A + (int64_t)v * a.ld + 4 * q) = make_float4(bv.v[0], bv.v[1], bv.v[2], bv.v[3]);
+      *reinterpret_cast<int4 *>(a.ARG + (int64_t)v * a.ld + 4 * q) = make_int4(bi.v[0], bi.v[1], bi.v[2], bi.v[3]);
+    }
+    ch = false;
+  }
+  if (ch && chg && l == 0) mark_bit(chg, v);
+}
+
+// cooperative path for rows with more than kBigDeg in-neighbours: grid (kBigParts, n_big);
+// each workgroup selects over its slice of the neighbour list and stores a partial row
+template <bool IS_MIN, int LPR>
+__global__ __launch_bounds__(256) void k_big_partial(AggArgs a, const int32_t *big_list, float *part_v,
+                                                     int32_t *part_i) {
+  __shared__ float sv[4][kWave * 4];
+  __shared__ int si[4][kWave * 4];
+  const int l = lane_id(), w = threadIdx.x / kWave;
+  const int q = l % LPR;
+  const bool lane_on = 4 * q < a.ld;
+  int v = big_list[blockIdx.y];
+  int64_t deg = a.in_deg[v];
+  int64_t off = a.in_off[v];
+  int64_t p0 = deg * blockIdx.x / kBigParts, p1 = deg * (blockIdx.x + 1) / kBigParts;
+  int64_t len = p1 - p0;
+  int64_t w0 = p0 + len * w / 4, w1 = p0 + len * (w + 1) / 4;
+  F4 bv; I4 bi;
+  gather_range<IS_MIN, LPR>(a.in_ids + off, w0, w1, a.M, a.ldm, lane_on, q, bv, bi);
+#pragma unroll
+  for (int c = 0; c < 4; c++) { sv[w][l * 4 + c] = bv.v[c]; si[w][l * 4 + c] = bi.v[c]; }
+  __syncthreads();
+  if (w == 0) {
+#pragma unroll
+    for (int ww = 1; ww < 4; ww++)
+#pragma unroll
+      for (int c = 0; c < 4; c++) take<IS_MIN>(sv[ww][l * 4 + c], si[ww][l * 4 + c], bv.v[c], bi.v[c]);
+    if (lane_on && l < LPR) {
+      int64_t o = ((int64_t)blockIdx.y * kBigParts + blockIdx.x) * a.ld + 4 * q;
+#pragma unroll
+      for (int c = 0; c < 4; c++) { part_v[o + c] = bv.v[c]; part_i[o + c] = bi.v[c]; }
+    }
+  }
+}
+
+// one wave per big row: reduce the partial rows and store
+template <bool IS_MIN, int LPR>
+__global__ __launch_bounds__(64) void k_big_final(AggArgs a, const int32_t *big_list, const float *part_v,
+                                                  const int32_t *part_i, uint64_t *chg, int compare) {
+  const int l = lane_id();
+  const int q = l % LPR;
+  const bool lane_on = 4 * q < a.ld;
+  int v = big_list[blockIdx.x];
+  F4 bv; I4 bi;
+#pragma unroll
+  for (int c = 0; c < 4; c++) { bv.v[c] = worst<IS_MIN>(); bi.v[c] = 0x7fffffff; }
+  if (lane_on && l < LPR) {
+    for (int p = 0; p < kBigParts; p++) {
+      int64_t o = ((int64_t)blockIdx.x * kBigParts + p) * a.ld + 4 * q;
+#pragma unroll
+      for (int c = 0; c < 4; c++) take<IS_MIN>(part_v[o + c], part_i[o + c], bv.v[c], bi.v[c]);
+    }
+  }
+  finish_empty(bv, bi);
+  RowOut o{a.A, a.ARG, a.ld, a.d};
+  F4 dum; I4 dumi;
+  bool ch = store_row<LPR>(o, v, lane_on, q, bv, bi, false, dum, dumi);
+  if (compare && ch && chg && l == 0) mark_bit(chg, v);
+}
+
+// ------------------------------------------------------------------ event-driven incremental update
+// Events of a target arrive as one contiguous segment of ev_val (kind << 30 | source id).
+//   DEL  (edge u -> v removed):    dimension i needs a reset iff arg[v][i] == u
+//   ADD  (edge s -> v inserted):   (m_s[i], s) is a candidate
+//   CHG  (message of u changed, edge kept): (m_u[i], u) is a candidate; if u held dimension i and
+//        its value got worse the dimension needs a reset, if equal nothing happened there
+// A reset dimension is covered when the best candidate strictly beats the old value, otherwise
+// the row is exposed and recomputed from its whole current neighbourhood.
+template <bool IS_MIN, int LPR>
+__global__ __launch_bounds__(256) void k_agg_events(AggArgs a, const int32_t *targets, const int32_t *seg,
+                                                    int64_t n_targets, const uint32_t *ev, uint64_t *chg,
+                                                    int32_t *big_list, Counters *cnt) {
+  constexpr int G = kWave / LPR;
+  const int l = lane_id();
+  const int q = l % LPR, g = l / LPR;
+  const bool lane_on = 4 * q < a.ld;
+  int64_t wid = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kWave;
+  if (wid >= n_targets) return;
+  int v = targets[wid];
+  int e0 = seg[wid], e1 = seg[wid + 1];
+  F4 ov; I4 oi;
+#pragma unroll
+  for (int c = 0; c < 4; c++) { ov.v[c] = 0.f; oi.v[c] = -1; }
+  if (lane_on) {
+    float4 x = ld4(a.A + (int64_t)v * a.ld + 4 * q);
+    int4 y = *reinterpret_cast<const int4 *>(a.ARG + (int64_t)v * a.ld + 4 * q);
+    ov.v[0] = x.x; ov.v[1] = x.y; ov.v[2] = x.z; ov.v[3] = x.w;
+    oi.v[0] = y.x; oi.v[1] = y.y; oi.v[2] = y.z; oi.v[3] = y.w;
+  }
+  F4 cv; I4 ci;
+  bool reset[4] = {false, false, false, false};
+#pragma unroll
+  for (int c = 0; c < 4; c++) { cv.v[c] = worst<IS_MIN>(); ci.v[c] = 0x7fffffff; }
+  for (int eb = e0; eb < e1; eb += kWave) {
+    int ee = eb + l;
+    uint32_t mine = ee < e1 ? ev[ee] : 0xFFFFFFFFu;
+    int cntw = (e1 - eb) < kWave ? (e1 - eb) : kWave;
+    for (int it = 0; it < cntw; it += G) {
+      int k = it + g;
+      uint32_t x = __shfl(mine, k < kWave ? k : 0, kWave);
+      if (k >= cntw || !lane_on) continue;
+      uint32_t kind = x >> kEvKindShift;
+      int u = (int)(x & kEvIdMask);
+      if (kind == EV_DEL) {
+#pragma unroll
+        for (int c = 0; c < 4; c++) reset[c] |= (oi.v[c] == u);
+      } else {
+        float4 r4 = ld4(a.M + (int64_t)u * a.ldm + 4 * q);
+        float r[4] = {r4.x, r4.y, r4.z, r4.w};
+#pragma unroll
+        for (int c = 0; c < 4; c++) {
+          if (kind == EV_CHG && oi.v[c] == u && better<IS_MIN>(ov.v[c], r[c])) reset[c] = true;
+          take<IS_MIN>(r[c], u, cv.v[c], ci.v[c]);
+        }
+      }
+    }
+  }
+  // combine the lane groups
+#pragma unroll
+  for (int off = LPR; off < kWave; off <<= 1)
+#pragma unroll
+    for (int c = 0; c < 4; c++) reset[c] |= (bool)__shfl_xor((int)reset[c], off, kWave);
+  reduce_groups<IS_MIN, LPR>(cv, ci);
+  F4 nv = ov; I4 ni = oi;
+  bool exposed = false;
+#pragma unroll
+  for (int c = 0; c < 4; c++) {
+    bool has_cand = ci.v[c] != 0x7fffffff;
+    if (oi.v[c] < 0) {                       // no neighbours before this batch
+      if (has_cand) { nv.v[c] = cv.v[c]; ni.v[c] = ci.v[c]; }
+    } else if (reset[c]) {
+      if (has_cand && better<IS_MIN>(cv.v[c], ov.v[c])) { nv.v[c] = cv.v[c]; ni.v[c] = ci.v[c]; }
+      else exposed = true;
+    } else if (has_cand) {
+      take<IS_MIN>(cv.v[c], ci.v[c], nv.v[c], ni.v[c]);
+    }
+  }
+  exposed = __ballot(exposed && lane_on) != 0ull;
+  if (exposed) {
+    int deg = a.in_deg[v];
+    if (l == 0) {
+      atomicAdd(&cnt->v[C_EXPOSED], 1);
+      atomicAdd((unsigned long long *)&cnt->v[C_REGATHER_LO], (unsigned long long)deg);
+    }
+    if (deg > kBigDeg) {
+      if (l == 0) big_list[atomicAdd(&cnt->v[C_NBIG], 1)] = v;
+      return;
+    }
+    gather_range<IS_MIN, LPR>(a.in_ids + a.in_off[v], 0, deg, a.M, a.ldm, lane_on, q, nv, ni);
+    finish_empty(nv, ni);
+  }
+  RowOut o{a.A, a.ARG, a.ld, a.d};
+  bool ch = store_row<LPR>(o, v, lane_on, q, nv, ni, true, ov, oi);
+  if (ch && l == 0) { mark_bit(chg, v); atomicAdd(&cnt->v[C_ACHG], 1); }
+}
+
+// ------------------------------------------------------------------ host side
+static int lanes_per_row(int ld) { return ld <= 64 ? 16 : (ld <= 128 ? 32 : 64); }
+
+template <bool IS_MIN, int LPR>
+static hipError_t run_big(ink_ctx *c, const AggArgs &a, int n_big, uint64_t *chg, int compare) {
+  const int chunk = 512;
+  INK_TRY(c->big_part_v.reserve((size_t)chunk * kBigParts * a.ld * sizeof(float)));
+  INK_TRY(c->big_part_i.reserve((size_t)chunk * kBigParts * a.ld * sizeof(int32_t)));
+  const int32_t *list = c->big_list.as<int32_t>();
+  for (int b0 = 0; b0 < n_big; b0 += chunk) {
+    int nb = n_big - b0 < chunk ? n_big - b0 : chunk;
+    hipLaunchKernelGGL((k_big_partial<IS_MIN, LPR>), dim3(kBigParts, nb), dim3(256), 0, c->stream, a, list + b0,
+                       c->big_part_v.as<float>(), c->big_part_i.as<int32_t>());
+    hipLaunchKernelGGL((k_big_final<IS_MIN, LPR>), dim3(nb), dim3(64), 0, c->stream, a, list + b0,
+                       (const float *)c->big_part_v.as<float>(), (const int32_t *)c->big_part_i.as<int32_t>(), chg,
+                       compare);
+  }
+  return hipGetLastError();
+}
+
+static hipError_t read_counters(ink_ctx *c) {
+  INK_TRY(hipMemcpyAsync(c->h_cnt, c->d_cnt, sizeof(Counters), hipMemcpyDeviceToHost, c->stream));
+  return hipStreamSynchronize(c->stream);
+}
+
+template <bool IS_MIN, int LPR>
+static hipError_t full_t(ink_ctx *c, const AggArgs &a, const int32_t *targets, int64_t n_targets, uint64_t *chg) {
+  if (n_targets <= 0) return hipSuccess;
+  int compare = chg != nullptr;
+  INK_TRY(hipMemsetAsync(&c->d_cnt->v[C_NBIG], 0, sizeof(int32_t), c->stream));
+  int64_t blocks = (n_targets + 3) / 4;
+  hipLaunchKernelGGL((k_agg_full<IS_MIN, LPR>), dim3((unsigned)blocks), dim3(256), 0, c->stream, a, targets, n_targets,
+                     chg, c->big_list.as<int32_t>(), &c->d_cnt->v[C_NBIG], compare);
+  INK_TRY(hipGetLastError());
+  INK_TRY(read_counters(c));
+  int n_big = c->h_cnt->v[C_NBIG];
+  if (n_big > 0) INK_TRY((run_big<IS_MIN, LPR>(c, a, n_big, chg, compare)));
+  return hipSuccess;
+}
+
+template <bool IS_MIN, int LPR>
+static hipError_t events_t(ink_ctx *c, const AggArgs &a, const int32_t *targets, const int32_t *seg,
+                           int64_t n_targets, const uint32_t *ev, uint64_t *chg) {
+  if (n_targets <= 0) return hipSuccess;
+  int64_t blocks = (n_targets + 3) / 4;
+  hipLaunchKernelGGL((k_agg_events<IS_MIN, LPR>), dim3((unsigned)blocks), dim3(256), 0, c->stream, a, targets, seg,
+                     n_targets, ev, chg, c->big_list.as<int32_t>(), c->d_cnt);
+  INK_TRY(hipGetLastError());
+  INK_TRY(read_counters(c));
+  int n_big = c->h_cnt->v[C_NBIG];
+  if (n_big > 0) INK_TRY((run_big<IS_MIN, LPR>(c, a, n_big, chg, 1)));
+  return hipSuccess;
+}
+
+#define DISPATCH(fn, ...)                                                         \
+  do {                                                                            \
+    int lpr_ = lanes_per_row(a.ld);                                               \
+    if (a.is_min) {                                                               \
+      if (lpr_ == 16) return fn<true, 16>(__VA_ARGS__);                           \
+      if (lpr_ == 32) return fn<true, 32>(__VA_ARGS__);                           \
+      return fn<true, 64>(__VA_ARGS__);                                           \
+    } else {                                                                      \
+      if (lpr_ == 16) return fn<false, 16>(__VA_ARGS__);                          \
+      if (lpr_ == 32) return fn<false, 32>(__VA_ARGS__);                          \
+      return fn<false, 64>(__VA_ARGS__);                                          \
+    }                                                                             \
+  } while (0)
+
+hipError_t agg_select_full(ink_ctx *c, const AggArgs &a, const int32_t *targets, int64_t n_targets, uint64_t *chg) {
+  DISPATCH(full_t, c, a, targets, n_targets, chg);
+}
+
+hipError_t agg_select_events(ink_ctx *c, const AggArgs &a, const int32_t *targets, const int32_t *seg,
+                             int64_t n_targets, const uint32_t *ev_val, uint64_t *chg) {
+  DISPATCH(events_t, c, a, targets, seg, n_targets, ev_val, chg);
+}
+
+}  // namespace ink

@@ -1,0 +1,578 @@
+// C ABI entry points and the per-layer driver of the incremental update (Sec. 2.3 workflow):
+// for every aggregation layer  seed events from the changed edges -> expand events from the
+// changed sources -> group by target -> incremental aggregation / recompute -> dense combination
+// on the changed rows -> compare-and-emit the next layer's sources.
+#include <algorithm>
+#include <chrono>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "ctx.h"
+
+using namespace ink;
+
+#define API_TRY(x)                                                                         \
+  do {                                                                                     \
+    hipError_t e_ = (x);                                                                   \
+    if (e_ != hipSuccess) {                                                                \
+      c->err = std::string("HIP error: ") + hipGetErrorString(e_) + " at " #x;             \
+      return e_ == hipErrorOutOfMemory ? INK_E_OOM : INK_E_DEVICE;                         \
+    }                                                                                      \
+  } while (0)
+
+static thread_local std::string g_create_err;
+
+static inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
+static inline dim3 grid1(int64_t n, int per = 256) { return dim3((unsigned)std::max<int64_t>(1, (n + per - 1) / per)); }
+
+// ------------------------------------------------------------------------------------ kernels
+__global__ void k_seed_events(const int32_t *del_s, const int32_t *del_d, const int32_t *ins_s, const int32_t *ins_d,
+                              int n_del, int n_ins, uint32_t *key, uint32_t *val) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n_del) { key[i] = (uint32_t)del_d[i]; val[i] = (EV_DEL << kEvKindShift) | (uint32_t)del_s[i]; }
+  else if (i < n_del + n_ins) {
+    int j = (int)i - n_del;
+    key[i] = (uint32_t)ins_d[j]; val[i] = (EV_ADD << kEvKindShift) | (uint32_t)ins_s[j];
+  }
+}
+
+// out-edges of a changed source that exist in both snapshots: the block minus the ids appended
+// by this batch
+struct KeptOutDeg {
+  const int32_t *F; const int32_t *deg; const int32_t *new_out;
+  __device__ int operator()(int64_t i) const { int u = F[i]; return deg[u] - new_out[u]; }
+};
+struct StorePref { int32_t *p; __device__ void operator()(int64_t i, int, int ex) const { p[i] = ex; } };
+
+// one thread per propagated event: source = the changed node owning event e, target = its e-th
+// kept out-neighbour.  payload_index: store the position in F instead of the node id.
+__global__ void k_expand_events(const int32_t *F, int nF, const int32_t *pref, int n_ev, const int64_t *off,
+                                const int32_t *ids, uint32_t *key, uint32_t *val, int payload_index) {
+  int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= n_ev) return;
+  int lo = 0, hi = nF - 1;
+  while (lo < hi) {
+    int mid = (lo + hi + 1) >> 1;
+    if (pref[mid] <= e) lo = mid; else hi = mid - 1;
+  }
+  int u = F[lo];
+  int p = (int)e - pref[lo];
+  key[e] = (uint32_t)ids[off[u] + p];
+  val[e] = (EV_CHG << kEvKindShift) | (uint32_t)(payload_index ? lo : u);
+}
+
+__global__ void k_mark_nodes(const int32_t *list, int n, uint64_t *bm) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) { int v = list[i]; atomicOr((unsigned long long *)&bm[v >> 6], 1ull << (v & 63)); }
+}
+
+__global__ void k_gather_i32(const int32_t *table, const int32_t *idx, int n, int32_t *out) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) out[i] = table[idx[i]];
+}
+
+__global__ void k_gather_rows(const float *table, int ld, int d, const int32_t *rows, int64_t n, float *out) {
+  int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t r = t / d;
+  int k = (int)(t % d);
+  if (r < n) out[r * d + k] = table[(int64_t)rows[r] * ld + k];
+}
+
+__global__ void k_pack_rows(const void *table, int ld, int d, int64_t row0, int64_t nrows, void *out) {
+  int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t r = t / d;
+  int k = (int)(t % d);
+  if (r < nrows) ((uint32_t *)out)[r * d + k] = ((const uint32_t *)table)[(row0 + r) * ld + k];
+}
+
+__global__ void k_unpack_rows(const float *in, int d, int ld, int64_t n, float *table) {
+  int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t r = t / d;
+  int k = (int)(t % d);
+  if (r < n) table[r * ld + k] = in[r * d + k];
+}
+
+// ------------------------------------------------------------------------------------ helpers
+static ink_status fail(ink_ctx *c, ink_status st, const std::string &msg) {
+  if (c) c->err = msg; else g_create_err = msg;
+  return st;
+}
+
+static hipError_t alloc_table(Table &t, int64_t n, int d) {
+  t.d = d;
+  t.ld = round_up(d, 4);
+  size_t bytes = (size_t)n * t.ld * 4;
+  hipError_t e = hipMalloc(&t.p, bytes);
+  if (e != hipSuccess) return e;
+  return hipMemset(t.p, 0, bytes);
+}
+
+// uploads W ([K][N], host or device) zero-padded to [Kp][Np]
+static hipError_t upload_padded(const float *src, int K, int N, int Kp, int Np, int row_off, float *dst, bool src_dev) {
+  std::vector<float> h((size_t)K * N);
+  hipError_t e = hipMemcpy(h.data(), src, h.size() * 4, src_dev ? hipMemcpyDeviceToHost : hipMemcpyHostToHost);
+  if (e != hipSuccess) return e;
+  std::vector<float> p((size_t)K * Np, 0.f);
+  for (int k = 0; k < K; k++) std::copy(h.begin() + (size_t)k * N, h.begin() + (size_t)(k + 1) * N, p.begin() + (size_t)k * Np);
+  return hipMemcpy(dst + (size_t)row_off * Np, p.data(), p.size() * 4, hipMemcpyHostToDevice);
+}
+
+static hipError_t upload_vec(const float *src, int n, float **dst, bool src_dev) {
+  if (!src) { *dst = nullptr; return hipSuccess; }
+  hipError_t e = hipMalloc((void **)dst, (size_t)round_up(n, 32) * 4);
+  if (e != hipSuccess) return e;
+  e = hipMemset(*dst, 0, (size_t)round_up(n, 32) * 4);
+  if (e != hipSuccess) return e;
+  return hipMemcpy(*dst, src, (size_t)n * 4, src_dev ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice);
+}
+
+struct Prof {
+  ink_ctx *c; int cls; hipEvent_t a = nullptr, b = nullptr;
+  Prof(ink_ctx *c_, int cls_) : c(c_), cls(cls_) {
+    c->stats.launches[cls]++;
+    if (!c->profile) return;
+    if (c->ev_free.size() < 2) { hipEvent_t e; (void)hipEventCreate(&e); c->ev_free.push_back(e); (void)hipEventCreate(&e); c->ev_free.push_back(e); }
+    a = c->ev_free.back(); c->ev_free.pop_back();
+    b = c->ev_free.back(); c->ev_free.pop_back();
+    (void)hipEventRecord(a, c->stream);
+  }
+  ~Prof() {
+    if (!c->profile) return;
+    (void)hipEventRecord(b, c->stream);
+    c->ev_pending.push_back({cls, a, b});
+  }
+};
+
+static void prof_collect(ink_ctx *c) {
+  for (auto &p : c->ev_pending) {
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, p.a, p.b) == hipSuccess) c->stats.ms[p.cls] += ms;
+    c->ev_free.push_back(p.a); c->ev_free.push_back(p.b);
+  }
+  c->ev_pending.clear();
+}
+
+static hipError_t read_counters(ink_ctx *c) {
+  hipError_t e = hipMemcpyAsync(c->h_cnt, c->d_cnt, sizeof(Counters), hipMemcpyDeviceToHost, c->stream);
+  if (e != hipSuccess) return e;
+  return hipStreamSynchronize(c->stream);
+}
+
+static AggArgs agg_args(ink_ctx *c, int l) {       // layer l in 1..k aggregates m_l = H[l-1]
+  AggArgs a;
+  a.n = c->n;
+  a.in_off = c->gin.off; a.in_deg = c->gin.deg; a.in_ids = c->gin.ids;
+  a.M = c->H[l - 1].f(); a.ldm = c->H[l - 1].ld;
+  a.A = c->A[l].f(); a.ARG = c->ARG[l].i(); a.ld = c->A[l].ld; a.d = c->A[l].d;
+  a.is_min = c->is_min;
+  return a;
+}
+
+// dense combination of layer l for the rows in `rows` (null: all nodes).  With flags != null the
+// layer's table is updated with compare-and-emit.
+static hipError_t run_transform(ink_ctx *c, int l, const int32_t *rows, int64_t n_rows, uint8_t *flags) {
+  const DevLayer &L = c->layers[l - 1];
+  XformArgs x;
+  memset(&x, 0, sizeof(x));
+  x.rows = rows; x.n_rows = n_rows;
+  x.A = c->A[l].f(); x.lda = c->A[l].ld;
+  x.Hp = c->H[l - 1].f(); x.ldh = c->H[l - 1].ld;
+  x.d_in = L.in_dim; x.eps = c->eps;
+  if (c->kind == INK_MODEL_SAGE) {
+    x.mode = 0;
+    x.W = L.W1; x.Kp = L.K1p; x.Np = L.N1p; x.bias = L.b1; x.n_out = L.out_dim; x.relu = L.act == INK_ACT_RELU;
+    x.out = c->H[l].f(); x.ld_out = c->H[l].ld; x.to_table = 1; x.row_changed = flags;
+    return xform_run(c, x);
+  }
+  // GIN: two linear maps through a staging buffer
+  hipError_t e = c->stage0.reserve((size_t)n_rows * L.N1p * 4);
+  if (e != hipSuccess) return e;
+  x.mode = 1;
+  x.W = L.W1; x.Kp = L.K1p; x.Np = L.N1p; x.bias = L.b1; x.n_out = L.hidden; x.relu = 1;
+  x.out = c->stage0.as<float>(); x.ld_out = L.N1p; x.to_table = 0;
+  e = xform_run(c, x);
+  if (e != hipSuccess) return e;
+  XformArgs y;
+  memset(&y, 0, sizeof(y));
+  y.mode = 2; y.rows = rows; y.n_rows = n_rows;
+  y.Hp = c->stage0.as<float>(); y.ldh = L.N1p; y.d_in = L.hidden;
+  y.W = L.W2; y.Kp = L.K2p; y.Np = L.N2p; y.bias = L.b2; y.n_out = L.out_dim; y.relu = L.act == INK_ACT_RELU;
+  y.out = c->H[l].f(); y.ld_out = c->H[l].ld; y.to_table = 1; y.row_changed = flags; y.out_rows = rows;
+  return xform_run(c, y);
+}
+
+// ------------------------------------------------------------------------------------ create
+static ink_status validate_model(const ink_model *m, int feat_dim, std::string &why) {
+  if (m->n_layers < 1 || m->n_layers > INK_MAX_LAYERS || !m->layers) { why = "n_layers out of range or layers NULL"; return INK_E_ARG; }
+  if (m->kind != INK_MODEL_SAGE && m->kind != INK_MODEL_GIN && m->kind != INK_MODEL_GCN) { why = "unknown model kind"; return INK_E_ARG; }
+  bool select = m->agg == INK_AGG_MAX || m->agg == INK_AGG_MIN;
+  if (!select) { why = "aggregator not supported by this build for this model"; return INK_E_ARG; }
+  if (m->kind == INK_MODEL_GCN) { why = "GCN requires INK_AGG_GCN_SYM"; return INK_E_ARG; }
+  int d = feat_dim;
+  for (int l = 0; l < m->n_layers; l++) {
+    const ink_layer &L = m->layers[l];
+    if (L.in_dim != d) { why = "layer in_dim does not match the previous width"; return INK_E_ARG; }
+    if (L.in_dim < 1 || L.out_dim < 1 || L.in_dim > INK_MAX_AGG_DIM || L.out_dim > 256) { why = "layer width out of range (1..256)"; return INK_E_ARG; }
+    if (!L.W_neigh) { why = "W_neigh is NULL"; return INK_E_ARG; }
+    if (m->kind == INK_MODEL_SAGE && !L.W_self) { why = "GraphSAGE needs W_self"; return INK_E_ARG; }
+    if (m->kind == INK_MODEL_GIN && (!L.W_mlp2 || L.mlp_hidden < 1 || L.mlp_hidden > 256)) { why = "GIN needs W_mlp2 and 1 <= mlp_hidden <= 256"; return INK_E_ARG; }
+    if (L.act != INK_ACT_NONE && L.act != INK_ACT_RELU) { why = "unknown activation"; return INK_E_ARG; }
+    d = L.out_dim;
+  }
+  return INK_OK;
+}
+
+extern "C" ink_status ink_create(const ink_csr *g, const float *features, int32_t feat_dim, const ink_model *model,
+                                 const ink_options *opts, ink_ctx **out) {
+  if (out) *out = nullptr;
+  if (!g || !features || !model || !out || !g->rowptr || (g->n_edges > 0 && !g->col))
+    return fail(nullptr, INK_E_ARG, "ink_create: NULL argument");
+  if (g->n_nodes < 1 || g->n_edges < 0 || feat_dim < 1 || g->n_nodes >= (1 << 30))
+    return fail(nullptr, INK_E_ARG, "ink_create: bad n_nodes / n_edges / feat_dim");
+  std::string why;
+  ink_status st = validate_model(model, feat_dim, why);
+  if (st != INK_OK) return fail(nullptr, st, "ink_create: " + why);
+  const bool dev = opts && opts->mem == INK_MEM_DEVICE;
+  const int n = g->n_nodes;
+  const int64_t E = g->n_edges;
+  // graph to the host (validation and block layout are host work)
+  std::vector<int64_t> rowptr((size_t)n + 1);
+  std::vector<int32_t> col((size_t)E);
+  if (hipMemcpy(rowptr.data(), g->rowptr, rowptr.size() * 8, dev ? hipMemcpyDeviceToHost : hipMemcpyHostToHost) != hipSuccess ||
+      (E && hipMemcpy(col.data(), g->col, col.size() * 4, dev ? hipMemcpyDeviceToHost : hipMemcpyHostToHost) != hipSuccess))
+    return fail(nullptr, INK_E_DEVICE, "ink_create: cannot read the graph arrays");
+  if (rowptr[0] != 0 || rowptr[n] != E) return fail(nullptr, INK_E_ARG, "ink_create: rowptr[0] != 0 or rowptr[n] != n_edges");
+  for (int v = 0; v < n; v++) {
+    if (rowptr[v + 1] < rowptr[v]) return fail(nullptr, INK_E_ARG, "ink_create: rowptr not monotone");
+    for (int64_t e = rowptr[v]; e < rowptr[v + 1]; e++) {
+      int32_t u = col[e];
+      if (u < 0 || u >= n) return fail(nullptr, INK_E_RANGE, "ink_create: column id out of range");
+      if (u == v) return fail(nullptr, INK_E_ARG, "ink_create: self loop in the graph");
+      if (e > rowptr[v] && col[e - 1] >= u) return fail(nullptr, INK_E_ARG, "ink_create: row not strictly ascending");
+    }
+  }
+  ink_ctx *c = new (std::nothrow) ink_ctx();
+  if (!c) return fail(nullptr, INK_E_OOM, "ink_create: host allocation failed");
+  c->n = n; c->n_edges = E; c->n_edges_now = E;
+  c->id_bits = 1; while ((1ll << c->id_bits) < n) c->id_bits++;
+  c->kind = model->kind; c->agg = model->agg; c->n_layers = model->n_layers; c->eps = model->gin_eps;
+  c->is_select = true; c->is_min = model->agg == INK_AGG_MIN;
+  c->mem = dev ? INK_MEM_DEVICE : INK_MEM_HOST;
+  c->slack = (opts && opts->slack_factor > 0.f) ? opts->slack_factor : 0.25f;
+  c->profile = opts ? opts->profile : 0;
+  memset(&c->stats, 0, sizeof(c->stats));
+#define CREATE_TRY(x)                                                                              \
+  do {                                                                                             \
+    hipError_t e_ = (x);                                                                           \
+    if (e_ != hipSuccess) {                                                                        \
+      g_create_err = std::string("ink_create: HIP error: ") + hipGetErrorString(e_) + " at " #x;   \
+      ink_destroy(c);                                                                              \
+      return e_ == hipErrorOutOfMemory ? INK_E_OOM : INK_E_DEVICE;                                 \
+    }                                                                                              \
+  } while (0)
+  if (opts && opts->hip_stream) c->stream = (hipStream_t)opts->hip_stream;
+  else { CREATE_TRY(hipStreamCreate(&c->stream)); c->own_stream = true; }
+  CREATE_TRY(graph_build(c, rowptr.data(), col.data()));
+  CREATE_TRY(hipMalloc(&c->new_out, (size_t)n * 4));
+  CREATE_TRY(hipMemset(c->new_out, 0, (size_t)n * 4));
+  CREATE_TRY(hipMalloc(&c->d_cnt, sizeof(Counters)));
+  CREATE_TRY(hipMemset(c->d_cnt, 0, sizeof(Counters)));
+  CREATE_TRY(hipHostMalloc((void **)&c->h_cnt, sizeof(Counters)));
+  size_t bmw = ((size_t)n + 63) / 64;
+  CREATE_TRY(hipMalloc(&c->bm_a, bmw * 8));
+  CREATE_TRY(hipMemset(c->bm_a, 0, bmw * 8));
+  CREATE_TRY(c->big_list.reserve((size_t)(c->gin.pool_cap / kBigDeg + 4096) * 4));
+  // tables
+  c->H.resize(c->n_layers + 1); c->A.resize(c->n_layers + 1); c->ARG.resize(c->n_layers + 1);
+  CREATE_TRY(alloc_table(c->H[0], n, feat_dim));
+  {
+    DevBuf tmp;
+    const float *src = features;
+    if (!dev) {
+      CREATE_TRY(tmp.reserve((size_t)n * feat_dim * 4));
+      CREATE_TRY(hipMemcpy(tmp.p, features, (size_t)n * feat_dim * 4, hipMemcpyHostToDevice));
+      src = tmp.as<float>();
+    }
+    hipLaunchKernelGGL(k_unpack_rows, grid1((int64_t)n * feat_dim), dim3(256), 0, c->stream, src, (int)feat_dim,
+                       c->H[0].ld, (int64_t)n, c->H[0].f());
+    CREATE_TRY(hipStreamSynchronize(c->stream));
+    tmp.release();
+  }
+  c->layers.resize(c->n_layers);
+  for (int l = 1; l <= c->n_layers; l++) {
+    const ink_layer &S = model->layers[l - 1];
+    DevLayer &L = c->layers[l - 1];
+    L.in_dim = S.in_dim; L.out_dim = S.out_dim; L.hidden = S.mlp_hidden; L.act = S.act;
+    CREATE_TRY(alloc_table(c->H[l], n, S.out_dim));
+    CREATE_TRY(alloc_table(c->A[l], n, S.in_dim));
+    CREATE_TRY(alloc_table(c->ARG[l], n, S.in_dim));
+    if (c->kind == INK_MODEL_SAGE) {
+      L.K1 = 2 * S.in_dim; L.K1p = round_up(L.K1, 32); L.N1 = S.out_dim; L.N1p = round_up(L.N1, 32);
+      CREATE_TRY(hipMalloc(&L.W1, (size_t)L.K1p * L.N1p * 4));
+      CREATE_TRY(hipMemset(L.W1, 0, (size_t)L.K1p * L.N1p * 4));
+      CREATE_TRY(upload_padded(S.W_neigh, S.in_dim, S.out_dim, L.K1p, L.N1p, 0, L.W1, dev));
+      CREATE_TRY(upload_padded(S.W_self, S.in_dim, S.out_dim, L.K1p, L.N1p, S.in_dim, L.W1, dev));
+      CREATE_TRY(upload_vec(S.bias, S.out_dim, &L.b1, dev));
+    } else {   // GIN
+      L.K1 = S.in_dim; L.K1p = round_up(L.K1, 32); L.N1 = S.mlp_hidden; L.N1p = round_up(L.N1, 32);
+      L.K2 = S.mlp_hidden; L.K2p = round_up(L.K2, 32); L.N2 = S.out_dim; L.N2p = round_up(L.N2, 32);
+      CREATE_TRY(hipMalloc(&L.W1, (size_t)L.K1p * L.N1p * 4));
+      CREATE_TRY(hipMemset(L.W1, 0, (size_t)L.K1p * L.N1p * 4));
+      CREATE_TRY(upload_padded(S.W_neigh, S.in_dim, S.mlp_hidden, L.K1p, L.N1p, 0, L.W1, dev));
+      CREATE_TRY(upload_vec(S.bias, S.mlp_hidden, &L.b1, dev));
+      CREATE_TRY(hipMalloc(&L.W2, (size_t)L.K2p * L.N2p * 4));
+      CREATE_TRY(hipMemset(L.W2, 0, (size_t)L.K2p * L.N2p * 4));
+      CREATE_TRY(upload_padded(S.W_mlp2, S.mlp_hidden, S.out_dim, L.K2p, L.N2p, 0, L.W2, dev));
+      CREATE_TRY(upload_vec(S.bias_mlp2, S.out_dim, &L.b2, dev));
+    }
+  }
+  *out = c;
+  return INK_OK;
+}
+
+extern "C" void ink_destroy(ink_ctx *c) {
+  if (!c) return;
+  if (c->stream) (void)hipStreamSynchronize(c->stream);
+  for (GraphSide *g : {&c->gin, &c->gout}) {
+    if (g->off) (void)hipFree(g->off);
+    if (g->deg) (void)hipFree(g->deg);
+    if (g->cap) (void)hipFree(g->cap);
+    if (g->ids) (void)hipFree(g->ids);
+  }
+  if (c->new_out) (void)hipFree(c->new_out);
+  for (auto &L : c->layers) for (float *p : {L.W1, L.b1, L.W2, L.b2}) if (p) (void)hipFree(p);
+  for (auto *vec : {&c->H, &c->A, &c->ARG, &c->XW, &c->Msc}) for (auto &t : *vec) if (t.p) (void)hipFree(t.p);
+  if (c->cnorm) (void)hipFree(c->cnorm);
+  if (c->d_cnt) (void)hipFree(c->d_cnt);
+  if (c->h_cnt) (void)hipHostFree(c->h_cnt);
+  if (c->bm_a) (void)hipFree(c->bm_a);
+  if (c->bm_b) (void)hipFree(c->bm_b);
+  for (DevBuf *b : {&c->ws.blk, &c->ws.hist, &c->ws.tmpk, &c->ws.tmpv, &c->b_raw, &c->b_misc, &c->b_uniq, &c->b_del_s,
+                    &c->b_del_d, &c->b_ins_s, &c->b_ins_d, &c->f_list[0], &c->f_list[1], &c->f_old[0], &c->f_old[1],
+                    &c->f_pref, &c->ev_key, &c->ev_val, &c->t_list, &c->t_seg, &c->c_list, &c->c_flag, &c->c_idx,
+                    &c->big_list, &c->big_part_v, &c->big_part_i, &c->stage0, &c->stage1, &c->res_ids, &c->res_emb})
+    b->release();
+  for (auto e : c->ev_free) (void)hipEventDestroy(e);
+  for (auto &p : c->ev_pending) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
+  if (c->own_stream && c->stream) (void)hipStreamDestroy(c->stream);
+  delete c;
+}
+
+extern "C" const char *ink_last_error(const ink_ctx *c) { return c ? c->err.c_str() : g_create_err.c_str(); }
+
+// ------------------------------------------------------------------------------------ full inference
+extern "C" ink_status ink_full_infer(ink_ctx *c) {
+  if (!c) return INK_E_ARG;
+  auto t0 = std::chrono::steady_clock::now();
+  memset(&c->stats, 0, sizeof(c->stats));
+  c->stats.n_layers = c->n_layers;
+  for (int l = 1; l <= c->n_layers; l++) {
+    AggArgs a = agg_args(c, l);
+    { Prof p(c, INK_T_AGG); API_TRY(agg_select_full(c, a, nullptr, c->n, nullptr)); }
+    { Prof p(c, INK_T_TRANSFORM); API_TRY(run_transform(c, l, nullptr, c->n, nullptr)); }
+    ink_layer_stats &S = c->stats.layer[l - 1];
+    S.dense = 1; S.n_targets = c->n; S.n_exposed = c->n; S.n_regather_nb = c->n_edges_now; S.n_transformed = c->n;
+  }
+  API_TRY(hipStreamSynchronize(c->stream));
+  prof_collect(c);
+  c->inferred = true;
+  c->stats.ms_total = std::chrono::duration<float, std::milli>(std::chrono::steady_clock::now() - t0).count();
+  return INK_OK;
+}
+
+// ------------------------------------------------------------------------------------ updates
+extern "C" ink_status ink_apply_updates(ink_ctx *c, const ink_edge_update *upd, int64_t n, ink_update_result *out) {
+  if (!c) return INK_E_ARG;
+  if (!out || n < 0 || (n > 0 && !upd)) return fail(c, INK_E_ARG, "ink_apply_updates: NULL argument or negative n");
+  if (!c->inferred) return fail(c, INK_E_STATE, "ink_apply_updates: call ink_full_infer first");
+  if (n >= (1ll << 30)) return fail(c, INK_E_ARG, "ink_apply_updates: batch too large");
+  auto t0 = std::chrono::steady_clock::now();
+  memset(out, 0, sizeof(*out));
+  hipStream_t s = c->stream;
+  // validation on the host before anything is touched
+  std::vector<ink_edge_update> staged;
+  const ink_edge_update *h = upd;
+  if (c->mem == INK_MEM_DEVICE && n > 0) {
+    staged.resize((size_t)n);
+    API_TRY(hipMemcpy(staged.data(), upd, (size_t)n * sizeof(ink_edge_update), hipMemcpyDeviceToHost));
+    h = staged.data();
+  }
+  for (int64_t i = 0; i < n; i++) {
+    if (h[i].op > 1) return fail(c, INK_E_ARG, "ink_apply_updates: op must be 0 (insert) or 1 (delete)");
+    if (h[i].src < 0 || h[i].src >= c->n || h[i].dst < 0 || h[i].dst >= c->n)
+      return fail(c, INK_E_RANGE, "ink_apply_updates: node id out of range");
+  }
+  memset(&c->stats, 0, sizeof(c->stats));
+  c->stats.n_layers = c->n_layers;
+  int64_t n_ins = 0, n_del = 0;
+  if (n > 0) {
+    Prof p(c, INK_T_GRAPH);
+    API_TRY(c->b_raw.reserve((size_t)n * sizeof(ink_edge_update)));
+    API_TRY(hipMemcpyAsync(c->b_raw.p, upd, (size_t)n * sizeof(ink_edge_update),
+                           c->mem == INK_MEM_DEVICE ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice, s));
+    ink_status st = graph_apply_batch(c, n, &n_ins, &n_del);
+    if (st != INK_OK) return st;
+  }
+  out->n_applied_ins = n_ins; out->n_applied_del = n_del; out->n_noop = n - n_ins - n_del;
+  c->n_edges_now += n_ins - n_del;
+
+  int64_t nF = 0;            // |F_l|: sources whose message changed (F_1 is empty: features are static)
+  int cur = 0;               // f_list[cur] holds F_l
+  const int64_t n_seed = n_ins + n_del;
+  for (int l = 1; l <= c->n_layers && (n_seed > 0 || nF > 0); l++) {
+    ink_layer_stats &S = c->stats.layer[l - 1];
+    S.n_sources = nF;
+    Counters *dc = c->d_cnt;
+    const int32_t *F = c->f_list[cur].as<int32_t>();
+    AggArgs a = agg_args(c, l);
+    // ---- events: count what the changed sources will propagate
+    int64_t n_chg = 0;
+    {
+      Prof p(c, INK_T_EVENTS);
+      API_TRY(hipMemsetAsync(dc, 0, sizeof(Counters), s));
+      if (nF > 0) {
+        API_TRY(c->f_pref.reserve((size_t)(nF + 1) * 4));
+        API_TRY(tile_scan(c->ws, KeptOutDeg{F, c->gout.deg, c->new_out}, StorePref{c->f_pref.as<int32_t>()}, nF,
+                          &dc->v[C_NEV], s));
+        API_TRY(read_counters(c));
+        n_chg = (uint32_t)c->h_cnt->v[C_NEV];
+      }
+    }
+    int64_t nE = n_seed + n_chg;
+    S.n_events = nE;
+    uint64_t *bm = c->bm_a;
+    bool dense = nE > 0 && (double)nE > c->dense_frac * (double)std::max<int64_t>(c->n_edges_now, 1) && nE > 4096;
+    S.dense = dense;
+    if (dense) {
+      // so many events that re-aggregating every node costs less than grouping them
+      Prof p(c, INK_T_AGG);
+      API_TRY(agg_select_full(c, a, nullptr, c->n, bm));
+      S.n_targets = c->n; S.n_exposed = c->n; S.n_regather_nb = c->n_edges_now;
+    } else if (nE > 0) {
+      {
+        Prof p(c, INK_T_EVENTS);
+        API_TRY(c->ev_key.reserve((size_t)nE * 4));
+        API_TRY(c->ev_val.reserve((size_t)nE * 4));
+        uint32_t *key = c->ev_key.as<uint32_t>(), *val = c->ev_val.as<uint32_t>();
+        if (n_seed > 0)
+          hipLaunchKernelGGL(k_seed_events, grid1(n_seed), dim3(256), 0, s, (const int32_t *)c->del_src,
+                             (const int32_t *)c->del_dst, (const int32_t *)c->ins_src, (const int32_t *)c->ins_dst,
+                             (int)n_del, (int)n_ins, key, val);
+        if (n_chg > 0)
+          hipLaunchKernelGGL(k_expand_events, grid1(n_chg), dim3(256), 0, s, F, (int)nF,
+                             (const int32_t *)c->f_pref.as<int32_t>(), (int)n_chg, (const int64_t *)c->gout.off,
+                             (const int32_t *)c->gout.ids, key + n_seed, val + n_seed, 0);
+        API_TRY(hipGetLastError());
+      }
+      {
+        Prof p(c, INK_T_GROUP);
+        API_TRY(radix_sort_pairs(c->ws, c->ev_key.as<uint32_t>(), c->ev_val.as<uint32_t>(), nE, c->id_bits, s));
+        API_TRY(c->t_list.reserve((size_t)(nE + 1) * 4));
+        API_TRY(c->t_seg.reserve((size_t)(nE + 2) * 4));
+        API_TRY(segment_heads(c->ws, c->ev_key.as<uint32_t>(), nE, c->t_list.as<int32_t>(), c->t_seg.as<int32_t>(),
+                              &dc->v[C_NT], s));
+        API_TRY(read_counters(c));
+      }
+      int64_t nT = c->h_cnt->v[C_NT];
+      S.n_targets = nT;
+      {
+        Prof p(c, INK_T_AGG);
+        API_TRY(agg_select_events(c, a, c->t_list.as<int32_t>(), c->t_seg.as<int32_t>(), nT,
+                                  c->ev_val.as<uint32_t>(), bm));
+        S.n_exposed = c->h_cnt->v[C_EXPOSED];
+        S.n_regather_nb = *(int64_t *)&c->h_cnt->v[C_REGATHER_LO];
+        S.n_alpha_changed = c->h_cnt->v[C_ACHG];
+      }
+    }
+    // ---- rows to transform: alpha changed, or own previous-layer embedding changed (self term)
+    int64_t nC = 0;
+    {
+      Prof p(c, INK_T_COMPACT);
+      if (nF > 0) hipLaunchKernelGGL(k_mark_nodes, grid1(nF), dim3(256), 0, s, F, (int)nF, bm);
+      API_TRY(c->c_list.reserve((size_t)c->n * 4));
+      API_TRY(bitmap_to_list(c->ws, bm, c->n, c->c_list.as<int32_t>(), &dc->v[C_NC], 1, s));
+      API_TRY(read_counters(c));
+      nC = c->h_cnt->v[C_NC];
+    }
+    S.n_transformed = nC;
+    int nxt = cur ^ 1;
+    int64_t nF2 = 0;
+    if (nC > 0) {
+      API_TRY(c->c_flag.reserve((size_t)nC + 64));
+      API_TRY(c->c_idx.reserve((size_t)nC * 4));
+      API_TRY(c->f_list[nxt].reserve((size_t)nC * 4));
+      {
+        Prof p(c, INK_T_TRANSFORM);
+        API_TRY(run_transform(c, l, c->c_list.as<int32_t>(), nC, c->c_flag.as<uint8_t>()));
+      }
+      {
+        Prof p(c, INK_T_COMPACT);
+        API_TRY(compact_flags_u8(c->ws, c->c_flag.as<uint8_t>(), nC, c->c_idx.as<int32_t>(), &dc->v[C_NEXT], s));
+        API_TRY(read_counters(c));
+        nF2 = c->h_cnt->v[C_NEXT];
+        if (nF2 > 0)
+          hipLaunchKernelGGL(k_gather_i32, grid1(nF2), dim3(256), 0, s, (const int32_t *)c->c_list.as<int32_t>(),
+                             (const int32_t *)c->c_idx.as<int32_t>(), (int)nF2, c->f_list[nxt].as<int32_t>());
+      }
+    }
+    S.n_changed = nF2;
+    nF = nF2;
+    cur = nxt;
+    if (l == c->n_layers) {
+      out->n_changed = nF;
+      if (nF > 0) {
+        int d = c->H[l].d;
+        API_TRY(c->res_ids.reserve((size_t)nF * 4));
+        API_TRY(c->res_emb.reserve((size_t)nF * d * 4));
+        API_TRY(hipMemcpyAsync(c->res_ids.p, c->f_list[cur].p, (size_t)nF * 4, hipMemcpyDeviceToDevice, s));
+        hipLaunchKernelGGL(k_gather_rows, grid1(nF * d), dim3(256), 0, s, (const float *)c->H[l].f(), c->H[l].ld, d,
+                           (const int32_t *)c->res_ids.p, nF, c->res_emb.as<float>());
+        out->changed_ids = c->res_ids.as<int32_t>();
+        out->embeddings = c->res_emb.as<float>();
+      }
+    }
+  }
+  API_TRY(graph_end_batch(c));
+  API_TRY(hipStreamSynchronize(s));
+  prof_collect(c);
+  c->stats.ms_total = std::chrono::duration<float, std::milli>(std::chrono::steady_clock::now() - t0).count();
+  return INK_OK;
+}
+
+// ------------------------------------------------------------------------------------ inspection
+extern "C" ink_status ink_get_layer(ink_ctx *c, int32_t layer, int32_t which, int64_t row0, int64_t nrows, void *dst,
+                                    int32_t dst_mem, int32_t *width_out) {
+  if (!c) return INK_E_ARG;
+  if (!c->inferred) return fail(c, INK_E_STATE, "ink_get_layer: call ink_full_infer first");
+  if (layer < 0 || layer > c->n_layers || which < 0 || which > 2 || (which > 0 && layer == 0))
+    return fail(c, INK_E_RANGE, "ink_get_layer: layer / which out of range");
+  if (row0 < 0 || nrows < 0 || row0 + nrows > c->n) return fail(c, INK_E_RANGE, "ink_get_layer: rows out of range");
+  const Table &t = which == 0 ? c->H[layer] : (which == 1 ? c->A[layer] : c->ARG[layer]);
+  if (!t.p) return fail(c, INK_E_ARG, "ink_get_layer: table not kept for this model");
+  if (width_out) *width_out = t.d;
+  if (nrows == 0) return INK_OK;
+  if (!dst) return fail(c, INK_E_ARG, "ink_get_layer: dst is NULL");
+  size_t bytes = (size_t)nrows * t.d * 4;
+  void *dev_dst = dst;
+  if (dst_mem != INK_MEM_DEVICE) { API_TRY(c->stage1.reserve(bytes)); dev_dst = c->stage1.p; }
+  hipLaunchKernelGGL(k_pack_rows, grid1(nrows * t.d), dim3(256), 0, c->stream, (const void *)t.p, t.ld, t.d, row0, nrows,
+                     dev_dst);
+  API_TRY(hipGetLastError());
+  if (dst_mem != INK_MEM_DEVICE) API_TRY(hipMemcpyAsync(dst, dev_dst, bytes, hipMemcpyDeviceToHost, c->stream));
+  API_TRY(hipStreamSynchronize(c->stream));
+  return INK_OK;
+}
+
+extern "C" ink_status ink_get_graph(ink_ctx *c, int64_t *rowptr, int32_t *col) {
+  if (!c || !rowptr) return INK_E_ARG;
+  API_TRY(hipStreamSynchronize(c->stream));
+  API_TRY(graph_export(c, rowptr, col));
+  return INK_OK;
+}
+
+extern "C" ink_status ink_get_stats(ink_ctx *c, void *dst, size_t bytes) {
+  if (!c || !dst) return INK_E_ARG;
+  memcpy(dst, &c->stats, std::min(bytes, sizeof(ink_stats)));
+  return INK_OK;
+}

@@ -1,0 +1,145 @@
+// Internal context of the library: device-resident graph store, cached per-layer tables and
+// the work buffers of the per-layer event pipeline.  Not part of the C ABI.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <string>
+#include <vector>
+
+#include "../../include/ink.h"
+#include "prim.h"
+
+namespace ink {
+
+constexpr int kBigDeg = 4096;      // rows with more in-neighbours are re-gathered cooperatively
+constexpr int kBigParts = 64;      // workgroups sharing one such row
+constexpr uint32_t kEvKindShift = 30;
+constexpr uint32_t kEvIdMask = (1u << kEvKindShift) - 1;
+enum : uint32_t { EV_DEL = 0, EV_ADD = 1, EV_CHG = 2 };   // removed edge / inserted edge / changed source
+
+// One direction of the graph store: per-node edge blocks with slack inside one id pool.
+struct GraphSide {
+  int64_t *off = nullptr;    // [n] first slot of the node's block
+  int32_t *deg = nullptr;    // [n] used slots
+  int32_t *cap = nullptr;    // [n] block capacity
+  int32_t *ids = nullptr;    // pool
+  int64_t pool_cap = 0;      // slots in the pool
+  int64_t pool_top = 0;      // first free slot (host mirror, exact)
+};
+
+struct Table {               // N x d float (or int) table with row stride ld (multiple of 4)
+  void *p = nullptr;
+  int d = 0, ld = 0;
+  float *f() const { return (float *)p; }
+  int32_t *i() const { return (int32_t *)p; }
+};
+
+struct DevLayer {
+  int in_dim = 0, out_dim = 0, hidden = 0, act = 0;
+  // first (or only) linear map: rows = K (padded to a multiple of 32), cols = ldw (multiple of 32)
+  float *W1 = nullptr; int K1 = 0, K1p = 0, N1 = 0, N1p = 0; float *b1 = nullptr;
+  float *W2 = nullptr; int K2 = 0, K2p = 0, N2 = 0, N2p = 0; float *b2 = nullptr;   // GIN second linear
+};
+
+struct Counters {            // device-written, host-read through pinned memory
+  int32_t v[32];
+};
+enum { C_NF = 0, C_NEV, C_NT, C_NBIG, C_NC, C_NEXT, C_EXPOSED, C_ACHG, C_TMP0, C_TMP1, C_TMP2, C_TMP3,
+       C_REGATHER_LO = 16, C_REGATHER_HI = 17 };
+
+}  // namespace ink
+
+struct ink_ctx {
+  int n = 0;
+  int64_t n_edges = 0, n_edges_now = 0;
+  double dense_frac = 0.75;          // events / edges above which a layer re-aggregates every node
+  int id_bits = 1;
+  int kind = 0, agg = 0, n_layers = 0, mem = 0, profile = 0;
+  float eps = 0.f, slack = 0.25f;
+  bool is_select = true, is_min = false, inferred = false, own_stream = false;
+  hipStream_t stream = nullptr;
+  std::string err;
+
+  ink::GraphSide gin, gout;
+  int32_t *new_out = nullptr;        // [n] out-edges appended by the current batch (tail of the block)
+  std::vector<ink::DevLayer> layers;
+  // tables: H[0..k]; A[1..k] aggregated (sum-type: plain sums); ARG[1..k]
+  std::vector<ink::Table> H, A, ARG;
+  // GCN only: XW[l] = unscaled transformed messages h_{l-1} W_l, H-like scaled copies live in Msc[l]
+  std::vector<ink::Table> XW, Msc;
+  float *cnorm = nullptr;            // GCN: (indeg + 1)^(-1/2) per node
+
+  ink::PrimWorkspace ws;
+  ink::Counters *d_cnt = nullptr;    // device counters
+  ink::Counters *h_cnt = nullptr;    // pinned host mirror
+  uint64_t *bm_a = nullptr;          // node bitmaps (n bits each)
+  uint64_t *bm_b = nullptr;
+
+  // batch buffers (sized for max_batch, grown on demand)
+  int64_t n_touched_src = 0;         // sources whose out-block got new ids in the current batch
+  ink::DevBuf b_raw, b_k0, b_k1, b_v0, b_v1, b_op, b_eff, b_pos, b_seg, b_uniq, b_misc;
+  int32_t *del_src = nullptr, *del_dst = nullptr, *ins_src = nullptr, *ins_dst = nullptr;  // Delta E lists
+  ink::DevBuf b_del_s, b_del_d, b_ins_s, b_ins_d;
+  int64_t n_del = 0, n_ins = 0;
+
+  // per-layer pipeline buffers
+  ink::DevBuf f_list[2];             // F_l (ascending node ids), ping-pong between layers
+  ink::DevBuf f_old[2];              // old message rows of F_l (sum-type aggregators)
+  ink::DevBuf f_pref;                // prefix of out-degrees over F_l
+  ink::DevBuf ev_key, ev_val;        // events
+  ink::DevBuf t_list, t_seg;         // unique targets, segment offsets
+  ink::DevBuf c_list, c_flag, c_idx; // rows to transform, per-row changed flag, compacted positions
+  ink::DevBuf big_list, big_part_v, big_part_i;   // cooperative re-gather
+  ink::DevBuf stage0, stage1;        // transform staging
+  ink::DevBuf res_ids, res_emb;      // result of the last batch
+
+  ink_stats stats;
+  struct Pending { int cls; hipEvent_t a, b; };
+  std::vector<hipEvent_t> ev_free;
+  std::vector<Pending> ev_pending;
+};
+
+namespace ink {
+
+// ---- graph store (graph.hip)
+hipError_t graph_build(ink_ctx *c, const int64_t *rowptr_h, const int32_t *col_h);
+// applies a validated batch already on the device in c->b_raw; fills Delta E lists and counts
+ink_status graph_apply_batch(ink_ctx *c, int64_t n, int64_t *n_ins, int64_t *n_del);
+hipError_t graph_end_batch(ink_ctx *c);     // clears per-batch marks (new_out)
+hipError_t graph_export(ink_ctx *c, int64_t *rowptr_h, int32_t *col_h);
+
+// ---- aggregation (agg.hip)
+struct AggArgs {
+  int n;
+  const int64_t *in_off; const int32_t *in_deg; const int32_t *in_ids;
+  const float *M; int ldm;          // message table
+  float *A; int32_t *ARG; int ld;   // aggregated table and argument table (row stride ld)
+  int d;
+  bool is_min;
+};
+// full re-aggregation of every node (targets == nullptr) or of a target list; flags rows whose
+// alpha changed in bitmap `chg` (may be null); big rows go through the cooperative path
+hipError_t agg_select_full(ink_ctx *c, const AggArgs &a, const int32_t *targets, int64_t n_targets,
+                           uint64_t *chg);
+hipError_t agg_select_events(ink_ctx *c, const AggArgs &a, const int32_t *targets, const int32_t *seg,
+                             int64_t n_targets, const uint32_t *ev_val, uint64_t *chg);
+
+// ---- dense transform (xform.hip)
+struct XformArgs {
+  int mode;                 // 0 SAGE concat [A | Hprev], 1 GIN (1+eps) Hprev + A, 2 dense rows
+  const int32_t *rows;      // row ids (null: identity)
+  int64_t n_rows;
+  const float *A; int lda;  // aggregated table
+  const float *Hp; int ldh; // previous-layer table (or dense input for mode 2)
+  int d_in;
+  float eps;
+  const float *W; int Kp; int Np; const float *bias; int n_out; int relu;
+  // output: either staging (dense [n_rows][ld_out]) or table rows with compare-and-emit
+  float *out; int ld_out; int to_table;
+  uint8_t *row_changed;     // [n_rows] set to 1 if the table row changed bitwise (to_table)
+  float *old_rows; int ld_old;   // optional copy of the previous table rows ([n_rows][ld_old])
+  const int32_t *out_rows;  // table row ids for to_table when the input is dense (mode 2); null: identity
+};
+hipError_t xform_run(ink_ctx *c, const XformArgs &x);
+
+}  // namespace ink

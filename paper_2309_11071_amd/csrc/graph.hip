@@ -1,0 +1,532 @@
+// Device graph store: for each direction (in-neighbours for aggregation / recompute, Sec. 2.5.2;
+// out-neighbours for event propagation, Sec. 2.4.2) every node owns a block of ids with slack
+// inside one pool.  A batch is normalised to its net effect on the edge set, then applied per
+// touched node: deleted slots are refilled from the block's tail, inserted ids are appended, a
+// full block moves to a larger one at the pool's end.  Every step is a deterministic function of
+// the batch and the current store.
+#include <algorithm>
+#include <vector>
+
+#include "ctx.h"
+
+namespace ink {
+
+
+#define INK_TRYS(x) do { hipError_t e_ = (x); if (e_ != hipSuccess) { c->err = std::string("HIP error: ") + hipGetErrorString(e_); return INK_E_DEVICE; } } while (0)
+
+static inline int64_t align4(int64_t x) { return (x + 3) & ~(int64_t)3; }
+
+static int32_t block_cap(int64_t deg, float slack) {
+  int64_t extra = (int64_t)(deg * (double)slack + 0.999);
+  if (extra < 4) extra = 4;
+  return (int32_t)align4(deg + extra);
+}
+
+static hipError_t side_alloc(GraphSide &g, int n, const std::vector<int64_t> &off, const std::vector<int32_t> &deg,
+                             const std::vector<int32_t> &cap, const std::vector<int32_t> &ids, int64_t top) {
+  int64_t reserve = std::max<int64_t>(top / 4, 1 << 20);
+  g.pool_cap = top + reserve;
+  g.pool_top = top;
+  INK_TRY(hipMalloc(&g.off, sizeof(int64_t) * (size_t)n));
+  INK_TRY(hipMalloc(&g.deg, sizeof(int32_t) * (size_t)n));
+  INK_TRY(hipMalloc(&g.cap, sizeof(int32_t) * (size_t)n));
+  INK_TRY(hipMalloc(&g.ids, sizeof(int32_t) * (size_t)g.pool_cap));
+  INK_TRY(hipMemcpy(g.off, off.data(), sizeof(int64_t) * (size_t)n, hipMemcpyHostToDevice));
+  INK_TRY(hipMemcpy(g.deg, deg.data(), sizeof(int32_t) * (size_t)n, hipMemcpyHostToDevice));
+  INK_TRY(hipMemcpy(g.cap, cap.data(), sizeof(int32_t) * (size_t)n, hipMemcpyHostToDevice));
+  INK_TRY(hipMemcpy(g.ids, ids.data(), sizeof(int32_t) * (size_t)top, hipMemcpyHostToDevice));
+  return hipSuccess;
+}
+
+hipError_t graph_build(ink_ctx *c, const int64_t *rowptr, const int32_t *col) {
+  const int n = c->n;
+  const int64_t E = rowptr[n];
+  std::vector<int64_t> off(n);
+  std::vector<int32_t> deg(n), cap(n);
+  // in side straight from the CSR
+  int64_t top = 0;
+  for (int v = 0; v < n; v++) {
+    int64_t d = rowptr[v + 1] - rowptr[v];
+    off[v] = top; deg[v] = (int32_t)d; cap[v] = block_cap(d, c->slack);
+    top += cap[v];
+  }
+  {
+    std::vector<int32_t> ids((size_t)top, -1);
+    for (int v = 0; v < n; v++) std::copy(col + rowptr[v], col + rowptr[v + 1], ids.begin() + off[v]);
+    INK_TRY(side_alloc(c->gin, n, off, deg, cap, ids, top));
+  }
+  // out side: transpose
+  std::vector<int32_t> odeg(n, 0);
+  for (int64_t e = 0; e < E; e++) odeg[col[e]]++;
+  top = 0;
+  for (int v = 0; v < n; v++) {
+    off[v] = top; deg[v] = odeg[v]; cap[v] = block_cap(odeg[v], c->slack);
+    top += cap[v];
+  }
+  {
+    std::vector<int32_t> ids((size_t)top, -1);
+    std::vector<int64_t> cur(off);
+    for (int v = 0; v < n; v++)
+      for (int64_t e = rowptr[v]; e < rowptr[v + 1]; e++) ids[cur[col[e]]++] = v;
+    INK_TRY(side_alloc(c->gout, n, off, deg, cap, ids, top));
+  }
+  return hipSuccess;
+}
+
+hipError_t graph_export(ink_ctx *c, int64_t *rowptr, int32_t *col) {
+  const int n = c->n;
+  std::vector<int64_t> off(n);
+  std::vector<int32_t> deg(n);
+  INK_TRY(hipMemcpy(off.data(), c->gin.off, sizeof(int64_t) * (size_t)n, hipMemcpyDeviceToHost));
+  INK_TRY(hipMemcpy(deg.data(), c->gin.deg, sizeof(int32_t) * (size_t)n, hipMemcpyDeviceToHost));
+  rowptr[0] = 0;
+  for (int v = 0; v < n; v++) rowptr[v + 1] = rowptr[v] + deg[v];
+  if (!col) return hipSuccess;
+  std::vector<int32_t> pool((size_t)c->gin.pool_top);
+  INK_TRY(hipMemcpy(pool.data(), c->gin.ids, sizeof(int32_t) * pool.size(), hipMemcpyDeviceToHost));
+  for (int v = 0; v < n; v++) {
+    std::copy(pool.begin() + off[v], pool.begin() + off[v] + deg[v], col + rowptr[v]);
+    std::sort(col + rowptr[v], col + rowptr[v + 1]);
+  }
+  return hipSuccess;
+}
+
+// ------------------------------------------------------------------------------- batch kernels
+struct RawUpdate { uint8_t op; uint8_t pad[3]; int32_t src, dst; };
+
+__global__ void k_unpack(const RawUpdate *raw, int64_t n, uint32_t *src, uint32_t *dst, uint32_t *pos) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  src[i] = (uint32_t)raw[i].src;
+  dst[i] = (uint32_t)raw[i].dst;
+  pos[i] = (uint32_t)i;
+}
+
+__global__ void k_gather_u32(const uint32_t *table, const uint32_t *idx, int64_t n, uint32_t *out) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) out[i] = table[idx[i]];
+}
+
+// entry j (in (dst, src, position) order) is the final word on its edge if the next entry names
+// another edge; self loops never count
+__global__ void k_mark_last(const RawUpdate *raw, const uint32_t *perm, int64_t n, uint8_t *flag) {
+  int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= n) return;
+  RawUpdate a = raw[perm[j]];
+  bool last = true;
+  if (j + 1 < n) {
+    RawUpdate b = raw[perm[j + 1]];
+    last = (a.src != b.src) || (a.dst != b.dst);
+  }
+  flag[j] = last && a.src != a.dst;
+}
+
+// unique ops in (dst, src) order: node = dst, other = src, op = final op
+__global__ void k_take_ops(const RawUpdate *raw, const uint32_t *perm, const int32_t *idx, const int32_t *count,
+                           uint32_t *node, int32_t *other, uint8_t *op, int32_t *pos) {
+  int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (k >= *count) return;
+  RawUpdate a = raw[perm[idx[k]]];
+  node[k] = (uint32_t)a.dst;
+  other[k] = a.src;
+  op[k] = a.op;
+  pos[k] = -1;
+}
+
+// chunks of 2048 block slots per touched node
+constexpr int kChunk = 2048;
+__global__ void k_chunk_counts(const int32_t *nodes, const int32_t *n_nodes, const int32_t *deg, int32_t *chunks) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= *n_nodes) return;
+  chunks[i] = (deg[nodes[i]] + kChunk - 1) / kChunk;
+}
+
+// Walk the blocks of the touched nodes; an id found in the node's op list records its slot and,
+// if the op is a delete, becomes a tombstone (-1).
+__global__ __launch_bounds__(256) void k_classify(const int32_t *nodes, const int32_t *n_nodes, const int32_t *seg,
+                                                  const int32_t *chunk_pref, const int32_t *n_chunks,
+                                                  const int64_t *off, const int32_t *deg, int32_t *ids,
+                                                  const int32_t *other, const uint8_t *op, int32_t *pos) {
+  int total = *n_chunks, nn = *n_nodes;
+  for (int ch = blockIdx.x; ch < total; ch += gridDim.x) {
+    // node owning this chunk: last i with chunk_pref[i] <= ch
+    int lo = 0, hi = nn - 1;
+    while (lo < hi) {
+      int mid = (lo + hi + 1) >> 1;
+      if (chunk_pref[mid] <= ch) lo = mid; else hi = mid - 1;
+    }
+    int i = lo;
+    int v = nodes[i];
+    int s0 = seg[i], s1 = seg[i + 1];
+    int d = deg[v];
+    int64_t base = off[v];
+    int p0 = (ch - chunk_pref[i]) * kChunk;
+    int p1 = p0 + kChunk < d ? p0 + kChunk : d;
+    for (int p = p0 + threadIdx.x; p < p1; p += blockDim.x) {
+      int e = ids[base + p];
+      int a = s0, b = s1 - 1;
+      while (a <= b) {
+        int m = (a + b) >> 1;
+        int x = other[m];
+        if (x == e) {
+          pos[m] = p;
+          if (op[m] == 1) ids[base + p] = -1;
+          break;
+        }
+        if (x < e) a = m + 1; else b = m - 1;
+      }
+    }
+  }
+}
+
+// per touched node: effective op flags, counts and the pool space a relocation would need.
+// eff: 0 no-op, 1 insert, 2 delete.  One wave per node.
+__global__ __launch_bounds__(256) void k_effect(const int32_t *nodes, const int32_t *n_nodes, const int32_t *seg,
+                                                const uint8_t *op, const int32_t *pos, uint8_t *eff,
+                                                const int32_t *deg, const int32_t *cap, int32_t *nd_ins,
+                                                int32_t *nd_del, float slack, unsigned long long *need,
+                                                int32_t *tot_ins, int32_t *tot_del) {
+  int64_t w = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kWave;
+  int l = threadIdx.x & (kWave - 1);
+  if (w >= *n_nodes) return;
+  int s0 = seg[w], s1 = seg[w + 1];
+  int ni = 0, nd = 0;
+  for (int k = s0 + l; k < s1; k += kWave) {
+    int e = 0;
+    if (op[k] == 0) e = pos[k] < 0 ? 1 : 0;
+    else e = pos[k] >= 0 ? 2 : 0;
+    eff[k] = (uint8_t)e;
+    ni += e == 1;
+    nd += e == 2;
+  }
+  for (int o = 32; o > 0; o >>= 1) { ni += __shfl_xor(ni, o, kWave); nd += __shfl_xor(nd, o, kWave); }
+  if (l == 0) {
+    int v = nodes[w];
+    nd_ins[w] = ni; nd_del[w] = nd;
+    int nd2 = deg[v] - nd + ni;
+    if (nd2 > cap[v]) {
+      long long want = 2ll * cap[v];
+      long long extra = (long long)(nd2 * (double)slack + 0.999);
+      if (extra < 4) extra = 4;
+      if (want < nd2 + extra) want = nd2 + extra;
+      want = (want + 3) & ~3ll;
+      atomicAdd(need, (unsigned long long)want);
+    }
+    if (ni) atomicAdd(tot_ins, ni);
+    if (nd) atomicAdd(tot_del, nd);
+  }
+}
+
+// One workgroup per touched node: refill deleted slots from the tail, relocate if the block is
+// too small, append inserted ids.  `fill` is scratch with one slot per op of the batch.
+__global__ __launch_bounds__(256) void k_apply(const int32_t *nodes, const int32_t *seg, const int32_t *other,
+                                               const uint8_t *eff, const int32_t *pos, const int32_t *nd_ins,
+                                               const int32_t *nd_del, int64_t *off, int32_t *deg, int32_t *cap,
+                                               int32_t *ids, unsigned long long *pool_top, float slack,
+                                               int32_t *fill, int32_t *new_cnt) {
+  __shared__ int sm[kScanThreads / kWave + 1];
+  __shared__ long long s_newoff;
+  const int i = blockIdx.x;
+  const int v = nodes[i];
+  const int s0 = seg[i], s1 = seg[i + 1];
+  const int ni = nd_ins[i], nd = nd_del[i];
+  if (ni == 0 && nd == 0) return;
+  const int d0 = deg[v];
+  const int d1 = d0 - nd;             // survivors of the old block
+  int64_t base = off[v];
+  if (nd > 0) {
+    // survivors in the tail [d1, d0), in slot order -> fill[s0 ...]
+    int carry = 0;
+    for (int p0 = d1; p0 < d0; p0 += kScanThreads) {
+      int p = p0 + threadIdx.x;
+      int e = p < d0 ? ids[base + p] : -1;
+      int tot;
+      int ex = block_excl_scan(e >= 0 ? 1 : 0, sm, &tot);
+      if (e >= 0) fill[s0 + carry + ex] = e;
+      carry += tot;
+      __syncthreads();
+    }
+    __threadfence_block();
+    __syncthreads();
+    // holes in the head [0, d1), in op order, take them in turn
+    carry = 0;
+    for (int k0 = s0; k0 < s1; k0 += kScanThreads) {
+      int k = k0 + threadIdx.x;
+      bool hole = k < s1 && eff[k] == 2 && pos[k] < d1;
+      int tot;
+      int ex = block_excl_scan(hole ? 1 : 0, sm, &tot);
+      if (hole) ids[base + pos[k]] = fill[s0 + carry + ex];
+      carry += tot;
+      __syncthreads();
+    }
+  }
+  int d2 = d1 + ni;
+  if (d2 > cap[v]) {
+    if (threadIdx.x == 0) {
+      long long want = 2ll * cap[v];
+      long long extra = (long long)(d2 * (double)slack + 0.999);
+      if (extra < 4) extra = 4;
+      if (want < d2 + extra) want = d2 + extra;
+      want = (want + 3) & ~3ll;
+      s_newoff = (long long)atomicAdd(pool_top, (unsigned long long)want);
+      cap[v] = (int32_t)want;
+      off[v] = s_newoff;
+    }
+    __syncthreads();
+    int64_t nb = s_newoff;
+    for (int p = threadIdx.x; p < d1; p += blockDim.x) ids[nb + p] = ids[base + p];
+    base = nb;
+    __syncthreads();
+  }
+  if (ni > 0) {
+    int carry = 0;
+    for (int k0 = s0; k0 < s1; k0 += kScanThreads) {
+      int k = k0 + threadIdx.x;
+      bool ins = k < s1 && eff[k] == 1;
+      int tot;
+      int ex = block_excl_scan(ins ? 1 : 0, sm, &tot);
+      if (ins) ids[base + d1 + carry + ex] = other[k];
+      carry += tot;
+      __syncthreads();
+    }
+  }
+  if (threadIdx.x == 0) {
+    deg[v] = d2;
+    if (new_cnt) new_cnt[v] = ni;
+  }
+}
+
+// effective ops -> Delta E lists in (node, other) order
+__global__ void k_split_ops(const uint32_t *node, const int32_t *other, const uint8_t *eff, const int32_t *n_ops,
+                            const int32_t *idx_ins, const int32_t *idx_del, int32_t *ins_s, int32_t *ins_d,
+                            int32_t *del_s, int32_t *del_d, const int32_t *n_ins, const int32_t *n_del) {
+  int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (k < *n_ins) { int j = idx_ins[k]; ins_s[k] = other[j]; ins_d[k] = (int32_t)node[j]; }
+  if (k < *n_del) { int j = idx_del[k]; del_s[k] = other[j]; del_d[k] = (int32_t)node[j]; }
+}
+__global__ void k_flag_eq(const uint8_t *eff, const int32_t *n_ops, uint8_t want, uint8_t *flag) {
+  int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (k < *n_ops) flag[k] = eff[k] == want;
+}
+
+// out side: ops = [deletes | inserts] keyed by source
+__global__ void k_out_ops(const int32_t *del_s, const int32_t *del_d, const int32_t *ins_s, const int32_t *ins_d,
+                          int n_del, int n_ins, uint32_t *key, uint32_t *val) {
+  int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (k < n_del) { key[k] = (uint32_t)del_s[k]; val[k] = (uint32_t)k; }
+  else if (k < n_del + n_ins) { key[k] = (uint32_t)ins_s[k - n_del]; val[k] = (uint32_t)k; }
+}
+// after a stable sort by source of entries that were in (dst, src) order per kind, entries of one
+// source are not yet ordered by destination across the two kinds; a second stable sort fixes the
+// order: we sort by destination first, then by source (both stable)
+__global__ void k_out_dst_key(const int32_t *del_d, const int32_t *ins_d, int n_del, int n_ins, uint32_t *key,
+                              uint32_t *val) {
+  int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (k < n_del) { key[k] = (uint32_t)del_d[k]; val[k] = (uint32_t)k; }
+  else if (k < n_del + n_ins) { key[k] = (uint32_t)ins_d[k - n_del]; val[k] = (uint32_t)k; }
+}
+__global__ void k_out_take(const uint32_t *perm, const int32_t *del_s, const int32_t *del_d, const int32_t *ins_s,
+                           const int32_t *ins_d, int n_del, int n_ins, uint32_t *node, int32_t *other, uint8_t *op,
+                           int32_t *pos) {
+  int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (k >= n_del + n_ins) return;
+  int j = (int)perm[k];
+  if (j < n_del) { node[k] = (uint32_t)del_s[j]; other[k] = del_d[j]; op[k] = 1; }
+  else { node[k] = (uint32_t)ins_s[j - n_del]; other[k] = ins_d[j - n_del]; op[k] = 0; }
+  pos[k] = -1;
+}
+
+__global__ void k_zero_at(const int32_t *nodes, int n, int32_t *arr) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) arr[nodes[i]] = 0;
+}
+
+__global__ void k_copy_blocks(int n, const int64_t *off, const int32_t *deg, const int32_t *src, int32_t *dst) {
+  // one wave per node; offsets are unchanged (same layout in a larger pool)
+  int64_t w = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kWave;
+  int l = threadIdx.x & (kWave - 1);
+  if (w >= n) return;
+  int64_t o = off[w];
+  int d = deg[w];
+  for (int p = l; p < d; p += kWave) dst[o + p] = src[o + p];
+}
+
+static inline dim3 grid1(int64_t n, int per = 256) { return dim3((unsigned)std::max<int64_t>(1, (n + per - 1) / per)); }
+
+struct Arena {
+  char *base; size_t used = 0, cap;
+  Arena(DevBuf &b) : base((char *)b.p), cap(b.cap) {}
+  template <class T> T *get(size_t n) {
+    size_t bytes = (n * sizeof(T) + 255) & ~(size_t)255;
+    T *p = (T *)(base + used);
+    used += bytes;
+    return p;
+  }
+};
+
+static hipError_t grow_pool(ink_ctx *c, GraphSide &g, int64_t need_total) {
+  int64_t new_cap = std::max<int64_t>(g.pool_cap * 2, g.pool_top + need_total + (1 << 20));
+  int32_t *np = nullptr;
+  INK_TRY(hipMalloc(&np, sizeof(int32_t) * (size_t)new_cap));
+  hipLaunchKernelGGL(k_copy_blocks, grid1((int64_t)c->n * kWave), dim3(256), 0, c->stream, c->n,
+                     (const int64_t *)g.off, (const int32_t *)g.deg, (const int32_t *)g.ids, np);
+  INK_TRY(hipStreamSynchronize(c->stream));
+  INK_TRY(hipFree(g.ids));
+  g.ids = np;
+  g.pool_cap = new_cap;
+  return hipSuccess;
+}
+
+// One direction.  Ops (node, other, op, pos) are in (node, other) order on the device; n_ops is
+// known on the host.  all_effective: presence was already established (out side).
+struct SideBufs {
+  uint32_t *node; int32_t *other; uint8_t *op; int32_t *pos; uint8_t *eff;
+  int32_t *uniq, *seg, *chunks, *chunk_pref, *nd_ins, *nd_del, *fill;
+};
+
+static ink_status apply_side(ink_ctx *c, GraphSide &g, SideBufs &b, int64_t n_ops, int32_t *new_cnt,
+                             int *n_touched_out, int64_t *tot_ins, int64_t *tot_del) {
+  hipStream_t s = c->stream;
+  Counters *dc = c->d_cnt;
+  INK_TRYS(hipMemsetAsync(dc, 0, sizeof(Counters), s));
+  INK_TRYS(segment_heads(c->ws, b.node, n_ops, b.uniq, b.seg, &dc->v[C_TMP0], s));
+  hipLaunchKernelGGL(k_chunk_counts, grid1(n_ops), dim3(256), 0, s, (const int32_t *)b.uniq,
+                     (const int32_t *)&dc->v[C_TMP0], (const int32_t *)g.deg, b.chunks);
+  // n_touched <= n_ops: scan over the upper bound is wasteful; read the count instead
+  INK_TRYS(hipMemcpyAsync(c->h_cnt, dc, sizeof(Counters), hipMemcpyDeviceToHost, s));
+  INK_TRYS(hipStreamSynchronize(s));
+  int n_touched = c->h_cnt->v[C_TMP0];
+  *n_touched_out = n_touched;
+  INK_TRYS(scan_excl_i32(c->ws, b.chunks, b.chunk_pref, n_touched, &dc->v[C_TMP1], s));
+  hipLaunchKernelGGL(k_classify, dim3(2048), dim3(256), 0, s, (const int32_t *)b.uniq, (const int32_t *)&dc->v[C_TMP0],
+                     (const int32_t *)b.seg, (const int32_t *)b.chunk_pref, (const int32_t *)&dc->v[C_TMP1],
+                     (const int64_t *)g.off, (const int32_t *)g.deg, g.ids, (const int32_t *)b.other,
+                     (const uint8_t *)b.op, b.pos);
+  hipLaunchKernelGGL(k_effect, grid1((int64_t)n_touched * kWave), dim3(256), 0, s, (const int32_t *)b.uniq,
+                     (const int32_t *)&dc->v[C_TMP0], (const int32_t *)b.seg, (const uint8_t *)b.op,
+                     (const int32_t *)b.pos, b.eff, (const int32_t *)g.deg, (const int32_t *)g.cap, b.nd_ins, b.nd_del,
+                     c->slack, (unsigned long long *)&dc->v[C_REGATHER_LO], &dc->v[C_TMP2], &dc->v[C_TMP3]);
+  INK_TRYS(hipMemcpyAsync(c->h_cnt, dc, sizeof(Counters), hipMemcpyDeviceToHost, s));
+  INK_TRYS(hipStreamSynchronize(s));
+  int64_t need = *(int64_t *)&c->h_cnt->v[C_REGATHER_LO];
+  *tot_ins = c->h_cnt->v[C_TMP2];
+  *tot_del = c->h_cnt->v[C_TMP3];
+  if (g.pool_top + need > g.pool_cap) {
+    hipError_t e = grow_pool(c, g, need);
+    if (e == hipErrorOutOfMemory) { c->err = "out of device memory while growing the edge pool"; return INK_E_OOM; }
+    INK_TRYS(e);
+  }
+  // device copy of the pool top lives in the counter block (64-bit slot)
+  unsigned long long *d_top = (unsigned long long *)&dc->v[C_REGATHER_LO];
+  unsigned long long top = (unsigned long long)g.pool_top;
+  INK_TRYS(hipMemcpyAsync(d_top, &top, sizeof(top), hipMemcpyHostToDevice, s));
+  if (n_touched > 0)
+    hipLaunchKernelGGL(k_apply, dim3(n_touched), dim3(256), 0, s, (const int32_t *)b.uniq, (const int32_t *)b.seg,
+                       (const int32_t *)b.other, (const uint8_t *)b.eff, (const int32_t *)b.pos,
+                       (const int32_t *)b.nd_ins, (const int32_t *)b.nd_del, g.off, g.deg, g.cap, g.ids, d_top,
+                       c->slack, b.fill, new_cnt);
+  INK_TRYS(hipGetLastError());
+  g.pool_top += need;      // exact: the apply kernel allocates precisely what k_effect summed
+  return INK_OK;
+}
+
+ink_status graph_apply_batch(ink_ctx *c, int64_t n, int64_t *n_ins_out, int64_t *n_del_out) {
+  hipStream_t s = c->stream;
+  *n_ins_out = *n_del_out = 0;
+  c->n_ins = c->n_del = 0;
+  if (n == 0) return INK_OK;
+  const RawUpdate *raw = c->b_raw.as<RawUpdate>();
+  size_t per = ((size_t)(n + 64) * 4 + 255) & ~(size_t)255;
+  INK_TRYS(c->b_misc.reserve(per * 28));
+  INK_TRYS(c->b_del_s.reserve(per)); INK_TRYS(c->b_del_d.reserve(per));
+  INK_TRYS(c->b_ins_s.reserve(per)); INK_TRYS(c->b_ins_d.reserve(per));
+  Arena ar(c->b_misc);
+  uint32_t *k0 = ar.get<uint32_t>(n), *v0 = ar.get<uint32_t>(n), *k1 = ar.get<uint32_t>(n);
+  uint32_t *srcv = ar.get<uint32_t>(n), *dstv = ar.get<uint32_t>(n);
+  uint8_t *flag = ar.get<uint8_t>(n + 64);
+  int32_t *idx = ar.get<int32_t>(n), *idx2 = ar.get<int32_t>(n);
+  SideBufs b;
+  b.node = ar.get<uint32_t>(n); b.other = ar.get<int32_t>(n); b.op = ar.get<uint8_t>(n + 64);
+  b.pos = ar.get<int32_t>(n); b.eff = ar.get<uint8_t>(n + 64);
+  b.uniq = ar.get<int32_t>(n + 1); b.seg = ar.get<int32_t>(n + 2); b.chunks = ar.get<int32_t>(n + 1);
+  b.chunk_pref = ar.get<int32_t>(n + 1); b.nd_ins = ar.get<int32_t>(n + 1); b.nd_del = ar.get<int32_t>(n + 1);
+  b.fill = ar.get<int32_t>(n + 1);
+  Counters *dc = c->d_cnt;
+
+  // (dst, src, position) order through two stable sorts
+  hipLaunchKernelGGL(k_unpack, grid1(n), dim3(256), 0, s, raw, n, srcv, dstv, v0);
+  INK_TRYS(hipMemcpyAsync(k0, srcv, (size_t)n * 4, hipMemcpyDeviceToDevice, s));
+  INK_TRYS(radix_sort_pairs(c->ws, k0, v0, n, c->id_bits, s));
+  hipLaunchKernelGGL(k_gather_u32, grid1(n), dim3(256), 0, s, (const uint32_t *)dstv, (const uint32_t *)v0, n, k1);
+  INK_TRYS(radix_sort_pairs(c->ws, k1, v0, n, c->id_bits, s));
+  // final op per distinct edge
+  hipLaunchKernelGGL(k_mark_last, grid1(n), dim3(256), 0, s, raw, (const uint32_t *)v0, n, flag);
+  INK_TRYS(compact_flags_u8(c->ws, flag, n, idx, &dc->v[C_TMP0], s));
+  hipLaunchKernelGGL(k_take_ops, grid1(n), dim3(256), 0, s, raw, (const uint32_t *)v0, (const int32_t *)idx,
+                     (const int32_t *)&dc->v[C_TMP0], b.node, b.other, b.op, b.pos);
+  INK_TRYS(hipMemcpyAsync(c->h_cnt, dc, sizeof(Counters), hipMemcpyDeviceToHost, s));
+  INK_TRYS(hipStreamSynchronize(s));
+  int64_t n_ops = c->h_cnt->v[C_TMP0];
+  if (n_ops == 0) return INK_OK;
+
+  int n_touched = 0;
+  int64_t ti = 0, td = 0;
+  ink_status st = apply_side(c, c->gin, b, n_ops, nullptr, &n_touched, &ti, &td);
+  if (st != INK_OK) return st;
+  c->n_ins = ti; c->n_del = td;
+  *n_ins_out = ti; *n_del_out = td;
+  if (ti + td == 0) return INK_OK;
+
+  // Delta E lists, (dst, src) order
+  int32_t *n_ops_d = &dc->v[C_TMP0];
+  int32_t nops32 = (int32_t)n_ops;
+  INK_TRYS(hipMemcpyAsync(&dc->v[C_TMP0], &nops32, sizeof(int32_t), hipMemcpyHostToDevice, s));
+  hipLaunchKernelGGL(k_flag_eq, grid1(n_ops), dim3(256), 0, s, (const uint8_t *)b.eff, (const int32_t *)n_ops_d,
+                     (uint8_t)1, flag);
+  INK_TRYS(compact_flags_u8(c->ws, flag, n_ops, idx, &dc->v[C_TMP2], s));
+  hipLaunchKernelGGL(k_flag_eq, grid1(n_ops), dim3(256), 0, s, (const uint8_t *)b.eff, (const int32_t *)n_ops_d,
+                     (uint8_t)2, flag);
+  INK_TRYS(compact_flags_u8(c->ws, flag, n_ops, idx2, &dc->v[C_TMP3], s));
+  c->del_src = c->b_del_s.as<int32_t>(); c->del_dst = c->b_del_d.as<int32_t>();
+  c->ins_src = c->b_ins_s.as<int32_t>(); c->ins_dst = c->b_ins_d.as<int32_t>();
+  hipLaunchKernelGGL(k_split_ops, grid1(n_ops), dim3(256), 0, s, (const uint32_t *)b.node, (const int32_t *)b.other,
+                     (const uint8_t *)b.eff, (const int32_t *)n_ops_d, (const int32_t *)idx, (const int32_t *)idx2,
+                     c->ins_src, c->ins_dst, c->del_src, c->del_dst, (const int32_t *)&dc->v[C_TMP2],
+                     (const int32_t *)&dc->v[C_TMP3]);
+
+  // out side: the effective ops in (src, dst) order
+  int64_t m = ti + td;
+  hipLaunchKernelGGL(k_out_dst_key, grid1(m), dim3(256), 0, s, (const int32_t *)c->del_dst, (const int32_t *)c->ins_dst,
+                     (int)td, (int)ti, k0, v0);
+  INK_TRYS(radix_sort_pairs(c->ws, k0, v0, m, c->id_bits, s));
+  // key <- source of the permuted entries
+  hipLaunchKernelGGL(k_out_ops, grid1(m), dim3(256), 0, s, (const int32_t *)c->del_src, (const int32_t *)c->del_dst,
+                     (const int32_t *)c->ins_src, (const int32_t *)c->ins_dst, (int)td, (int)ti, srcv, dstv);
+  hipLaunchKernelGGL(k_gather_u32, grid1(m), dim3(256), 0, s, (const uint32_t *)srcv, (const uint32_t *)v0, m, k1);
+  INK_TRYS(radix_sort_pairs(c->ws, k1, v0, m, c->id_bits, s));
+  hipLaunchKernelGGL(k_out_take, grid1(m), dim3(256), 0, s, (const uint32_t *)v0, (const int32_t *)c->del_src,
+                     (const int32_t *)c->del_dst, (const int32_t *)c->ins_src, (const int32_t *)c->ins_dst, (int)td,
+                     (int)ti, b.node, b.other, b.op, b.pos);
+  int64_t oi = 0, od = 0;
+  st = apply_side(c, c->gout, b, m, c->new_out, &n_touched, &oi, &od);
+  if (st != INK_OK) return st;
+  if (oi != ti || od != td) {
+    c->err = "graph store inconsistent: in- and out-adjacency disagree";
+    return INK_E_DEVICE;
+  }
+  // remember the touched sources so that the per-batch marks can be cleared
+  INK_TRYS(c->b_uniq.reserve((size_t)(n_touched + 1) * 4));
+  INK_TRYS(hipMemcpyAsync(c->b_uniq.p, b.uniq, (size_t)n_touched * 4, hipMemcpyDeviceToDevice, s));
+  c->n_touched_src = n_touched;
+  return INK_OK;
+}
+
+hipError_t graph_end_batch(ink_ctx *c) {
+  if (c->n_touched_src > 0)
+    hipLaunchKernelGGL(k_zero_at, grid1(c->n_touched_src), dim3(256), 0, c->stream, (const int32_t *)c->b_uniq.p,
+                       (int)c->n_touched_src, c->new_out);
+  c->n_touched_src = 0;
+  return hipGetLastError();
+}
+
+}  // namespace ink

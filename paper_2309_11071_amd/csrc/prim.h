@@ -1,0 +1,178 @@
+// Device-wide primitives on one HIP stream: exclusive scan, stream compaction and a stable
+// LSD radix sort of (u32 key, u32 value) pairs.  All are multi-kernel (reduce / scan the
+// block sums / apply), never spin on other workgroups, and are deterministic.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ink {
+
+constexpr int kWave = 64;
+constexpr int kScanThreads = 256;
+constexpr int kScanItems = 8;
+constexpr int kScanTile = kScanThreads * kScanItems;   // items per workgroup
+
+struct DevBuf {            // grow-only device buffer (contents are NOT kept across growth)
+  void *p = nullptr;
+  size_t cap = 0;
+  hipError_t reserve(size_t bytes) {
+    if (bytes <= cap) return hipSuccess;
+    if (p) { hipError_t e = hipFree(p); p = nullptr; cap = 0; if (e != hipSuccess) return e; }
+    size_t want = bytes + bytes / 4 + 256;
+    hipError_t e = hipMalloc(&p, want);
+    if (e != hipSuccess) { p = nullptr; return e; }
+    cap = want;
+    return hipSuccess;
+  }
+  void release() { if (p) (void)hipFree(p); p = nullptr; cap = 0; }
+  template <class T> T *as() const { return reinterpret_cast<T *>(p); }
+};
+
+struct PrimWorkspace {     // scratch shared by scan / compaction / sort calls on one stream
+  DevBuf blk;              // block sums
+  DevBuf hist;             // radix histograms
+  DevBuf tmpk, tmpv;       // radix ping-pong
+};
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
+
+// inclusive scan across the 64 lanes of a wave
+__device__ __forceinline__ int wave_incl_scan(int x) {
+  int l = lane_id();
+#pragma unroll
+  for (int o = 1; o < kWave; o <<= 1) {
+    int y = __shfl_up(x, o, kWave);
+    if (l >= o) x += y;
+  }
+  return x;
+}
+
+// exclusive scan over a workgroup of kScanThreads threads; *total gets the block sum.
+// smem must hold kScanThreads / kWave + 1 ints.  Contains __syncthreads.
+__device__ __forceinline__ int block_excl_scan(int x, int *smem, int *total) {
+  int incl = wave_incl_scan(x);
+  int w = threadIdx.x / kWave, l = lane_id();
+  constexpr int nw = kScanThreads / kWave;
+  __syncthreads();
+  if (l == kWave - 1) smem[w] = incl;
+  __syncthreads();
+  int base = 0, tot = 0;
+#pragma unroll
+  for (int i = 0; i < nw; i++) {
+    int s = smem[i];
+    if (i < w) base += s;
+    tot += s;
+  }
+  *total = tot;
+  return base + incl - x;
+}
+
+#define INK_TRY(x) do { hipError_t e_ = (x); if (e_ != hipSuccess) return e_; } while (0)
+
+inline int nblocks(int64_t n, int per) { return (int)((n + per - 1) / per); }
+
+// ---------------------------------------------------------------- generic tile scan machinery
+// Functor F: __device__ int operator()(int64_t i) const  -> value of item i
+// Functor W: __device__ void operator()(int64_t i, int v, int excl) const -> consume exclusive prefix
+
+template <class F>
+__global__ __launch_bounds__(kScanThreads) void k_tile_reduce(F f, int64_t n, int32_t *blk) {
+  __shared__ int sm[kScanThreads / kWave + 1];
+  int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kScanItems;
+  int s = 0;
+#pragma unroll
+  for (int k = 0; k < kScanItems; k++) {
+    int64_t i = base + k;
+    if (i < n) s += f(i);
+  }
+  int tot;
+  block_excl_scan(s, sm, &tot);
+  if (threadIdx.x == 0) blk[blockIdx.x] = tot;
+}
+
+// single workgroup: exclusive scan of blk[0..nb) in place, total to *total
+template <int DUMMY>
+__global__ __launch_bounds__(kScanThreads) void k_scan_blk(int32_t *blk, int nb, int32_t *total) {
+  __shared__ int sm[kScanThreads / kWave + 1];
+  int carry = 0;
+  for (int b0 = 0; b0 < nb; b0 += kScanThreads) {
+    int i = b0 + threadIdx.x;
+    int x = i < nb ? blk[i] : 0;
+    int tot;
+    int ex = block_excl_scan(x, sm, &tot);
+    if (i < nb) blk[i] = carry + ex;
+    carry += tot;
+    __syncthreads();
+  }
+  if (threadIdx.x == 0 && total) *total = carry;
+}
+
+template <class F, class W>
+__global__ __launch_bounds__(kScanThreads) void k_tile_apply(F f, W w, int64_t n, const int32_t *blk,
+                                                              int32_t *total_single) {
+  __shared__ int sm[kScanThreads / kWave + 1];
+  int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kScanItems;
+  int v[kScanItems];
+  int s = 0;
+#pragma unroll
+  for (int k = 0; k < kScanItems; k++) {
+    int64_t i = base + k;
+    v[k] = i < n ? f(i) : 0;
+    s += v[k];
+  }
+  int tot;
+  int ex = block_excl_scan(s, sm, &tot);
+  ex += blk ? blk[blockIdx.x] : 0;
+#pragma unroll
+  for (int k = 0; k < kScanItems; k++) {
+    int64_t i = base + k;
+    if (i < n) w(i, v[k], ex);
+    ex += v[k];
+  }
+  if (total_single && threadIdx.x == 0) *total_single = tot;   // only used when gridDim.x == 1
+}
+
+template <class F, class W>
+inline hipError_t tile_scan(PrimWorkspace &ws, F f, W w, int64_t n, int32_t *total, hipStream_t s) {
+  if (n <= 0) {
+    if (total) INK_TRY(hipMemsetAsync(total, 0, sizeof(int32_t), s));
+    return hipSuccess;
+  }
+  int nb = nblocks(n, kScanTile);
+  if (nb == 1) {
+    hipLaunchKernelGGL((k_tile_apply<F, W>), dim3(1), dim3(kScanThreads), 0, s, f, w, n,
+                       (const int32_t *)nullptr, total);
+    return hipGetLastError();
+  }
+  INK_TRY(ws.blk.reserve((size_t)nb * sizeof(int32_t)));
+  int32_t *blk = ws.blk.as<int32_t>();
+  hipLaunchKernelGGL((k_tile_reduce<F>), dim3(nb), dim3(kScanThreads), 0, s, f, n, blk);
+  hipLaunchKernelGGL((k_scan_blk<0>), dim3(1), dim3(kScanThreads), 0, s, blk, nb, total);
+  hipLaunchKernelGGL((k_tile_apply<F, W>), dim3(nb), dim3(kScanThreads), 0, s, f, w, n,
+                     (const int32_t *)blk, (int32_t *)nullptr);
+  return hipGetLastError();
+}
+
+// out[i] = sum_{j<i} in[j] for i < n, *total = sum of all (device pointers; total may alias nothing)
+hipError_t scan_excl_i32(PrimWorkspace &ws, const int32_t *in, int32_t *out, int64_t n,
+                         int32_t *total, hipStream_t s);
+
+// indices i < n with flags[i] != 0, ascending, to out_idx; *count = how many
+hipError_t compact_flags_u8(PrimWorkspace &ws, const uint8_t *flags, int64_t n, int32_t *out_idx,
+                            int32_t *count, hipStream_t s);
+
+// set bits of a bitmap of n_bits bits (uint64 words, bit b of word w = item 64 w + b) as an
+// ascending list; words are cleared to zero afterwards if clear != 0
+hipError_t bitmap_to_list(PrimWorkspace &ws, uint64_t *words, int64_t n_bits, int32_t *out_idx,
+                          int32_t *count, int clear, hipStream_t s);
+
+// segment heads of a sorted key array: uniq[j] = j-th distinct key, seg[j] = first index of its
+// run, seg[*count] = n
+hipError_t segment_heads(PrimWorkspace &ws, const uint32_t *keys, int64_t n, int32_t *uniq,
+                         int32_t *seg, int32_t *count, hipStream_t s);
+
+// stable sort of (key, val) pairs by the low `bits` bits of key, in place (uses ws.tmpk / tmpv)
+hipError_t radix_sort_pairs(PrimWorkspace &ws, uint32_t *keys, uint32_t *vals, int64_t n, int bits,
+                            hipStream_t s);
+
+}  // namespace ink

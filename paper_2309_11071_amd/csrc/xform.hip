@@ -1,0 +1,149 @@
+// Dense combination on compacted rows with fp32 MFMA (v_mfma_f32_32x32x2_f32), fused with the
+// gather of the input rows, bias, activation and the compare-and-emit step (a row is reported
+// as changed only if its new value differs bitwise from the cached one; Sec. 2.5.2).
+//
+// Every output element is one chain of fused multiply-adds over k = 0 .. K-1 in ascending order
+// starting from +0 (the MFMA unit applies its two k-steps in that order), independent of the
+// tile or row slot it is computed in, so a row's result never depends on which other rows share
+// the launch.  Zero-padded k-steps leave the accumulator unchanged.
+#include "ctx.h"
+
+namespace ink {
+
+typedef float f16v __attribute__((ext_vector_type(16)));
+
+constexpr int BM = 64;       // rows per workgroup
+constexpr int KT = 32;       // k-chunk staged in LDS
+
+template <int MODE>
+__device__ __forceinline__ float fetch_x(const XformArgs &x, int64_t row, int k) {
+  if (MODE == 0) {           // SAGE: [alpha | h_prev]
+    if (k < x.d_in) return x.A[row * x.lda + k];
+    if (k < 2 * x.d_in) return x.Hp[row * x.ldh + (k - x.d_in)];
+    return 0.f;
+  } else if (MODE == 1) {    // GIN: (1 + eps) h_prev + alpha
+    if (k < x.d_in) return __fadd_rn(__fmul_rn(1.0f + x.eps, x.Hp[row * x.ldh + k]), x.A[row * x.lda + k]);
+    return 0.f;
+  } else {                   // dense rows
+    if (k < x.d_in) return x.Hp[row * x.ldh + k];
+    return 0.f;
+  }
+}
+
+template <int MODE, int TPW>
+__global__ __launch_bounds__(256) void k_xform(XformArgs x) {
+  extern __shared__ float smem[];
+  float *Xs = smem;                           // [BM][KT + 1]
+  float *Ws = smem + BM * (KT + 1);           // [KT][Np]
+  __shared__ int64_t srow[BM];     // input row (gather) of each tile row, -1 past the end
+  __shared__ int64_t sout[BM];     // table row written by the epilogue
+  __shared__ int schg[BM];
+  const int t = threadIdx.x, l = t & 63, w = t >> 6;
+  const int rt = w & 1;                       // row tile of this wave
+  const int ct0 = w >> 1;                     // first column tile; then += 2
+  const int NT = x.Np / 32;
+  const int64_t r0 = (int64_t)blockIdx.x * BM;
+  if (t < BM) {
+    int64_t j = r0 + t;
+    int64_t row = -1;
+    if (j < x.n_rows) row = (MODE == 2) ? j : (x.rows ? (int64_t)x.rows[j] : j);
+    srow[t] = row;
+    sout[t] = (row >= 0 && MODE == 2 && x.to_table && x.out_rows) ? (int64_t)x.out_rows[j] : row;
+    schg[t] = 0;
+  }
+  f16v acc[TPW];
+#pragma unroll
+  for (int i = 0; i < TPW; i++)
+#pragma unroll
+    for (int r = 0; r < 16; r++) acc[i][r] = 0.f;
+  __syncthreads();
+  for (int k0 = 0; k0 < x.Kp; k0 += KT) {
+    {   // stage X: thread -> row t / 4, 8 consecutive k
+      int r = t >> 2, ks = (t & 3) * 8;
+      int64_t row = srow[r];
+#pragma unroll
+      for (int kk = 0; kk < 8; kk++)
+        Xs[r * (KT + 1) + ks + kk] = row >= 0 ? fetch_x<MODE>(x, row, k0 + ks + kk) : 0.f;
+    }
+    {   // stage W rows k0 .. k0 + KT (padded matrix: always in bounds)
+      const float4 *src = reinterpret_cast<const float4 *>(x.W + (int64_t)k0 * x.Np);
+      float4 *dst = reinterpret_cast<float4 *>(Ws);
+      int n4 = KT * x.Np / 4;
+      for (int i = t; i < n4; i += 256) dst[i] = src[i];
+    }
+    __syncthreads();
+#pragma unroll 4
+    for (int kk = 0; kk < KT; kk += 2) {
+      float a = Xs[(rt * 32 + (l & 31)) * (KT + 1) + kk + (l >> 5)];
+#pragma unroll
+      for (int i = 0; i < TPW; i++) {
+        int ct = ct0 + 2 * i;
+        if (ct < NT) {
+          float b = Ws[(kk + (l >> 5)) * x.Np + ct * 32 + (l & 31)];
+          acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc[i], 0, 0, 0);
+        }
+      }
+    }
+    __syncthreads();
+  }
+  // epilogue: lane holds rows 8*(r/4) + 4*(l/32) + r%4 of its row tile, column l % 32 of each tile
+#pragma unroll
+  for (int i = 0; i < TPW; i++) {
+    int ct = ct0 + 2 * i;
+    if (ct >= NT) continue;
+    int col = ct * 32 + (l & 31);
+    if (col >= x.n_out) continue;
+    float bias = x.bias ? x.bias[col] : 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; r++) {
+      int rl = rt * 32 + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3);
+      int64_t row = srow[rl];
+      if (row < 0) continue;
+      float v = acc[i][r];
+      if (x.bias) v = __fadd_rn(v, bias);
+      if (x.relu) v = v > 0.f ? v : 0.f;
+      int64_t j = r0 + rl;
+      if (x.to_table) {
+        float *p = x.out + sout[rl] * x.ld_out + col;
+        float old = *p;
+        if (x.old_rows) x.old_rows[j * x.ld_old + col] = old;
+        if (__float_as_uint(old) != __float_as_uint(v)) { *p = v; schg[rl] = 1; }
+      } else {
+        x.out[j * x.ld_out + col] = v;
+      }
+    }
+  }
+  if (x.to_table && x.row_changed) {
+    __syncthreads();
+    if (t < BM && srow[t] >= 0) x.row_changed[r0 + t] = (uint8_t)schg[t];
+  }
+}
+
+template <int MODE>
+static hipError_t launch(ink_ctx *c, const XformArgs &x) {
+  int NT = x.Np / 32;
+  int tpw = (NT + 1) / 2;
+  size_t sh = (size_t)(BM * (KT + 1) + KT * x.Np) * sizeof(float);
+  dim3 grid((unsigned)((x.n_rows + BM - 1) / BM));
+  switch (tpw) {
+    case 1: hipLaunchKernelGGL((k_xform<MODE, 1>), grid, dim3(256), sh, c->stream, x); break;
+    case 2: hipLaunchKernelGGL((k_xform<MODE, 2>), grid, dim3(256), sh, c->stream, x); break;
+    case 3: hipLaunchKernelGGL((k_xform<MODE, 3>), grid, dim3(256), sh, c->stream, x); break;
+    case 4: hipLaunchKernelGGL((k_xform<MODE, 4>), grid, dim3(256), sh, c->stream, x); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+hipError_t xform_run(ink_ctx *c, const XformArgs &x) {
+  if (x.n_rows <= 0) return hipSuccess;
+  if (x.Np % 32 || x.Kp % KT || x.Np > 256) return hipErrorInvalidValue;
+  switch (x.mode) {
+    case 0: return launch<0>(c, x);
+    case 1: return launch<1>(c, x);
+    case 2: return launch<2>(c, x);
+  }
+  return hipErrorInvalidValue;
+}
+
+}  // namespace ink

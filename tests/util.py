@@ -1,0 +1,69 @@
+"""Helpers shared by the GPU parity tests (oracle on one side, the C-ABI library on the other)."""
+import numpy as np
+
+import oracle
+import synth
+
+
+def row_rel_err(got, ref):
+    """Per row: max_i |got - ref| / max(max_i |ref|, tiny); returns the maximum over rows."""
+    got = got.astype(np.float64)
+    ref = ref.astype(np.float64)
+    if got.size == 0:
+        return 0.0
+    num = np.abs(got - ref).max(axis=1)
+    den = np.maximum(np.abs(ref).max(axis=1), 1e-30)
+    return float((num / den).max())
+
+
+class Harness:
+    """Keeps the oracle's view (edge-key set, full inference) next to an Ink context."""
+
+    def __init__(self, cfg, model=None, precision="f32", slack=0.25, profile=False):
+        from paper_2309_11071_amd import Ink
+        self.cfg = cfg
+        self.src, self.dst = synth.make_graph(cfg)
+        self.n = cfg.n_nodes
+        self.X = synth.make_features(cfg)
+        self.model = model if model is not None else synth.make_model(cfg)
+        self.precision = precision
+        self.keys = np.unique(synth.edge_keys(self.src, self.dst))
+        rp, col = oracle.csr_from_keys(self.n, self.keys)
+        self.ink = Ink(rp, col, self.X, self.model, slack_factor=slack, profile=profile)
+        self.ink.full_infer()
+        self.ref = oracle.full_infer(rp, col, self.X, self.model, precision)
+        self.sampler = synth.BatchSampler(cfg, self.src, self.dst)
+
+    def check_state(self, exact=True, tol=1e-5):
+        k = len(self.model["layers"])
+        select = self.model["agg"] in ("max", "min")
+        for l in range(1, k + 1):
+            h = self.ink.get_layer(l, 0)
+            if exact:
+                assert np.array_equal(h.view(np.uint32), self.ref["h"][l].view(np.uint32)), "h_%d differs" % l
+            else:
+                assert row_rel_err(h, self.ref["h"][l]) <= tol, "h_%d beyond tolerance" % l
+            if select:
+                a = self.ink.get_layer(l, 1)
+                g = self.ink.get_layer(l, 2)
+                if exact:
+                    assert np.array_equal(a.view(np.uint32), self.ref["alpha"][l].view(np.uint32)), "alpha_%d" % l
+                    assert np.array_equal(g, self.ref["arg"][l]), "argmax_%d differs" % l
+
+    def check_graph(self):
+        rp, col = self.ink.get_graph()
+        rp2, col2 = oracle.csr_from_keys(self.n, self.keys)
+        assert np.array_equal(rp, rp2) and np.array_equal(col, col2), "graph store differs from the oracle's edge set"
+
+    def step(self, op, bs, bd, exact=True, tol=1e-5):
+        from paper_2309_11071_amd.binding import make_updates
+        res = self.ink.apply_updates(make_updates(op, bs, bd))
+        keys2, n_ins, n_del, n_noop = oracle.apply_batch(self.keys, op, bs, bd)
+        assert (res["n_applied_ins"], res["n_applied_del"], res["n_noop"]) == (n_ins, n_del, n_noop)
+        post = oracle.full_infer(*oracle.csr_from_keys(self.n, keys2), self.X, self.model, self.precision)
+        want = oracle.changed_nodes(self.ref, post)[-1]
+        if exact:
+            assert np.array_equal(res["changed_ids"], want), "changed-node set differs"
+            assert np.array_equal(res["embeddings"].view(np.uint32), post["h"][-1][want].view(np.uint32))
+        self.keys, self.ref = keys2, post
+        return res, want
