@@ -99,6 +99,13 @@ typedef struct {
   float slack_factor; /* extra capacity per edge block, as a fraction of its degree (default 0.25) */
   int32_t max_batch;  /* hint: largest update batch expected (sizes buffers up front); 0 = default */
   int32_t profile;    /* non-zero: time each kernel class with HIP events (see ink_stats) */
+  float dense_threshold; /* a layer whose event count exceeds this fraction of the edge count
+                            re-aggregates every node instead of grouping events (the dense
+                            fallback Sec. 5.1 argues for when updates are not sparse);
+                            0 = default 0.75, negative = never */
+  int64_t pool_reserve;  /* free id slots kept behind the edge blocks of each direction for blocks
+                            that outgrow their slack; when they run out the pool is re-allocated
+                            at twice the size.  0 = default max(25 % of the pool, 2^20) */
 } ink_options;
 
 /* One streaming update (Sec. 2.1: Delta E holds inserted and removed edges). */

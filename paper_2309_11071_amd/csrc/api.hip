@@ -261,6 +261,8 @@ extern "C" ink_status ink_create(const ink_csr *g, const float *features, int32_
   c->mem = dev ? INK_MEM_DEVICE : INK_MEM_HOST;
   c->slack = (opts && opts->slack_factor > 0.f) ? opts->slack_factor : 0.25f;
   c->profile = opts ? opts->profile : 0;
+  c->pool_reserve = opts ? opts->pool_reserve : 0;
+  if (opts && opts->dense_threshold != 0.f) c->dense_frac = opts->dense_threshold < 0.f ? 1e30 : opts->dense_threshold;
   memset(&c->stats, 0, sizeof(c->stats));
 #define CREATE_TRY(x)                                                                              \
   do {                                                                                             \
@@ -442,7 +444,7 @@ extern "C" ink_status ink_apply_updates(ink_ctx *c, const ink_edge_update *upd, 
     int64_t nE = n_seed + n_chg;
     S.n_events = nE;
     uint64_t *bm = c->bm_a;
-    bool dense = nE > 0 && (double)nE > c->dense_frac * (double)std::max<int64_t>(c->n_edges_now, 1) && nE > 4096;
+    bool dense = nE > 0 && (double)nE > c->dense_frac * (double)std::max<int64_t>(c->n_edges_now, 1);
     S.dense = dense;
     if (dense) {
       // so many events that re-aggregating every node costs less than grouping them

@@ -52,6 +52,7 @@ enum { C_NF = 0, C_NEV, C_NT, C_NBIG, C_NC, C_NEXT, C_EXPOSED, C_ACHG, C_TMP0, C
 struct ink_ctx {
   int n = 0;
   int64_t n_edges = 0, n_edges_now = 0;
+  int64_t pool_reserve = 0;
   double dense_frac = 0.75;          // events / edges above which a layer re-aggregates every node
   int id_bits = 1;
   int kind = 0, agg = 0, n_layers = 0, mem = 0, profile = 0;

@@ -23,8 +23,9 @@ static int32_t block_cap(int64_t deg, float slack) {
 }
 
 static hipError_t side_alloc(GraphSide &g, int n, const std::vector<int64_t> &off, const std::vector<int32_t> &deg,
-                             const std::vector<int32_t> &cap, const std::vector<int32_t> &ids, int64_t top) {
-  int64_t reserve = std::max<int64_t>(top / 4, 1 << 20);
+                             const std::vector<int32_t> &cap, const std::vector<int32_t> &ids, int64_t top,
+                             int64_t reserve_opt) {
+  int64_t reserve = reserve_opt > 0 ? reserve_opt : std::max<int64_t>(top / 4, 1 << 20);
   g.pool_cap = top + reserve;
   g.pool_top = top;
   INK_TRY(hipMalloc(&g.off, sizeof(int64_t) * (size_t)n));
@@ -53,7 +54,7 @@ hipError_t graph_build(ink_ctx *c, const int64_t *rowptr, const int32_t *col) {
   {
     std::vector<int32_t> ids((size_t)top, -1);
     for (int v = 0; v < n; v++) std::copy(col + rowptr[v], col + rowptr[v + 1], ids.begin() + off[v]);
-    INK_TRY(side_alloc(c->gin, n, off, deg, cap, ids, top));
+    INK_TRY(side_alloc(c->gin, n, off, deg, cap, ids, top, c->pool_reserve));
   }
   // out side: transpose
   std::vector<int32_t> odeg(n, 0);
@@ -68,7 +69,7 @@ hipError_t graph_build(ink_ctx *c, const int64_t *rowptr, const int32_t *col) {
     std::vector<int64_t> cur(off);
     for (int v = 0; v < n; v++)
       for (int64_t e = rowptr[v]; e < rowptr[v + 1]; e++) ids[cur[col[e]]++] = v;
-    INK_TRY(side_alloc(c->gout, n, off, deg, cap, ids, top));
+    INK_TRY(side_alloc(c->gout, n, off, deg, cap, ids, top, c->pool_reserve));
   }
   return hipSuccess;
 }

@@ -16,49 +16,59 @@ def keys_to_edges(keys):
     return (keys & 0xFFFFFFFF).astype(np.int32), (keys >> 32).astype(np.int32)
 
 
-def _draw(rng, n, scale, a, b, c):
-    """Draw n (src, dst) pairs in [0, 2**scale)^2, one quadrant choice per bit level."""
-    src = np.zeros(n, dtype=np.int64)
-    dst = np.zeros(n, dtype=np.int64)
-    ab, abc = a + b, a + b + c
+def _draw(seed_seq, n, scale, a, b, c, n_nodes):
+    """Draw n (src, dst) pairs in [0, 2**scale)^2, one quadrant choice per bit level; returns the
+    int64 keys (dst << 32 | src) of the pairs that are in range and not self loops."""
+    rng = np.random.Generator(np.random.PCG64(seed_seq))
+    src = np.zeros(n, dtype=np.int32)
+    dst = np.zeros(n, dtype=np.int32)
+    # 16-bit thresholds: quadrant probabilities are honoured to within 2**-16
+    t_a, t_ab, t_abc = (int(round(x * 65536)) for x in (a, a + b, a + b + c))
     for _ in range(scale):
-        u = rng.random(n, dtype=np.float32)
-        sbit = u >= ab                      # quadrants c, d: source bit set
-        dbit = ((u >= a) & (u < ab)) | (u >= abc)   # quadrants b, d: destination bit set
-        src = (src << 1) | sbit
-        dst = (dst << 1) | dbit
-    return src, dst
+        u = rng.integers(0, 65536, size=n, dtype=np.uint16)
+        sbit = u >= t_ab                              # quadrants c, d: source bit set
+        dbit = ((u >= t_a) & (u < t_ab)) | (u >= t_abc)   # quadrants b, d: destination bit set
+        src <<= 1
+        src |= sbit
+        dst <<= 1
+        dst |= dbit
+    ok = (src < n_nodes) & (dst < n_nodes) & (src != dst)
+    return (dst[ok].astype(np.int64) << 32) | src[ok].astype(np.int64)
 
 
 def rmat_edges(n_nodes, n_edges, a=0.57, b=0.19, c=0.19, seed=0, symmetrise=False,
-               permute=True, chunk=1 << 24):
+               permute=True, chunk=1 << 22, workers=8):
     """Unique directed edges without self loops, as (src, dst) int32 arrays sorted by (dst, src).
 
-    Samples with an endpoint >= n_nodes are rejected; drawing continues until `n_edges`
-    distinct pairs exist (first occurrences in draw order are kept).  With `symmetrise`
-    the reverse of every edge is added afterwards and duplicates dropped, so the count is
-    then about 2x n_edges.  A seeded random relabelling spreads the hubs over the id range.
+    Samples with an endpoint >= n_nodes are rejected; drawing continues in rounds until at least
+    `n_edges` distinct pairs exist, then a seeded random subset of exactly `n_edges` is kept.
+    With `symmetrise` the reverse of every edge is added afterwards and duplicates dropped, so the
+    count is then about 2x n_edges.  A seeded random relabelling spreads the hubs over the id
+    range.  Chunks of one round are drawn by worker threads, each from its own child stream of
+    the seed, so the result does not depend on the number of workers.
     """
-    rng = np.random.Generator(np.random.PCG64(seed))
+    from concurrent.futures import ThreadPoolExecutor
+    root = np.random.SeedSequence(seed)
+    rng = np.random.Generator(np.random.PCG64(root.spawn(1)[0]))
     scale = max(1, int(np.ceil(np.log2(max(n_nodes, 2)))))
-    have = np.empty(0, dtype=np.int64)      # unique keys, in first-occurrence order
-    guard = 0
-    while have.size < n_edges:
-        need = n_edges - have.size
-        n_draw = int(min(max(need * 1.3 + 1024, 4096), 4 * chunk))
-        parts = []
-        for s0 in range(0, n_draw, chunk):
-            s, d = _draw(rng, min(chunk, n_draw - s0), scale, a, b, c)
-            ok = (s < n_nodes) & (d < n_nodes) & (s != d)
-            parts.append((d[ok] << 32) | s[ok])
-        cand = np.concatenate([have] + parts)
-        _, first = np.unique(cand, return_index=True)
-        first.sort()
-        have = cand[first]
-        guard += 1
-        if guard > 10000:
-            raise RuntimeError("R-MAT: cannot reach the requested unique edge count")
-    have = have[:n_edges]
+    have = np.empty(0, dtype=np.int64)
+    rounds = 0
+    with ThreadPoolExecutor(max_workers=workers) as ex:
+        while have.size < n_edges:
+            need = n_edges - have.size
+            n_draw = int(max(need * 1.25 + 1024, 4096))
+            sizes = [min(chunk, n_draw - s0) for s0 in range(0, n_draw, chunk)]
+            seeds = root.spawn(len(sizes))
+            parts = list(ex.map(lambda t: _draw(t[0], t[1], scale, a, b, c, n_nodes), zip(seeds, sizes)))
+            have = np.unique(np.concatenate([have] + parts))
+            rounds += 1
+            if rounds > 1000:
+                raise RuntimeError("R-MAT: cannot reach the requested unique edge count")
+    if have.size > n_edges:
+        drop = rng.permutation(have.size)[:have.size - n_edges]
+        keep = np.ones(have.size, dtype=bool)
+        keep[drop] = False
+        have = have[keep]
     src = (have & 0xFFFFFFFF)
     dst = (have >> 32)
     if permute:
@@ -66,7 +76,10 @@ def rmat_edges(n_nodes, n_edges, a=0.57, b=0.19, c=0.19, seed=0, symmetrise=Fals
         src, dst = perm[src], perm[dst]
     if symmetrise:
         src, dst = np.concatenate([src, dst]), np.concatenate([dst, src])
-    keys = np.unique((dst << 32) | src)
+    keys = (dst << 32) | src
+    keys.sort()
+    if symmetrise:
+        keys = np.unique(keys)
     return (keys & 0xFFFFFFFF).astype(np.int32), (keys >> 32).astype(np.int32)
 
 

@@ -1,0 +1,223 @@
+"""Edge cases of the incremental max/min path on the GPU, each checked against the oracle."""
+import numpy as np
+import pytest
+
+import oracle
+import synth
+from util import Harness
+
+pytestmark = pytest.mark.gpu
+
+INS, DEL = 0, 1
+
+
+def arr(x, dt=np.int32):
+    return np.asarray(x, dtype=dt)
+
+
+def tiny_model(kind, agg, dims, seed=0, hidden=8):
+    cfg = synth.WorkloadConfig(7, "t", kind, agg, 1, 1, False, tuple(dims), hidden, 2, False)
+    rng = np.random.default_rng(seed)
+    model = synth.make_model(cfg, bias_scale=0.3)
+    for L in model["layers"]:
+        for k in list(L):
+            if isinstance(L[k], np.ndarray):
+                L[k] = (rng.standard_normal(L[k].shape) * 0.4).astype(np.float32)
+    return model
+
+
+def star(n_leaves, d, seed=0, extra=4):
+    """Leaves 1..n_leaves point to 0; `extra` isolated spare nodes follow."""
+    n = 1 + n_leaves + extra
+    src = np.arange(1, n_leaves + 1, dtype=np.int32)
+    dst = np.zeros(n_leaves, np.int32)
+    X = np.random.default_rng(seed).standard_normal((n, d)).astype(np.float32)
+    return (n, src, dst), X
+
+
+def run(h, ops):
+    op = arr([o for o, _, _ in ops], np.uint8)
+    return h.step(op, arr([s for _, s, _ in ops]), arr([d for _, _, d in ops]))
+
+
+def test_reset_conditions_on_a_star():
+    """No reset, covered reset, exposed reset and the equal-value corner cases (Sec. 2.5.1)."""
+    g, X = star(6, 4, extra=6)
+    # dimension 0: leaf 3 holds the max; dimension 1: leaves 2 and 5 tie (lowest id 2 holds it)
+    X[1:7, 0] = [1, 2, 9, 3, 4, 5]
+    X[1:7, 1] = [0, 7, 1, 2, 7, 3]
+    X[7:, 0] = [10, 9, 8.5, -5, 0, 0]      # spare nodes 7.. used as inserted sources
+    X[7:, 1] = [0, 7, 0, -5, 0, 0]
+    model = tiny_model("sage", "max", (4, 4, 3))
+    h = Harness(graph=g, X=X, model=model)
+    run(h, [(DEL, 1, 0)])                         # deletion without effect: no reset
+    h.check_state()
+    run(h, [(DEL, 3, 0), (INS, 7, 0)])            # holder deleted, inserted 10 > 9: covered
+    h.check_state()
+    run(h, [(DEL, 7, 0), (INS, 9, 0)])            # holder deleted, inserted 8.5 < 10: exposed
+    h.check_state()
+    run(h, [(INS, 8, 0)])                         # dim 1: 8 ties with value 7 but has a higher id
+    h.check_state()
+    run(h, [(DEL, 2, 0)])                         # tie holder leaves: next lowest id takes over
+    h.check_state()
+    run(h, [(DEL, 5, 0), (INS, 2, 0)])            # holder deleted, equal value comes back: not strictly covered
+    h.check_state()
+    run(h, [(INS, 10, 0)])                        # insertion that changes nothing: resilient target
+    h.check_state()
+    h.check_graph()
+    h.ink.close()
+
+
+def test_empty_and_noop_batches():
+    g, X = star(5, 4)
+    h = Harness(graph=g, X=X, model=tiny_model("sage", "max", (4, 4, 4)))
+    res, want = run(h, [])
+    assert res["n_changed"] == 0
+    res, want = run(h, [(INS, 1, 0), (DEL, 1, 2), (INS, 3, 3), (INS, 6, 0), (DEL, 6, 0), (DEL, 6, 0)])
+    assert res["n_changed"] == 0 and res["n_noop"] == 6 and want.size == 0
+    res, _ = run(h, [(INS, 6, 0), (INS, 6, 0), (DEL, 2, 0), (INS, 2, 0), (DEL, 2, 0)])
+    assert (res["n_applied_ins"], res["n_applied_del"], res["n_noop"]) == (1, 1, 3)
+    h.check_state()
+    h.check_graph()
+    h.ink.close()
+
+
+def test_first_and_last_edge_of_a_node():
+    n, d = 6, 5
+    X = np.random.default_rng(3).standard_normal((n, d)).astype(np.float32)
+    src, dst = arr([0, 1]), arr([1, 2])
+    h = Harness(graph=(n, src, dst), X=X, model=tiny_model("sage", "max", (d, 4, 3)))
+    run(h, [(INS, 4, 5)])                 # node 5 had no in-neighbour: cached alpha is not a bound
+    h.check_state()
+    run(h, [(DEL, 4, 5), (DEL, 0, 1)])    # back to empty: alpha 0, arg -1
+    h.check_state()
+    assert (h.ink.get_layer(1, 2)[5] == -1).all() and not h.ink.get_layer(1, 1)[5].any()
+    h.check_graph()
+    h.ink.close()
+
+
+@pytest.mark.parametrize("kind,agg,dims", [
+    ("sage", "min", (8, 8, 8)),
+    ("sage", "max", (100, 47, 5)),        # widths that are not multiples of 4 / 32
+    ("sage", "max", (256, 130, 256)),     # full-wave rows
+    ("sage", "max", (16, 16, 16, 16)),    # three layers
+    ("gin", "max", (12, 20, 9)),
+    ("gin", "min", (64, 64, 64)),
+])
+def test_random_sequences(kind, agg, dims):
+    cfg = synth.WorkloadConfig(6, "t", kind, agg, 3000, 20000, False, tuple(dims), 24, 300, True)
+    model = tiny_model(kind, agg, dims, seed=len(dims), hidden=24)
+    rng = np.random.default_rng(5)
+    src, dst = synth.make_graph(cfg)
+    X = rng.standard_normal((cfg.n_nodes, dims[0])).astype(np.float32)
+    X[rng.random(X.shape) < 0.3] = 0.0                      # exact ties
+    h = Harness(cfg=cfg, graph=(cfg.n_nodes, src, dst), X=X, model=model)
+    h.check_state()
+    for b in range(4):
+        op, bs, bd = h.sampler.next_batch()
+        h.step(op, bs, bd)
+        h.check_state()
+    h.check_graph()
+    h.ink.close()
+
+
+def test_hub_rows_use_the_cooperative_recompute():
+    """A node with > 4096 in-neighbours loses the holders of several dimensions."""
+    n_leaves, d = 6000, 8
+    g, X = star(n_leaves, d, seed=9, extra=8)
+    h = Harness(graph=g, X=X, model=tiny_model("sage", "max", (d, 8, 4)))
+    h.check_state()
+    arg = h.ink.get_layer(1, 2)[0]
+    holders = sorted(set(int(a) for a in arg))
+    res, _ = run(h, [(DEL, u, 0) for u in holders[:3]])
+    assert h.ink.stats()["layers"][0]["n_exposed"] >= 1
+    h.check_state()
+    run(h, [(INS, u, 0) for u in holders[:3]] + [(DEL, holders[-1], 0)])
+    h.check_state()
+    h.check_graph()
+    h.ink.close()
+
+
+def test_blocks_outgrow_their_slack_and_the_pool():
+    n, d = 3000, 4
+    rng = np.random.default_rng(2)
+    X = rng.standard_normal((n, d)).astype(np.float32)
+    src, dst = arr([1, 2]), arr([0, 0])
+    h = Harness(graph=(n, src, dst), X=X, model=tiny_model("sage", "max", (d, 4, 4)), slack=0.01,
+                pool_reserve=1024)     # forces the pool itself to be re-allocated
+    for r in range(4):       # node 0 gains hundreds of in-edges, node 5 hundreds of out-edges, per batch
+        lo, hi = 10 + 600 * r, 10 + 600 * (r + 1)
+        ops = [(INS, u, 0) for u in range(lo, hi)] + [(INS, 5, v) for v in range(lo, hi)]
+        run(h, ops)
+        h.check_graph()
+        h.check_state()
+    run(h, [(DEL, u, 0) for u in range(10, 1500)])
+    h.check_graph()
+    h.check_state()
+    h.ink.close()
+
+
+def test_insert_then_delete_restores_the_cache_exactly():
+    cfg = synth.get_config(1, 4)
+    h = Harness(cfg)
+    before = [h.ink.get_layer(l, w) for l in (1, 2) for w in (0, 1, 2)]
+    op, bs, bd = h.sampler.next_batch()
+    h.step(op, bs, bd)
+    h.step((1 - op)[::-1].copy(), bs[::-1].copy(), bd[::-1].copy())
+    after = [h.ink.get_layer(l, w) for l in (1, 2) for w in (0, 1, 2)]
+    for a, b in zip(before, after):
+        assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+    h.ink.close()
+
+
+def test_dense_fallback_matches():
+    cfg = synth.get_config(1, 8)
+    h = Harness(cfg, dense_threshold=1e-4)
+    for b in range(3):
+        op, bs, bd = h.sampler.next_batch()
+        h.step(op, bs, bd)
+        assert any(L["dense"] for L in h.ink.stats()["layers"])
+        h.check_state()
+    h.ink.close()
+
+
+def test_two_contexts_are_bit_identical():
+    cfg = synth.get_config(1, 4)
+    a, b = Harness(cfg), Harness(cfg)
+    for i in range(3):
+        op, bs, bd = a.sampler.next_batch()
+        ra, _ = a.step(op, bs, bd)
+        rb, _ = b.step(op, bs, bd)
+        assert np.array_equal(ra["changed_ids"], rb["changed_ids"])
+        assert np.array_equal(ra["embeddings"].view(np.uint32), rb["embeddings"].view(np.uint32))
+    a.ink.close(); b.ink.close()
+
+
+def test_error_paths_leave_the_state_untouched():
+    from paper_2309_11071_amd import Ink, InkError
+    from paper_2309_11071_amd.binding import make_updates
+    g, X = star(5, 4)
+    n, src, dst = g
+    rp, col = synth.in_csr_from_edges(n, src, dst)
+    model = tiny_model("sage", "max", (4, 4, 4))
+    ink = Ink(rp, col, X, model)
+    with pytest.raises(InkError) as e:
+        ink.apply_updates(make_updates(arr([0], np.uint8), arr([1]), arr([2])))
+    assert e.value.status == 2                                   # INK_E_STATE
+    ink.full_infer()
+    h1 = ink.get_layer(2, 0)
+    for bad, code in ((make_updates(arr([0, 0], np.uint8), arr([1, n]), arr([2, 0])), 5),
+                      (make_updates(arr([0, 0], np.uint8), arr([1, -1]), arr([2, 0])), 5),
+                      (make_updates(arr([0, 7], np.uint8), arr([1, 2]), arr([2, 0])), 1)):
+        with pytest.raises(InkError) as e:
+            ink.apply_updates(bad)
+        assert e.value.status == code
+    rp2, col2 = ink.get_graph()
+    assert np.array_equal(rp, rp2) and np.array_equal(col, col2)
+    assert np.array_equal(h1, ink.get_layer(2, 0))
+    bad_rp = rp.copy(); bad_rp[-1] += 1
+    with pytest.raises(InkError):
+        Ink(bad_rp, col, X, model)
+    with pytest.raises(InkError):
+        Ink(rp, col[::-1].copy(), X, model)                      # rows not ascending
+    ink.close()

@@ -19,20 +19,29 @@ def row_rel_err(got, ref):
 class Harness:
     """Keeps the oracle's view (edge-key set, full inference) next to an Ink context."""
 
-    def __init__(self, cfg, model=None, precision="f32", slack=0.25, profile=False):
+    def __init__(self, cfg=None, model=None, precision="f32", slack=0.25, profile=False, graph=None, X=None,
+                 dense_threshold=0.0, pool_reserve=0):
+        """Either a workload config, or an explicit graph=(n, src, dst) with features X and a model."""
         from paper_2309_11071_amd import Ink
         self.cfg = cfg
-        self.src, self.dst = synth.make_graph(cfg)
-        self.n = cfg.n_nodes
-        self.X = synth.make_features(cfg)
+        if graph is None:
+            self.src, self.dst = synth.make_graph(cfg)
+            self.n = cfg.n_nodes
+            self.X = synth.make_features(cfg)
+        else:
+            self.n, self.src, self.dst = graph
+            self.src = np.asarray(self.src, np.int32)
+            self.dst = np.asarray(self.dst, np.int32)
+            self.X = np.ascontiguousarray(X, np.float32)
         self.model = model if model is not None else synth.make_model(cfg)
         self.precision = precision
         self.keys = np.unique(synth.edge_keys(self.src, self.dst))
         rp, col = oracle.csr_from_keys(self.n, self.keys)
-        self.ink = Ink(rp, col, self.X, self.model, slack_factor=slack, profile=profile)
+        self.ink = Ink(rp, col, self.X, self.model, slack_factor=slack, profile=profile,
+                       dense_threshold=dense_threshold, pool_reserve=pool_reserve)
         self.ink.full_infer()
         self.ref = oracle.full_infer(rp, col, self.X, self.model, precision)
-        self.sampler = synth.BatchSampler(cfg, self.src, self.dst)
+        self.sampler = synth.BatchSampler(cfg, self.src, self.dst) if cfg is not None else None
 
     def check_state(self, exact=True, tol=1e-5):
         k = len(self.model["layers"])
