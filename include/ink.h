@@ -12,7 +12,8 @@
  * Conventions for every entry point
  *   - Plain C types only.  Pointers are HOST pointers unless `ink_options.mem` says
  *     INK_MEM_DEVICE, in which case caller arrays (graph, features, weights, update
- *     batches) are device pointers on the current HIP device.
+ *     batches) are device pointers on the current HIP device (`ink_options.batch_mem`
+ *     can place only the update batches on the device).
  *   - The caller keeps ownership of everything it passes in; the library copies what it
  *     needs.  Buffers returned by the library are library-owned DEVICE memory, valid until
  *     the next ink_apply_updates / ink_full_infer / ink_destroy on the same context.
@@ -103,6 +104,10 @@ typedef struct {
                             re-aggregates every node instead of grouping events (the dense
                             fallback Sec. 5.1 argues for when updates are not sparse);
                             0 = default 0.75, negative = never */
+  int32_t batch_mem;     /* ink_mem of the `updates` array of ink_apply_updates when it differs from
+                            `mem` (e.g. host-built graph, device-resident update stream): the
+                            effective location is device if either field says INK_MEM_DEVICE */
+  int32_t pad_;
   int64_t pool_reserve;  /* free id slots kept behind the edge blocks of each direction for blocks
                             that outgrow their slack; when they run out the pool is re-allocated
                             at twice the size.  0 = default max(25 % of the pool, 2^20) */
@@ -176,9 +181,10 @@ ink_status ink_apply_updates(ink_ctx *ctx, const ink_edge_update *updates, int64
  * device per dst_mem), densely packed [nrows][width].  layer in 0..n_layers.
  *   which = 0: h_layer, the output of layer `layer` (layer 0 = input features); it is the
  *              message m_{layer+1} of the aggregate-first models (Sec. 2.1).
- *   which = 1: alpha_layer, the aggregated neighbourhood of layer `layer` >= 1 (for SUM-type
- *              aggregators the cached plain sum; for GCN the normalised aggregate of the
- *              transformed features, a = A_hat (h_{layer-1} W_layer)).
+ *   which = 1: alpha_layer, the aggregated neighbourhood of layer `layer` >= 1.  For SUM / MEAN
+ *              it is the cached plain sum of the neighbours' messages; for GCN_SYM the cached
+ *              sum over in-neighbours u of c_u (h_{layer-1} W_layer)_u with c = dhat^(-1/2)
+ *              (the row-local factor c_v and the self term are applied when h is formed).
  *   which = 2: int32 argmax/argmin neighbour ids of layer `layer` >= 1 (MAX / MIN only).
  * width is returned in *width_out if not NULL. */
 ink_status ink_get_layer(ink_ctx *ctx, int32_t layer, int32_t which, int64_t row0, int64_t nrows,

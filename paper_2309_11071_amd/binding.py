@@ -46,7 +46,8 @@ class _Model(C.Structure):
 
 class _Options(C.Structure):
     _fields_ = [("mem", C.c_int32), ("hip_stream", C.c_void_p), ("slack_factor", C.c_float),
-                ("max_batch", C.c_int32), ("profile", C.c_int32), ("dense_threshold", C.c_float), ("pool_reserve", C.c_int64)]
+                ("max_batch", C.c_int32), ("profile", C.c_int32), ("dense_threshold", C.c_float), ("batch_mem", C.c_int32),
+                ("pad_", C.c_int32), ("pool_reserve", C.c_int64)]
 
 
 class _Result(C.Structure):
@@ -120,7 +121,7 @@ class Ink:
     """One context.  `model` is the dict layout of synth.make_model (host numpy weights)."""
 
     def __init__(self, rowptr, col, features, model, slack_factor=0.25, profile=False, stream=None,
-                 dense_threshold=0.0, pool_reserve=0):
+                 dense_threshold=0.0, pool_reserve=0, batch_device=False):
         self._lib = load_library()
         self._h = C.c_void_p()
         rowptr = np.ascontiguousarray(rowptr, np.int64)
@@ -142,7 +143,8 @@ class Ink:
         m = _Model(MODEL_KINDS[model["kind"]], AGGS[model["agg"]], float(model.get("gin_eps", 0.0)),
                    len(model["layers"]), layers)
         g = _Csr(rowptr.size - 1, col.size, rowptr.ctypes.data, col.ctypes.data if col.size else None)
-        o = _Options(0, stream, slack_factor, 0, int(bool(profile)), dense_threshold, pool_reserve)
+        o = _Options(0, stream, slack_factor, 0, int(bool(profile)), dense_threshold,
+                     1 if batch_device else 0, 0, pool_reserve)
         st = self._lib.ink_create(C.byref(g), features.ctypes.data, features.shape[1], C.byref(m), C.byref(o),
                                   C.byref(self._h))
         if st != 0:
@@ -150,6 +152,12 @@ class Ink:
         self.n = rowptr.size - 1
         self.n_layers = len(model["layers"])
         self.out_dim = model["layers"][-1]["out_dim"]
+        self.batch_device = batch_device
+        # width of the aggregated rows of each layer (what the aggregation kernels move)
+        if model["kind"] == "gcn":
+            self.agg_widths = [L["out_dim"] for L in model["layers"]]
+        else:
+            self.agg_widths = [L["in_dim"] for L in model["layers"]]
 
     def _check(self, st):
         if st != 0:
@@ -161,6 +169,7 @@ class Ink:
     def apply_updates(self, updates, fetch=True):
         """updates: structured array (EDGE_UPDATE_DTYPE).  Returns dict; with fetch the changed ids
         and embeddings are copied to host numpy arrays."""
+        assert not self.batch_device, "context expects device batches"
         updates = np.ascontiguousarray(updates, dtype=EDGE_UPDATE_DTYPE)
         r = _Result()
         self._check(self._lib.ink_apply_updates(self._h, updates.ctypes.data if updates.size else None,
@@ -175,6 +184,14 @@ class Ink:
                 _dtoh(emb, r.embeddings)
             out["changed_ids"], out["embeddings"] = ids, emb
         return out
+
+    def apply_updates_device(self, dev_ptr, n):
+        """Batch already in device memory (context created with batch_device=True); results stay on the device."""
+        assert self.batch_device
+        r = _Result()
+        self._check(self._lib.ink_apply_updates(self._h, C.c_void_p(dev_ptr), n, C.byref(r)))
+        return dict(n_changed=r.n_changed, n_applied_ins=r.n_applied_ins, n_applied_del=r.n_applied_del,
+                    n_noop=r.n_noop, changed_ids_ptr=r.changed_ids, embeddings_ptr=r.embeddings)
 
     def get_layer(self, layer, which, row0=0, nrows=None):
         nrows = self.n - row0 if nrows is None else nrows

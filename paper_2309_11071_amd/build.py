@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libink.so")
-SOURCES = ["prim.hip", "graph.hip", "agg.hip", "xform.hip", "api.hip"]
+SOURCES = ["prim.hip", "graph.hip", "agg.hip", "agg_sum.hip", "xform.hip", "api.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

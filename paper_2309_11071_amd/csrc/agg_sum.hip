@@ -1,0 +1,283 @@
+// Aggregation kernels for the accumulative aggregators (sum, mean, degree-normalised sum):
+// the cached state is the plain sum S_v of the (possibly pre-scaled) message rows of the
+// in-neighbours, updated by adding deltas (the extension sketched in Sec. 7): for a removed edge
+// the old message is subtracted, for an inserted edge the new one is added, and for a kept edge
+// whose source changed the difference new - old is added.  The three edge sets are disjoint, so
+// no message is counted twice.  Events of a target are consumed in their stored order and lane
+// groups are combined in a fixed pattern: results are reproducible run to run.
+#include "ctx.h"
+
+namespace ink {
+
+struct S4 { float v[4]; };
+
+__device__ __forceinline__ float4 ldf4(const float *p) { return *reinterpret_cast<const float4 *>(p); }
+
+template <int LPR> __device__ __forceinline__ void sum_groups(S4 &a) {
+#pragma unroll
+  for (int off = LPR; off < kWave; off <<= 1)
+#pragma unroll
+    for (int c = 0; c < 4; c++) a.v[c] = __fadd_rn(a.v[c], __shfl_xor(a.v[c], off, kWave));
+}
+
+// sum of rows M[ids[j]] for j in [j0, j1): group g takes j0 + g, j0 + g + G, ... in order
+template <int LPR>
+__device__ __forceinline__ void sum_range(const int32_t *ids, int64_t j0, int64_t j1, const float *M, int ldm,
+                                          bool lane_on, int q, S4 &acc) {
+  constexpr int G = kWave / LPR;
+  const int l = lane_id();
+  const int g = l / LPR;
+#pragma unroll
+  for (int c = 0; c < 4; c++) acc.v[c] = 0.f;
+  for (int64_t jb = j0; jb < j1; jb += kWave) {
+    int64_t jj = jb + l;
+    int myid = jj < j1 ? ids[jj] : -1;
+    int cnt = (int)((j1 - jb) < kWave ? (j1 - jb) : kWave);
+    constexpr int U = 4;
+    for (int it = 0; it < cnt; it += G * U) {
+      int id[U];
+      float4 row[U];
+#pragma unroll
+      for (int u = 0; u < U; u++) {
+        int k = it + u * G + g;
+        id[u] = __shfl(myid, k < kWave ? k : 0, kWave);
+        if (k >= cnt) id[u] = -1;
+        if (id[u] >= 0 && lane_on) row[u] = ldf4(M + (int64_t)id[u] * ldm + 4 * q);
+      }
+#pragma unroll
+      for (int u = 0; u < U; u++) {
+        if (id[u] >= 0 && lane_on) {
+          acc.v[0] = __fadd_rn(acc.v[0], row[u].x); acc.v[1] = __fadd_rn(acc.v[1], row[u].y);
+          acc.v[2] = __fadd_rn(acc.v[2], row[u].z); acc.v[3] = __fadd_rn(acc.v[3], row[u].w);
+        }
+      }
+    }
+  }
+  sum_groups<LPR>(acc);
+}
+
+__device__ __forceinline__ void mark_bit_s(uint64_t *bm, int v) {
+  atomicOr((unsigned long long *)&bm[v >> 6], 1ull << (v & 63));
+}
+
+// stores the row; returns wave-uniform "some value of the first d dimensions changed"
+template <int LPR>
+__device__ __forceinline__ bool store_sum(float *A, int ld, int d, int v, bool lane_on, int q, const S4 &nv,
+                                          bool compare) {
+  const int l = lane_id();
+  bool writer = lane_on && l < LPR;
+  bool chg = false;
+  if (writer) {
+    float *p = A + (int64_t)v * ld + 4 * q;
+    if (compare) {
+      float4 o = ldf4(p);
+      float ov[4] = {o.x, o.y, o.z, o.w};
+#pragma unroll
+      for (int c = 0; c < 4; c++)
+        if (4 * q + c < d) chg |= __float_as_uint(ov[c]) != __float_as_uint(nv.v[c]);
+    }
+    if (!compare || chg) *reinterpret_cast<float4 *>(p) = make_float4(nv.v[0], nv.v[1], nv.v[2], nv.v[3]);
+  }
+  return __ballot(chg) != 0ull;
+}
+
+template <int LPR>
+__global__ __launch_bounds__(256) void k_sum_full(AggArgs a, const int32_t *targets, int64_t n_targets, uint64_t *chg,
+                                                  int32_t *big_list, int32_t *n_big, int compare) {
+  const int l = lane_id();
+  const int q = l % LPR;
+  const bool lane_on = 4 * q < a.ld;
+  int64_t wid = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kWave;
+  if (wid >= n_targets) return;
+  int v = targets ? targets[wid] : (int)wid;
+  int deg = a.in_deg[v];
+  if (deg > kBigDeg) {
+    if (l == 0) big_list[atomicAdd(n_big, 1)] = v;
+    return;
+  }
+  S4 acc;
+  sum_range<LPR>(a.in_ids + a.in_off[v], 0, deg, a.M, a.ldm, lane_on, q, acc);
+  bool ch = store_sum<LPR>(a.A, a.ld, a.d, v, lane_on, q, acc, compare != 0);
+  if (ch && chg && l == 0) mark_bit_s(chg, v);
+}
+
+template <int LPR>
+__global__ __launch_bounds__(256) void k_sum_big_partial(AggArgs a, const int32_t *big_list, float *part) {
+  __shared__ float sv[4][kWave * 4];
+  const int l = lane_id(), w = threadIdx.x / kWave;
+  const int q = l % LPR;
+  const bool lane_on = 4 * q < a.ld;
+  int v = big_list[blockIdx.y];
+  int64_t deg = a.in_deg[v];
+  int64_t off = a.in_off[v];
+  int64_t p0 = deg * blockIdx.x / kBigParts, p1 = deg * (blockIdx.x + 1) / kBigParts;
+  int64_t len = p1 - p0;
+  int64_t w0 = p0 + len * w / 4, w1 = p0 + len * (w + 1) / 4;
+  S4 acc;
+  sum_range<LPR>(a.in_ids + off, w0, w1, a.M, a.ldm, lane_on, q, acc);
+#pragma unroll
+  for (int c = 0; c < 4; c++) sv[w][l * 4 + c] = acc.v[c];
+  __syncthreads();
+  if (w == 0) {
+#pragma unroll
+    for (int ww = 1; ww < 4; ww++)
+#pragma unroll
+      for (int c = 0; c < 4; c++) acc.v[c] = __fadd_rn(acc.v[c], sv[ww][l * 4 + c]);
+    if (lane_on && l < LPR) {
+      int64_t o = ((int64_t)blockIdx.y * kBigParts + blockIdx.x) * a.ld + 4 * q;
+#pragma unroll
+      for (int c = 0; c < 4; c++) part[o + c] = acc.v[c];
+    }
+  }
+}
+
+template <int LPR>
+__global__ __launch_bounds__(64) void k_sum_big_final(AggArgs a, const int32_t *big_list, const float *part,
+                                                      uint64_t *chg, int compare) {
+  const int l = lane_id();
+  const int q = l % LPR;
+  const bool lane_on = 4 * q < a.ld;
+  int v = big_list[blockIdx.x];
+  S4 acc;
+#pragma unroll
+  for (int c = 0; c < 4; c++) acc.v[c] = 0.f;
+  if (lane_on && l < LPR) {
+    for (int p = 0; p < kBigParts; p++) {
+      int64_t o = ((int64_t)blockIdx.x * kBigParts + p) * a.ld + 4 * q;
+#pragma unroll
+      for (int c = 0; c < 4; c++) acc.v[c] = __fadd_rn(acc.v[c], part[o + c]);
+    }
+  }
+  bool ch = store_sum<LPR>(a.A, a.ld, a.d, v, lane_on, q, acc, compare != 0);
+  if (ch && chg && l == 0) mark_bit_s(chg, v);
+}
+
+__device__ __forceinline__ int find_in(const int32_t *F, int nF, int u) {   // position of u in ascending F, or -1
+  int lo = 0, hi = nF - 1;
+  while (lo <= hi) {
+    int m = (lo + hi) >> 1;
+    int x = F[m];
+    if (x == u) return m;
+    if (x < u) lo = m + 1; else hi = m - 1;
+  }
+  return -1;
+}
+
+template <int LPR>
+__global__ __launch_bounds__(256) void k_sum_events(AggArgs a, const int32_t *targets, const int32_t *seg,
+                                                    int64_t n_targets, const uint32_t *ev, const int32_t *F, int nF,
+                                                    const float *f_old, int ld_old, uint64_t *chg, Counters *cnt) {
+  constexpr int G = kWave / LPR;
+  const int l = lane_id();
+  const int q = l % LPR, g = l / LPR;
+  const bool lane_on = 4 * q < a.ld;
+  int64_t wid = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kWave;
+  if (wid >= n_targets) return;
+  int v = targets[wid];
+  int e0 = seg[wid], e1 = seg[wid + 1];
+  S4 acc;
+#pragma unroll
+  for (int c = 0; c < 4; c++) acc.v[c] = 0.f;
+  for (int eb = e0; eb < e1; eb += kWave) {
+    int ee = eb + l;
+    uint32_t mine = ee < e1 ? ev[ee] : 0xFFFFFFFFu;
+    int cntw = (e1 - eb) < kWave ? (e1 - eb) : kWave;
+    for (int it = 0; it < cntw; it += G) {
+      int k = it + g;
+      uint32_t x = __shfl(mine, k < kWave ? k : 0, kWave);
+      if (k >= cntw || !lane_on) continue;
+      uint32_t kind = x >> kEvKindShift;
+      int id = (int)(x & kEvIdMask);
+      if (kind == EV_DEL) {
+        int pos = nF > 0 ? find_in(F, nF, id) : -1;
+        float4 r = pos >= 0 ? ldf4(f_old + (int64_t)pos * ld_old + 4 * q) : ldf4(a.M + (int64_t)id * a.ldm + 4 * q);
+        acc.v[0] = __fsub_rn(acc.v[0], r.x); acc.v[1] = __fsub_rn(acc.v[1], r.y);
+        acc.v[2] = __fsub_rn(acc.v[2], r.z); acc.v[3] = __fsub_rn(acc.v[3], r.w);
+      } else if (kind == EV_ADD) {
+        float4 r = ldf4(a.M + (int64_t)id * a.ldm + 4 * q);
+        acc.v[0] = __fadd_rn(acc.v[0], r.x); acc.v[1] = __fadd_rn(acc.v[1], r.y);
+        acc.v[2] = __fadd_rn(acc.v[2], r.z); acc.v[3] = __fadd_rn(acc.v[3], r.w);
+      } else {   // EV_CHG: id is the position of the source in F
+        int u = F[id];
+        float4 n4 = ldf4(a.M + (int64_t)u * a.ldm + 4 * q);
+        float4 o4 = ldf4(f_old + (int64_t)id * ld_old + 4 * q);
+        acc.v[0] = __fadd_rn(acc.v[0], __fsub_rn(n4.x, o4.x)); acc.v[1] = __fadd_rn(acc.v[1], __fsub_rn(n4.y, o4.y));
+        acc.v[2] = __fadd_rn(acc.v[2], __fsub_rn(n4.z, o4.z)); acc.v[3] = __fadd_rn(acc.v[3], __fsub_rn(n4.w, o4.w));
+      }
+    }
+  }
+  sum_groups<LPR>(acc);
+  S4 nv;
+#pragma unroll
+  for (int c = 0; c < 4; c++) nv.v[c] = 0.f;
+  if (lane_on) {
+    float4 o = ldf4(a.A + (int64_t)v * a.ld + 4 * q);
+    nv.v[0] = __fadd_rn(o.x, acc.v[0]); nv.v[1] = __fadd_rn(o.y, acc.v[1]);
+    nv.v[2] = __fadd_rn(o.z, acc.v[2]); nv.v[3] = __fadd_rn(o.w, acc.v[3]);
+  }
+  bool ch = store_sum<LPR>(a.A, a.ld, a.d, v, lane_on, q, nv, true);
+  if (ch && l == 0) { mark_bit_s(chg, v); atomicAdd(&cnt->v[C_ACHG], 1); }
+}
+
+static int lanes_per_row(int ld) { return ld <= 64 ? 16 : (ld <= 128 ? 32 : 64); }
+
+static hipError_t read_counters(ink_ctx *c) {
+  INK_TRY(hipMemcpyAsync(c->h_cnt, c->d_cnt, sizeof(Counters), hipMemcpyDeviceToHost, c->stream));
+  return hipStreamSynchronize(c->stream);
+}
+
+template <int LPR>
+static hipError_t sum_full_t(ink_ctx *c, const AggArgs &a, const int32_t *targets, int64_t n_targets, uint64_t *chg) {
+  if (n_targets <= 0) return hipSuccess;
+  int compare = chg != nullptr;
+  INK_TRY(hipMemsetAsync(&c->d_cnt->v[C_NBIG], 0, sizeof(int32_t), c->stream));
+  hipLaunchKernelGGL((k_sum_full<LPR>), dim3((unsigned)((n_targets + 3) / 4)), dim3(256), 0, c->stream, a, targets,
+                     n_targets, chg, c->big_list.as<int32_t>(), &c->d_cnt->v[C_NBIG], compare);
+  INK_TRY(hipGetLastError());
+  INK_TRY(read_counters(c));
+  int n_big = c->h_cnt->v[C_NBIG];
+  if (n_big > 0) {
+    const int chunk = 512;
+    INK_TRY(c->big_part_v.reserve((size_t)chunk * kBigParts * a.ld * sizeof(float)));
+    const int32_t *list = c->big_list.as<int32_t>();
+    for (int b0 = 0; b0 < n_big; b0 += chunk) {
+      int nb = n_big - b0 < chunk ? n_big - b0 : chunk;
+      hipLaunchKernelGGL((k_sum_big_partial<LPR>), dim3(kBigParts, nb), dim3(256), 0, c->stream, a, list + b0,
+                         c->big_part_v.as<float>());
+      hipLaunchKernelGGL((k_sum_big_final<LPR>), dim3(nb), dim3(64), 0, c->stream, a, list + b0,
+                         (const float *)c->big_part_v.as<float>(), chg, compare);
+    }
+    INK_TRY(hipGetLastError());
+  }
+  return hipSuccess;
+}
+
+template <int LPR>
+static hipError_t sum_events_t(ink_ctx *c, const AggArgs &a, const int32_t *targets, const int32_t *seg,
+                               int64_t n_targets, const uint32_t *ev, const int32_t *F, int nF, const float *f_old,
+                               int ld_old, uint64_t *chg) {
+  if (n_targets <= 0) return hipSuccess;
+  hipLaunchKernelGGL((k_sum_events<LPR>), dim3((unsigned)((n_targets + 3) / 4)), dim3(256), 0, c->stream, a, targets,
+                     seg, n_targets, ev, F, nF, f_old, ld_old, chg, c->d_cnt);
+  return hipGetLastError();
+}
+
+hipError_t agg_sum_full(ink_ctx *c, const AggArgs &a, const int32_t *targets, int64_t n_targets, uint64_t *chg) {
+  switch (lanes_per_row(a.ld)) {
+    case 16: return sum_full_t<16>(c, a, targets, n_targets, chg);
+    case 32: return sum_full_t<32>(c, a, targets, n_targets, chg);
+    default: return sum_full_t<64>(c, a, targets, n_targets, chg);
+  }
+}
+
+hipError_t agg_sum_events(ink_ctx *c, const AggArgs &a, const int32_t *targets, const int32_t *seg,
+                          int64_t n_targets, const uint32_t *ev_val, const int32_t *F, int nF, const float *f_old,
+                          int ld_old, uint64_t *chg) {
+  switch (lanes_per_row(a.ld)) {
+    case 16: return sum_events_t<16>(c, a, targets, seg, n_targets, ev_val, F, nF, f_old, ld_old, chg);
+    case 32: return sum_events_t<32>(c, a, targets, seg, n_targets, ev_val, F, nF, f_old, ld_old, chg);
+    default: return sum_events_t<64>(c, a, targets, seg, n_targets, ev_val, F, nF, f_old, ld_old, chg);
+  }
+}
+
+}  // namespace ink

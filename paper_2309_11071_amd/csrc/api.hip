@@ -93,6 +93,61 @@ __global__ void k_unpack_rows(const float *in, int d, int ld, int64_t n, float *
   if (r < n) table[r * ld + k] = in[r * d + k];
 }
 
+__global__ void k_gather_rows_ld(const float *in, int ld, const int32_t *idx, int64_t n, float *out) {
+  // out[i][:] = in[idx[i]][:], both with row stride ld
+  int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t r = t / ld;
+  int k = (int)(t % ld);
+  if (r < n) out[r * ld + k] = in[(int64_t)idx[r] * ld + k];
+}
+
+__device__ __forceinline__ float gcn_coef(int indeg) {      // (indeg + 1)^(-1/2)
+  return __fdiv_rn(1.0f, __fsqrt_rn((float)(indeg + 1)));
+}
+
+__global__ void k_gcn_coef_all(const int32_t *deg, int n, float *cnorm) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) cnorm[i] = gcn_coef(deg[i]);
+}
+
+// scaled = c_v * raw for the nodes in `nodes` (null: all); optionally keeps the old scaled rows
+// and flags rows that changed bitwise (flag must be pre-zeroed)
+__global__ void k_gcn_rescale(const int32_t *nodes, int64_t n, const int32_t *deg, float *cnorm, const float *raw,
+                              float *scaled, int ld, int d, float *old_rows, uint8_t *flag) {
+  int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t i = t / ld;
+  int k = (int)(t % ld);
+  if (i >= n) return;
+  int v = nodes ? nodes[i] : (int)i;
+  float cv = gcn_coef(deg[v]);
+  if (k == 0) cnorm[v] = cv;
+  float o = scaled[(int64_t)v * ld + k];
+  float nv = k < d ? __fmul_rn(cv, raw[(int64_t)v * ld + k]) : 0.f;
+  if (old_rows) old_rows[i * ld + k] = o;
+  if (__float_as_uint(o) != __float_as_uint(nv)) {
+    scaled[(int64_t)v * ld + k] = nv;
+    if (flag) flag[i] = 1;
+  }
+}
+
+// last GCN layer: h = act(c_v (S + own scaled message) + b) for the listed rows, compare-and-emit
+__global__ void k_gcn_final(const int32_t *rows, int64_t n, const float *S, const float *Msc, const float *cnorm,
+                            const float *bias, int relu, float *H, int ld, int d, uint8_t *flag) {
+  int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t i = t / ld;
+  int k = (int)(t % ld);
+  if (i >= n || k >= d) return;
+  int64_t v = rows ? rows[i] : i;
+  float x = __fmul_rn(cnorm[v], __fadd_rn(S[v * ld + k], Msc[v * ld + k]));
+  if (bias) x = __fadd_rn(x, bias[k]);
+  if (relu) x = x > 0.f ? x : 0.f;
+  float o = H[v * ld + k];
+  if (__float_as_uint(o) != __float_as_uint(x)) {
+    H[v * ld + k] = x;
+    if (flag) flag[i] = 1;
+  }
+}
+
 // ------------------------------------------------------------------------------------ helpers
 static ink_status fail(ink_ctx *c, ink_status st, const std::string &msg) {
   if (c) c->err = msg; else g_create_err = msg;
@@ -159,23 +214,31 @@ static hipError_t read_counters(ink_ctx *c) {
   return hipStreamSynchronize(c->stream);
 }
 
-static AggArgs agg_args(ink_ctx *c, int l) {       // layer l in 1..k aggregates m_l = H[l-1]
+static const Table &msg_table(ink_ctx *c, int l) {   // m_l: h_{l-1} (aggregate first) or GCN's scaled h_{l-1} W_l
+  return c->kind == INK_MODEL_GCN ? c->Msc[l] : c->H[l - 1];
+}
+
+static AggArgs agg_args(ink_ctx *c, int l) {       // layer l in 1..k
   AggArgs a;
   a.n = c->n;
   a.in_off = c->gin.off; a.in_deg = c->gin.deg; a.in_ids = c->gin.ids;
-  a.M = c->H[l - 1].f(); a.ldm = c->H[l - 1].ld;
-  a.A = c->A[l].f(); a.ARG = c->ARG[l].i(); a.ld = c->A[l].ld; a.d = c->A[l].d;
+  const Table &M = msg_table(c, l);
+  a.M = M.f(); a.ldm = M.ld;
+  a.A = c->A[l].f(); a.ARG = c->is_select ? c->ARG[l].i() : nullptr; a.ld = c->A[l].ld; a.d = c->A[l].d;
   a.is_min = c->is_min;
   return a;
 }
 
 // dense combination of layer l for the rows in `rows` (null: all nodes).  With flags != null the
 // layer's table is updated with compare-and-emit.
-static hipError_t run_transform(ink_ctx *c, int l, const int32_t *rows, int64_t n_rows, uint8_t *flags) {
+static hipError_t run_transform(ink_ctx *c, int l, const int32_t *rows, int64_t n_rows, uint8_t *flags,
+                                float *old_rows = nullptr) {
   const DevLayer &L = c->layers[l - 1];
   XformArgs x;
   memset(&x, 0, sizeof(x));
   x.rows = rows; x.n_rows = n_rows;
+  x.old_rows = old_rows; x.ld_old = c->H[l].ld;
+  if (c->agg == INK_AGG_MEAN) x.mean_deg = c->gin.deg;
   x.A = c->A[l].f(); x.lda = c->A[l].ld;
   x.Hp = c->H[l - 1].f(); x.ldh = c->H[l - 1].ld;
   x.d_in = L.in_dim; x.eps = c->eps;
@@ -190,7 +253,7 @@ static hipError_t run_transform(ink_ctx *c, int l, const int32_t *rows, int64_t 
   if (e != hipSuccess) return e;
   x.mode = 1;
   x.W = L.W1; x.Kp = L.K1p; x.Np = L.N1p; x.bias = L.b1; x.n_out = L.hidden; x.relu = 1;
-  x.out = c->stage0.as<float>(); x.ld_out = L.N1p; x.to_table = 0;
+  x.out = c->stage0.as<float>(); x.ld_out = L.N1p; x.to_table = 0; x.old_rows = nullptr;
   e = xform_run(c, x);
   if (e != hipSuccess) return e;
   XformArgs y;
@@ -199,6 +262,7 @@ static hipError_t run_transform(ink_ctx *c, int l, const int32_t *rows, int64_t 
   y.Hp = c->stage0.as<float>(); y.ldh = L.N1p; y.d_in = L.hidden;
   y.W = L.W2; y.Kp = L.K2p; y.Np = L.N2p; y.bias = L.b2; y.n_out = L.out_dim; y.relu = L.act == INK_ACT_RELU;
   y.out = c->H[l].f(); y.ld_out = c->H[l].ld; y.to_table = 1; y.row_changed = flags; y.out_rows = rows;
+  y.old_rows = old_rows; y.ld_old = c->H[l].ld;
   return xform_run(c, y);
 }
 
@@ -206,14 +270,14 @@ static hipError_t run_transform(ink_ctx *c, int l, const int32_t *rows, int64_t 
 static ink_status validate_model(const ink_model *m, int feat_dim, std::string &why) {
   if (m->n_layers < 1 || m->n_layers > INK_MAX_LAYERS || !m->layers) { why = "n_layers out of range or layers NULL"; return INK_E_ARG; }
   if (m->kind != INK_MODEL_SAGE && m->kind != INK_MODEL_GIN && m->kind != INK_MODEL_GCN) { why = "unknown model kind"; return INK_E_ARG; }
-  bool select = m->agg == INK_AGG_MAX || m->agg == INK_AGG_MIN;
-  if (!select) { why = "aggregator not supported by this build for this model"; return INK_E_ARG; }
-  if (m->kind == INK_MODEL_GCN) { why = "GCN requires INK_AGG_GCN_SYM"; return INK_E_ARG; }
+  if (m->agg < INK_AGG_MAX || m->agg > INK_AGG_GCN_SYM) { why = "unknown aggregator"; return INK_E_ARG; }
+  if ((m->kind == INK_MODEL_GCN) != (m->agg == INK_AGG_GCN_SYM)) { why = "GCN needs INK_AGG_GCN_SYM (and only GCN takes it)"; return INK_E_ARG; }
   int d = feat_dim;
   for (int l = 0; l < m->n_layers; l++) {
     const ink_layer &L = m->layers[l];
     if (L.in_dim != d) { why = "layer in_dim does not match the previous width"; return INK_E_ARG; }
-    if (L.in_dim < 1 || L.out_dim < 1 || L.in_dim > INK_MAX_AGG_DIM || L.out_dim > 256) { why = "layer width out of range (1..256)"; return INK_E_ARG; }
+    int agg_w = m->kind == INK_MODEL_GCN ? L.out_dim : L.in_dim;      // GCN aggregates after the linear map
+    if (L.in_dim < 1 || L.out_dim < 1 || agg_w > INK_MAX_AGG_DIM || L.out_dim > 256 || L.in_dim > 16384) { why = "layer width out of range"; return INK_E_ARG; }
     if (!L.W_neigh) { why = "W_neigh is NULL"; return INK_E_ARG; }
     if (m->kind == INK_MODEL_SAGE && !L.W_self) { why = "GraphSAGE needs W_self"; return INK_E_ARG; }
     if (m->kind == INK_MODEL_GIN && (!L.W_mlp2 || L.mlp_hidden < 1 || L.mlp_hidden > 256)) { why = "GIN needs W_mlp2 and 1 <= mlp_hidden <= 256"; return INK_E_ARG; }
@@ -257,11 +321,12 @@ extern "C" ink_status ink_create(const ink_csr *g, const float *features, int32_
   c->n = n; c->n_edges = E; c->n_edges_now = E;
   c->id_bits = 1; while ((1ll << c->id_bits) < n) c->id_bits++;
   c->kind = model->kind; c->agg = model->agg; c->n_layers = model->n_layers; c->eps = model->gin_eps;
-  c->is_select = true; c->is_min = model->agg == INK_AGG_MIN;
+  c->is_select = model->agg == INK_AGG_MAX || model->agg == INK_AGG_MIN; c->is_min = model->agg == INK_AGG_MIN;
   c->mem = dev ? INK_MEM_DEVICE : INK_MEM_HOST;
   c->slack = (opts && opts->slack_factor > 0.f) ? opts->slack_factor : 0.25f;
   c->profile = opts ? opts->profile : 0;
   c->pool_reserve = opts ? opts->pool_reserve : 0;
+  c->batch_dev = dev || (opts && opts->batch_mem == INK_MEM_DEVICE);
   if (opts && opts->dense_threshold != 0.f) c->dense_frac = opts->dense_threshold < 0.f ? 1e30 : opts->dense_threshold;
   memset(&c->stats, 0, sizeof(c->stats));
 #define CREATE_TRY(x)                                                                              \
@@ -287,6 +352,8 @@ extern "C" ink_status ink_create(const ink_csr *g, const float *features, int32_
   CREATE_TRY(c->big_list.reserve((size_t)(c->gin.pool_cap / kBigDeg + 4096) * 4));
   // tables
   c->H.resize(c->n_layers + 1); c->A.resize(c->n_layers + 1); c->ARG.resize(c->n_layers + 1);
+  c->XW.resize(c->n_layers + 1); c->Msc.resize(c->n_layers + 1);
+  if (c->kind == INK_MODEL_GCN) CREATE_TRY(hipMalloc(&c->cnorm, (size_t)n * 4));
   CREATE_TRY(alloc_table(c->H[0], n, feat_dim));
   {
     DevBuf tmp;
@@ -307,9 +374,17 @@ extern "C" ink_status ink_create(const ink_csr *g, const float *features, int32_
     DevLayer &L = c->layers[l - 1];
     L.in_dim = S.in_dim; L.out_dim = S.out_dim; L.hidden = S.mlp_hidden; L.act = S.act;
     CREATE_TRY(alloc_table(c->H[l], n, S.out_dim));
-    CREATE_TRY(alloc_table(c->A[l], n, S.in_dim));
-    CREATE_TRY(alloc_table(c->ARG[l], n, S.in_dim));
-    if (c->kind == INK_MODEL_SAGE) {
+    CREATE_TRY(alloc_table(c->A[l], n, c->kind == INK_MODEL_GCN ? S.out_dim : S.in_dim));
+    if (c->is_select) CREATE_TRY(alloc_table(c->ARG[l], n, S.in_dim));
+    if (c->kind == INK_MODEL_GCN) {
+      CREATE_TRY(alloc_table(c->Msc[l], n, S.out_dim));
+      if (l == 1) CREATE_TRY(alloc_table(c->XW[1], n, S.out_dim));
+      L.K1 = S.in_dim; L.K1p = round_up(L.K1, 32); L.N1 = S.out_dim; L.N1p = round_up(L.N1, 32);
+      CREATE_TRY(hipMalloc(&L.W1, (size_t)L.K1p * L.N1p * 4));
+      CREATE_TRY(hipMemset(L.W1, 0, (size_t)L.K1p * L.N1p * 4));
+      CREATE_TRY(upload_padded(S.W_neigh, S.in_dim, S.out_dim, L.K1p, L.N1p, 0, L.W1, dev));
+      CREATE_TRY(upload_vec(S.bias, S.out_dim, &L.b1, dev));
+    } else if (c->kind == INK_MODEL_SAGE) {
       L.K1 = 2 * S.in_dim; L.K1p = round_up(L.K1, 32); L.N1 = S.out_dim; L.N1p = round_up(L.N1, 32);
       CREATE_TRY(hipMalloc(&L.W1, (size_t)L.K1p * L.N1p * 4));
       CREATE_TRY(hipMemset(L.W1, 0, (size_t)L.K1p * L.N1p * 4));
@@ -352,7 +427,8 @@ extern "C" void ink_destroy(ink_ctx *c) {
   if (c->bm_b) (void)hipFree(c->bm_b);
   for (DevBuf *b : {&c->ws.blk, &c->ws.hist, &c->ws.tmpk, &c->ws.tmpv, &c->b_raw, &c->b_misc, &c->b_uniq, &c->b_del_s,
                     &c->b_del_d, &c->b_ins_s, &c->b_ins_d, &c->f_list[0], &c->f_list[1], &c->f_old[0], &c->f_old[1],
-                    &c->f_pref, &c->ev_key, &c->ev_val, &c->t_list, &c->t_seg, &c->c_list, &c->c_flag, &c->c_idx,
+                    &c->f_pref, &c->ev_key, &c->ev_val, &c->t_list, &c->t_seg, &c->c_list, &c->c_flag, &c->c_idx, &c->c_old,
+                    &c->b_touch_in,
                     &c->big_list, &c->big_part_v, &c->big_part_i, &c->stage0, &c->stage1, &c->res_ids, &c->res_emb})
     b->release();
   for (auto e : c->ev_free) (void)hipEventDestroy(e);
@@ -364,19 +440,71 @@ extern "C" void ink_destroy(ink_ctx *c) {
 extern "C" const char *ink_last_error(const ink_ctx *c) { return c ? c->err.c_str() : g_create_err.c_str(); }
 
 // ------------------------------------------------------------------------------------ full inference
+static hipError_t agg_full_any(ink_ctx *c, const AggArgs &a, uint64_t *chg) {
+  return c->is_select ? agg_select_full(c, a, nullptr, c->n, chg) : agg_sum_full(c, a, nullptr, c->n, chg);
+}
+
+// GCN: message table of layer l + 1 from the finished layer l (rows == null: every node):
+// h_l = act(c (S_l + m_l) + b_l) is stored, then m_{l+1} = c * (h_l W_{l+1}) with compare-and-emit
+static hipError_t gcn_next_messages(ink_ctx *c, int l, const int32_t *rows, int64_t n_rows, uint8_t *flags,
+                                    float *old_rows) {
+  const DevLayer &L = c->layers[l - 1], &Ln = c->layers[l];
+  XformArgs x;
+  memset(&x, 0, sizeof(x));
+  x.mode = 3; x.rows = rows; x.n_rows = n_rows;
+  x.A = c->A[l].f(); x.lda = c->A[l].ld; x.Hp = c->Msc[l].f(); x.ldh = c->Msc[l].ld; x.d_in = L.out_dim;
+  x.cnorm = c->cnorm; x.in_bias = L.b1; x.in_relu = L.act == INK_ACT_RELU;
+  x.h_store = c->H[l].f(); x.ld_hs = c->H[l].ld;
+  x.W = Ln.W1; x.Kp = Ln.K1p; x.Np = Ln.N1p; x.bias = nullptr; x.n_out = Ln.out_dim; x.relu = 0;
+  x.out_scale = c->cnorm;
+  x.out = c->Msc[l + 1].f(); x.ld_out = c->Msc[l + 1].ld; x.to_table = 1; x.row_changed = flags;
+  x.old_rows = old_rows; x.ld_old = c->Msc[l + 1].ld;
+  return xform_run(c, x);
+}
+
+static hipError_t gcn_final(ink_ctx *c, const int32_t *rows, int64_t n_rows, uint8_t *flags) {
+  int k = c->n_layers;
+  const DevLayer &L = c->layers[k - 1];
+  if (n_rows <= 0) return hipSuccess;
+  hipLaunchKernelGGL(k_gcn_final, grid1(n_rows * c->H[k].ld), dim3(256), 0, c->stream, rows, n_rows,
+                     (const float *)c->A[k].f(), (const float *)c->Msc[k].f(), (const float *)c->cnorm,
+                     (const float *)L.b1, (int)(L.act == INK_ACT_RELU), c->H[k].f(), c->H[k].ld, c->H[k].d, flags);
+  return hipGetLastError();
+}
+
 extern "C" ink_status ink_full_infer(ink_ctx *c) {
   if (!c) return INK_E_ARG;
   auto t0 = std::chrono::steady_clock::now();
   memset(&c->stats, 0, sizeof(c->stats));
   c->stats.n_layers = c->n_layers;
+  hipStream_t s = c->stream;
+  if (c->kind == INK_MODEL_GCN) {
+    Prof p(c, INK_T_TRANSFORM);
+    const DevLayer &L = c->layers[0];
+    XformArgs x;
+    memset(&x, 0, sizeof(x));
+    x.mode = 2; x.n_rows = c->n; x.Hp = c->H[0].f(); x.ldh = c->H[0].ld; x.d_in = L.in_dim;
+    x.W = L.W1; x.Kp = L.K1p; x.Np = L.N1p; x.n_out = L.out_dim;
+    x.out = c->XW[1].f(); x.ld_out = c->XW[1].ld; x.to_table = 0;
+    API_TRY(xform_run(c, x));
+    hipLaunchKernelGGL(k_gcn_rescale, grid1((int64_t)c->n * c->Msc[1].ld), dim3(256), 0, s, (const int32_t *)nullptr,
+                       (int64_t)c->n, (const int32_t *)c->gin.deg, c->cnorm, (const float *)c->XW[1].f(),
+                       c->Msc[1].f(), c->Msc[1].ld, c->Msc[1].d, (float *)nullptr, (uint8_t *)nullptr);
+    API_TRY(hipGetLastError());
+  }
   for (int l = 1; l <= c->n_layers; l++) {
     AggArgs a = agg_args(c, l);
-    { Prof p(c, INK_T_AGG); API_TRY(agg_select_full(c, a, nullptr, c->n, nullptr)); }
-    { Prof p(c, INK_T_TRANSFORM); API_TRY(run_transform(c, l, nullptr, c->n, nullptr)); }
+    { Prof p(c, INK_T_AGG); API_TRY(agg_full_any(c, a, nullptr)); }
+    {
+      Prof p(c, INK_T_TRANSFORM);
+      if (c->kind != INK_MODEL_GCN) API_TRY(run_transform(c, l, nullptr, c->n, nullptr));
+      else if (l < c->n_layers) API_TRY(gcn_next_messages(c, l, nullptr, c->n, nullptr, nullptr));
+      else API_TRY(gcn_final(c, nullptr, c->n, nullptr));
+    }
     ink_layer_stats &S = c->stats.layer[l - 1];
     S.dense = 1; S.n_targets = c->n; S.n_exposed = c->n; S.n_regather_nb = c->n_edges_now; S.n_transformed = c->n;
   }
-  API_TRY(hipStreamSynchronize(c->stream));
+  API_TRY(hipStreamSynchronize(s));
   prof_collect(c);
   c->inferred = true;
   c->stats.ms_total = std::chrono::duration<float, std::milli>(std::chrono::steady_clock::now() - t0).count();
@@ -384,6 +512,120 @@ extern "C" ink_status ink_full_infer(ink_ctx *c) {
 }
 
 // ------------------------------------------------------------------------------------ updates
+// Events + grouping + aggregation of layer l.  F (nF ids, ascending) are the sources whose message
+// changed, f_old their previous message rows (sum-type only).  Marks targets whose aggregate
+// changed in c->bm_a.
+static ink_status layer_aggregate(ink_ctx *c, int l, const int32_t *F, int64_t nF, const float *f_old, int ld_old,
+                                  int64_t n_ins, int64_t n_del) {
+  hipStream_t s = c->stream;
+  ink_layer_stats &S = c->stats.layer[l - 1];
+  Counters *dc = c->d_cnt;
+  AggArgs a = agg_args(c, l);
+  const int64_t n_seed = n_ins + n_del;
+  S.n_sources = nF;
+  int64_t n_chg = 0;
+  {
+    Prof p(c, INK_T_EVENTS);
+    API_TRY(hipMemsetAsync(dc, 0, sizeof(Counters), s));
+    if (nF > 0) {
+      API_TRY(c->f_pref.reserve((size_t)(nF + 1) * 4));
+      API_TRY(tile_scan(c->ws, KeptOutDeg{F, c->gout.deg, c->new_out}, StorePref{c->f_pref.as<int32_t>()}, nF,
+                        &dc->v[C_NEV], s));
+      API_TRY(read_counters(c));
+      n_chg = (uint32_t)c->h_cnt->v[C_NEV];
+    }
+  }
+  int64_t nE = n_seed + n_chg;
+  S.n_events = nE;
+  uint64_t *bm = c->bm_a;
+  bool dense = nE > 0 && (double)nE > c->dense_frac * (double)std::max<int64_t>(c->n_edges_now, 1);
+  S.dense = dense;
+  if (dense) {
+    // so many events that re-aggregating every node costs less than grouping them (Sec. 5.1)
+    Prof p(c, INK_T_AGG);
+    API_TRY(agg_full_any(c, a, bm));
+    S.n_targets = c->n; S.n_exposed = c->n; S.n_regather_nb = c->n_edges_now;
+    return INK_OK;
+  }
+  if (nE == 0) return INK_OK;
+  {
+    Prof p(c, INK_T_EVENTS);
+    API_TRY(c->ev_key.reserve((size_t)nE * 4));
+    API_TRY(c->ev_val.reserve((size_t)nE * 4));
+    uint32_t *key = c->ev_key.as<uint32_t>(), *val = c->ev_val.as<uint32_t>();
+    if (n_seed > 0)
+      hipLaunchKernelGGL(k_seed_events, grid1(n_seed), dim3(256), 0, s, (const int32_t *)c->del_src,
+                         (const int32_t *)c->del_dst, (const int32_t *)c->ins_src, (const int32_t *)c->ins_dst,
+                         (int)n_del, (int)n_ins, key, val);
+    if (n_chg > 0)
+      hipLaunchKernelGGL(k_expand_events, grid1(n_chg), dim3(256), 0, s, F, (int)nF,
+                         (const int32_t *)c->f_pref.as<int32_t>(), (int)n_chg, (const int64_t *)c->gout.off,
+                         (const int32_t *)c->gout.ids, key + n_seed, val + n_seed, c->is_select ? 0 : 1);
+    API_TRY(hipGetLastError());
+  }
+  {
+    Prof p(c, INK_T_GROUP);
+    API_TRY(radix_sort_pairs(c->ws, c->ev_key.as<uint32_t>(), c->ev_val.as<uint32_t>(), nE, c->id_bits, s));
+    API_TRY(c->t_list.reserve((size_t)(nE + 1) * 4));
+    API_TRY(c->t_seg.reserve((size_t)(nE + 2) * 4));
+    API_TRY(segment_heads(c->ws, c->ev_key.as<uint32_t>(), nE, c->t_list.as<int32_t>(), c->t_seg.as<int32_t>(),
+                          &dc->v[C_NT], s));
+    API_TRY(read_counters(c));
+  }
+  int64_t nT = c->h_cnt->v[C_NT];
+  S.n_targets = nT;
+  {
+    Prof p(c, INK_T_AGG);
+    if (c->is_select) {
+      API_TRY(agg_select_events(c, a, c->t_list.as<int32_t>(), c->t_seg.as<int32_t>(), nT, c->ev_val.as<uint32_t>(), bm));
+      S.n_exposed = c->h_cnt->v[C_EXPOSED];
+      S.n_regather_nb = *(int64_t *)&c->h_cnt->v[C_REGATHER_LO];
+      S.n_alpha_changed = c->h_cnt->v[C_ACHG];
+    } else {
+      API_TRY(agg_sum_events(c, a, c->t_list.as<int32_t>(), c->t_seg.as<int32_t>(), nT, c->ev_val.as<uint32_t>(), F,
+                             (int)nF, f_old, ld_old, bm));
+    }
+  }
+  return INK_OK;
+}
+
+// bitmap (plus extra id lists) -> ascending row list in c->c_list; returns the count
+static ink_status collect_rows(ink_ctx *c, const int32_t *extra0, int64_t n0, const int32_t *extra1, int64_t n1,
+                               int64_t *nC) {
+  hipStream_t s = c->stream;
+  Prof p(c, INK_T_COMPACT);
+  if (n0 > 0) hipLaunchKernelGGL(k_mark_nodes, grid1(n0), dim3(256), 0, s, extra0, (int)n0, c->bm_a);
+  if (n1 > 0) hipLaunchKernelGGL(k_mark_nodes, grid1(n1), dim3(256), 0, s, extra1, (int)n1, c->bm_a);
+  API_TRY(c->c_list.reserve((size_t)c->n * 4));
+  API_TRY(bitmap_to_list(c->ws, c->bm_a, c->n, c->c_list.as<int32_t>(), &c->d_cnt->v[C_NC], 1, s));
+  API_TRY(read_counters(c));
+  *nC = c->h_cnt->v[C_NC];
+  return INK_OK;
+}
+
+// rows of c_list whose flag is set -> f_list[nxt] (ids) and, for sum-type, f_old[nxt] (old rows
+// taken from c_old with row stride ld)
+static ink_status emit_changed(ink_ctx *c, int64_t nC, int nxt, bool keep_old, int ld, int64_t *nF2) {
+  hipStream_t s = c->stream;
+  Prof p(c, INK_T_COMPACT);
+  API_TRY(compact_flags_u8(c->ws, c->c_flag.as<uint8_t>(), nC, c->c_idx.as<int32_t>(), &c->d_cnt->v[C_NEXT], s));
+  API_TRY(read_counters(c));
+  int64_t n = c->h_cnt->v[C_NEXT];
+  *nF2 = n;
+  if (n > 0) {
+    API_TRY(c->f_list[nxt].reserve((size_t)n * 4));
+    hipLaunchKernelGGL(k_gather_i32, grid1(n), dim3(256), 0, s, (const int32_t *)c->c_list.as<int32_t>(),
+                       (const int32_t *)c->c_idx.as<int32_t>(), (int)n, c->f_list[nxt].as<int32_t>());
+    if (keep_old) {
+      API_TRY(c->f_old[nxt].reserve((size_t)n * ld * 4));
+      hipLaunchKernelGGL(k_gather_rows_ld, grid1(n * ld), dim3(256), 0, s, (const float *)c->c_old.as<float>(), ld,
+                         (const int32_t *)c->c_idx.as<int32_t>(), n, c->f_old[nxt].as<float>());
+    }
+    API_TRY(hipGetLastError());
+  }
+  return INK_OK;
+}
+
 extern "C" ink_status ink_apply_updates(ink_ctx *c, const ink_edge_update *upd, int64_t n, ink_update_result *out) {
   if (!c) return INK_E_ARG;
   if (!out || n < 0 || (n > 0 && !upd)) return fail(c, INK_E_ARG, "ink_apply_updates: NULL argument or negative n");
@@ -395,7 +637,7 @@ extern "C" ink_status ink_apply_updates(ink_ctx *c, const ink_edge_update *upd, 
   // validation on the host before anything is touched
   std::vector<ink_edge_update> staged;
   const ink_edge_update *h = upd;
-  if (c->mem == INK_MEM_DEVICE && n > 0) {
+  if (c->batch_dev && n > 0) {
     staged.resize((size_t)n);
     API_TRY(hipMemcpy(staged.data(), upd, (size_t)n * sizeof(ink_edge_update), hipMemcpyDeviceToHost));
     h = staged.data();
@@ -412,111 +654,72 @@ extern "C" ink_status ink_apply_updates(ink_ctx *c, const ink_edge_update *upd, 
     Prof p(c, INK_T_GRAPH);
     API_TRY(c->b_raw.reserve((size_t)n * sizeof(ink_edge_update)));
     API_TRY(hipMemcpyAsync(c->b_raw.p, upd, (size_t)n * sizeof(ink_edge_update),
-                           c->mem == INK_MEM_DEVICE ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice, s));
+                           c->batch_dev ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice, s));
     ink_status st = graph_apply_batch(c, n, &n_ins, &n_del);
     if (st != INK_OK) return st;
   }
   out->n_applied_ins = n_ins; out->n_applied_del = n_del; out->n_noop = n - n_ins - n_del;
   c->n_edges_now += n_ins - n_del;
-
-  int64_t nF = 0;            // |F_l|: sources whose message changed (F_1 is empty: features are static)
-  int cur = 0;               // f_list[cur] holds F_l
   const int64_t n_seed = n_ins + n_del;
+  const bool gcn = c->kind == INK_MODEL_GCN;
+  const bool keep_old = !c->is_select;          // sum-type aggregators subtract the old message rows
+  // nodes whose in-degree may have changed: their normalisation (GCN, mean) changes row-locally
+  const int32_t *D = (const int32_t *)c->b_touch_in.p;
+  const int64_t nD = (n_seed > 0 && (gcn || c->agg == INK_AGG_MEAN)) ? c->n_touched_in : 0;
+
+  int64_t nF = 0;            // |F_l|: sources whose message m_l changed
+  int cur = 0;               // f_list[cur] / f_old[cur] describe F_l
+  if (gcn && nD > 0) {
+    // layer-1 messages are c_u * (x_u W_1): a degree change rescales the row
+    Prof p(c, INK_T_TRANSFORM);
+    int ld = c->Msc[1].ld;
+    API_TRY(c->c_flag.reserve((size_t)nD + 64));
+    API_TRY(c->c_idx.reserve((size_t)nD * 4));
+    API_TRY(c->c_old.reserve((size_t)nD * ld * 4));
+    API_TRY(c->c_list.reserve((size_t)c->n * 4));
+    API_TRY(hipMemsetAsync(c->c_flag.p, 0, (size_t)nD, s));
+    API_TRY(hipMemcpyAsync(c->c_list.p, D, (size_t)nD * 4, hipMemcpyDeviceToDevice, s));
+    hipLaunchKernelGGL(k_gcn_rescale, grid1(nD * ld), dim3(256), 0, s, D, nD, (const int32_t *)c->gin.deg, c->cnorm,
+                       (const float *)c->XW[1].f(), c->Msc[1].f(), ld, c->Msc[1].d, c->c_old.as<float>(),
+                       c->c_flag.as<uint8_t>());
+    API_TRY(hipGetLastError());
+    ink_status st = emit_changed(c, nD, cur, true, ld, &nF);
+    if (st != INK_OK) return st;
+  }
   for (int l = 1; l <= c->n_layers && (n_seed > 0 || nF > 0); l++) {
     ink_layer_stats &S = c->stats.layer[l - 1];
-    S.n_sources = nF;
-    Counters *dc = c->d_cnt;
     const int32_t *F = c->f_list[cur].as<int32_t>();
-    AggArgs a = agg_args(c, l);
-    // ---- events: count what the changed sources will propagate
-    int64_t n_chg = 0;
-    {
-      Prof p(c, INK_T_EVENTS);
-      API_TRY(hipMemsetAsync(dc, 0, sizeof(Counters), s));
-      if (nF > 0) {
-        API_TRY(c->f_pref.reserve((size_t)(nF + 1) * 4));
-        API_TRY(tile_scan(c->ws, KeptOutDeg{F, c->gout.deg, c->new_out}, StorePref{c->f_pref.as<int32_t>()}, nF,
-                          &dc->v[C_NEV], s));
-        API_TRY(read_counters(c));
-        n_chg = (uint32_t)c->h_cnt->v[C_NEV];
-      }
-    }
-    int64_t nE = n_seed + n_chg;
-    S.n_events = nE;
-    uint64_t *bm = c->bm_a;
-    bool dense = nE > 0 && (double)nE > c->dense_frac * (double)std::max<int64_t>(c->n_edges_now, 1);
-    S.dense = dense;
-    if (dense) {
-      // so many events that re-aggregating every node costs less than grouping them
-      Prof p(c, INK_T_AGG);
-      API_TRY(agg_select_full(c, a, nullptr, c->n, bm));
-      S.n_targets = c->n; S.n_exposed = c->n; S.n_regather_nb = c->n_edges_now;
-    } else if (nE > 0) {
-      {
-        Prof p(c, INK_T_EVENTS);
-        API_TRY(c->ev_key.reserve((size_t)nE * 4));
-        API_TRY(c->ev_val.reserve((size_t)nE * 4));
-        uint32_t *key = c->ev_key.as<uint32_t>(), *val = c->ev_val.as<uint32_t>();
-        if (n_seed > 0)
-          hipLaunchKernelGGL(k_seed_events, grid1(n_seed), dim3(256), 0, s, (const int32_t *)c->del_src,
-                             (const int32_t *)c->del_dst, (const int32_t *)c->ins_src, (const int32_t *)c->ins_dst,
-                             (int)n_del, (int)n_ins, key, val);
-        if (n_chg > 0)
-          hipLaunchKernelGGL(k_expand_events, grid1(n_chg), dim3(256), 0, s, F, (int)nF,
-                             (const int32_t *)c->f_pref.as<int32_t>(), (int)n_chg, (const int64_t *)c->gout.off,
-                             (const int32_t *)c->gout.ids, key + n_seed, val + n_seed, 0);
-        API_TRY(hipGetLastError());
-      }
-      {
-        Prof p(c, INK_T_GROUP);
-        API_TRY(radix_sort_pairs(c->ws, c->ev_key.as<uint32_t>(), c->ev_val.as<uint32_t>(), nE, c->id_bits, s));
-        API_TRY(c->t_list.reserve((size_t)(nE + 1) * 4));
-        API_TRY(c->t_seg.reserve((size_t)(nE + 2) * 4));
-        API_TRY(segment_heads(c->ws, c->ev_key.as<uint32_t>(), nE, c->t_list.as<int32_t>(), c->t_seg.as<int32_t>(),
-                              &dc->v[C_NT], s));
-        API_TRY(read_counters(c));
-      }
-      int64_t nT = c->h_cnt->v[C_NT];
-      S.n_targets = nT;
-      {
-        Prof p(c, INK_T_AGG);
-        API_TRY(agg_select_events(c, a, c->t_list.as<int32_t>(), c->t_seg.as<int32_t>(), nT,
-                                  c->ev_val.as<uint32_t>(), bm));
-        S.n_exposed = c->h_cnt->v[C_EXPOSED];
-        S.n_regather_nb = *(int64_t *)&c->h_cnt->v[C_REGATHER_LO];
-        S.n_alpha_changed = c->h_cnt->v[C_ACHG];
-      }
-    }
-    // ---- rows to transform: alpha changed, or own previous-layer embedding changed (self term)
+    int ld_msg = msg_table(c, l).ld;
+    ink_status st = layer_aggregate(c, l, F, nF, keep_old ? c->f_old[cur].as<float>() : nullptr, ld_msg, n_ins, n_del);
+    if (st != INK_OK) return st;
+    // rows to transform: aggregate changed; own message changed (self term); degree changed
     int64_t nC = 0;
-    {
-      Prof p(c, INK_T_COMPACT);
-      if (nF > 0) hipLaunchKernelGGL(k_mark_nodes, grid1(nF), dim3(256), 0, s, F, (int)nF, bm);
-      API_TRY(c->c_list.reserve((size_t)c->n * 4));
-      API_TRY(bitmap_to_list(c->ws, bm, c->n, c->c_list.as<int32_t>(), &dc->v[C_NC], 1, s));
-      API_TRY(read_counters(c));
-      nC = c->h_cnt->v[C_NC];
-    }
+    st = collect_rows(c, F, nF, D, nD, &nC);
+    if (st != INK_OK) return st;
     S.n_transformed = nC;
+    if (!c->is_select && !S.dense) S.n_alpha_changed = c->h_cnt->v[C_ACHG];
     int nxt = cur ^ 1;
     int64_t nF2 = 0;
     if (nC > 0) {
+      const bool last = l == c->n_layers;
+      int ld_next = gcn ? (last ? c->H[l].ld : c->Msc[l + 1].ld) : c->H[l].ld;
       API_TRY(c->c_flag.reserve((size_t)nC + 64));
       API_TRY(c->c_idx.reserve((size_t)nC * 4));
-      API_TRY(c->f_list[nxt].reserve((size_t)nC * 4));
+      bool want_old = keep_old && !last;
+      if (want_old) API_TRY(c->c_old.reserve((size_t)nC * ld_next * 4));
       {
         Prof p(c, INK_T_TRANSFORM);
-        API_TRY(run_transform(c, l, c->c_list.as<int32_t>(), nC, c->c_flag.as<uint8_t>()));
+        const int32_t *rows = c->c_list.as<int32_t>();
+        float *old_rows = want_old ? c->c_old.as<float>() : nullptr;
+        if (!gcn) API_TRY(run_transform(c, l, rows, nC, c->c_flag.as<uint8_t>(), old_rows));
+        else {
+          API_TRY(hipMemsetAsync(c->c_flag.p, 0, (size_t)nC, s));
+          if (!last) API_TRY(gcn_next_messages(c, l, rows, nC, c->c_flag.as<uint8_t>(), old_rows));
+          else API_TRY(gcn_final(c, rows, nC, c->c_flag.as<uint8_t>()));
+        }
       }
-      {
-        Prof p(c, INK_T_COMPACT);
-        API_TRY(compact_flags_u8(c->ws, c->c_flag.as<uint8_t>(), nC, c->c_idx.as<int32_t>(), &dc->v[C_NEXT], s));
-        API_TRY(read_counters(c));
-        nF2 = c->h_cnt->v[C_NEXT];
-        if (nF2 > 0)
-          hipLaunchKernelGGL(k_gather_i32, grid1(nF2), dim3(256), 0, s, (const int32_t *)c->c_list.as<int32_t>(),
-                             (const int32_t *)c->c_idx.as<int32_t>(), (int)nF2, c->f_list[nxt].as<int32_t>());
-      }
+      st = emit_changed(c, nC, nxt, want_old, ld_next, &nF2);
+      if (st != INK_OK) return st;
     }
     S.n_changed = nF2;
     nF = nF2;
@@ -550,6 +753,7 @@ extern "C" ink_status ink_get_layer(ink_ctx *c, int32_t layer, int32_t which, in
   if (layer < 0 || layer > c->n_layers || which < 0 || which > 2 || (which > 0 && layer == 0))
     return fail(c, INK_E_RANGE, "ink_get_layer: layer / which out of range");
   if (row0 < 0 || nrows < 0 || row0 + nrows > c->n) return fail(c, INK_E_RANGE, "ink_get_layer: rows out of range");
+  if (which == 2 && !c->is_select) return fail(c, INK_E_ARG, "ink_get_layer: no argument table for sum-type aggregators");
   const Table &t = which == 0 ? c->H[layer] : (which == 1 ? c->A[layer] : c->ARG[layer]);
   if (!t.p) return fail(c, INK_E_ARG, "ink_get_layer: table not kept for this model");
   if (width_out) *width_out = t.d;

@@ -57,6 +57,7 @@ struct ink_ctx {
   int id_bits = 1;
   int kind = 0, agg = 0, n_layers = 0, mem = 0, profile = 0;
   float eps = 0.f, slack = 0.25f;
+  bool batch_dev = false;
   bool is_select = true, is_min = false, inferred = false, own_stream = false;
   hipStream_t stream = nullptr;
   std::string err;
@@ -90,6 +91,9 @@ struct ink_ctx {
   ink::DevBuf ev_key, ev_val;        // events
   ink::DevBuf t_list, t_seg;         // unique targets, segment offsets
   ink::DevBuf c_list, c_flag, c_idx; // rows to transform, per-row changed flag, compacted positions
+  ink::DevBuf c_old;                 // previous table rows of the transformed rows (sum-type)
+  ink::DevBuf b_touch_in;            // destinations touched by the current batch
+  int64_t n_touched_in = 0;
   ink::DevBuf big_list, big_part_v, big_part_i;   // cooperative re-gather
   ink::DevBuf stage0, stage1;        // transform staging
   ink::DevBuf res_ids, res_emb;      // result of the last batch
@@ -124,10 +128,17 @@ hipError_t agg_select_full(ink_ctx *c, const AggArgs &a, const int32_t *targets,
                            uint64_t *chg);
 hipError_t agg_select_events(ink_ctx *c, const AggArgs &a, const int32_t *targets, const int32_t *seg,
                              int64_t n_targets, const uint32_t *ev_val, uint64_t *chg);
+// sum-type aggregators (agg_sum.hip): A holds the plain sum of message rows.  F (ascending ids)
+// and f_old (their previous message rows, row stride ld_old) describe the changed sources.
+hipError_t agg_sum_full(ink_ctx *c, const AggArgs &a, const int32_t *targets, int64_t n_targets, uint64_t *chg);
+hipError_t agg_sum_events(ink_ctx *c, const AggArgs &a, const int32_t *targets, const int32_t *seg,
+                          int64_t n_targets, const uint32_t *ev_val, const int32_t *F, int nF, const float *f_old,
+                          int ld_old, uint64_t *chg);
 
 // ---- dense transform (xform.hip)
 struct XformArgs {
-  int mode;                 // 0 SAGE concat [A | Hprev], 1 GIN (1+eps) Hprev + A, 2 dense rows
+  int mode;                 // 0 SAGE concat [A | Hprev], 1 GIN (1+eps) Hprev + A, 2 dense rows,
+                            // 3 GCN: x = act(c_v (A + Hp) + in_bias), with A = neighbour sums, Hp = own scaled message
   const int32_t *rows;      // row ids (null: identity)
   int64_t n_rows;
   const float *A; int lda;  // aggregated table
@@ -140,6 +151,11 @@ struct XformArgs {
   uint8_t *row_changed;     // [n_rows] set to 1 if the table row changed bitwise (to_table)
   float *old_rows; int ld_old;   // optional copy of the previous table rows ([n_rows][ld_old])
   const int32_t *out_rows;  // table row ids for to_table when the input is dense (mode 2); null: identity
+  const int32_t *mean_deg;  // modes 0/1 with mean aggregation: A is divided by max(deg, 1)
+  const float *cnorm;       // mode 3: per-node c_v
+  const float *in_bias; int in_relu;   // mode 3
+  float *h_store; int ld_hs;           // mode 3: where x (= h_l) is written, one row per node
+  const float *out_scale;   // per-node factor applied to the output row (after bias), null: none
 };
 hipError_t xform_run(ink_ctx *c, const XformArgs &x);
 

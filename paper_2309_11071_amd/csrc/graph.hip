@@ -435,6 +435,7 @@ ink_status graph_apply_batch(ink_ctx *c, int64_t n, int64_t *n_ins_out, int64_t 
   hipStream_t s = c->stream;
   *n_ins_out = *n_del_out = 0;
   c->n_ins = c->n_del = 0;
+  c->n_touched_in = 0;
   if (n == 0) return INK_OK;
   const RawUpdate *raw = c->b_raw.as<RawUpdate>();
   size_t per = ((size_t)(n + 64) * 4 + 255) & ~(size_t)255;
@@ -476,6 +477,9 @@ ink_status graph_apply_batch(ink_ctx *c, int64_t n, int64_t *n_ins_out, int64_t 
   if (st != INK_OK) return st;
   c->n_ins = ti; c->n_del = td;
   *n_ins_out = ti; *n_del_out = td;
+  c->n_touched_in = n_touched;
+  INK_TRYS(c->b_touch_in.reserve((size_t)(n_touched + 1) * 4));
+  INK_TRYS(hipMemcpyAsync(c->b_touch_in.p, b.uniq, (size_t)n_touched * 4, hipMemcpyDeviceToDevice, s));
   if (ti + td == 0) return INK_OK;
 
   // Delta E lists, (dst, src) order

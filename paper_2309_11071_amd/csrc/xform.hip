@@ -15,15 +15,28 @@ typedef float f16v __attribute__((ext_vector_type(16)));
 constexpr int BM = 64;       // rows per workgroup
 constexpr int KT = 32;       // k-chunk staged in LDS
 
+__device__ __forceinline__ float agg_value(const XformArgs &x, int64_t row, int k) {
+  float a = x.A[row * x.lda + k];
+  if (x.mean_deg) { int dg = x.mean_deg[row]; a = __fdiv_rn(a, (float)(dg > 0 ? dg : 1)); }
+  return a;
+}
+
 template <int MODE>
 __device__ __forceinline__ float fetch_x(const XformArgs &x, int64_t row, int k) {
   if (MODE == 0) {           // SAGE: [alpha | h_prev]
-    if (k < x.d_in) return x.A[row * x.lda + k];
+    if (k < x.d_in) return agg_value(x, row, k);
     if (k < 2 * x.d_in) return x.Hp[row * x.ldh + (k - x.d_in)];
     return 0.f;
   } else if (MODE == 1) {    // GIN: (1 + eps) h_prev + alpha
-    if (k < x.d_in) return __fadd_rn(__fmul_rn(1.0f + x.eps, x.Hp[row * x.ldh + k]), x.A[row * x.lda + k]);
+    if (k < x.d_in) return __fadd_rn(__fmul_rn(1.0f + x.eps, x.Hp[row * x.ldh + k]), agg_value(x, row, k));
     return 0.f;
+  } else if (MODE == 3) {    // GCN: h = act(c_v (S + own scaled message) + b); also stored as h_l
+    if (k >= x.d_in) return 0.f;
+    float v = __fmul_rn(x.cnorm[row], __fadd_rn(x.A[row * x.lda + k], x.Hp[row * x.ldh + k]));
+    if (x.in_bias) v = __fadd_rn(v, x.in_bias[k]);
+    if (x.in_relu) v = v > 0.f ? v : 0.f;
+    if (x.h_store) x.h_store[row * x.ld_hs + k] = v;
+    return v;
   } else {                   // dense rows
     if (k < x.d_in) return x.Hp[row * x.ldh + k];
     return 0.f;
@@ -101,6 +114,7 @@ __global__ __launch_bounds__(256) void k_xform(XformArgs x) {
       if (row < 0) continue;
       float v = acc[i][r];
       if (x.bias) v = __fadd_rn(v, bias);
+      if (x.out_scale) v = __fmul_rn(v, x.out_scale[sout[rl]]);
       if (x.relu) v = v > 0.f ? v : 0.f;
       int64_t j = r0 + rl;
       if (x.to_table) {
@@ -142,6 +156,7 @@ hipError_t xform_run(ink_ctx *c, const XformArgs &x) {
     case 0: return launch<0>(c, x);
     case 1: return launch<1>(c, x);
     case 2: return launch<2>(c, x);
+    case 3: return launch<3>(c, x);
   }
   return hipErrorInvalidValue;
 }
