@@ -76,10 +76,12 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=3)
+    ap.add_argument("--config", type=int, default=2)
     ap.add_argument("--scale-div", type=int, default=1)
     ap.add_argument("--batch", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy so that a profiler's byte counters can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1",
@@ -118,6 +120,13 @@ def main():
         u = make_updates(op, bs, bd)
         batches.append(torch.from_numpy(u.view(np.uint8).copy()).cuda())
     torch.cuda.synchronize()
+    if args.copy_calibration:
+        a = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        b = torch.empty_like(a)
+        torch.cuda.synchronize()
+        b.copy_(a)                      # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del a, b
     for i in range(args.warmup):
         ink.apply_updates_device(batches[i].data_ptr(), cfg.batch)
     lat, agg_ms, agg_launches, agg_bytes, changed = [], 0.0, 0, 0, 0
