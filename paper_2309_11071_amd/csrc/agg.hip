@@ -3,7 +3,7 @@
 // update with reset detection (Sec. 2.5.1).  One wave64 owns one target row; a lane holds four
 // consecutive dimensions, so a row of d floats occupies LPR = 16/32/64 lanes and a wave works on
 // 64 / LPR neighbour rows at a time.  Rows are read as coalesced 16-byte lane loads.
-#include "ctx.h"
+#include "bigrows.h"
 
 namespace ink {
 
@@ -53,7 +53,7 @@ __device__ __forceinline__ void gather_range(const int32_t *ids, int64_t j0, int
     int64_t jj = jb + l;
     int myid = jj < j1 ? ids[jj] : -1;
     int cnt = (int)((j1 - jb) < kWave ? (j1 - jb) : kWave);
-    constexpr int U = 4;
+    constexpr int U = INK_GATHER_U;       // neighbour rows in flight per lane group
     for (int it = 0; it < cnt; it += G * U) {
       int id[U];
       float4 row[U];
@@ -153,22 +153,22 @@ __global__ __launch_bounds__(256) void k_agg_full(AggArgs a, const int32_t *targ
   if (ch && chg && l == 0) mark_bit(chg, v);
 }
 
-// cooperative path for rows with more than kBigDeg in-neighbours: grid (kBigParts, n_big);
-// each workgroup selects over its slice of the neighbour list and stores a partial row
+// cooperative path for rows with more than kBigDeg in-neighbours: one workgroup per chunk of
+// kBigChunk neighbours (its 4 waves take a quarter each), partial rows to scratch
 template <bool IS_MIN, int LPR>
-__global__ __launch_bounds__(256) void k_big_partial(AggArgs a, const int32_t *big_list, float *part_v,
-                                                     int32_t *part_i) {
+__global__ __launch_bounds__(256) void k_big_partial(AggArgs a, const int32_t *big_list, const int32_t *pref, int row0,
+                                                     int row1, int chunk0, float *part_v, int32_t *part_i) {
   __shared__ float sv[4][kWave * 4];
   __shared__ int si[4][kWave * 4];
   const int l = lane_id(), w = threadIdx.x / kWave;
   const int q = l % LPR;
   const bool lane_on = 4 * q < a.ld;
-  int v = big_list[blockIdx.y];
-  int64_t deg = a.in_deg[v];
+  int i, v;
+  int64_t j0, j1;
+  big_chunk_of_block(pref, row0, row1, chunk0, big_list, a.in_deg, i, v, j0, j1);
   int64_t off = a.in_off[v];
-  int64_t p0 = deg * blockIdx.x / kBigParts, p1 = deg * (blockIdx.x + 1) / kBigParts;
-  int64_t len = p1 - p0;
-  int64_t w0 = p0 + len * w / 4, w1 = p0 + len * (w + 1) / 4;
+  int64_t len = j1 - j0;
+  int64_t w0 = j0 + len * w / 4, w1 = j0 + len * (w + 1) / 4;
   F4 bv; I4 bi;
   gather_range<IS_MIN, LPR>(a.in_ids + off, w0, w1, a.M, a.ldm, lane_on, q, bv, bi);
 #pragma unroll
@@ -180,27 +180,29 @@ __global__ __launch_bounds__(256) void k_big_partial(AggArgs a, const int32_t *b
 #pragma unroll
       for (int c = 0; c < 4; c++) take<IS_MIN>(sv[ww][l * 4 + c], si[ww][l * 4 + c], bv.v[c], bi.v[c]);
     if (lane_on && l < LPR) {
-      int64_t o = ((int64_t)blockIdx.y * kBigParts + blockIdx.x) * a.ld + 4 * q;
+      int64_t o = (int64_t)blockIdx.x * a.ld + 4 * q;
 #pragma unroll
       for (int c = 0; c < 4; c++) { part_v[o + c] = bv.v[c]; part_i[o + c] = bi.v[c]; }
     }
   }
 }
 
-// one wave per big row: reduce the partial rows and store
+// one wave per big row: reduce its partial rows and store
 template <bool IS_MIN, int LPR>
-__global__ __launch_bounds__(64) void k_big_final(AggArgs a, const int32_t *big_list, const float *part_v,
-                                                  const int32_t *part_i, uint64_t *chg, int compare) {
+__global__ __launch_bounds__(64) void k_big_final(AggArgs a, const int32_t *big_list, const int32_t *pref, int row0,
+                                                  int chunk0, const float *part_v, const int32_t *part_i,
+                                                  uint64_t *chg, int compare) {
   const int l = lane_id();
   const int q = l % LPR;
   const bool lane_on = 4 * q < a.ld;
-  int v = big_list[blockIdx.x];
+  int i = row0 + blockIdx.x;
+  int v = big_list[i];
   F4 bv; I4 bi;
 #pragma unroll
   for (int c = 0; c < 4; c++) { bv.v[c] = worst<IS_MIN>(); bi.v[c] = 0x7fffffff; }
   if (lane_on && l < LPR) {
-    for (int p = 0; p < kBigParts; p++) {
-      int64_t o = ((int64_t)blockIdx.x * kBigParts + p) * a.ld + 4 * q;
+    for (int p = pref[i] - chunk0; p < pref[i + 1] - chunk0; p++) {
+      int64_t o = (int64_t)p * a.ld + 4 * q;
 #pragma unroll
       for (int c = 0; c < 4; c++) take<IS_MIN>(part_v[o + c], part_i[o + c], bv.v[c], bi.v[c]);
     }
@@ -249,22 +251,38 @@ __global__ __launch_bounds__(256) void k_agg_events(AggArgs a, const int32_t *ta
     int ee = eb + l;
     uint32_t mine = ee < e1 ? ev[ee] : 0xFFFFFFFFu;
     int cntw = (e1 - eb) < kWave ? (e1 - eb) : kWave;
-    for (int it = 0; it < cntw; it += G) {
-      int k = it + g;
-      uint32_t x = __shfl(mine, k < kWave ? k : 0, kWave);
-      if (k >= cntw || !lane_on) continue;
-      uint32_t kind = x >> kEvKindShift;
-      int u = (int)(x & kEvIdMask);
-      if (kind == EV_DEL) {
+    constexpr int U = 4;       // events in flight per lane group
+    for (int it = 0; it < cntw; it += G * U) {
+      int src[U];
+      bool chgk[U];
+      float4 r4[U];
 #pragma unroll
-        for (int c = 0; c < 4; c++) reset[c] |= (oi.v[c] == u);
-      } else {
-        float4 r4 = ld4(a.M + (int64_t)u * a.ldm + 4 * q);
-        float r[4] = {r4.x, r4.y, r4.z, r4.w};
+      for (int u = 0; u < U; u++) {
+        int k = it + u * G + g;
+        uint32_t x = __shfl(mine, k < kWave ? k : 0, kWave);
+        src[u] = -1;
+        chgk[u] = false;
+        if (k < cntw && lane_on) {
+          uint32_t kind = x >> kEvKindShift;
+          int uu = (int)(x & kEvIdMask);
+          if (kind == EV_DEL) {
+#pragma unroll
+            for (int c = 0; c < 4; c++) reset[c] |= (oi.v[c] == uu);
+          } else {
+            src[u] = uu;
+            chgk[u] = kind == EV_CHG;
+            r4[u] = ld4(a.M + (int64_t)uu * a.ldm + 4 * q);
+          }
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < U; u++) {
+        if (src[u] < 0) continue;
+        float r[4] = {r4[u].x, r4[u].y, r4[u].z, r4[u].w};
 #pragma unroll
         for (int c = 0; c < 4; c++) {
-          if (kind == EV_CHG && oi.v[c] == u && better<IS_MIN>(ov.v[c], r[c])) reset[c] = true;
-          take<IS_MIN>(r[c], u, cv.v[c], ci.v[c]);
+          if (chgk[u] && oi.v[c] == src[u] && better<IS_MIN>(ov.v[c], r[c])) reset[c] = true;
+          take<IS_MIN>(r[c], src[u], cv.v[c], ci.v[c]);
         }
       }
     }
@@ -293,8 +311,8 @@ __global__ __launch_bounds__(256) void k_agg_events(AggArgs a, const int32_t *ta
   if (exposed) {
     int deg = a.in_deg[v];
     if (l == 0) {
-      atomicAdd(&cnt->v[C_EXPOSED], 1);
-      atomicAdd((unsigned long long *)&cnt->v[C_REGATHER_LO], (unsigned long long)deg);
+      atomicAdd(&cnt->stripe[blockIdx.x % kStripes][ST_EXPOSED], 1ull);
+      atomicAdd(&cnt->stripe[blockIdx.x % kStripes][ST_REGATHER], (unsigned long long)deg);
     }
     if (deg > kBigDeg) {
       if (l == 0) big_list[atomicAdd(&cnt->v[C_NBIG], 1)] = v;
@@ -305,7 +323,7 @@ __global__ __launch_bounds__(256) void k_agg_events(AggArgs a, const int32_t *ta
   }
   RowOut o{a.A, a.ARG, a.ld, a.d};
   bool ch = store_row<LPR>(o, v, lane_on, q, nv, ni, true, ov, oi);
-  if (ch && l == 0) { mark_bit(chg, v); atomicAdd(&cnt->v[C_ACHG], 1); }
+  if (ch && l == 0) { mark_bit(chg, v); atomicAdd(&cnt->stripe[blockIdx.x % kStripes][ST_ACHG], 1ull); }
 }
 
 // ------------------------------------------------------------------ host side
@@ -313,17 +331,22 @@ static int lanes_per_row(int ld) { return ld <= 64 ? 16 : (ld <= 128 ? 32 : 64);
 
 template <bool IS_MIN, int LPR>
 static hipError_t run_big(ink_ctx *c, const AggArgs &a, int n_big, uint64_t *chg, int compare) {
-  const int chunk = 512;
-  INK_TRY(c->big_part_v.reserve((size_t)chunk * kBigParts * a.ld * sizeof(float)));
-  INK_TRY(c->big_part_i.reserve((size_t)chunk * kBigParts * a.ld * sizeof(int32_t)));
+  std::vector<BigSlice> slices;
+  INK_TRY(plan_big_rows(c, n_big, a.in_deg, slices));
+  INK_TRY(c->big_part_v.reserve((size_t)kBigSliceChunks * a.ld * sizeof(float)));
+  INK_TRY(c->big_part_i.reserve((size_t)kBigSliceChunks * a.ld * sizeof(int32_t)));
   const int32_t *list = c->big_list.as<int32_t>();
-  for (int b0 = 0; b0 < n_big; b0 += chunk) {
-    int nb = n_big - b0 < chunk ? n_big - b0 : chunk;
-    hipLaunchKernelGGL((k_big_partial<IS_MIN, LPR>), dim3(kBigParts, nb), dim3(256), 0, c->stream, a, list + b0,
-                       c->big_part_v.as<float>(), c->big_part_i.as<int32_t>());
-    hipLaunchKernelGGL((k_big_final<IS_MIN, LPR>), dim3(nb), dim3(64), 0, c->stream, a, list + b0,
-                       (const float *)c->big_part_v.as<float>(), (const int32_t *)c->big_part_i.as<int32_t>(), chg,
-                       compare);
+  const int32_t *pref = c->big_pref.as<int32_t>();
+  for (const BigSlice &sl : slices) {
+    int nch = sl.chunk1 - sl.chunk0;
+    size_t need = (size_t)nch * a.ld * 4;            // a single row may exceed the usual slice
+    INK_TRY(c->big_part_v.reserve(need));
+    INK_TRY(c->big_part_i.reserve(need));
+    hipLaunchKernelGGL((k_big_partial<IS_MIN, LPR>), dim3(nch), dim3(256), 0, c->stream, a, list, pref, sl.row0,
+                       sl.row1, sl.chunk0, c->big_part_v.as<float>(), c->big_part_i.as<int32_t>());
+    hipLaunchKernelGGL((k_big_final<IS_MIN, LPR>), dim3(sl.row1 - sl.row0), dim3(64), 0, c->stream, a, list, pref,
+                       sl.row0, sl.chunk0, (const float *)c->big_part_v.as<float>(),
+                       (const int32_t *)c->big_part_i.as<int32_t>(), chg, compare);
   }
   return hipGetLastError();
 }

@@ -5,7 +5,9 @@
 // whose source changed the difference new - old is added.  The three edge sets are disjoint, so
 // no message is counted twice.  Events of a target are consumed in their stored order and lane
 // groups are combined in a fixed pattern: results are reproducible run to run.
-#include "ctx.h"
+#include <algorithm>
+
+#include "bigrows.h"
 
 namespace ink {
 
@@ -33,7 +35,7 @@ __device__ __forceinline__ void sum_range(const int32_t *ids, int64_t j0, int64_
     int64_t jj = jb + l;
     int myid = jj < j1 ? ids[jj] : -1;
     int cnt = (int)((j1 - jb) < kWave ? (j1 - jb) : kWave);
-    constexpr int U = 4;
+    constexpr int U = INK_GATHER_U;       // neighbour rows in flight per lane group
     for (int it = 0; it < cnt; it += G * U) {
       int id[U];
       float4 row[U];
@@ -102,17 +104,18 @@ __global__ __launch_bounds__(256) void k_sum_full(AggArgs a, const int32_t *targ
 }
 
 template <int LPR>
-__global__ __launch_bounds__(256) void k_sum_big_partial(AggArgs a, const int32_t *big_list, float *part) {
+__global__ __launch_bounds__(256) void k_sum_big_partial(AggArgs a, const int32_t *big_list, const int32_t *pref,
+                                                         int row0, int row1, int chunk0, float *part) {
   __shared__ float sv[4][kWave * 4];
   const int l = lane_id(), w = threadIdx.x / kWave;
   const int q = l % LPR;
   const bool lane_on = 4 * q < a.ld;
-  int v = big_list[blockIdx.y];
-  int64_t deg = a.in_deg[v];
+  int i, v;
+  int64_t j0, j1;
+  big_chunk_of_block(pref, row0, row1, chunk0, big_list, a.in_deg, i, v, j0, j1);
   int64_t off = a.in_off[v];
-  int64_t p0 = deg * blockIdx.x / kBigParts, p1 = deg * (blockIdx.x + 1) / kBigParts;
-  int64_t len = p1 - p0;
-  int64_t w0 = p0 + len * w / 4, w1 = p0 + len * (w + 1) / 4;
+  int64_t len = j1 - j0;
+  int64_t w0 = j0 + len * w / 4, w1 = j0 + len * (w + 1) / 4;
   S4 acc;
   sum_range<LPR>(a.in_ids + off, w0, w1, a.M, a.ldm, lane_on, q, acc);
 #pragma unroll
@@ -124,7 +127,7 @@ __global__ __launch_bounds__(256) void k_sum_big_partial(AggArgs a, const int32_
 #pragma unroll
       for (int c = 0; c < 4; c++) acc.v[c] = __fadd_rn(acc.v[c], sv[ww][l * 4 + c]);
     if (lane_on && l < LPR) {
-      int64_t o = ((int64_t)blockIdx.y * kBigParts + blockIdx.x) * a.ld + 4 * q;
+      int64_t o = (int64_t)blockIdx.x * a.ld + 4 * q;
 #pragma unroll
       for (int c = 0; c < 4; c++) part[o + c] = acc.v[c];
     }
@@ -132,18 +135,20 @@ __global__ __launch_bounds__(256) void k_sum_big_partial(AggArgs a, const int32_
 }
 
 template <int LPR>
-__global__ __launch_bounds__(64) void k_sum_big_final(AggArgs a, const int32_t *big_list, const float *part,
-                                                      uint64_t *chg, int compare) {
+__global__ __launch_bounds__(64) void k_sum_big_final(AggArgs a, const int32_t *big_list, const int32_t *pref,
+                                                      int row0, int chunk0, const float *part, uint64_t *chg,
+                                                      int compare) {
   const int l = lane_id();
   const int q = l % LPR;
   const bool lane_on = 4 * q < a.ld;
-  int v = big_list[blockIdx.x];
+  int i = row0 + blockIdx.x;
+  int v = big_list[i];
   S4 acc;
 #pragma unroll
   for (int c = 0; c < 4; c++) acc.v[c] = 0.f;
   if (lane_on && l < LPR) {
-    for (int p = 0; p < kBigParts; p++) {
-      int64_t o = ((int64_t)blockIdx.x * kBigParts + p) * a.ld + 4 * q;
+    for (int p = pref[i] - chunk0; p < pref[i + 1] - chunk0; p++) {
+      int64_t o = (int64_t)p * a.ld + 4 * q;
 #pragma unroll
       for (int c = 0; c < 4; c++) acc.v[c] = __fadd_rn(acc.v[c], part[o + c]);
     }
@@ -163,10 +168,19 @@ __device__ __forceinline__ int find_in(const int32_t *F, int nF, int u) {   // p
   return -1;
 }
 
+__global__ void k_delta_rows(const float *M, int ldm, const int32_t *F, int nF, const float *f_old, float *f_delta,
+                             int ld_old) {
+  int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t i = t / ld_old;
+  int k = (int)(t % ld_old);
+  if (i < nF) f_delta[i * ld_old + k] = __fsub_rn(M[(int64_t)F[i] * ldm + k], f_old[i * ld_old + k]);
+}
+
 template <int LPR>
 __global__ __launch_bounds__(256) void k_sum_events(AggArgs a, const int32_t *targets, const int32_t *seg,
                                                     int64_t n_targets, const uint32_t *ev, const int32_t *F, int nF,
-                                                    const float *f_old, int ld_old, uint64_t *chg, Counters *cnt) {
+                                                    const float *f_old, const float *f_delta, int ld_old,
+                                                    uint64_t *chg, Counters *cnt) {
   constexpr int G = kWave / LPR;
   const int l = lane_id();
   const int q = l % LPR, g = l / LPR;
@@ -182,27 +196,42 @@ __global__ __launch_bounds__(256) void k_sum_events(AggArgs a, const int32_t *ta
     int ee = eb + l;
     uint32_t mine = ee < e1 ? ev[ee] : 0xFFFFFFFFu;
     int cntw = (e1 - eb) < kWave ? (e1 - eb) : kWave;
-    for (int it = 0; it < cntw; it += G) {
-      int k = it + g;
-      uint32_t x = __shfl(mine, k < kWave ? k : 0, kWave);
-      if (k >= cntw || !lane_on) continue;
-      uint32_t kind = x >> kEvKindShift;
-      int id = (int)(x & kEvIdMask);
-      if (kind == EV_DEL) {
-        int pos = nF > 0 ? find_in(F, nF, id) : -1;
-        float4 r = pos >= 0 ? ldf4(f_old + (int64_t)pos * ld_old + 4 * q) : ldf4(a.M + (int64_t)id * a.ldm + 4 * q);
-        acc.v[0] = __fsub_rn(acc.v[0], r.x); acc.v[1] = __fsub_rn(acc.v[1], r.y);
-        acc.v[2] = __fsub_rn(acc.v[2], r.z); acc.v[3] = __fsub_rn(acc.v[3], r.w);
-      } else if (kind == EV_ADD) {
-        float4 r = ldf4(a.M + (int64_t)id * a.ldm + 4 * q);
-        acc.v[0] = __fadd_rn(acc.v[0], r.x); acc.v[1] = __fadd_rn(acc.v[1], r.y);
-        acc.v[2] = __fadd_rn(acc.v[2], r.z); acc.v[3] = __fadd_rn(acc.v[3], r.w);
-      } else {   // EV_CHG: id is the position of the source in F
-        int u = F[id];
-        float4 n4 = ldf4(a.M + (int64_t)u * a.ldm + 4 * q);
-        float4 o4 = ldf4(f_old + (int64_t)id * ld_old + 4 * q);
-        acc.v[0] = __fadd_rn(acc.v[0], __fsub_rn(n4.x, o4.x)); acc.v[1] = __fadd_rn(acc.v[1], __fsub_rn(n4.y, o4.y));
-        acc.v[2] = __fadd_rn(acc.v[2], __fsub_rn(n4.z, o4.z)); acc.v[3] = __fadd_rn(acc.v[3], __fsub_rn(n4.w, o4.w));
+    constexpr int U = 4;       // events in flight per lane group
+    for (int it = 0; it < cntw; it += G * U) {
+      const float *p[U];
+      bool neg[U];
+      float4 r[U];
+#pragma unroll
+      for (int u = 0; u < U; u++) {
+        int k = it + u * G + g;
+        uint32_t x = __shfl(mine, k < kWave ? k : 0, kWave);
+        p[u] = nullptr;
+        neg[u] = false;
+        if (k < cntw && lane_on) {
+          uint32_t kind = x >> kEvKindShift;
+          int id = (int)(x & kEvIdMask);
+          if (kind == EV_CHG) {          // id = position of the source in F: add (new - old)
+            p[u] = f_delta + (int64_t)id * ld_old + 4 * q;
+          } else if (kind == EV_ADD) {
+            p[u] = a.M + (int64_t)id * a.ldm + 4 * q;
+          } else {                        // removed edge: subtract what the source contributed before
+            int pos = nF > 0 ? find_in(F, nF, id) : -1;
+            p[u] = pos >= 0 ? f_old + (int64_t)pos * ld_old + 4 * q : a.M + (int64_t)id * a.ldm + 4 * q;
+            neg[u] = true;
+          }
+          r[u] = ldf4(p[u]);
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < U; u++) {
+        if (!p[u]) continue;
+        if (neg[u]) {
+          acc.v[0] = __fsub_rn(acc.v[0], r[u].x); acc.v[1] = __fsub_rn(acc.v[1], r[u].y);
+          acc.v[2] = __fsub_rn(acc.v[2], r[u].z); acc.v[3] = __fsub_rn(acc.v[3], r[u].w);
+        } else {
+          acc.v[0] = __fadd_rn(acc.v[0], r[u].x); acc.v[1] = __fadd_rn(acc.v[1], r[u].y);
+          acc.v[2] = __fadd_rn(acc.v[2], r[u].z); acc.v[3] = __fadd_rn(acc.v[3], r[u].w);
+        }
       }
     }
   }
@@ -216,7 +245,7 @@ __global__ __launch_bounds__(256) void k_sum_events(AggArgs a, const int32_t *ta
     nv.v[2] = __fadd_rn(o.z, acc.v[2]); nv.v[3] = __fadd_rn(o.w, acc.v[3]);
   }
   bool ch = store_sum<LPR>(a.A, a.ld, a.d, v, lane_on, q, nv, true);
-  if (ch && l == 0) { mark_bit_s(chg, v); atomicAdd(&cnt->v[C_ACHG], 1); }
+  if (ch && l == 0) { mark_bit_s(chg, v); atomicAdd(&cnt->stripe[blockIdx.x % kStripes][ST_ACHG], 1ull); }
 }
 
 static int lanes_per_row(int ld) { return ld <= 64 ? 16 : (ld <= 128 ? 32 : 64); }
@@ -237,15 +266,17 @@ static hipError_t sum_full_t(ink_ctx *c, const AggArgs &a, const int32_t *target
   INK_TRY(read_counters(c));
   int n_big = c->h_cnt->v[C_NBIG];
   if (n_big > 0) {
-    const int chunk = 512;
-    INK_TRY(c->big_part_v.reserve((size_t)chunk * kBigParts * a.ld * sizeof(float)));
+    std::vector<BigSlice> slices;
+    INK_TRY(plan_big_rows(c, n_big, a.in_deg, slices));
     const int32_t *list = c->big_list.as<int32_t>();
-    for (int b0 = 0; b0 < n_big; b0 += chunk) {
-      int nb = n_big - b0 < chunk ? n_big - b0 : chunk;
-      hipLaunchKernelGGL((k_sum_big_partial<LPR>), dim3(kBigParts, nb), dim3(256), 0, c->stream, a, list + b0,
-                         c->big_part_v.as<float>());
-      hipLaunchKernelGGL((k_sum_big_final<LPR>), dim3(nb), dim3(64), 0, c->stream, a, list + b0,
-                         (const float *)c->big_part_v.as<float>(), chg, compare);
+    const int32_t *pref = c->big_pref.as<int32_t>();
+    for (const BigSlice &sl : slices) {
+      int nch = sl.chunk1 - sl.chunk0;
+      INK_TRY(c->big_part_v.reserve((size_t)std::max(nch, kBigSliceChunks) * a.ld * sizeof(float)));
+      hipLaunchKernelGGL((k_sum_big_partial<LPR>), dim3(nch), dim3(256), 0, c->stream, a, list, pref, sl.row0, sl.row1,
+                         sl.chunk0, c->big_part_v.as<float>());
+      hipLaunchKernelGGL((k_sum_big_final<LPR>), dim3(sl.row1 - sl.row0), dim3(64), 0, c->stream, a, list, pref,
+                         sl.row0, sl.chunk0, (const float *)c->big_part_v.as<float>(), chg, compare);
     }
     INK_TRY(hipGetLastError());
   }
@@ -255,10 +286,10 @@ static hipError_t sum_full_t(ink_ctx *c, const AggArgs &a, const int32_t *target
 template <int LPR>
 static hipError_t sum_events_t(ink_ctx *c, const AggArgs &a, const int32_t *targets, const int32_t *seg,
                                int64_t n_targets, const uint32_t *ev, const int32_t *F, int nF, const float *f_old,
-                               int ld_old, uint64_t *chg) {
+                               const float *f_delta, int ld_old, uint64_t *chg) {
   if (n_targets <= 0) return hipSuccess;
   hipLaunchKernelGGL((k_sum_events<LPR>), dim3((unsigned)((n_targets + 3) / 4)), dim3(256), 0, c->stream, a, targets,
-                     seg, n_targets, ev, F, nF, f_old, ld_old, chg, c->d_cnt);
+                     seg, n_targets, ev, F, nF, f_old, f_delta, ld_old, chg, c->d_cnt);
   return hipGetLastError();
 }
 
@@ -272,12 +303,21 @@ hipError_t agg_sum_full(ink_ctx *c, const AggArgs &a, const int32_t *targets, in
 
 hipError_t agg_sum_events(ink_ctx *c, const AggArgs &a, const int32_t *targets, const int32_t *seg,
                           int64_t n_targets, const uint32_t *ev_val, const int32_t *F, int nF, const float *f_old,
-                          int ld_old, uint64_t *chg) {
+                          const float *f_delta, int ld_old, uint64_t *chg) {
   switch (lanes_per_row(a.ld)) {
-    case 16: return sum_events_t<16>(c, a, targets, seg, n_targets, ev_val, F, nF, f_old, ld_old, chg);
-    case 32: return sum_events_t<32>(c, a, targets, seg, n_targets, ev_val, F, nF, f_old, ld_old, chg);
-    default: return sum_events_t<64>(c, a, targets, seg, n_targets, ev_val, F, nF, f_old, ld_old, chg);
+    case 16: return sum_events_t<16>(c, a, targets, seg, n_targets, ev_val, F, nF, f_old, f_delta, ld_old, chg);
+    case 32: return sum_events_t<32>(c, a, targets, seg, n_targets, ev_val, F, nF, f_old, f_delta, ld_old, chg);
+    default: return sum_events_t<64>(c, a, targets, seg, n_targets, ev_val, F, nF, f_old, f_delta, ld_old, chg);
   }
+}
+
+hipError_t agg_sum_delta_rows(ink_ctx *c, const AggArgs &a, const int32_t *F, int nF, const float *f_old,
+                              float *f_delta, int ld_old) {
+  if (nF <= 0) return hipSuccess;
+  int64_t n = (int64_t)nF * ld_old;
+  hipLaunchKernelGGL(k_delta_rows, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->stream, a.M, a.ldm, F, nF, f_old,
+                     f_delta, ld_old);
+  return hipGetLastError();
 }
 
 }  // namespace ink

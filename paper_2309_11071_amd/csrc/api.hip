@@ -429,7 +429,7 @@ extern "C" void ink_destroy(ink_ctx *c) {
                     &c->b_del_d, &c->b_ins_s, &c->b_ins_d, &c->f_list[0], &c->f_list[1], &c->f_old[0], &c->f_old[1],
                     &c->f_pref, &c->ev_key, &c->ev_val, &c->t_list, &c->t_seg, &c->c_list, &c->c_flag, &c->c_idx, &c->c_old,
                     &c->b_touch_in,
-                    &c->big_list, &c->big_part_v, &c->big_part_i, &c->stage0, &c->stage1, &c->res_ids, &c->res_emb})
+                    &c->big_list, &c->big_part_v, &c->big_part_i, &c->big_deg, &c->big_pref, &c->f_delta, &c->stage0, &c->stage1, &c->res_ids, &c->res_emb})
     b->release();
   for (auto e : c->ev_free) (void)hipEventDestroy(e);
   for (auto &p : c->ev_pending) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
@@ -578,12 +578,16 @@ static ink_status layer_aggregate(ink_ctx *c, int l, const int32_t *F, int64_t n
     Prof p(c, INK_T_AGG);
     if (c->is_select) {
       API_TRY(agg_select_events(c, a, c->t_list.as<int32_t>(), c->t_seg.as<int32_t>(), nT, c->ev_val.as<uint32_t>(), bm));
-      S.n_exposed = c->h_cnt->v[C_EXPOSED];
-      S.n_regather_nb = *(int64_t *)&c->h_cnt->v[C_REGATHER_LO];
-      S.n_alpha_changed = c->h_cnt->v[C_ACHG];
+      S.n_exposed = (int64_t)c->h_cnt->sum(ST_EXPOSED);
+      S.n_regather_nb = (int64_t)c->h_cnt->sum(ST_REGATHER);
+      S.n_alpha_changed = (int64_t)c->h_cnt->sum(ST_ACHG);
     } else {
+      if (nF > 0) {
+        API_TRY(c->f_delta.reserve((size_t)nF * ld_old * 4));
+        API_TRY(agg_sum_delta_rows(c, a, F, (int)nF, f_old, c->f_delta.as<float>(), ld_old));
+      }
       API_TRY(agg_sum_events(c, a, c->t_list.as<int32_t>(), c->t_seg.as<int32_t>(), nT, c->ev_val.as<uint32_t>(), F,
-                             (int)nF, f_old, ld_old, bm));
+                             (int)nF, f_old, c->f_delta.as<float>(), ld_old, bm));
     }
   }
   return INK_OK;
@@ -697,7 +701,7 @@ extern "C" ink_status ink_apply_updates(ink_ctx *c, const ink_edge_update *upd, 
     st = collect_rows(c, F, nF, D, nD, &nC);
     if (st != INK_OK) return st;
     S.n_transformed = nC;
-    if (!c->is_select && !S.dense) S.n_alpha_changed = c->h_cnt->v[C_ACHG];
+    if (!c->is_select && !S.dense) S.n_alpha_changed = (int64_t)c->h_cnt->sum(ST_ACHG);
     int nxt = cur ^ 1;
     int64_t nF2 = 0;
     if (nC > 0) {

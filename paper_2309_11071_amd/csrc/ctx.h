@@ -11,8 +11,13 @@
 
 namespace ink {
 
-constexpr int kBigDeg = 4096;      // rows with more in-neighbours are re-gathered cooperatively
-constexpr int kBigParts = 64;      // workgroups sharing one such row
+#ifndef INK_BIG_DEG
+#define INK_BIG_DEG 1024
+#endif
+#ifndef INK_GATHER_U
+#define INK_GATHER_U 4
+#endif
+constexpr int kBigDeg = INK_BIG_DEG;      // rows with more in-neighbours are re-gathered cooperatively (bigrows.h)
 constexpr uint32_t kEvKindShift = 30;
 constexpr uint32_t kEvIdMask = (1u << kEvKindShift) - 1;
 enum : uint32_t { EV_DEL = 0, EV_ADD = 1, EV_CHG = 2 };   // removed edge / inserted edge / changed source
@@ -41,8 +46,17 @@ struct DevLayer {
   float *W2 = nullptr; int K2 = 0, K2p = 0, N2 = 0, N2p = 0; float *b2 = nullptr;   // GIN second linear
 };
 
+constexpr int kStripes = 64;
+enum { ST_EXPOSED = 0, ST_REGATHER, ST_ACHG, ST_PAD };
 struct Counters {            // device-written, host-read through pinned memory
   int32_t v[32];
+  // statistics that many waves bump: striped by workgroup so that no single address is contended
+  unsigned long long stripe[kStripes][4];
+  unsigned long long sum(int which) const {
+    unsigned long long t = 0;
+    for (int i = 0; i < kStripes; i++) t += stripe[i][which];
+    return t;
+  }
 };
 enum { C_NF = 0, C_NEV, C_NT, C_NBIG, C_NC, C_NEXT, C_EXPOSED, C_ACHG, C_TMP0, C_TMP1, C_TMP2, C_TMP3,
        C_REGATHER_LO = 16, C_REGATHER_HI = 17 };
@@ -88,13 +102,14 @@ struct ink_ctx {
   ink::DevBuf f_list[2];             // F_l (ascending node ids), ping-pong between layers
   ink::DevBuf f_old[2];              // old message rows of F_l (sum-type aggregators)
   ink::DevBuf f_pref;                // prefix of out-degrees over F_l
+  ink::DevBuf f_delta;               // new - old message rows of F_l (sum-type aggregators)
   ink::DevBuf ev_key, ev_val;        // events
   ink::DevBuf t_list, t_seg;         // unique targets, segment offsets
   ink::DevBuf c_list, c_flag, c_idx; // rows to transform, per-row changed flag, compacted positions
   ink::DevBuf c_old;                 // previous table rows of the transformed rows (sum-type)
   ink::DevBuf b_touch_in;            // destinations touched by the current batch
   int64_t n_touched_in = 0;
-  ink::DevBuf big_list, big_part_v, big_part_i;   // cooperative re-gather
+  ink::DevBuf big_list, big_part_v, big_part_i, big_deg, big_pref;   // cooperative re-gather
   ink::DevBuf stage0, stage1;        // transform staging
   ink::DevBuf res_ids, res_emb;      // result of the last batch
 
@@ -133,7 +148,10 @@ hipError_t agg_select_events(ink_ctx *c, const AggArgs &a, const int32_t *target
 hipError_t agg_sum_full(ink_ctx *c, const AggArgs &a, const int32_t *targets, int64_t n_targets, uint64_t *chg);
 hipError_t agg_sum_events(ink_ctx *c, const AggArgs &a, const int32_t *targets, const int32_t *seg,
                           int64_t n_targets, const uint32_t *ev_val, const int32_t *F, int nF, const float *f_old,
-                          int ld_old, uint64_t *chg);
+                          const float *f_delta, int ld_old, uint64_t *chg);
+// f_delta[i] = M[F[i]] - f_old[i] (row stride ld_old): what a kept edge of changed source i adds
+hipError_t agg_sum_delta_rows(ink_ctx *c, const AggArgs &a, const int32_t *F, int nF, const float *f_old,
+                              float *f_delta, int ld_old);
 
 // ---- dense transform (xform.hip)
 struct XformArgs {

@@ -75,13 +75,13 @@ inline int nblocks(int64_t n, int per) { return (int)((n + per - 1) / per); }
 // Functor F: __device__ int operator()(int64_t i) const  -> value of item i
 // Functor W: __device__ void operator()(int64_t i, int v, int excl) const -> consume exclusive prefix
 
-template <class F>
+template <class F, int ITEMS>
 __global__ __launch_bounds__(kScanThreads) void k_tile_reduce(F f, int64_t n, int32_t *blk) {
   __shared__ int sm[kScanThreads / kWave + 1];
-  int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kScanItems;
+  int64_t base = (int64_t)blockIdx.x * (kScanThreads * ITEMS) + (int64_t)threadIdx.x * ITEMS;
   int s = 0;
 #pragma unroll
-  for (int k = 0; k < kScanItems; k++) {
+  for (int k = 0; k < ITEMS; k++) {
     int64_t i = base + k;
     if (i < n) s += f(i);
   }
@@ -107,15 +107,15 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_blk(int32_t *blk, int nb,
   if (threadIdx.x == 0 && total) *total = carry;
 }
 
-template <class F, class W>
+template <class F, class W, int ITEMS>
 __global__ __launch_bounds__(kScanThreads) void k_tile_apply(F f, W w, int64_t n, const int32_t *blk,
                                                               int32_t *total_single) {
   __shared__ int sm[kScanThreads / kWave + 1];
-  int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kScanItems;
-  int v[kScanItems];
+  int64_t base = (int64_t)blockIdx.x * (kScanThreads * ITEMS) + (int64_t)threadIdx.x * ITEMS;
+  int v[ITEMS];
   int s = 0;
 #pragma unroll
-  for (int k = 0; k < kScanItems; k++) {
+  for (int k = 0; k < ITEMS; k++) {
     int64_t i = base + k;
     v[k] = i < n ? f(i) : 0;
     s += v[k];
@@ -124,7 +124,7 @@ __global__ __launch_bounds__(kScanThreads) void k_tile_apply(F f, W w, int64_t n
   int ex = block_excl_scan(s, sm, &tot);
   ex += blk ? blk[blockIdx.x] : 0;
 #pragma unroll
-  for (int k = 0; k < kScanItems; k++) {
+  for (int k = 0; k < ITEMS; k++) {
     int64_t i = base + k;
     if (i < n) w(i, v[k], ex);
     ex += v[k];
@@ -132,23 +132,23 @@ __global__ __launch_bounds__(kScanThreads) void k_tile_apply(F f, W w, int64_t n
   if (total_single && threadIdx.x == 0) *total_single = tot;   // only used when gridDim.x == 1
 }
 
-template <class F, class W>
+template <class F, class W, int ITEMS = kScanItems>
 inline hipError_t tile_scan(PrimWorkspace &ws, F f, W w, int64_t n, int32_t *total, hipStream_t s) {
   if (n <= 0) {
     if (total) INK_TRY(hipMemsetAsync(total, 0, sizeof(int32_t), s));
     return hipSuccess;
   }
-  int nb = nblocks(n, kScanTile);
+  int nb = nblocks(n, kScanThreads * ITEMS);
   if (nb == 1) {
-    hipLaunchKernelGGL((k_tile_apply<F, W>), dim3(1), dim3(kScanThreads), 0, s, f, w, n,
+    hipLaunchKernelGGL((k_tile_apply<F, W, ITEMS>), dim3(1), dim3(kScanThreads), 0, s, f, w, n,
                        (const int32_t *)nullptr, total);
     return hipGetLastError();
   }
   INK_TRY(ws.blk.reserve((size_t)nb * sizeof(int32_t)));
   int32_t *blk = ws.blk.as<int32_t>();
-  hipLaunchKernelGGL((k_tile_reduce<F>), dim3(nb), dim3(kScanThreads), 0, s, f, n, blk);
+  hipLaunchKernelGGL((k_tile_reduce<F, ITEMS>), dim3(nb), dim3(kScanThreads), 0, s, f, n, blk);
   hipLaunchKernelGGL((k_scan_blk<0>), dim3(1), dim3(kScanThreads), 0, s, blk, nb, total);
-  hipLaunchKernelGGL((k_tile_apply<F, W>), dim3(nb), dim3(kScanThreads), 0, s, f, w, n,
+  hipLaunchKernelGGL((k_tile_apply<F, W, ITEMS>), dim3(nb), dim3(kScanThreads), 0, s, f, w, n,
                      (const int32_t *)blk, (int32_t *)nullptr);
   return hipGetLastError();
 }

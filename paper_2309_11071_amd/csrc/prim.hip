@@ -44,7 +44,7 @@ struct StoreBits {
 hipError_t bitmap_to_list(PrimWorkspace &ws, uint64_t *words, int64_t n_bits, int32_t *out_idx,
                           int32_t *count, int clear, hipStream_t s) {
   int64_t nw = (n_bits + 63) / 64;
-  return tile_scan(ws, LoadPop{words}, StoreBits{words, out_idx, clear}, nw, count, s);
+  return tile_scan<LoadPop, StoreBits, 1>(ws, LoadPop{words}, StoreBits{words, out_idx, clear}, nw, count, s);
 }
 
 // ---------------------------------------------------------------- segment heads of sorted keys

@@ -43,6 +43,73 @@ __device__ __forceinline__ float fetch_x(const XformArgs &x, int64_t row, int k)
   }
 }
 
+__device__ __forceinline__ void ld4v(const float *p, float out[4]) {
+  float4 v = *reinterpret_cast<const float4 *>(p);
+  out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
+}
+
+// four consecutive inputs k .. k + 3 (k a multiple of 4) of one row; 16-byte loads when the group
+// lies inside one table row, element-wise otherwise.  Results are identical to fetch_x.
+template <int MODE>
+__device__ __forceinline__ void fetch_x4(const XformArgs &x, int64_t row, int k, float out[4]) {
+  if (MODE == 0) {
+    if ((x.d_in & 3) == 0 && k + 3 < 2 * x.d_in) {
+      if (k < x.d_in) {
+        ld4v(x.A + row * x.lda + k, out);
+        if (x.mean_deg) {
+          int dg = x.mean_deg[row];
+          float dv = (float)(dg > 0 ? dg : 1);
+#pragma unroll
+          for (int i = 0; i < 4; i++) out[i] = __fdiv_rn(out[i], dv);
+        }
+      } else {
+        ld4v(x.Hp + row * x.ldh + (k - x.d_in), out);
+      }
+      return;
+    }
+  } else if (MODE == 1) {
+    if (k + 3 < x.lda && k + 3 < x.ldh) {
+      float a[4], h[4];
+      ld4v(x.A + row * x.lda + k, a);
+      ld4v(x.Hp + row * x.ldh + k, h);
+      float dv = 1.f;
+      if (x.mean_deg) { int dg = x.mean_deg[row]; dv = (float)(dg > 0 ? dg : 1); }
+#pragma unroll
+      for (int i = 0; i < 4; i++) {
+        float av = x.mean_deg ? __fdiv_rn(a[i], dv) : a[i];
+        out[i] = k + i < x.d_in ? __fadd_rn(__fmul_rn(1.0f + x.eps, h[i]), av) : 0.f;
+      }
+      return;
+    }
+  } else if (MODE == 3) {
+    if (k + 3 < x.lda && k + 3 < x.ldh) {
+      float a[4], h[4];
+      ld4v(x.A + row * x.lda + k, a);
+      ld4v(x.Hp + row * x.ldh + k, h);
+      float cv = x.cnorm[row];
+#pragma unroll
+      for (int i = 0; i < 4; i++) {
+        float v = __fmul_rn(cv, __fadd_rn(a[i], h[i]));
+        if (x.in_bias && k + i < x.d_in) v = __fadd_rn(v, x.in_bias[k + i]);
+        if (x.in_relu) v = v > 0.f ? v : 0.f;
+        out[i] = k + i < x.d_in ? v : 0.f;
+      }
+      if (x.h_store && k + 3 < x.ld_hs)
+        *reinterpret_cast<float4 *>(x.h_store + row * x.ld_hs + k) = make_float4(out[0], out[1], out[2], out[3]);
+      return;
+    }
+  } else {
+    if ((x.ldh & 3) == 0 && k + 3 < x.ldh) {
+      ld4v(x.Hp + row * x.ldh + k, out);
+#pragma unroll
+      for (int i = 0; i < 4; i++) out[i] = k + i < x.d_in ? out[i] : 0.f;
+      return;
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 4; i++) out[i] = fetch_x<MODE>(x, row, k + i);
+}
+
 template <int MODE, int TPW>
 __global__ __launch_bounds__(256) void k_xform(XformArgs x) {
   extern __shared__ float smem[];
@@ -74,9 +141,15 @@ __global__ __launch_bounds__(256) void k_xform(XformArgs x) {
     {   // stage X: thread -> row t / 4, 8 consecutive k
       int r = t >> 2, ks = (t & 3) * 8;
       int64_t row = srow[r];
+      float xv[8];
 #pragma unroll
-      for (int kk = 0; kk < 8; kk++)
-        Xs[r * (KT + 1) + ks + kk] = row >= 0 ? fetch_x<MODE>(x, row, k0 + ks + kk) : 0.f;
+      for (int kk = 0; kk < 8; kk++) xv[kk] = 0.f;
+      if (row >= 0) {
+        fetch_x4<MODE>(x, row, k0 + ks, xv);
+        fetch_x4<MODE>(x, row, k0 + ks + 4, xv + 4);
+      }
+#pragma unroll
+      for (int kk = 0; kk < 8; kk++) Xs[r * (KT + 1) + ks + kk] = xv[kk];
     }
     {   // stage W rows k0 .. k0 + KT (padded matrix: always in bounds)
       const float4 *src = reinterpret_cast<const float4 *>(x.W + (int64_t)k0 * x.Np);

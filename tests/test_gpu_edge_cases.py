@@ -122,7 +122,7 @@ def test_random_sequences(kind, agg, dims):
 
 
 def test_hub_rows_use_the_cooperative_recompute():
-    """A node with > 4096 in-neighbours loses the holders of several dimensions."""
+    """A node with thousands of in-neighbours (cooperative chunked path) loses the holders of several dimensions."""
     n_leaves, d = 6000, 8
     g, X = star(n_leaves, d, seed=9, extra=8)
     h = Harness(graph=g, X=X, model=tiny_model("sage", "max", (d, 8, 4)))
