@@ -80,6 +80,8 @@ def main():
     ap.add_argument("--scale-div", type=int, default=1)
     ap.add_argument("--batch", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep", action="store_true",
+                    help="after the timed steps, run 20 seeded batches at each batch size 1..100k and report p50/p99")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy so that a profiler's byte counters can be scaled")
     args = ap.parse_args()
@@ -99,7 +101,7 @@ def main():
         cfg = replace(cfg, batch=args.batch)
     t0 = time.perf_counter()
     src, dst = synth.make_graph(cfg)
-    rp, col = synth.in_csr_from_edges(cfg.n_nodes, src, dst)
+    rp, col = synth.in_csr_from_edges(cfg.n_nodes, src, dst, assume_sorted=True)
     X = synth.make_features(cfg)
     model = synth.make_model(cfg)
     t_gen = time.perf_counter() - t0
@@ -185,6 +187,27 @@ def main():
         "full_inference_s": t_full,
         "full_inference_agg_ms": full_stats["ms"]["agg"],
     }
+    if args.sweep:
+        sweep = []
+        ink.set_profiling(False)
+        for B in (1, 10, 100, 1000, 10000, 100000):
+            bl = []
+            for _ in range(20):
+                u = make_updates(*sampler.next_batch(B))
+                bl.append(torch.from_numpy(u.view(np.uint8).copy()).cuda())
+            torch.cuda.synchronize()
+            lt = []
+            for t in bl:
+                t1 = time.perf_counter()
+                ink.apply_updates_device(t.data_ptr(), B)
+                lt.append((time.perf_counter() - t1) * 1e3)
+            lt = np.array(lt)
+            sweep.append({"batch": B, "p50_ms": float(np.percentile(lt, 50)), "p99_ms": float(np.percentile(lt, 99)),
+                          "edges_per_s": float(B * len(lt) / (lt.sum() / 1e3))})
+            print("[bench] sweep B=%d p50 %.3f ms p99 %.3f ms" % (B, sweep[-1]["p50_ms"], sweep[-1]["p99_ms"]),
+                  file=sys.stderr, flush=True)
+        out["sweep"] = sweep
+        ink.set_profiling(True)
     if not args.no_cpu_baseline:
         cs, cd = sampler.current_edges()
         keys = synth.edge_keys(cs, cd)

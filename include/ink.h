@@ -194,6 +194,10 @@ ink_status ink_get_layer(ink_ctx *ctx, int32_t layer, int32_t which, int64_t row
  * col is not NULL, col [n_edges] (each row ascending).  Pass col = NULL first to size it. */
 ink_status ink_get_graph(ink_ctx *ctx, int64_t *rowptr, int32_t *col);
 
+/* Turns the per-kernel-class HIP-event timing of ink_stats on or off (it costs a few event
+ * records per layer, which matters for the latency of tiny batches). */
+ink_status ink_set_profiling(ink_ctx *ctx, int32_t on);
+
 /* Copies min(bytes, sizeof(ink_stats)) bytes of the last call's statistics. */
 ink_status ink_get_stats(ink_ctx *ctx, void *stats_out, size_t bytes);
 

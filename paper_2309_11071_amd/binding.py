@@ -96,6 +96,8 @@ def load_library():
     lib.ink_get_layer.restype = C.c_int
     lib.ink_get_graph.argtypes = [vp, vp, vp]
     lib.ink_get_graph.restype = C.c_int
+    lib.ink_set_profiling.argtypes = [vp, C.c_int32]
+    lib.ink_set_profiling.restype = C.c_int
     lib.ink_get_stats.argtypes = [vp, vp, C.c_size_t]
     lib.ink_get_stats.restype = C.c_int
     lib.ink_last_error.argtypes = [vp]
@@ -207,6 +209,9 @@ class Ink:
         col = np.empty(int(rowptr[-1]), np.int32)
         self._check(self._lib.ink_get_graph(self._h, rowptr.ctypes.data, col.ctypes.data if col.size else None))
         return rowptr, col
+
+    def set_profiling(self, on):
+        self._check(self._lib.ink_set_profiling(self._h, int(bool(on))))
 
     def stats(self):
         s = _Stats()

@@ -131,7 +131,7 @@ __global__ __launch_bounds__(256) void k_agg_full(AggArgs a, const int32_t *targ
   if (wid >= n_targets) return;
   int v = targets ? targets[wid] : (int)wid;
   int deg = a.in_deg[v];
-  if (deg > kBigDeg) {
+  if (deg > a.big_deg) {
     if (l == 0) big_list[atomicAdd(n_big, 1)] = v;
     return;
   }
@@ -153,65 +153,74 @@ __global__ __launch_bounds__(256) void k_agg_full(AggArgs a, const int32_t *targ
   if (ch && chg && l == 0) mark_bit(chg, v);
 }
 
-// cooperative path for rows with more than kBigDeg in-neighbours: one workgroup per chunk of
+// cooperative path for rows with more than kBigDeg in-neighbours: a workgroup per chunk of
 // kBigChunk neighbours (its 4 waves take a quarter each), partial rows to scratch
 template <bool IS_MIN, int LPR>
-__global__ __launch_bounds__(256) void k_big_partial(AggArgs a, const int32_t *big_list, const int32_t *pref, int row0,
-                                                     int row1, int chunk0, float *part_v, int32_t *part_i) {
-  __shared__ float sv[4][kWave * 4];
-  __shared__ int si[4][kWave * 4];
-  const int l = lane_id(), w = threadIdx.x / kWave;
+__global__ __launch_bounds__(1024) void k_big_partial(AggArgs a, const int32_t *big_list, const int32_t *n_big_p,
+                                                      const int32_t *pref, const int32_t *total_p, float *part_v,
+                                                      int32_t *part_i) {
+  __shared__ float sv[kBigMaxWaves][kWave * 4];
+  __shared__ int si[kBigMaxWaves][kWave * 4];
+  const int l = lane_id(), w = threadIdx.x / kWave, nw = blockDim.x / kWave;
   const int q = l % LPR;
   const bool lane_on = 4 * q < a.ld;
-  int i, v;
-  int64_t j0, j1;
-  big_chunk_of_block(pref, row0, row1, chunk0, big_list, a.in_deg, i, v, j0, j1);
-  int64_t off = a.in_off[v];
-  int64_t len = j1 - j0;
-  int64_t w0 = j0 + len * w / 4, w1 = j0 + len * (w + 1) / 4;
-  F4 bv; I4 bi;
-  gather_range<IS_MIN, LPR>(a.in_ids + off, w0, w1, a.M, a.ldm, lane_on, q, bv, bi);
+  const int total = *total_p, n_big = *n_big_p;
+  for (int cg = blockIdx.x; cg < total; cg += gridDim.x) {
+    int i, v;
+    int64_t j0, j1;
+    big_chunk(pref, n_big, cg, big_list, a.in_deg, i, v, j0, j1);
+    int64_t off = a.in_off[v];
+    int64_t len = j1 - j0;
+    int64_t w0 = j0 + len * w / nw, w1 = j0 + len * (w + 1) / nw;
+    F4 bv; I4 bi;
+    gather_range<IS_MIN, LPR>(a.in_ids + off, w0, w1, a.M, a.ldm, lane_on, q, bv, bi);
 #pragma unroll
-  for (int c = 0; c < 4; c++) { sv[w][l * 4 + c] = bv.v[c]; si[w][l * 4 + c] = bi.v[c]; }
-  __syncthreads();
-  if (w == 0) {
+    for (int c = 0; c < 4; c++) { sv[w][l * 4 + c] = bv.v[c]; si[w][l * 4 + c] = bi.v[c]; }
+    __syncthreads();
+    if (w == 0) {
+      for (int ww = 1; ww < nw; ww++)
 #pragma unroll
-    for (int ww = 1; ww < 4; ww++)
+        for (int c = 0; c < 4; c++) take<IS_MIN>(sv[ww][l * 4 + c], si[ww][l * 4 + c], bv.v[c], bi.v[c]);
+      if (lane_on && l < LPR) {
+        int64_t o = (int64_t)cg * a.ld + 4 * q;
 #pragma unroll
-      for (int c = 0; c < 4; c++) take<IS_MIN>(sv[ww][l * 4 + c], si[ww][l * 4 + c], bv.v[c], bi.v[c]);
-    if (lane_on && l < LPR) {
-      int64_t o = (int64_t)blockIdx.x * a.ld + 4 * q;
-#pragma unroll
-      for (int c = 0; c < 4; c++) { part_v[o + c] = bv.v[c]; part_i[o + c] = bi.v[c]; }
+        for (int c = 0; c < 4; c++) { part_v[o + c] = bv.v[c]; part_i[o + c] = bi.v[c]; }
+      }
     }
+    __syncthreads();
   }
 }
 
 // one wave per big row: reduce its partial rows and store
 template <bool IS_MIN, int LPR>
-__global__ __launch_bounds__(64) void k_big_final(AggArgs a, const int32_t *big_list, const int32_t *pref, int row0,
-                                                  int chunk0, const float *part_v, const int32_t *part_i,
-                                                  uint64_t *chg, int compare) {
+__global__ __launch_bounds__(64) void k_big_final(AggArgs a, const int32_t *big_list, const int32_t *n_big_p,
+                                                  const int32_t *pref, const float *part_v, const int32_t *part_i,
+                                                  uint64_t *chg, int compare, Counters *cnt) {
   const int l = lane_id();
   const int q = l % LPR;
   const bool lane_on = 4 * q < a.ld;
-  int i = row0 + blockIdx.x;
-  int v = big_list[i];
-  F4 bv; I4 bi;
+  const int n_big = *n_big_p;
+  for (int i = blockIdx.x; i < n_big; i += gridDim.x) {
+    int v = big_list[i];
+    F4 bv; I4 bi;
 #pragma unroll
-  for (int c = 0; c < 4; c++) { bv.v[c] = worst<IS_MIN>(); bi.v[c] = 0x7fffffff; }
-  if (lane_on && l < LPR) {
-    for (int p = pref[i] - chunk0; p < pref[i + 1] - chunk0; p++) {
-      int64_t o = (int64_t)p * a.ld + 4 * q;
+    for (int c = 0; c < 4; c++) { bv.v[c] = worst<IS_MIN>(); bi.v[c] = 0x7fffffff; }
+    if (lane_on && l < LPR) {
+      for (int p = pref[i]; p < pref[i + 1]; p++) {
+        int64_t o = (int64_t)p * a.ld + 4 * q;
 #pragma unroll
-      for (int c = 0; c < 4; c++) take<IS_MIN>(part_v[o + c], part_i[o + c], bv.v[c], bi.v[c]);
+        for (int c = 0; c < 4; c++) take<IS_MIN>(part_v[o + c], part_i[o + c], bv.v[c], bi.v[c]);
+      }
+    }
+    finish_empty(bv, bi);
+    RowOut o{a.A, a.ARG, a.ld, a.d};
+    F4 dum; I4 dumi;
+    bool ch = store_row<LPR>(o, v, lane_on, q, bv, bi, false, dum, dumi);
+    if (compare && ch && chg && l == 0) {
+      mark_bit(chg, v);
+      atomicAdd(&cnt->stripe[blockIdx.x % kStripes][ST_ACHG], 1ull);
     }
   }
-  finish_empty(bv, bi);
-  RowOut o{a.A, a.ARG, a.ld, a.d};
-  F4 dum; I4 dumi;
-  bool ch = store_row<LPR>(o, v, lane_on, q, bv, bi, false, dum, dumi);
-  if (compare && ch && chg && l == 0) mark_bit(chg, v);
 }
 
 // ------------------------------------------------------------------ event-driven incremental update
@@ -224,14 +233,14 @@ __global__ __launch_bounds__(64) void k_big_final(AggArgs a, const int32_t *big_
 // the row is exposed and recomputed from its whole current neighbourhood.
 template <bool IS_MIN, int LPR>
 __global__ __launch_bounds__(256) void k_agg_events(AggArgs a, const int32_t *targets, const int32_t *seg,
-                                                    int64_t n_targets, const uint32_t *ev, uint64_t *chg,
+                                                    const int32_t *n_targets_p, const uint32_t *ev, uint64_t *chg,
                                                     int32_t *big_list, Counters *cnt) {
   constexpr int G = kWave / LPR;
   const int l = lane_id();
   const int q = l % LPR, g = l / LPR;
   const bool lane_on = 4 * q < a.ld;
   int64_t wid = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kWave;
-  if (wid >= n_targets) return;
+  if (wid >= *n_targets_p) return;
   int v = targets[wid];
   int e0 = seg[wid], e1 = seg[wid + 1];
   F4 ov; I4 oi;
@@ -314,7 +323,7 @@ __global__ __launch_bounds__(256) void k_agg_events(AggArgs a, const int32_t *ta
       atomicAdd(&cnt->stripe[blockIdx.x % kStripes][ST_EXPOSED], 1ull);
       atomicAdd(&cnt->stripe[blockIdx.x % kStripes][ST_REGATHER], (unsigned long long)deg);
     }
-    if (deg > kBigDeg) {
+    if (deg > a.big_deg) {
       if (l == 0) big_list[atomicAdd(&cnt->v[C_NBIG], 1)] = v;
       return;
     }
@@ -330,59 +339,49 @@ __global__ __launch_bounds__(256) void k_agg_events(AggArgs a, const int32_t *ta
 static int lanes_per_row(int ld) { return ld <= 64 ? 16 : (ld <= 128 ? 32 : 64); }
 
 template <bool IS_MIN, int LPR>
-static hipError_t run_big(ink_ctx *c, const AggArgs &a, int n_big, uint64_t *chg, int compare) {
-  std::vector<BigSlice> slices;
-  INK_TRY(plan_big_rows(c, n_big, a.in_deg, slices));
-  INK_TRY(c->big_part_v.reserve((size_t)kBigSliceChunks * a.ld * sizeof(float)));
-  INK_TRY(c->big_part_i.reserve((size_t)kBigSliceChunks * a.ld * sizeof(int32_t)));
+static hipError_t run_big(ink_ctx *c, const AggArgs &a, uint64_t *chg, int compare, int block_threads,
+                          int64_t n_rows_max) {
   const int32_t *list = c->big_list.as<int32_t>();
-  const int32_t *pref = c->big_pref.as<int32_t>();
-  for (const BigSlice &sl : slices) {
-    int nch = sl.chunk1 - sl.chunk0;
-    size_t need = (size_t)nch * a.ld * 4;            // a single row may exceed the usual slice
-    INK_TRY(c->big_part_v.reserve(need));
-    INK_TRY(c->big_part_i.reserve(need));
-    hipLaunchKernelGGL((k_big_partial<IS_MIN, LPR>), dim3(nch), dim3(256), 0, c->stream, a, list, pref, sl.row0,
-                       sl.row1, sl.chunk0, c->big_part_v.as<float>(), c->big_part_i.as<int32_t>());
-    hipLaunchKernelGGL((k_big_final<IS_MIN, LPR>), dim3(sl.row1 - sl.row0), dim3(64), 0, c->stream, a, list, pref,
-                       sl.row0, sl.chunk0, (const float *)c->big_part_v.as<float>(),
-                       (const int32_t *)c->big_part_i.as<int32_t>(), chg, compare);
-  }
+  int32_t *pref = c->big_pref.as<int32_t>();
+  int32_t *n_big = &c->d_cnt->v[C_NBIG], *total = &c->d_cnt->v[C_NCHUNK];
+  INK_TRY(plan_big_rows(c, n_rows_max, a.in_deg));
+  hipLaunchKernelGGL((k_big_partial<IS_MIN, LPR>), dim3(big_partial_grid(c, a.big_grid, block_threads)), dim3(block_threads), 0, c->stream, a, list,
+                     (const int32_t *)n_big, (const int32_t *)pref, (const int32_t *)total, c->big_part_v.as<float>(),
+                     c->big_part_i.as<int32_t>());
+  hipLaunchKernelGGL((k_big_final<IS_MIN, LPR>), dim3(kBigGrid), dim3(64), 0, c->stream, a, list,
+                     (const int32_t *)n_big, (const int32_t *)pref, (const float *)c->big_part_v.as<float>(),
+                     (const int32_t *)c->big_part_i.as<int32_t>(), chg, compare, c->d_cnt);
   return hipGetLastError();
 }
 
-static hipError_t read_counters(ink_ctx *c) {
-  INK_TRY(hipMemcpyAsync(c->h_cnt, c->d_cnt, sizeof(Counters), hipMemcpyDeviceToHost, c->stream));
-  return hipStreamSynchronize(c->stream);
-}
-
 template <bool IS_MIN, int LPR>
-static hipError_t full_t(ink_ctx *c, const AggArgs &a, const int32_t *targets, int64_t n_targets, uint64_t *chg) {
+static hipError_t full_t(ink_ctx *c, const AggArgs &a_in, const int32_t *targets, int64_t n_targets, uint64_t *chg) {
   if (n_targets <= 0) return hipSuccess;
+  AggArgs a = a_in;
+  a.big_deg = big_threshold(n_targets, LPR);
   int compare = chg != nullptr;
+  INK_TRY(ensure_big_buffers(c, a.ld, true));
   INK_TRY(hipMemsetAsync(&c->d_cnt->v[C_NBIG], 0, sizeof(int32_t), c->stream));
   int64_t blocks = (n_targets + 3) / 4;
   hipLaunchKernelGGL((k_agg_full<IS_MIN, LPR>), dim3((unsigned)blocks), dim3(256), 0, c->stream, a, targets, n_targets,
                      chg, c->big_list.as<int32_t>(), &c->d_cnt->v[C_NBIG], compare);
   INK_TRY(hipGetLastError());
-  INK_TRY(read_counters(c));
-  int n_big = c->h_cnt->v[C_NBIG];
-  if (n_big > 0) INK_TRY((run_big<IS_MIN, LPR>(c, a, n_big, chg, compare)));
-  return hipSuccess;
+  return run_big<IS_MIN, LPR>(c, a, chg, compare, big_block_threads(n_targets), n_targets);
 }
 
+// n_targets may be an upper bound: the kernel stops at the device-side count n_targets_dev
 template <bool IS_MIN, int LPR>
-static hipError_t events_t(ink_ctx *c, const AggArgs &a, const int32_t *targets, const int32_t *seg,
-                           int64_t n_targets, const uint32_t *ev, uint64_t *chg) {
+static hipError_t events_t(ink_ctx *c, const AggArgs &a_in, const int32_t *targets, const int32_t *seg,
+                           int64_t n_targets, const int32_t *n_targets_dev, const uint32_t *ev, uint64_t *chg) {
   if (n_targets <= 0) return hipSuccess;
+  AggArgs a = a_in;
+  a.big_deg = big_threshold(n_targets, LPR);
+  INK_TRY(ensure_big_buffers(c, a.ld, true));
   int64_t blocks = (n_targets + 3) / 4;
   hipLaunchKernelGGL((k_agg_events<IS_MIN, LPR>), dim3((unsigned)blocks), dim3(256), 0, c->stream, a, targets, seg,
-                     n_targets, ev, chg, c->big_list.as<int32_t>(), c->d_cnt);
+                     n_targets_dev, ev, chg, c->big_list.as<int32_t>(), c->d_cnt);
   INK_TRY(hipGetLastError());
-  INK_TRY(read_counters(c));
-  int n_big = c->h_cnt->v[C_NBIG];
-  if (n_big > 0) INK_TRY((run_big<IS_MIN, LPR>(c, a, n_big, chg, 1)));
-  return hipSuccess;
+  return run_big<IS_MIN, LPR>(c, a, chg, 1, big_block_threads(n_targets), n_targets);
 }
 
 #define DISPATCH(fn, ...)                                                         \
@@ -404,8 +403,8 @@ hipError_t agg_select_full(ink_ctx *c, const AggArgs &a, const int32_t *targets,
 }
 
 hipError_t agg_select_events(ink_ctx *c, const AggArgs &a, const int32_t *targets, const int32_t *seg,
-                             int64_t n_targets, const uint32_t *ev_val, uint64_t *chg) {
-  DISPATCH(events_t, c, a, targets, seg, n_targets, ev_val, chg);
+                             int64_t n_targets, const int32_t *n_targets_dev, const uint32_t *ev_val, uint64_t *chg) {
+  DISPATCH(events_t, c, a, targets, seg, n_targets, n_targets_dev, ev_val, chg);
 }
 
 }  // namespace ink

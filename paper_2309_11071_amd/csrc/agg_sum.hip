@@ -93,7 +93,7 @@ __global__ __launch_bounds__(256) void k_sum_full(AggArgs a, const int32_t *targ
   if (wid >= n_targets) return;
   int v = targets ? targets[wid] : (int)wid;
   int deg = a.in_deg[v];
-  if (deg > kBigDeg) {
+  if (deg > a.big_deg) {
     if (l == 0) big_list[atomicAdd(n_big, 1)] = v;
     return;
   }
@@ -104,57 +104,62 @@ __global__ __launch_bounds__(256) void k_sum_full(AggArgs a, const int32_t *targ
 }
 
 template <int LPR>
-__global__ __launch_bounds__(256) void k_sum_big_partial(AggArgs a, const int32_t *big_list, const int32_t *pref,
-                                                         int row0, int row1, int chunk0, float *part) {
-  __shared__ float sv[4][kWave * 4];
-  const int l = lane_id(), w = threadIdx.x / kWave;
+__global__ __launch_bounds__(1024) void k_sum_big_partial(AggArgs a, const int32_t *big_list, const int32_t *n_big_p,
+                                                          const int32_t *pref, const int32_t *total_p, float *part) {
+  __shared__ float sv[kBigMaxWaves][kWave * 4];
+  const int l = lane_id(), w = threadIdx.x / kWave, nw = blockDim.x / kWave;
   const int q = l % LPR;
   const bool lane_on = 4 * q < a.ld;
-  int i, v;
-  int64_t j0, j1;
-  big_chunk_of_block(pref, row0, row1, chunk0, big_list, a.in_deg, i, v, j0, j1);
-  int64_t off = a.in_off[v];
-  int64_t len = j1 - j0;
-  int64_t w0 = j0 + len * w / 4, w1 = j0 + len * (w + 1) / 4;
-  S4 acc;
-  sum_range<LPR>(a.in_ids + off, w0, w1, a.M, a.ldm, lane_on, q, acc);
+  const int total = *total_p, n_big = *n_big_p;
+  for (int cg = blockIdx.x; cg < total; cg += gridDim.x) {
+    int i, v;
+    int64_t j0, j1;
+    big_chunk(pref, n_big, cg, big_list, a.in_deg, i, v, j0, j1);
+    int64_t off = a.in_off[v];
+    int64_t len = j1 - j0;
+    int64_t w0 = j0 + len * w / nw, w1 = j0 + len * (w + 1) / nw;
+    S4 acc;
+    sum_range<LPR>(a.in_ids + off, w0, w1, a.M, a.ldm, lane_on, q, acc);
 #pragma unroll
-  for (int c = 0; c < 4; c++) sv[w][l * 4 + c] = acc.v[c];
-  __syncthreads();
-  if (w == 0) {
+    for (int c = 0; c < 4; c++) sv[w][l * 4 + c] = acc.v[c];
+    __syncthreads();
+    if (w == 0) {
+      for (int ww = 1; ww < nw; ww++)
 #pragma unroll
-    for (int ww = 1; ww < 4; ww++)
+        for (int c = 0; c < 4; c++) acc.v[c] = __fadd_rn(acc.v[c], sv[ww][l * 4 + c]);
+      if (lane_on && l < LPR) {
+        int64_t o = (int64_t)cg * a.ld + 4 * q;
 #pragma unroll
-      for (int c = 0; c < 4; c++) acc.v[c] = __fadd_rn(acc.v[c], sv[ww][l * 4 + c]);
-    if (lane_on && l < LPR) {
-      int64_t o = (int64_t)blockIdx.x * a.ld + 4 * q;
-#pragma unroll
-      for (int c = 0; c < 4; c++) part[o + c] = acc.v[c];
+        for (int c = 0; c < 4; c++) part[o + c] = acc.v[c];
+      }
     }
+    __syncthreads();
   }
 }
 
 template <int LPR>
-__global__ __launch_bounds__(64) void k_sum_big_final(AggArgs a, const int32_t *big_list, const int32_t *pref,
-                                                      int row0, int chunk0, const float *part, uint64_t *chg,
+__global__ __launch_bounds__(64) void k_sum_big_final(AggArgs a, const int32_t *big_list, const int32_t *n_big_p,
+                                                      const int32_t *pref, const float *part, uint64_t *chg,
                                                       int compare) {
   const int l = lane_id();
   const int q = l % LPR;
   const bool lane_on = 4 * q < a.ld;
-  int i = row0 + blockIdx.x;
-  int v = big_list[i];
-  S4 acc;
+  const int n_big = *n_big_p;
+  for (int i = blockIdx.x; i < n_big; i += gridDim.x) {
+    int v = big_list[i];
+    S4 acc;
 #pragma unroll
-  for (int c = 0; c < 4; c++) acc.v[c] = 0.f;
-  if (lane_on && l < LPR) {
-    for (int p = pref[i] - chunk0; p < pref[i + 1] - chunk0; p++) {
-      int64_t o = (int64_t)p * a.ld + 4 * q;
+    for (int c = 0; c < 4; c++) acc.v[c] = 0.f;
+    if (lane_on && l < LPR) {
+      for (int p = pref[i]; p < pref[i + 1]; p++) {
+        int64_t o = (int64_t)p * a.ld + 4 * q;
 #pragma unroll
-      for (int c = 0; c < 4; c++) acc.v[c] = __fadd_rn(acc.v[c], part[o + c]);
+        for (int c = 0; c < 4; c++) acc.v[c] = __fadd_rn(acc.v[c], part[o + c]);
+      }
     }
+    bool ch = store_sum<LPR>(a.A, a.ld, a.d, v, lane_on, q, acc, compare != 0);
+    if (ch && chg && l == 0) mark_bit_s(chg, v);
   }
-  bool ch = store_sum<LPR>(a.A, a.ld, a.d, v, lane_on, q, acc, compare != 0);
-  if (ch && chg && l == 0) mark_bit_s(chg, v);
 }
 
 __device__ __forceinline__ int find_in(const int32_t *F, int nF, int u) {   // position of u in ascending F, or -1
@@ -178,15 +183,15 @@ __global__ void k_delta_rows(const float *M, int ldm, const int32_t *F, int nF, 
 
 template <int LPR>
 __global__ __launch_bounds__(256) void k_sum_events(AggArgs a, const int32_t *targets, const int32_t *seg,
-                                                    int64_t n_targets, const uint32_t *ev, const int32_t *F, int nF,
-                                                    const float *f_old, const float *f_delta, int ld_old,
+                                                    const int32_t *n_targets_p, const uint32_t *ev, const int32_t *F,
+                                                    int nF, const float *f_old, const float *f_delta, int ld_old,
                                                     uint64_t *chg, Counters *cnt) {
   constexpr int G = kWave / LPR;
   const int l = lane_id();
   const int q = l % LPR, g = l / LPR;
   const bool lane_on = 4 * q < a.ld;
   int64_t wid = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kWave;
-  if (wid >= n_targets) return;
+  if (wid >= *n_targets_p) return;
   int v = targets[wid];
   int e0 = seg[wid], e1 = seg[wid + 1];
   S4 acc;
@@ -250,46 +255,37 @@ __global__ __launch_bounds__(256) void k_sum_events(AggArgs a, const int32_t *ta
 
 static int lanes_per_row(int ld) { return ld <= 64 ? 16 : (ld <= 128 ? 32 : 64); }
 
-static hipError_t read_counters(ink_ctx *c) {
-  INK_TRY(hipMemcpyAsync(c->h_cnt, c->d_cnt, sizeof(Counters), hipMemcpyDeviceToHost, c->stream));
-  return hipStreamSynchronize(c->stream);
-}
-
 template <int LPR>
-static hipError_t sum_full_t(ink_ctx *c, const AggArgs &a, const int32_t *targets, int64_t n_targets, uint64_t *chg) {
+static hipError_t sum_full_t(ink_ctx *c, const AggArgs &a_in, const int32_t *targets, int64_t n_targets,
+                             uint64_t *chg) {
   if (n_targets <= 0) return hipSuccess;
+  AggArgs a = a_in;
+  a.big_deg = big_threshold(n_targets, LPR);
   int compare = chg != nullptr;
+  INK_TRY(ensure_big_buffers(c, a.ld, false));
   INK_TRY(hipMemsetAsync(&c->d_cnt->v[C_NBIG], 0, sizeof(int32_t), c->stream));
   hipLaunchKernelGGL((k_sum_full<LPR>), dim3((unsigned)((n_targets + 3) / 4)), dim3(256), 0, c->stream, a, targets,
                      n_targets, chg, c->big_list.as<int32_t>(), &c->d_cnt->v[C_NBIG], compare);
   INK_TRY(hipGetLastError());
-  INK_TRY(read_counters(c));
-  int n_big = c->h_cnt->v[C_NBIG];
-  if (n_big > 0) {
-    std::vector<BigSlice> slices;
-    INK_TRY(plan_big_rows(c, n_big, a.in_deg, slices));
-    const int32_t *list = c->big_list.as<int32_t>();
-    const int32_t *pref = c->big_pref.as<int32_t>();
-    for (const BigSlice &sl : slices) {
-      int nch = sl.chunk1 - sl.chunk0;
-      INK_TRY(c->big_part_v.reserve((size_t)std::max(nch, kBigSliceChunks) * a.ld * sizeof(float)));
-      hipLaunchKernelGGL((k_sum_big_partial<LPR>), dim3(nch), dim3(256), 0, c->stream, a, list, pref, sl.row0, sl.row1,
-                         sl.chunk0, c->big_part_v.as<float>());
-      hipLaunchKernelGGL((k_sum_big_final<LPR>), dim3(sl.row1 - sl.row0), dim3(64), 0, c->stream, a, list, pref,
-                         sl.row0, sl.chunk0, (const float *)c->big_part_v.as<float>(), chg, compare);
-    }
-    INK_TRY(hipGetLastError());
-  }
-  return hipSuccess;
+  const int32_t *list = c->big_list.as<int32_t>();
+  int32_t *pref = c->big_pref.as<int32_t>();
+  int32_t *n_big = &c->d_cnt->v[C_NBIG], *total = &c->d_cnt->v[C_NCHUNK];
+  INK_TRY(plan_big_rows(c, n_targets, a.in_deg));
+  hipLaunchKernelGGL((k_sum_big_partial<LPR>), dim3(big_partial_grid(c, a.big_grid, big_block_threads(n_targets))),
+                     dim3(big_block_threads(n_targets)), 0, c->stream, a, list, (const int32_t *)n_big,
+                     (const int32_t *)pref, (const int32_t *)total, c->big_part_v.as<float>());
+  hipLaunchKernelGGL((k_sum_big_final<LPR>), dim3(kBigGrid), dim3(64), 0, c->stream, a, list, (const int32_t *)n_big,
+                     (const int32_t *)pref, (const float *)c->big_part_v.as<float>(), chg, compare);
+  return hipGetLastError();
 }
 
 template <int LPR>
 static hipError_t sum_events_t(ink_ctx *c, const AggArgs &a, const int32_t *targets, const int32_t *seg,
-                               int64_t n_targets, const uint32_t *ev, const int32_t *F, int nF, const float *f_old,
-                               const float *f_delta, int ld_old, uint64_t *chg) {
+                               int64_t n_targets, const int32_t *n_targets_dev, const uint32_t *ev, const int32_t *F,
+                               int nF, const float *f_old, const float *f_delta, int ld_old, uint64_t *chg) {
   if (n_targets <= 0) return hipSuccess;
   hipLaunchKernelGGL((k_sum_events<LPR>), dim3((unsigned)((n_targets + 3) / 4)), dim3(256), 0, c->stream, a, targets,
-                     seg, n_targets, ev, F, nF, f_old, f_delta, ld_old, chg, c->d_cnt);
+                     seg, n_targets_dev, ev, F, nF, f_old, f_delta, ld_old, chg, c->d_cnt);
   return hipGetLastError();
 }
 
@@ -302,12 +298,12 @@ hipError_t agg_sum_full(ink_ctx *c, const AggArgs &a, const int32_t *targets, in
 }
 
 hipError_t agg_sum_events(ink_ctx *c, const AggArgs &a, const int32_t *targets, const int32_t *seg,
-                          int64_t n_targets, const uint32_t *ev_val, const int32_t *F, int nF, const float *f_old,
-                          const float *f_delta, int ld_old, uint64_t *chg) {
+                          int64_t n_targets, const int32_t *n_targets_dev, const uint32_t *ev_val, const int32_t *F,
+                          int nF, const float *f_old, const float *f_delta, int ld_old, uint64_t *chg) {
   switch (lanes_per_row(a.ld)) {
-    case 16: return sum_events_t<16>(c, a, targets, seg, n_targets, ev_val, F, nF, f_old, f_delta, ld_old, chg);
-    case 32: return sum_events_t<32>(c, a, targets, seg, n_targets, ev_val, F, nF, f_old, f_delta, ld_old, chg);
-    default: return sum_events_t<64>(c, a, targets, seg, n_targets, ev_val, F, nF, f_old, f_delta, ld_old, chg);
+    case 16: return sum_events_t<16>(c, a, targets, seg, n_targets, n_targets_dev, ev_val, F, nF, f_old, f_delta, ld_old, chg);
+    case 32: return sum_events_t<32>(c, a, targets, seg, n_targets, n_targets_dev, ev_val, F, nF, f_old, f_delta, ld_old, chg);
+    default: return sum_events_t<64>(c, a, targets, seg, n_targets, n_targets_dev, ev_val, F, nF, f_old, f_delta, ld_old, chg);
   }
 }
 

@@ -41,7 +41,12 @@ __global__ void k_seed_events(const int32_t *del_s, const int32_t *del_d, const 
 // by this batch
 struct KeptOutDeg {
   const int32_t *F; const int32_t *deg; const int32_t *new_out;
-  __device__ int operator()(int64_t i) const { int u = F[i]; return deg[u] - new_out[u]; }
+  const int32_t *n_dev;      // optional device-side length of F (the launch may cover more)
+  __device__ int operator()(int64_t i) const {
+    if (n_dev && i >= *n_dev) return 0;
+    int u = F[i];
+    return deg[u] - new_out[u];
+  }
 };
 struct StorePref { int32_t *p; __device__ void operator()(int64_t i, int, int ex) const { p[i] = ex; } };
 
@@ -67,8 +72,9 @@ __global__ void k_mark_nodes(const int32_t *list, int n, uint64_t *bm) {
   if (i < n) { int v = list[i]; atomicOr((unsigned long long *)&bm[v >> 6], 1ull << (v & 63)); }
 }
 
-__global__ void k_gather_i32(const int32_t *table, const int32_t *idx, int n, int32_t *out) {
+__global__ void k_gather_i32(const int32_t *table, const int32_t *idx, int n, const int32_t *n_dev, int32_t *out) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (n_dev) n = *n_dev;
   if (i < n) out[i] = table[idx[i]];
 }
 
@@ -93,11 +99,13 @@ __global__ void k_unpack_rows(const float *in, int d, int ld, int64_t n, float *
   if (r < n) table[r * ld + k] = in[r * d + k];
 }
 
-__global__ void k_gather_rows_ld(const float *in, int ld, const int32_t *idx, int64_t n, float *out) {
+__global__ void k_gather_rows_ld(const float *in, int ld, const int32_t *idx, int64_t n, const int32_t *n_dev,
+                                 float *out) {
   // out[i][:] = in[idx[i]][:], both with row stride ld
   int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   int64_t r = t / ld;
   int k = (int)(t % ld);
+  if (n_dev) n = *n_dev;
   if (r < n) out[r * ld + k] = in[(int64_t)idx[r] * ld + k];
 }
 
@@ -226,6 +234,8 @@ static AggArgs agg_args(ink_ctx *c, int l) {       // layer l in 1..k
   a.M = M.f(); a.ldm = M.ld;
   a.A = c->A[l].f(); a.ARG = c->is_select ? c->ARG[l].i() : nullptr; a.ld = c->A[l].ld; a.d = c->A[l].d;
   a.is_min = c->is_min;
+  a.big_deg = kBigDeg;
+  a.big_grid = 2 * c->big_hint[l] + 1024;
   return a;
 }
 
@@ -440,7 +450,9 @@ extern "C" void ink_destroy(ink_ctx *c) {
 extern "C" const char *ink_last_error(const ink_ctx *c) { return c ? c->err.c_str() : g_create_err.c_str(); }
 
 // ------------------------------------------------------------------------------------ full inference
-static hipError_t agg_full_any(ink_ctx *c, const AggArgs &a, uint64_t *chg) {
+static hipError_t agg_full_any(ink_ctx *c, const AggArgs &a_in, uint64_t *chg) {
+  AggArgs a = a_in;      // every node is recomputed: the chunk count is bounded by the edge count
+  a.big_grid = c->n_edges_now / kBigChunk + std::min<int64_t>(c->n, c->n_edges_now / kBigDeg) + 1;
   return c->is_select ? agg_select_full(c, a, nullptr, c->n, chg) : agg_sum_full(c, a, nullptr, c->n, chg);
 }
 
@@ -513,38 +525,29 @@ extern "C" ink_status ink_full_infer(ink_ctx *c) {
 
 // ------------------------------------------------------------------------------------ updates
 // Events + grouping + aggregation of layer l.  F (nF ids, ascending) are the sources whose message
-// changed, f_old their previous message rows (sum-type only).  Marks targets whose aggregate
-// changed in c->bm_a.
-static ink_status layer_aggregate(ink_ctx *c, int l, const int32_t *F, int64_t nF, const float *f_old, int ld_old,
-                                  int64_t n_ins, int64_t n_del) {
+// changed and n_chg the events they propagate (their kept out-edges, prefix already in f_pref);
+// f_old holds their previous message rows (sum-type only).  Marks targets whose aggregate changed
+// in c->bm_a.  Counters are read back by the caller's next synchronisation.
+constexpr int64_t kNoSyncEvents = 1 << 18;     // below this the target count stays on the device
+
+static ink_status layer_aggregate(ink_ctx *c, int l, const int32_t *F, int64_t nF, int64_t n_chg, const float *f_old,
+                                  int ld_old, int64_t n_ins, int64_t n_del) {
   hipStream_t s = c->stream;
   ink_layer_stats &S = c->stats.layer[l - 1];
   Counters *dc = c->d_cnt;
   AggArgs a = agg_args(c, l);
   const int64_t n_seed = n_ins + n_del;
   S.n_sources = nF;
-  int64_t n_chg = 0;
-  {
-    Prof p(c, INK_T_EVENTS);
-    API_TRY(hipMemsetAsync(dc, 0, sizeof(Counters), s));
-    if (nF > 0) {
-      API_TRY(c->f_pref.reserve((size_t)(nF + 1) * 4));
-      API_TRY(tile_scan(c->ws, KeptOutDeg{F, c->gout.deg, c->new_out}, StorePref{c->f_pref.as<int32_t>()}, nF,
-                        &dc->v[C_NEV], s));
-      API_TRY(read_counters(c));
-      n_chg = (uint32_t)c->h_cnt->v[C_NEV];
-    }
-  }
   int64_t nE = n_seed + n_chg;
   S.n_events = nE;
   uint64_t *bm = c->bm_a;
+  API_TRY(hipMemsetAsync(dc, 0, sizeof(Counters), s));
   bool dense = nE > 0 && (double)nE > c->dense_frac * (double)std::max<int64_t>(c->n_edges_now, 1);
   S.dense = dense;
   if (dense) {
     // so many events that re-aggregating every node costs less than grouping them (Sec. 5.1)
     Prof p(c, INK_T_AGG);
     API_TRY(agg_full_any(c, a, bm));
-    S.n_targets = c->n; S.n_exposed = c->n; S.n_regather_nb = c->n_edges_now;
     return INK_OK;
   }
   if (nE == 0) return INK_OK;
@@ -563,6 +566,7 @@ static ink_status layer_aggregate(ink_ctx *c, int l, const int32_t *F, int64_t n
                          (const int32_t *)c->gout.ids, key + n_seed, val + n_seed, c->is_select ? 0 : 1);
     API_TRY(hipGetLastError());
   }
+  int64_t nT = std::min<int64_t>(nE, c->n);       // upper bound unless read back below
   {
     Prof p(c, INK_T_GROUP);
     API_TRY(radix_sort_pairs(c->ws, c->ev_key.as<uint32_t>(), c->ev_val.as<uint32_t>(), nE, c->id_bits, s));
@@ -570,27 +574,40 @@ static ink_status layer_aggregate(ink_ctx *c, int l, const int32_t *F, int64_t n
     API_TRY(c->t_seg.reserve((size_t)(nE + 2) * 4));
     API_TRY(segment_heads(c->ws, c->ev_key.as<uint32_t>(), nE, c->t_list.as<int32_t>(), c->t_seg.as<int32_t>(),
                           &dc->v[C_NT], s));
-    API_TRY(read_counters(c));
+    if (nE > kNoSyncEvents) {
+      API_TRY(read_counters(c));
+      nT = c->h_cnt->v[C_NT];
+    }
   }
-  int64_t nT = c->h_cnt->v[C_NT];
-  S.n_targets = nT;
   {
     Prof p(c, INK_T_AGG);
     if (c->is_select) {
-      API_TRY(agg_select_events(c, a, c->t_list.as<int32_t>(), c->t_seg.as<int32_t>(), nT, c->ev_val.as<uint32_t>(), bm));
-      S.n_exposed = (int64_t)c->h_cnt->sum(ST_EXPOSED);
-      S.n_regather_nb = (int64_t)c->h_cnt->sum(ST_REGATHER);
-      S.n_alpha_changed = (int64_t)c->h_cnt->sum(ST_ACHG);
+      API_TRY(agg_select_events(c, a, c->t_list.as<int32_t>(), c->t_seg.as<int32_t>(), nT, &dc->v[C_NT],
+                                c->ev_val.as<uint32_t>(), bm));
     } else {
       if (nF > 0) {
         API_TRY(c->f_delta.reserve((size_t)nF * ld_old * 4));
         API_TRY(agg_sum_delta_rows(c, a, F, (int)nF, f_old, c->f_delta.as<float>(), ld_old));
       }
-      API_TRY(agg_sum_events(c, a, c->t_list.as<int32_t>(), c->t_seg.as<int32_t>(), nT, c->ev_val.as<uint32_t>(), F,
-                             (int)nF, f_old, c->f_delta.as<float>(), ld_old, bm));
+      API_TRY(agg_sum_events(c, a, c->t_list.as<int32_t>(), c->t_seg.as<int32_t>(), nT, &dc->v[C_NT],
+                             c->ev_val.as<uint32_t>(), F, (int)nF, f_old, c->f_delta.as<float>(), ld_old, bm));
     }
   }
   return INK_OK;
+}
+
+// fills the layer's statistics from the counters of the last read-back
+static void layer_stats_from_counters(ink_ctx *c, int l) {
+  ink_layer_stats &S = c->stats.layer[l - 1];
+  if (S.dense) {
+    S.n_targets = c->n; S.n_exposed = c->n; S.n_regather_nb = c->n_edges_now;
+    return;
+  }
+  c->big_hint[l] = c->h_cnt->v[C_NCHUNK];
+  S.n_targets = c->h_cnt->v[C_NT];
+  S.n_exposed = (int64_t)c->h_cnt->sum(ST_EXPOSED);
+  S.n_regather_nb = (int64_t)c->h_cnt->sum(ST_REGATHER);
+  S.n_alpha_changed = (int64_t)c->h_cnt->sum(ST_ACHG);
 }
 
 // bitmap (plus extra id lists) -> ascending row list in c->c_list; returns the count
@@ -608,25 +625,34 @@ static ink_status collect_rows(ink_ctx *c, const int32_t *extra0, int64_t n0, co
 }
 
 // rows of c_list whose flag is set -> f_list[nxt] (ids) and, for sum-type, f_old[nxt] (old rows
-// taken from c_old with row stride ld)
-static ink_status emit_changed(ink_ctx *c, int64_t nC, int nxt, bool keep_old, int ld, int64_t *nF2) {
+// taken from c_old with row stride ld).  With want_events the events those rows will propagate in
+// the next layer are counted in the same round trip (prefix of kept out-degrees in f_pref).
+static ink_status emit_changed(ink_ctx *c, int64_t nC, int nxt, bool keep_old, int ld, bool want_events,
+                               int64_t *nF2, int64_t *n_chg) {
   hipStream_t s = c->stream;
   Prof p(c, INK_T_COMPACT);
-  API_TRY(compact_flags_u8(c->ws, c->c_flag.as<uint8_t>(), nC, c->c_idx.as<int32_t>(), &c->d_cnt->v[C_NEXT], s));
-  API_TRY(read_counters(c));
-  int64_t n = c->h_cnt->v[C_NEXT];
-  *nF2 = n;
-  if (n > 0) {
-    API_TRY(c->f_list[nxt].reserve((size_t)n * 4));
-    hipLaunchKernelGGL(k_gather_i32, grid1(n), dim3(256), 0, s, (const int32_t *)c->c_list.as<int32_t>(),
-                       (const int32_t *)c->c_idx.as<int32_t>(), (int)n, c->f_list[nxt].as<int32_t>());
-    if (keep_old) {
-      API_TRY(c->f_old[nxt].reserve((size_t)n * ld * 4));
-      hipLaunchKernelGGL(k_gather_rows_ld, grid1(n * ld), dim3(256), 0, s, (const float *)c->c_old.as<float>(), ld,
-                         (const int32_t *)c->c_idx.as<int32_t>(), n, c->f_old[nxt].as<float>());
-    }
-    API_TRY(hipGetLastError());
+  Counters *dc = c->d_cnt;
+  *nF2 = 0; *n_chg = 0;
+  API_TRY(compact_flags_u8(c->ws, c->c_flag.as<uint8_t>(), nC, c->c_idx.as<int32_t>(), &dc->v[C_NEXT], s));
+  API_TRY(c->f_list[nxt].reserve((size_t)nC * 4));
+  hipLaunchKernelGGL(k_gather_i32, grid1(nC), dim3(256), 0, s, (const int32_t *)c->c_list.as<int32_t>(),
+                     (const int32_t *)c->c_idx.as<int32_t>(), 0, (const int32_t *)&dc->v[C_NEXT],
+                     c->f_list[nxt].as<int32_t>());
+  if (keep_old) {
+    API_TRY(c->f_old[nxt].reserve((size_t)nC * ld * 4));
+    hipLaunchKernelGGL(k_gather_rows_ld, grid1(nC * ld), dim3(256), 0, s, (const float *)c->c_old.as<float>(), ld,
+                       (const int32_t *)c->c_idx.as<int32_t>(), (int64_t)0, (const int32_t *)&dc->v[C_NEXT],
+                       c->f_old[nxt].as<float>());
   }
+  if (want_events) {
+    API_TRY(c->f_pref.reserve((size_t)(nC + 1) * 4));
+    API_TRY(tile_scan(c->ws, KeptOutDeg{c->f_list[nxt].as<int32_t>(), c->gout.deg, c->new_out, &dc->v[C_NEXT]},
+                      StorePref{c->f_pref.as<int32_t>()}, nC, &dc->v[C_NEV], s));
+  }
+  API_TRY(hipGetLastError());
+  API_TRY(read_counters(c));
+  *nF2 = c->h_cnt->v[C_NEXT];
+  if (want_events) *n_chg = (uint32_t)c->h_cnt->v[C_NEV];
   return INK_OK;
 }
 
@@ -672,6 +698,7 @@ extern "C" ink_status ink_apply_updates(ink_ctx *c, const ink_edge_update *upd, 
   const int64_t nD = (n_seed > 0 && (gcn || c->agg == INK_AGG_MEAN)) ? c->n_touched_in : 0;
 
   int64_t nF = 0;            // |F_l|: sources whose message m_l changed
+  int64_t n_chg = 0;         // events F_l propagates along its kept out-edges
   int cur = 0;               // f_list[cur] / f_old[cur] describe F_l
   if (gcn && nD > 0) {
     // layer-1 messages are c_u * (x_u W_1): a degree change rescales the row
@@ -687,23 +714,24 @@ extern "C" ink_status ink_apply_updates(ink_ctx *c, const ink_edge_update *upd, 
                        (const float *)c->XW[1].f(), c->Msc[1].f(), ld, c->Msc[1].d, c->c_old.as<float>(),
                        c->c_flag.as<uint8_t>());
     API_TRY(hipGetLastError());
-    ink_status st = emit_changed(c, nD, cur, true, ld, &nF);
+    ink_status st = emit_changed(c, nD, cur, true, ld, true, &nF, &n_chg);
     if (st != INK_OK) return st;
   }
   for (int l = 1; l <= c->n_layers && (n_seed > 0 || nF > 0); l++) {
     ink_layer_stats &S = c->stats.layer[l - 1];
     const int32_t *F = c->f_list[cur].as<int32_t>();
     int ld_msg = msg_table(c, l).ld;
-    ink_status st = layer_aggregate(c, l, F, nF, keep_old ? c->f_old[cur].as<float>() : nullptr, ld_msg, n_ins, n_del);
+    ink_status st = layer_aggregate(c, l, F, nF, n_chg, keep_old ? c->f_old[cur].as<float>() : nullptr, ld_msg,
+                                    n_ins, n_del);
     if (st != INK_OK) return st;
     // rows to transform: aggregate changed; own message changed (self term); degree changed
     int64_t nC = 0;
     st = collect_rows(c, F, nF, D, nD, &nC);
     if (st != INK_OK) return st;
     S.n_transformed = nC;
-    if (!c->is_select && !S.dense) S.n_alpha_changed = (int64_t)c->h_cnt->sum(ST_ACHG);
+    layer_stats_from_counters(c, l);
     int nxt = cur ^ 1;
-    int64_t nF2 = 0;
+    int64_t nF2 = 0, n_chg2 = 0;
     if (nC > 0) {
       const bool last = l == c->n_layers;
       int ld_next = gcn ? (last ? c->H[l].ld : c->Msc[l + 1].ld) : c->H[l].ld;
@@ -722,11 +750,12 @@ extern "C" ink_status ink_apply_updates(ink_ctx *c, const ink_edge_update *upd, 
           else API_TRY(gcn_final(c, rows, nC, c->c_flag.as<uint8_t>()));
         }
       }
-      st = emit_changed(c, nC, nxt, want_old, ld_next, &nF2);
+      st = emit_changed(c, nC, nxt, want_old, ld_next, !last, &nF2, &n_chg2);
       if (st != INK_OK) return st;
     }
     S.n_changed = nF2;
     nF = nF2;
+    n_chg = n_chg2;
     cur = nxt;
     if (l == c->n_layers) {
       out->n_changed = nF;
@@ -778,6 +807,12 @@ extern "C" ink_status ink_get_graph(ink_ctx *c, int64_t *rowptr, int32_t *col) {
   if (!c || !rowptr) return INK_E_ARG;
   API_TRY(hipStreamSynchronize(c->stream));
   API_TRY(graph_export(c, rowptr, col));
+  return INK_OK;
+}
+
+extern "C" ink_status ink_set_profiling(ink_ctx *c, int32_t on) {
+  if (!c) return INK_E_ARG;
+  c->profile = on != 0;
   return INK_OK;
 }
 

@@ -1,57 +1,77 @@
 // Work list for rows with more than kBigDeg in-neighbours: each such row is cut into chunks of
 // kBigChunk neighbours, one workgroup per chunk, then one wave per row combines its chunks in
-// order.  The chunk prefix is built on the host from the degrees of the listed rows.
+// order.  The plan (chunk prefix over the listed rows) is built on the device from the device-side
+// row count, and the chunk / row kernels run a fixed grid that strides over it, so no host
+// round trip is needed; with no long rows they return at once.
 #pragma once
-#include <vector>
-
 #include "ctx.h"
 
 namespace ink {
 
-#ifndef INK_BIG_CHUNK
-#define INK_BIG_CHUNK 1024
-#endif
-constexpr int kBigChunk = INK_BIG_CHUNK;
-constexpr int kBigSliceChunks = 65536;     // chunks whose partial rows are kept at one time
+constexpr int kBigGrid = 4096;             // workgroups of the per-row combine kernel
 
-template <int DUMMY>
-__global__ void k_big_degs(const int32_t *list, int n, const int32_t *deg, int32_t *out) {
-  int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) out[i] = deg[list[i]];
+// upper bound of the chunks any launch can need: every long row has at most deg / chunk + 1
+inline int64_t big_chunk_capacity(const ink_ctx *c) {
+  int64_t e = c->n_edges_now > c->n_edges ? c->n_edges_now : c->n_edges;
+  return e / kBigChunk + e / kBigDeg + 32768;
 }
 
-struct BigSlice { int row0, row1, chunk0, chunk1; };
+// one workgroup per expected chunk (the hardware balances them); never fewer than fill the chip
+inline unsigned big_partial_grid(const ink_ctx *c, int64_t want, int block_threads) {
+  int64_t lo = block_threads >= 1024 ? 512 : 2048, hi = big_chunk_capacity(c);
+  if (want < lo) want = lo;
+  if (want > hi) want = hi;
+  return (unsigned)want;
+}
 
-// fills c->big_pref (device, n_big + 1 ints) and returns the slices to run
-inline hipError_t plan_big_rows(ink_ctx *c, int n_big, const int32_t *in_deg, std::vector<BigSlice> &slices) {
-  INK_TRY(c->big_deg.reserve((size_t)n_big * 4));
-  INK_TRY(c->big_pref.reserve((size_t)(n_big + 1) * 4));
-  hipLaunchKernelGGL((k_big_degs<0>), dim3((n_big + 255) / 256), dim3(256), 0, c->stream,
-                     (const int32_t *)c->big_list.as<int32_t>(), n_big, in_deg, c->big_deg.as<int32_t>());
-  std::vector<int32_t> deg((size_t)n_big), pref((size_t)n_big + 1);
-  INK_TRY(hipMemcpyAsync(deg.data(), c->big_deg.p, (size_t)n_big * 4, hipMemcpyDeviceToHost, c->stream));
-  INK_TRY(hipStreamSynchronize(c->stream));
-  pref[0] = 0;
-  for (int i = 0; i < n_big; i++) pref[i + 1] = pref[i] + (deg[i] + kBigChunk - 1) / kBigChunk;
-  INK_TRY(hipMemcpyAsync(c->big_pref.p, pref.data(), pref.size() * 4, hipMemcpyHostToDevice, c->stream));
-  INK_TRY(hipStreamSynchronize(c->stream));       // pref is a stack-local vector
-  slices.clear();
-  int r0 = 0;
-  while (r0 < n_big) {
-    int r1 = r0 + 1;
-    while (r1 < n_big && pref[r1 + 1] - pref[r0] <= kBigSliceChunks) r1++;
-    slices.push_back({r0, r1, pref[r0], pref[r1]});
-    r0 = r1;
-  }
+// buffers of the long-row path; call before the kernel that fills the list (growing drops contents)
+inline hipError_t ensure_big_buffers(ink_ctx *c, int ld, bool with_ids) {
+  int64_t e = c->n_edges_now > c->n_edges ? c->n_edges_now : c->n_edges;
+  int64_t rows = e / kBigDeg + 32768;
+  INK_TRY(c->big_list.reserve((size_t)rows * 4));
+  INK_TRY(c->big_pref.reserve((size_t)(c->big_list.cap / 4 + 1) * 4));
+  int64_t cap = big_chunk_capacity(c);
+  INK_TRY(c->big_part_v.reserve((size_t)cap * ld * sizeof(float)));
+  if (with_ids) INK_TRY(c->big_part_i.reserve((size_t)cap * ld * sizeof(int32_t)));
   return hipSuccess;
 }
 
-// (row index in the list, first neighbour, end neighbour) of the chunk handled by this workgroup
-__device__ __forceinline__ void big_chunk_of_block(const int32_t *pref, int row0, int row1, int chunk0,
-                                                   const int32_t *list, const int32_t *in_deg, int &i, int &v,
-                                                   int64_t &j0, int64_t &j1) {
-  int cg = chunk0 + blockIdx.x;
-  int lo = row0, hi = row1 - 1;
+// Few targets (small batches): latency matters more than throughput, so rows are handed to the
+// cooperative path much earlier and each chunk is shared by 16 waves instead of 4.
+constexpr int kLatencyTargets = 8192;
+inline bool latency_mode(int64_t n_targets) { return n_targets <= kLatencyTargets; }
+inline int big_threshold(int64_t n_targets, int lanes_per_row) {
+  return latency_mode(n_targets) ? 32 * (kWave / lanes_per_row) : kBigDeg;
+}
+inline int big_block_threads(int64_t n_targets) { return latency_mode(n_targets) ? 1024 : 256; }
+constexpr int kBigMaxWaves = 16;
+
+// plan: pref[i] = chunks of the listed rows before i (i <= n_big), *total = all chunks
+struct BigChunkCount {
+  const int32_t *list; const int32_t *n_big; const int32_t *deg;
+  __device__ int operator()(int64_t i) const { return i < *n_big ? (deg[list[i]] + kBigChunk - 1) / kBigChunk : 0; }
+};
+struct BigPrefStore {
+  int32_t *pref; const int32_t *n_big;
+  __device__ void operator()(int64_t i, int v, int ex) const {
+    int n = *n_big;
+    if (i < n) pref[i] = ex;
+    if (i == n - 1) pref[n] = ex + v;
+  }
+};
+// n_rows_max bounds the device-side row count
+inline hipError_t plan_big_rows(ink_ctx *c, int64_t n_rows_max, const int32_t *in_deg) {
+  int64_t cap = (int64_t)(c->big_list.cap / 4);
+  if (n_rows_max > cap) n_rows_max = cap;
+  const int32_t *n_big = &c->d_cnt->v[C_NBIG];
+  return tile_scan(c->ws, BigChunkCount{c->big_list.as<int32_t>(), n_big, in_deg},
+                   BigPrefStore{c->big_pref.as<int32_t>(), n_big}, n_rows_max, &c->d_cnt->v[C_NCHUNK], c->stream);
+}
+
+// row (index in the list), node id and neighbour range of global chunk cg
+__device__ __forceinline__ void big_chunk(const int32_t *pref, int n_big, int cg, const int32_t *list,
+                                          const int32_t *in_deg, int &i, int &v, int64_t &j0, int64_t &j1) {
+  int lo = 0, hi = n_big - 1;
   while (lo < hi) {
     int mid = (lo + hi + 1) >> 1;
     if (pref[mid] <= cg) lo = mid; else hi = mid - 1;

@@ -17,6 +17,10 @@ namespace ink {
 #ifndef INK_GATHER_U
 #define INK_GATHER_U 4
 #endif
+#ifndef INK_BIG_CHUNK
+#define INK_BIG_CHUNK 1024
+#endif
+constexpr int kBigChunk = INK_BIG_CHUNK;  // neighbours per chunk of such a row
 constexpr int kBigDeg = INK_BIG_DEG;      // rows with more in-neighbours are re-gathered cooperatively (bigrows.h)
 constexpr uint32_t kEvKindShift = 30;
 constexpr uint32_t kEvIdMask = (1u << kEvKindShift) - 1;
@@ -58,8 +62,8 @@ struct Counters {            // device-written, host-read through pinned memory
     return t;
   }
 };
-enum { C_NF = 0, C_NEV, C_NT, C_NBIG, C_NC, C_NEXT, C_EXPOSED, C_ACHG, C_TMP0, C_TMP1, C_TMP2, C_TMP3,
-       C_REGATHER_LO = 16, C_REGATHER_HI = 17 };
+enum { C_NF = 0, C_NEV, C_NT, C_NBIG, C_NC, C_NEXT, C_NCHUNK, C_SPARE, C_TMP0, C_TMP1, C_TMP2, C_TMP3,
+       C_REGATHER_LO = 16, C_REGATHER_HI = 17, C_BIGWORK = 18 };
 
 }  // namespace ink
 
@@ -67,6 +71,7 @@ struct ink_ctx {
   int n = 0;
   int64_t n_edges = 0, n_edges_now = 0;
   int64_t pool_reserve = 0;
+  int64_t big_hint[INK_MAX_LAYERS + 1] = {0};   // chunks of long rows seen by the last update at each layer
   double dense_frac = 0.75;          // events / edges above which a layer re-aggregates every node
   int id_bits = 1;
   int kind = 0, agg = 0, n_layers = 0, mem = 0, profile = 0;
@@ -88,6 +93,7 @@ struct ink_ctx {
   ink::PrimWorkspace ws;
   ink::Counters *d_cnt = nullptr;    // device counters
   ink::Counters *h_cnt = nullptr;    // pinned host mirror
+  unsigned long long h_top = 0;      // staging for the device copy of a pool top
   uint64_t *bm_a = nullptr;          // node bitmaps (n bits each)
   uint64_t *bm_b = nullptr;
 
@@ -136,19 +142,22 @@ struct AggArgs {
   float *A; int32_t *ARG; int ld;   // aggregated table and argument table (row stride ld)
   int d;
   bool is_min;
+  int big_deg;                      // rows with more in-neighbours go to the chunked cooperative path
+  int64_t big_grid;                 // workgroups to launch for the chunk kernel (it strides if there are more chunks)
 };
 // full re-aggregation of every node (targets == nullptr) or of a target list; flags rows whose
 // alpha changed in bitmap `chg` (may be null); big rows go through the cooperative path
 hipError_t agg_select_full(ink_ctx *c, const AggArgs &a, const int32_t *targets, int64_t n_targets,
                            uint64_t *chg);
+// n_targets may be an upper bound of the device-side count *n_targets_dev
 hipError_t agg_select_events(ink_ctx *c, const AggArgs &a, const int32_t *targets, const int32_t *seg,
-                             int64_t n_targets, const uint32_t *ev_val, uint64_t *chg);
+                             int64_t n_targets, const int32_t *n_targets_dev, const uint32_t *ev_val, uint64_t *chg);
 // sum-type aggregators (agg_sum.hip): A holds the plain sum of message rows.  F (ascending ids)
 // and f_old (their previous message rows, row stride ld_old) describe the changed sources.
 hipError_t agg_sum_full(ink_ctx *c, const AggArgs &a, const int32_t *targets, int64_t n_targets, uint64_t *chg);
 hipError_t agg_sum_events(ink_ctx *c, const AggArgs &a, const int32_t *targets, const int32_t *seg,
-                          int64_t n_targets, const uint32_t *ev_val, const int32_t *F, int nF, const float *f_old,
-                          const float *f_delta, int ld_old, uint64_t *chg);
+                          int64_t n_targets, const int32_t *n_targets_dev, const uint32_t *ev_val, const int32_t *F,
+                          int nF, const float *f_old, const float *f_delta, int ld_old, uint64_t *chg);
 // f_delta[i] = M[F[i]] - f_old[i] (row stride ld_old): what a kept edge of changed source i adds
 hipError_t agg_sum_delta_rows(ink_ctx *c, const AggArgs &a, const int32_t *F, int nF, const float *f_old,
                               float *f_delta, int ld_old);

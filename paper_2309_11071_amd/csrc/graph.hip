@@ -136,10 +136,11 @@ __global__ void k_take_ops(const RawUpdate *raw, const uint32_t *perm, const int
 
 // chunks of 2048 block slots per touched node
 constexpr int kChunk = 2048;
-__global__ void k_chunk_counts(const int32_t *nodes, const int32_t *n_nodes, const int32_t *deg, int32_t *chunks) {
+__global__ void k_chunk_counts(const int32_t *nodes, const int32_t *n_nodes, int64_t n_max, const int32_t *deg,
+                               int32_t *chunks) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= *n_nodes) return;
-  chunks[i] = (deg[nodes[i]] + kChunk - 1) / kChunk;
+  if (i >= n_max) return;
+  chunks[i] = i < *n_nodes ? (deg[nodes[i]] + kChunk - 1) / kChunk : 0;
 }
 
 // Walk the blocks of the touched nodes; an id found in the node's op list records its slot and,
@@ -305,9 +306,9 @@ __global__ void k_split_ops(const uint32_t *node, const int32_t *other, const ui
   if (k < *n_ins) { int j = idx_ins[k]; ins_s[k] = other[j]; ins_d[k] = (int32_t)node[j]; }
   if (k < *n_del) { int j = idx_del[k]; del_s[k] = other[j]; del_d[k] = (int32_t)node[j]; }
 }
-__global__ void k_flag_eq(const uint8_t *eff, const int32_t *n_ops, uint8_t want, uint8_t *flag) {
+__global__ void k_flag_eq(const uint8_t *eff, const int32_t *n_ops, int64_t n_max, uint8_t want, uint8_t *flag) {
   int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (k < *n_ops) flag[k] = eff[k] == want;
+  if (k < n_max) flag[k] = k < *n_ops && eff[k] == want;
 }
 
 // out side: ops = [deletes | inserts] keyed by source
@@ -385,33 +386,35 @@ struct SideBufs {
   int32_t *uniq, *seg, *chunks, *chunk_pref, *nd_ins, *nd_del, *fill;
 };
 
-static ink_status apply_side(ink_ctx *c, GraphSide &g, SideBufs &b, int64_t n_ops, int32_t *new_cnt,
-                             int *n_touched_out, int64_t *tot_ins, int64_t *tot_del) {
+// n_ops_max bounds the number of ops; the exact count sits on the device in *n_ops_dev.  One host
+// round trip per direction: it returns the touched-node count, the totals and the pool space
+// that relocations need.
+static ink_status apply_side(ink_ctx *c, GraphSide &g, SideBufs &b, int64_t n_ops_max, const int32_t *n_ops_dev,
+                             int32_t *new_cnt, int *n_touched_out, int64_t *tot_ins, int64_t *tot_del) {
   hipStream_t s = c->stream;
   Counters *dc = c->d_cnt;
-  INK_TRYS(hipMemsetAsync(dc, 0, sizeof(Counters), s));
-  INK_TRYS(segment_heads(c->ws, b.node, n_ops, b.uniq, b.seg, &dc->v[C_TMP0], s));
-  hipLaunchKernelGGL(k_chunk_counts, grid1(n_ops), dim3(256), 0, s, (const int32_t *)b.uniq,
-                     (const int32_t *)&dc->v[C_TMP0], (const int32_t *)g.deg, b.chunks);
-  // n_touched <= n_ops: scan over the upper bound is wasteful; read the count instead
-  INK_TRYS(hipMemcpyAsync(c->h_cnt, dc, sizeof(Counters), hipMemcpyDeviceToHost, s));
-  INK_TRYS(hipStreamSynchronize(s));
-  int n_touched = c->h_cnt->v[C_TMP0];
-  *n_touched_out = n_touched;
-  INK_TRYS(scan_excl_i32(c->ws, b.chunks, b.chunk_pref, n_touched, &dc->v[C_TMP1], s));
+  INK_TRYS(hipMemsetAsync(&dc->v[C_TMP0], 0, 4 * sizeof(int32_t), s));
+  INK_TRYS(hipMemsetAsync(&dc->v[C_REGATHER_LO], 0, 2 * sizeof(int32_t), s));
+  INK_TRYS(segment_heads(c->ws, b.node, n_ops_max, b.uniq, b.seg, &dc->v[C_TMP0], s, n_ops_dev));
+  hipLaunchKernelGGL(k_chunk_counts, grid1(n_ops_max), dim3(256), 0, s, (const int32_t *)b.uniq,
+                     (const int32_t *)&dc->v[C_TMP0], n_ops_max, (const int32_t *)g.deg, b.chunks);
+  INK_TRYS(scan_excl_i32(c->ws, b.chunks, b.chunk_pref, n_ops_max, &dc->v[C_TMP1], s));
   hipLaunchKernelGGL(k_classify, dim3(2048), dim3(256), 0, s, (const int32_t *)b.uniq, (const int32_t *)&dc->v[C_TMP0],
                      (const int32_t *)b.seg, (const int32_t *)b.chunk_pref, (const int32_t *)&dc->v[C_TMP1],
                      (const int64_t *)g.off, (const int32_t *)g.deg, g.ids, (const int32_t *)b.other,
                      (const uint8_t *)b.op, b.pos);
-  hipLaunchKernelGGL(k_effect, grid1((int64_t)n_touched * kWave), dim3(256), 0, s, (const int32_t *)b.uniq,
+  hipLaunchKernelGGL(k_effect, grid1(n_ops_max * kWave), dim3(256), 0, s, (const int32_t *)b.uniq,
                      (const int32_t *)&dc->v[C_TMP0], (const int32_t *)b.seg, (const uint8_t *)b.op,
                      (const int32_t *)b.pos, b.eff, (const int32_t *)g.deg, (const int32_t *)g.cap, b.nd_ins, b.nd_del,
                      c->slack, (unsigned long long *)&dc->v[C_REGATHER_LO], &dc->v[C_TMP2], &dc->v[C_TMP3]);
   INK_TRYS(hipMemcpyAsync(c->h_cnt, dc, sizeof(Counters), hipMemcpyDeviceToHost, s));
   INK_TRYS(hipStreamSynchronize(s));
+  int n_touched = c->h_cnt->v[C_TMP0];
+  *n_touched_out = n_touched;
   int64_t need = *(int64_t *)&c->h_cnt->v[C_REGATHER_LO];
   *tot_ins = c->h_cnt->v[C_TMP2];
   *tot_del = c->h_cnt->v[C_TMP3];
+  if (n_touched == 0) return INK_OK;
   if (g.pool_top + need > g.pool_cap) {
     hipError_t e = grow_pool(c, g, need);
     if (e == hipErrorOutOfMemory) { c->err = "out of device memory while growing the edge pool"; return INK_E_OOM; }
@@ -419,13 +422,12 @@ static ink_status apply_side(ink_ctx *c, GraphSide &g, SideBufs &b, int64_t n_op
   }
   // device copy of the pool top lives in the counter block (64-bit slot)
   unsigned long long *d_top = (unsigned long long *)&dc->v[C_REGATHER_LO];
-  unsigned long long top = (unsigned long long)g.pool_top;
-  INK_TRYS(hipMemcpyAsync(d_top, &top, sizeof(top), hipMemcpyHostToDevice, s));
-  if (n_touched > 0)
-    hipLaunchKernelGGL(k_apply, dim3(n_touched), dim3(256), 0, s, (const int32_t *)b.uniq, (const int32_t *)b.seg,
-                       (const int32_t *)b.other, (const uint8_t *)b.eff, (const int32_t *)b.pos,
-                       (const int32_t *)b.nd_ins, (const int32_t *)b.nd_del, g.off, g.deg, g.cap, g.ids, d_top,
-                       c->slack, b.fill, new_cnt);
+  c->h_top = (unsigned long long)g.pool_top;
+  INK_TRYS(hipMemcpyAsync(d_top, &c->h_top, sizeof(unsigned long long), hipMemcpyHostToDevice, s));
+  hipLaunchKernelGGL(k_apply, dim3(n_touched), dim3(256), 0, s, (const int32_t *)b.uniq, (const int32_t *)b.seg,
+                     (const int32_t *)b.other, (const uint8_t *)b.eff, (const int32_t *)b.pos,
+                     (const int32_t *)b.nd_ins, (const int32_t *)b.nd_del, g.off, g.deg, g.cap, g.ids, d_top,
+                     c->slack, b.fill, new_cnt);
   INK_TRYS(hipGetLastError());
   g.pool_top += need;      // exact: the apply kernel allocates precisely what k_effect summed
   return INK_OK;
@@ -454,6 +456,7 @@ ink_status graph_apply_batch(ink_ctx *c, int64_t n, int64_t *n_ins_out, int64_t 
   b.chunk_pref = ar.get<int32_t>(n + 1); b.nd_ins = ar.get<int32_t>(n + 1); b.nd_del = ar.get<int32_t>(n + 1);
   b.fill = ar.get<int32_t>(n + 1);
   Counters *dc = c->d_cnt;
+  int32_t *n_ops_d = &dc->v[C_SPARE];
 
   // (dst, src, position) order through two stable sorts
   hipLaunchKernelGGL(k_unpack, grid1(n), dim3(256), 0, s, raw, n, srcv, dstv, v0);
@@ -461,40 +464,33 @@ ink_status graph_apply_batch(ink_ctx *c, int64_t n, int64_t *n_ins_out, int64_t 
   INK_TRYS(radix_sort_pairs(c->ws, k0, v0, n, c->id_bits, s));
   hipLaunchKernelGGL(k_gather_u32, grid1(n), dim3(256), 0, s, (const uint32_t *)dstv, (const uint32_t *)v0, n, k1);
   INK_TRYS(radix_sort_pairs(c->ws, k1, v0, n, c->id_bits, s));
-  // final op per distinct edge
+  // final op per distinct edge; their number stays on the device (n bounds it)
   hipLaunchKernelGGL(k_mark_last, grid1(n), dim3(256), 0, s, raw, (const uint32_t *)v0, n, flag);
-  INK_TRYS(compact_flags_u8(c->ws, flag, n, idx, &dc->v[C_TMP0], s));
+  INK_TRYS(compact_flags_u8(c->ws, flag, n, idx, n_ops_d, s));
   hipLaunchKernelGGL(k_take_ops, grid1(n), dim3(256), 0, s, raw, (const uint32_t *)v0, (const int32_t *)idx,
-                     (const int32_t *)&dc->v[C_TMP0], b.node, b.other, b.op, b.pos);
-  INK_TRYS(hipMemcpyAsync(c->h_cnt, dc, sizeof(Counters), hipMemcpyDeviceToHost, s));
-  INK_TRYS(hipStreamSynchronize(s));
-  int64_t n_ops = c->h_cnt->v[C_TMP0];
-  if (n_ops == 0) return INK_OK;
+                     (const int32_t *)n_ops_d, b.node, b.other, b.op, b.pos);
 
   int n_touched = 0;
   int64_t ti = 0, td = 0;
-  ink_status st = apply_side(c, c->gin, b, n_ops, nullptr, &n_touched, &ti, &td);
+  ink_status st = apply_side(c, c->gin, b, n, n_ops_d, nullptr, &n_touched, &ti, &td);
   if (st != INK_OK) return st;
   c->n_ins = ti; c->n_del = td;
   *n_ins_out = ti; *n_del_out = td;
   c->n_touched_in = n_touched;
+  if (ti + td == 0) return INK_OK;
   INK_TRYS(c->b_touch_in.reserve((size_t)(n_touched + 1) * 4));
   INK_TRYS(hipMemcpyAsync(c->b_touch_in.p, b.uniq, (size_t)n_touched * 4, hipMemcpyDeviceToDevice, s));
-  if (ti + td == 0) return INK_OK;
 
   // Delta E lists, (dst, src) order
-  int32_t *n_ops_d = &dc->v[C_TMP0];
-  int32_t nops32 = (int32_t)n_ops;
-  INK_TRYS(hipMemcpyAsync(&dc->v[C_TMP0], &nops32, sizeof(int32_t), hipMemcpyHostToDevice, s));
-  hipLaunchKernelGGL(k_flag_eq, grid1(n_ops), dim3(256), 0, s, (const uint8_t *)b.eff, (const int32_t *)n_ops_d,
+  hipLaunchKernelGGL(k_flag_eq, grid1(n), dim3(256), 0, s, (const uint8_t *)b.eff, (const int32_t *)n_ops_d, n,
                      (uint8_t)1, flag);
-  INK_TRYS(compact_flags_u8(c->ws, flag, n_ops, idx, &dc->v[C_TMP2], s));
-  hipLaunchKernelGGL(k_flag_eq, grid1(n_ops), dim3(256), 0, s, (const uint8_t *)b.eff, (const int32_t *)n_ops_d,
+  INK_TRYS(compact_flags_u8(c->ws, flag, n, idx, &dc->v[C_TMP2], s));
+  hipLaunchKernelGGL(k_flag_eq, grid1(n), dim3(256), 0, s, (const uint8_t *)b.eff, (const int32_t *)n_ops_d, n,
                      (uint8_t)2, flag);
-  INK_TRYS(compact_flags_u8(c->ws, flag, n_ops, idx2, &dc->v[C_TMP3], s));
+  INK_TRYS(compact_flags_u8(c->ws, flag, n, idx2, &dc->v[C_TMP3], s));
   c->del_src = c->b_del_s.as<int32_t>(); c->del_dst = c->b_del_d.as<int32_t>();
   c->ins_src = c->b_ins_s.as<int32_t>(); c->ins_dst = c->b_ins_d.as<int32_t>();
-  hipLaunchKernelGGL(k_split_ops, grid1(n_ops), dim3(256), 0, s, (const uint32_t *)b.node, (const int32_t *)b.other,
+  hipLaunchKernelGGL(k_split_ops, grid1(n), dim3(256), 0, s, (const uint32_t *)b.node, (const int32_t *)b.other,
                      (const uint8_t *)b.eff, (const int32_t *)n_ops_d, (const int32_t *)idx, (const int32_t *)idx2,
                      c->ins_src, c->ins_dst, c->del_src, c->del_dst, (const int32_t *)&dc->v[C_TMP2],
                      (const int32_t *)&dc->v[C_TMP3]);
@@ -513,7 +509,7 @@ ink_status graph_apply_batch(ink_ctx *c, int64_t n, int64_t *n_ins_out, int64_t 
                      (const int32_t *)c->del_dst, (const int32_t *)c->ins_src, (const int32_t *)c->ins_dst, (int)td,
                      (int)ti, b.node, b.other, b.op, b.pos);
   int64_t oi = 0, od = 0;
-  st = apply_side(c, c->gout, b, m, c->new_out, &n_touched, &oi, &od);
+  st = apply_side(c, c->gout, b, m, nullptr, c->new_out, &n_touched, &oi, &od);
   if (st != INK_OK) return st;
   if (oi != ti || od != td) {
     c->err = "graph store inconsistent: in- and out-adjacency disagree";

@@ -168,8 +168,9 @@ hipError_t bitmap_to_list(PrimWorkspace &ws, uint64_t *words, int64_t n_bits, in
 
 // segment heads of a sorted key array: uniq[j] = j-th distinct key, seg[j] = first index of its
 // run, seg[*count] = n
+// n_dev (optional): device-side number of valid keys, n is then an upper bound
 hipError_t segment_heads(PrimWorkspace &ws, const uint32_t *keys, int64_t n, int32_t *uniq,
-                         int32_t *seg, int32_t *count, hipStream_t s);
+                         int32_t *seg, int32_t *count, hipStream_t s, const int32_t *n_dev = nullptr);
 
 // stable sort of (key, val) pairs by the low `bits` bits of key, in place (uses ws.tmpk / tmpv)
 hipError_t radix_sort_pairs(PrimWorkspace &ws, uint32_t *keys, uint32_t *vals, int64_t n, int bits,

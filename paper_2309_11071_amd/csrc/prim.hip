@@ -49,22 +49,24 @@ hipError_t bitmap_to_list(PrimWorkspace &ws, uint64_t *words, int64_t n_bits, in
 
 // ---------------------------------------------------------------- segment heads of sorted keys
 struct LoadHead {
-  const uint32_t *k;
-  __device__ int operator()(int64_t i) const { return i == 0 || k[i] != k[i - 1]; }
-};
-struct StoreHead {
-  const uint32_t *k; int32_t *uniq; int32_t *seg;
-  __device__ void operator()(int64_t i, int v, int ex) const {
-    if (v) { uniq[ex] = (int32_t)k[i]; seg[ex] = (int32_t)i; }
+  const uint32_t *k; const int32_t *n_dev;
+  __device__ int operator()(int64_t i) const {
+    if (n_dev && i >= *n_dev) return 0;
+    return i == 0 || k[i] != k[i - 1];
   }
 };
-__global__ void k_seg_tail(const int32_t *count, int32_t *seg, int32_t n) { seg[*count] = n; }
+struct StoreHead {
+  const uint32_t *k; int32_t *uniq; int32_t *seg; int64_t n; const int32_t *n_dev;
+  __device__ void operator()(int64_t i, int v, int ex) const {
+    if (v) { uniq[ex] = (int32_t)k[i]; seg[ex] = (int32_t)i; }
+    int64_t nn = n_dev ? (int64_t)*n_dev : n;
+    if (i == nn - 1) seg[ex + v] = (int32_t)nn;    // closing offset after the last run
+  }
+};
 
 hipError_t segment_heads(PrimWorkspace &ws, const uint32_t *keys, int64_t n, int32_t *uniq,
-                         int32_t *seg, int32_t *count, hipStream_t s) {
-  INK_TRY(tile_scan(ws, LoadHead{keys}, StoreHead{keys, uniq, seg}, n, count, s));
-  hipLaunchKernelGGL(k_seg_tail, dim3(1), dim3(1), 0, s, (const int32_t *)count, seg, (int32_t)n);
-  return hipGetLastError();
+                         int32_t *seg, int32_t *count, hipStream_t s, const int32_t *n_dev) {
+  return tile_scan(ws, LoadHead{keys, n_dev}, StoreHead{keys, uniq, seg, n, n_dev}, n, count, s);
 }
 
 // ---------------------------------------------------------------- stable LSD radix sort
@@ -151,12 +153,91 @@ __global__ __launch_bounds__(kSortThreads) void k_radix_scatter(const uint32_t *
   }
 }
 
-struct Ident { __device__ int operator()(int64_t) const { return 0; } };
+// Whole sort in one workgroup for n <= kSmallSort: the same stable digit ranking, all passes in
+// LDS, one launch.
+constexpr int kSmallItems = 16;
+constexpr int kSmallSort = kSortThreads * kSmallItems;     // 4096 pairs, 64 KB of LDS
+
+__global__ __launch_bounds__(kSortThreads) void k_small_sort(uint32_t *keys, uint32_t *vals, int n, int passes) {
+  __shared__ uint32_t sk[2][kSmallSort];
+  __shared__ uint32_t sv[2][kSmallSort];
+  __shared__ int cnt[kSortWaves][kRadix];
+  __shared__ int dbase[kRadix];
+  const int w = threadIdx.x / kWave, l = lane_id();
+  for (int i = threadIdx.x; i < n; i += kSortThreads) { sk[0][i] = keys[i]; sv[0][i] = vals[i]; }
+  __syncthreads();
+  int cur = 0;
+  const int per_wave = kSmallItems * kWave;
+  for (int p = 0; p < passes; p++) {
+    int shift = p * kRadixBits;
+    for (int i = threadIdx.x; i < kSortWaves * kRadix; i += kSortThreads) (&cnt[0][0])[i] = 0;
+    __syncthreads();
+    uint32_t key[kSmallItems], val[kSmallItems];
+    int rank[kSmallItems];
+#pragma unroll
+    for (int k = 0; k < kSmallItems; k++) {
+      int i = w * per_wave + k * kWave + l;
+      bool ok = i < n;
+      key[k] = ok ? sk[cur][i] : 0xFFFFFFFFu;
+      val[k] = ok ? sv[cur][i] : 0;
+      int dg = ok ? (int)((key[k] >> shift) & (kRadix - 1)) : kRadix;
+      uint64_t same = __ballot(ok);
+#pragma unroll
+      for (int b = 0; b < kRadixBits; b++) {
+        uint64_t m = __ballot((dg >> b) & 1);
+        same &= ((dg >> b) & 1) ? m : ~m;
+      }
+      uint64_t lt = (l == 0) ? 0ull : (~0ull >> (kWave - l));
+      int before = __popcll(same & lt);
+      int prev = 0;
+      if (ok) prev = cnt[w][dg];
+      rank[k] = prev + before;
+      bool leader = ok && ((same >> l) >> 1) == 0;
+      if (leader) cnt[w][dg] = prev + before + 1;
+    }
+    __syncthreads();
+    {   // digit totals -> exclusive prefix over digits (thread t = digit t), then per-wave bases
+      int d = threadIdx.x;
+      int tot = 0;
+#pragma unroll
+      for (int i = 0; i < kSortWaves; i++) tot += cnt[i][d];
+      int incl = wave_incl_scan(tot);
+      __shared__ int wsum[kSortWaves];
+      if (l == kWave - 1) wsum[w] = incl;
+      __syncthreads();
+      int base = 0;
+#pragma unroll
+      for (int i = 0; i < kSortWaves; i++) if (i < w) base += wsum[i];
+      int run = base + incl - tot;
+#pragma unroll
+      for (int i = 0; i < kSortWaves; i++) { int c = cnt[i][d]; cnt[i][d] = run; run += c; }
+      (void)dbase;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < kSmallItems; k++) {
+      int i = w * per_wave + k * kWave + l;
+      if (i < n) {
+        int dg = (key[k] >> shift) & (kRadix - 1);
+        int pos = cnt[w][dg] + rank[k];
+        sk[cur ^ 1][pos] = key[k];
+        sv[cur ^ 1][pos] = val[k];
+      }
+    }
+    __syncthreads();
+    cur ^= 1;
+  }
+  for (int i = threadIdx.x; i < n; i += kSortThreads) { keys[i] = sk[cur][i]; vals[i] = sv[cur][i]; }
+}
 
 hipError_t radix_sort_pairs(PrimWorkspace &ws, uint32_t *keys, uint32_t *vals, int64_t n, int bits,
                             hipStream_t s) {
   if (n <= 1 || bits <= 0) return hipSuccess;
   int passes = (bits + kRadixBits - 1) / kRadixBits;
+  if (n <= kSmallSort) {
+    hipLaunchKernelGGL(k_small_sort, dim3(1), dim3(kSortThreads), 0, s, keys, vals, (int)n, passes);
+    return hipGetLastError();
+  }
   int nb = nblocks(n, kSortTile);
   INK_TRY(ws.hist.reserve((size_t)kRadix * nb * sizeof(int32_t)));
   INK_TRY(ws.tmpk.reserve((size_t)n * sizeof(uint32_t)));

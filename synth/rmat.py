@@ -83,8 +83,13 @@ def rmat_edges(n_nodes, n_edges, a=0.57, b=0.19, c=0.19, seed=0, symmetrise=Fals
     return (keys & 0xFFFFFFFF).astype(np.int32), (keys >> 32).astype(np.int32)
 
 
-def in_csr_from_edges(n_nodes, src, dst):
-    """In-neighbour CSR: row v lists the sources u of edges u -> v in ascending order."""
+def in_csr_from_edges(n_nodes, src, dst, assume_sorted=False):
+    """In-neighbour CSR: row v lists the sources u of edges u -> v in ascending order.
+    assume_sorted: the edges are already unique and ordered by (dst, src), as rmat_edges returns."""
+    if assume_sorted:
+        rowptr = np.zeros(n_nodes + 1, dtype=np.int64)
+        np.cumsum(np.bincount(dst, minlength=n_nodes), out=rowptr[1:])
+        return rowptr, np.ascontiguousarray(src, dtype=np.int32)
     keys = np.unique(edge_keys(np.asarray(src), np.asarray(dst)))
     s, d = keys_to_edges(keys)
     rowptr = np.zeros(n_nodes + 1, dtype=np.int64)

@@ -25,6 +25,7 @@ class WorkloadConfig:
     batch: int
     hub_biased_deletes: bool
     rmat: tuple = (0.57, 0.19, 0.19)
+    graph_seed: int = 0     # 0: 1000 + cfg_id
 
     @property
     def n_layers(self):
@@ -49,7 +50,7 @@ CONFIGS = {
     4: WorkloadConfig(4, "cfg4-gin-sum-20M", "gin", "sum", 20_000_000, 400_000_000, False,
                       (128, 128, 128, 172), 128, 10_000, False),
     5: WorkloadConfig(5, "cfg5-sage-max-20M", "sage", "max", 20_000_000, 400_000_000, False,
-                      (128, 128, 128, 128), 0, 10_000, False),
+                      (128, 128, 128, 128), 0, 10_000, False, graph_seed=1004),   # the graph of config 4
 }
 
 
@@ -58,9 +59,10 @@ def get_config(cfg_id, scale_div=1):
 
 
 def make_graph(cfg):
-    """(src, dst) int32, unique, no self loops, sorted by (dst, src).  Seed 1000 + cfg."""
+    """(src, dst) int32, unique, no self loops, sorted by (dst, src).  Seed 1000 + cfg (config 5 reuses
+    the graph of config 4, as its description says)."""
     a, b, c = cfg.rmat
-    return rmat_edges(cfg.n_nodes, cfg.n_edges, a, b, c, seed=1000 + cfg.cfg_id,
+    return rmat_edges(cfg.n_nodes, cfg.n_edges, a, b, c, seed=cfg.graph_seed or 1000 + cfg.cfg_id,
                       symmetrise=cfg.symmetrise)
 
 
