@@ -53,7 +53,7 @@ __device__ __forceinline__ void gather_range(const int32_t *ids, int64_t j0, int
     int64_t jj = jb + l;
     int myid = jj < j1 ? ids[jj] : -1;
     int cnt = (int)((j1 - jb) < kWave ? (j1 - jb) : kWave);
-    constexpr int U = INK_GATHER_U;       // neighbour rows in flight per lane group
+    constexpr int U = LPR == 16 ? INK_U_SEL16 : (LPR == 32 ? INK_U_SEL32 : INK_U_SEL64);
     for (int it = 0; it < cnt; it += G * U) {
       int id[U];
       float4 row[U];
@@ -156,7 +156,7 @@ __global__ __launch_bounds__(256) void k_agg_full(AggArgs a, const int32_t *targ
 // cooperative path for rows with more than kBigDeg in-neighbours: a workgroup per chunk of
 // kBigChunk neighbours (its 4 waves take a quarter each), partial rows to scratch
 template <bool IS_MIN, int LPR>
-__global__ __launch_bounds__(1024) void k_big_partial(AggArgs a, const int32_t *big_list, const int32_t *n_big_p,
+__global__ __launch_bounds__(INK_BIG_LB) void k_big_partial(AggArgs a, const int32_t *big_list, const int32_t *n_big_p,
                                                       const int32_t *pref, const int32_t *total_p, float *part_v,
                                                       int32_t *part_i) {
   __shared__ float sv[kBigMaxWaves][kWave * 4];

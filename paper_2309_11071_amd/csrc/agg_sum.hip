@@ -35,7 +35,7 @@ __device__ __forceinline__ void sum_range(const int32_t *ids, int64_t j0, int64_
     int64_t jj = jb + l;
     int myid = jj < j1 ? ids[jj] : -1;
     int cnt = (int)((j1 - jb) < kWave ? (j1 - jb) : kWave);
-    constexpr int U = INK_GATHER_U;       // neighbour rows in flight per lane group
+    constexpr int U = LPR == 16 ? INK_U_SUM16 : (LPR == 32 ? INK_U_SUM32 : INK_U_SUM64);
     for (int it = 0; it < cnt; it += G * U) {
       int id[U];
       float4 row[U];
@@ -104,7 +104,7 @@ __global__ __launch_bounds__(256) void k_sum_full(AggArgs a, const int32_t *targ
 }
 
 template <int LPR>
-__global__ __launch_bounds__(1024) void k_sum_big_partial(AggArgs a, const int32_t *big_list, const int32_t *n_big_p,
+__global__ __launch_bounds__(INK_BIG_LB) void k_sum_big_partial(AggArgs a, const int32_t *big_list, const int32_t *n_big_p,
                                                           const int32_t *pref, const int32_t *total_p, float *part) {
   __shared__ float sv[kBigMaxWaves][kWave * 4];
   const int l = lane_id(), w = threadIdx.x / kWave, nw = blockDim.x / kWave;

@@ -8,6 +8,13 @@
 
 namespace ink {
 
+#ifndef INK_BIG_LB
+#define INK_BIG_LB 1024
+#endif
+#ifndef INK_BIG_GRID_CAP
+#define INK_BIG_GRID_CAP (1 << 30)
+#endif
+
 constexpr int kBigGrid = 4096;             // workgroups of the per-row combine kernel
 
 // upper bound of the chunks any launch can need: every long row has at most deg / chunk + 1
@@ -21,6 +28,7 @@ inline unsigned big_partial_grid(const ink_ctx *c, int64_t want, int block_threa
   int64_t lo = block_threads >= 1024 ? 512 : 2048, hi = big_chunk_capacity(c);
   if (want < lo) want = lo;
   if (want > hi) want = hi;
+  if (want > INK_BIG_GRID_CAP) want = INK_BIG_GRID_CAP;
   return (unsigned)want;
 }
 
@@ -43,8 +51,8 @@ inline bool latency_mode(int64_t n_targets) { return n_targets <= kLatencyTarget
 inline int big_threshold(int64_t n_targets, int lanes_per_row) {
   return latency_mode(n_targets) ? 32 * (kWave / lanes_per_row) : kBigDeg;
 }
-inline int big_block_threads(int64_t n_targets) { return latency_mode(n_targets) ? 1024 : 256; }
-constexpr int kBigMaxWaves = 16;
+inline int big_block_threads(int64_t n_targets) { return latency_mode(n_targets) ? (INK_BIG_LB >= 1024 ? 1024 : 256) : 256; }
+constexpr int kBigMaxWaves = INK_BIG_LB / 64;
 
 // plan: pref[i] = chunks of the listed rows before i (i <= n_big), *total = all chunks
 struct BigChunkCount {

@@ -14,8 +14,24 @@ namespace ink {
 #ifndef INK_BIG_DEG
 #define INK_BIG_DEG 1024
 #endif
-#ifndef INK_GATHER_U
-#define INK_GATHER_U 4
+// neighbour rows in flight per lane group while gathering, by aggregator family and lanes per row
+#ifndef INK_U_SEL16
+#define INK_U_SEL16 4
+#endif
+#ifndef INK_U_SEL32
+#define INK_U_SEL32 4
+#endif
+#ifndef INK_U_SEL64
+#define INK_U_SEL64 4
+#endif
+#ifndef INK_U_SUM16
+#define INK_U_SUM16 4
+#endif
+#ifndef INK_U_SUM32
+#define INK_U_SUM32 4
+#endif
+#ifndef INK_U_SUM64
+#define INK_U_SUM64 4
 #endif
 #ifndef INK_BIG_CHUNK
 #define INK_BIG_CHUNK 1024
