@@ -23,6 +23,15 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 
+# HBM bytes per aggregation launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs
+# of this script, summaries under profiles/): all aggregation kernels of one update batch, fetch
+# counter scaled by 2.0 and write counter by 1.0 (what a plain 1 GiB copy kernel reads back in the
+# same runs), divided by the aggregation launches of the batch (one per layer).
+MEASURED_TRAFFIC_PER_LAUNCH = {
+    2: {"bytes": 8.27e9, "source": "profiles/all_kernels_cfg2_gcn.md"},
+    3: {"bytes": 15.9e9, "source": "profiles/all_kernels_cfg3_sage_max.md"},
+}
+
 
 def agg_algorithmic_bytes(layer_stats, agg_width, n_del):
     """Bytes the aggregation kernels of one step must move (per layer, summed).
@@ -177,7 +186,11 @@ def main():
                    "edges": int(src.size), "dims": list(cfg.dims), "batch": cfg.batch,
                    "hub_biased_deletes": cfg.hub_biased_deletes},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": (MEASURED_TRAFFIC_PER_LAUNCH.get(args.config, {}).get("bytes")
+                                 if args.scale_div == 1 and not args.batch else None),
+                     "traffic_source": MEASURED_TRAFFIC_PER_LAUNCH.get(args.config, {}).get("source"),
+                     "algorithmic_bytes_per_launch": agg_bytes / max(agg_launches, 1),
                      "kernel": "aggregation (k_agg_events / k_agg_full / k_big_*), all layers",
                      "avg_launch_ms": agg_ms / max(agg_launches, 1),
                      "algorithmic_bytes_per_step": agg_bytes / args.steps},

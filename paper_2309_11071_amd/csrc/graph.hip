@@ -186,8 +186,7 @@ __global__ __launch_bounds__(256) void k_classify(const int32_t *nodes, const in
 __global__ __launch_bounds__(256) void k_effect(const int32_t *nodes, const int32_t *n_nodes, const int32_t *seg,
                                                 const uint8_t *op, const int32_t *pos, uint8_t *eff,
                                                 const int32_t *deg, const int32_t *cap, int32_t *nd_ins,
-                                                int32_t *nd_del, float slack, unsigned long long *need,
-                                                int32_t *tot_ins, int32_t *tot_del) {
+                                                int32_t *nd_del, float slack, Counters *cnt) {
   int64_t w = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kWave;
   int l = threadIdx.x & (kWave - 1);
   if (w >= *n_nodes) return;
@@ -212,10 +211,10 @@ __global__ __launch_bounds__(256) void k_effect(const int32_t *nodes, const int3
       if (extra < 4) extra = 4;
       if (want < nd2 + extra) want = nd2 + extra;
       want = (want + 3) & ~3ll;
-      atomicAdd(need, (unsigned long long)want);
+      atomicAdd(&cnt->stripe[blockIdx.x % kStripes][ST_REGATHER], (unsigned long long)want);   // pool space needed
     }
-    if (ni) atomicAdd(tot_ins, ni);
-    if (nd) atomicAdd(tot_del, nd);
+    if (ni) atomicAdd(&cnt->stripe[blockIdx.x % kStripes][ST_EXPOSED], (unsigned long long)ni);  // effective inserts
+    if (nd) atomicAdd(&cnt->stripe[blockIdx.x % kStripes][ST_ACHG], (unsigned long long)nd);     // effective deletes
   }
 }
 
@@ -394,7 +393,7 @@ static ink_status apply_side(ink_ctx *c, GraphSide &g, SideBufs &b, int64_t n_op
   hipStream_t s = c->stream;
   Counters *dc = c->d_cnt;
   INK_TRYS(hipMemsetAsync(&dc->v[C_TMP0], 0, 4 * sizeof(int32_t), s));
-  INK_TRYS(hipMemsetAsync(&dc->v[C_REGATHER_LO], 0, 2 * sizeof(int32_t), s));
+  INK_TRYS(hipMemsetAsync(&dc->stripe[0][0], 0, sizeof(dc->stripe), s));
   INK_TRYS(segment_heads(c->ws, b.node, n_ops_max, b.uniq, b.seg, &dc->v[C_TMP0], s, n_ops_dev));
   hipLaunchKernelGGL(k_chunk_counts, grid1(n_ops_max), dim3(256), 0, s, (const int32_t *)b.uniq,
                      (const int32_t *)&dc->v[C_TMP0], n_ops_max, (const int32_t *)g.deg, b.chunks);
@@ -406,14 +405,14 @@ static ink_status apply_side(ink_ctx *c, GraphSide &g, SideBufs &b, int64_t n_op
   hipLaunchKernelGGL(k_effect, grid1(n_ops_max * kWave), dim3(256), 0, s, (const int32_t *)b.uniq,
                      (const int32_t *)&dc->v[C_TMP0], (const int32_t *)b.seg, (const uint8_t *)b.op,
                      (const int32_t *)b.pos, b.eff, (const int32_t *)g.deg, (const int32_t *)g.cap, b.nd_ins, b.nd_del,
-                     c->slack, (unsigned long long *)&dc->v[C_REGATHER_LO], &dc->v[C_TMP2], &dc->v[C_TMP3]);
+                     c->slack, dc);
   INK_TRYS(hipMemcpyAsync(c->h_cnt, dc, sizeof(Counters), hipMemcpyDeviceToHost, s));
   INK_TRYS(hipStreamSynchronize(s));
   int n_touched = c->h_cnt->v[C_TMP0];
   *n_touched_out = n_touched;
-  int64_t need = *(int64_t *)&c->h_cnt->v[C_REGATHER_LO];
-  *tot_ins = c->h_cnt->v[C_TMP2];
-  *tot_del = c->h_cnt->v[C_TMP3];
+  int64_t need = (int64_t)c->h_cnt->sum(ST_REGATHER);
+  *tot_ins = (int64_t)c->h_cnt->sum(ST_EXPOSED);
+  *tot_del = (int64_t)c->h_cnt->sum(ST_ACHG);
   if (n_touched == 0) return INK_OK;
   if (g.pool_top + need > g.pool_cap) {
     hipError_t e = grow_pool(c, g, need);
