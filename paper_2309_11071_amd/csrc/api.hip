@@ -171,14 +171,19 @@ static hipError_t alloc_table(Table &t, int64_t n, int d) {
   return hipMemset(t.p, 0, bytes);
 }
 
-// uploads W ([K][N], host or device) zero-padded to [Kp][Np]
+// uploads rows [row_off, row_off + K) of a weight matrix W ([K][N], host or device) into the
+// zero-initialised padded device matrix `dst` ([Kp][Np] elements) in the order the transform
+// kernel stages it (xform_weight_index)
 static hipError_t upload_padded(const float *src, int K, int N, int Kp, int Np, int row_off, float *dst, bool src_dev) {
   std::vector<float> h((size_t)K * N);
   hipError_t e = hipMemcpy(h.data(), src, h.size() * 4, src_dev ? hipMemcpyDeviceToHost : hipMemcpyHostToHost);
   if (e != hipSuccess) return e;
-  std::vector<float> p((size_t)K * Np, 0.f);
-  for (int k = 0; k < K; k++) std::copy(h.begin() + (size_t)k * N, h.begin() + (size_t)(k + 1) * N, p.begin() + (size_t)k * Np);
-  return hipMemcpy(dst + (size_t)row_off * Np, p.data(), p.size() * 4, hipMemcpyHostToDevice);
+  std::vector<float> p((size_t)Kp * Np);
+  e = hipMemcpy(p.data(), dst, p.size() * 4, hipMemcpyDeviceToHost);
+  if (e != hipSuccess) return e;
+  for (int k = 0; k < K; k++)
+    for (int j = 0; j < N; j++) p[xform_weight_index(row_off + k, j, Np)] = h[(size_t)k * N + j];
+  return hipMemcpy(dst, p.data(), p.size() * 4, hipMemcpyHostToDevice);
 }
 
 static hipError_t upload_vec(const float *src, int n, float **dst, bool src_dev) {

@@ -201,5 +201,10 @@ struct XformArgs {
   const float *out_scale;   // per-node factor applied to the output row (after bias), null: none
 };
 hipError_t xform_run(ink_ctx *c, const XformArgs &x);
+// position of W[k][col] in the padded device copy: k-chunks of 32, inside a chunk one row of 32 per
+// column holding first the 16 even then the 16 odd k (the order the MFMA steps consume them)
+inline size_t xform_weight_index(int k, int col, int Np) {
+  return (size_t)(k / 32) * 32 * Np + (size_t)col * 32 + (size_t)(k & 1) * 16 + (size_t)((k % 32) >> 1);
+}
 
 }  // namespace ink

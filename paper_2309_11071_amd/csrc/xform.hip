@@ -110,18 +110,53 @@ __device__ __forceinline__ void fetch_x4(const XformArgs &x, int64_t row, int k,
   for (int i = 0; i < 4; i++) out[i] = fetch_x<MODE>(x, row, k + i);
 }
 
-template <int MODE, int TPW>
+// LDS layouts (floats): X tile [BM][2][16] with row stride XS, W tile [Np][2][16] with row stride
+// XS.  Index [.][p][s] holds k = k0 + 2 s + p, so the 16 values a lane feeds to the 16 MFMA steps
+// of a chunk (lanes 0-31 take the even k, lanes 32-63 the odd k) are contiguous: four 16-byte LDS
+// reads.  The stride of 36 floats spreads 16 lanes x 4 banks over all 64 banks.  The weights are
+// stored in global memory already in this order (see xform_weight_index).
+constexpr int XS = 36;
+
+// Compute phase of one k-chunk for the NTW column tiles ct0, ct0 + 2, ... of this wave: all LDS
+// reads of a tile are issued before its 16 back-to-back MFMAs.
+template <int NTW>
+__device__ __forceinline__ void mfma_chunk(const float *Xs, const float *Ws, int rt, int ct0, int l, f16v *acc) {
+  const float *ap = Xs + (rt * 32 + (l & 31)) * XS + (l >> 5) * 16;
+  float a[16];
+#pragma unroll
+  for (int v = 0; v < 4; v++) {
+    float4 t4 = *reinterpret_cast<const float4 *>(ap + 4 * v);
+    a[4 * v] = t4.x; a[4 * v + 1] = t4.y; a[4 * v + 2] = t4.z; a[4 * v + 3] = t4.w;
+  }
+#pragma unroll
+  for (int i = 0; i < NTW; i++) {
+    const float *bp = Ws + ((ct0 + 2 * i) * 32 + (l & 31)) * XS + (l >> 5) * 16;
+    float b[16];
+#pragma unroll
+    for (int v = 0; v < 4; v++) {
+      float4 t4 = *reinterpret_cast<const float4 *>(bp + 4 * v);
+      b[4 * v] = t4.x; b[4 * v + 1] = t4.y; b[4 * v + 2] = t4.z; b[4 * v + 3] = t4.w;
+    }
+#pragma unroll
+    for (int sidx = 0; sidx < 16; sidx++)
+      acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[sidx], b[sidx], acc[i], 0, 0, 0);
+  }
+}
+
+// NT = number of 32-column tiles (Np / 32).  Waves 0,1 take tiles 0,2,4,..; waves 2,3 tiles 1,3,5,..
+template <int MODE, int NT>
 __global__ __launch_bounds__(256) void k_xform(XformArgs x) {
   extern __shared__ float smem[];
-  float *Xs = smem;                           // [BM][KT + 1]
-  float *Ws = smem + BM * (KT + 1);           // [KT][Np]
+  float *Xs = smem;                           // [BM][XS]
+  float *Ws = smem + BM * XS;                 // [Np][XS]
   __shared__ int64_t srow[BM];     // input row (gather) of each tile row, -1 past the end
   __shared__ int64_t sout[BM];     // table row written by the epilogue
   __shared__ int schg[BM];
+  constexpr int TPW = (NT + 1) / 2;
+  constexpr int Np = NT * 32;
   const int t = threadIdx.x, l = t & 63, w = t >> 6;
   const int rt = w & 1;                       // row tile of this wave
   const int ct0 = w >> 1;                     // first column tile; then += 2
-  const int NT = x.Np / 32;
   const int64_t r0 = (int64_t)blockIdx.x * BM;
   if (t < BM) {
     int64_t j = r0 + t;
@@ -138,7 +173,7 @@ __global__ __launch_bounds__(256) void k_xform(XformArgs x) {
     for (int r = 0; r < 16; r++) acc[i][r] = 0.f;
   __syncthreads();
   for (int k0 = 0; k0 < x.Kp; k0 += KT) {
-    {   // stage X: thread -> row t / 4, 8 consecutive k
+    {   // stage X: thread -> row t / 4, 8 consecutive k, split into even and odd k
       int r = t >> 2, ks = (t & 3) * 8;
       int64_t row = srow[r];
       float xv[8];
@@ -148,28 +183,19 @@ __global__ __launch_bounds__(256) void k_xform(XformArgs x) {
         fetch_x4<MODE>(x, row, k0 + ks, xv);
         fetch_x4<MODE>(x, row, k0 + ks + 4, xv + 4);
       }
-#pragma unroll
-      for (int kk = 0; kk < 8; kk++) Xs[r * (KT + 1) + ks + kk] = xv[kk];
+      float *xp = Xs + r * XS + (ks >> 1);
+      *reinterpret_cast<float4 *>(xp) = make_float4(xv[0], xv[2], xv[4], xv[6]);
+      *reinterpret_cast<float4 *>(xp + 16) = make_float4(xv[1], xv[3], xv[5], xv[7]);
     }
-    {   // stage W rows k0 .. k0 + KT (padded matrix: always in bounds)
-      const float4 *src = reinterpret_cast<const float4 *>(x.W + (int64_t)k0 * x.Np);
-      float4 *dst = reinterpret_cast<float4 *>(Ws);
-      int n4 = KT * x.Np / 4;
-      for (int i = t; i < n4; i += 256) dst[i] = src[i];
+    {   // stage the W chunk: global [Np][32] in LDS order -> rows of stride XS
+      const float4 *src = reinterpret_cast<const float4 *>(x.W + (int64_t)k0 * Np);
+      constexpr int n4 = KT * Np / 4;
+#pragma unroll
+      for (int i = t; i < n4; i += 256) *reinterpret_cast<float4 *>(Ws + (i >> 3) * XS + (i & 7) * 4) = src[i];
     }
     __syncthreads();
-#pragma unroll 4
-    for (int kk = 0; kk < KT; kk += 2) {
-      float a = Xs[(rt * 32 + (l & 31)) * (KT + 1) + kk + (l >> 5)];
-#pragma unroll
-      for (int i = 0; i < TPW; i++) {
-        int ct = ct0 + 2 * i;
-        if (ct < NT) {
-          float b = Ws[(kk + (l >> 5)) * x.Np + ct * 32 + (l & 31)];
-          acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc[i], 0, 0, 0);
-        }
-      }
-    }
+    if (ct0 == 0) mfma_chunk<(NT + 1) / 2>(Xs, Ws, rt, 0, l, acc);
+    else if (NT / 2 > 0) mfma_chunk<(NT / 2 > 0 ? NT / 2 : 1)>(Xs, Ws, rt, 1, l, acc);
     __syncthreads();
   }
   // epilogue: lane holds rows 8*(r/4) + 4*(l/32) + r%4 of its row tile, column l % 32 of each tile
@@ -209,14 +235,17 @@ __global__ __launch_bounds__(256) void k_xform(XformArgs x) {
 template <int MODE>
 static hipError_t launch(ink_ctx *c, const XformArgs &x) {
   int NT = x.Np / 32;
-  int tpw = (NT + 1) / 2;
-  size_t sh = (size_t)(BM * (KT + 1) + KT * x.Np) * sizeof(float);
+  size_t sh = (size_t)(BM + x.Np) * XS * sizeof(float);
   dim3 grid((unsigned)((x.n_rows + BM - 1) / BM));
-  switch (tpw) {
+  switch (NT) {
     case 1: hipLaunchKernelGGL((k_xform<MODE, 1>), grid, dim3(256), sh, c->stream, x); break;
     case 2: hipLaunchKernelGGL((k_xform<MODE, 2>), grid, dim3(256), sh, c->stream, x); break;
     case 3: hipLaunchKernelGGL((k_xform<MODE, 3>), grid, dim3(256), sh, c->stream, x); break;
     case 4: hipLaunchKernelGGL((k_xform<MODE, 4>), grid, dim3(256), sh, c->stream, x); break;
+    case 5: hipLaunchKernelGGL((k_xform<MODE, 5>), grid, dim3(256), sh, c->stream, x); break;
+    case 6: hipLaunchKernelGGL((k_xform<MODE, 6>), grid, dim3(256), sh, c->stream, x); break;
+    case 7: hipLaunchKernelGGL((k_xform<MODE, 7>), grid, dim3(256), sh, c->stream, x); break;
+    case 8: hipLaunchKernelGGL((k_xform<MODE, 8>), grid, dim3(256), sh, c->stream, x); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
