@@ -172,18 +172,23 @@ __global__ __launch_bounds__(256) void k_xform(XformArgs x) {
 #pragma unroll
     for (int r = 0; r < 16; r++) acc[i][r] = 0.f;
   __syncthreads();
-  for (int k0 = 0; k0 < x.Kp; k0 += KT) {
-    {   // stage X: thread -> row t / 4, 8 consecutive k, split into even and odd k
-      int r = t >> 2, ks = (t & 3) * 8;
-      int64_t row = srow[r];
-      float xv[8];
+  // thread -> row t / 4, 8 consecutive k of the X chunk; the next chunk's values are fetched into
+  // registers before the MFMA phase so that the gather latency overlaps it
+  const int xr = t >> 2, xks = (t & 3) * 8;
+  const int64_t xrow = srow[xr];
+  float xv[8];
+  auto fetch_chunk = [&](int k0) {
 #pragma unroll
-      for (int kk = 0; kk < 8; kk++) xv[kk] = 0.f;
-      if (row >= 0) {
-        fetch_x4<MODE>(x, row, k0 + ks, xv);
-        fetch_x4<MODE>(x, row, k0 + ks + 4, xv + 4);
-      }
-      float *xp = Xs + r * XS + (ks >> 1);
+    for (int kk = 0; kk < 8; kk++) xv[kk] = 0.f;
+    if (xrow >= 0) {
+      fetch_x4<MODE>(x, xrow, k0 + xks, xv);
+      fetch_x4<MODE>(x, xrow, k0 + xks + 4, xv + 4);
+    }
+  };
+  fetch_chunk(0);
+  for (int k0 = 0; k0 < x.Kp; k0 += KT) {
+    {   // even k first, then odd k
+      float *xp = Xs + xr * XS + (xks >> 1);
       *reinterpret_cast<float4 *>(xp) = make_float4(xv[0], xv[2], xv[4], xv[6]);
       *reinterpret_cast<float4 *>(xp + 16) = make_float4(xv[1], xv[3], xv[5], xv[7]);
     }
@@ -194,6 +199,7 @@ __global__ __launch_bounds__(256) void k_xform(XformArgs x) {
       for (int i = t; i < n4; i += 256) *reinterpret_cast<float4 *>(Ws + (i >> 3) * XS + (i & 7) * 4) = src[i];
     }
     __syncthreads();
+    if (k0 + KT < x.Kp) fetch_chunk(k0 + KT);
     if (ct0 == 0) mfma_chunk<(NT + 1) / 2>(Xs, Ws, rt, 0, l, acc);
     else if (NT / 2 > 0) mfma_chunk<(NT / 2 > 0 ? NT / 2 : 1)>(Xs, Ws, rt, 1, l, acc);
     __syncthreads();
@@ -206,6 +212,14 @@ __global__ __launch_bounds__(256) void k_xform(XformArgs x) {
     int col = ct * 32 + (l & 31);
     if (col >= x.n_out) continue;
     float bias = x.bias ? x.bias[col] : 0.f;
+    float oldv[16];
+    if (x.to_table) {      // all loads of the cached values first, then compare and store
+#pragma unroll
+      for (int r = 0; r < 16; r++) {
+        int rl = rt * 32 + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3);
+        oldv[r] = srow[rl] >= 0 ? x.out[sout[rl] * x.ld_out + col] : 0.f;
+      }
+    }
 #pragma unroll
     for (int r = 0; r < 16; r++) {
       int rl = rt * 32 + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3);
@@ -217,10 +231,9 @@ __global__ __launch_bounds__(256) void k_xform(XformArgs x) {
       if (x.relu) v = v > 0.f ? v : 0.f;
       int64_t j = r0 + rl;
       if (x.to_table) {
-        float *p = x.out + sout[rl] * x.ld_out + col;
-        float old = *p;
+        float old = oldv[r];
         if (x.old_rows) x.old_rows[j * x.ld_old + col] = old;
-        if (__float_as_uint(old) != __float_as_uint(v)) { *p = v; schg[rl] = 1; }
+        if (__float_as_uint(old) != __float_as_uint(v)) { x.out[sout[rl] * x.ld_out + col] = v; schg[rl] = 1; }
       } else {
         x.out[j * x.ld_out + col] = v;
       }
