@@ -140,6 +140,11 @@ typedef struct {
   int64_t n_alpha_changed; /* targets whose alpha changed (not resilient)         Sec. 2.5.2 */
   int64_t n_transformed; /* rows through the dense combination                              */
   int64_t n_changed;     /* rows whose layer output changed: next layer's sources           */
+  /* MAX / MIN only: how the targets that were NOT recomputed split over the conditions of
+   * Sec. 2.5.1 (the distribution of Sec. 5.2); together with n_exposed they sum to n_targets */
+  int64_t n_no_deletion;        /* only additions arrived                                    */
+  int64_t n_deletion_no_effect; /* something was cancelled but no dimension needed a reset   */
+  int64_t n_covered;            /* resets, all covered by added messages                     */
   int32_t dense;         /* 1 if the layer fell back to re-aggregating every node           */
   int32_t pad_;
 } ink_layer_stats;

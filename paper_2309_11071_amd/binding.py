@@ -58,7 +58,8 @@ class _Result(C.Structure):
 class _LayerStats(C.Structure):
     _fields_ = [(k, C.c_int64) for k in ("n_sources", "n_events", "n_targets", "n_exposed",
                                          "n_regather_nb", "n_alpha_changed", "n_transformed",
-                                         "n_changed")] + [("dense", C.c_int32), ("pad_", C.c_int32)]
+                                         "n_changed", "n_no_deletion", "n_deletion_no_effect",
+                                         "n_covered")] + [("dense", C.c_int32), ("pad_", C.c_int32)]
 
 
 class _Stats(C.Structure):

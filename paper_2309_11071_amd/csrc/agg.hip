@@ -254,6 +254,7 @@ __global__ __launch_bounds__(256) void k_agg_events(AggArgs a, const int32_t *ta
   }
   F4 cv; I4 ci;
   bool reset[4] = {false, false, false, false};
+  bool any_del = false;      // the segment cancels something: a removed edge or a changed source
 #pragma unroll
   for (int c = 0; c < 4; c++) { cv.v[c] = worst<IS_MIN>(); ci.v[c] = 0x7fffffff; }
   for (int eb = e0; eb < e1; eb += kWave) {
@@ -274,6 +275,7 @@ __global__ __launch_bounds__(256) void k_agg_events(AggArgs a, const int32_t *ta
         if (k < cntw && lane_on) {
           uint32_t kind = x >> kEvKindShift;
           int uu = (int)(x & kEvIdMask);
+          any_del |= kind != EV_ADD;
           if (kind == EV_DEL) {
 #pragma unroll
             for (int c = 0; c < 4; c++) reset[c] |= (oi.v[c] == uu);
@@ -317,6 +319,15 @@ __global__ __launch_bounds__(256) void k_agg_events(AggArgs a, const int32_t *ta
     }
   }
   exposed = __ballot(exposed && lane_on) != 0ull;
+  {   // condition of this target (Sec. 2.5.1; the distribution shown in Sec. 5.2)
+    bool rs = (reset[0] || reset[1] || reset[2] || reset[3]) && lane_on;
+    bool any_reset = __ballot(rs) != 0ull;
+    bool dl = __ballot(any_del) != 0ull;
+    if (l == 0 && !exposed) {
+      int which = !dl ? ST_NODEL : (!any_reset ? ST_NOEFFECT : ST_COVERED);
+      atomicAdd(&cnt->stripe[blockIdx.x % kStripes][which], 1ull);
+    }
+  }
   if (exposed) {
     int deg = a.in_deg[v];
     if (l == 0) {

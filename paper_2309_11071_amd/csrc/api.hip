@@ -613,6 +613,9 @@ static void layer_stats_from_counters(ink_ctx *c, int l) {
   S.n_exposed = (int64_t)c->h_cnt->sum(ST_EXPOSED);
   S.n_regather_nb = (int64_t)c->h_cnt->sum(ST_REGATHER);
   S.n_alpha_changed = (int64_t)c->h_cnt->sum(ST_ACHG);
+  S.n_no_deletion = (int64_t)c->h_cnt->sum(ST_NODEL);
+  S.n_deletion_no_effect = (int64_t)c->h_cnt->sum(ST_NOEFFECT);
+  S.n_covered = (int64_t)c->h_cnt->sum(ST_COVERED);
 }
 
 // bitmap (plus extra id lists) -> ascending row list in c->c_list; returns the count

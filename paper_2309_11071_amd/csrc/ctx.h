@@ -67,11 +67,11 @@ struct DevLayer {
 };
 
 constexpr int kStripes = 64;
-enum { ST_EXPOSED = 0, ST_REGATHER, ST_ACHG, ST_PAD };
+enum { ST_EXPOSED = 0, ST_REGATHER, ST_ACHG, ST_NODEL, ST_NOEFFECT, ST_COVERED, ST_PAD6, ST_PAD7, ST_N };
 struct Counters {            // device-written, host-read through pinned memory
   int32_t v[32];
   // statistics that many waves bump: striped by workgroup so that no single address is contended
-  unsigned long long stripe[kStripes][4];
+  unsigned long long stripe[kStripes][ST_N];
   unsigned long long sum(int which) const {
     unsigned long long t = 0;
     for (int i = 0; i < kStripes; i++) t += stripe[i][which];

@@ -48,15 +48,25 @@ def test_reset_conditions_on_a_star():
     X[1:7, 1] = [0, 7, 1, 2, 7, 3]
     X[7:, 0] = [10, 9, 8.5, -5, 0, 0]      # spare nodes 7.. used as inserted sources
     X[7:, 1] = [0, 7, 0, -5, 0, 0]
+    X[:, 2:4] = -1.0                        # dimensions 2, 3: leaf 6 holds them throughout
+    X[6, 2:4] = 50.0
     model = tiny_model("sage", "max", (4, 4, 3))
     h = Harness(graph=g, X=X, model=model)
+    def cond():      # (no deletion, deletion without effect, covered, exposed) of layer 1's only target
+        L = h.ink.stats()["layers"][0]
+        assert L["n_targets"] == 1
+        return (L["n_no_deletion"], L["n_deletion_no_effect"], L["n_covered"], L["n_exposed"])
     run(h, [(DEL, 1, 0)])                         # deletion without effect: no reset
+    assert cond() == (0, 1, 0, 0)
     h.check_state()
     run(h, [(DEL, 3, 0), (INS, 7, 0)])            # holder deleted, inserted 10 > 9: covered
+    assert cond() == (0, 0, 1, 0)
     h.check_state()
     run(h, [(DEL, 7, 0), (INS, 9, 0)])            # holder deleted, inserted 8.5 < 10: exposed
+    assert cond() == (0, 0, 0, 1)
     h.check_state()
     run(h, [(INS, 8, 0)])                         # dim 1: 8 ties with value 7 but has a higher id
+    assert cond() == (1, 0, 0, 0)
     h.check_state()
     run(h, [(DEL, 2, 0)])                         # tie holder leaves: next lowest id takes over
     h.check_state()
