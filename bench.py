@@ -89,6 +89,8 @@ def main():
     ap.add_argument("--scale-div", type=int, default=1)
     ap.add_argument("--batch", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--method", choices=["incremental", "affected"], default="incremental",
+                    help="affected: time the affected-area recompute baseline (Sec. 4.1) instead")
     ap.add_argument("--sweep", action="store_true",
                     help="after the timed steps, run 20 seeded batches at each batch size 1..100k and report p50/p99")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -138,8 +140,9 @@ def main():
         torch.mul(a, 1.0, out=b)        # plain elementwise kernel: reads 1 GiB, writes 1 GiB
         torch.cuda.synchronize()
         del a, b
+    aff = args.method == "affected"
     for i in range(args.warmup):
-        ink.apply_updates_device(batches[i].data_ptr(), cfg.batch)
+        ink.apply_updates_device(batches[i].data_ptr(), cfg.batch, affected=aff)
     lat, agg_ms, agg_launches, agg_bytes, changed = [], 0.0, 0, 0, 0
     per_class = {}
     layer_tot = None
@@ -147,7 +150,7 @@ def main():
     t_start = time.perf_counter()
     for i in range(args.warmup, args.warmup + args.steps):
         t1 = time.perf_counter()
-        r = ink.apply_updates_device(batches[i].data_ptr(), cfg.batch)
+        r = ink.apply_updates_device(batches[i].data_ptr(), cfg.batch, affected=aff)
         lat.append(time.perf_counter() - t1)
         st = ink.stats()                      # host-side struct copy, no GPU work
         agg_ms += st["ms"]["agg"]
@@ -182,6 +185,7 @@ def main():
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
+        "method": args.method,
         "config": {"workload": cfg.name, "model": cfg.model, "aggregator": cfg.agg, "nodes": cfg.n_nodes,
                    "edges": int(src.size), "dims": list(cfg.dims), "batch": cfg.batch,
                    "hub_biased_deletes": cfg.hub_biased_deletes},
@@ -212,7 +216,7 @@ def main():
             lt = []
             for t in bl:
                 t1 = time.perf_counter()
-                ink.apply_updates_device(t.data_ptr(), B)
+                ink.apply_updates_device(t.data_ptr(), B, affected=aff)
                 lt.append((time.perf_counter() - t1) * 1e3)
             lt = np.array(lt)
             sweep.append({"batch": B, "p50_ms": float(np.percentile(lt, 50)), "p99_ms": float(np.percentile(lt, 99)),

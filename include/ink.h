@@ -182,6 +182,14 @@ ink_status ink_full_infer(ink_ctx *ctx);
 ink_status ink_apply_updates(ink_ctx *ctx, const ink_edge_update *updates, int64_t n,
                              ink_update_result *out);
 
+/* Baseline for comparison, same arguments and result as ink_apply_updates: the "Affected" method
+ * of Sec. 4.1 (inference on the theoretically affected area; Fig. "Inference on a streaming graph"
+ * (b)).  Every node reached by a changed edge or by an affected node of the previous layer is
+ * recomputed from its whole neighbourhood and re-transformed, and propagates whether or not it
+ * changed.  The cache ends in the same state as after ink_apply_updates. */
+ink_status ink_apply_updates_affected(ink_ctx *ctx, const ink_edge_update *updates, int64_t n,
+                                      ink_update_result *out);
+
 /* Inspection for tests: copies rows [row0, row0 + nrows) of a cached table to dst (host or
  * device per dst_mem), densely packed [nrows][width].  layer in 0..n_layers.
  *   which = 0: h_layer, the output of layer `layer` (layer 0 = input features); it is the

@@ -92,6 +92,8 @@ def load_library():
     lib.ink_full_infer.restype = C.c_int
     lib.ink_apply_updates.argtypes = [vp, vp, C.c_int64, C.POINTER(_Result)]
     lib.ink_apply_updates.restype = C.c_int
+    lib.ink_apply_updates_affected.argtypes = [vp, vp, C.c_int64, C.POINTER(_Result)]
+    lib.ink_apply_updates_affected.restype = C.c_int
     lib.ink_get_layer.argtypes = [vp, C.c_int32, C.c_int32, C.c_int64, C.c_int64, vp, C.c_int32,
                                   C.POINTER(C.c_int32)]
     lib.ink_get_layer.restype = C.c_int
@@ -169,14 +171,14 @@ class Ink:
     def full_infer(self):
         self._check(self._lib.ink_full_infer(self._h))
 
-    def apply_updates(self, updates, fetch=True):
+    def apply_updates(self, updates, fetch=True, affected=False):
         """updates: structured array (EDGE_UPDATE_DTYPE).  Returns dict; with fetch the changed ids
-        and embeddings are copied to host numpy arrays."""
+        and embeddings are copied to host numpy arrays.  affected: run the affected-area baseline."""
         assert not self.batch_device, "context expects device batches"
         updates = np.ascontiguousarray(updates, dtype=EDGE_UPDATE_DTYPE)
         r = _Result()
-        self._check(self._lib.ink_apply_updates(self._h, updates.ctypes.data if updates.size else None,
-                                                updates.size, C.byref(r)))
+        fn = self._lib.ink_apply_updates_affected if affected else self._lib.ink_apply_updates
+        self._check(fn(self._h, updates.ctypes.data if updates.size else None, updates.size, C.byref(r)))
         out = dict(n_changed=r.n_changed, n_applied_ins=r.n_applied_ins, n_applied_del=r.n_applied_del,
                    n_noop=r.n_noop, changed_ids_ptr=r.changed_ids, embeddings_ptr=r.embeddings)
         if fetch:
@@ -188,11 +190,12 @@ class Ink:
             out["changed_ids"], out["embeddings"] = ids, emb
         return out
 
-    def apply_updates_device(self, dev_ptr, n):
+    def apply_updates_device(self, dev_ptr, n, affected=False):
         """Batch already in device memory (context created with batch_device=True); results stay on the device."""
         assert self.batch_device
         r = _Result()
-        self._check(self._lib.ink_apply_updates(self._h, C.c_void_p(dev_ptr), n, C.byref(r)))
+        fn = self._lib.ink_apply_updates_affected if affected else self._lib.ink_apply_updates
+        self._check(fn(self._h, C.c_void_p(dev_ptr), n, C.byref(r)))
         return dict(n_changed=r.n_changed, n_applied_ins=r.n_applied_ins, n_applied_del=r.n_applied_del,
                     n_noop=r.n_noop, changed_ids_ptr=r.changed_ids, embeddings_ptr=r.embeddings)
 

@@ -123,7 +123,8 @@ __device__ __forceinline__ void mark_bit(uint64_t *bm, int v) {
 // ------------------------------------------------------------------ full re-aggregation
 template <bool IS_MIN, int LPR>
 __global__ __launch_bounds__(256) void k_agg_full(AggArgs a, const int32_t *targets, int64_t n_targets,
-                                                  uint64_t *chg, int32_t *big_list, int32_t *n_big, int compare) {
+                                                  uint64_t *chg, int32_t *big_list, int32_t *n_big, int compare,
+                                                  Counters *cnt) {
   const int l = lane_id();
   const int q = l % LPR;
   const bool lane_on = 4 * q < a.ld;
@@ -131,6 +132,7 @@ __global__ __launch_bounds__(256) void k_agg_full(AggArgs a, const int32_t *targ
   if (wid >= n_targets) return;
   int v = targets ? targets[wid] : (int)wid;
   int deg = a.in_deg[v];
+  if (targets && l == 0) atomicAdd(&cnt->stripe[blockIdx.x % kStripes][ST_REGATHER], (unsigned long long)deg);
   if (deg > a.big_deg) {
     if (l == 0) big_list[atomicAdd(n_big, 1)] = v;
     return;
@@ -375,7 +377,7 @@ static hipError_t full_t(ink_ctx *c, const AggArgs &a_in, const int32_t *targets
   INK_TRY(hipMemsetAsync(&c->d_cnt->v[C_NBIG], 0, sizeof(int32_t), c->stream));
   int64_t blocks = (n_targets + 3) / 4;
   hipLaunchKernelGGL((k_agg_full<IS_MIN, LPR>), dim3((unsigned)blocks), dim3(256), 0, c->stream, a, targets, n_targets,
-                     chg, c->big_list.as<int32_t>(), &c->d_cnt->v[C_NBIG], compare);
+                     chg, c->big_list.as<int32_t>(), &c->d_cnt->v[C_NBIG], compare, c->d_cnt);
   INK_TRY(hipGetLastError());
   return run_big<IS_MIN, LPR>(c, a, chg, compare, big_block_threads(n_targets), n_targets);
 }

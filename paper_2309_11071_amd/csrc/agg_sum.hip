@@ -85,7 +85,7 @@ __device__ __forceinline__ bool store_sum(float *A, int ld, int d, int v, bool l
 
 template <int LPR>
 __global__ __launch_bounds__(256) void k_sum_full(AggArgs a, const int32_t *targets, int64_t n_targets, uint64_t *chg,
-                                                  int32_t *big_list, int32_t *n_big, int compare) {
+                                                  int32_t *big_list, int32_t *n_big, int compare, Counters *cnt) {
   const int l = lane_id();
   const int q = l % LPR;
   const bool lane_on = 4 * q < a.ld;
@@ -93,6 +93,7 @@ __global__ __launch_bounds__(256) void k_sum_full(AggArgs a, const int32_t *targ
   if (wid >= n_targets) return;
   int v = targets ? targets[wid] : (int)wid;
   int deg = a.in_deg[v];
+  if (targets && l == 0) atomicAdd(&cnt->stripe[blockIdx.x % kStripes][ST_REGATHER], (unsigned long long)deg);
   if (deg > a.big_deg) {
     if (l == 0) big_list[atomicAdd(n_big, 1)] = v;
     return;
@@ -265,7 +266,7 @@ static hipError_t sum_full_t(ink_ctx *c, const AggArgs &a_in, const int32_t *tar
   INK_TRY(ensure_big_buffers(c, a.ld, false));
   INK_TRY(hipMemsetAsync(&c->d_cnt->v[C_NBIG], 0, sizeof(int32_t), c->stream));
   hipLaunchKernelGGL((k_sum_full<LPR>), dim3((unsigned)((n_targets + 3) / 4)), dim3(256), 0, c->stream, a, targets,
-                     n_targets, chg, c->big_list.as<int32_t>(), &c->d_cnt->v[C_NBIG], compare);
+                     n_targets, chg, c->big_list.as<int32_t>(), &c->d_cnt->v[C_NBIG], compare, c->d_cnt);
   INK_TRY(hipGetLastError());
   const int32_t *list = c->big_list.as<int32_t>();
   int32_t *pref = c->big_pref.as<int32_t>();

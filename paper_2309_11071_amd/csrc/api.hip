@@ -455,10 +455,15 @@ extern "C" void ink_destroy(ink_ctx *c) {
 extern "C" const char *ink_last_error(const ink_ctx *c) { return c ? c->err.c_str() : g_create_err.c_str(); }
 
 // ------------------------------------------------------------------------------------ full inference
-static hipError_t agg_full_any(ink_ctx *c, const AggArgs &a_in, uint64_t *chg) {
-  AggArgs a = a_in;      // every node is recomputed: the chunk count is bounded by the edge count
-  a.big_grid = c->n_edges_now / kBigChunk + std::min<int64_t>(c->n, c->n_edges_now / kBigDeg) + 1;
-  return c->is_select ? agg_select_full(c, a, nullptr, c->n, chg) : agg_sum_full(c, a, nullptr, c->n, chg);
+// recompute of every node (targets == null) or of the listed ones
+static hipError_t agg_full_any(ink_ctx *c, const AggArgs &a_in, uint64_t *chg, const int32_t *targets = nullptr,
+                               int64_t n_targets = -1) {
+  AggArgs a = a_in;
+  if (!targets) {        // every node: the chunk count is bounded by the edge count
+    n_targets = c->n;
+    a.big_grid = c->n_edges_now / kBigChunk + std::min<int64_t>(c->n, c->n_edges_now / kBigDeg) + 1;
+  }
+  return c->is_select ? agg_select_full(c, a, targets, n_targets, chg) : agg_sum_full(c, a, targets, n_targets, chg);
 }
 
 // GCN: message table of layer l + 1 from the finished layer l (rows == null: every node):
@@ -584,6 +589,19 @@ static ink_status layer_aggregate(ink_ctx *c, int l, const int32_t *F, int64_t n
       nT = c->h_cnt->v[C_NT];
     }
   }
+  if (c->affected_mode) {
+    // baseline "Affected" (Sec. 4.1): every node an event reaches is recomputed from its whole
+    // neighbourhood, without looking at the events' content, and counts as affected
+    Prof p(c, INK_T_AGG);
+    if (nE <= kNoSyncEvents) {
+      API_TRY(read_counters(c));
+      nT = c->h_cnt->v[C_NT];
+    }
+    API_TRY(agg_full_any(c, a, bm, c->t_list.as<int32_t>(), nT));
+    if (nT > 0) hipLaunchKernelGGL(k_mark_nodes, grid1(nT), dim3(256), 0, s, (const int32_t *)c->t_list.as<int32_t>(), (int)nT, bm);
+    API_TRY(hipGetLastError());
+    return INK_OK;
+  }
   {
     Prof p(c, INK_T_AGG);
     if (c->is_select) {
@@ -610,6 +628,10 @@ static void layer_stats_from_counters(ink_ctx *c, int l) {
   }
   c->big_hint[l] = c->h_cnt->v[C_NCHUNK];
   S.n_targets = c->h_cnt->v[C_NT];
+  if (c->affected_mode) {
+    S.n_exposed = S.n_targets; S.n_regather_nb = (int64_t)c->h_cnt->sum(ST_REGATHER);
+    return;
+  }
   S.n_exposed = (int64_t)c->h_cnt->sum(ST_EXPOSED);
   S.n_regather_nb = (int64_t)c->h_cnt->sum(ST_REGATHER);
   S.n_alpha_changed = (int64_t)c->h_cnt->sum(ST_ACHG);
@@ -664,8 +686,24 @@ static ink_status emit_changed(ink_ctx *c, int64_t nC, int nxt, bool keep_old, i
   return INK_OK;
 }
 
+static ink_status apply_updates_impl(ink_ctx *c, const ink_edge_update *upd, int64_t n, ink_update_result *out);
+
 extern "C" ink_status ink_apply_updates(ink_ctx *c, const ink_edge_update *upd, int64_t n, ink_update_result *out) {
   if (!c) return INK_E_ARG;
+  c->affected_mode = false;
+  return apply_updates_impl(c, upd, n, out);
+}
+
+extern "C" ink_status ink_apply_updates_affected(ink_ctx *c, const ink_edge_update *upd, int64_t n,
+                                                 ink_update_result *out) {
+  if (!c) return INK_E_ARG;
+  c->affected_mode = true;
+  ink_status st = apply_updates_impl(c, upd, n, out);
+  c->affected_mode = false;
+  return st;
+}
+
+static ink_status apply_updates_impl(ink_ctx *c, const ink_edge_update *upd, int64_t n, ink_update_result *out) {
   if (!out || n < 0 || (n > 0 && !upd)) return fail(c, INK_E_ARG, "ink_apply_updates: NULL argument or negative n");
   if (!c->inferred) return fail(c, INK_E_STATE, "ink_apply_updates: call ink_full_infer first");
   if (n >= (1ll << 30)) return fail(c, INK_E_ARG, "ink_apply_updates: batch too large");
@@ -700,7 +738,7 @@ extern "C" ink_status ink_apply_updates(ink_ctx *c, const ink_edge_update *upd, 
   c->n_edges_now += n_ins - n_del;
   const int64_t n_seed = n_ins + n_del;
   const bool gcn = c->kind == INK_MODEL_GCN;
-  const bool keep_old = !c->is_select;          // sum-type aggregators subtract the old message rows
+  const bool keep_old = !c->is_select && !c->affected_mode;   // delta updates subtract the old message rows
   // nodes whose in-degree may have changed: their normalisation (GCN, mean) changes row-locally
   const int32_t *D = (const int32_t *)c->b_touch_in.p;
   const int64_t nD = (n_seed > 0 && (gcn || c->agg == INK_AGG_MEAN)) ? c->n_touched_in : 0;
@@ -757,6 +795,8 @@ extern "C" ink_status ink_apply_updates(ink_ctx *c, const ink_edge_update *upd, 
           if (!last) API_TRY(gcn_next_messages(c, l, rows, nC, c->c_flag.as<uint8_t>(), old_rows));
           else API_TRY(gcn_final(c, rows, nC, c->c_flag.as<uint8_t>()));
         }
+        // the baseline propagates from every node of the affected area, changed or not
+        if (c->affected_mode && !last) API_TRY(hipMemsetAsync(c->c_flag.p, 1, (size_t)nC, s));
       }
       st = emit_changed(c, nC, nxt, want_old, ld_next, !last, &nF2, &n_chg2);
       if (st != INK_OK) return st;

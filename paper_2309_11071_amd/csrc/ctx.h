@@ -93,6 +93,7 @@ struct ink_ctx {
   int kind = 0, agg = 0, n_layers = 0, mem = 0, profile = 0;
   float eps = 0.f, slack = 0.25f;
   bool batch_dev = false;
+  bool affected_mode = false;        // current call is the affected-area recompute baseline
   bool is_select = true, is_min = false, inferred = false, own_stream = false;
   hipStream_t stream = nullptr;
   std::string err;

@@ -96,3 +96,23 @@ def test_scaled_configs(cfg_id):
     h.check_state(exact=False, tol=TOL)
     h.check_graph()
     h.ink.close()
+
+
+@pytest.mark.parametrize("kind,agg,exact", [("sage", "max", True), ("gin", "sum", False), ("gcn", "gcn_sym", False)])
+def test_affected_area_baseline_reaches_the_same_state(kind, agg, exact):
+    """The affected-area recompute and the incremental update may be interleaved freely."""
+    dims = (10, 12, 6)
+    cfg = synth.WorkloadConfig(6, "t", kind, agg, 2000, 15000, False, dims, 16, 100, False)
+    model = tiny_model(kind, agg, dims, seed=2, hidden=16)
+    src, dst = synth.make_graph(cfg)
+    X = np.random.default_rng(7).standard_normal((cfg.n_nodes, dims[0])).astype(np.float32)
+    h = Harness(cfg=cfg, graph=(cfg.n_nodes, src, dst), X=X, model=model, precision="f32" if exact else "f64",
+                dense_threshold=-1)
+    visited = []
+    for b in range(4):
+        op, bs, bd = h.sampler.next_batch()
+        h.step(op, bs, bd, exact=exact, tol=TOL, affected=(b % 2 == 0))
+        visited.append(sum(L["n_targets"] for L in h.ink.stats()["layers"]))
+        h.check_state(exact=exact, tol=TOL)
+    h.check_graph()
+    h.ink.close()

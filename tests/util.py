@@ -79,9 +79,9 @@ class Harness:
         rp2, col2 = oracle.csr_from_keys(self.n, self.keys)
         assert np.array_equal(rp, rp2) and np.array_equal(col, col2), "graph store differs from the oracle's edge set"
 
-    def step(self, op, bs, bd, exact=True, tol=1e-5):
+    def step(self, op, bs, bd, exact=True, tol=1e-5, affected=False):
         from paper_2309_11071_amd.binding import make_updates
-        res = self.ink.apply_updates(make_updates(op, bs, bd))
+        res = self.ink.apply_updates(make_updates(op, bs, bd), affected=affected)
         keys2, n_ins, n_del, n_noop = oracle.apply_batch(self.keys, op, bs, bd)
         assert (res["n_applied_ins"], res["n_applied_del"], res["n_noop"]) == (n_ins, n_del, n_noop)
         post = oracle.full_infer(*oracle.csr_from_keys(self.n, keys2), self.X, self.model, self.precision)
