@@ -1,0 +1,76 @@
+"""Randomised update streams with many degenerate entries (duplicates, cancelling pairs, self
+loops, deletes of absent edges, repeated touches of one node) against the oracle, and the drift of
+the delta-accumulated sums over a long sequence (Sec. 7 warns that the loss grows)."""
+import numpy as np
+import pytest
+
+import synth
+from util import Harness, scaled_rel_err
+from test_gpu_edge_cases import tiny_model
+
+pytestmark = pytest.mark.gpu
+
+
+def messy_batch(rng, n, keys, size):
+    """Random ops biased towards a few nodes and towards edges that already exist."""
+    src, dst = synth.keys_to_edges(keys)
+    hot = rng.integers(0, n, size=6)
+    op = rng.integers(0, 2, size=size).astype(np.uint8)
+    s = rng.integers(0, n, size=size).astype(np.int32)
+    d = rng.integers(0, n, size=size).astype(np.int32)
+    pick = rng.random(size)
+    ex = rng.integers(0, src.size, size=size)
+    use_existing = pick < 0.45
+    s[use_existing], d[use_existing] = src[ex[use_existing]], dst[ex[use_existing]]
+    to_hot = (pick >= 0.45) & (pick < 0.75)
+    d[to_hot] = hot[rng.integers(0, hot.size, size=int(to_hot.sum()))]
+    from_hot = (pick >= 0.75) & (pick < 0.85)
+    s[from_hot] = hot[rng.integers(0, hot.size, size=int(from_hot.sum()))]
+    loops = pick >= 0.97
+    d[loops] = s[loops]
+    # repeat a prefix so that the same edges appear several times with different ops
+    k = size // 4
+    s[-k:], d[-k:] = s[:k], d[:k]
+    return op, s, d
+
+
+@pytest.mark.parametrize("kind,agg,exact", [("sage", "max", True), ("gin", "min", True), ("gin", "sum", False),
+                                            ("gcn", "gcn_sym", False), ("sage", "mean", False)])
+def test_messy_update_streams(kind, agg, exact):
+    dims = (9, 10, 7)
+    n = 600
+    cfg = synth.WorkloadConfig(8, "t", kind, agg, n, 5000, False, dims, 12, 50, False)
+    src, dst = synth.make_graph(cfg)
+    rng = np.random.default_rng(11)
+    X = rng.integers(-3, 4, size=(n, dims[0])).astype(np.float32)       # many exact ties
+    h = Harness(cfg=cfg, graph=(n, src, dst), X=X, model=tiny_model(kind, agg, dims, seed=3, hidden=12),
+                precision="f32" if exact else "f64", slack=0.05)
+    for b in range(8):
+        op, s, d = messy_batch(rng, n, h.keys, int(rng.integers(1, 400)))
+        h.step(op, s, d, exact=exact, tol=1e-5)
+        h.check_graph()
+    h.check_state(exact=exact, tol=1e-5)
+    h.ink.close()
+
+
+def test_sum_drift_over_a_long_sequence():
+    cfg = synth.WorkloadConfig(8, "t", "gin", "sum", 4000, 40000, False, (16, 16, 16, 8), 16, 100, False)
+    src, dst = synth.make_graph(cfg)
+    X = np.random.default_rng(2).standard_normal((cfg.n_nodes, 16)).astype(np.float32)
+    h = Harness(cfg=cfg, graph=(cfg.n_nodes, src, dst), X=X, model=tiny_model("gin", "sum", cfg.dims, 5, 16),
+                precision="f64", dense_threshold=-1)
+    import oracle
+    from paper_2309_11071_amd.binding import make_updates
+    errs = []
+    for b in range(40):
+        op, bs, bd = h.sampler.next_batch()
+        h.ink.apply_updates(make_updates(op, bs, bd))
+        h.keys, _, _, _ = oracle.apply_batch(h.keys, op, bs, bd)
+        if b % 10 == 9:
+            ref = oracle.full_infer(*oracle.csr_from_keys(h.n, h.keys), h.X, h.model, "f64")
+            errs.append(scaled_rel_err(h.ink.get_layer(3, 0), ref["h"][3]))
+    assert max(errs) <= 1e-5, errs
+    h.ink.full_infer()                       # rebuilding the cache removes the accumulated loss
+    ref = oracle.full_infer(*oracle.csr_from_keys(h.n, h.keys), h.X, h.model, "f64")
+    assert scaled_rel_err(h.ink.get_layer(3, 0), ref["h"][3]) <= max(errs) + 1e-7
+    h.ink.close()
