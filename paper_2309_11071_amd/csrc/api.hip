@@ -364,6 +364,10 @@ extern "C" ink_status ink_create(const ink_csr *g, const float *features, int32_
   size_t bmw = ((size_t)n + 63) / 64;
   CREATE_TRY(hipMalloc(&c->bm_a, bmw * 8));
   CREATE_TRY(hipMemset(c->bm_a, 0, bmw * 8));
+  if (opts && opts->max_batch > 0) {       // size the batch staging up front
+    CREATE_TRY(c->b_raw.reserve((size_t)opts->max_batch * sizeof(ink_edge_update)));
+    CREATE_TRY(c->b_misc.reserve((((size_t)opts->max_batch + 64) * 4 + 255) / 256 * 256 * 28));
+  }
   CREATE_TRY(c->big_list.reserve((size_t)(c->gin.pool_cap / kBigDeg + 4096) * 4));
   // tables
   c->H.resize(c->n_layers + 1); c->A.resize(c->n_layers + 1); c->ARG.resize(c->n_layers + 1);
@@ -439,12 +443,11 @@ extern "C" void ink_destroy(ink_ctx *c) {
   if (c->d_cnt) (void)hipFree(c->d_cnt);
   if (c->h_cnt) (void)hipHostFree(c->h_cnt);
   if (c->bm_a) (void)hipFree(c->bm_a);
-  if (c->bm_b) (void)hipFree(c->bm_b);
   for (DevBuf *b : {&c->ws.blk, &c->ws.hist, &c->ws.tmpk, &c->ws.tmpv, &c->b_raw, &c->b_misc, &c->b_uniq, &c->b_del_s,
                     &c->b_del_d, &c->b_ins_s, &c->b_ins_d, &c->f_list[0], &c->f_list[1], &c->f_old[0], &c->f_old[1],
                     &c->f_pref, &c->ev_key, &c->ev_val, &c->t_list, &c->t_seg, &c->c_list, &c->c_flag, &c->c_idx, &c->c_old,
                     &c->b_touch_in,
-                    &c->big_list, &c->big_part_v, &c->big_part_i, &c->big_deg, &c->big_pref, &c->f_delta, &c->stage0, &c->stage1, &c->res_ids, &c->res_emb})
+                    &c->big_list, &c->big_part_v, &c->big_part_i, &c->big_pref, &c->f_delta, &c->stage0, &c->stage1, &c->res_ids, &c->res_emb})
     b->release();
   for (auto e : c->ev_free) (void)hipEventDestroy(e);
   for (auto &p : c->ev_pending) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }

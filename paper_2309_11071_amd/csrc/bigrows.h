@@ -11,9 +11,6 @@ namespace ink {
 #ifndef INK_BIG_LB
 #define INK_BIG_LB 1024
 #endif
-#ifndef INK_BIG_GRID_CAP
-#define INK_BIG_GRID_CAP (1 << 30)
-#endif
 
 constexpr int kBigGrid = 4096;             // workgroups of the per-row combine kernel
 
@@ -28,7 +25,6 @@ inline unsigned big_partial_grid(const ink_ctx *c, int64_t want, int block_threa
   int64_t lo = block_threads >= 1024 ? 512 : 2048, hi = big_chunk_capacity(c);
   if (want < lo) want = lo;
   if (want > hi) want = hi;
-  if (want > INK_BIG_GRID_CAP) want = INK_BIG_GRID_CAP;
   return (unsigned)want;
 }
 

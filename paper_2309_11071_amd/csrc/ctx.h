@@ -78,8 +78,11 @@ struct Counters {            // device-written, host-read through pinned memory
     return t;
   }
 };
-enum { C_NF = 0, C_NEV, C_NT, C_NBIG, C_NC, C_NEXT, C_NCHUNK, C_SPARE, C_TMP0, C_TMP1, C_TMP2, C_TMP3,
-       C_REGATHER_LO = 16, C_REGATHER_HI = 17, C_BIGWORK = 18 };
+// slots of Counters::v: event count of the next layer, unique targets, long rows listed, rows to
+// transform, rows changed, chunks of long rows, distinct ops of a batch, scratch of the graph stage,
+// and a 64-bit slot (pool top handed to the apply kernel)
+enum { C_NEV = 1, C_NT, C_NBIG, C_NC, C_NEXT, C_NCHUNK, C_NOPS, C_TMP0, C_TMP1, C_TMP2, C_TMP3,
+       C_TOP64 = 16 };
 
 }  // namespace ink
 
@@ -112,11 +115,10 @@ struct ink_ctx {
   ink::Counters *h_cnt = nullptr;    // pinned host mirror
   unsigned long long h_top = 0;      // staging for the device copy of a pool top
   uint64_t *bm_a = nullptr;          // node bitmaps (n bits each)
-  uint64_t *bm_b = nullptr;
 
-  // batch buffers (sized for max_batch, grown on demand)
+  // batch buffers (grown on demand)
   int64_t n_touched_src = 0;         // sources whose out-block got new ids in the current batch
-  ink::DevBuf b_raw, b_k0, b_k1, b_v0, b_v1, b_op, b_eff, b_pos, b_seg, b_uniq, b_misc;
+  ink::DevBuf b_raw, b_uniq, b_misc;
   int32_t *del_src = nullptr, *del_dst = nullptr, *ins_src = nullptr, *ins_dst = nullptr;  // Delta E lists
   ink::DevBuf b_del_s, b_del_d, b_ins_s, b_ins_d;
   int64_t n_del = 0, n_ins = 0;
@@ -132,7 +134,7 @@ struct ink_ctx {
   ink::DevBuf c_old;                 // previous table rows of the transformed rows (sum-type)
   ink::DevBuf b_touch_in;            // destinations touched by the current batch
   int64_t n_touched_in = 0;
-  ink::DevBuf big_list, big_part_v, big_part_i, big_deg, big_pref;   // cooperative re-gather
+  ink::DevBuf big_list, big_part_v, big_part_i, big_pref;   // cooperative re-gather of long rows
   ink::DevBuf stage0, stage1;        // transform staging
   ink::DevBuf res_ids, res_emb;      // result of the last batch
 

@@ -420,7 +420,7 @@ static ink_status apply_side(ink_ctx *c, GraphSide &g, SideBufs &b, int64_t n_op
     INK_TRYS(e);
   }
   // device copy of the pool top lives in the counter block (64-bit slot)
-  unsigned long long *d_top = (unsigned long long *)&dc->v[C_REGATHER_LO];
+  unsigned long long *d_top = (unsigned long long *)&dc->v[C_TOP64];
   c->h_top = (unsigned long long)g.pool_top;
   INK_TRYS(hipMemcpyAsync(d_top, &c->h_top, sizeof(unsigned long long), hipMemcpyHostToDevice, s));
   hipLaunchKernelGGL(k_apply, dim3(n_touched), dim3(256), 0, s, (const int32_t *)b.uniq, (const int32_t *)b.seg,
@@ -455,7 +455,7 @@ ink_status graph_apply_batch(ink_ctx *c, int64_t n, int64_t *n_ins_out, int64_t 
   b.chunk_pref = ar.get<int32_t>(n + 1); b.nd_ins = ar.get<int32_t>(n + 1); b.nd_del = ar.get<int32_t>(n + 1);
   b.fill = ar.get<int32_t>(n + 1);
   Counters *dc = c->d_cnt;
-  int32_t *n_ops_d = &dc->v[C_SPARE];
+  int32_t *n_ops_d = &dc->v[C_NOPS];
 
   // (dst, src, position) order through two stable sorts
   hipLaunchKernelGGL(k_unpack, grid1(n), dim3(256), 0, s, raw, n, srcv, dstv, v0);
