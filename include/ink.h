@@ -24,8 +24,8 @@
  *   - Node ids are int32 in [0, n_nodes); the graph is a simple directed graph without self
  *     loops; n_nodes is fixed for the life of the context (the paper updates edges only,
  *     Sec. 2.1).  Edge (u -> v) makes u an in-neighbour of v: v aggregates m_u.
- *   - All matrices are row-major float32.  Aggregated widths (the width of m_l at every
- *     layer) must be <= INK_MAX_AGG_DIM.
+ *   - All matrices are row-major float32.  Layer outputs are at most INK_MAX_OUT_DIM wide, layer
+ *     inputs (the feature width in particular) at most INK_MAX_IN_DIM.
  */
 #ifndef INK_H
 #define INK_H
@@ -37,7 +37,8 @@
 extern "C" {
 #endif
 
-#define INK_MAX_AGG_DIM 256
+#define INK_MAX_OUT_DIM 256
+#define INK_MAX_IN_DIM 16384
 #define INK_MAX_LAYERS 8
 
 typedef struct ink_ctx ink_ctx; /* opaque; owns all device state */

@@ -127,7 +127,7 @@ __global__ __launch_bounds__(256) void k_agg_full(AggArgs a, const int32_t *targ
                                                   Counters *cnt) {
   const int l = lane_id();
   const int q = l % LPR;
-  const bool lane_on = 4 * q < a.ld;
+  const bool lane_on = 4 * q < a.wd;
   int64_t wid = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kWave;
   if (wid >= n_targets) return;
   int v = targets ? targets[wid] : (int)wid;
@@ -165,7 +165,7 @@ __global__ __launch_bounds__(INK_BIG_LB) void k_big_partial(AggArgs a, const int
   __shared__ int si[kBigMaxWaves][kWave * 4];
   const int l = lane_id(), w = threadIdx.x / kWave, nw = blockDim.x / kWave;
   const int q = l % LPR;
-  const bool lane_on = 4 * q < a.ld;
+  const bool lane_on = 4 * q < a.wd;
   const int total = *total_p, n_big = *n_big_p;
   for (int cg = blockIdx.x; cg < total; cg += gridDim.x) {
     int i, v;
@@ -184,7 +184,7 @@ __global__ __launch_bounds__(INK_BIG_LB) void k_big_partial(AggArgs a, const int
 #pragma unroll
         for (int c = 0; c < 4; c++) take<IS_MIN>(sv[ww][l * 4 + c], si[ww][l * 4 + c], bv.v[c], bi.v[c]);
       if (lane_on && l < LPR) {
-        int64_t o = (int64_t)cg * a.ld + 4 * q;
+        int64_t o = (int64_t)cg * a.wd + 4 * q;
 #pragma unroll
         for (int c = 0; c < 4; c++) { part_v[o + c] = bv.v[c]; part_i[o + c] = bi.v[c]; }
       }
@@ -200,7 +200,7 @@ __global__ __launch_bounds__(64) void k_big_final(AggArgs a, const int32_t *big_
                                                   uint64_t *chg, int compare, Counters *cnt) {
   const int l = lane_id();
   const int q = l % LPR;
-  const bool lane_on = 4 * q < a.ld;
+  const bool lane_on = 4 * q < a.wd;
   const int n_big = *n_big_p;
   for (int i = blockIdx.x; i < n_big; i += gridDim.x) {
     int v = big_list[i];
@@ -209,7 +209,7 @@ __global__ __launch_bounds__(64) void k_big_final(AggArgs a, const int32_t *big_
     for (int c = 0; c < 4; c++) { bv.v[c] = worst<IS_MIN>(); bi.v[c] = 0x7fffffff; }
     if (lane_on && l < LPR) {
       for (int p = pref[i]; p < pref[i + 1]; p++) {
-        int64_t o = (int64_t)p * a.ld + 4 * q;
+        int64_t o = (int64_t)p * a.wd + 4 * q;
 #pragma unroll
         for (int c = 0; c < 4; c++) take<IS_MIN>(part_v[o + c], part_i[o + c], bv.v[c], bi.v[c]);
       }
@@ -240,7 +240,7 @@ __global__ __launch_bounds__(256) void k_agg_events(AggArgs a, const int32_t *ta
   constexpr int G = kWave / LPR;
   const int l = lane_id();
   const int q = l % LPR, g = l / LPR;
-  const bool lane_on = 4 * q < a.ld;
+  const bool lane_on = 4 * q < a.wd;
   int64_t wid = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kWave;
   if (wid >= *n_targets_p) return;
   int v = targets[wid];
@@ -373,7 +373,7 @@ static hipError_t full_t(ink_ctx *c, const AggArgs &a_in, const int32_t *targets
   AggArgs a = a_in;
   a.big_deg = big_threshold(n_targets, LPR);
   int compare = chg != nullptr;
-  INK_TRY(ensure_big_buffers(c, a.ld, true));
+  INK_TRY(ensure_big_buffers(c, a.wd, true));
   INK_TRY(hipMemsetAsync(&c->d_cnt->v[C_NBIG], 0, sizeof(int32_t), c->stream));
   int64_t blocks = (n_targets + 3) / 4;
   hipLaunchKernelGGL((k_agg_full<IS_MIN, LPR>), dim3((unsigned)blocks), dim3(256), 0, c->stream, a, targets, n_targets,
@@ -389,7 +389,7 @@ static hipError_t events_t(ink_ctx *c, const AggArgs &a_in, const int32_t *targe
   if (n_targets <= 0) return hipSuccess;
   AggArgs a = a_in;
   a.big_deg = big_threshold(n_targets, LPR);
-  INK_TRY(ensure_big_buffers(c, a.ld, true));
+  INK_TRY(ensure_big_buffers(c, a.wd, true));
   int64_t blocks = (n_targets + 3) / 4;
   hipLaunchKernelGGL((k_agg_events<IS_MIN, LPR>), dim3((unsigned)blocks), dim3(256), 0, c->stream, a, targets, seg,
                      n_targets_dev, ev, chg, c->big_list.as<int32_t>(), c->d_cnt);
@@ -399,7 +399,7 @@ static hipError_t events_t(ink_ctx *c, const AggArgs &a_in, const int32_t *targe
 
 #define DISPATCH(fn, ...)                                                         \
   do {                                                                            \
-    int lpr_ = lanes_per_row(a.ld);                                               \
+    int lpr_ = lanes_per_row(a.wd);                                               \
     if (a.is_min) {                                                               \
       if (lpr_ == 16) return fn<true, 16>(__VA_ARGS__);                           \
       if (lpr_ == 32) return fn<true, 32>(__VA_ARGS__);                           \

@@ -88,7 +88,7 @@ __global__ __launch_bounds__(256) void k_sum_full(AggArgs a, const int32_t *targ
                                                   int32_t *big_list, int32_t *n_big, int compare, Counters *cnt) {
   const int l = lane_id();
   const int q = l % LPR;
-  const bool lane_on = 4 * q < a.ld;
+  const bool lane_on = 4 * q < a.wd;
   int64_t wid = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kWave;
   if (wid >= n_targets) return;
   int v = targets ? targets[wid] : (int)wid;
@@ -110,7 +110,7 @@ __global__ __launch_bounds__(INK_BIG_LB) void k_sum_big_partial(AggArgs a, const
   __shared__ float sv[kBigMaxWaves][kWave * 4];
   const int l = lane_id(), w = threadIdx.x / kWave, nw = blockDim.x / kWave;
   const int q = l % LPR;
-  const bool lane_on = 4 * q < a.ld;
+  const bool lane_on = 4 * q < a.wd;
   const int total = *total_p, n_big = *n_big_p;
   for (int cg = blockIdx.x; cg < total; cg += gridDim.x) {
     int i, v;
@@ -129,7 +129,7 @@ __global__ __launch_bounds__(INK_BIG_LB) void k_sum_big_partial(AggArgs a, const
 #pragma unroll
         for (int c = 0; c < 4; c++) acc.v[c] = __fadd_rn(acc.v[c], sv[ww][l * 4 + c]);
       if (lane_on && l < LPR) {
-        int64_t o = (int64_t)cg * a.ld + 4 * q;
+        int64_t o = (int64_t)cg * a.wd + 4 * q;
 #pragma unroll
         for (int c = 0; c < 4; c++) part[o + c] = acc.v[c];
       }
@@ -144,7 +144,7 @@ __global__ __launch_bounds__(64) void k_sum_big_final(AggArgs a, const int32_t *
                                                       int compare) {
   const int l = lane_id();
   const int q = l % LPR;
-  const bool lane_on = 4 * q < a.ld;
+  const bool lane_on = 4 * q < a.wd;
   const int n_big = *n_big_p;
   for (int i = blockIdx.x; i < n_big; i += gridDim.x) {
     int v = big_list[i];
@@ -153,7 +153,7 @@ __global__ __launch_bounds__(64) void k_sum_big_final(AggArgs a, const int32_t *
     for (int c = 0; c < 4; c++) acc.v[c] = 0.f;
     if (lane_on && l < LPR) {
       for (int p = pref[i]; p < pref[i + 1]; p++) {
-        int64_t o = (int64_t)p * a.ld + 4 * q;
+        int64_t o = (int64_t)p * a.wd + 4 * q;
 #pragma unroll
         for (int c = 0; c < 4; c++) acc.v[c] = __fadd_rn(acc.v[c], part[o + c]);
       }
@@ -190,7 +190,7 @@ __global__ __launch_bounds__(256) void k_sum_events(AggArgs a, const int32_t *ta
   constexpr int G = kWave / LPR;
   const int l = lane_id();
   const int q = l % LPR, g = l / LPR;
-  const bool lane_on = 4 * q < a.ld;
+  const bool lane_on = 4 * q < a.wd;
   int64_t wid = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kWave;
   if (wid >= *n_targets_p) return;
   int v = targets[wid];
@@ -263,7 +263,7 @@ static hipError_t sum_full_t(ink_ctx *c, const AggArgs &a_in, const int32_t *tar
   AggArgs a = a_in;
   a.big_deg = big_threshold(n_targets, LPR);
   int compare = chg != nullptr;
-  INK_TRY(ensure_big_buffers(c, a.ld, false));
+  INK_TRY(ensure_big_buffers(c, a.wd, false));
   INK_TRY(hipMemsetAsync(&c->d_cnt->v[C_NBIG], 0, sizeof(int32_t), c->stream));
   hipLaunchKernelGGL((k_sum_full<LPR>), dim3((unsigned)((n_targets + 3) / 4)), dim3(256), 0, c->stream, a, targets,
                      n_targets, chg, c->big_list.as<int32_t>(), &c->d_cnt->v[C_NBIG], compare, c->d_cnt);
@@ -291,7 +291,7 @@ static hipError_t sum_events_t(ink_ctx *c, const AggArgs &a, const int32_t *targ
 }
 
 hipError_t agg_sum_full(ink_ctx *c, const AggArgs &a, const int32_t *targets, int64_t n_targets, uint64_t *chg) {
-  switch (lanes_per_row(a.ld)) {
+  switch (lanes_per_row(a.wd)) {
     case 16: return sum_full_t<16>(c, a, targets, n_targets, chg);
     case 32: return sum_full_t<32>(c, a, targets, n_targets, chg);
     default: return sum_full_t<64>(c, a, targets, n_targets, chg);
@@ -301,7 +301,7 @@ hipError_t agg_sum_full(ink_ctx *c, const AggArgs &a, const int32_t *targets, in
 hipError_t agg_sum_events(ink_ctx *c, const AggArgs &a, const int32_t *targets, const int32_t *seg,
                           int64_t n_targets, const int32_t *n_targets_dev, const uint32_t *ev_val, const int32_t *F,
                           int nF, const float *f_old, const float *f_delta, int ld_old, uint64_t *chg) {
-  switch (lanes_per_row(a.ld)) {
+  switch (lanes_per_row(a.wd)) {
     case 16: return sum_events_t<16>(c, a, targets, seg, n_targets, n_targets_dev, ev_val, F, nF, f_old, f_delta, ld_old, chg);
     case 32: return sum_events_t<32>(c, a, targets, seg, n_targets, n_targets_dev, ev_val, F, nF, f_old, f_delta, ld_old, chg);
     default: return sum_events_t<64>(c, a, targets, seg, n_targets, n_targets_dev, ev_val, F, nF, f_old, f_delta, ld_old, chg);

@@ -238,6 +238,7 @@ static AggArgs agg_args(ink_ctx *c, int l) {       // layer l in 1..k
   const Table &M = msg_table(c, l);
   a.M = M.f(); a.ldm = M.ld;
   a.A = c->A[l].f(); a.ARG = c->is_select ? c->ARG[l].i() : nullptr; a.ld = c->A[l].ld; a.d = c->A[l].d;
+  a.wd = round_up(a.d, 4);
   a.is_min = c->is_min;
   a.big_deg = kBigDeg;
   a.big_grid = 2 * c->big_hint[l] + 1024;
@@ -292,7 +293,8 @@ static ink_status validate_model(const ink_model *m, int feat_dim, std::string &
     const ink_layer &L = m->layers[l];
     if (L.in_dim != d) { why = "layer in_dim does not match the previous width"; return INK_E_ARG; }
     int agg_w = m->kind == INK_MODEL_GCN ? L.out_dim : L.in_dim;      // GCN aggregates after the linear map
-    if (L.in_dim < 1 || L.out_dim < 1 || agg_w > INK_MAX_AGG_DIM || L.out_dim > 256 || L.in_dim > 16384) { why = "layer width out of range"; return INK_E_ARG; }
+    (void)agg_w;
+    if (L.in_dim < 1 || L.out_dim < 1 || L.out_dim > INK_MAX_OUT_DIM || L.in_dim > INK_MAX_IN_DIM) { why = "layer width out of range"; return INK_E_ARG; }
     if (!L.W_neigh) { why = "W_neigh is NULL"; return INK_E_ARG; }
     if (m->kind == INK_MODEL_SAGE && !L.W_self) { why = "GraphSAGE needs W_self"; return INK_E_ARG; }
     if (m->kind == INK_MODEL_GIN && (!L.W_mlp2 || L.mlp_hidden < 1 || L.mlp_hidden > 256)) { why = "GIN needs W_mlp2 and 1 <= mlp_hidden <= 256"; return INK_E_ARG; }
@@ -458,6 +460,20 @@ extern "C" void ink_destroy(ink_ctx *c) {
 extern "C" const char *ink_last_error(const ink_ctx *c) { return c ? c->err.c_str() : g_create_err.c_str(); }
 
 // ------------------------------------------------------------------------------------ full inference
+// Aggregated rows wider than one wave covers (256 floats) are handled one 256-column block at a
+// time: the aggregators act per dimension, so the blocks are independent.
+constexpr int kAggBlock = 256;
+static int agg_blocks(const AggArgs &a) { return (a.d + kAggBlock - 1) / kAggBlock; }
+static AggArgs agg_block(const AggArgs &a, int b) {
+  AggArgs r = a;
+  int c0 = b * kAggBlock;
+  r.M += c0; r.A += c0;
+  if (r.ARG) r.ARG += c0;
+  r.d = std::min(kAggBlock, a.d - c0);
+  r.wd = round_up(r.d, 4);
+  return r;
+}
+
 // recompute of every node (targets == null) or of the listed ones
 static hipError_t agg_full_any(ink_ctx *c, const AggArgs &a_in, uint64_t *chg, const int32_t *targets = nullptr,
                                int64_t n_targets = -1) {
@@ -466,7 +482,13 @@ static hipError_t agg_full_any(ink_ctx *c, const AggArgs &a_in, uint64_t *chg, c
     n_targets = c->n;
     a.big_grid = c->n_edges_now / kBigChunk + std::min<int64_t>(c->n, c->n_edges_now / kBigDeg) + 1;
   }
-  return c->is_select ? agg_select_full(c, a, targets, n_targets, chg) : agg_sum_full(c, a, targets, n_targets, chg);
+  for (int b = 0; b < agg_blocks(a); b++) {
+    AggArgs ab = agg_block(a, b);
+    hipError_t e = c->is_select ? agg_select_full(c, ab, targets, n_targets, chg)
+                                : agg_sum_full(c, ab, targets, n_targets, chg);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 // GCN: message table of layer l + 1 from the finished layer l (rows == null: every node):
@@ -607,16 +629,21 @@ static ink_status layer_aggregate(ink_ctx *c, int l, const int32_t *F, int64_t n
   }
   {
     Prof p(c, INK_T_AGG);
-    if (c->is_select) {
-      API_TRY(agg_select_events(c, a, c->t_list.as<int32_t>(), c->t_seg.as<int32_t>(), nT, &dc->v[C_NT],
-                                c->ev_val.as<uint32_t>(), bm));
-    } else {
-      if (nF > 0) {
-        API_TRY(c->f_delta.reserve((size_t)nF * ld_old * 4));
-        API_TRY(agg_sum_delta_rows(c, a, F, (int)nF, f_old, c->f_delta.as<float>(), ld_old));
-      }
-      API_TRY(agg_sum_events(c, a, c->t_list.as<int32_t>(), c->t_seg.as<int32_t>(), nT, &dc->v[C_NT],
-                             c->ev_val.as<uint32_t>(), F, (int)nF, f_old, c->f_delta.as<float>(), ld_old, bm));
+    if (!c->is_select && nF > 0) {
+      API_TRY(c->f_delta.reserve((size_t)nF * ld_old * 4));
+      API_TRY(agg_sum_delta_rows(c, a, F, (int)nF, f_old, c->f_delta.as<float>(), ld_old));
+    }
+    for (int b = 0; b < agg_blocks(a); b++) {
+      AggArgs ab = agg_block(a, b);
+      int c0 = b * kAggBlock;
+      if (b > 0) API_TRY(hipMemsetAsync(&dc->v[C_NBIG], 0, sizeof(int32_t), s));
+      if (c->is_select)
+        API_TRY(agg_select_events(c, ab, c->t_list.as<int32_t>(), c->t_seg.as<int32_t>(), nT, &dc->v[C_NT],
+                                  c->ev_val.as<uint32_t>(), bm));
+      else
+        API_TRY(agg_sum_events(c, ab, c->t_list.as<int32_t>(), c->t_seg.as<int32_t>(), nT, &dc->v[C_NT],
+                               c->ev_val.as<uint32_t>(), F, (int)nF, f_old ? f_old + c0 : nullptr,
+                               c->f_delta.as<float>() ? c->f_delta.as<float>() + c0 : nullptr, ld_old, bm));
     }
   }
   return INK_OK;

@@ -159,7 +159,8 @@ struct AggArgs {
   const int64_t *in_off; const int32_t *in_deg; const int32_t *in_ids;
   const float *M; int ldm;          // message table
   float *A; int32_t *ARG; int ld;   // aggregated table and argument table (row stride ld)
-  int d;
+  int d;                            // columns handled by this launch (<= 256; wider rows go block by block)
+  int wd;                           // d rounded up to 4
   bool is_min;
   int big_deg;                      // rows with more in-neighbours go to the chunked cooperative path
   int64_t big_grid;                 // workgroups to launch for the chunk kernel (it strides if there are more chunks)

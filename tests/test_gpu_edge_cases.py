@@ -113,6 +113,8 @@ def test_first_and_last_edge_of_a_node():
     ("sage", "max", (16, 16, 16, 16)),    # three layers
     ("gin", "max", (12, 20, 9)),
     ("gin", "min", (64, 64, 64)),
+    ("sage", "max", (602, 64, 8)),        # feature rows wider than one wave covers: column blocks
+    ("gin", "max", (300, 40, 6)),
 ])
 def test_random_sequences(kind, agg, dims):
     cfg = synth.WorkloadConfig(6, "t", kind, agg, 3000, 20000, False, tuple(dims), 24, 300, True)

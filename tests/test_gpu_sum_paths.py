@@ -19,6 +19,8 @@ TOL = 1e-5
     ("gcn", "gcn_sym", (40, 24, 7)),
     ("gcn", "gcn_sym", (70, 256, 41)),
     ("gcn", "gcn_sym", (12, 8, 8, 5)),
+    ("gin", "sum", (500, 32, 8)),          # aggregated rows wider than 256 floats
+    ("sage", "mean", (602, 24, 8)),
 ])
 def test_random_sequences(kind, agg, dims):
     cfg = synth.WorkloadConfig(6, "t", kind, agg, 3000, 20000, False, tuple(dims), 24, 200, False)
