@@ -392,8 +392,8 @@ static ink_status apply_side(ink_ctx *c, GraphSide &g, SideBufs &b, int64_t n_op
                              int32_t *new_cnt, int *n_touched_out, int64_t *tot_ins, int64_t *tot_del) {
   hipStream_t s = c->stream;
   Counters *dc = c->d_cnt;
-  INK_TRYS(hipMemsetAsync(&dc->v[C_TMP0], 0, 4 * sizeof(int32_t), s));
-  INK_TRYS(hipMemsetAsync(&dc->stripe[0][0], 0, sizeof(dc->stripe), s));
+  // scratch slots, the 64-bit slot and the stripes in one fill (the batch's op count sits before them)
+  INK_TRYS(hipMemsetAsync(&dc->v[C_TMP0], 0, sizeof(Counters) - C_TMP0 * sizeof(int32_t), s));
   INK_TRYS(segment_heads(c->ws, b.node, n_ops_max, b.uniq, b.seg, &dc->v[C_TMP0], s, n_ops_dev));
   hipLaunchKernelGGL(k_chunk_counts, grid1(n_ops_max), dim3(256), 0, s, (const int32_t *)b.uniq,
                      (const int32_t *)&dc->v[C_TMP0], n_ops_max, (const int32_t *)g.deg, b.chunks);

@@ -158,7 +158,11 @@ __global__ __launch_bounds__(kSortThreads) void k_radix_scatter(const uint32_t *
 constexpr int kSmallItems = 16;
 constexpr int kSmallSort = kSortThreads * kSmallItems;     // 4096 pairs, 64 KB of LDS
 
+// ITEMS keys per thread: n <= 256 * ITEMS
+template <int ITEMS>
 __global__ __launch_bounds__(kSortThreads) void k_small_sort(uint32_t *keys, uint32_t *vals, int n, int passes) {
+  constexpr int kSmallItems = ITEMS;
+  constexpr int kSmallSort = kSortThreads * ITEMS;
   __shared__ uint32_t sk[2][kSmallSort];
   __shared__ uint32_t sv[2][kSmallSort];
   __shared__ int cnt[kSortWaves][kRadix];
@@ -235,7 +239,12 @@ hipError_t radix_sort_pairs(PrimWorkspace &ws, uint32_t *keys, uint32_t *vals, i
   if (n <= 1 || bits <= 0) return hipSuccess;
   int passes = (bits + kRadixBits - 1) / kRadixBits;
   if (n <= kSmallSort) {
-    hipLaunchKernelGGL(k_small_sort, dim3(1), dim3(kSortThreads), 0, s, keys, vals, (int)n, passes);
+    if (n <= kSortThreads)
+      hipLaunchKernelGGL((k_small_sort<1>), dim3(1), dim3(kSortThreads), 0, s, keys, vals, (int)n, passes);
+    else if (n <= 4 * kSortThreads)
+      hipLaunchKernelGGL((k_small_sort<4>), dim3(1), dim3(kSortThreads), 0, s, keys, vals, (int)n, passes);
+    else
+      hipLaunchKernelGGL((k_small_sort<kSmallItems>), dim3(1), dim3(kSortThreads), 0, s, keys, vals, (int)n, passes);
     return hipGetLastError();
   }
   int nb = nblocks(n, kSortTile);
