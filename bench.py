@@ -203,6 +203,13 @@ def main():
         "changed_nodes_per_step": changed / args.steps,
         "full_inference_s": t_full,
         "full_inference_agg_ms": full_stats["ms"]["agg"],
+        # the recompute kernels at their largest shape: every edge gathers one id and one message row,
+        # every node writes its aggregate (and argument) row
+        "full_inference_roofline": (lambda b, ms: {"bound": "hbm", "achieved": b / 1e9 / (ms / 1e3), "peak": HBM_PEAK_GBS,
+                                                   "unit": "GB/s", "frac": b / 1e9 / (ms / 1e3) / HBM_PEAK_GBS,
+                                                   "algorithmic_bytes": b})(
+            sum(int(src.size) * (4 + 4 * d) + cfg.n_nodes * (8 if cfg.agg in ("max", "min") else 4) * d
+                for d in ink.agg_widths), max(full_stats["ms"]["agg"], 1e-6)),
     }
     if args.sweep:
         sweep = []
