@@ -200,6 +200,9 @@ ink_status ink_apply_updates_affected(ink_ctx *ctx, const ink_edge_update *updat
  *              sum over in-neighbours u of c_u (h_{layer-1} W_layer)_u with c = dhat^(-1/2)
  *              (the row-local factor c_v and the self term are applied when h is formed).
  *   which = 2: int32 argmax/argmin neighbour ids of layer `layer` >= 1 (MAX / MIN only).
+ *   which = 3: MAX / MIN only: the cached bound on the best value among the neighbours other
+ *              than the holder (>= it for MAX, <= it for MIN; -inf / +inf if there is none).  It is
+ *              exact after a recompute and may be loose afterwards; it never affects results.
  * width is returned in *width_out if not NULL. */
 ink_status ink_get_layer(ink_ctx *ctx, int32_t layer, int32_t which, int64_t row0, int64_t nrows,
                          void *dst, int32_t dst_mem, int32_t *width_out);

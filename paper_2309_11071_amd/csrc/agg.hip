@@ -3,6 +3,12 @@
 // update with reset detection (Sec. 2.5.1).  One wave64 owns one target row; a lane holds four
 // consecutive dimensions, so a row of d floats occupies LPR = 16/32/64 lanes and a wave works on
 // 64 / LPR neighbour rows at a time.  Rows are read as coalesced 16-byte lane loads.
+//
+// Next to the selected value and its holder the cache keeps, per dimension, a bound on the best
+// value among the OTHER neighbours (exact after a recompute, afterwards only ever loosened).  A
+// holder that got worse but still strictly beats that bound stays the holder, and a candidate that
+// strictly beats it covers a reset even if it is worse than the old value: both save the
+// recompute that the value-only rule of Sec. 2.5.1 would need.
 #include "bigrows.h"
 
 namespace ink {
@@ -23,32 +29,48 @@ template <bool IS_MIN> __device__ __forceinline__ void take(float x, int id, flo
   if (better<IS_MIN>(x, bv) || (x == bv && id < bi)) { bv = x; bi = id; }
 }
 
+template <bool IS_MIN> __device__ __forceinline__ float best_of(float x, float y) { return better<IS_MIN>(x, y) ? x : y; }
+// the same with the runner-up value sv (best value among the entries that are not the holder)
+template <bool IS_MIN> __device__ __forceinline__ void take2(float x, int id, float &bv, int &bi, float &sv) {
+  if (better<IS_MIN>(x, bv) || (x == bv && id < bi)) { sv = bv; bv = x; bi = id; }
+  else if (better<IS_MIN>(x, sv)) sv = x;
+}
+// merge of the triples of two disjoint sets
+template <bool IS_MIN> __device__ __forceinline__ void merge2(float ov, int oi, float os, float &bv, int &bi, float &sv) {
+  float loser;
+  if (better<IS_MIN>(ov, bv) || (ov == bv && oi < bi)) { loser = bv; bv = ov; bi = oi; }
+  else loser = ov;
+  sv = best_of<IS_MIN>(loser, best_of<IS_MIN>(sv, os));
+}
+
 __device__ __forceinline__ float4 ld4(const float *p) { return *reinterpret_cast<const float4 *>(p); }
 
 // Reduce (bv, bi) over the lane groups of a wave (groups are LPR lanes wide); every lane ends
 // with the result for its 4 dimensions.
-template <bool IS_MIN, int LPR> __device__ __forceinline__ void reduce_groups(F4 &bv, I4 &bi) {
+template <bool IS_MIN, int LPR> __device__ __forceinline__ void reduce_groups(F4 &bv, I4 &bi, F4 &sv) {
 #pragma unroll
   for (int off = LPR; off < kWave; off <<= 1) {
 #pragma unroll
     for (int c = 0; c < 4; c++) {
       float ov = __shfl_xor(bv.v[c], off, kWave);
       int oi = __shfl_xor(bi.v[c], off, kWave);
-      take<IS_MIN>(ov, oi, bv.v[c], bi.v[c]);
+      float os = __shfl_xor(sv.v[c], off, kWave);
+      merge2<IS_MIN>(ov, oi, os, bv.v[c], bi.v[c], sv.v[c]);
     }
   }
 }
 
 // Selection over neighbours ids[j0 .. j1) of one row, by the whole wave.  On return every lane
-// holds the best (value, id) of its 4 dimensions over the range; (worst, INT_MAX) if empty.
+// holds the best (value, id) and the runner-up value of its 4 dimensions over the range;
+// (worst, INT_MAX, worst) if empty.
 template <bool IS_MIN, int LPR>
 __device__ __forceinline__ void gather_range(const int32_t *ids, int64_t j0, int64_t j1, const float *M,
-                                             int ldm, bool lane_on, int q, F4 &bv, I4 &bi) {
+                                             int ldm, bool lane_on, int q, F4 &bv, I4 &bi, F4 &sv) {
   constexpr int G = kWave / LPR;
   const int l = lane_id();
   const int g = l / LPR;
 #pragma unroll
-  for (int c = 0; c < 4; c++) { bv.v[c] = worst<IS_MIN>(); bi.v[c] = 0x7fffffff; }
+  for (int c = 0; c < 4; c++) { bv.v[c] = worst<IS_MIN>(); bi.v[c] = 0x7fffffff; sv.v[c] = worst<IS_MIN>(); }
   for (int64_t jb = j0; jb < j1; jb += kWave) {
     int64_t jj = jb + l;
     int myid = jj < j1 ? ids[jj] : -1;
@@ -67,29 +89,31 @@ __device__ __forceinline__ void gather_range(const int32_t *ids, int64_t j0, int
 #pragma unroll
       for (int u = 0; u < U; u++) {
         if (id[u] >= 0 && lane_on) {
-          take<IS_MIN>(row[u].x, id[u], bv.v[0], bi.v[0]);
-          take<IS_MIN>(row[u].y, id[u], bv.v[1], bi.v[1]);
-          take<IS_MIN>(row[u].z, id[u], bv.v[2], bi.v[2]);
-          take<IS_MIN>(row[u].w, id[u], bv.v[3], bi.v[3]);
+          take2<IS_MIN>(row[u].x, id[u], bv.v[0], bi.v[0], sv.v[0]);
+          take2<IS_MIN>(row[u].y, id[u], bv.v[1], bi.v[1], sv.v[1]);
+          take2<IS_MIN>(row[u].z, id[u], bv.v[2], bi.v[2], sv.v[2]);
+          take2<IS_MIN>(row[u].w, id[u], bv.v[3], bi.v[3], sv.v[3]);
         }
       }
     }
   }
-  reduce_groups<IS_MIN, LPR>(bv, bi);
+  reduce_groups<IS_MIN, LPR>(bv, bi, sv);
 }
 
 struct RowOut {
-  float *A; int32_t *ARG; int ld; int d;
+  float *A; int32_t *ARG; float *UB; int ld; int d;
 };
 
 // Writes (bv, bi) as the new aggregated row of v if it differs from what is stored; returns
 // (wave-uniform) whether any VALUE of the first d dimensions changed bitwise.
 template <int LPR>
 __device__ __forceinline__ bool store_row(const RowOut &o, int v, bool lane_on, int q, const F4 &bv,
-                                          const I4 &bi, bool have_old, const F4 &ov, const I4 &oi) {
+                                          const I4 &bi, const F4 &sv, bool have_old, const F4 &ov, const I4 &oi) {
   const int l = lane_id();
   bool writer = lane_on && l < LPR;
   bool vchg = false, ichg = false;
+  if (writer)      // the bound is rewritten unconditionally (it never decides whether a row "changed")
+    *reinterpret_cast<float4 *>(o.UB + (int64_t)v * o.ld + 4 * q) = make_float4(sv.v[0], sv.v[1], sv.v[2], sv.v[3]);
   if (writer) {
     F4 cv = ov; I4 ci = oi;
     if (!have_old) {
@@ -111,9 +135,10 @@ __device__ __forceinline__ bool store_row(const RowOut &o, int v, bool lane_on, 
   return __ballot(vchg) != 0ull;
 }
 
-__device__ __forceinline__ void finish_empty(F4 &bv, I4 &bi) {   // no in-neighbours: alpha = 0, arg = -1
+template <bool IS_MIN>
+__device__ __forceinline__ void finish_empty(F4 &bv, I4 &bi, F4 &sv) {   // no in-neighbours: alpha = 0, arg = -1
 #pragma unroll
-  for (int c = 0; c < 4; c++) if (bi.v[c] == 0x7fffffff) { bv.v[c] = 0.f; bi.v[c] = -1; }
+  for (int c = 0; c < 4; c++) if (bi.v[c] == 0x7fffffff) { bv.v[c] = 0.f; bi.v[c] = -1; sv.v[c] = worst<IS_MIN>(); }
 }
 
 __device__ __forceinline__ void mark_bit(uint64_t *bm, int v) {
@@ -138,17 +163,18 @@ __global__ __launch_bounds__(256) void k_agg_full(AggArgs a, const int32_t *targ
     return;
   }
   int64_t off = a.in_off[v];
-  F4 bv; I4 bi;
-  gather_range<IS_MIN, LPR>(a.in_ids + off, 0, deg, a.M, a.ldm, lane_on, q, bv, bi);
-  finish_empty(bv, bi);
-  RowOut o{a.A, a.ARG, a.ld, a.d};
+  F4 bv; I4 bi; F4 sv;
+  gather_range<IS_MIN, LPR>(a.in_ids + off, 0, deg, a.M, a.ldm, lane_on, q, bv, bi, sv);
+  finish_empty<IS_MIN>(bv, bi, sv);
+  RowOut o{a.A, a.ARG, a.UB, a.ld, a.d};
   F4 dum; I4 dumi;
   bool ch;
-  if (compare) ch = store_row<LPR>(o, v, lane_on, q, bv, bi, false, dum, dumi);
+  if (compare) ch = store_row<LPR>(o, v, lane_on, q, bv, bi, sv, false, dum, dumi);
   else {
     if (lane_on && l < LPR) {
       *reinterpret_cast<float4 *>(a.A + (int64_t)v * a.ld + 4 * q) = make_float4(bv.v[0], bv.v[1], bv.v[2], bv.v[3]);
       *reinterpret_cast<int4 *>(a.ARG + (int64_t)v * a.ld + 4 * q) = make_int4(bi.v[0], bi.v[1], bi.v[2], bi.v[3]);
+      *reinterpret_cast<float4 *>(a.UB + (int64_t)v * a.ld + 4 * q) = make_float4(sv.v[0], sv.v[1], sv.v[2], sv.v[3]);
     }
     ch = false;
   }
@@ -160,9 +186,10 @@ __global__ __launch_bounds__(256) void k_agg_full(AggArgs a, const int32_t *targ
 template <bool IS_MIN, int LPR>
 __global__ __launch_bounds__(INK_BIG_LB) void k_big_partial(AggArgs a, const int32_t *big_list, const int32_t *n_big_p,
                                                       const int32_t *pref, const int32_t *total_p, float *part_v,
-                                                      int32_t *part_i) {
+                                                      int32_t *part_i, float *part_s) {
   __shared__ float sv[kBigMaxWaves][kWave * 4];
   __shared__ int si[kBigMaxWaves][kWave * 4];
+  __shared__ float ss[kBigMaxWaves][kWave * 4];
   const int l = lane_id(), w = threadIdx.x / kWave, nw = blockDim.x / kWave;
   const int q = l % LPR;
   const bool lane_on = 4 * q < a.wd;
@@ -174,19 +201,20 @@ __global__ __launch_bounds__(INK_BIG_LB) void k_big_partial(AggArgs a, const int
     int64_t off = a.in_off[v];
     int64_t len = j1 - j0;
     int64_t w0 = j0 + len * w / nw, w1 = j0 + len * (w + 1) / nw;
-    F4 bv; I4 bi;
-    gather_range<IS_MIN, LPR>(a.in_ids + off, w0, w1, a.M, a.ldm, lane_on, q, bv, bi);
+    F4 bv; I4 bi; F4 s2;
+    gather_range<IS_MIN, LPR>(a.in_ids + off, w0, w1, a.M, a.ldm, lane_on, q, bv, bi, s2);
 #pragma unroll
-    for (int c = 0; c < 4; c++) { sv[w][l * 4 + c] = bv.v[c]; si[w][l * 4 + c] = bi.v[c]; }
+    for (int c = 0; c < 4; c++) { sv[w][l * 4 + c] = bv.v[c]; si[w][l * 4 + c] = bi.v[c]; ss[w][l * 4 + c] = s2.v[c]; }
     __syncthreads();
     if (w == 0) {
       for (int ww = 1; ww < nw; ww++)
 #pragma unroll
-        for (int c = 0; c < 4; c++) take<IS_MIN>(sv[ww][l * 4 + c], si[ww][l * 4 + c], bv.v[c], bi.v[c]);
+        for (int c = 0; c < 4; c++)
+          merge2<IS_MIN>(sv[ww][l * 4 + c], si[ww][l * 4 + c], ss[ww][l * 4 + c], bv.v[c], bi.v[c], s2.v[c]);
       if (lane_on && l < LPR) {
         int64_t o = (int64_t)cg * a.wd + 4 * q;
 #pragma unroll
-        for (int c = 0; c < 4; c++) { part_v[o + c] = bv.v[c]; part_i[o + c] = bi.v[c]; }
+        for (int c = 0; c < 4; c++) { part_v[o + c] = bv.v[c]; part_i[o + c] = bi.v[c]; part_s[o + c] = s2.v[c]; }
       }
     }
     __syncthreads();
@@ -197,27 +225,27 @@ __global__ __launch_bounds__(INK_BIG_LB) void k_big_partial(AggArgs a, const int
 template <bool IS_MIN, int LPR>
 __global__ __launch_bounds__(64) void k_big_final(AggArgs a, const int32_t *big_list, const int32_t *n_big_p,
                                                   const int32_t *pref, const float *part_v, const int32_t *part_i,
-                                                  uint64_t *chg, int compare, Counters *cnt) {
+                                                  const float *part_s, uint64_t *chg, int compare, Counters *cnt) {
   const int l = lane_id();
   const int q = l % LPR;
   const bool lane_on = 4 * q < a.wd;
   const int n_big = *n_big_p;
   for (int i = blockIdx.x; i < n_big; i += gridDim.x) {
     int v = big_list[i];
-    F4 bv; I4 bi;
+    F4 bv; I4 bi; F4 s2;
 #pragma unroll
-    for (int c = 0; c < 4; c++) { bv.v[c] = worst<IS_MIN>(); bi.v[c] = 0x7fffffff; }
+    for (int c = 0; c < 4; c++) { bv.v[c] = worst<IS_MIN>(); bi.v[c] = 0x7fffffff; s2.v[c] = worst<IS_MIN>(); }
     if (lane_on && l < LPR) {
       for (int p = pref[i]; p < pref[i + 1]; p++) {
         int64_t o = (int64_t)p * a.wd + 4 * q;
 #pragma unroll
-        for (int c = 0; c < 4; c++) take<IS_MIN>(part_v[o + c], part_i[o + c], bv.v[c], bi.v[c]);
+        for (int c = 0; c < 4; c++) merge2<IS_MIN>(part_v[o + c], part_i[o + c], part_s[o + c], bv.v[c], bi.v[c], s2.v[c]);
       }
     }
-    finish_empty(bv, bi);
-    RowOut o{a.A, a.ARG, a.ld, a.d};
+    finish_empty<IS_MIN>(bv, bi, s2);
+    RowOut o{a.A, a.ARG, a.UB, a.ld, a.d};
     F4 dum; I4 dumi;
-    bool ch = store_row<LPR>(o, v, lane_on, q, bv, bi, false, dum, dumi);
+    bool ch = store_row<LPR>(o, v, lane_on, q, bv, bi, s2, false, dum, dumi);
     if (compare && ch && chg && l == 0) {
       mark_bit(chg, v);
       atomicAdd(&cnt->stripe[blockIdx.x % kStripes][ST_ACHG], 1ull);
@@ -245,20 +273,22 @@ __global__ __launch_bounds__(256) void k_agg_events(AggArgs a, const int32_t *ta
   if (wid >= *n_targets_p) return;
   int v = targets[wid];
   int e0 = seg[wid], e1 = seg[wid + 1];
-  F4 ov; I4 oi;
+  F4 ov; I4 oi; F4 ou;       // cached value, holder and bound on the other neighbours
 #pragma unroll
-  for (int c = 0; c < 4; c++) { ov.v[c] = 0.f; oi.v[c] = -1; }
+  for (int c = 0; c < 4; c++) { ov.v[c] = 0.f; oi.v[c] = -1; ou.v[c] = worst<IS_MIN>(); }
   if (lane_on) {
     float4 x = ld4(a.A + (int64_t)v * a.ld + 4 * q);
     int4 y = *reinterpret_cast<const int4 *>(a.ARG + (int64_t)v * a.ld + 4 * q);
+    float4 z = ld4(a.UB + (int64_t)v * a.ld + 4 * q);
     ov.v[0] = x.x; ov.v[1] = x.y; ov.v[2] = x.z; ov.v[3] = x.w;
     oi.v[0] = y.x; oi.v[1] = y.y; oi.v[2] = y.z; oi.v[3] = y.w;
+    ou.v[0] = z.x; ou.v[1] = z.y; ou.v[2] = z.z; ou.v[3] = z.w;
   }
-  F4 cv; I4 ci;
+  F4 cv; I4 ci; F4 cs;       // best candidate, its source, runner-up candidate value
   bool reset[4] = {false, false, false, false};
   bool any_del = false;      // the segment cancels something: a removed edge or a changed source
 #pragma unroll
-  for (int c = 0; c < 4; c++) { cv.v[c] = worst<IS_MIN>(); ci.v[c] = 0x7fffffff; }
+  for (int c = 0; c < 4; c++) { cv.v[c] = worst<IS_MIN>(); ci.v[c] = 0x7fffffff; cs.v[c] = worst<IS_MIN>(); }
   for (int eb = e0; eb < e1; eb += kWave) {
     int ee = eb + l;
     uint32_t mine = ee < e1 ? ev[ee] : 0xFFFFFFFFu;
@@ -295,7 +325,7 @@ __global__ __launch_bounds__(256) void k_agg_events(AggArgs a, const int32_t *ta
 #pragma unroll
         for (int c = 0; c < 4; c++) {
           if (chgk[u] && oi.v[c] == src[u] && better<IS_MIN>(ov.v[c], r[c])) reset[c] = true;
-          take<IS_MIN>(r[c], src[u], cv.v[c], ci.v[c]);
+          take2<IS_MIN>(r[c], src[u], cv.v[c], ci.v[c], cs.v[c]);
         }
       }
     }
@@ -305,19 +335,29 @@ __global__ __launch_bounds__(256) void k_agg_events(AggArgs a, const int32_t *ta
   for (int off = LPR; off < kWave; off <<= 1)
 #pragma unroll
     for (int c = 0; c < 4; c++) reset[c] |= (bool)__shfl_xor((int)reset[c], off, kWave);
-  reduce_groups<IS_MIN, LPR>(cv, ci);
-  F4 nv = ov; I4 ni = oi;
+  reduce_groups<IS_MIN, LPR>(cv, ci, cs);
+  F4 nv = ov; I4 ni = oi; F4 nu = ou;
   bool exposed = false;
 #pragma unroll
   for (int c = 0; c < 4; c++) {
-    bool has_cand = ci.v[c] != 0x7fffffff;
+    const bool has_cand = ci.v[c] != 0x7fffffff;
     if (oi.v[c] < 0) {                       // no neighbours before this batch
-      if (has_cand) { nv.v[c] = cv.v[c]; ni.v[c] = ci.v[c]; }
+      if (has_cand) { nv.v[c] = cv.v[c]; ni.v[c] = ci.v[c]; nu.v[c] = cs.v[c]; }
     } else if (reset[c]) {
-      if (has_cand && better<IS_MIN>(cv.v[c], ov.v[c])) { nv.v[c] = cv.v[c]; ni.v[c] = ci.v[c]; }
-      else exposed = true;
+      // the holder left or got worse (then its new value is one of the candidates): every other
+      // old neighbour is bounded by ou, so a candidate that strictly beats ou is the new selection
+      if (has_cand && better<IS_MIN>(cv.v[c], ou.v[c])) {
+        nv.v[c] = cv.v[c]; ni.v[c] = ci.v[c]; nu.v[c] = best_of<IS_MIN>(ou.v[c], cs.v[c]);
+      } else exposed = true;
     } else if (has_cand) {
-      take<IS_MIN>(cv.v[c], ci.v[c], nv.v[c], ni.v[c]);
+      if (ci.v[c] == oi.v[c]) {              // the holder itself, unchanged or better at this dimension
+        nv.v[c] = cv.v[c]; nu.v[c] = best_of<IS_MIN>(ou.v[c], cs.v[c]);
+      } else if (better<IS_MIN>(cv.v[c], ov.v[c]) || (cv.v[c] == ov.v[c] && ci.v[c] < oi.v[c])) {
+        nv.v[c] = cv.v[c]; ni.v[c] = ci.v[c];          // the old holder joins the others
+        nu.v[c] = best_of<IS_MIN>(best_of<IS_MIN>(ou.v[c], ov.v[c]), cs.v[c]);
+      } else {
+        nu.v[c] = best_of<IS_MIN>(ou.v[c], cv.v[c]);
+      }
     }
   }
   exposed = __ballot(exposed && lane_on) != 0ull;
@@ -340,11 +380,11 @@ __global__ __launch_bounds__(256) void k_agg_events(AggArgs a, const int32_t *ta
       if (l == 0) big_list[atomicAdd(&cnt->v[C_NBIG], 1)] = v;
       return;
     }
-    gather_range<IS_MIN, LPR>(a.in_ids + a.in_off[v], 0, deg, a.M, a.ldm, lane_on, q, nv, ni);
-    finish_empty(nv, ni);
+    gather_range<IS_MIN, LPR>(a.in_ids + a.in_off[v], 0, deg, a.M, a.ldm, lane_on, q, nv, ni, nu);
+    finish_empty<IS_MIN>(nv, ni, nu);
   }
-  RowOut o{a.A, a.ARG, a.ld, a.d};
-  bool ch = store_row<LPR>(o, v, lane_on, q, nv, ni, true, ov, oi);
+  RowOut o{a.A, a.ARG, a.UB, a.ld, a.d};
+  bool ch = store_row<LPR>(o, v, lane_on, q, nv, ni, nu, true, ov, oi);
   if (ch && l == 0) { mark_bit(chg, v); atomicAdd(&cnt->stripe[blockIdx.x % kStripes][ST_ACHG], 1ull); }
 }
 
@@ -360,10 +400,11 @@ static hipError_t run_big(ink_ctx *c, const AggArgs &a, uint64_t *chg, int compa
   INK_TRY(plan_big_rows(c, n_rows_max, a.in_deg));
   hipLaunchKernelGGL((k_big_partial<IS_MIN, LPR>), dim3(big_partial_grid(c, a.big_grid, block_threads)), dim3(block_threads), 0, c->stream, a, list,
                      (const int32_t *)n_big, (const int32_t *)pref, (const int32_t *)total, c->big_part_v.as<float>(),
-                     c->big_part_i.as<int32_t>());
+                     c->big_part_i.as<int32_t>(), c->big_part_s.as<float>());
   hipLaunchKernelGGL((k_big_final<IS_MIN, LPR>), dim3(kBigGrid), dim3(64), 0, c->stream, a, list,
                      (const int32_t *)n_big, (const int32_t *)pref, (const float *)c->big_part_v.as<float>(),
-                     (const int32_t *)c->big_part_i.as<int32_t>(), chg, compare, c->d_cnt);
+                     (const int32_t *)c->big_part_i.as<int32_t>(), (const float *)c->big_part_s.as<float>(), chg, compare,
+                     c->d_cnt);
   return hipGetLastError();
 }
 

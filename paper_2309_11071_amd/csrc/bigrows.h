@@ -36,7 +36,10 @@ inline hipError_t ensure_big_buffers(ink_ctx *c, int ld, bool with_ids) {
   INK_TRY(c->big_pref.reserve((size_t)(c->big_list.cap / 4 + 1) * 4));
   int64_t cap = big_chunk_capacity(c);
   INK_TRY(c->big_part_v.reserve((size_t)cap * ld * sizeof(float)));
-  if (with_ids) INK_TRY(c->big_part_i.reserve((size_t)cap * ld * sizeof(int32_t)));
+  if (with_ids) {
+    INK_TRY(c->big_part_i.reserve((size_t)cap * ld * sizeof(int32_t)));
+    INK_TRY(c->big_part_s.reserve((size_t)cap * ld * sizeof(float)));
+  }
   return hipSuccess;
 }
 

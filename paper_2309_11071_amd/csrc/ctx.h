@@ -105,7 +105,7 @@ struct ink_ctx {
   int32_t *new_out = nullptr;        // [n] out-edges appended by the current batch (tail of the block)
   std::vector<ink::DevLayer> layers;
   // tables: H[0..k]; A[1..k] aggregated (sum-type: plain sums); ARG[1..k]
-  std::vector<ink::Table> H, A, ARG;
+  std::vector<ink::Table> H, A, ARG, UB;   // UB: max/min only, bound on the runner-up value
   // GCN only: XW[l] = unscaled transformed messages h_{l-1} W_l, H-like scaled copies live in Msc[l]
   std::vector<ink::Table> XW, Msc;
   float *cnorm = nullptr;            // GCN: (indeg + 1)^(-1/2) per node
@@ -134,7 +134,7 @@ struct ink_ctx {
   ink::DevBuf c_old;                 // previous table rows of the transformed rows (sum-type)
   ink::DevBuf b_touch_in;            // destinations touched by the current batch
   int64_t n_touched_in = 0;
-  ink::DevBuf big_list, big_part_v, big_part_i, big_pref;   // cooperative re-gather of long rows
+  ink::DevBuf big_list, big_part_v, big_part_i, big_part_s, big_pref;   // cooperative re-gather of long rows
   ink::DevBuf stage0, stage1;        // transform staging
   ink::DevBuf res_ids, res_emb;      // result of the last batch
 
@@ -159,6 +159,7 @@ struct AggArgs {
   const int64_t *in_off; const int32_t *in_deg; const int32_t *in_ids;
   const float *M; int ldm;          // message table
   float *A; int32_t *ARG; int ld;   // aggregated table and argument table (row stride ld)
+  float *UB;                        // max/min: bound on the best value among the non-holders (same layout)
   int d;                            // columns handled by this launch (<= 256; wider rows go block by block)
   int wd;                           // d rounded up to 4
   bool is_min;

@@ -62,7 +62,10 @@ def test_reset_conditions_on_a_star():
     run(h, [(DEL, 3, 0), (INS, 7, 0)])            # holder deleted, inserted 10 > 9: covered
     assert cond() == (0, 0, 1, 0)
     h.check_state()
-    run(h, [(DEL, 7, 0), (INS, 9, 0)])            # holder deleted, inserted 8.5 < 10: exposed
+    run(h, [(DEL, 7, 0), (INS, 9, 0)])            # holder deleted, inserted 8.5 < 10 but above every other
+    assert cond() == (0, 0, 1, 0)                 # neighbour: covered thanks to the cached runner-up bound
+    h.check_state()
+    run(h, [(DEL, 9, 0), (INS, 10, 0)])           # holder deleted, inserted -5 is below the others: exposed
     assert cond() == (0, 0, 0, 1)
     h.check_state()
     run(h, [(INS, 8, 0)])                         # dim 1: 8 ties with value 7 but has a higher id
@@ -72,7 +75,7 @@ def test_reset_conditions_on_a_star():
     h.check_state()
     run(h, [(DEL, 5, 0), (INS, 2, 0)])            # holder deleted, equal value comes back: not strictly covered
     h.check_state()
-    run(h, [(INS, 10, 0)])                        # insertion that changes nothing: resilient target
+    run(h, [(INS, 11, 0)])                        # insertion that changes nothing: resilient target
     h.check_state()
     h.check_graph()
     h.ink.close()
@@ -125,10 +128,12 @@ def test_random_sequences(kind, agg, dims):
     X[rng.random(X.shape) < 0.3] = 0.0                      # exact ties
     h = Harness(cfg=cfg, graph=(cfg.n_nodes, src, dst), X=X, model=model)
     h.check_state()
+    h.check_bound(exact=True)
     for b in range(4):
         op, bs, bd = h.sampler.next_batch()
         h.step(op, bs, bd)
         h.check_state()
+        h.check_bound()
     h.check_graph()
     h.ink.close()
 

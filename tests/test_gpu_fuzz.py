@@ -49,6 +49,7 @@ def test_messy_update_streams(kind, agg, exact):
         op, s, d = messy_batch(rng, n, h.keys, int(rng.integers(1, 400)))
         h.step(op, s, d, exact=exact, tol=1e-5)
         h.check_graph()
+        h.check_bound()
     h.check_state(exact=exact, tol=1e-5)
     h.ink.close()
 

@@ -74,6 +74,32 @@ class Harness:
                     assert np.array_equal(a.view(np.uint32), self.ref["alpha"][l].view(np.uint32)), "alpha_%d" % l
                     assert np.array_equal(g, self.ref["arg"][l]), "argmax_%d differs" % l
 
+    def check_bound(self, exact=False, max_nodes=4000):
+        """The cached bound on the runner-up value (get_layer which=3) must dominate the best value
+        among the neighbours other than the holder; right after a full inference it is exact."""
+        if self.model["agg"] not in ("max", "min") or self.n > max_nodes:
+            return
+        is_min = self.model["agg"] == "min"
+        rp, col = oracle.csr_from_keys(self.n, self.keys)
+        for l in range(1, len(self.model["layers"]) + 1):
+            m = self.ref["h"][l - 1]
+            arg = self.ref["arg"][l]
+            ub = self.ink.get_layer(l, 3)
+            for v in range(self.n):
+                nb = col[rp[v]:rp[v + 1]]
+                if nb.size == 0:
+                    continue
+                rows = m[nb].astype(np.float64)                      # [deg, d]
+                holder = arg[v][None, :] == nb[:, None]
+                worst = np.inf if is_min else -np.inf
+                others = np.where(holder, worst, rows)
+                true2 = others.min(axis=0) if is_min else others.max(axis=0)
+                got = ub[v].astype(np.float64)
+                if exact:
+                    assert np.array_equal(got, true2), (l, v)
+                else:
+                    assert np.all(got <= true2) if is_min else np.all(got >= true2), (l, v)
+
     def check_graph(self):
         rp, col = self.ink.get_graph()
         rp2, col2 = oracle.csr_from_keys(self.n, self.keys)
