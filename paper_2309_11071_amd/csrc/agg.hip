@@ -183,14 +183,15 @@ __global__ __launch_bounds__(256) void k_agg_full(AggArgs a, const int32_t *targ
 
 // cooperative path for rows with more than kBigDeg in-neighbours: a workgroup per chunk of
 // kBigChunk neighbours (its 4 waves take a quarter each), partial rows to scratch
-template <bool IS_MIN, int LPR>
-__global__ __launch_bounds__(INK_BIG_LB) void k_big_partial(AggArgs a, const int32_t *big_list, const int32_t *n_big_p,
+template <bool IS_MIN, int LPR, int NW>
+__global__ __launch_bounds__(NW * kWave) void k_big_partial(AggArgs a, const int32_t *big_list, const int32_t *n_big_p,
                                                       const int32_t *pref, const int32_t *total_p, float *part_v,
                                                       int32_t *part_i, float *part_s) {
-  __shared__ float sv[kBigMaxWaves][kWave * 4];
-  __shared__ int si[kBigMaxWaves][kWave * 4];
-  __shared__ float ss[kBigMaxWaves][kWave * 4];
-  const int l = lane_id(), w = threadIdx.x / kWave, nw = blockDim.x / kWave;
+  __shared__ float sv[NW][kWave * 4];    // sized per variant: the 4-wave form must not pay the LDS of the 16-wave one
+  __shared__ int si[NW][kWave * 4];
+  __shared__ float ss[NW][kWave * 4];
+  const int l = lane_id(), w = threadIdx.x / kWave;
+  constexpr int nw = NW;
   const int q = l % LPR;
   const bool lane_on = 4 * q < a.wd;
   const int total = *total_p, n_big = *n_big_p;
@@ -398,9 +399,15 @@ static hipError_t run_big(ink_ctx *c, const AggArgs &a, uint64_t *chg, int compa
   int32_t *pref = c->big_pref.as<int32_t>();
   int32_t *n_big = &c->d_cnt->v[C_NBIG], *total = &c->d_cnt->v[C_NCHUNK];
   INK_TRY(plan_big_rows(c, n_rows_max, a.in_deg));
-  hipLaunchKernelGGL((k_big_partial<IS_MIN, LPR>), dim3(big_partial_grid(c, a.big_grid, block_threads)), dim3(block_threads), 0, c->stream, a, list,
-                     (const int32_t *)n_big, (const int32_t *)pref, (const int32_t *)total, c->big_part_v.as<float>(),
-                     c->big_part_i.as<int32_t>(), c->big_part_s.as<float>());
+  const dim3 grid(big_partial_grid(c, a.big_grid, block_threads));
+  if (block_threads == 1024)
+    hipLaunchKernelGGL((k_big_partial<IS_MIN, LPR, 16>), grid, dim3(1024), 0, c->stream, a, list, (const int32_t *)n_big,
+                       (const int32_t *)pref, (const int32_t *)total, c->big_part_v.as<float>(),
+                       c->big_part_i.as<int32_t>(), c->big_part_s.as<float>());
+  else
+    hipLaunchKernelGGL((k_big_partial<IS_MIN, LPR, 4>), grid, dim3(256), 0, c->stream, a, list, (const int32_t *)n_big,
+                       (const int32_t *)pref, (const int32_t *)total, c->big_part_v.as<float>(),
+                       c->big_part_i.as<int32_t>(), c->big_part_s.as<float>());
   hipLaunchKernelGGL((k_big_final<IS_MIN, LPR>), dim3(kBigGrid), dim3(64), 0, c->stream, a, list,
                      (const int32_t *)n_big, (const int32_t *)pref, (const float *)c->big_part_v.as<float>(),
                      (const int32_t *)c->big_part_i.as<int32_t>(), (const float *)c->big_part_s.as<float>(), chg, compare,

@@ -12,7 +12,7 @@
 namespace ink {
 
 #ifndef INK_BIG_DEG
-#define INK_BIG_DEG 1024
+#define INK_BIG_DEG 256
 #endif
 // neighbour rows in flight per lane group while gathering, by aggregator family and lanes per row
 #ifndef INK_U_SEL16

@@ -153,37 +153,39 @@ __global__ __launch_bounds__(kSortThreads) void k_radix_scatter(const uint32_t *
   }
 }
 
-// Whole sort in one workgroup for n <= kSmallSort: the same stable digit ranking, all passes in
-// LDS, one launch.
+// Whole sort in one workgroup: the same stable digit ranking, all passes in LDS, one launch.
+// Keys live in registers between the ranking and the scatter of a pass, so one LDS copy of the
+// pairs is enough.  THREADS x ITEMS pairs at most: 256 x {1,4,16} for short lists, 1024 x 16
+// (128 KB of pairs) up to kSmallSort.
+constexpr int kWideThreads = 1024;
 constexpr int kSmallItems = 16;
-constexpr int kSmallSort = kSortThreads * kSmallItems;     // 4096 pairs, 64 KB of LDS
+constexpr int kSmallSort = kWideThreads * kSmallItems;     // 16384 pairs
 
-// ITEMS keys per thread: n <= 256 * ITEMS
-template <int ITEMS>
-__global__ __launch_bounds__(kSortThreads) void k_small_sort(uint32_t *keys, uint32_t *vals, int n, int passes) {
-  constexpr int kSmallItems = ITEMS;
-  constexpr int kSmallSort = kSortThreads * ITEMS;
-  __shared__ uint32_t sk[2][kSmallSort];
-  __shared__ uint32_t sv[2][kSmallSort];
-  __shared__ int cnt[kSortWaves][kRadix];
-  __shared__ int dbase[kRadix];
+template <int THREADS, int ITEMS>
+__global__ __launch_bounds__(THREADS) void k_small_sort(uint32_t *keys, uint32_t *vals, int n, int passes) {
+  constexpr int kCap = THREADS * ITEMS;
+  constexpr int kWaves = THREADS / kWave;
+  constexpr int kDigitWaves = kRadix / kWave;    // the waves whose threads own one digit each
+  static_assert(THREADS >= kRadix, "one thread per digit");
+  __shared__ uint32_t sk[kCap];
+  __shared__ uint32_t sv[kCap];
+  __shared__ int cnt[kWaves][kRadix];
+  __shared__ int wsum[kDigitWaves];
   const int w = threadIdx.x / kWave, l = lane_id();
-  for (int i = threadIdx.x; i < n; i += kSortThreads) { sk[0][i] = keys[i]; sv[0][i] = vals[i]; }
-  __syncthreads();
-  int cur = 0;
-  const int per_wave = kSmallItems * kWave;
+  for (int i = threadIdx.x; i < n; i += THREADS) { sk[i] = keys[i]; sv[i] = vals[i]; }
+  const int per_wave = ITEMS * kWave;
   for (int p = 0; p < passes; p++) {
     int shift = p * kRadixBits;
-    for (int i = threadIdx.x; i < kSortWaves * kRadix; i += kSortThreads) (&cnt[0][0])[i] = 0;
+    for (int i = threadIdx.x; i < kWaves * kRadix; i += THREADS) (&cnt[0][0])[i] = 0;
     __syncthreads();
-    uint32_t key[kSmallItems], val[kSmallItems];
-    int rank[kSmallItems];
+    uint32_t key[ITEMS], val[ITEMS];
+    int rank[ITEMS];
 #pragma unroll
-    for (int k = 0; k < kSmallItems; k++) {
+    for (int k = 0; k < ITEMS; k++) {
       int i = w * per_wave + k * kWave + l;
       bool ok = i < n;
-      key[k] = ok ? sk[cur][i] : 0xFFFFFFFFu;
-      val[k] = ok ? sv[cur][i] : 0;
+      key[k] = ok ? sk[i] : 0xFFFFFFFFu;
+      val[k] = ok ? sv[i] : 0;
       int dg = ok ? (int)((key[k] >> shift) & (kRadix - 1)) : kRadix;
       uint64_t same = __ballot(ok);
 #pragma unroll
@@ -200,38 +202,38 @@ __global__ __launch_bounds__(kSortThreads) void k_small_sort(uint32_t *keys, uin
       if (leader) cnt[w][dg] = prev + before + 1;
     }
     __syncthreads();
-    {   // digit totals -> exclusive prefix over digits (thread t = digit t), then per-wave bases
-      int d = threadIdx.x;
-      int tot = 0;
+    // digit totals -> exclusive prefix over digits (thread t < kRadix = digit t), then per-wave bases
+    const bool digit_thread = threadIdx.x < kRadix;
+    int tot = 0, incl = 0;
+    if (digit_thread) {
 #pragma unroll
-      for (int i = 0; i < kSortWaves; i++) tot += cnt[i][d];
-      int incl = wave_incl_scan(tot);
-      __shared__ int wsum[kSortWaves];
+      for (int i = 0; i < kWaves; i++) tot += cnt[i][threadIdx.x];
+      incl = wave_incl_scan(tot);
       if (l == kWave - 1) wsum[w] = incl;
-      __syncthreads();
+    }
+    __syncthreads();
+    if (digit_thread) {
       int base = 0;
 #pragma unroll
-      for (int i = 0; i < kSortWaves; i++) if (i < w) base += wsum[i];
+      for (int i = 0; i < kDigitWaves; i++) if (i < w) base += wsum[i];
       int run = base + incl - tot;
 #pragma unroll
-      for (int i = 0; i < kSortWaves; i++) { int c = cnt[i][d]; cnt[i][d] = run; run += c; }
-      (void)dbase;
+      for (int i = 0; i < kWaves; i++) { int c = cnt[i][threadIdx.x]; cnt[i][threadIdx.x] = run; run += c; }
     }
     __syncthreads();
 #pragma unroll
-    for (int k = 0; k < kSmallItems; k++) {
+    for (int k = 0; k < ITEMS; k++) {
       int i = w * per_wave + k * kWave + l;
       if (i < n) {
         int dg = (key[k] >> shift) & (kRadix - 1);
         int pos = cnt[w][dg] + rank[k];
-        sk[cur ^ 1][pos] = key[k];
-        sv[cur ^ 1][pos] = val[k];
+        sk[pos] = key[k];
+        sv[pos] = val[k];
       }
     }
     __syncthreads();
-    cur ^= 1;
   }
-  for (int i = threadIdx.x; i < n; i += kSortThreads) { keys[i] = sk[cur][i]; vals[i] = sv[cur][i]; }
+  for (int i = threadIdx.x; i < n; i += THREADS) { keys[i] = sk[i]; vals[i] = sv[i]; }
 }
 
 hipError_t radix_sort_pairs(PrimWorkspace &ws, uint32_t *keys, uint32_t *vals, int64_t n, int bits,
@@ -239,12 +241,14 @@ hipError_t radix_sort_pairs(PrimWorkspace &ws, uint32_t *keys, uint32_t *vals, i
   if (n <= 1 || bits <= 0) return hipSuccess;
   int passes = (bits + kRadixBits - 1) / kRadixBits;
   if (n <= kSmallSort) {
-    if (n <= kSortThreads)
-      hipLaunchKernelGGL((k_small_sort<1>), dim3(1), dim3(kSortThreads), 0, s, keys, vals, (int)n, passes);
-    else if (n <= 4 * kSortThreads)
-      hipLaunchKernelGGL((k_small_sort<4>), dim3(1), dim3(kSortThreads), 0, s, keys, vals, (int)n, passes);
+    if (n <= 256)
+      hipLaunchKernelGGL((k_small_sort<256, 1>), dim3(1), dim3(256), 0, s, keys, vals, (int)n, passes);
+    else if (n <= 1024)
+      hipLaunchKernelGGL((k_small_sort<256, 4>), dim3(1), dim3(256), 0, s, keys, vals, (int)n, passes);
+    else if (n <= 4096)
+      hipLaunchKernelGGL((k_small_sort<kWideThreads, 4>), dim3(1), dim3(kWideThreads), 0, s, keys, vals, (int)n, passes);
     else
-      hipLaunchKernelGGL((k_small_sort<kSmallItems>), dim3(1), dim3(kSortThreads), 0, s, keys, vals, (int)n, passes);
+      hipLaunchKernelGGL((k_small_sort<kWideThreads, kSmallItems>), dim3(1), dim3(kWideThreads), 0, s, keys, vals, (int)n, passes);
     return hipGetLastError();
   }
   int nb = nblocks(n, kSortTile);
