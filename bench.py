@@ -28,26 +28,31 @@ HBM_PEAK_GBS = 8000.0
 # counter scaled by 2.0 and write counter by 1.0 (what a plain 1 GiB copy kernel reads back in the
 # same runs), divided by the aggregation launches of the batch (one per layer).
 MEASURED_TRAFFIC_PER_LAUNCH = {
-    2: {"bytes": 8.27e9, "source": "profiles/all_kernels_cfg2_gcn.md"},
-    3: {"bytes": 15.9e9, "source": "profiles/all_kernels_cfg3_sage_max.md"},
+    2: {"bytes": 8.28e9, "source": "profiles/all_kernels_cfg2_gcn.md"},
+    3: {"bytes": 3.58e9, "source": "profiles/all_kernels_cfg3_sage_max.md"},
 }
 
 
-def agg_algorithmic_bytes(layer_stats, agg_width, n_del):
+def agg_algorithmic_bytes(layer_stats, agg_width, n_del, select):
     """Bytes the aggregation kernels of one step must move (per layer, summed).
 
     events: 4 B payload each; every non-delete event reads one source row (4 d B);
-    targets: alpha + argument rows read (8 d B), rewritten when alpha changed (8 d B);
+    targets: the cached row is read and, when alpha changed, rewritten.  A cached row is alpha
+    alone for the sum-type aggregators (4 d B) and alpha + holder + runner-up bound for max / min
+    (12 d B; the bound, 4 d B, is rewritten for every target);
     recomputes: per neighbour one id (4 B) and one message row (4 d B).
     A dense layer is a recompute of every node."""
     total = 0
+    row = 12 if select else 4
     for L, d in zip(layer_stats, agg_width):
         if L["dense"]:
-            total += L["n_regather_nb"] * (4 + 4 * d) + L["n_targets"] * 8 * d
+            total += L["n_regather_nb"] * (4 + 4 * d) + L["n_targets"] * row * d
             continue
         ev = L["n_events"]
         total += ev * 4 + max(ev - n_del, 0) * 4 * d
-        total += L["n_targets"] * 8 * d + L["n_alpha_changed"] * 8 * d
+        total += L["n_targets"] * row * d + L["n_alpha_changed"] * row * d
+        if select:
+            total += (L["n_targets"] - L["n_alpha_changed"]) * 4 * d
         total += L["n_regather_nb"] * (4 + 4 * d)
     return total
 
@@ -155,7 +160,8 @@ def main():
         st = ink.stats()                      # host-side struct copy, no GPU work
         agg_ms += st["ms"]["agg"]
         agg_launches += sum(1 for L in st["layers"] if L["n_events"] > 0)
-        agg_bytes += agg_algorithmic_bytes(st["layers"], ink.agg_widths, r["n_applied_del"])
+        agg_bytes += agg_algorithmic_bytes(st["layers"], ink.agg_widths, r["n_applied_del"],
+                                           cfg.agg in ("max", "min"))
         changed += r["n_changed"]
         for k_, v in st["ms"].items():
             per_class[k_] = per_class.get(k_, 0.0) + v
@@ -204,11 +210,11 @@ def main():
         "full_inference_s": t_full,
         "full_inference_agg_ms": full_stats["ms"]["agg"],
         # the recompute kernels at their largest shape: every edge gathers one id and one message row,
-        # every node writes its aggregate (and argument) row
+        # every node writes its cached row (alpha; for max / min also holder and runner-up bound)
         "full_inference_roofline": (lambda b, ms: {"bound": "hbm", "achieved": b / 1e9 / (ms / 1e3), "peak": HBM_PEAK_GBS,
                                                    "unit": "GB/s", "frac": b / 1e9 / (ms / 1e3) / HBM_PEAK_GBS,
                                                    "algorithmic_bytes": b})(
-            sum(int(src.size) * (4 + 4 * d) + cfg.n_nodes * (8 if cfg.agg in ("max", "min") else 4) * d
+            sum(int(src.size) * (4 + 4 * d) + cfg.n_nodes * (12 if cfg.agg in ("max", "min") else 4) * d
                 for d in ink.agg_widths), max(full_stats["ms"]["agg"], 1e-6)),
     }
     if args.sweep:

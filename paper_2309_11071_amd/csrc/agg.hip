@@ -419,7 +419,7 @@ template <bool IS_MIN, int LPR>
 static hipError_t full_t(ink_ctx *c, const AggArgs &a_in, const int32_t *targets, int64_t n_targets, uint64_t *chg) {
   if (n_targets <= 0) return hipSuccess;
   AggArgs a = a_in;
-  a.big_deg = big_threshold(n_targets, LPR);
+  a.big_deg = big_threshold(n_targets, LPR, kBigDeg);
   int compare = chg != nullptr;
   INK_TRY(ensure_big_buffers(c, a.wd, true));
   INK_TRY(hipMemsetAsync(&c->d_cnt->v[C_NBIG], 0, sizeof(int32_t), c->stream));
@@ -436,7 +436,7 @@ static hipError_t events_t(ink_ctx *c, const AggArgs &a_in, const int32_t *targe
                            int64_t n_targets, const int32_t *n_targets_dev, const uint32_t *ev, uint64_t *chg) {
   if (n_targets <= 0) return hipSuccess;
   AggArgs a = a_in;
-  a.big_deg = big_threshold(n_targets, LPR);
+  a.big_deg = big_threshold(n_targets, LPR, kBigDeg);
   INK_TRY(ensure_big_buffers(c, a.wd, true));
   int64_t blocks = (n_targets + 3) / 4;
   hipLaunchKernelGGL((k_agg_events<IS_MIN, LPR>), dim3((unsigned)blocks), dim3(256), 0, c->stream, a, targets, seg,

@@ -261,7 +261,7 @@ static hipError_t sum_full_t(ink_ctx *c, const AggArgs &a_in, const int32_t *tar
                              uint64_t *chg) {
   if (n_targets <= 0) return hipSuccess;
   AggArgs a = a_in;
-  a.big_deg = big_threshold(n_targets, LPR);
+  a.big_deg = big_threshold(n_targets, LPR, kBigDegSum);
   int compare = chg != nullptr;
   INK_TRY(ensure_big_buffers(c, a.wd, false));
   INK_TRY(hipMemsetAsync(&c->d_cnt->v[C_NBIG], 0, sizeof(int32_t), c->stream));

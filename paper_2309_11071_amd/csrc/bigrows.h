@@ -47,8 +47,8 @@ inline hipError_t ensure_big_buffers(ink_ctx *c, int ld, bool with_ids) {
 // cooperative path much earlier and each chunk is shared by 16 waves instead of 4.
 constexpr int kLatencyTargets = 8192;
 inline bool latency_mode(int64_t n_targets) { return n_targets <= kLatencyTargets; }
-inline int big_threshold(int64_t n_targets, int lanes_per_row) {
-  return latency_mode(n_targets) ? 32 * (kWave / lanes_per_row) : kBigDeg;
+inline int big_threshold(int64_t n_targets, int lanes_per_row, int throughput_deg) {
+  return latency_mode(n_targets) ? 32 * (kWave / lanes_per_row) : throughput_deg;
 }
 inline int big_block_threads(int64_t n_targets) { return latency_mode(n_targets) ? (INK_BIG_LB >= 1024 ? 1024 : 256) : 256; }
 constexpr int kBigMaxWaves = INK_BIG_LB / 64;
@@ -71,8 +71,9 @@ inline hipError_t plan_big_rows(ink_ctx *c, int64_t n_rows_max, const int32_t *i
   int64_t cap = (int64_t)(c->big_list.cap / 4);
   if (n_rows_max > cap) n_rows_max = cap;
   const int32_t *n_big = &c->d_cnt->v[C_NBIG];
-  return tile_scan(c->ws, BigChunkCount{c->big_list.as<int32_t>(), n_big, in_deg},
-                   BigPrefStore{c->big_pref.as<int32_t>(), n_big}, n_rows_max, &c->d_cnt->v[C_NCHUNK], c->stream);
+  return tile_scan<BigChunkCount, BigPrefStore, kScanItems, true>(
+      c->ws, BigChunkCount{c->big_list.as<int32_t>(), n_big, in_deg}, BigPrefStore{c->big_pref.as<int32_t>(), n_big},
+      n_rows_max, &c->d_cnt->v[C_NCHUNK], c->stream);
 }
 
 // row (index in the list), node id and neighbour range of global chunk cg

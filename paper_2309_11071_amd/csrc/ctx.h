@@ -37,7 +37,14 @@ namespace ink {
 #define INK_BIG_CHUNK 1024
 #endif
 constexpr int kBigChunk = INK_BIG_CHUNK;  // neighbours per chunk of such a row
-constexpr int kBigDeg = INK_BIG_DEG;      // rows with more in-neighbours are re-gathered cooperatively (bigrows.h)
+#ifndef INK_BIG_DEG_SUM
+#define INK_BIG_DEG_SUM 1024
+#endif
+// rows with more in-neighbours are re-gathered cooperatively (bigrows.h): kBigDeg for max / min,
+// whose per-neighbour work is heavier, kBigDegSum for the sum-type aggregators (both measured)
+constexpr int kBigDeg = INK_BIG_DEG;
+constexpr int kBigDegSum = INK_BIG_DEG_SUM;
+static_assert(kBigDeg <= kBigDegSum, "buffer bounds of the long-row path use the smaller threshold");
 constexpr uint32_t kEvKindShift = 30;
 constexpr uint32_t kEvIdMask = (1u << kEvKindShift) - 1;
 enum : uint32_t { EV_DEL = 0, EV_ADD = 1, EV_CHG = 2 };   // removed edge / inserted edge / changed source

@@ -47,12 +47,13 @@ __device__ __forceinline__ int wave_incl_scan(int x) {
   return x;
 }
 
-// exclusive scan over a workgroup of kScanThreads threads; *total gets the block sum.
-// smem must hold kScanThreads / kWave + 1 ints.  Contains __syncthreads.
+// exclusive scan over a workgroup of THREADS threads; *total gets the block sum.
+// smem must hold THREADS / kWave + 1 ints.  Contains __syncthreads.
+template <int THREADS = kScanThreads>
 __device__ __forceinline__ int block_excl_scan(int x, int *smem, int *total) {
   int incl = wave_incl_scan(x);
   int w = threadIdx.x / kWave, l = lane_id();
-  constexpr int nw = kScanThreads / kWave;
+  constexpr int nw = THREADS / kWave;
   __syncthreads();
   if (l == kWave - 1) smem[w] = incl;
   __syncthreads();
@@ -132,7 +133,40 @@ __global__ __launch_bounds__(kScanThreads) void k_tile_apply(F f, W w, int64_t n
   if (total_single && threadIdx.x == 0) *total_single = tot;   // only used when gridDim.x == 1
 }
 
-template <class F, class W, int ITEMS = kScanItems>
+// short inputs: the whole scan in one workgroup and one launch, tile after tile with a carry
+constexpr int kOneWgThreads = 1024;
+constexpr int kOneWgItems = 4;
+constexpr int64_t kOneWgLimit = 16384;
+template <class F, class W>
+__global__ __launch_bounds__(kOneWgThreads) void k_tile_scan_one(F f, W w, int64_t n, int32_t *total) {
+  __shared__ int sm[kOneWgThreads / kWave + 1];
+  int carry = 0;
+  for (int64_t t0 = 0; t0 < n; t0 += kOneWgThreads * kOneWgItems) {
+    int64_t base = t0 + (int64_t)threadIdx.x * kOneWgItems;
+    int v[kOneWgItems];
+    int s = 0;
+#pragma unroll
+    for (int k = 0; k < kOneWgItems; k++) {
+      int64_t i = base + k;
+      v[k] = i < n ? f(i) : 0;
+      s += v[k];
+    }
+    int tot;
+    int ex = carry + block_excl_scan<kOneWgThreads>(s, sm, &tot);
+#pragma unroll
+    for (int k = 0; k < kOneWgItems; k++) {
+      int64_t i = base + k;
+      if (i < n) w(i, v[k], ex);
+      ex += v[k];
+    }
+    carry += tot;
+    __syncthreads();
+  }
+  if (total && threadIdx.x == 0) *total = carry;
+}
+
+// ONE_WG: only for functors that do O(1) work per item
+template <class F, class W, int ITEMS = kScanItems, bool ONE_WG = false>
 inline hipError_t tile_scan(PrimWorkspace &ws, F f, W w, int64_t n, int32_t *total, hipStream_t s) {
   if (n <= 0) {
     if (total) INK_TRY(hipMemsetAsync(total, 0, sizeof(int32_t), s));
@@ -142,6 +176,10 @@ inline hipError_t tile_scan(PrimWorkspace &ws, F f, W w, int64_t n, int32_t *tot
   if (nb == 1) {
     hipLaunchKernelGGL((k_tile_apply<F, W, ITEMS>), dim3(1), dim3(kScanThreads), 0, s, f, w, n,
                        (const int32_t *)nullptr, total);
+    return hipGetLastError();
+  }
+  if (ONE_WG && n <= kOneWgLimit) {
+    hipLaunchKernelGGL((k_tile_scan_one<F, W>), dim3(1), dim3(kOneWgThreads), 0, s, f, w, n, total);
     return hipGetLastError();
   }
   INK_TRY(ws.blk.reserve((size_t)nb * sizeof(int32_t)));

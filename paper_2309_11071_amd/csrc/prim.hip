@@ -10,7 +10,7 @@ struct StoreExcl { int32_t *p; __device__ void operator()(int64_t i, int, int ex
 
 hipError_t scan_excl_i32(PrimWorkspace &ws, const int32_t *in, int32_t *out, int64_t n,
                          int32_t *total, hipStream_t s) {
-  return tile_scan(ws, LoadI32{in}, StoreExcl{out}, n, total, s);
+  return tile_scan<LoadI32, StoreExcl, kScanItems, true>(ws, LoadI32{in}, StoreExcl{out}, n, total, s);
 }
 
 // ---------------------------------------------------------------- flag compaction
@@ -22,7 +22,7 @@ struct StoreIdx {
 
 hipError_t compact_flags_u8(PrimWorkspace &ws, const uint8_t *flags, int64_t n, int32_t *out_idx,
                             int32_t *count, hipStream_t s) {
-  return tile_scan(ws, LoadFlag{flags}, StoreIdx{out_idx}, n, count, s);
+  return tile_scan<LoadFlag, StoreIdx, kScanItems, true>(ws, LoadFlag{flags}, StoreIdx{out_idx}, n, count, s);
 }
 
 // ---------------------------------------------------------------- bitmap -> ascending id list
@@ -66,7 +66,8 @@ struct StoreHead {
 
 hipError_t segment_heads(PrimWorkspace &ws, const uint32_t *keys, int64_t n, int32_t *uniq,
                          int32_t *seg, int32_t *count, hipStream_t s, const int32_t *n_dev) {
-  return tile_scan(ws, LoadHead{keys, n_dev}, StoreHead{keys, uniq, seg, n, n_dev}, n, count, s);
+  return tile_scan<LoadHead, StoreHead, kScanItems, true>(ws, LoadHead{keys, n_dev}, StoreHead{keys, uniq, seg, n, n_dev}, n, count,
+                                                             s);
 }
 
 // ---------------------------------------------------------------- stable LSD radix sort
