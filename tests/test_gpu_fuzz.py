@@ -75,3 +75,25 @@ def test_sum_drift_over_a_long_sequence():
     ref = oracle.full_infer(*oracle.csr_from_keys(h.n, h.keys), h.X, h.model, "f64")
     assert scaled_rel_err(h.ink.get_layer(3, 0), ref["h"][3]) <= max(errs) + 1e-7
     h.ink.close()
+
+
+@pytest.mark.parametrize("kind,agg,exact", [("sage", "max", True), ("gin", "sum", False)])
+def test_batch_sizes_across_the_sort_and_scan_variants(kind, agg, exact):
+    """Batches of 200 .. 40 000 messy ops: the lists sorted and scanned on the device cross every
+    size class of the primitives (one workgroup with 256 or 1024 threads, several workgroups)."""
+    dims = (8, 8, 6)
+    n = 30000
+    cfg = synth.WorkloadConfig(8, "t", kind, agg, n, 240000, False, dims, 12, 50, False)
+    src, dst = synth.make_graph(cfg)
+    rng = np.random.default_rng(23)
+    X = rng.integers(-3, 4, size=(n, dims[0])).astype(np.float32)
+    h = Harness(cfg=cfg, graph=(n, src, dst), X=X, model=tiny_model(kind, agg, dims, seed=5, hidden=8),
+                precision="f32" if exact else "f64", slack=0.05)
+    for size in (200, 900, 1500, 3900, 4200, 9000, 16000, 17000, 40000):
+        op, s, d = messy_batch(rng, n, h.keys, size)
+        h.step(op, s, d, exact=exact, tol=1e-5)
+        h.check_graph()
+    if exact:
+        h.check_bound()
+    h.check_state(exact=exact, tol=1e-5)
+    h.ink.close()
