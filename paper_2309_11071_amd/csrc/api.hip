@@ -249,11 +249,11 @@ static AggArgs agg_args(ink_ctx *c, int l) {       // layer l in 1..k
 // dense combination of layer l for the rows in `rows` (null: all nodes).  With flags != null the
 // layer's table is updated with compare-and-emit.
 static hipError_t run_transform(ink_ctx *c, int l, const int32_t *rows, int64_t n_rows, uint8_t *flags,
-                                float *old_rows = nullptr) {
+                                float *old_rows = nullptr, const int32_t *n_rows_dev = nullptr) {
   const DevLayer &L = c->layers[l - 1];
   XformArgs x;
   memset(&x, 0, sizeof(x));
-  x.rows = rows; x.n_rows = n_rows;
+  x.rows = rows; x.n_rows = n_rows; x.n_rows_dev = n_rows_dev;
   x.old_rows = old_rows; x.ld_old = c->H[l].ld;
   if (c->agg == INK_AGG_MEAN) x.mean_deg = c->gin.deg;
   x.A = c->A[l].f(); x.lda = c->A[l].ld;
@@ -275,7 +275,7 @@ static hipError_t run_transform(ink_ctx *c, int l, const int32_t *rows, int64_t 
   if (e != hipSuccess) return e;
   XformArgs y;
   memset(&y, 0, sizeof(y));
-  y.mode = 2; y.rows = rows; y.n_rows = n_rows;
+  y.mode = 2; y.rows = rows; y.n_rows = n_rows; y.n_rows_dev = n_rows_dev;
   y.Hp = c->stage0.as<float>(); y.ldh = L.N1p; y.d_in = L.hidden;
   y.W = L.W2; y.Kp = L.K2p; y.Np = L.N2p; y.bias = L.b2; y.n_out = L.out_dim; y.relu = L.act == INK_ACT_RELU;
   y.out = c->H[l].f(); y.ld_out = c->H[l].ld; y.to_table = 1; y.row_changed = flags; y.out_rows = rows;
@@ -672,15 +672,17 @@ static void layer_stats_from_counters(ink_ctx *c, int l) {
   S.n_covered = (int64_t)c->h_cnt->sum(ST_COVERED);
 }
 
-// bitmap (plus extra id lists) -> ascending row list in c->c_list; returns the count
+// bitmap (plus extra id lists) -> ascending row list in c->c_list; returns the count, or, with
+// bound >= 0, that upper bound without waiting for the device (the count stays in C_NC)
 static ink_status collect_rows(ink_ctx *c, const int32_t *extra0, int64_t n0, const int32_t *extra1, int64_t n1,
-                               int64_t *nC) {
+                               int64_t *nC, int64_t bound = -1) {
   hipStream_t s = c->stream;
   Prof p(c, INK_T_COMPACT);
   if (n0 > 0) hipLaunchKernelGGL(k_mark_nodes, grid1(n0), dim3(256), 0, s, extra0, (int)n0, c->bm_a);
   if (n1 > 0) hipLaunchKernelGGL(k_mark_nodes, grid1(n1), dim3(256), 0, s, extra1, (int)n1, c->bm_a);
   API_TRY(c->c_list.reserve((size_t)c->n * 4));
   API_TRY(bitmap_to_list(c->ws, c->bm_a, c->n, c->c_list.as<int32_t>(), &c->d_cnt->v[C_NC], 1, s));
+  if (bound >= 0) { *nC = bound; return INK_OK; }
   API_TRY(read_counters(c));
   *nC = c->h_cnt->v[C_NC];
   return INK_OK;
@@ -802,12 +804,16 @@ static ink_status apply_updates_impl(ink_ctx *c, const ink_edge_update *upd, int
     ink_status st = layer_aggregate(c, l, F, nF, n_chg, keep_old ? c->f_old[cur].as<float>() : nullptr, ld_msg,
                                     n_ins, n_del);
     if (st != INK_OK) return st;
-    // rows to transform: aggregate changed; own message changed (self term); degree changed
+    // rows to transform: aggregate changed; own message changed (self term); degree changed.
+    // A layer with few events keeps the row count on the device: the transform and the emission
+    // are launched for an upper bound and stop at the count, which saves one host round trip.
     int64_t nC = 0;
-    st = collect_rows(c, F, nF, D, nD, &nC);
+    const bool lazy = !gcn && !S.dense && !c->affected_mode && S.n_events <= kNoSyncEvents;
+    const int64_t bound = lazy ? std::min<int64_t>(std::min<int64_t>(S.n_events, c->n) + nF + nD, c->n) : -1;
+    st = collect_rows(c, F, nF, D, nD, &nC, bound);
     if (st != INK_OK) return st;
-    S.n_transformed = nC;
-    layer_stats_from_counters(c, l);
+    const int32_t *nC_dev = lazy ? &c->d_cnt->v[C_NC] : nullptr;
+    if (!lazy) { S.n_transformed = nC; layer_stats_from_counters(c, l); }
     int nxt = cur ^ 1;
     int64_t nF2 = 0, n_chg2 = 0;
     if (nC > 0) {
@@ -821,8 +827,10 @@ static ink_status apply_updates_impl(ink_ctx *c, const ink_edge_update *upd, int
         Prof p(c, INK_T_TRANSFORM);
         const int32_t *rows = c->c_list.as<int32_t>();
         float *old_rows = want_old ? c->c_old.as<float>() : nullptr;
-        if (!gcn) API_TRY(run_transform(c, l, rows, nC, c->c_flag.as<uint8_t>(), old_rows));
-        else {
+        if (!gcn) {
+          if (lazy) API_TRY(hipMemsetAsync(c->c_flag.p, 0, (size_t)nC, s));   // flags past the count stay 0
+          API_TRY(run_transform(c, l, rows, nC, c->c_flag.as<uint8_t>(), old_rows, nC_dev));
+        } else {
           API_TRY(hipMemsetAsync(c->c_flag.p, 0, (size_t)nC, s));
           if (!last) API_TRY(gcn_next_messages(c, l, rows, nC, c->c_flag.as<uint8_t>(), old_rows));
           else API_TRY(gcn_final(c, rows, nC, c->c_flag.as<uint8_t>()));
@@ -832,7 +840,10 @@ static ink_status apply_updates_impl(ink_ctx *c, const ink_edge_update *upd, int
       }
       st = emit_changed(c, nC, nxt, want_old, ld_next, !last, &nF2, &n_chg2);
       if (st != INK_OK) return st;
+    } else if (lazy) {
+      API_TRY(read_counters(c));
     }
+    if (lazy) { S.n_transformed = c->h_cnt->v[C_NC]; layer_stats_from_counters(c, l); }
     S.n_changed = nF2;
     nF = nF2;
     n_chg = n_chg2;

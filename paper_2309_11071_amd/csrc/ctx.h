@@ -195,7 +195,8 @@ struct XformArgs {
   int mode;                 // 0 SAGE concat [A | Hprev], 1 GIN (1+eps) Hprev + A, 2 dense rows,
                             // 3 GCN: x = act(c_v (A + Hp) + in_bias), with A = neighbour sums, Hp = own scaled message
   const int32_t *rows;      // row ids (null: identity)
-  int64_t n_rows;
+  int64_t n_rows;           // rows to transform; an upper bound when n_rows_dev is set
+  const int32_t *n_rows_dev;   // optional device-side row count (<= n_rows)
   const float *A; int lda;  // aggregated table
   const float *Hp; int ldh; // previous-layer table (or dense input for mode 2)
   int d_in;

@@ -158,10 +158,16 @@ __global__ __launch_bounds__(256) void k_xform(XformArgs x) {
   const int rt = w & 1;                       // row tile of this wave
   const int ct0 = w >> 1;                     // first column tile; then += 2
   const int64_t r0 = (int64_t)blockIdx.x * BM;
+  int64_t n_rows = x.n_rows;
+  if (x.n_rows_dev) {          // the launch covers an upper bound; workgroups past the count leave
+    int64_t nd = *x.n_rows_dev;
+    n_rows = nd < n_rows ? nd : n_rows;
+    if (r0 >= n_rows) return;
+  }
   if (t < BM) {
     int64_t j = r0 + t;
     int64_t row = -1;
-    if (j < x.n_rows) row = (MODE == 2) ? j : (x.rows ? (int64_t)x.rows[j] : j);
+    if (j < n_rows) row = (MODE == 2) ? j : (x.rows ? (int64_t)x.rows[j] : j);
     srow[t] = row;
     sout[t] = (row >= 0 && MODE == 2 && x.to_table && x.out_rows) ? (int64_t)x.out_rows[j] : row;
     schg[t] = 0;
