@@ -191,6 +191,21 @@ ink_status ink_apply_updates(ink_ctx *ctx, const ink_edge_update *updates, int64
 ink_status ink_apply_updates_affected(ink_ctx *ctx, const ink_edge_update *updates, int64_t n,
                                       ink_update_result *out);
 
+/* Vertex feature update (the input-side counterpart of an edge update; Sec. 2.6 lets callers
+ * create and propagate events of their own next to the built-in ones, and this is the one such
+ * event a fixed-function library can offer): x_v <- rows[i] for v = node_ids[i], then the same
+ * layer-wise propagation as ink_apply_updates with F_1 = the nodes whose feature row changed
+ * bitwise (Sec. 2.4: a node whose message changed sends its old and new message to its
+ * out-neighbours; Sec. 3.2: its own next embedding depends on it too).  The graph is unchanged.
+ *   node_ids : [n] distinct ids in [0, n_nodes), any order
+ *   rows     : [n][feat_dim] fp32, row i belongs to node_ids[i]
+ * Both arrays are host or device memory like the update batches (ink_options.batch_mem, else
+ * ink_options.mem).  The result has the layout of ink_apply_updates' (n_applied_* are 0).
+ * Errors: INK_E_STATE before ink_full_infer; INK_E_RANGE for an id outside [0, n_nodes);
+ * INK_E_ARG for a repeated id, n < 0 or NULL arrays.  On error nothing is changed. */
+ink_status ink_update_features(ink_ctx *ctx, const int32_t *node_ids, const float *rows, int64_t n,
+                               ink_update_result *out);
+
 /* Inspection for tests: copies rows [row0, row0 + nrows) of a cached table to dst (host or
  * device per dst_mem), densely packed [nrows][width].  layer in 0..n_layers.
  *   which = 0: h_layer, the output of layer `layer` (layer 0 = input features); it is the

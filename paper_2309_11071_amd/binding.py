@@ -94,6 +94,8 @@ def load_library():
     lib.ink_apply_updates.restype = C.c_int
     lib.ink_apply_updates_affected.argtypes = [vp, vp, C.c_int64, C.POINTER(_Result)]
     lib.ink_apply_updates_affected.restype = C.c_int
+    lib.ink_update_features.argtypes = [vp, vp, vp, C.c_int64, C.POINTER(_Result)]
+    lib.ink_update_features.restype = C.c_int
     lib.ink_get_layer.argtypes = [vp, C.c_int32, C.c_int32, C.c_int64, C.c_int64, vp, C.c_int32,
                                   C.POINTER(C.c_int32)]
     lib.ink_get_layer.restype = C.c_int
@@ -155,6 +157,7 @@ class Ink:
         if st != 0:
             raise InkError(st, self._lib.ink_last_error(None).decode())
         self.n = rowptr.size - 1
+        self.feat_dim = int(features.shape[1])
         self.n_layers = len(model["layers"])
         self.out_dim = model["layers"][-1]["out_dim"]
         self.batch_device = batch_device
@@ -196,6 +199,38 @@ class Ink:
         r = _Result()
         fn = self._lib.ink_apply_updates_affected if affected else self._lib.ink_apply_updates
         self._check(fn(self._h, C.c_void_p(dev_ptr), n, C.byref(r)))
+        return dict(n_changed=r.n_changed, n_applied_ins=r.n_applied_ins, n_applied_del=r.n_applied_del,
+                    n_noop=r.n_noop, changed_ids_ptr=r.changed_ids, embeddings_ptr=r.embeddings)
+
+    def update_features(self, node_ids, rows, fetch=True):
+        """x_v <- rows[i] for v = node_ids[i] (distinct ids), then incremental propagation.
+        Host arrays; same result dict as apply_updates."""
+        assert not self.batch_device, "context expects device batches"
+        node_ids = np.ascontiguousarray(node_ids, dtype=np.int32)
+        rows = np.ascontiguousarray(rows, dtype=np.float32)
+        if node_ids.size:
+            rows = rows.reshape(node_ids.size, -1)
+            assert rows.shape[1] == self.feat_dim, "rows must be [n][feat_dim]"
+        r = _Result()
+        self._check(self._lib.ink_update_features(self._h, node_ids.ctypes.data if node_ids.size else None,
+                                                  rows.ctypes.data if node_ids.size else None, node_ids.size,
+                                                  C.byref(r)))
+        out = dict(n_changed=r.n_changed, n_applied_ins=r.n_applied_ins, n_applied_del=r.n_applied_del,
+                   n_noop=r.n_noop, changed_ids_ptr=r.changed_ids, embeddings_ptr=r.embeddings)
+        if fetch:
+            ids = np.empty(r.n_changed, np.int32)
+            emb = np.empty((r.n_changed, self.out_dim), np.float32)
+            if r.n_changed:
+                _dtoh(ids, r.changed_ids)
+                _dtoh(emb, r.embeddings)
+            out["changed_ids"], out["embeddings"] = ids, emb
+        return out
+
+    def update_features_device(self, ids_ptr, rows_ptr, n):
+        """Ids and rows already in device memory (context created with batch_device=True)."""
+        assert self.batch_device
+        r = _Result()
+        self._check(self._lib.ink_update_features(self._h, C.c_void_p(ids_ptr), C.c_void_p(rows_ptr), n, C.byref(r)))
         return dict(n_changed=r.n_changed, n_applied_ins=r.n_applied_ins, n_applied_del=r.n_applied_del,
                     n_noop=r.n_noop, changed_ids_ptr=r.changed_ids, embeddings_ptr=r.embeddings)
 

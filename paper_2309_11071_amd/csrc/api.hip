@@ -99,6 +99,38 @@ __global__ void k_unpack_rows(const float *in, int d, int ld, int64_t n, float *
   if (r < n) table[r * ld + k] = in[r * d + k];
 }
 
+__global__ void k_iota_u32(uint32_t *out, int64_t n) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) out[i] = (uint32_t)i;
+}
+
+// adjacent equal keys in a sorted list -> *flag = 1
+__global__ void k_any_adjacent_equal(const uint32_t *keys, int64_t n, int32_t *flag) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i + 1 < n && keys[i] == keys[i + 1]) *flag = 1;
+}
+
+// New input features for the nodes ids[i] (ascending); the caller's row of ids[i] is rows[perm[i]].
+// Writes the feature table with compare-and-emit: flag[i] = 1 if the row changed bitwise,
+// old_rows[i] = the previous row (optional), dense[i] = the new row padded to ld (optional).
+__global__ void k_set_features(const uint32_t *ids, const uint32_t *perm, int64_t n, const float *rows, int d, float *X,
+                               int ld, float *old_rows, float *dense, uint8_t *flag, int32_t *list) {
+  int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t i = t / ld;
+  int k = (int)(t % ld);
+  if (i >= n) return;
+  int64_t v = ids[i];
+  if (k == 0) list[i] = (int32_t)v;
+  float nv = k < d ? rows[(int64_t)perm[i] * d + k] : 0.f;
+  float o = X[v * ld + k];
+  if (old_rows) old_rows[i * ld + k] = o;
+  if (dense) dense[i * ld + k] = nv;
+  if (__float_as_uint(o) != __float_as_uint(nv)) {
+    X[v * ld + k] = nv;
+    flag[i] = 1;
+  }
+}
+
 __global__ void k_gather_rows_ld(const float *in, int ld, const int32_t *idx, int64_t n, const int32_t *n_dev,
                                  float *out) {
   // out[i][:] = in[idx[i]][:], both with row stride ld
@@ -720,6 +752,83 @@ static ink_status emit_changed(ink_ctx *c, int64_t nC, int nxt, bool keep_old, i
   return INK_OK;
 }
 
+// Layers 1..k for the sources F_1 = f_list[cur] (nF ids whose layer-1 message changed, n_chg events
+// along their kept out-edges) and the applied edge changes; D (nD ids) are nodes whose in-degree
+// changed (normalised aggregators).  Fills the result for layer k.
+static ink_status propagate_layers(ink_ctx *c, int64_t nF, int64_t n_chg, int cur, int64_t n_ins, int64_t n_del,
+                                   const int32_t *D, int64_t nD, ink_update_result *out) {
+  hipStream_t s = c->stream;
+  const int64_t n_seed = n_ins + n_del;
+  const bool gcn = c->kind == INK_MODEL_GCN;
+  const bool keep_old = !c->is_select && !c->affected_mode;   // delta updates subtract the old message rows
+  for (int l = 1; l <= c->n_layers && (n_seed > 0 || nF > 0); l++) {
+    ink_layer_stats &S = c->stats.layer[l - 1];
+    const int32_t *F = c->f_list[cur].as<int32_t>();
+    int ld_msg = msg_table(c, l).ld;
+    ink_status st = layer_aggregate(c, l, F, nF, n_chg, keep_old ? c->f_old[cur].as<float>() : nullptr, ld_msg,
+                                    n_ins, n_del);
+    if (st != INK_OK) return st;
+    // rows to transform: aggregate changed; own message changed (self term); degree changed.
+    // A layer with few events keeps the row count on the device: the transform and the emission
+    // are launched for an upper bound and stop at the count, which saves one host round trip.
+    int64_t nC = 0;
+    const bool lazy = !gcn && !S.dense && !c->affected_mode && S.n_events <= kNoSyncEvents;
+    const int64_t bound = lazy ? std::min<int64_t>(std::min<int64_t>(S.n_events, c->n) + nF + nD, c->n) : -1;
+    st = collect_rows(c, F, nF, D, nD, &nC, bound);
+    if (st != INK_OK) return st;
+    const int32_t *nC_dev = lazy ? &c->d_cnt->v[C_NC] : nullptr;
+    if (!lazy) { S.n_transformed = nC; layer_stats_from_counters(c, l); }
+    int nxt = cur ^ 1;
+    int64_t nF2 = 0, n_chg2 = 0;
+    if (nC > 0) {
+      const bool last = l == c->n_layers;
+      int ld_next = gcn ? (last ? c->H[l].ld : c->Msc[l + 1].ld) : c->H[l].ld;
+      API_TRY(c->c_flag.reserve((size_t)nC + 64));
+      API_TRY(c->c_idx.reserve((size_t)nC * 4));
+      bool want_old = keep_old && !last;
+      if (want_old) API_TRY(c->c_old.reserve((size_t)nC * ld_next * 4));
+      {
+        Prof p(c, INK_T_TRANSFORM);
+        const int32_t *rows = c->c_list.as<int32_t>();
+        float *old_rows = want_old ? c->c_old.as<float>() : nullptr;
+        if (!gcn) {
+          if (lazy) API_TRY(hipMemsetAsync(c->c_flag.p, 0, (size_t)nC, s));   // flags past the count stay 0
+          API_TRY(run_transform(c, l, rows, nC, c->c_flag.as<uint8_t>(), old_rows, nC_dev));
+        } else {
+          API_TRY(hipMemsetAsync(c->c_flag.p, 0, (size_t)nC, s));
+          if (!last) API_TRY(gcn_next_messages(c, l, rows, nC, c->c_flag.as<uint8_t>(), old_rows));
+          else API_TRY(gcn_final(c, rows, nC, c->c_flag.as<uint8_t>()));
+        }
+        // the baseline propagates from every node of the affected area, changed or not
+        if (c->affected_mode && !last) API_TRY(hipMemsetAsync(c->c_flag.p, 1, (size_t)nC, s));
+      }
+      st = emit_changed(c, nC, nxt, want_old, ld_next, !last, &nF2, &n_chg2);
+      if (st != INK_OK) return st;
+    } else if (lazy) {
+      API_TRY(read_counters(c));
+    }
+    if (lazy) { S.n_transformed = c->h_cnt->v[C_NC]; layer_stats_from_counters(c, l); }
+    S.n_changed = nF2;
+    nF = nF2;
+    n_chg = n_chg2;
+    cur = nxt;
+    if (l == c->n_layers) {
+      out->n_changed = nF;
+      if (nF > 0) {
+        int d = c->H[l].d;
+        API_TRY(c->res_ids.reserve((size_t)nF * 4));
+        API_TRY(c->res_emb.reserve((size_t)nF * d * 4));
+        API_TRY(hipMemcpyAsync(c->res_ids.p, c->f_list[cur].p, (size_t)nF * 4, hipMemcpyDeviceToDevice, s));
+        hipLaunchKernelGGL(k_gather_rows, grid1(nF * d), dim3(256), 0, s, (const float *)c->H[l].f(), c->H[l].ld, d,
+                           (const int32_t *)c->res_ids.p, nF, c->res_emb.as<float>());
+        out->changed_ids = c->res_ids.as<int32_t>();
+        out->embeddings = c->res_emb.as<float>();
+      }
+    }
+  }
+  return INK_OK;
+}
+
 static ink_status apply_updates_impl(ink_ctx *c, const ink_edge_update *upd, int64_t n, ink_update_result *out);
 
 extern "C" ink_status ink_apply_updates(ink_ctx *c, const ink_edge_update *upd, int64_t n, ink_update_result *out) {
@@ -797,72 +906,101 @@ static ink_status apply_updates_impl(ink_ctx *c, const ink_edge_update *upd, int
     ink_status st = emit_changed(c, nD, cur, true, ld, true, &nF, &n_chg);
     if (st != INK_OK) return st;
   }
-  for (int l = 1; l <= c->n_layers && (n_seed > 0 || nF > 0); l++) {
-    ink_layer_stats &S = c->stats.layer[l - 1];
-    const int32_t *F = c->f_list[cur].as<int32_t>();
-    int ld_msg = msg_table(c, l).ld;
-    ink_status st = layer_aggregate(c, l, F, nF, n_chg, keep_old ? c->f_old[cur].as<float>() : nullptr, ld_msg,
-                                    n_ins, n_del);
+  {
+    ink_status st = propagate_layers(c, nF, n_chg, cur, n_ins, n_del, D, nD, out);
     if (st != INK_OK) return st;
-    // rows to transform: aggregate changed; own message changed (self term); degree changed.
-    // A layer with few events keeps the row count on the device: the transform and the emission
-    // are launched for an upper bound and stop at the count, which saves one host round trip.
-    int64_t nC = 0;
-    const bool lazy = !gcn && !S.dense && !c->affected_mode && S.n_events <= kNoSyncEvents;
-    const int64_t bound = lazy ? std::min<int64_t>(std::min<int64_t>(S.n_events, c->n) + nF + nD, c->n) : -1;
-    st = collect_rows(c, F, nF, D, nD, &nC, bound);
-    if (st != INK_OK) return st;
-    const int32_t *nC_dev = lazy ? &c->d_cnt->v[C_NC] : nullptr;
-    if (!lazy) { S.n_transformed = nC; layer_stats_from_counters(c, l); }
-    int nxt = cur ^ 1;
-    int64_t nF2 = 0, n_chg2 = 0;
-    if (nC > 0) {
-      const bool last = l == c->n_layers;
-      int ld_next = gcn ? (last ? c->H[l].ld : c->Msc[l + 1].ld) : c->H[l].ld;
-      API_TRY(c->c_flag.reserve((size_t)nC + 64));
-      API_TRY(c->c_idx.reserve((size_t)nC * 4));
-      bool want_old = keep_old && !last;
-      if (want_old) API_TRY(c->c_old.reserve((size_t)nC * ld_next * 4));
-      {
-        Prof p(c, INK_T_TRANSFORM);
-        const int32_t *rows = c->c_list.as<int32_t>();
-        float *old_rows = want_old ? c->c_old.as<float>() : nullptr;
-        if (!gcn) {
-          if (lazy) API_TRY(hipMemsetAsync(c->c_flag.p, 0, (size_t)nC, s));   // flags past the count stay 0
-          API_TRY(run_transform(c, l, rows, nC, c->c_flag.as<uint8_t>(), old_rows, nC_dev));
-        } else {
-          API_TRY(hipMemsetAsync(c->c_flag.p, 0, (size_t)nC, s));
-          if (!last) API_TRY(gcn_next_messages(c, l, rows, nC, c->c_flag.as<uint8_t>(), old_rows));
-          else API_TRY(gcn_final(c, rows, nC, c->c_flag.as<uint8_t>()));
-        }
-        // the baseline propagates from every node of the affected area, changed or not
-        if (c->affected_mode && !last) API_TRY(hipMemsetAsync(c->c_flag.p, 1, (size_t)nC, s));
-      }
-      st = emit_changed(c, nC, nxt, want_old, ld_next, !last, &nF2, &n_chg2);
-      if (st != INK_OK) return st;
-    } else if (lazy) {
-      API_TRY(read_counters(c));
-    }
-    if (lazy) { S.n_transformed = c->h_cnt->v[C_NC]; layer_stats_from_counters(c, l); }
-    S.n_changed = nF2;
-    nF = nF2;
-    n_chg = n_chg2;
-    cur = nxt;
-    if (l == c->n_layers) {
-      out->n_changed = nF;
-      if (nF > 0) {
-        int d = c->H[l].d;
-        API_TRY(c->res_ids.reserve((size_t)nF * 4));
-        API_TRY(c->res_emb.reserve((size_t)nF * d * 4));
-        API_TRY(hipMemcpyAsync(c->res_ids.p, c->f_list[cur].p, (size_t)nF * 4, hipMemcpyDeviceToDevice, s));
-        hipLaunchKernelGGL(k_gather_rows, grid1(nF * d), dim3(256), 0, s, (const float *)c->H[l].f(), c->H[l].ld, d,
-                           (const int32_t *)c->res_ids.p, nF, c->res_emb.as<float>());
-        out->changed_ids = c->res_ids.as<int32_t>();
-        out->embeddings = c->res_emb.as<float>();
-      }
-    }
   }
   API_TRY(graph_end_batch(c));
+  API_TRY(hipStreamSynchronize(s));
+  prof_collect(c);
+  c->stats.ms_total = std::chrono::duration<float, std::milli>(std::chrono::steady_clock::now() - t0).count();
+  return INK_OK;
+}
+
+// ------------------------------------------------------------------------------------ feature updates
+extern "C" ink_status ink_update_features(ink_ctx *c, const int32_t *node_ids, const float *rows, int64_t n,
+                                          ink_update_result *out) {
+  if (!c) return INK_E_ARG;
+  if (!out || n < 0 || (n > 0 && (!node_ids || !rows))) return fail(c, INK_E_ARG, "ink_update_features: NULL argument or negative n");
+  if (!c->inferred) return fail(c, INK_E_STATE, "ink_update_features: call ink_full_infer first");
+  if (n > c->n) return fail(c, INK_E_ARG, "ink_update_features: more rows than nodes (ids must be distinct)");
+  auto t0 = std::chrono::steady_clock::now();
+  memset(out, 0, sizeof(*out));
+  hipStream_t s = c->stream;
+  c->affected_mode = false;
+  const int d0 = c->H[0].d, ld0 = c->H[0].ld;
+  // validation before anything is touched: range on the host, distinctness on the sorted device copy
+  std::vector<int32_t> staged;
+  const int32_t *h = node_ids;
+  if (c->batch_dev && n > 0) {
+    staged.resize((size_t)n);
+    API_TRY(hipMemcpy(staged.data(), node_ids, (size_t)n * 4, hipMemcpyDeviceToHost));
+    h = staged.data();
+  }
+  for (int64_t i = 0; i < n; i++)
+    if (h[i] < 0 || h[i] >= c->n) return fail(c, INK_E_RANGE, "ink_update_features: node id out of range");
+  memset(&c->stats, 0, sizeof(c->stats));
+  c->stats.n_layers = c->n_layers;
+  if (n == 0) return INK_OK;
+  const bool gcn = c->kind == INK_MODEL_GCN;
+  const bool keep_old = !c->is_select;
+  Counters *dc = c->d_cnt;
+  int64_t nF = 0, n_chg = 0;
+  int cur = 0;
+  {
+    Prof p(c, INK_T_GRAPH);
+    const hipMemcpyKind kind = c->batch_dev ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice;
+    size_t per = ((size_t)n * 4 + 255) & ~(size_t)255;
+    API_TRY(c->b_misc.reserve(per * 2));
+    uint32_t *ids = c->b_misc.as<uint32_t>(), *perm = (uint32_t *)((char *)c->b_misc.p + per);
+    API_TRY(hipMemcpyAsync(ids, node_ids, (size_t)n * 4, kind, s));
+    const float *drows = rows;
+    if (!c->batch_dev) {
+      API_TRY(c->stage1.reserve((size_t)n * d0 * 4));
+      API_TRY(hipMemcpyAsync(c->stage1.p, rows, (size_t)n * d0 * 4, hipMemcpyHostToDevice, s));
+      drows = c->stage1.as<float>();
+    }
+    hipLaunchKernelGGL(k_iota_u32, grid1(n), dim3(256), 0, s, perm, n);
+    API_TRY(radix_sort_pairs(c->ws, ids, perm, n, c->id_bits, s));
+    API_TRY(hipMemsetAsync(dc, 0, sizeof(Counters), s));
+    hipLaunchKernelGGL(k_any_adjacent_equal, grid1(n), dim3(256), 0, s, (const uint32_t *)ids, n, &dc->v[C_TMP0]);
+    API_TRY(hipGetLastError());
+    API_TRY(read_counters(c));
+    if (c->h_cnt->v[C_TMP0]) return fail(c, INK_E_ARG, "ink_update_features: a node id appears more than once");
+    API_TRY(c->c_flag.reserve((size_t)n + 64));
+    API_TRY(c->c_idx.reserve((size_t)n * 4));
+    API_TRY(c->c_list.reserve((size_t)c->n * 4));
+    API_TRY(hipMemsetAsync(c->c_flag.p, 0, (size_t)n, s));
+    float *old0 = nullptr, *dense = nullptr;
+    if (keep_old && !gcn) { API_TRY(c->c_old.reserve((size_t)n * ld0 * 4)); old0 = c->c_old.as<float>(); }
+    if (gcn) { API_TRY(c->stage0.reserve((size_t)n * ld0 * 4)); dense = c->stage0.as<float>(); }
+    hipLaunchKernelGGL(k_set_features, grid1(n * ld0), dim3(256), 0, s, (const uint32_t *)ids, (const uint32_t *)perm, n,
+                       drows, d0, c->H[0].f(), ld0, old0, dense, c->c_flag.as<uint8_t>(), c->c_list.as<int32_t>());
+    API_TRY(hipGetLastError());
+  }
+  int ld_msg = ld0;
+  if (gcn) {
+    // layer-1 messages are c_u (x_u W_1): redo the product for the listed rows, then rescale
+    Prof p(c, INK_T_TRANSFORM);
+    const DevLayer &L = c->layers[0];
+    ld_msg = c->Msc[1].ld;
+    XformArgs x;
+    memset(&x, 0, sizeof(x));
+    x.mode = 2; x.n_rows = n; x.Hp = c->stage0.as<float>(); x.ldh = ld0; x.d_in = L.in_dim;
+    x.W = L.W1; x.Kp = L.K1p; x.Np = L.N1p; x.n_out = L.out_dim;
+    x.out = c->XW[1].f(); x.ld_out = c->XW[1].ld; x.to_table = 1; x.out_rows = c->c_list.as<int32_t>();
+    API_TRY(xform_run(c, x));
+    API_TRY(c->c_old.reserve((size_t)n * ld_msg * 4));
+    API_TRY(hipMemsetAsync(c->c_flag.p, 0, (size_t)n, s));
+    hipLaunchKernelGGL(k_gcn_rescale, grid1(n * ld_msg), dim3(256), 0, s, (const int32_t *)c->c_list.as<int32_t>(), n,
+                       (const int32_t *)c->gin.deg, c->cnorm, (const float *)c->XW[1].f(), c->Msc[1].f(), ld_msg,
+                       c->Msc[1].d, c->c_old.as<float>(), c->c_flag.as<uint8_t>());
+    API_TRY(hipGetLastError());
+  }
+  ink_status st = emit_changed(c, n, cur, keep_old, ld_msg, true, &nF, &n_chg);
+  if (st != INK_OK) return st;
+  st = propagate_layers(c, nF, n_chg, cur, 0, 0, nullptr, 0, out);
+  if (st != INK_OK) return st;
   API_TRY(hipStreamSynchronize(s));
   prof_collect(c);
   c->stats.ms_total = std::chrono::duration<float, std::milli>(std::chrono::steady_clock::now() - t0).count();

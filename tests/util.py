@@ -105,12 +105,8 @@ class Harness:
         rp2, col2 = oracle.csr_from_keys(self.n, self.keys)
         assert np.array_equal(rp, rp2) and np.array_equal(col, col2), "graph store differs from the oracle's edge set"
 
-    def step(self, op, bs, bd, exact=True, tol=1e-5, affected=False):
-        from paper_2309_11071_amd.binding import make_updates
-        res = self.ink.apply_updates(make_updates(op, bs, bd), affected=affected)
-        keys2, n_ins, n_del, n_noop = oracle.apply_batch(self.keys, op, bs, bd)
-        assert (res["n_applied_ins"], res["n_applied_del"], res["n_noop"]) == (n_ins, n_del, n_noop)
-        post = oracle.full_infer(*oracle.csr_from_keys(self.n, keys2), self.X, self.model, self.precision)
+    def _compare(self, res, post, exact, tol):
+        """Result of an incremental call against the oracle's inference `post` of the new snapshot."""
         want = oracle.changed_nodes(self.ref, post)[-1]
         if exact:
             assert np.array_equal(res["changed_ids"], want), "changed-node set differs"
@@ -130,5 +126,28 @@ class Harness:
             floor_rows = np.maximum(np.abs(hk_post[got]).max(axis=1), floor)
             err = np.abs(res["embeddings"].astype(np.float64) - hk_post[got]).max(axis=1) / floor_rows if got.size else np.zeros(0)
             assert got.size == 0 or err.max() <= tol, "returned embeddings beyond tolerance: %g" % err.max()
+        return want
+
+    def feature_step(self, ids, rows, exact=True, tol=1e-5):
+        """x_v <- rows[i] for v = ids[i] through ink_update_features, against the oracle's full
+        inference with the new feature table."""
+        ids = np.asarray(ids, np.int32)
+        rows = np.ascontiguousarray(rows, np.float32).reshape(ids.size, self.X.shape[1])
+        res = self.ink.update_features(ids, rows)
+        assert (res["n_applied_ins"], res["n_applied_del"], res["n_noop"]) == (0, 0, 0)
+        X2 = self.X.copy()
+        X2[ids] = rows
+        post = oracle.full_infer(*oracle.csr_from_keys(self.n, self.keys), X2, self.model, self.precision)
+        want = self._compare(res, post, exact, tol)
+        self.X, self.ref = X2, post
+        return res, want
+
+    def step(self, op, bs, bd, exact=True, tol=1e-5, affected=False):
+        from paper_2309_11071_amd.binding import make_updates
+        res = self.ink.apply_updates(make_updates(op, bs, bd), affected=affected)
+        keys2, n_ins, n_del, n_noop = oracle.apply_batch(self.keys, op, bs, bd)
+        assert (res["n_applied_ins"], res["n_applied_del"], res["n_noop"]) == (n_ins, n_del, n_noop)
+        post = oracle.full_infer(*oracle.csr_from_keys(self.n, keys2), self.X, self.model, self.precision)
+        want = self._compare(res, post, exact, tol)
         self.keys, self.ref = keys2, post
         return res, want
