@@ -112,6 +112,9 @@ typedef struct {
   int64_t pool_reserve;  /* free id slots kept behind the edge blocks of each direction for blocks
                             that outgrow their slack; when they run out the pool is re-allocated
                             at twice the size.  0 = default max(25 % of the pool, 2^20) */
+  int64_t node_capacity; /* largest node count the context can grow to with ink_add_nodes; every
+                            per-node table is allocated for it.  0 (or less than the graph's
+                            node count) = the graph's node count, i.e. no growth */
 } ink_options;
 
 /* One streaming update (Sec. 2.1: Delta E holds inserted and removed edges). */
@@ -205,6 +208,17 @@ ink_status ink_apply_updates_affected(ink_ctx *ctx, const ink_edge_update *updat
  * INK_E_ARG for a repeated id, n < 0 or NULL arrays.  On error nothing is changed. */
 ink_status ink_update_features(ink_ctx *ctx, const int32_t *node_ids, const float *rows, int64_t n,
                                ink_update_result *out);
+
+/* Node arrival (Sec. 1 names newly arriving nodes as one source of change; Sec. 2.1 defines the
+ * update stream over edges only, so a node arrives without edges and its edges follow through
+ * ink_apply_updates).  Appends n_new nodes with ids n_nodes .. n_nodes + n_new - 1 and the given
+ * feature rows ([n_new][feat_dim], host or device like the update batches).  Their cached state
+ * is that of a node with an empty neighbourhood (alpha = 0, argument -1; GCN: d-hat = 1) and
+ * their embeddings are computed layer by layer from it; no other node changes.  The result lists
+ * the new ids with their final embeddings.
+ * Errors: INK_E_STATE before ink_full_infer; INK_E_RANGE if the node count would exceed
+ * ink_options.node_capacity; INK_E_ARG for n_new < 0 or NULL features.  On error nothing changes. */
+ink_status ink_add_nodes(ink_ctx *ctx, const float *features, int64_t n_new, ink_update_result *out);
 
 /* Inspection for tests: copies rows [row0, row0 + nrows) of a cached table to dst (host or
  * device per dst_mem), densely packed [nrows][width].  layer in 0..n_layers.

@@ -47,7 +47,7 @@ class _Model(C.Structure):
 class _Options(C.Structure):
     _fields_ = [("mem", C.c_int32), ("hip_stream", C.c_void_p), ("slack_factor", C.c_float),
                 ("max_batch", C.c_int32), ("profile", C.c_int32), ("dense_threshold", C.c_float), ("batch_mem", C.c_int32),
-                ("pad_", C.c_int32), ("pool_reserve", C.c_int64)]
+                ("pad_", C.c_int32), ("pool_reserve", C.c_int64), ("node_capacity", C.c_int64)]
 
 
 class _Result(C.Structure):
@@ -96,6 +96,8 @@ def load_library():
     lib.ink_apply_updates_affected.restype = C.c_int
     lib.ink_update_features.argtypes = [vp, vp, vp, C.c_int64, C.POINTER(_Result)]
     lib.ink_update_features.restype = C.c_int
+    lib.ink_add_nodes.argtypes = [vp, vp, C.c_int64, C.POINTER(_Result)]
+    lib.ink_add_nodes.restype = C.c_int
     lib.ink_get_layer.argtypes = [vp, C.c_int32, C.c_int32, C.c_int64, C.c_int64, vp, C.c_int32,
                                   C.POINTER(C.c_int32)]
     lib.ink_get_layer.restype = C.c_int
@@ -128,7 +130,7 @@ class Ink:
     """One context.  `model` is the dict layout of synth.make_model (host numpy weights)."""
 
     def __init__(self, rowptr, col, features, model, slack_factor=0.25, profile=False, stream=None,
-                 dense_threshold=0.0, pool_reserve=0, batch_device=False):
+                 dense_threshold=0.0, pool_reserve=0, batch_device=False, node_capacity=0):
         self._lib = load_library()
         self._h = C.c_void_p()
         rowptr = np.ascontiguousarray(rowptr, np.int64)
@@ -151,7 +153,7 @@ class Ink:
                    len(model["layers"]), layers)
         g = _Csr(rowptr.size - 1, col.size, rowptr.ctypes.data, col.ctypes.data if col.size else None)
         o = _Options(0, stream, slack_factor, 0, int(bool(profile)), dense_threshold,
-                     1 if batch_device else 0, 0, pool_reserve)
+                     1 if batch_device else 0, 0, pool_reserve, node_capacity)
         st = self._lib.ink_create(C.byref(g), features.ctypes.data, features.shape[1], C.byref(m), C.byref(o),
                                   C.byref(self._h))
         if st != 0:
@@ -217,6 +219,24 @@ class Ink:
                                                   C.byref(r)))
         out = dict(n_changed=r.n_changed, n_applied_ins=r.n_applied_ins, n_applied_del=r.n_applied_del,
                    n_noop=r.n_noop, changed_ids_ptr=r.changed_ids, embeddings_ptr=r.embeddings)
+        if fetch:
+            ids = np.empty(r.n_changed, np.int32)
+            emb = np.empty((r.n_changed, self.out_dim), np.float32)
+            if r.n_changed:
+                _dtoh(ids, r.changed_ids)
+                _dtoh(emb, r.embeddings)
+            out["changed_ids"], out["embeddings"] = ids, emb
+        return out
+
+    def add_nodes(self, features, fetch=True):
+        """Appends len(features) nodes without edges; returns their ids and final embeddings."""
+        assert not self.batch_device, "context expects device batches"
+        features = np.ascontiguousarray(features, dtype=np.float32).reshape(-1, self.feat_dim)
+        r = _Result()
+        self._check(self._lib.ink_add_nodes(self._h, features.ctypes.data if features.size else None,
+                                            features.shape[0], C.byref(r)))
+        self.n += features.shape[0]
+        out = dict(n_changed=r.n_changed, changed_ids_ptr=r.changed_ids, embeddings_ptr=r.embeddings)
         if fetch:
             ids = np.empty(r.n_changed, np.int32)
             emb = np.empty((r.n_changed, self.out_dim), np.float32)

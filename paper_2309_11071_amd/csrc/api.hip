@@ -366,10 +366,12 @@ extern "C" ink_status ink_create(const ink_csr *g, const float *features, int32_
       if (e > rowptr[v] && col[e - 1] >= u) return fail(nullptr, INK_E_ARG, "ink_create: row not strictly ascending");
     }
   }
+  if (opts && opts->node_capacity >= (1 << 30)) return fail(nullptr, INK_E_ARG, "ink_create: node_capacity too large");
   ink_ctx *c = new (std::nothrow) ink_ctx();
   if (!c) return fail(nullptr, INK_E_OOM, "ink_create: host allocation failed");
   c->n = n; c->n_edges = E; c->n_edges_now = E;
-  c->id_bits = 1; while ((1ll << c->id_bits) < n) c->id_bits++;
+  c->n_cap = (opts && opts->node_capacity > n) ? opts->node_capacity : n;
+  c->id_bits = 1; while ((1ll << c->id_bits) < c->n_cap) c->id_bits++;
   c->kind = model->kind; c->agg = model->agg; c->n_layers = model->n_layers; c->eps = model->gin_eps;
   c->is_select = model->agg == INK_AGG_MAX || model->agg == INK_AGG_MIN; c->is_min = model->agg == INK_AGG_MIN;
   c->mem = dev ? INK_MEM_DEVICE : INK_MEM_HOST;
@@ -391,12 +393,13 @@ extern "C" ink_status ink_create(const ink_csr *g, const float *features, int32_
   if (opts && opts->hip_stream) c->stream = (hipStream_t)opts->hip_stream;
   else { CREATE_TRY(hipStreamCreate(&c->stream)); c->own_stream = true; }
   CREATE_TRY(graph_build(c, rowptr.data(), col.data()));
-  CREATE_TRY(hipMalloc(&c->new_out, (size_t)n * 4));
-  CREATE_TRY(hipMemset(c->new_out, 0, (size_t)n * 4));
+  const int64_t nc = c->n_cap;     // every per-node array is allocated for the capacity
+  CREATE_TRY(hipMalloc(&c->new_out, (size_t)nc * 4));
+  CREATE_TRY(hipMemset(c->new_out, 0, (size_t)nc * 4));
   CREATE_TRY(hipMalloc(&c->d_cnt, sizeof(Counters)));
   CREATE_TRY(hipMemset(c->d_cnt, 0, sizeof(Counters)));
   CREATE_TRY(hipHostMalloc((void **)&c->h_cnt, sizeof(Counters)));
-  size_t bmw = ((size_t)n + 63) / 64;
+  size_t bmw = ((size_t)nc + 63) / 64;
   CREATE_TRY(hipMalloc(&c->bm_a, bmw * 8));
   CREATE_TRY(hipMemset(c->bm_a, 0, bmw * 8));
   if (opts && opts->max_batch > 0) {       // size the batch staging up front
@@ -408,8 +411,8 @@ extern "C" ink_status ink_create(const ink_csr *g, const float *features, int32_
   c->H.resize(c->n_layers + 1); c->A.resize(c->n_layers + 1); c->ARG.resize(c->n_layers + 1);
   c->UB.resize(c->n_layers + 1);
   c->XW.resize(c->n_layers + 1); c->Msc.resize(c->n_layers + 1);
-  if (c->kind == INK_MODEL_GCN) CREATE_TRY(hipMalloc(&c->cnorm, (size_t)n * 4));
-  CREATE_TRY(alloc_table(c->H[0], n, feat_dim));
+  if (c->kind == INK_MODEL_GCN) CREATE_TRY(hipMalloc(&c->cnorm, (size_t)nc * 4));
+  CREATE_TRY(alloc_table(c->H[0], nc, feat_dim));
   {
     DevBuf tmp;
     const float *src = features;
@@ -428,12 +431,12 @@ extern "C" ink_status ink_create(const ink_csr *g, const float *features, int32_
     const ink_layer &S = model->layers[l - 1];
     DevLayer &L = c->layers[l - 1];
     L.in_dim = S.in_dim; L.out_dim = S.out_dim; L.hidden = S.mlp_hidden; L.act = S.act;
-    CREATE_TRY(alloc_table(c->H[l], n, S.out_dim));
-    CREATE_TRY(alloc_table(c->A[l], n, c->kind == INK_MODEL_GCN ? S.out_dim : S.in_dim));
-    if (c->is_select) { CREATE_TRY(alloc_table(c->ARG[l], n, S.in_dim)); CREATE_TRY(alloc_table(c->UB[l], n, S.in_dim)); }
+    CREATE_TRY(alloc_table(c->H[l], nc, S.out_dim));
+    CREATE_TRY(alloc_table(c->A[l], nc, c->kind == INK_MODEL_GCN ? S.out_dim : S.in_dim));
+    if (c->is_select) { CREATE_TRY(alloc_table(c->ARG[l], nc, S.in_dim)); CREATE_TRY(alloc_table(c->UB[l], nc, S.in_dim)); }
     if (c->kind == INK_MODEL_GCN) {
-      CREATE_TRY(alloc_table(c->Msc[l], n, S.out_dim));
-      if (l == 1) CREATE_TRY(alloc_table(c->XW[1], n, S.out_dim));
+      CREATE_TRY(alloc_table(c->Msc[l], nc, S.out_dim));
+      if (l == 1) CREATE_TRY(alloc_table(c->XW[1], nc, S.out_dim));
       L.K1 = S.in_dim; L.K1p = round_up(L.K1, 32); L.N1 = S.out_dim; L.N1p = round_up(L.N1, 32);
       CREATE_TRY(hipMalloc(&L.W1, (size_t)L.K1p * L.N1p * 4));
       CREATE_TRY(hipMemset(L.W1, 0, (size_t)L.K1p * L.N1p * 4));
@@ -1001,6 +1004,96 @@ extern "C" ink_status ink_update_features(ink_ctx *c, const int32_t *node_ids, c
   if (st != INK_OK) return st;
   st = propagate_layers(c, nF, n_chg, cur, 0, 0, nullptr, 0, out);
   if (st != INK_OK) return st;
+  API_TRY(hipStreamSynchronize(s));
+  prof_collect(c);
+  c->stats.ms_total = std::chrono::duration<float, std::milli>(std::chrono::steady_clock::now() - t0).count();
+  return INK_OK;
+}
+
+// ------------------------------------------------------------------------------------ node arrival
+__global__ void k_iota_i32(int32_t *out, int64_t n, int32_t first) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) out[i] = first + (int32_t)i;
+}
+
+__global__ void k_unpack_rows_at(const float *in, int d, int ld, int64_t row0, int64_t n, float *table) {
+  int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t i = t / ld;
+  int k = (int)(t % ld);
+  if (i >= n) return;
+  table[(row0 + i) * ld + k] = k < d ? in[i * d + k] : 0.f;
+}
+
+extern "C" ink_status ink_add_nodes(ink_ctx *c, const float *features, int64_t n_new, ink_update_result *out) {
+  if (!c) return INK_E_ARG;
+  if (!out || n_new < 0 || (n_new > 0 && !features)) return fail(c, INK_E_ARG, "ink_add_nodes: NULL argument or negative n_new");
+  if (!c->inferred) return fail(c, INK_E_STATE, "ink_add_nodes: call ink_full_infer first");
+  if ((int64_t)c->n + n_new > c->n_cap) return fail(c, INK_E_RANGE, "ink_add_nodes: beyond ink_options.node_capacity");
+  auto t0 = std::chrono::steady_clock::now();
+  memset(out, 0, sizeof(*out));
+  memset(&c->stats, 0, sizeof(c->stats));
+  c->stats.n_layers = c->n_layers;
+  if (n_new == 0) return INK_OK;
+  hipStream_t s = c->stream;
+  c->affected_mode = false;
+  const int n0 = c->n;
+  const int d0 = c->H[0].d, ld0 = c->H[0].ld;
+  const bool gcn = c->kind == INK_MODEL_GCN;
+  {
+    Prof p(c, INK_T_GRAPH);
+    ink_status st = graph_add_nodes(c, n_new);
+    if (st != INK_OK) return st;
+    const float *drows = features;
+    if (!c->batch_dev) {
+      API_TRY(c->stage1.reserve((size_t)n_new * d0 * 4));
+      API_TRY(hipMemcpyAsync(c->stage1.p, features, (size_t)n_new * d0 * 4, hipMemcpyHostToDevice, s));
+      drows = c->stage1.as<float>();
+    }
+    hipLaunchKernelGGL(k_unpack_rows_at, grid1(n_new * ld0), dim3(256), 0, s, drows, d0, ld0, (int64_t)n0, n_new, c->H[0].f());
+    API_TRY(c->res_ids.reserve((size_t)n_new * 4));
+    hipLaunchKernelGGL(k_iota_i32, grid1(n_new), dim3(256), 0, s, c->res_ids.as<int32_t>(), n_new, (int32_t)n0);
+    API_TRY(hipGetLastError());
+  }
+  c->n = n0 + (int)n_new;          // from here on the new ids are valid rows
+  const int32_t *rows = c->res_ids.as<int32_t>();
+  if (gcn) {
+    // layer-1 message of a node without in-edges: d-hat = 1, so c_v = 1 and m_1 = x W_1
+    Prof p(c, INK_T_TRANSFORM);
+    const DevLayer &L = c->layers[0];
+    XformArgs x;
+    memset(&x, 0, sizeof(x));
+    x.mode = 2; x.n_rows = n_new; x.Hp = c->H[0].f() + (int64_t)n0 * ld0; x.ldh = ld0; x.d_in = L.in_dim;
+    x.W = L.W1; x.Kp = L.K1p; x.Np = L.N1p; x.n_out = L.out_dim;
+    x.out = c->XW[1].f(); x.ld_out = c->XW[1].ld; x.to_table = 1; x.out_rows = rows;
+    API_TRY(xform_run(c, x));
+    hipLaunchKernelGGL(k_gcn_rescale, grid1(n_new * c->Msc[1].ld), dim3(256), 0, s, rows, n_new, (const int32_t *)c->gin.deg,
+                       c->cnorm, (const float *)c->XW[1].f(), c->Msc[1].f(), c->Msc[1].ld, c->Msc[1].d, (float *)nullptr,
+                       (uint8_t *)nullptr);
+    API_TRY(hipGetLastError());
+  }
+  for (int l = 1; l <= c->n_layers; l++) {
+    API_TRY(hipMemsetAsync(c->d_cnt, 0, sizeof(Counters), s));
+    AggArgs a = agg_args(c, l);
+    { Prof p(c, INK_T_AGG); API_TRY(agg_full_any(c, a, nullptr, rows, n_new)); }
+    {
+      Prof p(c, INK_T_TRANSFORM);
+      if (!gcn) API_TRY(run_transform(c, l, rows, n_new, nullptr));
+      else if (l < c->n_layers) API_TRY(gcn_next_messages(c, l, rows, n_new, nullptr, nullptr));
+      else API_TRY(gcn_final(c, rows, n_new, nullptr));
+    }
+    ink_layer_stats &S = c->stats.layer[l - 1];
+    S.n_targets = n_new; S.n_exposed = n_new; S.n_transformed = n_new; S.n_changed = n_new;
+  }
+  {
+    int k = c->n_layers, d = c->H[k].d;
+    API_TRY(c->res_emb.reserve((size_t)n_new * d * 4));
+    hipLaunchKernelGGL(k_gather_rows, grid1(n_new * d), dim3(256), 0, s, (const float *)c->H[k].f(), c->H[k].ld, d, rows,
+                       n_new, c->res_emb.as<float>());
+    API_TRY(hipGetLastError());
+    out->n_changed = n_new;
+    out->changed_ids = c->res_ids.as<int32_t>();
+    out->embeddings = c->res_emb.as<float>();
+  }
   API_TRY(hipStreamSynchronize(s));
   prof_collect(c);
   c->stats.ms_total = std::chrono::duration<float, std::milli>(std::chrono::steady_clock::now() - t0).count();

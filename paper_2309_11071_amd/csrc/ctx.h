@@ -97,6 +97,7 @@ struct ink_ctx {
   int n = 0;
   int64_t n_edges = 0, n_edges_now = 0;
   int64_t pool_reserve = 0;
+  int64_t n_cap = 0;          // node capacity: every per-node array has this many entries (>= n)
   int64_t big_hint[INK_MAX_LAYERS + 1] = {0};   // chunks of long rows seen by the last update at each layer
   double dense_frac = 0.75;          // events / edges above which a layer re-aggregates every node
   int id_bits = 1;
@@ -157,6 +158,7 @@ namespace ink {
 hipError_t graph_build(ink_ctx *c, const int64_t *rowptr_h, const int32_t *col_h);
 // applies a validated batch already on the device in c->b_raw; fills Delta E lists and counts
 ink_status graph_apply_batch(ink_ctx *c, int64_t n, int64_t *n_ins, int64_t *n_del);
+ink_status graph_add_nodes(ink_ctx *c, int64_t n_new);   // empty edge blocks for nodes n .. n + n_new - 1 (before n grows)
 hipError_t graph_end_batch(ink_ctx *c);     // clears per-batch marks (new_out)
 hipError_t graph_export(ink_ctx *c, int64_t *rowptr_h, int32_t *col_h);
 

@@ -41,9 +41,10 @@ static hipError_t side_alloc(GraphSide &g, int n, const std::vector<int64_t> &of
 
 hipError_t graph_build(ink_ctx *c, const int64_t *rowptr, const int32_t *col) {
   const int n = c->n;
+  const int nc = (int)c->n_cap;        // per-node arrays cover the capacity; nodes >= n own no block yet
   const int64_t E = rowptr[n];
-  std::vector<int64_t> off(n);
-  std::vector<int32_t> deg(n), cap(n);
+  std::vector<int64_t> off(nc, 0);
+  std::vector<int32_t> deg(nc, 0), cap(nc, 0);
   // in side straight from the CSR
   int64_t top = 0;
   for (int v = 0; v < n; v++) {
@@ -54,7 +55,7 @@ hipError_t graph_build(ink_ctx *c, const int64_t *rowptr, const int32_t *col) {
   {
     std::vector<int32_t> ids((size_t)top, -1);
     for (int v = 0; v < n; v++) std::copy(col + rowptr[v], col + rowptr[v + 1], ids.begin() + off[v]);
-    INK_TRY(side_alloc(c->gin, n, off, deg, cap, ids, top, c->pool_reserve));
+    INK_TRY(side_alloc(c->gin, nc, off, deg, cap, ids, top, c->pool_reserve));
   }
   // out side: transpose
   std::vector<int32_t> odeg(n, 0);
@@ -69,7 +70,7 @@ hipError_t graph_build(ink_ctx *c, const int64_t *rowptr, const int32_t *col) {
     std::vector<int64_t> cur(off);
     for (int v = 0; v < n; v++)
       for (int64_t e = rowptr[v]; e < rowptr[v + 1]; e++) ids[cur[col[e]]++] = v;
-    INK_TRY(side_alloc(c->gout, n, off, deg, cap, ids, top, c->pool_reserve));
+    INK_TRY(side_alloc(c->gout, nc, off, deg, cap, ids, top, c->pool_reserve));
   }
   return hipSuccess;
 }
@@ -376,6 +377,32 @@ static hipError_t grow_pool(ink_ctx *c, GraphSide &g, int64_t need_total) {
   g.ids = np;
   g.pool_cap = new_cap;
   return hipSuccess;
+}
+
+// empty blocks of kNewNodeCap slots for the nodes n0 .. n0 + n_new - 1 at the pool's top
+constexpr int kNewNodeCap = 4;
+__global__ void k_init_blocks(int64_t *off, int32_t *deg, int32_t *cap, int32_t *ids, int n0, int64_t n_new, int64_t top) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n_new) return;
+  int64_t o = top + i * kNewNodeCap;
+  off[n0 + i] = o; deg[n0 + i] = 0; cap[n0 + i] = kNewNodeCap;
+  for (int k = 0; k < kNewNodeCap; k++) ids[o + k] = -1;
+}
+
+ink_status graph_add_nodes(ink_ctx *c, int64_t n_new) {
+  for (GraphSide *g : {&c->gin, &c->gout}) {
+    int64_t need = n_new * kNewNodeCap;
+    if (g->pool_top + need > g->pool_cap) {
+      hipError_t e = grow_pool(c, *g, need);
+      if (e == hipErrorOutOfMemory) { c->err = "out of device memory while growing the edge pool"; return INK_E_OOM; }
+      INK_TRYS(e);
+    }
+    hipLaunchKernelGGL(k_init_blocks, grid1(n_new), dim3(256), 0, c->stream, g->off, g->deg, g->cap, g->ids, c->n, n_new,
+                       g->pool_top);
+    INK_TRYS(hipGetLastError());
+    g->pool_top += need;
+  }
+  return INK_OK;
 }
 
 // One direction.  Ops (node, other, op, pos) are in (node, other) order on the device; n_ops is

@@ -19,7 +19,7 @@ def declared_functions():
 
 def test_header_declares_the_boundary_calls():
     names = declared_functions()
-    for must in ("ink_create", "ink_full_infer", "ink_apply_updates", "ink_apply_updates_affected", "ink_update_features", "ink_get_layer", "ink_get_graph",
+    for must in ("ink_create", "ink_full_infer", "ink_apply_updates", "ink_apply_updates_affected", "ink_update_features", "ink_add_nodes", "ink_get_layer", "ink_get_graph",
                  "ink_get_stats", "ink_set_profiling", "ink_last_error", "ink_destroy"):
         assert must in names
 

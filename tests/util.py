@@ -34,7 +34,7 @@ class Harness:
     """Keeps the oracle's view (edge-key set, full inference) next to an Ink context."""
 
     def __init__(self, cfg=None, model=None, precision="f32", slack=0.25, profile=False, graph=None, X=None,
-                 dense_threshold=0.0, pool_reserve=0):
+                 dense_threshold=0.0, pool_reserve=0, node_capacity=0):
         """Either a workload config, or an explicit graph=(n, src, dst) with features X and a model."""
         from paper_2309_11071_amd import Ink
         self.cfg = cfg
@@ -52,7 +52,7 @@ class Harness:
         self.keys = np.unique(synth.edge_keys(self.src, self.dst))
         rp, col = oracle.csr_from_keys(self.n, self.keys)
         self.ink = Ink(rp, col, self.X, self.model, slack_factor=slack, profile=profile,
-                       dense_threshold=dense_threshold, pool_reserve=pool_reserve)
+                       dense_threshold=dense_threshold, pool_reserve=pool_reserve, node_capacity=node_capacity)
         self.ink.full_infer()
         self.ref = oracle.full_infer(rp, col, self.X, self.model, precision)
         self.sampler = synth.BatchSampler(cfg, self.src, self.dst) if cfg is not None else None
@@ -141,6 +141,26 @@ class Harness:
         want = self._compare(res, post, exact, tol)
         self.X, self.ref = X2, post
         return res, want
+
+    def add_nodes(self, features, exact=True, tol=1e-5):
+        """Appends nodes without edges through ink_add_nodes; the oracle re-runs on the grown graph."""
+        features = np.ascontiguousarray(features, np.float32).reshape(-1, self.X.shape[1])
+        k = features.shape[0]
+        res = self.ink.add_nodes(features)
+        n2 = self.n + k
+        X2 = np.concatenate([self.X, features], axis=0)
+        post = oracle.full_infer(*oracle.csr_from_keys(n2, self.keys), X2, self.model, self.precision)
+        ids = np.arange(self.n, n2, dtype=np.int32)
+        assert res["n_changed"] == k and np.array_equal(res["changed_ids"], ids)
+        for l in range(len(post["h"])):          # the old nodes' rows are untouched by definition
+            assert np.array_equal(post["h"][l][:self.n].view(np.uint32), self.ref["h"][l].view(np.uint32))
+        want = post["h"][-1][ids]
+        if exact:
+            assert np.array_equal(res["embeddings"].view(np.uint32), want.view(np.uint32))
+        elif k:
+            assert scaled_rel_err(res["embeddings"], want) <= tol
+        self.n, self.X, self.ref = n2, X2, post
+        return res
 
     def step(self, op, bs, bd, exact=True, tol=1e-5, affected=False):
         from paper_2309_11071_amd.binding import make_updates
