@@ -9,7 +9,13 @@
 // holder that got worse but still strictly beats that bound stays the holder, and a candidate that
 // strictly beats it covers a reset even if it is worse than the old value: both save the
 // recompute that the value-only rule of Sec. 2.5.1 would need.
+#include <algorithm>
+
 #include "bigrows.h"
+
+#ifndef INK_EVENT_GRID
+#define INK_EVENT_GRID 8192        // workgroups of the event kernel (measured: 4096-8192 best, fewer leave a tail)
+#endif
 
 namespace ink {
 
@@ -263,17 +269,12 @@ __global__ __launch_bounds__(64) void k_big_final(AggArgs a, const int32_t *big_
 // A reset dimension is covered when the best candidate strictly beats the old value, otherwise
 // the row is exposed and recomputed from its whole current neighbourhood.
 template <bool IS_MIN, int LPR>
-__global__ __launch_bounds__(256) void k_agg_events(AggArgs a, const int32_t *targets, const int32_t *seg,
-                                                    const int32_t *n_targets_p, const uint32_t *ev, uint64_t *chg,
-                                                    int32_t *big_list, Counters *cnt) {
+__device__ __forceinline__ void agg_events_one(const AggArgs &a, int v, int e0, int e1, const uint32_t *ev, uint64_t *chg,
+                                               int32_t *big_list, Counters *cnt) {
   constexpr int G = kWave / LPR;
   const int l = lane_id();
   const int q = l % LPR, g = l / LPR;
   const bool lane_on = 4 * q < a.wd;
-  int64_t wid = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kWave;
-  if (wid >= *n_targets_p) return;
-  int v = targets[wid];
-  int e0 = seg[wid], e1 = seg[wid + 1];
   F4 ov; I4 oi; F4 ou;       // cached value, holder and bound on the other neighbours
 #pragma unroll
   for (int c = 0; c < 4; c++) { ov.v[c] = 0.f; oi.v[c] = -1; ou.v[c] = worst<IS_MIN>(); }
@@ -389,6 +390,19 @@ __global__ __launch_bounds__(256) void k_agg_events(AggArgs a, const int32_t *ta
   if (ch && l == 0) { mark_bit(chg, v); atomicAdd(&cnt->stripe[blockIdx.x % kStripes][ST_ACHG], 1ull); }
 }
 
+// The grid is sized to what the chip holds at once; every wave walks the target list with the
+// grid's wave count as stride (a wave per target costs more in wave launches than in work when
+// a target has a handful of events).
+template <bool IS_MIN, int LPR>
+__global__ __launch_bounds__(256) void k_agg_events(AggArgs a, const int32_t *targets, const int32_t *seg,
+                                                    const int32_t *n_targets_p, const uint32_t *ev, uint64_t *chg,
+                                                    int32_t *big_list, Counters *cnt) {
+  const int64_t n = *n_targets_p;
+  const int64_t stride = (int64_t)gridDim.x * (blockDim.x / kWave);
+  for (int64_t wid = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kWave; wid < n; wid += stride)
+    agg_events_one<IS_MIN, LPR>(a, targets[wid], seg[wid], seg[wid + 1], ev, chg, big_list, cnt);
+}
+
 // ------------------------------------------------------------------ host side
 static int lanes_per_row(int ld) { return ld <= 64 ? 16 : (ld <= 128 ? 32 : 64); }
 
@@ -438,7 +452,7 @@ static hipError_t events_t(ink_ctx *c, const AggArgs &a_in, const int32_t *targe
   AggArgs a = a_in;
   a.big_deg = big_threshold(n_targets, LPR, kBigDeg);
   INK_TRY(ensure_big_buffers(c, a.wd, true));
-  int64_t blocks = (n_targets + 3) / 4;
+  int64_t blocks = std::min<int64_t>((n_targets + 3) / 4, INK_EVENT_GRID);
   hipLaunchKernelGGL((k_agg_events<IS_MIN, LPR>), dim3((unsigned)blocks), dim3(256), 0, c->stream, a, targets, seg,
                      n_targets_dev, ev, chg, c->big_list.as<int32_t>(), c->d_cnt);
   INK_TRY(hipGetLastError());
