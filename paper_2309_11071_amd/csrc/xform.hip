@@ -119,7 +119,7 @@ constexpr int XS = 36;
 
 // Compute phase of one k-chunk for the NTW column tiles ct0, ct0 + 2, ... of this wave: all LDS
 // reads of a tile are issued before its 16 back-to-back MFMAs.
-template <int NTW>
+template <int NTW, int CS>
 __device__ __forceinline__ void mfma_chunk(const float *Xs, const float *Ws, int rt, int ct0, int l, f16v *acc) {
   const float *ap = Xs + (rt * 32 + (l & 31)) * XS + (l >> 5) * 16;
   float a[16];
@@ -130,7 +130,7 @@ __device__ __forceinline__ void mfma_chunk(const float *Xs, const float *Ws, int
   }
 #pragma unroll
   for (int i = 0; i < NTW; i++) {
-    const float *bp = Ws + ((ct0 + 2 * i) * 32 + (l & 31)) * XS + (l >> 5) * 16;
+    const float *bp = Ws + ((ct0 + CS * i) * 32 + (l & 31)) * XS + (l >> 5) * 16;
     float b[16];
 #pragma unroll
     for (int v = 0; v < 4; v++) {
@@ -143,17 +143,22 @@ __device__ __forceinline__ void mfma_chunk(const float *Xs, const float *Ws, int
   }
 }
 
-// NT = number of 32-column tiles (Np / 32).  Waves 0,1 take tiles 0,2,4,..; waves 2,3 tiles 1,3,5,..
-template <int MODE, int NT>
-__global__ __launch_bounds__(256) void k_xform(XformArgs x) {
+// NT = number of 32-column tiles (Np / 32), NW = waves per workgroup (4 or 8).  Wave w works on
+// row tile w & 1 and on the column tiles w / 2, w / 2 + NW / 2, ...
+template <int MODE, int NT, int NW>
+__global__ __launch_bounds__(NW * 64) void k_xform(XformArgs x) {
   extern __shared__ float smem[];
   float *Xs = smem;                           // [BM][XS]
   float *Ws = smem + BM * XS;                 // [Np][XS]
   __shared__ int64_t srow[BM];     // input row (gather) of each tile row, -1 past the end
   __shared__ int64_t sout[BM];     // table row written by the epilogue
   __shared__ int schg[BM];
-  constexpr int TPW = (NT + 1) / 2;
+  constexpr int CS = NW / 2;                  // column-tile stride between the tiles of one wave
+  constexpr int TPW = (NT + CS - 1) / CS;
   constexpr int Np = NT * 32;
+  constexpr int NTHR = NW * 64;
+  constexpr int KPT = KT * BM / NTHR >= 4 ? KT * BM / NTHR : 4;   // consecutive k of one row that a thread stages (8 or 4)
+  constexpr int XTHR = KT * BM / KPT;         // threads that stage X (all of them up to 8 waves)
   const int t = threadIdx.x, l = t & 63, w = t >> 6;
   const int rt = w & 1;                       // row tile of this wave
   const int ct0 = w >> 1;                     // first column tile; then += 2
@@ -180,40 +185,47 @@ __global__ __launch_bounds__(256) void k_xform(XformArgs x) {
   __syncthreads();
   // thread -> row t / 4, 8 consecutive k of the X chunk; the next chunk's values are fetched into
   // registers before the MFMA phase so that the gather latency overlaps it
-  const int xr = t >> 2, xks = (t & 3) * 8;
-  const int64_t xrow = srow[xr];
-  float xv[8];
+  const bool xstage = t < XTHR;
+  const int xr = (t % XTHR) / (KT / KPT), xks = (t % (KT / KPT)) * KPT;
+  const int64_t xrow = xstage ? srow[xr] : -1;
+  float xv[KPT];
   auto fetch_chunk = [&](int k0) {
 #pragma unroll
-    for (int kk = 0; kk < 8; kk++) xv[kk] = 0.f;
+    for (int kk = 0; kk < KPT; kk++) xv[kk] = 0.f;
     if (xrow >= 0) {
-      fetch_x4<MODE>(x, xrow, k0 + xks, xv);
-      fetch_x4<MODE>(x, xrow, k0 + xks + 4, xv + 4);
+#pragma unroll
+      for (int kk = 0; kk < KPT; kk += 4) fetch_x4<MODE>(x, xrow, k0 + xks + kk, xv + kk);
     }
   };
   fetch_chunk(0);
   for (int k0 = 0; k0 < x.Kp; k0 += KT) {
-    {   // even k first, then odd k
+    if (xstage) {   // even k first, then odd k
       float *xp = Xs + xr * XS + (xks >> 1);
-      *reinterpret_cast<float4 *>(xp) = make_float4(xv[0], xv[2], xv[4], xv[6]);
-      *reinterpret_cast<float4 *>(xp + 16) = make_float4(xv[1], xv[3], xv[5], xv[7]);
+      if constexpr (KPT == 8) {
+        *reinterpret_cast<float4 *>(xp) = make_float4(xv[0], xv[2], xv[4], xv[6]);
+        *reinterpret_cast<float4 *>(xp + 16) = make_float4(xv[1], xv[3], xv[5], xv[7]);
+      } else {
+        *reinterpret_cast<float2 *>(xp) = make_float2(xv[0], xv[2]);
+        *reinterpret_cast<float2 *>(xp + 16) = make_float2(xv[1], xv[3]);
+      }
     }
     {   // stage the W chunk: global [Np][32] in LDS order -> rows of stride XS
       const float4 *src = reinterpret_cast<const float4 *>(x.W + (int64_t)k0 * Np);
       constexpr int n4 = KT * Np / 4;
 #pragma unroll
-      for (int i = t; i < n4; i += 256) *reinterpret_cast<float4 *>(Ws + (i >> 3) * XS + (i & 7) * 4) = src[i];
+      for (int i = t; i < n4; i += NTHR) *reinterpret_cast<float4 *>(Ws + (i >> 3) * XS + (i & 7) * 4) = src[i];
     }
     __syncthreads();
     if (k0 + KT < x.Kp) fetch_chunk(k0 + KT);
-    if (ct0 == 0) mfma_chunk<(NT + 1) / 2>(Xs, Ws, rt, 0, l, acc);
-    else if (NT / 2 > 0) mfma_chunk<(NT / 2 > 0 ? NT / 2 : 1)>(Xs, Ws, rt, 1, l, acc);
+    // this wave owns TPW column tiles, or one fewer when the last one would lie past NT
+    if (ct0 + (TPW - 1) * CS < NT) mfma_chunk<TPW, CS>(Xs, Ws, rt, ct0, l, acc);
+    else if (TPW > 1) mfma_chunk<(TPW > 1 ? TPW - 1 : 1), CS>(Xs, Ws, rt, ct0, l, acc);
     __syncthreads();
   }
   // epilogue: lane holds rows 8*(r/4) + 4*(l/32) + r%4 of its row tile, column l % 32 of each tile
 #pragma unroll
   for (int i = 0; i < TPW; i++) {
-    int ct = ct0 + 2 * i;
+    int ct = ct0 + CS * i;
     if (ct >= NT) continue;
     int col = ct * 32 + (l & 31);
     if (col >= x.n_out) continue;
@@ -251,20 +263,34 @@ __global__ __launch_bounds__(256) void k_xform(XformArgs x) {
   }
 }
 
+#ifndef INK_XF_WIDE_FROM
+#define INK_XF_WIDE_FROM 3      // 8 waves per workgroup from this many column tiles on
+#endif
+#ifndef INK_XF_WIDER_FROM
+#define INK_XF_WIDER_FROM 5     // 16 waves per workgroup from this many column tiles on
+#endif
+
+template <int MODE, int NT>
+static void launch_nt(ink_ctx *c, const XformArgs &x, dim3 grid, size_t sh) {
+  if (NT >= INK_XF_WIDER_FROM) hipLaunchKernelGGL((k_xform<MODE, NT, 16>), grid, dim3(1024), sh, c->stream, x);
+  else if (NT >= INK_XF_WIDE_FROM) hipLaunchKernelGGL((k_xform<MODE, NT, 8>), grid, dim3(512), sh, c->stream, x);
+  else hipLaunchKernelGGL((k_xform<MODE, NT, 4>), grid, dim3(256), sh, c->stream, x);
+}
+
 template <int MODE>
 static hipError_t launch(ink_ctx *c, const XformArgs &x) {
   int NT = x.Np / 32;
   size_t sh = (size_t)(BM + x.Np) * XS * sizeof(float);
   dim3 grid((unsigned)((x.n_rows + BM - 1) / BM));
   switch (NT) {
-    case 1: hipLaunchKernelGGL((k_xform<MODE, 1>), grid, dim3(256), sh, c->stream, x); break;
-    case 2: hipLaunchKernelGGL((k_xform<MODE, 2>), grid, dim3(256), sh, c->stream, x); break;
-    case 3: hipLaunchKernelGGL((k_xform<MODE, 3>), grid, dim3(256), sh, c->stream, x); break;
-    case 4: hipLaunchKernelGGL((k_xform<MODE, 4>), grid, dim3(256), sh, c->stream, x); break;
-    case 5: hipLaunchKernelGGL((k_xform<MODE, 5>), grid, dim3(256), sh, c->stream, x); break;
-    case 6: hipLaunchKernelGGL((k_xform<MODE, 6>), grid, dim3(256), sh, c->stream, x); break;
-    case 7: hipLaunchKernelGGL((k_xform<MODE, 7>), grid, dim3(256), sh, c->stream, x); break;
-    case 8: hipLaunchKernelGGL((k_xform<MODE, 8>), grid, dim3(256), sh, c->stream, x); break;
+    case 1: launch_nt<MODE, 1>(c, x, grid, sh); break;
+    case 2: launch_nt<MODE, 2>(c, x, grid, sh); break;
+    case 3: launch_nt<MODE, 3>(c, x, grid, sh); break;
+    case 4: launch_nt<MODE, 4>(c, x, grid, sh); break;
+    case 5: launch_nt<MODE, 5>(c, x, grid, sh); break;
+    case 6: launch_nt<MODE, 6>(c, x, grid, sh); break;
+    case 7: launch_nt<MODE, 7>(c, x, grid, sh); break;
+    case 8: launch_nt<MODE, 8>(c, x, grid, sh); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
