@@ -12,7 +12,6 @@ namespace ink {
 
 typedef float f16v __attribute__((ext_vector_type(16)));
 
-constexpr int BM = 64;       // rows per workgroup
 constexpr int KT = 32;       // k-chunk staged in LDS
 
 __device__ __forceinline__ float agg_value(const XformArgs &x, int64_t row, int k) {
@@ -143,9 +142,10 @@ __device__ __forceinline__ void mfma_chunk(const float *Xs, const float *Ws, int
   }
 }
 
-// NT = number of 32-column tiles (Np / 32), NW = waves per workgroup (4 or 8).  Wave w works on
-// row tile w & 1 and on the column tiles w / 2, w / 2 + NW / 2, ...
-template <int MODE, int NT, int NW>
+// BM = rows per workgroup (64 or 128), NT = number of 32-column tiles (Np / 32), NW = waves per
+// workgroup.  With RT = BM / 32 row tiles, wave w works on row tile w % RT and on the column tiles
+// w / RT, w / RT + NW / RT, ...
+template <int MODE, int NT, int NW, int BM>
 __global__ __launch_bounds__(NW * 64) void k_xform(XformArgs x) {
   extern __shared__ float smem[];
   float *Xs = smem;                           // [BM][XS]
@@ -153,15 +153,16 @@ __global__ __launch_bounds__(NW * 64) void k_xform(XformArgs x) {
   __shared__ int64_t srow[BM];     // input row (gather) of each tile row, -1 past the end
   __shared__ int64_t sout[BM];     // table row written by the epilogue
   __shared__ int schg[BM];
-  constexpr int CS = NW / 2;                  // column-tile stride between the tiles of one wave
+  constexpr int RT = BM / 32;
+  constexpr int CS = NW / RT;                 // column-tile stride between the tiles of one wave
   constexpr int TPW = (NT + CS - 1) / CS;
   constexpr int Np = NT * 32;
   constexpr int NTHR = NW * 64;
   constexpr int KPT = KT * BM / NTHR >= 4 ? KT * BM / NTHR : 4;   // consecutive k of one row that a thread stages (8 or 4)
   constexpr int XTHR = KT * BM / KPT;         // threads that stage X (all of them up to 8 waves)
   const int t = threadIdx.x, l = t & 63, w = t >> 6;
-  const int rt = w & 1;                       // row tile of this wave
-  const int ct0 = w >> 1;                     // first column tile; then += 2
+  const int rt = w % RT;                      // row tile of this wave
+  const int ct0 = w / RT;                     // first column tile; then += CS
   const int64_t r0 = (int64_t)blockIdx.x * BM;
   int64_t n_rows = x.n_rows;
   if (x.n_rows_dev) {          // the launch covers an upper bound; workgroups past the count leave
@@ -270,27 +271,28 @@ __global__ __launch_bounds__(NW * 64) void k_xform(XformArgs x) {
 #define INK_XF_WIDER_FROM 5     // 16 waves per workgroup from this many column tiles on
 #endif
 
+// 64 rows per workgroup: 128 rows (half the weight staging per row) measured the same or slower
 template <int MODE, int NT>
-static void launch_nt(ink_ctx *c, const XformArgs &x, dim3 grid, size_t sh) {
-  if (NT >= INK_XF_WIDER_FROM) hipLaunchKernelGGL((k_xform<MODE, NT, 16>), grid, dim3(1024), sh, c->stream, x);
-  else if (NT >= INK_XF_WIDE_FROM) hipLaunchKernelGGL((k_xform<MODE, NT, 8>), grid, dim3(512), sh, c->stream, x);
-  else hipLaunchKernelGGL((k_xform<MODE, NT, 4>), grid, dim3(256), sh, c->stream, x);
+static void launch_nt(ink_ctx *c, const XformArgs &x) {
+  constexpr int BM = 64;
+  size_t sh = (size_t)(BM + x.Np) * XS * sizeof(float);
+  dim3 grid((unsigned)((x.n_rows + BM - 1) / BM));
+  if (NT >= INK_XF_WIDER_FROM) hipLaunchKernelGGL((k_xform<MODE, NT, 16, BM>), grid, dim3(1024), sh, c->stream, x);
+  else if (NT >= INK_XF_WIDE_FROM) hipLaunchKernelGGL((k_xform<MODE, NT, 8, BM>), grid, dim3(512), sh, c->stream, x);
+  else hipLaunchKernelGGL((k_xform<MODE, NT, 4, BM>), grid, dim3(256), sh, c->stream, x);
 }
 
 template <int MODE>
 static hipError_t launch(ink_ctx *c, const XformArgs &x) {
-  int NT = x.Np / 32;
-  size_t sh = (size_t)(BM + x.Np) * XS * sizeof(float);
-  dim3 grid((unsigned)((x.n_rows + BM - 1) / BM));
-  switch (NT) {
-    case 1: launch_nt<MODE, 1>(c, x, grid, sh); break;
-    case 2: launch_nt<MODE, 2>(c, x, grid, sh); break;
-    case 3: launch_nt<MODE, 3>(c, x, grid, sh); break;
-    case 4: launch_nt<MODE, 4>(c, x, grid, sh); break;
-    case 5: launch_nt<MODE, 5>(c, x, grid, sh); break;
-    case 6: launch_nt<MODE, 6>(c, x, grid, sh); break;
-    case 7: launch_nt<MODE, 7>(c, x, grid, sh); break;
-    case 8: launch_nt<MODE, 8>(c, x, grid, sh); break;
+  switch (x.Np / 32) {
+    case 1: launch_nt<MODE, 1>(c, x); break;
+    case 2: launch_nt<MODE, 2>(c, x); break;
+    case 3: launch_nt<MODE, 3>(c, x); break;
+    case 4: launch_nt<MODE, 4>(c, x); break;
+    case 5: launch_nt<MODE, 5>(c, x); break;
+    case 6: launch_nt<MODE, 6>(c, x); break;
+    case 7: launch_nt<MODE, 7>(c, x); break;
+    case 8: launch_nt<MODE, 8>(c, x); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
