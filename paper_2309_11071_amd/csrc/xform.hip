@@ -277,8 +277,8 @@ static void launch_nt(ink_ctx *c, const XformArgs &x) {
   constexpr int BM = 64;
   size_t sh = (size_t)(BM + x.Np) * XS * sizeof(float);
   dim3 grid((unsigned)((x.n_rows + BM - 1) / BM));
-  if (NT >= INK_XF_WIDER_FROM) hipLaunchKernelGGL((k_xform<MODE, NT, 16, BM>), grid, dim3(1024), sh, c->stream, x);
-  else if (NT >= INK_XF_WIDE_FROM) hipLaunchKernelGGL((k_xform<MODE, NT, 8, BM>), grid, dim3(512), sh, c->stream, x);
+  if constexpr (NT >= INK_XF_WIDER_FROM) hipLaunchKernelGGL((k_xform<MODE, NT, 16, BM>), grid, dim3(1024), sh, c->stream, x);
+  else if constexpr (NT >= INK_XF_WIDE_FROM) hipLaunchKernelGGL((k_xform<MODE, NT, 8, BM>), grid, dim3(512), sh, c->stream, x);
   else hipLaunchKernelGGL((k_xform<MODE, NT, 4, BM>), grid, dim3(256), sh, c->stream, x);
 }
 
