@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0
 # same runs), divided by the aggregation launches of the batch (one per layer).
 MEASURED_TRAFFIC_PER_LAUNCH = {
     2: {"bytes": 8.28e9, "source": "profiles/all_kernels_cfg2_gcn.md"},
-    3: {"bytes": 3.58e9, "source": "profiles/all_kernels_cfg3_sage_max.md"},
+    3: {"bytes": 3.59e9, "source": "profiles/all_kernels_cfg3_sage_max.md"},
 }
 
 
