@@ -85,6 +85,21 @@ __global__ void k_gather_rows(const float *table, int ld, int d, const int32_t *
   if (r < n) out[r * d + k] = table[(int64_t)rows[r] * ld + k];
 }
 
+// the same, 16 bytes per thread, for d a multiple of 4
+__global__ void k_gather_rows4(const float *table, int ld, int d4, const int32_t *rows, int64_t n, float *out) {
+  int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t r = t / d4;
+  int k = (int)(t - r * d4);
+  if (r < n)
+    reinterpret_cast<float4 *>(out)[r * d4 + k] = *reinterpret_cast<const float4 *>(table + (int64_t)rows[r] * ld + 4 * k);
+}
+
+static void gather_rows(hipStream_t s, const float *table, int ld, int d, const int32_t *rows, int64_t n, float *out) {
+  if (n <= 0) return;
+  if (d % 4 == 0) hipLaunchKernelGGL(k_gather_rows4, grid1(n * (d / 4)), dim3(256), 0, s, table, ld, d / 4, rows, n, out);
+  else hipLaunchKernelGGL(k_gather_rows, grid1(n * d), dim3(256), 0, s, table, ld, d, rows, n, out);
+}
+
 __global__ void k_pack_rows(const void *table, int ld, int d, int64_t row0, int64_t nrows, void *out) {
   int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   int64_t r = t / d;
@@ -133,12 +148,14 @@ __global__ void k_set_features(const uint32_t *ids, const uint32_t *perm, int64_
 
 __global__ void k_gather_rows_ld(const float *in, int ld, const int32_t *idx, int64_t n, const int32_t *n_dev,
                                  float *out) {
-  // out[i][:] = in[idx[i]][:], both with row stride ld
+  // out[i][:] = in[idx[i]][:], both with row stride ld (a multiple of 4): 16 bytes per thread
+  const int ld4 = ld >> 2;
   int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  int64_t r = t / ld;
-  int k = (int)(t % ld);
+  int64_t r = t / ld4;
+  int k = (int)(t - r * ld4);
   if (n_dev) n = *n_dev;
-  if (r < n) out[r * ld + k] = in[(int64_t)idx[r] * ld + k];
+  if (r < n)
+    reinterpret_cast<float4 *>(out)[r * ld4 + k] = *reinterpret_cast<const float4 *>(in + (int64_t)idx[r] * ld + 4 * k);
 }
 
 __device__ __forceinline__ float gcn_coef(int indeg) {      // (indeg + 1)^(-1/2)
@@ -739,7 +756,7 @@ static ink_status emit_changed(ink_ctx *c, int64_t nC, int nxt, bool keep_old, i
                      c->f_list[nxt].as<int32_t>());
   if (keep_old) {
     API_TRY(c->f_old[nxt].reserve((size_t)nC * ld * 4));
-    hipLaunchKernelGGL(k_gather_rows_ld, grid1(nC * ld), dim3(256), 0, s, (const float *)c->c_old.as<float>(), ld,
+    hipLaunchKernelGGL(k_gather_rows_ld, grid1(nC * (ld / 4)), dim3(256), 0, s, (const float *)c->c_old.as<float>(), ld,
                        (const int32_t *)c->c_idx.as<int32_t>(), (int64_t)0, (const int32_t *)&dc->v[C_NEXT],
                        c->f_old[nxt].as<float>());
   }
@@ -822,8 +839,7 @@ static ink_status propagate_layers(ink_ctx *c, int64_t nF, int64_t n_chg, int cu
         API_TRY(c->res_ids.reserve((size_t)nF * 4));
         API_TRY(c->res_emb.reserve((size_t)nF * d * 4));
         API_TRY(hipMemcpyAsync(c->res_ids.p, c->f_list[cur].p, (size_t)nF * 4, hipMemcpyDeviceToDevice, s));
-        hipLaunchKernelGGL(k_gather_rows, grid1(nF * d), dim3(256), 0, s, (const float *)c->H[l].f(), c->H[l].ld, d,
-                           (const int32_t *)c->res_ids.p, nF, c->res_emb.as<float>());
+        gather_rows(s, (const float *)c->H[l].f(), c->H[l].ld, d, (const int32_t *)c->res_ids.p, nF, c->res_emb.as<float>());
         out->changed_ids = c->res_ids.as<int32_t>();
         out->embeddings = c->res_emb.as<float>();
       }
@@ -1087,8 +1103,7 @@ extern "C" ink_status ink_add_nodes(ink_ctx *c, const float *features, int64_t n
   {
     int k = c->n_layers, d = c->H[k].d;
     API_TRY(c->res_emb.reserve((size_t)n_new * d * 4));
-    hipLaunchKernelGGL(k_gather_rows, grid1(n_new * d), dim3(256), 0, s, (const float *)c->H[k].f(), c->H[k].ld, d, rows,
-                       n_new, c->res_emb.as<float>());
+    gather_rows(s, (const float *)c->H[k].f(), c->H[k].ld, d, rows, n_new, c->res_emb.as<float>());
     API_TRY(hipGetLastError());
     out->n_changed = n_new;
     out->changed_ids = c->res_ids.as<int32_t>();
