@@ -79,12 +79,7 @@ inline hipError_t plan_big_rows(ink_ctx *c, int64_t n_rows_max, const int32_t *i
 // row (index in the list), node id and neighbour range of global chunk cg
 __device__ __forceinline__ void big_chunk(const int32_t *pref, int n_big, int cg, const int32_t *list,
                                           const int32_t *in_deg, int &i, int &v, int64_t &j0, int64_t &j1) {
-  int lo = 0, hi = n_big - 1;
-  while (lo < hi) {
-    int mid = (lo + hi + 1) >> 1;
-    if (pref[mid] <= cg) lo = mid; else hi = mid - 1;
-  }
-  i = lo;
+  i = wave_last_le(pref, n_big, cg);      // called by whole waves with wave-uniform arguments
   v = list[i];
   int64_t deg = in_deg[v];
   j0 = (int64_t)(cg - pref[i]) * kBigChunk;

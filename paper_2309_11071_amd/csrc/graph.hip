@@ -153,12 +153,7 @@ __global__ __launch_bounds__(256) void k_classify(const int32_t *nodes, const in
   int total = *n_chunks, nn = *n_nodes;
   for (int ch = blockIdx.x; ch < total; ch += gridDim.x) {
     // node owning this chunk: last i with chunk_pref[i] <= ch
-    int lo = 0, hi = nn - 1;
-    while (lo < hi) {
-      int mid = (lo + hi + 1) >> 1;
-      if (chunk_pref[mid] <= ch) lo = mid; else hi = mid - 1;
-    }
-    int i = lo;
+    int i = wave_last_le(chunk_pref, nn, ch);
     int v = nodes[i];
     int s0 = seg[i], s1 = seg[i + 1];
     int d = deg[v];

@@ -68,6 +68,25 @@ __device__ __forceinline__ int block_excl_scan(int x, int *smem, int *total) {
   return base + incl - x;
 }
 
+// Last index i in [0, n) with a[i] <= key, for ascending a with a[0] <= key.  The whole wave
+// searches together, 64 probes per round, so a list of n entries costs ceil(log64 n) dependent
+// loads instead of log2 n.  Every lane must call it with the same arguments; all lanes get the result.
+__device__ __forceinline__ int wave_last_le(const int32_t *a, int n, int key) {
+  const int l = lane_id();
+  int lo = 0, len = n;
+  while (len > 1) {
+    int step = (len + kWave - 1) / kWave;
+    int idx = lo + l * step;
+    bool ok = idx < lo + len && a[idx] <= key;
+    int hit = __popcll(__ballot(ok));          // probes are ascending, so the hits are lanes 0 .. hit-1
+    int j = hit > 0 ? hit - 1 : 0;
+    int end = lo + len;
+    lo += j * step;
+    len = end - lo < step ? end - lo : step;
+  }
+  return lo;
+}
+
 #define INK_TRY(x) do { hipError_t e_ = (x); if (e_ != hipSuccess) return e_; } while (0)
 
 inline int nblocks(int64_t n, int per) { return (int)((n + per - 1) / per); }
