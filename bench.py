@@ -213,7 +213,9 @@ def main():
         # every node writes its cached row (alpha; for max / min also holder and runner-up bound)
         "full_inference_roofline": (lambda b, ms: {"bound": "hbm", "achieved": b / 1e9 / (ms / 1e3), "peak": HBM_PEAK_GBS,
                                                    "unit": "GB/s", "frac": b / 1e9 / (ms / 1e3) / HBM_PEAK_GBS,
-                                                   "algorithmic_bytes": b})(
+                                                   "algorithmic_bytes": b,
+                                                   "note": "algorithmic bytes over time: message tables that fit "
+                                                           "L2 / MALL are re-read from cache, so this can exceed the HBM peak"})(
             sum(int(src.size) * (4 + 4 * d) + cfg.n_nodes * (12 if cfg.agg in ("max", "min") else 4) * d
                 for d in ink.agg_widths), max(full_stats["ms"]["agg"], 1e-6)),
     }
