@@ -83,6 +83,11 @@ def load_library():
     path = lib_path()
     if not os.path.exists(path):
         raise RuntimeError("libink.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'`")
+    # PyTorch ships a HIP runtime of its own; whichever copy a process loads first is the one that
+    # can see the GPU, so torch (the allocator of every device buffer handed to the library) goes first
+    import torch
+    if torch.cuda.is_available():
+        torch.cuda.init()
     lib = C.CDLL(path)
     vp = C.c_void_p
     lib.ink_create.argtypes = [C.POINTER(_Csr), vp, C.c_int32, C.POINTER(_Model), C.POINTER(_Options),
