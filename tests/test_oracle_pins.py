@@ -331,3 +331,58 @@ def test_update_invariants(kind, agg):
         assert np.array_equal(back["h"][l], pre["h"][l])
         if agg == "max":
             assert np.array_equal(back["arg"][l], pre["arg"][l])
+
+
+@pytest.mark.parametrize("kind,agg", [("sage", "max"), ("gin", "sum"), ("gcn", "gcn_sym")])
+def test_feature_change_stays_in_the_out_neighbourhood(kind, agg):
+    """What ink_update_features is compared with: after x_v changes for v in S, layer l can only
+    change inside the l-hop out-neighbourhood of S (S itself included: the self term of Sec. 3.2,
+    GCN's self loop), and S itself does change at layer 1 for a generic new row."""
+    n, dims = 60, (5, 6, 4)
+    src, dst, X = tiny_graph(n, 260, 41, d=dims[0])
+    keys = np.unique(synth.edge_keys(src, dst))
+    model = small_model(kind, agg, dims, 9, hidden=5)
+    rp, col = oracle.csr_from_keys(n, keys)
+    pre = oracle.full_infer(rp, col, X, model)
+    S = np.array([3, 17, 44])
+    X2 = X.copy()
+    X2[S] = np.random.default_rng(5).standard_normal((S.size, dims[0])).astype(np.float32)
+    post = oracle.full_infer(rp, col, X2, model)
+    ch = oracle.changed_nodes(pre, post)
+    assert sorted(ch[0].tolist()) == S.tolist()
+    for l in (1, 2):
+        reach = khop_out(n, keys, set(S.tolist()), l)
+        assert reach[ch[l]].all(), l
+    assert ch[2].size > 0
+
+
+@pytest.mark.parametrize("kind,agg", [("sage", "max"), ("sage", "min"), ("sage", "mean"), ("gin", "sum"),
+                                      ("gcn", "gcn_sym")])
+def test_isolated_new_node_has_the_closed_form_embedding(kind, agg):
+    """What ink_add_nodes is compared with: a node without edges aggregates nothing (alpha = 0,
+    argument -1; GCN: d-hat = 1, only its own term), so its embeddings follow from its own row
+    alone, and appending it changes no other row."""
+    n, dims = 30, (4, 5, 3)
+    src, dst, X = tiny_graph(n, 140, 43, d=dims[0])
+    keys = np.unique(synth.edge_keys(src, dst))
+    model = small_model(kind, agg, dims, 10, hidden=4, eps=0.5) if kind == "gin" else small_model(kind, agg, dims, 10)
+    pre = oracle.full_infer(*oracle.csr_from_keys(n, keys), X, model)
+    x_new = np.random.default_rng(6).standard_normal((2, dims[0])).astype(np.float32)
+    X2 = np.concatenate([X, x_new])
+    post = oracle.full_infer(*oracle.csr_from_keys(n + 2, keys), X2, model)
+    for l in range(len(dims)):
+        assert np.array_equal(post["h"][l][:n], pre["h"][l])
+    h = x_new.astype(np.float64)
+    for l, L in enumerate(model["layers"]):
+        if kind == "sage":
+            z = h @ L["W_self"].astype(np.float64) + (L["bias"] if L.get("bias") is not None else 0.0)
+        elif kind == "gin":
+            z = relu(1.5 * h @ L["W_neigh"].astype(np.float64) + L["bias"])
+            z = z @ L["W_mlp2"].astype(np.float64) + L["bias_mlp2"]
+        else:
+            z = h @ L["W_neigh"].astype(np.float64) + L["bias"]
+        h = relu(z) if l == 0 else z
+        assert np.allclose(post["h"][l + 1][n:], h, rtol=1e-5, atol=1e-5), l
+        h = post["h"][l + 1][n:].astype(np.float64)
+    if agg in ("max", "min"):
+        assert (post["arg"][1][n:] == -1).all() and (post["alpha"][1][n:] == 0).all()
