@@ -118,6 +118,8 @@ def test_first_and_last_edge_of_a_node():
     ("gin", "min", (64, 64, 64)),
     ("sage", "max", (602, 64, 8)),        # feature rows wider than one wave covers: column blocks
     ("gin", "max", (300, 40, 6)),
+    ("sage", "max", (12, 7)),             # a single layer
+    ("sage", "max", (6,) * 9),            # the largest layer count the library takes
 ])
 def test_random_sequences(kind, agg, dims):
     cfg = synth.WorkloadConfig(6, "t", kind, agg, 3000, 20000, False, tuple(dims), 24, 300, True)

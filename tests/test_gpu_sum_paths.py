@@ -21,6 +21,9 @@ TOL = 1e-5
     ("gcn", "gcn_sym", (12, 8, 8, 5)),
     ("gin", "sum", (500, 32, 8)),          # aggregated rows wider than 256 floats
     ("sage", "mean", (602, 24, 8)),
+    ("gin", "sum", (12, 9)),               # a single layer
+    ("gcn", "gcn_sym", (12, 9)),
+    ("gin", "sum", (6,) * 9),              # the largest layer count the library takes
 ])
 def test_random_sequences(kind, agg, dims):
     cfg = synth.WorkloadConfig(6, "t", kind, agg, 3000, 20000, False, tuple(dims), 24, 200, False)
