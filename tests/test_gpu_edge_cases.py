@@ -240,3 +240,24 @@ def test_error_paths_leave_the_state_untouched():
     with pytest.raises(InkError):
         Ink(rp, col[::-1].copy(), X, model)                      # rows not ascending
     ink.close()
+
+
+def test_widest_feature_rows():
+    """Feature width at the library's limit (16 384 columns: 64 aggregation blocks, 1 024 k-chunks
+    of the combination), next to the widest output (256)."""
+    dims = (16384, 256, 5)
+    cfg = synth.WorkloadConfig(6, "t", "sage", "max", 400, 3000, False, dims, 8, 60, True)
+    model = tiny_model("sage", "max", dims, seed=3)
+    for L in model["layers"]:                      # keep the 32 768-term chains well conditioned
+        for k in list(L):
+            if isinstance(L[k], np.ndarray):
+                L[k] = (L[k] * 0.05).astype(np.float32)
+    src, dst = synth.make_graph(cfg)
+    X = np.random.default_rng(9).standard_normal((cfg.n_nodes, dims[0])).astype(np.float32)
+    h = Harness(cfg=cfg, graph=(cfg.n_nodes, src, dst), X=X, model=model, precision="f32")
+    h.check_state()
+    for b in range(2):
+        op, bs, bd = h.sampler.next_batch()
+        h.step(op, bs, bd)
+    h.check_state()
+    h.ink.close()
