@@ -1,7 +1,8 @@
 """Parity at the benchmark's sizes: configs 2 and 3 at full size (the oracle needs 10-20 s per
-full inference there), configs 4 and 5 on 1/16-scale replicas (their full size is 20 M nodes).
-State after a sequence of batches is compared table by table with a fresh oracle inference of
-the final snapshot: an error made by any earlier batch would persist in the cache."""
+full inference there), configs 4 and 5 on 1/16-scale replicas and, at their full size of 20 M
+nodes, on sampled rows that the oracle checks layer by layer.  State after a sequence of batches
+is compared table by table with a fresh oracle inference of the final snapshot: an error made by
+any earlier batch would persist in the cache."""
 import numpy as np
 import pytest
 
@@ -74,3 +75,86 @@ def test_config5_batch_sizes():
         res, want = h.step(op, bs, bd, exact=True)
     h.check_state(exact=True)
     h.ink.close()
+
+
+def _neighbour_lists(rp, col, rows, batches):
+    """In-neighbour lists of `rows` after the batches, from the initial CSR and the ops that name
+    them as destination, applied in order (net effect on the edge set)."""
+    want = {int(v): set(col[rp[v]:rp[v + 1]].tolist()) for v in rows}
+    for op, bs, bd in batches:
+        hit = np.nonzero(np.isin(bd, rows))[0]
+        for i in hit:
+            s, d = int(bs[i]), int(bd[i])
+            if s == d:
+                continue
+            if op[i] == 0:
+                want[d].add(s)
+            else:
+                want[d].discard(s)
+    lists = [np.array(sorted(want[int(v)]), np.int32) for v in rows]
+    rp_s = np.zeros(len(rows) + 1, np.int64)
+    rp_s[1:] = np.cumsum([x.size for x in lists])
+    col_s = np.concatenate(lists) if lists else np.zeros(0, np.int32)
+    return rp_s, col_s
+
+
+def _rows_of(ink, layer, which, rows):
+    return np.concatenate([ink.get_layer(layer, which, int(v), 1) for v in rows], axis=0)
+
+
+@pytest.mark.parametrize("cfg_id", [5, 4])
+def test_configs_4_and_5_full_size_sampled_rows(cfg_id):
+    """20 M nodes / 400 M edges, batches of 10 000 as bench.py runs them.  A full oracle inference
+    takes minutes there, so a sample of rows (random nodes, the highest in-degrees, destinations of
+    the last batch) is checked layer by layer: the oracle aggregates the library's own message
+    table over the row's neighbour list (kept on the oracle's side from the initial graph and the
+    ops) and combines it; both must reproduce the library's cached row — bit for bit for max, to
+    1e-5 for the accumulated sums."""
+    from paper_2309_11071_amd import Ink
+    from paper_2309_11071_amd.binding import make_updates
+    cfg = synth.get_config(cfg_id)
+    exact = cfg.agg in ("max", "min")
+    src, dst = synth.make_graph(cfg)
+    n = cfg.n_nodes
+    rp, col = synth.in_csr_from_edges(n, src, dst, assume_sorted=True)
+    X = synth.make_features(cfg)
+    model = synth.make_model(cfg)
+    ink = Ink(rp, col, X, model)
+    ink.full_infer()
+    sampler = synth.BatchSampler(cfg, src, dst)
+    del src, dst
+    batches = []
+    for b in range(2):
+        op, bs, bd = sampler.next_batch()
+        res = ink.apply_updates(make_updates(op, bs, bd), fetch=False)
+        assert res["n_applied_ins"] + res["n_applied_del"] + res["n_noop"] == cfg.batch
+        assert res["n_changed"] > 1000
+        batches.append((op, bs, bd))
+    rng = np.random.default_rng(77)
+    indeg = np.diff(rp)
+    rows = np.unique(np.concatenate([rng.choice(n, size=1500, replace=False),
+                                     np.argsort(indeg)[-40:],
+                                     rng.choice(batches[-1][2], size=400, replace=False)])).astype(np.int64)
+    rp_s, col_s = _neighbour_lists(rp, col, rows, batches)
+    assert rp_s[-1] > 100000
+    k = len(model["layers"])
+    prec = "f32" if exact else "f64"
+    for l in range(1, k + 1):
+        M = X if l == 1 else ink.get_layer(l - 1, 0)              # the library's own m_l = h_{l-1}
+        if l == 1:
+            assert np.array_equal(_rows_of(ink, 0, 0, rows[:50]), X[rows[:50]])
+        a_gpu = _rows_of(ink, l, 1, rows)
+        h_gpu = _rows_of(ink, l, 0, rows)
+        if exact:
+            a_ref, g_ref = oracle.agg_select(rp_s, col_s, M, is_min=cfg.agg == "min")
+            assert np.array_equal(a_gpu.view(np.uint32), a_ref.view(np.uint32)), "alpha_%d" % l
+            assert np.array_equal(_rows_of(ink, l, 2, rows), g_ref), "argmax_%d" % l
+            h_ref = oracle.transform(model, l - 1, a_gpu, M[rows], prec)
+            assert np.array_equal(h_gpu.view(np.uint32), h_ref.view(np.uint32)), "h_%d" % l
+        else:
+            a_ref = oracle.agg_sum(rp_s, col_s, M)
+            assert scaled_rel_err(a_gpu, a_ref) <= 1e-5, "sum_%d" % l
+            h_ref = oracle.transform(model, l - 1, a_ref, M[rows], prec)
+            assert scaled_rel_err(h_gpu, h_ref) <= 1e-5, "h_%d" % l
+        del M
+    ink.close()
