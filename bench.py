@@ -145,6 +145,23 @@ def main():
         torch.mul(a, 1.0, out=b)        # plain elementwise kernel: reads 1 GiB, writes 1 GiB
         torch.cuda.synchronize()
         del a, b
+    # practical HBM ceiling next to the nominal one: a plain device copy (1 GiB read + 1 GiB written)
+    copy_gbs = None
+    try:
+        a = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        b = torch.empty_like(a)
+        torch.mul(a, 1.0, out=b)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(5):
+            torch.mul(a, 1.0, out=b)
+        e1.record()
+        torch.cuda.synchronize()
+        copy_gbs = 5 * 2 * a.numel() * 4 / 1e9 / (e0.elapsed_time(e1) / 1e3)
+        del a, b
+    except RuntimeError:
+        pass
     aff = args.method == "affected"
     for i in range(args.warmup):
         ink.apply_updates_device(batches[i].data_ptr(), cfg.batch, affected=aff)
@@ -203,6 +220,7 @@ def main():
                      "algorithmic_bytes_per_launch": agg_bytes / max(agg_launches, 1),
                      "kernel": "aggregation (k_agg_events / k_agg_full / k_big_*), all layers",
                      "avg_launch_ms": agg_ms / max(agg_launches, 1),
+                     "measured_copy_GBs": copy_gbs,
                      "algorithmic_bytes_per_step": agg_bytes / args.steps},
         "gpu_ms_per_step_by_class": {k_: v / args.steps for k_, v in per_class.items()},
         "per_step_layer_counts": [{k_: v / args.steps for k_, v in L.items()} for L in (layer_tot or [])],
