@@ -97,3 +97,30 @@ def test_batch_sizes_across_the_sort_and_scan_variants(kind, agg, exact):
         h.check_bound()
     h.check_state(exact=exact, tol=1e-5)
     h.ink.close()
+
+
+@pytest.mark.parametrize("kind,agg,exact", [("sage", "max", True), ("gcn", "gcn_sym", False)])
+def test_long_run_of_messy_batches(kind, agg, exact):
+    """150 batches in a row on one context: blocks fill up, move and the pools grow, cached bounds
+    loosen and are refreshed, sums accumulate deltas; every batch is checked against the oracle
+    and the whole state at the end."""
+    dims = (12, 16, 8)
+    n = 12000
+    cfg = synth.WorkloadConfig(8, "t", kind, agg, n, 120000, False, dims, 12, 50, False)
+    src, dst = synth.make_graph(cfg)
+    rng = np.random.default_rng(31)
+    X = rng.standard_normal((n, dims[0])).astype(np.float32)
+    h = Harness(cfg=cfg, graph=(n, src, dst), X=X, model=tiny_model(kind, agg, dims, seed=7, hidden=12),
+                precision="f32" if exact else "f64", slack=0.02, pool_reserve=4096)
+    for b in range(150):
+        op, s, d = messy_batch(rng, n, h.keys, int(rng.integers(50, 2000)))
+        if b % 3 == 0:                      # net growth, so that blocks and pools run out of room
+            op[: op.size // 2] = 0
+        h.step(op, s, d, exact=exact, tol=1e-5)
+        if b % 25 == 0:
+            ids = rng.choice(n, size=40, replace=False)
+            h.feature_step(ids, rng.standard_normal((40, dims[0])).astype(np.float32), exact=exact, tol=1e-5)
+    h.check_graph()
+    h.check_state(exact=exact, tol=1e-5)
+    h.check_bound(max_nodes=n)
+    h.ink.close()
