@@ -232,6 +232,8 @@ ink_status ink_add_nodes(ink_ctx *ctx, const float *features, int64_t n_new, ink
  *   which = 3: MAX / MIN only: the cached bound on the best value among the neighbours other
  *              than the holder (>= it for MAX, <= it for MIN; -inf / +inf if there is none).  It is
  *              exact after a recompute and may be loose afterwards; it never affects results.
+ *   which = 4: MAX / MIN only, int32: the neighbour other than the holder that has exactly the
+ *              value of which = 3 (the lowest such id), or -1 where that is not known.
  * width is returned in *width_out if not NULL. */
 ink_status ink_get_layer(ink_ctx *ctx, int32_t layer, int32_t which, int64_t row0, int64_t nrows,
                          void *dst, int32_t dst_mem, int32_t *width_out);

@@ -263,7 +263,7 @@ class Ink:
         nrows = self.n - row0 if nrows is None else nrows
         w = C.c_int32()
         self._check(self._lib.ink_get_layer(self._h, layer, which, 0, 0, None, 0, C.byref(w)))
-        out = np.empty((nrows, w.value), np.int32 if which == 2 else np.float32)
+        out = np.empty((nrows, w.value), np.int32 if which in (2, 4) else np.float32)
         self._check(self._lib.ink_get_layer(self._h, layer, which, row0, nrows, out.ctypes.data, 0, None))
         return out
 

@@ -48,6 +48,30 @@ template <bool IS_MIN> __device__ __forceinline__ void merge2(float ov, int oi, 
   else loser = ov;
   sv = best_of<IS_MIN>(loser, best_of<IS_MIN>(sv, os));
 }
+// ... and with the runner-up's id si (lowest id among the non-holders that have the value sv)
+// ASC: the caller feeds ids in ascending order, so on equal values the entry seen first keeps its
+// place and the id comparisons drop out (8 instead of 12 vector instructions per value; the
+// re-gather is bound by them, not by memory, on wide rows)
+template <bool IS_MIN, bool ASC>
+__device__ __forceinline__ void take2i(float x, int id, float &bv, int &bi, float &sv, int &si) {
+  const bool first = better<IS_MIN>(x, bv) || (!ASC && x == bv && id < bi);
+  const bool second = better<IS_MIN>(x, sv) || (!ASC && x == sv && id < si);
+  const float nsv = first ? bv : (second ? x : sv);
+  const int nsi = first ? bi : (second ? id : si);
+  bv = first ? x : bv;
+  bi = first ? id : bi;
+  sv = nsv;
+  si = nsi;
+}
+// merge of the (best, runner-up) pairs of two disjoint sets
+template <bool IS_MIN>
+__device__ __forceinline__ void merge2i(float ov, int oi, float os, int osi, float &bv, int &bi, float &sv, int &si) {
+  float lv; int li;
+  if (better<IS_MIN>(ov, bv) || (ov == bv && oi < bi)) { lv = bv; li = bi; bv = ov; bi = oi; }
+  else { lv = ov; li = oi; }
+  if (better<IS_MIN>(lv, sv) || (lv == sv && li < si)) { sv = lv; si = li; }
+  if (better<IS_MIN>(os, sv) || (os == sv && osi < si)) { sv = os; si = osi; }
+}
 
 __device__ __forceinline__ float4 ld4(const float *p) { return *reinterpret_cast<const float4 *>(p); }
 
@@ -65,18 +89,31 @@ template <bool IS_MIN, int LPR> __device__ __forceinline__ void reduce_groups(F4
     }
   }
 }
+template <bool IS_MIN, int LPR> __device__ __forceinline__ void reduce_groups_i(F4 &bv, I4 &bi, F4 &sv, I4 &si) {
+#pragma unroll
+  for (int off = LPR; off < kWave; off <<= 1) {
+#pragma unroll
+    for (int c = 0; c < 4; c++) {
+      float ov = __shfl_xor(bv.v[c], off, kWave);
+      int oi = __shfl_xor(bi.v[c], off, kWave);
+      float os = __shfl_xor(sv.v[c], off, kWave);
+      int oj = __shfl_xor(si.v[c], off, kWave);
+      merge2i<IS_MIN>(ov, oi, os, oj, bv.v[c], bi.v[c], sv.v[c], si.v[c]);
+    }
+  }
+}
 
 // Selection over neighbours ids[j0 .. j1) of one row, by the whole wave.  On return every lane
 // holds the best (value, id) and the runner-up value of its 4 dimensions over the range;
 // (worst, INT_MAX, worst) if empty.
-template <bool IS_MIN, int LPR>
-__device__ __forceinline__ void gather_range(const int32_t *ids, int64_t j0, int64_t j1, const float *M,
-                                             int ldm, bool lane_on, int q, F4 &bv, I4 &bi, F4 &sv) {
+template <bool IS_MIN, int LPR, bool ASC>
+__device__ __forceinline__ void gather_range_t(const int32_t *ids, int64_t j0, int64_t j1, const float *M,
+                                               int ldm, bool lane_on, int q, F4 &bv, I4 &bi, F4 &sv, I4 &si) {
   constexpr int G = kWave / LPR;
   const int l = lane_id();
   const int g = l / LPR;
 #pragma unroll
-  for (int c = 0; c < 4; c++) { bv.v[c] = worst<IS_MIN>(); bi.v[c] = 0x7fffffff; sv.v[c] = worst<IS_MIN>(); }
+  for (int c = 0; c < 4; c++) { bv.v[c] = worst<IS_MIN>(); bi.v[c] = 0x7fffffff; sv.v[c] = worst<IS_MIN>(); si.v[c] = 0x7fffffff; }
   for (int64_t jb = j0; jb < j1; jb += kWave) {
     int64_t jj = jb + l;
     int myid = jj < j1 ? ids[jj] : -1;
@@ -95,31 +132,41 @@ __device__ __forceinline__ void gather_range(const int32_t *ids, int64_t j0, int
 #pragma unroll
       for (int u = 0; u < U; u++) {
         if (id[u] >= 0 && lane_on) {
-          take2<IS_MIN>(row[u].x, id[u], bv.v[0], bi.v[0], sv.v[0]);
-          take2<IS_MIN>(row[u].y, id[u], bv.v[1], bi.v[1], sv.v[1]);
-          take2<IS_MIN>(row[u].z, id[u], bv.v[2], bi.v[2], sv.v[2]);
-          take2<IS_MIN>(row[u].w, id[u], bv.v[3], bi.v[3], sv.v[3]);
+          take2i<IS_MIN, ASC>(row[u].x, id[u], bv.v[0], bi.v[0], sv.v[0], si.v[0]);
+          take2i<IS_MIN, ASC>(row[u].y, id[u], bv.v[1], bi.v[1], sv.v[1], si.v[1]);
+          take2i<IS_MIN, ASC>(row[u].z, id[u], bv.v[2], bi.v[2], sv.v[2], si.v[2]);
+          take2i<IS_MIN, ASC>(row[u].w, id[u], bv.v[3], bi.v[3], sv.v[3], si.v[3]);
         }
       }
     }
   }
-  reduce_groups<IS_MIN, LPR>(bv, bi, sv);
+  reduce_groups_i<IS_MIN, LPR>(bv, bi, sv, si);
+}
+// asc (wave-uniform): ids[j0 .. j1) are ascending, as they are for every node no op has touched yet
+template <bool IS_MIN, int LPR>
+__device__ __forceinline__ void gather_range(const int32_t *ids, int64_t j0, int64_t j1, const float *M, int ldm,
+                                             bool lane_on, int q, bool asc, F4 &bv, I4 &bi, F4 &sv, I4 &si) {
+  if (asc) gather_range_t<IS_MIN, LPR, true>(ids, j0, j1, M, ldm, lane_on, q, bv, bi, sv, si);
+  else gather_range_t<IS_MIN, LPR, false>(ids, j0, j1, M, ldm, lane_on, q, bv, bi, sv, si);
 }
 
 struct RowOut {
-  float *A; int32_t *ARG; float *UB; int ld; int d;
+  float *A; int32_t *ARG; float *UB; int32_t *ARG2; int ld; int d;
 };
 
 // Writes (bv, bi) as the new aggregated row of v if it differs from what is stored; returns
 // (wave-uniform) whether any VALUE of the first d dimensions changed bitwise.
 template <int LPR>
 __device__ __forceinline__ bool store_row(const RowOut &o, int v, bool lane_on, int q, const F4 &bv,
-                                          const I4 &bi, const F4 &sv, bool have_old, const F4 &ov, const I4 &oi) {
+                                          const I4 &bi, const F4 &sv, const I4 &si, bool have_old, const F4 &ov,
+                                          const I4 &oi) {
   const int l = lane_id();
   bool writer = lane_on && l < LPR;
   bool vchg = false, ichg = false;
-  if (writer)      // the bound is rewritten unconditionally (it never decides whether a row "changed")
+  if (writer) {    // bound and runner-up are rewritten unconditionally (they never decide whether a row "changed")
     *reinterpret_cast<float4 *>(o.UB + (int64_t)v * o.ld + 4 * q) = make_float4(sv.v[0], sv.v[1], sv.v[2], sv.v[3]);
+    *reinterpret_cast<int4 *>(o.ARG2 + (int64_t)v * o.ld + 4 * q) = make_int4(si.v[0], si.v[1], si.v[2], si.v[3]);
+  }
   if (writer) {
     F4 cv = ov; I4 ci = oi;
     if (!have_old) {
@@ -141,10 +188,14 @@ __device__ __forceinline__ bool store_row(const RowOut &o, int v, bool lane_on, 
   return __ballot(vchg) != 0ull;
 }
 
+// no in-neighbours: alpha = 0, arg = -1; fewer than two: no runner-up
 template <bool IS_MIN>
-__device__ __forceinline__ void finish_empty(F4 &bv, I4 &bi, F4 &sv) {   // no in-neighbours: alpha = 0, arg = -1
+__device__ __forceinline__ void finish_empty(F4 &bv, I4 &bi, F4 &sv, I4 &si) {
 #pragma unroll
-  for (int c = 0; c < 4; c++) if (bi.v[c] == 0x7fffffff) { bv.v[c] = 0.f; bi.v[c] = -1; sv.v[c] = worst<IS_MIN>(); }
+  for (int c = 0; c < 4; c++) {
+    if (bi.v[c] == 0x7fffffff) { bv.v[c] = 0.f; bi.v[c] = -1; sv.v[c] = worst<IS_MIN>(); }
+    if (si.v[c] == 0x7fffffff) si.v[c] = -1;
+  }
 }
 
 __device__ __forceinline__ void mark_bit(uint64_t *bm, int v) {
@@ -169,18 +220,19 @@ __global__ __launch_bounds__(256) void k_agg_full(AggArgs a, const int32_t *targ
     return;
   }
   int64_t off = a.in_off[v];
-  F4 bv; I4 bi; F4 sv;
-  gather_range<IS_MIN, LPR>(a.in_ids + off, 0, deg, a.M, a.ldm, lane_on, q, bv, bi, sv);
-  finish_empty<IS_MIN>(bv, bi, sv);
-  RowOut o{a.A, a.ARG, a.UB, a.ld, a.d};
+  F4 bv; I4 bi; F4 sv; I4 si;
+  gather_range<IS_MIN, LPR>(a.in_ids + off, 0, deg, a.M, a.ldm, lane_on, q, a.in_asc[v] != 0, bv, bi, sv, si);
+  finish_empty<IS_MIN>(bv, bi, sv, si);
+  RowOut o{a.A, a.ARG, a.UB, a.ARG2, a.ld, a.d};
   F4 dum; I4 dumi;
   bool ch;
-  if (compare) ch = store_row<LPR>(o, v, lane_on, q, bv, bi, sv, false, dum, dumi);
+  if (compare) ch = store_row<LPR>(o, v, lane_on, q, bv, bi, sv, si, false, dum, dumi);
   else {
     if (lane_on && l < LPR) {
       *reinterpret_cast<float4 *>(a.A + (int64_t)v * a.ld + 4 * q) = make_float4(bv.v[0], bv.v[1], bv.v[2], bv.v[3]);
       *reinterpret_cast<int4 *>(a.ARG + (int64_t)v * a.ld + 4 * q) = make_int4(bi.v[0], bi.v[1], bi.v[2], bi.v[3]);
       *reinterpret_cast<float4 *>(a.UB + (int64_t)v * a.ld + 4 * q) = make_float4(sv.v[0], sv.v[1], sv.v[2], sv.v[3]);
+      *reinterpret_cast<int4 *>(a.ARG2 + (int64_t)v * a.ld + 4 * q) = make_int4(si.v[0], si.v[1], si.v[2], si.v[3]);
     }
     ch = false;
   }
@@ -192,10 +244,11 @@ __global__ __launch_bounds__(256) void k_agg_full(AggArgs a, const int32_t *targ
 template <bool IS_MIN, int LPR, int NW>
 __global__ __launch_bounds__(NW * kWave) void k_big_partial(AggArgs a, const int32_t *big_list, const int32_t *n_big_p,
                                                       const int32_t *pref, const int32_t *total_p, float *part_v,
-                                                      int32_t *part_i, float *part_s) {
+                                                      int32_t *part_i, float *part_s, int32_t *part_j) {
   __shared__ float sv[NW][kWave * 4];    // sized per variant: the 4-wave form must not pay the LDS of the 16-wave one
   __shared__ int si[NW][kWave * 4];
   __shared__ float ss[NW][kWave * 4];
+  __shared__ int sj[NW][kWave * 4];
   const int l = lane_id(), w = threadIdx.x / kWave;
   constexpr int nw = NW;
   const int q = l % LPR;
@@ -208,20 +261,25 @@ __global__ __launch_bounds__(NW * kWave) void k_big_partial(AggArgs a, const int
     int64_t off = a.in_off[v];
     int64_t len = j1 - j0;
     int64_t w0 = j0 + len * w / nw, w1 = j0 + len * (w + 1) / nw;
-    F4 bv; I4 bi; F4 s2;
-    gather_range<IS_MIN, LPR>(a.in_ids + off, w0, w1, a.M, a.ldm, lane_on, q, bv, bi, s2);
+    F4 bv; I4 bi; F4 s2; I4 j2;
+    gather_range<IS_MIN, LPR>(a.in_ids + off, w0, w1, a.M, a.ldm, lane_on, q, a.in_asc[v] != 0, bv, bi, s2, j2);
 #pragma unroll
-    for (int c = 0; c < 4; c++) { sv[w][l * 4 + c] = bv.v[c]; si[w][l * 4 + c] = bi.v[c]; ss[w][l * 4 + c] = s2.v[c]; }
+    for (int c = 0; c < 4; c++) {
+      sv[w][l * 4 + c] = bv.v[c]; si[w][l * 4 + c] = bi.v[c]; ss[w][l * 4 + c] = s2.v[c]; sj[w][l * 4 + c] = j2.v[c];
+    }
     __syncthreads();
     if (w == 0) {
       for (int ww = 1; ww < nw; ww++)
 #pragma unroll
         for (int c = 0; c < 4; c++)
-          merge2<IS_MIN>(sv[ww][l * 4 + c], si[ww][l * 4 + c], ss[ww][l * 4 + c], bv.v[c], bi.v[c], s2.v[c]);
+          merge2i<IS_MIN>(sv[ww][l * 4 + c], si[ww][l * 4 + c], ss[ww][l * 4 + c], sj[ww][l * 4 + c], bv.v[c], bi.v[c],
+                          s2.v[c], j2.v[c]);
       if (lane_on && l < LPR) {
         int64_t o = (int64_t)cg * a.wd + 4 * q;
 #pragma unroll
-        for (int c = 0; c < 4; c++) { part_v[o + c] = bv.v[c]; part_i[o + c] = bi.v[c]; part_s[o + c] = s2.v[c]; }
+        for (int c = 0; c < 4; c++) {
+          part_v[o + c] = bv.v[c]; part_i[o + c] = bi.v[c]; part_s[o + c] = s2.v[c]; part_j[o + c] = j2.v[c];
+        }
       }
     }
     __syncthreads();
@@ -232,27 +290,31 @@ __global__ __launch_bounds__(NW * kWave) void k_big_partial(AggArgs a, const int
 template <bool IS_MIN, int LPR>
 __global__ __launch_bounds__(64) void k_big_final(AggArgs a, const int32_t *big_list, const int32_t *n_big_p,
                                                   const int32_t *pref, const float *part_v, const int32_t *part_i,
-                                                  const float *part_s, uint64_t *chg, int compare, Counters *cnt) {
+                                                  const float *part_s, const int32_t *part_j, uint64_t *chg,
+                                                  int compare, Counters *cnt) {
   const int l = lane_id();
   const int q = l % LPR;
   const bool lane_on = 4 * q < a.wd;
   const int n_big = *n_big_p;
   for (int i = blockIdx.x; i < n_big; i += gridDim.x) {
     int v = big_list[i];
-    F4 bv; I4 bi; F4 s2;
+    F4 bv; I4 bi; F4 s2; I4 j2;
 #pragma unroll
-    for (int c = 0; c < 4; c++) { bv.v[c] = worst<IS_MIN>(); bi.v[c] = 0x7fffffff; s2.v[c] = worst<IS_MIN>(); }
+    for (int c = 0; c < 4; c++) {
+      bv.v[c] = worst<IS_MIN>(); bi.v[c] = 0x7fffffff; s2.v[c] = worst<IS_MIN>(); j2.v[c] = 0x7fffffff;
+    }
     if (lane_on && l < LPR) {
       for (int p = pref[i]; p < pref[i + 1]; p++) {
         int64_t o = (int64_t)p * a.wd + 4 * q;
 #pragma unroll
-        for (int c = 0; c < 4; c++) merge2<IS_MIN>(part_v[o + c], part_i[o + c], part_s[o + c], bv.v[c], bi.v[c], s2.v[c]);
+        for (int c = 0; c < 4; c++)
+          merge2i<IS_MIN>(part_v[o + c], part_i[o + c], part_s[o + c], part_j[o + c], bv.v[c], bi.v[c], s2.v[c], j2.v[c]);
       }
     }
-    finish_empty<IS_MIN>(bv, bi, s2);
-    RowOut o{a.A, a.ARG, a.UB, a.ld, a.d};
+    finish_empty<IS_MIN>(bv, bi, s2, j2);
+    RowOut o{a.A, a.ARG, a.UB, a.ARG2, a.ld, a.d};
     F4 dum; I4 dumi;
-    bool ch = store_row<LPR>(o, v, lane_on, q, bv, bi, s2, false, dum, dumi);
+    bool ch = store_row<LPR>(o, v, lane_on, q, bv, bi, s2, j2, false, dum, dumi);
     if (compare && ch && chg && l == 0) {
       mark_bit(chg, v);
       atomicAdd(&cnt->stripe[blockIdx.x % kStripes][ST_ACHG], 1ull);
@@ -275,19 +337,22 @@ __device__ __forceinline__ void agg_events_one(const AggArgs &a, int v, int e0, 
   const int l = lane_id();
   const int q = l % LPR, g = l / LPR;
   const bool lane_on = 4 * q < a.wd;
-  F4 ov; I4 oi; F4 ou;       // cached value, holder and bound on the other neighbours
+  F4 ov; I4 oi; F4 ou; I4 o2;   // cached value, holder, bound on the other neighbours, runner-up id or -1
 #pragma unroll
-  for (int c = 0; c < 4; c++) { ov.v[c] = 0.f; oi.v[c] = -1; ou.v[c] = worst<IS_MIN>(); }
+  for (int c = 0; c < 4; c++) { ov.v[c] = 0.f; oi.v[c] = -1; ou.v[c] = worst<IS_MIN>(); o2.v[c] = -1; }
   if (lane_on) {
     float4 x = ld4(a.A + (int64_t)v * a.ld + 4 * q);
     int4 y = *reinterpret_cast<const int4 *>(a.ARG + (int64_t)v * a.ld + 4 * q);
     float4 z = ld4(a.UB + (int64_t)v * a.ld + 4 * q);
+    int4 y2 = *reinterpret_cast<const int4 *>(a.ARG2 + (int64_t)v * a.ld + 4 * q);
     ov.v[0] = x.x; ov.v[1] = x.y; ov.v[2] = x.z; ov.v[3] = x.w;
     oi.v[0] = y.x; oi.v[1] = y.y; oi.v[2] = y.z; oi.v[3] = y.w;
     ou.v[0] = z.x; ou.v[1] = z.y; ou.v[2] = z.z; ou.v[3] = z.w;
+    o2.v[0] = y2.x; o2.v[1] = y2.y; o2.v[2] = y2.z; o2.v[3] = y2.w;
   }
   F4 cv; I4 ci; F4 cs;       // best candidate, its source, runner-up candidate value
   bool reset[4] = {false, false, false, false};
+  bool inv2[4] = {false, false, false, false};   // the recorded runner-up left or changed its message
   bool any_del = false;      // the segment cancels something: a removed edge or a changed source
 #pragma unroll
   for (int c = 0; c < 4; c++) { cv.v[c] = worst<IS_MIN>(); ci.v[c] = 0x7fffffff; cs.v[c] = worst<IS_MIN>(); }
@@ -310,6 +375,10 @@ __device__ __forceinline__ void agg_events_one(const AggArgs &a, int v, int e0, 
           uint32_t kind = x >> kEvKindShift;
           int uu = (int)(x & kEvIdMask);
           any_del |= kind != EV_ADD;
+          if (kind != EV_ADD) {
+#pragma unroll
+            for (int c = 0; c < 4; c++) inv2[c] |= (o2.v[c] == uu);
+          }
           if (kind == EV_DEL) {
 #pragma unroll
             for (int c = 0; c < 4; c++) reset[c] |= (oi.v[c] == uu);
@@ -336,29 +405,54 @@ __device__ __forceinline__ void agg_events_one(const AggArgs &a, int v, int e0, 
 #pragma unroll
   for (int off = LPR; off < kWave; off <<= 1)
 #pragma unroll
-    for (int c = 0; c < 4; c++) reset[c] |= (bool)__shfl_xor((int)reset[c], off, kWave);
+    for (int c = 0; c < 4; c++) {
+      reset[c] |= (bool)__shfl_xor((int)reset[c], off, kWave);
+      inv2[c] |= (bool)__shfl_xor((int)inv2[c], off, kWave);
+    }
   reduce_groups<IS_MIN, LPR>(cv, ci, cs);
-  F4 nv = ov; I4 ni = oi; F4 nu = ou;
+  // Per dimension: (nv, ni) new value and holder, nu new bound on the others, n2 the other neighbour
+  // that has exactly the value nu (lowest such id) where that is certain, else -1.  A recorded
+  // runner-up is trusted only while it neither left nor changed; it lets a reset that no candidate
+  // covers be settled by promotion instead of a recompute, once per dimension between recomputes.
+  F4 nv = ov; I4 ni = oi; F4 nu = ou; I4 n2;
   bool exposed = false;
 #pragma unroll
   for (int c = 0; c < 4; c++) {
     const bool has_cand = ci.v[c] != 0x7fffffff;
+    const int r2 = inv2[c] ? -1 : o2.v[c];               // runner-up still known to hold ou
+    const bool ou_beats_cs = better<IS_MIN>(ou.v[c], cs.v[c]);
+    n2.v[c] = r2;
     if (oi.v[c] < 0) {                       // no neighbours before this batch
+      n2.v[c] = -1;
       if (has_cand) { nv.v[c] = cv.v[c]; ni.v[c] = ci.v[c]; nu.v[c] = cs.v[c]; }
     } else if (reset[c]) {
-      // the holder left or got worse (then its new value is one of the candidates): every other
-      // old neighbour is bounded by ou, so a candidate that strictly beats ou is the new selection
+      // the holder left or got worse (then its new value is one of the candidates); every other
+      // old neighbour is bounded by ou, and those that reach ou have ids above r2
       if (has_cand && better<IS_MIN>(cv.v[c], ou.v[c])) {
         nv.v[c] = cv.v[c]; ni.v[c] = ci.v[c]; nu.v[c] = best_of<IS_MIN>(ou.v[c], cs.v[c]);
+        n2.v[c] = ou_beats_cs ? r2 : -1;
+      } else if (r2 >= 0 && has_cand && cv.v[c] == ou.v[c] && ci.v[c] < r2) {
+        nv.v[c] = cv.v[c]; ni.v[c] = ci.v[c];            // candidate and runner-up tie: the lower id holds
+        n2.v[c] = ou_beats_cs ? r2 : -1;                 // nu stays ou, held by r2
+      } else if (r2 >= 0) {
+        nv.v[c] = ou.v[c]; ni.v[c] = r2;                 // the runner-up takes over; who follows is not known
+        n2.v[c] = -1;                                    // nu stays ou: it bounds the old others and every candidate
       } else exposed = true;
     } else if (has_cand) {
       if (ci.v[c] == oi.v[c]) {              // the holder itself, unchanged or better at this dimension
         nv.v[c] = cv.v[c]; nu.v[c] = best_of<IS_MIN>(ou.v[c], cs.v[c]);
+        n2.v[c] = ou_beats_cs ? r2 : -1;
       } else if (better<IS_MIN>(cv.v[c], ov.v[c]) || (cv.v[c] == ov.v[c] && ci.v[c] < oi.v[c])) {
         nv.v[c] = cv.v[c]; ni.v[c] = ci.v[c];          // the old holder joins the others
         nu.v[c] = best_of<IS_MIN>(best_of<IS_MIN>(ou.v[c], ov.v[c]), cs.v[c]);
+        n2.v[c] = -1;
+        if (better<IS_MIN>(ov.v[c], cs.v[c])) {        // it is their best unless the old runner-up ties with it
+          if (better<IS_MIN>(ov.v[c], ou.v[c])) n2.v[c] = oi.v[c];
+          else if (r2 >= 0) n2.v[c] = oi.v[c] < r2 ? oi.v[c] : r2;
+        }
       } else {
         nu.v[c] = best_of<IS_MIN>(ou.v[c], cv.v[c]);
+        n2.v[c] = better<IS_MIN>(ou.v[c], cv.v[c]) ? r2 : -1;
       }
     }
   }
@@ -382,11 +476,11 @@ __device__ __forceinline__ void agg_events_one(const AggArgs &a, int v, int e0, 
       if (l == 0) big_list[atomicAdd(&cnt->v[C_NBIG], 1)] = v;
       return;
     }
-    gather_range<IS_MIN, LPR>(a.in_ids + a.in_off[v], 0, deg, a.M, a.ldm, lane_on, q, nv, ni, nu);
-    finish_empty<IS_MIN>(nv, ni, nu);
+    gather_range<IS_MIN, LPR>(a.in_ids + a.in_off[v], 0, deg, a.M, a.ldm, lane_on, q, a.in_asc[v] != 0, nv, ni, nu, n2);
+    finish_empty<IS_MIN>(nv, ni, nu, n2);
   }
-  RowOut o{a.A, a.ARG, a.UB, a.ld, a.d};
-  bool ch = store_row<LPR>(o, v, lane_on, q, nv, ni, nu, true, ov, oi);
+  RowOut o{a.A, a.ARG, a.UB, a.ARG2, a.ld, a.d};
+  bool ch = store_row<LPR>(o, v, lane_on, q, nv, ni, nu, n2, true, ov, oi);
   if (ch && l == 0) { mark_bit(chg, v); atomicAdd(&cnt->stripe[blockIdx.x % kStripes][ST_ACHG], 1ull); }
 }
 
@@ -417,15 +511,15 @@ static hipError_t run_big(ink_ctx *c, const AggArgs &a, uint64_t *chg, int compa
   if (block_threads == 1024)
     hipLaunchKernelGGL((k_big_partial<IS_MIN, LPR, 16>), grid, dim3(1024), 0, c->stream, a, list, (const int32_t *)n_big,
                        (const int32_t *)pref, (const int32_t *)total, c->big_part_v.as<float>(),
-                       c->big_part_i.as<int32_t>(), c->big_part_s.as<float>());
+                       c->big_part_i.as<int32_t>(), c->big_part_s.as<float>(), c->big_part_j.as<int32_t>());
   else
     hipLaunchKernelGGL((k_big_partial<IS_MIN, LPR, 4>), grid, dim3(256), 0, c->stream, a, list, (const int32_t *)n_big,
                        (const int32_t *)pref, (const int32_t *)total, c->big_part_v.as<float>(),
-                       c->big_part_i.as<int32_t>(), c->big_part_s.as<float>());
+                       c->big_part_i.as<int32_t>(), c->big_part_s.as<float>(), c->big_part_j.as<int32_t>());
   hipLaunchKernelGGL((k_big_final<IS_MIN, LPR>), dim3(kBigGrid), dim3(64), 0, c->stream, a, list,
                      (const int32_t *)n_big, (const int32_t *)pref, (const float *)c->big_part_v.as<float>(),
-                     (const int32_t *)c->big_part_i.as<int32_t>(), (const float *)c->big_part_s.as<float>(), chg, compare,
-                     c->d_cnt);
+                     (const int32_t *)c->big_part_i.as<int32_t>(), (const float *)c->big_part_s.as<float>(),
+                     (const int32_t *)c->big_part_j.as<int32_t>(), chg, compare, c->d_cnt);
   return hipGetLastError();
 }
 

@@ -283,11 +283,12 @@ static const Table &msg_table(ink_ctx *c, int l) {   // m_l: h_{l-1} (aggregate 
 static AggArgs agg_args(ink_ctx *c, int l) {       // layer l in 1..k
   AggArgs a;
   a.n = c->n;
-  a.in_off = c->gin.off; a.in_deg = c->gin.deg; a.in_ids = c->gin.ids;
+  a.in_off = c->gin.off; a.in_deg = c->gin.deg; a.in_ids = c->gin.ids; a.in_asc = c->gin.asc;
   const Table &M = msg_table(c, l);
   a.M = M.f(); a.ldm = M.ld;
   a.A = c->A[l].f(); a.ARG = c->is_select ? c->ARG[l].i() : nullptr; a.ld = c->A[l].ld; a.d = c->A[l].d;
   a.UB = c->is_select ? c->UB[l].f() : nullptr;
+  a.ARG2 = c->is_select ? c->ARG2[l].i() : nullptr;
   a.wd = round_up(a.d, 4);
   a.is_min = c->is_min;
   a.big_deg = kBigDeg;
@@ -426,7 +427,7 @@ extern "C" ink_status ink_create(const ink_csr *g, const float *features, int32_
   CREATE_TRY(c->big_list.reserve((size_t)(c->gin.pool_cap / kBigDeg + 4096) * 4));
   // tables
   c->H.resize(c->n_layers + 1); c->A.resize(c->n_layers + 1); c->ARG.resize(c->n_layers + 1);
-  c->UB.resize(c->n_layers + 1);
+  c->UB.resize(c->n_layers + 1); c->ARG2.resize(c->n_layers + 1);
   c->XW.resize(c->n_layers + 1); c->Msc.resize(c->n_layers + 1);
   if (c->kind == INK_MODEL_GCN) CREATE_TRY(hipMalloc(&c->cnorm, (size_t)nc * 4));
   CREATE_TRY(alloc_table(c->H[0], nc, feat_dim));
@@ -450,7 +451,7 @@ extern "C" ink_status ink_create(const ink_csr *g, const float *features, int32_
     L.in_dim = S.in_dim; L.out_dim = S.out_dim; L.hidden = S.mlp_hidden; L.act = S.act;
     CREATE_TRY(alloc_table(c->H[l], nc, S.out_dim));
     CREATE_TRY(alloc_table(c->A[l], nc, c->kind == INK_MODEL_GCN ? S.out_dim : S.in_dim));
-    if (c->is_select) { CREATE_TRY(alloc_table(c->ARG[l], nc, S.in_dim)); CREATE_TRY(alloc_table(c->UB[l], nc, S.in_dim)); }
+    if (c->is_select) { CREATE_TRY(alloc_table(c->ARG[l], nc, S.in_dim)); CREATE_TRY(alloc_table(c->UB[l], nc, S.in_dim)); CREATE_TRY(alloc_table(c->ARG2[l], nc, S.in_dim)); }
     if (c->kind == INK_MODEL_GCN) {
       CREATE_TRY(alloc_table(c->Msc[l], nc, S.out_dim));
       if (l == 1) CREATE_TRY(alloc_table(c->XW[1], nc, S.out_dim));
@@ -490,11 +491,12 @@ extern "C" void ink_destroy(ink_ctx *c) {
     if (g->off) (void)hipFree(g->off);
     if (g->deg) (void)hipFree(g->deg);
     if (g->cap) (void)hipFree(g->cap);
+    if (g->asc) (void)hipFree(g->asc);
     if (g->ids) (void)hipFree(g->ids);
   }
   if (c->new_out) (void)hipFree(c->new_out);
   for (auto &L : c->layers) for (float *p : {L.W1, L.b1, L.W2, L.b2}) if (p) (void)hipFree(p);
-  for (auto *vec : {&c->H, &c->A, &c->ARG, &c->UB, &c->XW, &c->Msc}) for (auto &t : *vec) if (t.p) (void)hipFree(t.p);
+  for (auto *vec : {&c->H, &c->A, &c->ARG, &c->UB, &c->ARG2, &c->XW, &c->Msc}) for (auto &t : *vec) if (t.p) (void)hipFree(t.p);
   if (c->cnorm) (void)hipFree(c->cnorm);
   if (c->d_cnt) (void)hipFree(c->d_cnt);
   if (c->h_cnt) (void)hipHostFree(c->h_cnt);
@@ -503,7 +505,7 @@ extern "C" void ink_destroy(ink_ctx *c) {
                     &c->b_del_d, &c->b_ins_s, &c->b_ins_d, &c->f_list[0], &c->f_list[1], &c->f_old[0], &c->f_old[1],
                     &c->f_pref, &c->ev_key, &c->ev_val, &c->t_list, &c->t_seg, &c->c_list, &c->c_flag, &c->c_idx, &c->c_old,
                     &c->b_touch_in,
-                    &c->big_list, &c->big_part_v, &c->big_part_i, &c->big_part_s, &c->big_pref, &c->f_delta, &c->stage0, &c->stage1, &c->res_ids, &c->res_emb})
+                    &c->big_list, &c->big_part_v, &c->big_part_i, &c->big_part_s, &c->big_part_j, &c->big_pref, &c->f_delta, &c->stage0, &c->stage1, &c->res_ids, &c->res_emb})
     b->release();
   for (auto e : c->ev_free) (void)hipEventDestroy(e);
   for (auto &p : c->ev_pending) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
@@ -522,7 +524,7 @@ static AggArgs agg_block(const AggArgs &a, int b) {
   AggArgs r = a;
   int c0 = b * kAggBlock;
   r.M += c0; r.A += c0;
-  if (r.ARG) { r.ARG += c0; r.UB += c0; }
+  if (r.ARG) { r.ARG += c0; r.UB += c0; r.ARG2 += c0; }
   r.d = std::min(kAggBlock, a.d - c0);
   r.wd = round_up(r.d, 4);
   return r;
@@ -1120,11 +1122,11 @@ extern "C" ink_status ink_get_layer(ink_ctx *c, int32_t layer, int32_t which, in
                                     int32_t dst_mem, int32_t *width_out) {
   if (!c) return INK_E_ARG;
   if (!c->inferred) return fail(c, INK_E_STATE, "ink_get_layer: call ink_full_infer first");
-  if (layer < 0 || layer > c->n_layers || which < 0 || which > 3 || (which > 0 && layer == 0))
+  if (layer < 0 || layer > c->n_layers || which < 0 || which > 4 || (which > 0 && layer == 0))
     return fail(c, INK_E_RANGE, "ink_get_layer: layer / which out of range");
   if (row0 < 0 || nrows < 0 || row0 + nrows > c->n) return fail(c, INK_E_RANGE, "ink_get_layer: rows out of range");
   if (which >= 2 && !c->is_select) return fail(c, INK_E_ARG, "ink_get_layer: no argument table for sum-type aggregators");
-  const Table &t = which == 0 ? c->H[layer] : (which == 1 ? c->A[layer] : (which == 2 ? c->ARG[layer] : c->UB[layer]));
+  const Table &t = which == 0 ? c->H[layer] : (which == 1 ? c->A[layer] : (which == 2 ? c->ARG[layer] : (which == 3 ? c->UB[layer] : c->ARG2[layer])));
   if (!t.p) return fail(c, INK_E_ARG, "ink_get_layer: table not kept for this model");
   if (width_out) *width_out = t.d;
   if (nrows == 0) return INK_OK;

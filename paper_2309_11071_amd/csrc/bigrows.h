@@ -39,6 +39,7 @@ inline hipError_t ensure_big_buffers(ink_ctx *c, int ld, bool with_ids) {
   if (with_ids) {
     INK_TRY(c->big_part_i.reserve((size_t)cap * ld * sizeof(int32_t)));
     INK_TRY(c->big_part_s.reserve((size_t)cap * ld * sizeof(float)));
+    INK_TRY(c->big_part_j.reserve((size_t)cap * ld * sizeof(int32_t)));
   }
   return hipSuccess;
 }

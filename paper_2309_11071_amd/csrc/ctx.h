@@ -54,6 +54,7 @@ struct GraphSide {
   int64_t *off = nullptr;    // [n] first slot of the node's block
   int32_t *deg = nullptr;    // [n] used slots
   int32_t *cap = nullptr;    // [n] block capacity
+  uint8_t *asc = nullptr;    // [n] 1 while the block's ids are ascending (true until the node's first applied op)
   int32_t *ids = nullptr;    // pool
   int64_t pool_cap = 0;      // slots in the pool
   int64_t pool_top = 0;      // first free slot (host mirror, exact)
@@ -113,7 +114,7 @@ struct ink_ctx {
   int32_t *new_out = nullptr;        // [n] out-edges appended by the current batch (tail of the block)
   std::vector<ink::DevLayer> layers;
   // tables: H[0..k]; A[1..k] aggregated (sum-type: plain sums); ARG[1..k]
-  std::vector<ink::Table> H, A, ARG, UB;   // UB: max/min only, bound on the runner-up value
+  std::vector<ink::Table> H, A, ARG, UB, ARG2;   // UB / ARG2: max/min only, bound on the runner-up value and its holder when known
   // GCN only: XW[l] = unscaled transformed messages h_{l-1} W_l, H-like scaled copies live in Msc[l]
   std::vector<ink::Table> XW, Msc;
   float *cnorm = nullptr;            // GCN: (indeg + 1)^(-1/2) per node
@@ -142,7 +143,7 @@ struct ink_ctx {
   ink::DevBuf c_old;                 // previous table rows of the transformed rows (sum-type)
   ink::DevBuf b_touch_in;            // destinations touched by the current batch
   int64_t n_touched_in = 0;
-  ink::DevBuf big_list, big_part_v, big_part_i, big_part_s, big_pref;   // cooperative re-gather of long rows
+  ink::DevBuf big_list, big_part_v, big_part_i, big_part_s, big_part_j, big_pref;   // cooperative re-gather of long rows
   ink::DevBuf stage0, stage1;        // transform staging
   ink::DevBuf res_ids, res_emb;      // result of the last batch
 
@@ -169,6 +170,8 @@ struct AggArgs {
   const float *M; int ldm;          // message table
   float *A; int32_t *ARG; int ld;   // aggregated table and argument table (row stride ld)
   float *UB;                        // max/min: bound on the best value among the non-holders (same layout)
+  const uint8_t *in_asc;            // per node: in-list ascending by id (lets ties go to the first seen)
+  int32_t *ARG2;                    // max/min: the non-holder that has exactly that value (lowest id), or -1 if not known
   int d;                            // columns handled by this launch (<= 256; wider rows go block by block)
   int wd;                           // d rounded up to 4
   bool is_min;

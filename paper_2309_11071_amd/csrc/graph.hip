@@ -31,6 +31,8 @@ static hipError_t side_alloc(GraphSide &g, int n, const std::vector<int64_t> &of
   INK_TRY(hipMalloc(&g.off, sizeof(int64_t) * (size_t)n));
   INK_TRY(hipMalloc(&g.deg, sizeof(int32_t) * (size_t)n));
   INK_TRY(hipMalloc(&g.cap, sizeof(int32_t) * (size_t)n));
+  INK_TRY(hipMalloc(&g.asc, (size_t)n));
+  INK_TRY(hipMemset(g.asc, 1, (size_t)n));       // built from ascending CSR rows; empty blocks are ascending too
   INK_TRY(hipMalloc(&g.ids, sizeof(int32_t) * (size_t)g.pool_cap));
   INK_TRY(hipMemcpy(g.off, off.data(), sizeof(int64_t) * (size_t)n, hipMemcpyHostToDevice));
   INK_TRY(hipMemcpy(g.deg, deg.data(), sizeof(int32_t) * (size_t)n, hipMemcpyHostToDevice));
@@ -220,7 +222,7 @@ __global__ __launch_bounds__(256) void k_apply(const int32_t *nodes, const int32
                                                const uint8_t *eff, const int32_t *pos, const int32_t *nd_ins,
                                                const int32_t *nd_del, int64_t *off, int32_t *deg, int32_t *cap,
                                                int32_t *ids, unsigned long long *pool_top, float slack,
-                                               int32_t *fill, int32_t *new_cnt) {
+                                               int32_t *fill, int32_t *new_cnt, uint8_t *asc) {
   __shared__ int sm[kScanThreads / kWave + 1];
   __shared__ long long s_newoff;
   const int i = blockIdx.x;
@@ -289,6 +291,7 @@ __global__ __launch_bounds__(256) void k_apply(const int32_t *nodes, const int32
   }
   if (threadIdx.x == 0) {
     deg[v] = d2;
+    asc[v] = 0;              // holes were refilled from the tail / ids appended: order no longer known
     if (new_cnt) new_cnt[v] = ni;
   }
 }
@@ -448,7 +451,7 @@ static ink_status apply_side(ink_ctx *c, GraphSide &g, SideBufs &b, int64_t n_op
   hipLaunchKernelGGL(k_apply, dim3(n_touched), dim3(256), 0, s, (const int32_t *)b.uniq, (const int32_t *)b.seg,
                      (const int32_t *)b.other, (const uint8_t *)b.eff, (const int32_t *)b.pos,
                      (const int32_t *)b.nd_ins, (const int32_t *)b.nd_del, g.off, g.deg, g.cap, g.ids, d_top,
-                     c->slack, b.fill, new_cnt);
+                     c->slack, b.fill, new_cnt, g.asc);
   INK_TRYS(hipGetLastError());
   g.pool_top += need;      // exact: the apply kernel allocates precisely what k_effect summed
   return INK_OK;

@@ -48,7 +48,7 @@ def test_reset_conditions_on_a_star():
     X[1:7, 1] = [0, 7, 1, 2, 7, 3]
     X[7:, 0] = [10, 9, 8.5, -5, 0, 0]      # spare nodes 7.. used as inserted sources
     X[7:, 1] = [0, 7, 0, -5, 0, 0]
-    X[:, 2:4] = -1.0                        # dimensions 2, 3: leaf 6 holds them throughout
+    X[:, 2:4] = -1.0                        # dimensions 2, 3: leaf 6 holds them while it is there
     X[6, 2:4] = 50.0
     model = tiny_model("sage", "max", (4, 4, 3))
     h = Harness(graph=g, X=X, model=model)
@@ -65,9 +65,15 @@ def test_reset_conditions_on_a_star():
     run(h, [(DEL, 7, 0), (INS, 9, 0)])            # holder deleted, inserted 8.5 < 10 but above every other
     assert cond() == (0, 0, 1, 0)                 # neighbour: covered thanks to the cached runner-up bound
     h.check_state()
-    run(h, [(DEL, 9, 0), (INS, 10, 0)])           # holder deleted, inserted -5 is below the others: exposed
+    run(h, [(DEL, 9, 0), (INS, 10, 0)])           # holder deleted, inserted -5 is below the others: the
+    assert cond() == (0, 0, 1, 0)                 # recorded runner-up (leaf 6, value 5) takes over
+    h.check_state()
+    assert h.ink.get_layer(1, 2)[0][0] == 6 and h.ink.get_layer(1, 4)[0][0] == -1
+    run(h, [(DEL, 6, 0)])                         # that holder leaves too and nobody is recorded behind it: exposed
     assert cond() == (0, 0, 0, 1)
     h.check_state()
+    h.check_bound()
+    assert (h.ink.get_layer(1, 4)[0] >= 0).all()  # a recompute leaves the exact runner-up and its id
     run(h, [(INS, 8, 0)])                         # dim 1: 8 ties with value 7 but has a higher id
     assert cond() == (1, 0, 0, 0)
     h.check_state()
@@ -148,9 +154,15 @@ def test_hub_rows_use_the_cooperative_recompute():
     h.check_state()
     arg = h.ink.get_layer(1, 2)[0]
     holders = sorted(set(int(a) for a in arg))
-    res, _ = run(h, [(DEL, u, 0) for u in holders[:3]])
-    assert h.ink.stats()["layers"][0]["n_exposed"] >= 1
+    res, _ = run(h, [(DEL, u, 0) for u in holders[:3]])      # the recorded runners-up take over
+    assert h.ink.stats()["layers"][0]["n_exposed"] == 0
     h.check_state()
+    arg2 = h.ink.get_layer(1, 2)[0]
+    res, _ = run(h, [(DEL, int(u), 0) for u in sorted(set(arg2.tolist()) - set(arg.tolist()))])
+    assert h.ink.stats()["layers"][0]["n_exposed"] == 1       # nobody recorded behind them: cooperative recompute
+    h.check_state()
+    h.check_bound(max_nodes=10000)
+    assert (h.ink.get_layer(1, 4)[0] >= 0).all()  # the recompute recorded the runner-up of every dimension
     run(h, [(INS, u, 0) for u in holders[:3]] + [(DEL, holders[-1], 0)])
     h.check_state()
     h.check_graph()

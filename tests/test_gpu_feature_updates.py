@@ -58,8 +58,9 @@ def test_unchanged_and_partly_changed_rows():
 
 
 def test_holder_gets_worse_and_recovers_on_a_star():
-    """Feature changes of the leaf that holds the maximum: a decrease below the runner-up exposes
-    the centre, a decrease that stays above it does not, and restoring the row restores the cache."""
+    """Feature changes of the leaf that holds the maximum: a decrease that stays above the
+    runner-up changes nothing else, one below it hands the dimensions to the recorded runner-up,
+    a second such change exposes the centre, and restoring the rows restores the cache."""
     d = 4
     graph, X = star(12, d, seed=3)
     X[1:13] = np.random.default_rng(5).uniform(0.0, 1.0, size=(12, d)).astype(np.float32)
@@ -68,7 +69,12 @@ def test_holder_gets_worse_and_recovers_on_a_star():
     x5 = h.X[5].copy()
     h.feature_step([5], (x5 - 5.0)[None, :])          # 5.0: still above every other leaf
     assert h.ink.stats()["layers"][0]["n_exposed"] == 0
-    h.feature_step([5], np.full((1, d), -1.0, np.float32))   # below the runner-up: recompute
+    h.feature_step([5], np.full((1, d), -1.0, np.float32))   # below the runner-up: it takes over
+    assert h.ink.stats()["layers"][0]["n_exposed"] == 0
+    new_holders = sorted(set(h.ink.get_layer(1, 2)[0].tolist()))
+    assert 5 not in new_holders
+    rows = np.full((len(new_holders), d), -2.0, np.float32)
+    h.feature_step(new_holders, rows)                        # they drop as well, nobody recorded behind: recompute
     assert h.ink.stats()["layers"][0]["n_exposed"] == 1
     h.feature_step([5], x5[None, :])
     h.check_state()

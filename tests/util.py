@@ -76,7 +76,9 @@ class Harness:
 
     def check_bound(self, exact=False, max_nodes=4000):
         """The cached bound on the runner-up value (get_layer which=3) must dominate the best value
-        among the neighbours other than the holder; right after a full inference it is exact."""
+        among the neighbours other than the holder; right after a full inference it is exact.
+        Where a runner-up id is recorded (which=4) it must be a neighbour other than the holder
+        that has exactly the bound's value, and no other non-holder may beat it (value, then lower id)."""
         if self.model["agg"] not in ("max", "min") or self.n > max_nodes:
             return
         is_min = self.model["agg"] == "min"
@@ -85,9 +87,11 @@ class Harness:
             m = self.ref["h"][l - 1]
             arg = self.ref["arg"][l]
             ub = self.ink.get_layer(l, 3)
+            a2 = self.ink.get_layer(l, 4)
             for v in range(self.n):
                 nb = col[rp[v]:rp[v + 1]]
                 if nb.size == 0:
+                    assert (a2[v] == -1).all(), (l, v)
                     continue
                 rows = m[nb].astype(np.float64)                      # [deg, d]
                 holder = arg[v][None, :] == nb[:, None]
@@ -95,10 +99,17 @@ class Harness:
                 others = np.where(holder, worst, rows)
                 true2 = others.min(axis=0) if is_min else others.max(axis=0)
                 got = ub[v].astype(np.float64)
+                # lowest id among the non-holders that reach the runner-up value (-1: fewer than 2 neighbours)
+                first = np.where(others == true2[None, :], nb.astype(np.int64)[:, None], np.int64(1) << 60).min(axis=0)
+                true_id = np.where(np.isfinite(true2), first, -1)
                 if exact:
                     assert np.array_equal(got, true2), (l, v)
+                    assert np.array_equal(a2[v], true_id), (l, v)
                 else:
                     assert np.all(got <= true2) if is_min else np.all(got >= true2), (l, v)
+                    known = a2[v] >= 0
+                    assert np.array_equal(a2[v][known], true_id[known]), (l, v)
+                    assert np.array_equal(got[known], true2[known]), (l, v)
 
     def check_graph(self):
         rp, col = self.ink.get_graph()
