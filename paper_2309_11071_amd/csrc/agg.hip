@@ -351,8 +351,9 @@ __device__ __forceinline__ void agg_events_one(const AggArgs &a, int v, int e0, 
     o2.v[0] = y2.x; o2.v[1] = y2.y; o2.v[2] = y2.z; o2.v[3] = y2.w;
   }
   F4 cv; I4 ci; F4 cs;       // best candidate, its source, runner-up candidate value
-  bool reset[4] = {false, false, false, false};
-  bool inv2[4] = {false, false, false, false};   // the recorded runner-up left or changed its message
+  // per dimension c: bit c = reset (the holder left or got worse), bit 4 + c = the recorded
+  // runner-up left or changed its message (one register instead of eight flags)
+  unsigned fl = 0u;
   bool any_del = false;      // the segment cancels something: a removed edge or a changed source
 #pragma unroll
   for (int c = 0; c < 4; c++) { cv.v[c] = worst<IS_MIN>(); ci.v[c] = 0x7fffffff; cs.v[c] = worst<IS_MIN>(); }
@@ -362,29 +363,26 @@ __device__ __forceinline__ void agg_events_one(const AggArgs &a, int v, int e0, 
     int cntw = (e1 - eb) < kWave ? (e1 - eb) : kWave;
     constexpr int U = 4;       // events in flight per lane group
     for (int it = 0; it < cntw; it += G * U) {
-      int src[U];
-      bool chgk[U];
+      int src[U];                // source id, bit 30 set for a changed source (ids stay below 2^30)
       float4 r4[U];
 #pragma unroll
       for (int u = 0; u < U; u++) {
         int k = it + u * G + g;
         uint32_t x = __shfl(mine, k < kWave ? k : 0, kWave);
         src[u] = -1;
-        chgk[u] = false;
         if (k < cntw && lane_on) {
           uint32_t kind = x >> kEvKindShift;
           int uu = (int)(x & kEvIdMask);
           any_del |= kind != EV_ADD;
           if (kind != EV_ADD) {
 #pragma unroll
-            for (int c = 0; c < 4; c++) inv2[c] |= (o2.v[c] == uu);
+            for (int c = 0; c < 4; c++) fl |= (unsigned)(o2.v[c] == uu) << (4 + c);
           }
           if (kind == EV_DEL) {
 #pragma unroll
-            for (int c = 0; c < 4; c++) reset[c] |= (oi.v[c] == uu);
+            for (int c = 0; c < 4; c++) fl |= (unsigned)(oi.v[c] == uu) << c;
           } else {
-            src[u] = uu;
-            chgk[u] = kind == EV_CHG;
+            src[u] = uu | (kind == EV_CHG ? (1 << 30) : 0);
             r4[u] = ld4(a.M + (int64_t)uu * a.ldm + 4 * q);
           }
         }
@@ -392,23 +390,23 @@ __device__ __forceinline__ void agg_events_one(const AggArgs &a, int v, int e0, 
 #pragma unroll
       for (int u = 0; u < U; u++) {
         if (src[u] < 0) continue;
+        const bool changed = (src[u] >> 30) & 1;
+        const int id = src[u] & kEvIdMask;
         float r[4] = {r4[u].x, r4[u].y, r4[u].z, r4[u].w};
 #pragma unroll
         for (int c = 0; c < 4; c++) {
-          if (chgk[u] && oi.v[c] == src[u] && better<IS_MIN>(ov.v[c], r[c])) reset[c] = true;
-          take2<IS_MIN>(r[c], src[u], cv.v[c], ci.v[c], cs.v[c]);
+          fl |= (unsigned)(changed && oi.v[c] == id && better<IS_MIN>(ov.v[c], r[c])) << c;
+          take2<IS_MIN>(r[c], id, cv.v[c], ci.v[c], cs.v[c]);
         }
       }
     }
   }
   // combine the lane groups
 #pragma unroll
-  for (int off = LPR; off < kWave; off <<= 1)
+  for (int off = LPR; off < kWave; off <<= 1) fl |= (unsigned)__shfl_xor((int)fl, off, kWave);
+  bool reset[4], inv2[4];
 #pragma unroll
-    for (int c = 0; c < 4; c++) {
-      reset[c] |= (bool)__shfl_xor((int)reset[c], off, kWave);
-      inv2[c] |= (bool)__shfl_xor((int)inv2[c], off, kWave);
-    }
+  for (int c = 0; c < 4; c++) { reset[c] = (fl >> c) & 1u; inv2[c] = (fl >> (4 + c)) & 1u; }
   reduce_groups<IS_MIN, LPR>(cv, ci, cs);
   // Per dimension: (nv, ni) new value and holder, nu new bound on the others, n2 the other neighbour
   // that has exactly the value nu (lowest such id) where that is certain, else -1.  A recorded
