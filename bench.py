@@ -28,8 +28,8 @@ HBM_PEAK_GBS = 8000.0
 # counter scaled by 2.0 and write counter by 1.0 (what a plain 1 GiB copy kernel reads back in the
 # same runs), divided by the aggregation launches of the batch (one per layer).
 MEASURED_TRAFFIC_PER_LAUNCH = {
-    2: {"bytes": 8.28e9, "source": "profiles/all_kernels_cfg2_gcn.md"},
-    3: {"bytes": 3.59e9, "source": "profiles/all_kernels_cfg3_sage_max.md"},
+    2: {"bytes": 8.29e9, "source": "profiles/all_kernels_cfg2_gcn.md"},
+    3: {"bytes": 8.82e8, "source": "profiles/all_kernels_cfg3_sage_max.md"},
 }
 
 
@@ -38,12 +38,12 @@ def agg_algorithmic_bytes(layer_stats, agg_width, n_del, select):
 
     events: 4 B payload each; every non-delete event reads one source row (4 d B);
     targets: the cached row is read and, when alpha changed, rewritten.  A cached row is alpha
-    alone for the sum-type aggregators (4 d B) and alpha + holder + runner-up bound for max / min
-    (12 d B; the bound, 4 d B, is rewritten for every target);
+    alone for the sum-type aggregators (4 d B) and alpha + holder + runner-up value + runner-up
+    id for max / min (16 d B; the runner-up pair, 8 d B, is rewritten for every target);
     recomputes: per neighbour one id (4 B) and one message row (4 d B).
     A dense layer is a recompute of every node."""
     total = 0
-    row = 12 if select else 4
+    row = 16 if select else 4
     for L, d in zip(layer_stats, agg_width):
         if L["dense"]:
             total += L["n_regather_nb"] * (4 + 4 * d) + L["n_targets"] * row * d
@@ -52,7 +52,7 @@ def agg_algorithmic_bytes(layer_stats, agg_width, n_del, select):
         total += ev * 4 + max(ev - n_del, 0) * 4 * d
         total += L["n_targets"] * row * d + L["n_alpha_changed"] * row * d
         if select:
-            total += (L["n_targets"] - L["n_alpha_changed"]) * 4 * d
+            total += (L["n_targets"] - L["n_alpha_changed"]) * 8 * d
         total += L["n_regather_nb"] * (4 + 4 * d)
     return total
 
@@ -229,13 +229,13 @@ def main():
         "full_inference_s": t_full,
         "full_inference_agg_ms": full_stats["ms"]["agg"],
         # the recompute kernels at their largest shape: every edge gathers one id and one message row,
-        # every node writes its cached row (alpha; for max / min also holder and runner-up bound)
+        # every node writes its cached row (alpha; for max / min also holder, runner-up value and id)
         "full_inference_roofline": (lambda b, ms: {"bound": "hbm", "achieved": b / 1e9 / (ms / 1e3), "peak": HBM_PEAK_GBS,
                                                    "unit": "GB/s", "frac": b / 1e9 / (ms / 1e3) / HBM_PEAK_GBS,
                                                    "algorithmic_bytes": b,
                                                    "note": "algorithmic bytes over time: message tables that fit "
                                                            "L2 / MALL are re-read from cache, so this can exceed the HBM peak"})(
-            sum(int(src.size) * (4 + 4 * d) + cfg.n_nodes * (12 if cfg.agg in ("max", "min") else 4) * d
+            sum(int(src.size) * (4 + 4 * d) + cfg.n_nodes * (16 if cfg.agg in ("max", "min") else 4) * d
                 for d in ink.agg_widths), max(full_stats["ms"]["agg"], 1e-6)),
     }
     if args.sweep:
