@@ -108,7 +108,10 @@ typedef struct {
   int32_t batch_mem;     /* ink_mem of the `updates` array of ink_apply_updates when it differs from
                             `mem` (e.g. host-built graph, device-resident update stream): the
                             effective location is device if either field says INK_MEM_DEVICE */
-  int32_t pad_;
+  int32_t small_batch_limit; /* update batches of at most this many entries take the single-workgroup
+                                form of the graph-store update (same result, fewer launches, one
+                                host read-back instead of two); 0 = default 4096, which is also the
+                                largest value; negative = never */
   int64_t pool_reserve;  /* free id slots kept behind the edge blocks of each direction for blocks
                             that outgrow their slack; when they run out the pool is re-allocated
                             at twice the size.  0 = default max(25 % of the pool, 2^20) */

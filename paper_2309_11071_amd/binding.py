@@ -47,7 +47,7 @@ class _Model(C.Structure):
 class _Options(C.Structure):
     _fields_ = [("mem", C.c_int32), ("hip_stream", C.c_void_p), ("slack_factor", C.c_float),
                 ("max_batch", C.c_int32), ("profile", C.c_int32), ("dense_threshold", C.c_float), ("batch_mem", C.c_int32),
-                ("pad_", C.c_int32), ("pool_reserve", C.c_int64), ("node_capacity", C.c_int64)]
+                ("small_batch_limit", C.c_int32), ("pool_reserve", C.c_int64), ("node_capacity", C.c_int64)]
 
 
 class _Result(C.Structure):
@@ -135,7 +135,7 @@ class Ink:
     """One context.  `model` is the dict layout of synth.make_model (host numpy weights)."""
 
     def __init__(self, rowptr, col, features, model, slack_factor=0.25, profile=False, stream=None,
-                 dense_threshold=0.0, pool_reserve=0, batch_device=False, node_capacity=0):
+                 dense_threshold=0.0, pool_reserve=0, batch_device=False, node_capacity=0, small_batch_limit=0):
         self._lib = load_library()
         self._h = C.c_void_p()
         rowptr = np.ascontiguousarray(rowptr, np.int64)
@@ -158,7 +158,7 @@ class Ink:
                    len(model["layers"]), layers)
         g = _Csr(rowptr.size - 1, col.size, rowptr.ctypes.data, col.ctypes.data if col.size else None)
         o = _Options(0, stream, slack_factor, 0, int(bool(profile)), dense_threshold,
-                     1 if batch_device else 0, 0, pool_reserve, node_capacity)
+                     1 if batch_device else 0, small_batch_limit, pool_reserve, node_capacity)
         st = self._lib.ink_create(C.byref(g), features.ctypes.data, features.shape[1], C.byref(m), C.byref(o),
                                   C.byref(self._h))
         if st != 0:

@@ -396,6 +396,8 @@ extern "C" ink_status ink_create(const ink_csr *g, const float *features, int32_
   c->slack = (opts && opts->slack_factor > 0.f) ? opts->slack_factor : 0.25f;
   c->profile = opts ? opts->profile : 0;
   c->pool_reserve = opts ? opts->pool_reserve : 0;
+  if (opts && opts->small_batch_limit != 0)
+    c->small_batch = opts->small_batch_limit < 0 ? 0 : std::min<int64_t>(opts->small_batch_limit, 4096);
   c->batch_dev = dev || (opts && opts->batch_mem == INK_MEM_DEVICE);
   if (opts && opts->dense_threshold != 0.f) c->dense_frac = opts->dense_threshold < 0.f ? 1e30 : opts->dense_threshold;
   memset(&c->stats, 0, sizeof(c->stats));
@@ -874,18 +876,15 @@ static ink_status apply_updates_impl(ink_ctx *c, const ink_edge_update *upd, int
   auto t0 = std::chrono::steady_clock::now();
   memset(out, 0, sizeof(*out));
   hipStream_t s = c->stream;
-  // validation on the host before anything is touched
-  std::vector<ink_edge_update> staged;
-  const ink_edge_update *h = upd;
-  if (c->batch_dev && n > 0) {
-    staged.resize((size_t)n);
-    API_TRY(hipMemcpy(staged.data(), upd, (size_t)n * sizeof(ink_edge_update), hipMemcpyDeviceToHost));
-    h = staged.data();
-  }
-  for (int64_t i = 0; i < n; i++) {
-    if (h[i].op > 1) return fail(c, INK_E_ARG, "ink_apply_updates: op must be 0 (insert) or 1 (delete)");
-    if (h[i].src < 0 || h[i].src >= c->n || h[i].dst < 0 || h[i].dst >= c->n)
-      return fail(c, INK_E_RANGE, "ink_apply_updates: node id out of range");
+  // Validation before anything is touched: a host-resident batch is checked here; a device-resident
+  // one by the first kernel of the graph stage, which drops the whole batch on a bad entry (the
+  // graph stage reports it after its first read-back, before any block is modified).
+  if (!c->batch_dev) {
+    for (int64_t i = 0; i < n; i++) {
+      if (upd[i].op > 1) return fail(c, INK_E_ARG, "ink_apply_updates: op must be 0 (insert) or 1 (delete)");
+      if (upd[i].src < 0 || upd[i].src >= c->n || upd[i].dst < 0 || upd[i].dst >= c->n)
+        return fail(c, INK_E_RANGE, "ink_apply_updates: node id out of range");
+    }
   }
   memset(&c->stats, 0, sizeof(c->stats));
   c->stats.n_layers = c->n_layers;

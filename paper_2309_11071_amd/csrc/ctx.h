@@ -88,9 +88,10 @@ struct Counters {            // device-written, host-read through pinned memory
 };
 // slots of Counters::v: event count of the next layer, unique targets, long rows listed, rows to
 // transform, rows changed, chunks of long rows, distinct ops of a batch, scratch of the graph stage,
-// and a 64-bit slot (pool top handed to the apply kernel)
-enum { C_NEV = 1, C_NT, C_NBIG, C_NC, C_NEXT, C_NCHUNK, C_NOPS, C_TMP0, C_TMP1, C_TMP2, C_TMP3,
-       C_TOP64 = 16 };
+// touched nodes and block chunks of the out side (single-workgroup graph stage), and two 64-bit
+// slots (pool tops handed to the apply kernels).  Slot 0 flags a malformed update batch.
+enum { C_ERR = 0, C_NEV = 1, C_NT, C_NBIG, C_NC, C_NEXT, C_NCHUNK, C_NOPS, C_TMP0, C_TMP1, C_TMP2, C_TMP3,
+       C_OT, C_OCH, C_TOP64 = 16, C_TOP64B = 18 };
 
 }  // namespace ink
 
@@ -122,7 +123,8 @@ struct ink_ctx {
   ink::PrimWorkspace ws;
   ink::Counters *d_cnt = nullptr;    // device counters
   ink::Counters *h_cnt = nullptr;    // pinned host mirror
-  unsigned long long h_top = 0;      // staging for the device copy of a pool top
+  unsigned long long h_top = 0, h_top2 = 0;   // staging for the device copies of the pool tops
+  int64_t small_batch = 4096;        // batches up to this size take the single-workgroup graph stage
   uint64_t *bm_a = nullptr;          // node bitmaps (n bits each)
 
   // batch buffers (grown on demand)

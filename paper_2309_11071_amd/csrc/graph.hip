@@ -98,11 +98,24 @@ hipError_t graph_export(ink_ctx *c, int64_t *rowptr, int32_t *col) {
 // ------------------------------------------------------------------------------- batch kernels
 struct RawUpdate { uint8_t op; uint8_t pad[3]; int32_t src, dst; };
 
-__global__ void k_unpack(const RawUpdate *raw, int64_t n, uint32_t *src, uint32_t *dst, uint32_t *pos) {
+// what is wrong with a list entry: bit 0 = op is neither insert nor delete, bit 1 = id out of range
+__device__ __forceinline__ int entry_error(const RawUpdate &a, int n_nodes) {
+  int e = a.op > 1 ? 1 : 0;
+  if (a.src < 0 || a.src >= n_nodes || a.dst < 0 || a.dst >= n_nodes) e |= 2;
+  return e;
+}
+
+// Also validates the batch: a bad entry sets *err, and no kernel uses an id as an index before
+// k_mark_last has seen *err and dropped every entry.
+__global__ void k_unpack(const RawUpdate *raw, int64_t n, int n_nodes, uint32_t *src, uint32_t *dst, uint32_t *pos,
+                         int32_t *err) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= n) return;
-  src[i] = (uint32_t)raw[i].src;
-  dst[i] = (uint32_t)raw[i].dst;
+  RawUpdate a = raw[i];
+  int e = entry_error(a, n_nodes);
+  if (e) atomicOr(err, e);
+  src[i] = (uint32_t)a.src;
+  dst[i] = (uint32_t)a.dst;
   pos[i] = (uint32_t)i;
 }
 
@@ -113,9 +126,10 @@ __global__ void k_gather_u32(const uint32_t *table, const uint32_t *idx, int64_t
 
 // entry j (in (dst, src, position) order) is the final word on its edge if the next entry names
 // another edge; self loops never count
-__global__ void k_mark_last(const RawUpdate *raw, const uint32_t *perm, int64_t n, uint8_t *flag) {
+__global__ void k_mark_last(const RawUpdate *raw, const uint32_t *perm, int64_t n, uint8_t *flag, const int32_t *err) {
   int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (j >= n) return;
+  if (*err) { flag[j] = 0; return; }
   RawUpdate a = raw[perm[j]];
   bool last = true;
   if (j + 1 < n) {
@@ -184,7 +198,8 @@ __global__ __launch_bounds__(256) void k_classify(const int32_t *nodes, const in
 __global__ __launch_bounds__(256) void k_effect(const int32_t *nodes, const int32_t *n_nodes, const int32_t *seg,
                                                 const uint8_t *op, const int32_t *pos, uint8_t *eff,
                                                 const int32_t *deg, const int32_t *cap, int32_t *nd_ins,
-                                                int32_t *nd_del, float slack, Counters *cnt) {
+                                                int32_t *nd_del, float slack, Counters *cnt, int st_need,
+                                                int st_ins, int st_del) {
   int64_t w = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kWave;
   int l = threadIdx.x & (kWave - 1);
   if (w >= *n_nodes) return;
@@ -209,10 +224,10 @@ __global__ __launch_bounds__(256) void k_effect(const int32_t *nodes, const int3
       if (extra < 4) extra = 4;
       if (want < nd2 + extra) want = nd2 + extra;
       want = (want + 3) & ~3ll;
-      atomicAdd(&cnt->stripe[blockIdx.x % kStripes][ST_REGATHER], (unsigned long long)want);   // pool space needed
+      atomicAdd(&cnt->stripe[blockIdx.x % kStripes][st_need], (unsigned long long)want);   // pool space needed
     }
-    if (ni) atomicAdd(&cnt->stripe[blockIdx.x % kStripes][ST_EXPOSED], (unsigned long long)ni);  // effective inserts
-    if (nd) atomicAdd(&cnt->stripe[blockIdx.x % kStripes][ST_ACHG], (unsigned long long)nd);     // effective deletes
+    if (ni) atomicAdd(&cnt->stripe[blockIdx.x % kStripes][st_ins], (unsigned long long)ni);  // effective inserts
+    if (nd) atomicAdd(&cnt->stripe[blockIdx.x % kStripes][st_del], (unsigned long long)nd);  // effective deletes
   }
 }
 
@@ -403,6 +418,17 @@ ink_status graph_add_nodes(ink_ctx *c, int64_t n_new) {
   return INK_OK;
 }
 
+// A kernel found a malformed entry and dropped the whole batch before any block was touched:
+// clear the flag and report.
+static ink_status batch_error(ink_ctx *c) {
+  int e = c->h_cnt->v[C_ERR];
+  INK_TRYS(hipMemsetAsync(&c->d_cnt->v[C_ERR], 0, sizeof(int32_t), c->stream));
+  INK_TRYS(hipStreamSynchronize(c->stream));
+  if (e & 2) { c->err = "ink_apply_updates: node id out of range"; return INK_E_RANGE; }
+  c->err = "ink_apply_updates: op must be 0 (insert) or 1 (delete)";
+  return INK_E_ARG;
+}
+
 // One direction.  Ops (node, other, op, pos) are in (node, other) order on the device; n_ops is
 // known on the host.  all_effective: presence was already established (out side).
 struct SideBufs {
@@ -430,9 +456,10 @@ static ink_status apply_side(ink_ctx *c, GraphSide &g, SideBufs &b, int64_t n_op
   hipLaunchKernelGGL(k_effect, grid1(n_ops_max * kWave), dim3(256), 0, s, (const int32_t *)b.uniq,
                      (const int32_t *)&dc->v[C_TMP0], (const int32_t *)b.seg, (const uint8_t *)b.op,
                      (const int32_t *)b.pos, b.eff, (const int32_t *)g.deg, (const int32_t *)g.cap, b.nd_ins, b.nd_del,
-                     c->slack, dc);
+                     c->slack, dc, (int)ST_REGATHER, (int)ST_EXPOSED, (int)ST_ACHG);
   INK_TRYS(hipMemcpyAsync(c->h_cnt, dc, sizeof(Counters), hipMemcpyDeviceToHost, s));
   INK_TRYS(hipStreamSynchronize(s));
+  if (c->h_cnt->v[C_ERR]) return batch_error(c);
   int n_touched = c->h_cnt->v[C_TMP0];
   *n_touched_out = n_touched;
   int64_t need = (int64_t)c->h_cnt->sum(ST_REGATHER);
@@ -457,12 +484,256 @@ static ink_status apply_side(ink_ctx *c, GraphSide &g, SideBufs &b, int64_t n_op
   return INK_OK;
 }
 
+// ------------------------------------------------------------ short batches: one workgroup
+// A batch of at most kSmallBatch entries goes through the same steps in two single-workgroup
+// kernels (one per direction) instead of some thirty launches: everything up to the per-node
+// op lists, their segment heads and the chunk plan of the blocks to walk happens in LDS.  Both
+// directions are classified before the host looks at the counters, so the batch costs one round
+// trip instead of two.  The lists these kernels write are the ones the general path writes.
+constexpr int kSmallThreads = 1024;
+constexpr int kSmallItems = 4;
+constexpr int kSmallBatch = kSmallThreads * kSmallItems;
+typedef SmallSortLds<kSmallThreads, kSmallItems> SmallLds;
+
+struct SmallSide {           // what one direction's kernels hand on (device pointers)
+  uint32_t *node; int32_t *other; uint8_t *op; int32_t *pos; uint8_t *eff;
+  int32_t *uniq, *seg, *chunk_pref, *nd_ins, *nd_del, *fill;
+};
+
+// Ops [0, n_ops) are in (node, other) order with their node ids in S.sk.  Writes the distinct
+// nodes, the start of each node's ops (plus the closing offset) and the exclusive prefix of the
+// chunk counts of their blocks; *n_uniq_out / *n_chunks_out get the totals.  s_u is LDS scratch
+// for kSmallBatch ints, sm for the block scan.
+__device__ __forceinline__ void small_heads_and_chunks(SmallLds &S, int *s_u, int *sm, int n_ops, const int32_t *deg,
+                                                       int32_t *uniq, int32_t *seg, int32_t *chunk_pref,
+                                                       int32_t *n_uniq_out, int32_t *n_chunks_out) {
+  const int t0 = threadIdx.x * kSmallItems;
+  int h[kSmallItems], cnt = 0;
+#pragma unroll
+  for (int k = 0; k < kSmallItems; k++) {
+    int i = t0 + k;
+    h[k] = i < n_ops && (i == 0 || S.sk[i] != S.sk[i - 1]);
+    cnt += h[k];
+  }
+  int n_uniq;
+  int ex = block_excl_scan<kSmallThreads>(cnt, sm, &n_uniq);
+#pragma unroll
+  for (int k = 0; k < kSmallItems; k++) {
+    int i = t0 + k;
+    if (h[k]) { uniq[ex] = (int32_t)S.sk[i]; seg[ex] = i; s_u[ex] = (int)S.sk[i]; ex++; }
+  }
+  if (threadIdx.x == 0) seg[n_uniq] = n_ops;
+  __syncthreads();
+  int ch[kSmallItems];
+  cnt = 0;
+#pragma unroll
+  for (int k = 0; k < kSmallItems; k++) {
+    int i = t0 + k;
+    ch[k] = i < n_uniq ? (deg[s_u[i]] + kChunk - 1) / kChunk : 0;
+    cnt += ch[k];
+  }
+  int n_chunks;
+  ex = block_excl_scan<kSmallThreads>(cnt, sm, &n_chunks);
+#pragma unroll
+  for (int k = 0; k < kSmallItems; k++) {
+    int i = t0 + k;
+    if (i < n_uniq) chunk_pref[i] = ex;
+    ex += ch[k];
+  }
+  if (threadIdx.x == 0) { *n_uniq_out = n_uniq; *n_chunks_out = n_chunks; }
+}
+
+// In side: validate, order by (dst, src, position), keep the final op per edge, build the op
+// lists of the touched destinations.
+__global__ __launch_bounds__(kSmallThreads) void k_small_in(const RawUpdate *raw, int n, int n_nodes, int passes,
+                                                            SmallSide o, const int32_t *deg, Counters *cnt) {
+  __shared__ SmallLds S;
+  __shared__ int s_src[kSmallBatch], s_dst[kSmallBatch];
+  __shared__ uint8_t s_op[kSmallBatch];
+  __shared__ int sm[kSmallThreads / kWave + 1];
+  // the stripes and the slots that later kernels fill start from zero; the slots before them
+  // are written below, the error flag is sticky
+  {
+    int32_t *z = &cnt->v[C_TMP2];
+    const int words = (int)((sizeof(Counters) - C_TMP2 * sizeof(int32_t)) / sizeof(int32_t));
+    for (int i = threadIdx.x; i < words; i += kSmallThreads) z[i] = 0;
+  }
+  int bad = 0;
+  for (int i = threadIdx.x; i < n; i += kSmallThreads) {
+    RawUpdate a = raw[i];
+    bad |= entry_error(a, n_nodes);
+    s_src[i] = a.src; s_dst[i] = a.dst; s_op[i] = a.op;
+    S.sk[i] = (uint32_t)a.src; S.sv[i] = (uint32_t)i;
+  }
+  int any_bad = __syncthreads_or(bad);
+  if (any_bad) {              // drop the batch: nothing below uses an id as an index
+    if (bad) atomicOr(&cnt->v[C_ERR], bad);
+    if (threadIdx.x == 0) { cnt->v[C_NOPS] = 0; cnt->v[C_TMP0] = 0; cnt->v[C_TMP1] = 0; o.seg[0] = 0; }
+    return;
+  }
+  small_sort_lds<kSmallThreads, kSmallItems>(S, n, passes);
+  for (int i = threadIdx.x; i < n; i += kSmallThreads) S.sk[i] = (uint32_t)s_dst[S.sv[i]];
+  small_sort_lds<kSmallThreads, kSmallItems>(S, n, passes);
+  // the last entry of each run of equal (dst, src) is the edge's final op; self loops never count
+  const int t0 = threadIdx.x * kSmallItems;
+  int keep[kSmallItems], c = 0;
+#pragma unroll
+  for (int k = 0; k < kSmallItems; k++) {
+    int j = t0 + k;
+    keep[k] = 0;
+    if (j < n) {
+      int a = (int)S.sv[j];
+      bool last = true;
+      if (j + 1 < n) { int b = (int)S.sv[j + 1]; last = s_src[a] != s_src[b] || s_dst[a] != s_dst[b]; }
+      keep[k] = last && s_src[a] != s_dst[a];
+    }
+    c += keep[k];
+  }
+  int n_ops;
+  int ex = block_excl_scan<kSmallThreads>(c, sm, &n_ops);
+#pragma unroll
+  for (int k = 0; k < kSmallItems; k++) {
+    if (keep[k]) {
+      int a = (int)S.sv[t0 + k];
+      o.node[ex] = (uint32_t)s_dst[a]; o.other[ex] = s_src[a]; o.op[ex] = s_op[a]; o.pos[ex] = -1;
+      S.sk[ex] = (uint32_t)s_dst[a];       // sk is not read in this phase
+      ex++;
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) cnt->v[C_NOPS] = n_ops;
+  small_heads_and_chunks(S, s_src, sm, n_ops, deg, o.uniq, o.seg, o.chunk_pref, &cnt->v[C_TMP0], &cnt->v[C_TMP1]);
+}
+
+// Out side, after the in side's k_effect: the effective ops become Delta E (inserted and removed
+// edges, each in (dst, src) order) and, stably re-ordered by source, the op lists of the touched
+// sources.
+__global__ __launch_bounds__(kSmallThreads) void k_small_out(SmallSide in, int passes, int32_t *ins_s, int32_t *ins_d,
+                                                             int32_t *del_s, int32_t *del_d, SmallSide o,
+                                                             const int32_t *deg, Counters *cnt) {
+  __shared__ SmallLds S;
+  __shared__ int s_u[kSmallBatch];
+  __shared__ int sm[kSmallThreads / kWave + 1];
+  const int n_ops = cnt->v[C_NOPS];
+  const int t0 = threadIdx.x * kSmallItems;
+  int e[kSmallItems], packed = 0;       // inserts in the low half, deletes in the high half
+#pragma unroll
+  for (int k = 0; k < kSmallItems; k++) {
+    int j = t0 + k;
+    e[k] = j < n_ops ? in.eff[j] : 0;
+    packed += (e[k] == 1) + ((e[k] == 2) << 16);
+  }
+  int tot;
+  int ex = block_excl_scan<kSmallThreads>(packed, sm, &tot);
+  int xi = ex & 0xFFFF, xd = ex >> 16;
+  const int n_ins = tot & 0xFFFF, n_del = tot >> 16;
+#pragma unroll
+  for (int k = 0; k < kSmallItems; k++) {
+    int j = t0 + k;
+    if (e[k] == 0) continue;
+    int src = in.other[j], dst = (int)in.node[j];
+    S.sk[xi + xd] = (uint32_t)src; S.sv[xi + xd] = (uint32_t)j;
+    if (e[k] == 1) { ins_s[xi] = src; ins_d[xi] = dst; xi++; }
+    else { del_s[xd] = src; del_d[xd] = dst; xd++; }
+  }
+  const int m = n_ins + n_del;
+  small_sort_lds<kSmallThreads, kSmallItems>(S, m, passes);
+  for (int p = threadIdx.x; p < m; p += kSmallThreads) {
+    int j = (int)S.sv[p];
+    o.node[p] = S.sk[p]; o.other[p] = (int)in.node[j]; o.op[p] = in.eff[j] == 2 ? 1 : 0; o.pos[p] = -1;
+  }
+  if (threadIdx.x == 0) { cnt->v[C_TMP2] = n_ins; cnt->v[C_TMP3] = n_del; }
+  small_heads_and_chunks(S, s_u, sm, m, deg, o.uniq, o.seg, o.chunk_pref, &cnt->v[C_OT], &cnt->v[C_OCH]);
+}
+
+static ink_status graph_apply_small(ink_ctx *c, int64_t n, int64_t *n_ins_out, int64_t *n_del_out) {
+  hipStream_t s = c->stream;
+  const size_t per = ((size_t)(n + 64) * 4 + 255) & ~(size_t)255;
+  INK_TRYS(c->b_misc.reserve(per * 28));
+  INK_TRYS(c->b_del_s.reserve(per)); INK_TRYS(c->b_del_d.reserve(per));
+  INK_TRYS(c->b_ins_s.reserve(per)); INK_TRYS(c->b_ins_d.reserve(per));
+  INK_TRYS(c->b_touch_in.reserve(per)); INK_TRYS(c->b_uniq.reserve(per));
+  Arena ar(c->b_misc);
+  SmallSide sd[2];
+  for (int k = 0; k < 2; k++) {
+    SmallSide &b = sd[k];
+    b.node = ar.get<uint32_t>(n); b.other = ar.get<int32_t>(n); b.op = ar.get<uint8_t>(n + 64);
+    b.pos = ar.get<int32_t>(n); b.eff = ar.get<uint8_t>(n + 64);
+    b.seg = ar.get<int32_t>(n + 2); b.chunk_pref = ar.get<int32_t>(n + 1);
+    b.nd_ins = ar.get<int32_t>(n + 1); b.nd_del = ar.get<int32_t>(n + 1); b.fill = ar.get<int32_t>(n + 1);
+  }
+  sd[0].uniq = c->b_touch_in.as<int32_t>();     // the touched lists are written in place
+  sd[1].uniq = c->b_uniq.as<int32_t>();
+  Counters *dc = c->d_cnt;
+  const int passes = (c->id_bits + kRadixBits - 1) / kRadixBits;
+  c->del_src = c->b_del_s.as<int32_t>(); c->del_dst = c->b_del_d.as<int32_t>();
+  c->ins_src = c->b_ins_s.as<int32_t>(); c->ins_dst = c->b_ins_d.as<int32_t>();
+  const int st[2][3] = {{ST_REGATHER, ST_EXPOSED, ST_ACHG}, {ST_NODEL, ST_NOEFFECT, ST_COVERED}};
+  const int slot_n[2] = {C_TMP0, C_OT}, slot_ch[2] = {C_TMP1, C_OCH};
+  GraphSide *gs[2] = {&c->gin, &c->gout};
+  for (int k = 0; k < 2; k++) {
+    SmallSide &b = sd[k];
+    GraphSide &g = *gs[k];
+    if (k == 0)
+      hipLaunchKernelGGL(k_small_in, dim3(1), dim3(kSmallThreads), 0, s, c->b_raw.as<RawUpdate>(), (int)n, c->n, passes,
+                         b, (const int32_t *)g.deg, dc);
+    else
+      hipLaunchKernelGGL(k_small_out, dim3(1), dim3(kSmallThreads), 0, s, sd[0], passes, c->ins_src, c->ins_dst,
+                         c->del_src, c->del_dst, b, (const int32_t *)g.deg, dc);
+    hipLaunchKernelGGL(k_classify, dim3(256), dim3(256), 0, s, (const int32_t *)b.uniq,
+                       (const int32_t *)&dc->v[slot_n[k]], (const int32_t *)b.seg, (const int32_t *)b.chunk_pref,
+                       (const int32_t *)&dc->v[slot_ch[k]], (const int64_t *)g.off, (const int32_t *)g.deg, g.ids,
+                       (const int32_t *)b.other, (const uint8_t *)b.op, b.pos);
+    hipLaunchKernelGGL(k_effect, grid1(n * kWave), dim3(256), 0, s, (const int32_t *)b.uniq,
+                       (const int32_t *)&dc->v[slot_n[k]], (const int32_t *)b.seg, (const uint8_t *)b.op,
+                       (const int32_t *)b.pos, b.eff, (const int32_t *)g.deg, (const int32_t *)g.cap, b.nd_ins, b.nd_del,
+                       c->slack, dc, st[k][0], st[k][1], st[k][2]);
+  }
+  INK_TRYS(hipMemcpyAsync(c->h_cnt, dc, sizeof(Counters), hipMemcpyDeviceToHost, s));
+  INK_TRYS(hipStreamSynchronize(s));
+  if (c->h_cnt->v[C_ERR]) return batch_error(c);
+  const int64_t ti = (int64_t)c->h_cnt->sum(st[0][1]), td = (int64_t)c->h_cnt->sum(st[0][2]);
+  if ((int64_t)c->h_cnt->sum(st[1][1]) != ti || (int64_t)c->h_cnt->sum(st[1][2]) != td) {
+    c->err = "graph store inconsistent: in- and out-adjacency disagree";
+    return INK_E_DEVICE;
+  }
+  c->n_ins = ti; c->n_del = td;
+  *n_ins_out = ti; *n_del_out = td;
+  c->n_touched_in = c->h_cnt->v[C_TMP0];
+  c->n_touched_src = c->h_cnt->v[C_OT];
+  if (ti + td == 0) { c->n_touched_src = 0; return INK_OK; }
+  unsigned long long *h_top[2] = {&c->h_top, &c->h_top2};
+  const int slot_top[2] = {C_TOP64, C_TOP64B};
+  for (int k = 0; k < 2; k++) {
+    SmallSide &b = sd[k];
+    GraphSide &g = *gs[k];
+    const int64_t need = (int64_t)c->h_cnt->sum(st[k][0]);
+    const int n_touched = c->h_cnt->v[slot_n[k]];
+    if (g.pool_top + need > g.pool_cap) {
+      hipError_t e = grow_pool(c, g, need);
+      if (e == hipErrorOutOfMemory) { c->err = "out of device memory while growing the edge pool"; return INK_E_OOM; }
+      INK_TRYS(e);
+    }
+    unsigned long long *d_top = (unsigned long long *)&dc->v[slot_top[k]];
+    *h_top[k] = (unsigned long long)g.pool_top;
+    INK_TRYS(hipMemcpyAsync(d_top, h_top[k], sizeof(unsigned long long), hipMemcpyHostToDevice, s));
+    hipLaunchKernelGGL(k_apply, dim3(n_touched), dim3(256), 0, s, (const int32_t *)b.uniq, (const int32_t *)b.seg,
+                       (const int32_t *)b.other, (const uint8_t *)b.eff, (const int32_t *)b.pos,
+                       (const int32_t *)b.nd_ins, (const int32_t *)b.nd_del, g.off, g.deg, g.cap, g.ids, d_top,
+                       c->slack, b.fill, k == 1 ? c->new_out : nullptr, g.asc);
+    INK_TRYS(hipGetLastError());
+    g.pool_top += need;
+  }
+  return INK_OK;
+}
+
 ink_status graph_apply_batch(ink_ctx *c, int64_t n, int64_t *n_ins_out, int64_t *n_del_out) {
   hipStream_t s = c->stream;
   *n_ins_out = *n_del_out = 0;
   c->n_ins = c->n_del = 0;
   c->n_touched_in = 0;
   if (n == 0) return INK_OK;
+  if (n <= c->small_batch) return graph_apply_small(c, n, n_ins_out, n_del_out);
   const RawUpdate *raw = c->b_raw.as<RawUpdate>();
   size_t per = ((size_t)(n + 64) * 4 + 255) & ~(size_t)255;
   INK_TRYS(c->b_misc.reserve(per * 28));
@@ -483,13 +754,14 @@ ink_status graph_apply_batch(ink_ctx *c, int64_t n, int64_t *n_ins_out, int64_t 
   int32_t *n_ops_d = &dc->v[C_NOPS];
 
   // (dst, src, position) order through two stable sorts
-  hipLaunchKernelGGL(k_unpack, grid1(n), dim3(256), 0, s, raw, n, srcv, dstv, v0);
+  hipLaunchKernelGGL(k_unpack, grid1(n), dim3(256), 0, s, raw, n, c->n, srcv, dstv, v0, &dc->v[C_ERR]);
   INK_TRYS(hipMemcpyAsync(k0, srcv, (size_t)n * 4, hipMemcpyDeviceToDevice, s));
   INK_TRYS(radix_sort_pairs(c->ws, k0, v0, n, c->id_bits, s));
   hipLaunchKernelGGL(k_gather_u32, grid1(n), dim3(256), 0, s, (const uint32_t *)dstv, (const uint32_t *)v0, n, k1);
   INK_TRYS(radix_sort_pairs(c->ws, k1, v0, n, c->id_bits, s));
   // final op per distinct edge; their number stays on the device (n bounds it)
-  hipLaunchKernelGGL(k_mark_last, grid1(n), dim3(256), 0, s, raw, (const uint32_t *)v0, n, flag);
+  hipLaunchKernelGGL(k_mark_last, grid1(n), dim3(256), 0, s, raw, (const uint32_t *)v0, n, flag,
+                     (const int32_t *)&dc->v[C_ERR]);
   INK_TRYS(compact_flags_u8(c->ws, flag, n, idx, n_ops_d, s));
   hipLaunchKernelGGL(k_take_ops, grid1(n), dim3(256), 0, s, raw, (const uint32_t *)v0, (const int32_t *)idx,
                      (const int32_t *)n_ops_d, b.node, b.other, b.op, b.pos);

@@ -87,6 +87,92 @@ __device__ __forceinline__ int wave_last_le(const int32_t *a, int n, int key) {
   return lo;
 }
 
+// ---------------------------------------------------------------- stable LSD radix sort, 8 bits a pass
+constexpr int kRadixBits = 8;
+constexpr int kRadix = 1 << kRadixBits;
+
+// One workgroup sorts up to THREADS * ITEMS (key, value) pairs that sit in LDS: per pass every
+// wave ranks its own slice digit by digit with ballots, the digit totals are scanned, and the
+// pairs are scattered in place (a thread holds its pairs in registers across the barrier).
+template <int THREADS, int ITEMS>
+struct SmallSortLds {
+  uint32_t sk[THREADS * ITEMS];
+  uint32_t sv[THREADS * ITEMS];
+  int cnt[THREADS / kWave][kRadix];
+  int wsum[kRadix / kWave];
+};
+
+// On entry sk / sv [0, n) are written (no barrier needed after the writes); on return they hold
+// the pairs in ascending key order, equal keys in their input order, and a barrier has passed.
+// `passes` 8-bit digits of the key are sorted, lowest first.
+template <int THREADS, int ITEMS>
+__device__ __forceinline__ void small_sort_lds(SmallSortLds<THREADS, ITEMS> &S, int n, int passes) {
+  constexpr int kWaves = THREADS / kWave;
+  constexpr int kDigitWaves = kRadix / kWave;    // the waves whose threads own one digit each
+  static_assert(THREADS >= kRadix, "one thread per digit");
+  const int w = threadIdx.x / kWave, l = lane_id();
+  const int per_wave = ITEMS * kWave;
+  for (int p = 0; p < passes; p++) {
+    int shift = p * kRadixBits;
+    for (int i = threadIdx.x; i < kWaves * kRadix; i += THREADS) (&S.cnt[0][0])[i] = 0;
+    __syncthreads();
+    uint32_t key[ITEMS], val[ITEMS];
+    int rank[ITEMS];
+#pragma unroll
+    for (int k = 0; k < ITEMS; k++) {
+      int i = w * per_wave + k * kWave + l;
+      bool ok = i < n;
+      key[k] = ok ? S.sk[i] : 0xFFFFFFFFu;
+      val[k] = ok ? S.sv[i] : 0;
+      int dg = ok ? (int)((key[k] >> shift) & (kRadix - 1)) : kRadix;
+      uint64_t same = __ballot(ok);
+#pragma unroll
+      for (int b = 0; b < kRadixBits; b++) {
+        uint64_t m = __ballot((dg >> b) & 1);
+        same &= ((dg >> b) & 1) ? m : ~m;
+      }
+      uint64_t lt = (l == 0) ? 0ull : (~0ull >> (kWave - l));
+      int before = __popcll(same & lt);
+      int prev = 0;
+      if (ok) prev = S.cnt[w][dg];
+      rank[k] = prev + before;
+      bool leader = ok && ((same >> l) >> 1) == 0;
+      if (leader) S.cnt[w][dg] = prev + before + 1;
+    }
+    __syncthreads();
+    // digit totals -> exclusive prefix over digits (thread t < kRadix = digit t), then per-wave bases
+    const bool digit_thread = threadIdx.x < kRadix;
+    int tot = 0, incl = 0;
+    if (digit_thread) {
+#pragma unroll
+      for (int i = 0; i < kWaves; i++) tot += S.cnt[i][threadIdx.x];
+      incl = wave_incl_scan(tot);
+      if (l == kWave - 1) S.wsum[w] = incl;
+    }
+    __syncthreads();
+    if (digit_thread) {
+      int base = 0;
+#pragma unroll
+      for (int i = 0; i < kDigitWaves; i++) if (i < w) base += S.wsum[i];
+      int run = base + incl - tot;
+#pragma unroll
+      for (int i = 0; i < kWaves; i++) { int c = S.cnt[i][threadIdx.x]; S.cnt[i][threadIdx.x] = run; run += c; }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < ITEMS; k++) {
+      int i = w * per_wave + k * kWave + l;
+      if (i < n) {
+        int dg = (key[k] >> shift) & (kRadix - 1);
+        int pos = S.cnt[w][dg] + rank[k];
+        S.sk[pos] = key[k];
+        S.sv[pos] = val[k];
+      }
+    }
+    __syncthreads();
+  }
+}
+
 #define INK_TRY(x) do { hipError_t e_ = (x); if (e_ != hipSuccess) return e_; } while (0)
 
 inline int nblocks(int64_t n, int per) { return (int)((n + per - 1) / per); }

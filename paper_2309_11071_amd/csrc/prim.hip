@@ -71,8 +71,6 @@ hipError_t segment_heads(PrimWorkspace &ws, const uint32_t *keys, int64_t n, int
 }
 
 // ---------------------------------------------------------------- stable LSD radix sort
-constexpr int kRadixBits = 8;
-constexpr int kRadix = 1 << kRadixBits;
 constexpr int kSortThreads = 256;
 constexpr int kSortWaves = kSortThreads / kWave;
 constexpr int kSortItems = 8;                                 // keys per thread
@@ -164,77 +162,10 @@ constexpr int kSmallSort = kWideThreads * kSmallItems;     // 16384 pairs
 
 template <int THREADS, int ITEMS>
 __global__ __launch_bounds__(THREADS) void k_small_sort(uint32_t *keys, uint32_t *vals, int n, int passes) {
-  constexpr int kCap = THREADS * ITEMS;
-  constexpr int kWaves = THREADS / kWave;
-  constexpr int kDigitWaves = kRadix / kWave;    // the waves whose threads own one digit each
-  static_assert(THREADS >= kRadix, "one thread per digit");
-  __shared__ uint32_t sk[kCap];
-  __shared__ uint32_t sv[kCap];
-  __shared__ int cnt[kWaves][kRadix];
-  __shared__ int wsum[kDigitWaves];
-  const int w = threadIdx.x / kWave, l = lane_id();
-  for (int i = threadIdx.x; i < n; i += THREADS) { sk[i] = keys[i]; sv[i] = vals[i]; }
-  const int per_wave = ITEMS * kWave;
-  for (int p = 0; p < passes; p++) {
-    int shift = p * kRadixBits;
-    for (int i = threadIdx.x; i < kWaves * kRadix; i += THREADS) (&cnt[0][0])[i] = 0;
-    __syncthreads();
-    uint32_t key[ITEMS], val[ITEMS];
-    int rank[ITEMS];
-#pragma unroll
-    for (int k = 0; k < ITEMS; k++) {
-      int i = w * per_wave + k * kWave + l;
-      bool ok = i < n;
-      key[k] = ok ? sk[i] : 0xFFFFFFFFu;
-      val[k] = ok ? sv[i] : 0;
-      int dg = ok ? (int)((key[k] >> shift) & (kRadix - 1)) : kRadix;
-      uint64_t same = __ballot(ok);
-#pragma unroll
-      for (int b = 0; b < kRadixBits; b++) {
-        uint64_t m = __ballot((dg >> b) & 1);
-        same &= ((dg >> b) & 1) ? m : ~m;
-      }
-      uint64_t lt = (l == 0) ? 0ull : (~0ull >> (kWave - l));
-      int before = __popcll(same & lt);
-      int prev = 0;
-      if (ok) prev = cnt[w][dg];
-      rank[k] = prev + before;
-      bool leader = ok && ((same >> l) >> 1) == 0;
-      if (leader) cnt[w][dg] = prev + before + 1;
-    }
-    __syncthreads();
-    // digit totals -> exclusive prefix over digits (thread t < kRadix = digit t), then per-wave bases
-    const bool digit_thread = threadIdx.x < kRadix;
-    int tot = 0, incl = 0;
-    if (digit_thread) {
-#pragma unroll
-      for (int i = 0; i < kWaves; i++) tot += cnt[i][threadIdx.x];
-      incl = wave_incl_scan(tot);
-      if (l == kWave - 1) wsum[w] = incl;
-    }
-    __syncthreads();
-    if (digit_thread) {
-      int base = 0;
-#pragma unroll
-      for (int i = 0; i < kDigitWaves; i++) if (i < w) base += wsum[i];
-      int run = base + incl - tot;
-#pragma unroll
-      for (int i = 0; i < kWaves; i++) { int c = cnt[i][threadIdx.x]; cnt[i][threadIdx.x] = run; run += c; }
-    }
-    __syncthreads();
-#pragma unroll
-    for (int k = 0; k < ITEMS; k++) {
-      int i = w * per_wave + k * kWave + l;
-      if (i < n) {
-        int dg = (key[k] >> shift) & (kRadix - 1);
-        int pos = cnt[w][dg] + rank[k];
-        sk[pos] = key[k];
-        sv[pos] = val[k];
-      }
-    }
-    __syncthreads();
-  }
-  for (int i = threadIdx.x; i < n; i += THREADS) { keys[i] = sk[i]; vals[i] = sv[i]; }
+  __shared__ SmallSortLds<THREADS, ITEMS> S;
+  for (int i = threadIdx.x; i < n; i += THREADS) { S.sk[i] = keys[i]; S.sv[i] = vals[i]; }
+  small_sort_lds<THREADS, ITEMS>(S, n, passes);
+  for (int i = threadIdx.x; i < n; i += THREADS) { keys[i] = S.sk[i]; vals[i] = S.sv[i]; }
 }
 
 hipError_t radix_sort_pairs(PrimWorkspace &ws, uint32_t *keys, uint32_t *vals, int64_t n, int bits,

@@ -30,7 +30,8 @@ def messy_batch(rng, n, keys, size):
     d[loops] = s[loops]
     # repeat a prefix so that the same edges appear several times with different ops
     k = size // 4
-    s[-k:], d[-k:] = s[:k], d[:k]
+    if k:
+        s[-k:], d[-k:] = s[:k], d[:k]
     return op, s, d
 
 

@@ -34,7 +34,7 @@ class Harness:
     """Keeps the oracle's view (edge-key set, full inference) next to an Ink context."""
 
     def __init__(self, cfg=None, model=None, precision="f32", slack=0.25, profile=False, graph=None, X=None,
-                 dense_threshold=0.0, pool_reserve=0, node_capacity=0):
+                 dense_threshold=0.0, pool_reserve=0, node_capacity=0, small_batch_limit=0):
         """Either a workload config, or an explicit graph=(n, src, dst) with features X and a model."""
         from paper_2309_11071_amd import Ink
         self.cfg = cfg
@@ -52,7 +52,8 @@ class Harness:
         self.keys = np.unique(synth.edge_keys(self.src, self.dst))
         rp, col = oracle.csr_from_keys(self.n, self.keys)
         self.ink = Ink(rp, col, self.X, self.model, slack_factor=slack, profile=profile,
-                       dense_threshold=dense_threshold, pool_reserve=pool_reserve, node_capacity=node_capacity)
+                       dense_threshold=dense_threshold, pool_reserve=pool_reserve, node_capacity=node_capacity,
+                       small_batch_limit=small_batch_limit)
         self.ink.full_infer()
         self.ref = oracle.full_infer(rp, col, self.X, self.model, precision)
         self.sampler = synth.BatchSampler(cfg, self.src, self.dst) if cfg is not None else None
