@@ -78,26 +78,33 @@ __global__ void k_gather_i32(const int32_t *table, const int32_t *idx, int n, co
   if (i < n) out[i] = table[idx[i]];
 }
 
-__global__ void k_gather_rows(const float *table, int ld, int d, const int32_t *rows, int64_t n, float *out) {
+__global__ void k_gather_rows(const float *table, int ld, int d, const int32_t *rows, int64_t n, const int32_t *n_dev,
+                              float *out) {
   int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (n_dev) n = *n_dev;
   int64_t r = t / d;
   int k = (int)(t % d);
   if (r < n) out[r * d + k] = table[(int64_t)rows[r] * ld + k];
 }
 
 // the same, 16 bytes per thread, for d a multiple of 4
-__global__ void k_gather_rows4(const float *table, int ld, int d4, const int32_t *rows, int64_t n, float *out) {
+__global__ void k_gather_rows4(const float *table, int ld, int d4, const int32_t *rows, int64_t n, const int32_t *n_dev,
+                               float *out) {
   int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (n_dev) n = *n_dev;
   int64_t r = t / d4;
   int k = (int)(t - r * d4);
   if (r < n)
     reinterpret_cast<float4 *>(out)[r * d4 + k] = *reinterpret_cast<const float4 *>(table + (int64_t)rows[r] * ld + 4 * k);
 }
 
-static void gather_rows(hipStream_t s, const float *table, int ld, int d, const int32_t *rows, int64_t n, float *out) {
+// n bounds the row count (and sizes the launch); with n_dev the exact count is read on the device
+static void gather_rows(hipStream_t s, const float *table, int ld, int d, const int32_t *rows, int64_t n, float *out,
+                        const int32_t *n_dev = nullptr) {
   if (n <= 0) return;
-  if (d % 4 == 0) hipLaunchKernelGGL(k_gather_rows4, grid1(n * (d / 4)), dim3(256), 0, s, table, ld, d / 4, rows, n, out);
-  else hipLaunchKernelGGL(k_gather_rows, grid1(n * d), dim3(256), 0, s, table, ld, d, rows, n, out);
+  if (d % 4 == 0)
+    hipLaunchKernelGGL(k_gather_rows4, grid1(n * (d / 4)), dim3(256), 0, s, table, ld, d / 4, rows, n, n_dev, out);
+  else hipLaunchKernelGGL(k_gather_rows, grid1(n * d), dim3(256), 0, s, table, ld, d, rows, n, n_dev, out);
 }
 
 __global__ void k_pack_rows(const void *table, int ld, int d, int64_t row0, int64_t nrows, void *out) {
@@ -747,8 +754,13 @@ static ink_status collect_rows(ink_ctx *c, const int32_t *extra0, int64_t n0, co
 // rows of c_list whose flag is set -> f_list[nxt] (ids) and, for sum-type, f_old[nxt] (old rows
 // taken from c_old with row stride ld).  With want_events the events those rows will propagate in
 // the next layer are counted in the same round trip (prefix of kept out-degrees in f_pref).
+// With `result` (the last layer's output table) and a modest nC, the new rows of the changed nodes
+// are gathered into res_emb and the batch's marks are cleared before that round trip, so nothing
+// is left to launch after it; *result_done says whether that happened.
+constexpr size_t kEagerResultBytes = (size_t)64 << 20;
 static ink_status emit_changed(ink_ctx *c, int64_t nC, int nxt, bool keep_old, int ld, bool want_events,
-                               int64_t *nF2, int64_t *n_chg) {
+                               int64_t *nF2, int64_t *n_chg, const Table *result = nullptr,
+                               bool *result_done = nullptr) {
   hipStream_t s = c->stream;
   Prof p(c, INK_T_COMPACT);
   Counters *dc = c->d_cnt;
@@ -768,6 +780,13 @@ static ink_status emit_changed(ink_ctx *c, int64_t nC, int nxt, bool keep_old, i
     API_TRY(c->f_pref.reserve((size_t)(nC + 1) * 4));
     API_TRY(tile_scan(c->ws, KeptOutDeg{c->f_list[nxt].as<int32_t>(), c->gout.deg, c->new_out, &dc->v[C_NEXT]},
                       StorePref{c->f_pref.as<int32_t>()}, nC, &dc->v[C_NEV], s));
+  }
+  if (result && (size_t)nC * result->d * 4 <= kEagerResultBytes) {
+    API_TRY(c->res_emb.reserve((size_t)nC * result->d * 4));
+    gather_rows(s, (const float *)result->f(), result->ld, result->d, (const int32_t *)c->f_list[nxt].as<int32_t>(), nC,
+                c->res_emb.as<float>(), &dc->v[C_NEXT]);
+    API_TRY(graph_end_batch(c));
+    *result_done = true;
   }
   API_TRY(hipGetLastError());
   API_TRY(read_counters(c));
@@ -804,6 +823,7 @@ static ink_status propagate_layers(ink_ctx *c, int64_t nF, int64_t n_chg, int cu
     if (!lazy) { S.n_transformed = nC; layer_stats_from_counters(c, l); }
     int nxt = cur ^ 1;
     int64_t nF2 = 0, n_chg2 = 0;
+    bool result_done = false;
     if (nC > 0) {
       const bool last = l == c->n_layers;
       int ld_next = gcn ? (last ? c->H[l].ld : c->Msc[l + 1].ld) : c->H[l].ld;
@@ -826,7 +846,7 @@ static ink_status propagate_layers(ink_ctx *c, int64_t nF, int64_t n_chg, int cu
         // the baseline propagates from every node of the affected area, changed or not
         if (c->affected_mode && !last) API_TRY(hipMemsetAsync(c->c_flag.p, 1, (size_t)nC, s));
       }
-      st = emit_changed(c, nC, nxt, want_old, ld_next, !last, &nF2, &n_chg2);
+      st = emit_changed(c, nC, nxt, want_old, ld_next, !last, &nF2, &n_chg2, last ? &c->H[l] : nullptr, &result_done);
       if (st != INK_OK) return st;
     } else if (lazy) {
       API_TRY(read_counters(c));
@@ -840,11 +860,11 @@ static ink_status propagate_layers(ink_ctx *c, int64_t nF, int64_t n_chg, int cu
       out->n_changed = nF;
       if (nF > 0) {
         int d = c->H[l].d;
-        API_TRY(c->res_ids.reserve((size_t)nF * 4));
-        API_TRY(c->res_emb.reserve((size_t)nF * d * 4));
-        API_TRY(hipMemcpyAsync(c->res_ids.p, c->f_list[cur].p, (size_t)nF * 4, hipMemcpyDeviceToDevice, s));
-        gather_rows(s, (const float *)c->H[l].f(), c->H[l].ld, d, (const int32_t *)c->res_ids.p, nF, c->res_emb.as<float>());
-        out->changed_ids = c->res_ids.as<int32_t>();
+        out->changed_ids = c->f_list[cur].as<int32_t>();    // stays untouched until the next call
+        if (!result_done) {
+          API_TRY(c->res_emb.reserve((size_t)nF * d * 4));
+          gather_rows(s, (const float *)c->H[l].f(), c->H[l].ld, d, out->changed_ids, nF, c->res_emb.as<float>());
+        }
         out->embeddings = c->res_emb.as<float>();
       }
     }

@@ -490,10 +490,7 @@ static ink_status apply_side(ink_ctx *c, GraphSide &g, SideBufs &b, int64_t n_op
 // op lists, their segment heads and the chunk plan of the blocks to walk happens in LDS.  Both
 // directions are classified before the host looks at the counters, so the batch costs one round
 // trip instead of two.  The lists these kernels write are the ones the general path writes.
-constexpr int kSmallThreads = 1024;
-constexpr int kSmallItems = 4;
-constexpr int kSmallBatch = kSmallThreads * kSmallItems;
-typedef SmallSortLds<kSmallThreads, kSmallItems> SmallLds;
+constexpr int kSmallBatch = 4096;      // largest batch of the single-workgroup form (1024 threads x 4)
 
 struct SmallSide {           // what one direction's kernels hand on (device pointers)
   uint32_t *node; int32_t *other; uint8_t *op; int32_t *pos; uint8_t *eff;
@@ -503,39 +500,40 @@ struct SmallSide {           // what one direction's kernels hand on (device poi
 // Ops [0, n_ops) are in (node, other) order with their node ids in S.sk.  Writes the distinct
 // nodes, the start of each node's ops (plus the closing offset) and the exclusive prefix of the
 // chunk counts of their blocks; *n_uniq_out / *n_chunks_out get the totals.  s_u is LDS scratch
-// for kSmallBatch ints, sm for the block scan.
-__device__ __forceinline__ void small_heads_and_chunks(SmallLds &S, int *s_u, int *sm, int n_ops, const int32_t *deg,
+// for THREADS * ITEMS ints, sm for the block scan.
+template <int THREADS, int ITEMS>
+__device__ __forceinline__ void small_heads_and_chunks(SmallSortLds<THREADS, ITEMS> &S, int *s_u, int *sm, int n_ops, const int32_t *deg,
                                                        int32_t *uniq, int32_t *seg, int32_t *chunk_pref,
                                                        int32_t *n_uniq_out, int32_t *n_chunks_out) {
-  const int t0 = threadIdx.x * kSmallItems;
-  int h[kSmallItems], cnt = 0;
+  const int t0 = threadIdx.x * ITEMS;
+  int h[ITEMS], cnt = 0;
 #pragma unroll
-  for (int k = 0; k < kSmallItems; k++) {
+  for (int k = 0; k < ITEMS; k++) {
     int i = t0 + k;
     h[k] = i < n_ops && (i == 0 || S.sk[i] != S.sk[i - 1]);
     cnt += h[k];
   }
   int n_uniq;
-  int ex = block_excl_scan<kSmallThreads>(cnt, sm, &n_uniq);
+  int ex = block_excl_scan<THREADS>(cnt, sm, &n_uniq);
 #pragma unroll
-  for (int k = 0; k < kSmallItems; k++) {
+  for (int k = 0; k < ITEMS; k++) {
     int i = t0 + k;
     if (h[k]) { uniq[ex] = (int32_t)S.sk[i]; seg[ex] = i; s_u[ex] = (int)S.sk[i]; ex++; }
   }
   if (threadIdx.x == 0) seg[n_uniq] = n_ops;
   __syncthreads();
-  int ch[kSmallItems];
+  int ch[ITEMS];
   cnt = 0;
 #pragma unroll
-  for (int k = 0; k < kSmallItems; k++) {
+  for (int k = 0; k < ITEMS; k++) {
     int i = t0 + k;
     ch[k] = i < n_uniq ? (deg[s_u[i]] + kChunk - 1) / kChunk : 0;
     cnt += ch[k];
   }
   int n_chunks;
-  ex = block_excl_scan<kSmallThreads>(cnt, sm, &n_chunks);
+  ex = block_excl_scan<THREADS>(cnt, sm, &n_chunks);
 #pragma unroll
-  for (int k = 0; k < kSmallItems; k++) {
+  for (int k = 0; k < ITEMS; k++) {
     int i = t0 + k;
     if (i < n_uniq) chunk_pref[i] = ex;
     ex += ch[k];
@@ -545,21 +543,22 @@ __device__ __forceinline__ void small_heads_and_chunks(SmallLds &S, int *s_u, in
 
 // In side: validate, order by (dst, src, position), keep the final op per edge, build the op
 // lists of the touched destinations.
-__global__ __launch_bounds__(kSmallThreads) void k_small_in(const RawUpdate *raw, int n, int n_nodes, int passes,
+template <int THREADS, int ITEMS>
+__global__ __launch_bounds__(THREADS) void k_small_in(const RawUpdate *raw, int n, int n_nodes, int passes,
                                                             SmallSide o, const int32_t *deg, Counters *cnt) {
-  __shared__ SmallLds S;
-  __shared__ int s_src[kSmallBatch], s_dst[kSmallBatch];
-  __shared__ uint8_t s_op[kSmallBatch];
-  __shared__ int sm[kSmallThreads / kWave + 1];
+  __shared__ SmallSortLds<THREADS, ITEMS> S;
+  __shared__ int s_src[THREADS * ITEMS], s_dst[THREADS * ITEMS];
+  __shared__ uint8_t s_op[THREADS * ITEMS];
+  __shared__ int sm[THREADS / kWave + 1];
   // the stripes and the slots that later kernels fill start from zero; the slots before them
   // are written below, the error flag is sticky
   {
     int32_t *z = &cnt->v[C_TMP2];
     const int words = (int)((sizeof(Counters) - C_TMP2 * sizeof(int32_t)) / sizeof(int32_t));
-    for (int i = threadIdx.x; i < words; i += kSmallThreads) z[i] = 0;
+    for (int i = threadIdx.x; i < words; i += THREADS) z[i] = 0;
   }
   int bad = 0;
-  for (int i = threadIdx.x; i < n; i += kSmallThreads) {
+  for (int i = threadIdx.x; i < n; i += THREADS) {
     RawUpdate a = raw[i];
     bad |= entry_error(a, n_nodes);
     s_src[i] = a.src; s_dst[i] = a.dst; s_op[i] = a.op;
@@ -571,14 +570,14 @@ __global__ __launch_bounds__(kSmallThreads) void k_small_in(const RawUpdate *raw
     if (threadIdx.x == 0) { cnt->v[C_NOPS] = 0; cnt->v[C_TMP0] = 0; cnt->v[C_TMP1] = 0; o.seg[0] = 0; }
     return;
   }
-  small_sort_lds<kSmallThreads, kSmallItems>(S, n, passes);
-  for (int i = threadIdx.x; i < n; i += kSmallThreads) S.sk[i] = (uint32_t)s_dst[S.sv[i]];
-  small_sort_lds<kSmallThreads, kSmallItems>(S, n, passes);
+  small_sort_lds<THREADS, ITEMS>(S, n, passes);
+  for (int i = threadIdx.x; i < n; i += THREADS) S.sk[i] = (uint32_t)s_dst[S.sv[i]];
+  small_sort_lds<THREADS, ITEMS>(S, n, passes);
   // the last entry of each run of equal (dst, src) is the edge's final op; self loops never count
-  const int t0 = threadIdx.x * kSmallItems;
-  int keep[kSmallItems], c = 0;
+  const int t0 = threadIdx.x * ITEMS;
+  int keep[ITEMS], c = 0;
 #pragma unroll
-  for (int k = 0; k < kSmallItems; k++) {
+  for (int k = 0; k < ITEMS; k++) {
     int j = t0 + k;
     keep[k] = 0;
     if (j < n) {
@@ -590,9 +589,9 @@ __global__ __launch_bounds__(kSmallThreads) void k_small_in(const RawUpdate *raw
     c += keep[k];
   }
   int n_ops;
-  int ex = block_excl_scan<kSmallThreads>(c, sm, &n_ops);
+  int ex = block_excl_scan<THREADS>(c, sm, &n_ops);
 #pragma unroll
-  for (int k = 0; k < kSmallItems; k++) {
+  for (int k = 0; k < ITEMS; k++) {
     if (keep[k]) {
       int a = (int)S.sv[t0 + k];
       o.node[ex] = (uint32_t)s_dst[a]; o.other[ex] = s_src[a]; o.op[ex] = s_op[a]; o.pos[ex] = -1;
@@ -602,33 +601,34 @@ __global__ __launch_bounds__(kSmallThreads) void k_small_in(const RawUpdate *raw
   }
   __syncthreads();
   if (threadIdx.x == 0) cnt->v[C_NOPS] = n_ops;
-  small_heads_and_chunks(S, s_src, sm, n_ops, deg, o.uniq, o.seg, o.chunk_pref, &cnt->v[C_TMP0], &cnt->v[C_TMP1]);
+  small_heads_and_chunks<THREADS, ITEMS>(S, s_src, sm, n_ops, deg, o.uniq, o.seg, o.chunk_pref, &cnt->v[C_TMP0], &cnt->v[C_TMP1]);
 }
 
 // Out side, after the in side's k_effect: the effective ops become Delta E (inserted and removed
 // edges, each in (dst, src) order) and, stably re-ordered by source, the op lists of the touched
 // sources.
-__global__ __launch_bounds__(kSmallThreads) void k_small_out(SmallSide in, int passes, int32_t *ins_s, int32_t *ins_d,
+template <int THREADS, int ITEMS>
+__global__ __launch_bounds__(THREADS) void k_small_out(SmallSide in, int passes, int32_t *ins_s, int32_t *ins_d,
                                                              int32_t *del_s, int32_t *del_d, SmallSide o,
                                                              const int32_t *deg, Counters *cnt) {
-  __shared__ SmallLds S;
-  __shared__ int s_u[kSmallBatch];
-  __shared__ int sm[kSmallThreads / kWave + 1];
+  __shared__ SmallSortLds<THREADS, ITEMS> S;
+  __shared__ int s_u[THREADS * ITEMS];
+  __shared__ int sm[THREADS / kWave + 1];
   const int n_ops = cnt->v[C_NOPS];
-  const int t0 = threadIdx.x * kSmallItems;
-  int e[kSmallItems], packed = 0;       // inserts in the low half, deletes in the high half
+  const int t0 = threadIdx.x * ITEMS;
+  int e[ITEMS], packed = 0;       // inserts in the low half, deletes in the high half
 #pragma unroll
-  for (int k = 0; k < kSmallItems; k++) {
+  for (int k = 0; k < ITEMS; k++) {
     int j = t0 + k;
     e[k] = j < n_ops ? in.eff[j] : 0;
     packed += (e[k] == 1) + ((e[k] == 2) << 16);
   }
   int tot;
-  int ex = block_excl_scan<kSmallThreads>(packed, sm, &tot);
+  int ex = block_excl_scan<THREADS>(packed, sm, &tot);
   int xi = ex & 0xFFFF, xd = ex >> 16;
   const int n_ins = tot & 0xFFFF, n_del = tot >> 16;
 #pragma unroll
-  for (int k = 0; k < kSmallItems; k++) {
+  for (int k = 0; k < ITEMS; k++) {
     int j = t0 + k;
     if (e[k] == 0) continue;
     int src = in.other[j], dst = (int)in.node[j];
@@ -637,13 +637,13 @@ __global__ __launch_bounds__(kSmallThreads) void k_small_out(SmallSide in, int p
     else { del_s[xd] = src; del_d[xd] = dst; xd++; }
   }
   const int m = n_ins + n_del;
-  small_sort_lds<kSmallThreads, kSmallItems>(S, m, passes);
-  for (int p = threadIdx.x; p < m; p += kSmallThreads) {
+  small_sort_lds<THREADS, ITEMS>(S, m, passes);
+  for (int p = threadIdx.x; p < m; p += THREADS) {
     int j = (int)S.sv[p];
     o.node[p] = S.sk[p]; o.other[p] = (int)in.node[j]; o.op[p] = in.eff[j] == 2 ? 1 : 0; o.pos[p] = -1;
   }
   if (threadIdx.x == 0) { cnt->v[C_TMP2] = n_ins; cnt->v[C_TMP3] = n_del; }
-  small_heads_and_chunks(S, s_u, sm, m, deg, o.uniq, o.seg, o.chunk_pref, &cnt->v[C_OT], &cnt->v[C_OCH]);
+  small_heads_and_chunks<THREADS, ITEMS>(S, s_u, sm, m, deg, o.uniq, o.seg, o.chunk_pref, &cnt->v[C_OT], &cnt->v[C_OCH]);
 }
 
 static ink_status graph_apply_small(ink_ctx *c, int64_t n, int64_t *n_ins_out, int64_t *n_del_out) {
@@ -674,12 +674,20 @@ static ink_status graph_apply_small(ink_ctx *c, int64_t n, int64_t *n_ins_out, i
   for (int k = 0; k < 2; k++) {
     SmallSide &b = sd[k];
     GraphSide &g = *gs[k];
-    if (k == 0)
-      hipLaunchKernelGGL(k_small_in, dim3(1), dim3(kSmallThreads), 0, s, c->b_raw.as<RawUpdate>(), (int)n, c->n, passes,
-                         b, (const int32_t *)g.deg, dc);
-    else
-      hipLaunchKernelGGL(k_small_out, dim3(1), dim3(kSmallThreads), 0, s, sd[0], passes, c->ins_src, c->ins_dst,
-                         c->del_src, c->del_dst, b, (const int32_t *)g.deg, dc);
+#define INK_SMALL_LAUNCH(T, I)                                                                                      \
+  do {                                                                                                             \
+    if (k == 0)                                                                                                    \
+      hipLaunchKernelGGL((k_small_in<T, I>), dim3(1), dim3(T), 0, s, c->b_raw.as<RawUpdate>(), (int)n, c->n,       \
+                         passes, b, (const int32_t *)g.deg, dc);                                                   \
+    else                                                                                                           \
+      hipLaunchKernelGGL((k_small_out<T, I>), dim3(1), dim3(T), 0, s, sd[0], passes, c->ins_src, c->ins_dst,       \
+                         c->del_src, c->del_dst, b, (const int32_t *)g.deg, dc);                                   \
+  } while (0)
+    // fewer waves make every barrier of the sort cheaper
+    if (n <= 256) INK_SMALL_LAUNCH(256, 1);
+    else if (n <= 1024) INK_SMALL_LAUNCH(256, 4);
+    else INK_SMALL_LAUNCH(1024, 4);
+#undef INK_SMALL_LAUNCH
     hipLaunchKernelGGL(k_classify, dim3(256), dim3(256), 0, s, (const int32_t *)b.uniq,
                        (const int32_t *)&dc->v[slot_n[k]], (const int32_t *)b.seg, (const int32_t *)b.chunk_pref,
                        (const int32_t *)&dc->v[slot_ch[k]], (const int64_t *)g.off, (const int32_t *)g.deg, g.ids,
