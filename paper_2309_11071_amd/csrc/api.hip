@@ -27,14 +27,20 @@ static inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
 static inline dim3 grid1(int64_t n, int per = 256) { return dim3((unsigned)std::max<int64_t>(1, (n + per - 1) / per)); }
 
 // ------------------------------------------------------------------------------------ kernels
+// event i of the applied edge changes: deletions first, then insertions; key = target
+__device__ __forceinline__ void seed_event(int i, const int32_t *del_s, const int32_t *del_d, const int32_t *ins_s,
+                                           const int32_t *ins_d, int n_del, uint32_t *key, uint32_t *val) {
+  if (i < n_del) { *key = (uint32_t)del_d[i]; *val = (EV_DEL << kEvKindShift) | (uint32_t)del_s[i]; }
+  else {
+    int j = i - n_del;
+    *key = (uint32_t)ins_d[j]; *val = (EV_ADD << kEvKindShift) | (uint32_t)ins_s[j];
+  }
+}
+
 __global__ void k_seed_events(const int32_t *del_s, const int32_t *del_d, const int32_t *ins_s, const int32_t *ins_d,
                               int n_del, int n_ins, uint32_t *key, uint32_t *val) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n_del) { key[i] = (uint32_t)del_d[i]; val[i] = (EV_DEL << kEvKindShift) | (uint32_t)del_s[i]; }
-  else if (i < n_del + n_ins) {
-    int j = (int)i - n_del;
-    key[i] = (uint32_t)ins_d[j]; val[i] = (EV_ADD << kEvKindShift) | (uint32_t)ins_s[j];
-  }
+  if (i < n_del + n_ins) seed_event((int)i, del_s, del_d, ins_s, ins_d, n_del, &key[i], &val[i]);
 }
 
 // out-edges of a changed source that exist in both snapshots: the block minus the ids appended
@@ -50,21 +56,112 @@ struct KeptOutDeg {
 };
 struct StorePref { int32_t *p; __device__ void operator()(int64_t i, int, int ex) const { p[i] = ex; } };
 
-// one thread per propagated event: source = the changed node owning event e, target = its e-th
-// kept out-neighbour.  payload_index: store the position in F instead of the node id.
-__global__ void k_expand_events(const int32_t *F, int nF, const int32_t *pref, int n_ev, const int64_t *off,
-                                const int32_t *ids, uint32_t *key, uint32_t *val, int payload_index) {
-  int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (e >= n_ev) return;
+// propagated event e: source = the changed node owning it, target = its e-th kept out-neighbour.
+// payload_index: store the position in F instead of the node id.
+__device__ __forceinline__ void expand_event(int e, const int32_t *F, int nF, const int32_t *pref, const int64_t *off,
+                                             const int32_t *ids, int payload_index, uint32_t *key, uint32_t *val) {
   int lo = 0, hi = nF - 1;
   while (lo < hi) {
     int mid = (lo + hi + 1) >> 1;
     if (pref[mid] <= e) lo = mid; else hi = mid - 1;
   }
   int u = F[lo];
-  int p = (int)e - pref[lo];
-  key[e] = (uint32_t)ids[off[u] + p];
-  val[e] = (EV_CHG << kEvKindShift) | (uint32_t)(payload_index ? lo : u);
+  int p = e - pref[lo];
+  *key = (uint32_t)ids[off[u] + p];
+  *val = (EV_CHG << kEvKindShift) | (uint32_t)(payload_index ? lo : u);
+}
+
+__global__ void k_expand_events(const int32_t *F, int nF, const int32_t *pref, int n_ev, const int64_t *off,
+                                const int32_t *ids, uint32_t *key, uint32_t *val, int payload_index) {
+  int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e < n_ev) expand_event((int)e, F, nF, pref, off, ids, payload_index, &key[e], &val[e]);
+}
+
+// A layer with few events (at most THREADS * ITEMS): clearing the counters, creating the events,
+// grouping them by target (stable, so deletions stay ahead of insertions ahead of changes) and
+// the segment heads in one workgroup.  Output as from the separate kernels: val in grouped
+// order, the distinct targets, the start of each target's events plus the closing offset, and
+// the target count in the counter block.
+template <int THREADS, int ITEMS>
+__global__ __launch_bounds__(THREADS) void k_small_group(const int32_t *del_s, const int32_t *del_d, const int32_t *ins_s,
+                                                         const int32_t *ins_d, int n_del, int n_ins, const int32_t *F,
+                                                         int nF, const int32_t *pref, int n_chg, const int64_t *off,
+                                                         const int32_t *ids, int payload_index, int passes,
+                                                         uint32_t *key_out, uint32_t *val_out, int32_t *t_list,
+                                                         int32_t *t_seg, Counters *cnt) {
+  __shared__ SmallSortLds<THREADS, ITEMS> S;
+  __shared__ int sm[THREADS / kWave + 1];
+  {
+    int32_t *z = (int32_t *)cnt;
+    for (int i = threadIdx.x; i < (int)(sizeof(Counters) / sizeof(int32_t)); i += THREADS)
+      if (i != C_NT) z[i] = 0;
+  }
+  const int n_seed = n_del + n_ins, nE = n_seed + n_chg;
+  for (int e = threadIdx.x; e < nE; e += THREADS) {
+    uint32_t k, v;
+    if (e < n_seed) seed_event(e, del_s, del_d, ins_s, ins_d, n_del, &k, &v);
+    else expand_event(e - n_seed, F, nF, pref, off, ids, payload_index, &k, &v);
+    S.sk[e] = k; S.sv[e] = v;
+  }
+  small_sort_lds<THREADS, ITEMS>(S, nE, passes);
+  const int t0 = threadIdx.x * ITEMS;
+  int h[ITEMS], c = 0;
+#pragma unroll
+  for (int k = 0; k < ITEMS; k++) {
+    int i = t0 + k;
+    h[k] = i < nE && (i == 0 || S.sk[i] != S.sk[i - 1]);
+    c += h[k];
+    if (i < nE) { key_out[i] = S.sk[i]; val_out[i] = S.sv[i]; }
+  }
+  int nT;
+  int ex = block_excl_scan<THREADS>(c, sm, &nT);
+#pragma unroll
+  for (int k = 0; k < ITEMS; k++)
+    if (h[k]) { t_list[ex] = (int32_t)S.sk[t0 + k]; t_seg[ex] = t0 + k; ex++; }
+  if (threadIdx.x == 0) { t_seg[nT] = nE; cnt->v[C_NT] = nT; }
+}
+
+// The emission of a layer with few transformed rows (at most THREADS * ITEMS) in one workgroup:
+// rows whose flag is set -> their positions (idx) and ids (f_list), the count, and, with
+// want_events, the exclusive prefix of their kept out-degrees and its total.
+template <int THREADS, int ITEMS>
+__global__ __launch_bounds__(THREADS) void k_small_emit(const uint8_t *flag, const int32_t *rows, int nC, int32_t *idx,
+                                                        int32_t *f_list, int want_events, const int32_t *deg,
+                                                        const int32_t *new_out, int32_t *f_pref, Counters *cnt) {
+  __shared__ int s_f[THREADS * ITEMS];
+  __shared__ int sm[THREADS / kWave + 1];
+  const int t0 = threadIdx.x * ITEMS;
+  int f[ITEMS], c = 0;
+#pragma unroll
+  for (int k = 0; k < ITEMS; k++) {
+    int i = t0 + k;
+    f[k] = i < nC && flag[i] != 0;
+    c += f[k];
+  }
+  int nF;
+  int ex = block_excl_scan<THREADS>(c, sm, &nF);
+#pragma unroll
+  for (int k = 0; k < ITEMS; k++)
+    if (f[k]) { int u = rows[t0 + k]; idx[ex] = t0 + k; f_list[ex] = u; s_f[ex] = u; ex++; }
+  if (threadIdx.x == 0) cnt->v[C_NEXT] = nF;
+  if (!want_events) return;
+  __syncthreads();
+  int kd[ITEMS];
+  c = 0;
+#pragma unroll
+  for (int k = 0; k < ITEMS; k++) {
+    int i = t0 + k;
+    kd[k] = i < nF ? deg[s_f[i]] - new_out[s_f[i]] : 0;
+    c += kd[k];
+  }
+  int n_ev;
+  ex = block_excl_scan<THREADS>(c, sm, &n_ev);
+#pragma unroll
+  for (int k = 0; k < ITEMS; k++) {
+    if (t0 + k < nC) f_pref[t0 + k] = ex;
+    ex += kd[k];
+  }
+  if (threadIdx.x == 0) cnt->v[C_NEV] = n_ev;
 }
 
 __global__ void k_mark_nodes(const int32_t *list, int n, uint64_t *bm) {
@@ -628,6 +725,7 @@ extern "C" ink_status ink_full_infer(ink_ctx *c) {
 // changed and n_chg the events they propagate (their kept out-edges, prefix already in f_pref);
 // f_old holds their previous message rows (sum-type only).  Marks targets whose aggregate changed
 // in c->bm_a.  Counters are read back by the caller's next synchronisation.
+constexpr int64_t kSmallLayer = 4096;           // events / rows up to which a layer's bookkeeping runs in one workgroup
 constexpr int64_t kNoSyncEvents = 1 << 18;     // below this the target count stays on the device
 
 static ink_status layer_aggregate(ink_ctx *c, int l, const int32_t *F, int64_t nF, int64_t n_chg, const float *f_old,
@@ -641,9 +739,10 @@ static ink_status layer_aggregate(ink_ctx *c, int l, const int32_t *F, int64_t n
   int64_t nE = n_seed + n_chg;
   S.n_events = nE;
   uint64_t *bm = c->bm_a;
-  API_TRY(hipMemsetAsync(dc, 0, sizeof(Counters), s));
   bool dense = nE > 0 && (double)nE > c->dense_frac * (double)std::max<int64_t>(c->n_edges_now, 1);
   S.dense = dense;
+  const bool small = !dense && nE > 0 && nE <= kSmallLayer;
+  if (!small) API_TRY(hipMemsetAsync(dc, 0, sizeof(Counters), s));
   if (dense) {
     // so many events that re-aggregating every node costs less than grouping them (Sec. 5.1)
     Prof p(c, INK_T_AGG);
@@ -651,29 +750,43 @@ static ink_status layer_aggregate(ink_ctx *c, int l, const int32_t *F, int64_t n
     return INK_OK;
   }
   if (nE == 0) return INK_OK;
-  {
-    Prof p(c, INK_T_EVENTS);
-    API_TRY(c->ev_key.reserve((size_t)nE * 4));
-    API_TRY(c->ev_val.reserve((size_t)nE * 4));
-    uint32_t *key = c->ev_key.as<uint32_t>(), *val = c->ev_val.as<uint32_t>();
-    if (n_seed > 0)
-      hipLaunchKernelGGL(k_seed_events, grid1(n_seed), dim3(256), 0, s, (const int32_t *)c->del_src,
-                         (const int32_t *)c->del_dst, (const int32_t *)c->ins_src, (const int32_t *)c->ins_dst,
-                         (int)n_del, (int)n_ins, key, val);
-    if (n_chg > 0)
-      hipLaunchKernelGGL(k_expand_events, grid1(n_chg), dim3(256), 0, s, F, (int)nF,
-                         (const int32_t *)c->f_pref.as<int32_t>(), (int)n_chg, (const int64_t *)c->gout.off,
-                         (const int32_t *)c->gout.ids, key + n_seed, val + n_seed, c->is_select ? 0 : 1);
-    API_TRY(hipGetLastError());
-  }
+  API_TRY(c->ev_key.reserve((size_t)nE * 4));
+  API_TRY(c->ev_val.reserve((size_t)nE * 4));
+  API_TRY(c->t_list.reserve((size_t)(nE + 1) * 4));
+  API_TRY(c->t_seg.reserve((size_t)(nE + 2) * 4));
+  uint32_t *key = c->ev_key.as<uint32_t>(), *val = c->ev_val.as<uint32_t>();
   int64_t nT = std::min<int64_t>(nE, c->n);       // upper bound unless read back below
-  {
+  if (small) {
+    // few events: counters, events, grouping and segment heads in one launch
     Prof p(c, INK_T_GROUP);
-    API_TRY(radix_sort_pairs(c->ws, c->ev_key.as<uint32_t>(), c->ev_val.as<uint32_t>(), nE, c->id_bits, s));
-    API_TRY(c->t_list.reserve((size_t)(nE + 1) * 4));
-    API_TRY(c->t_seg.reserve((size_t)(nE + 2) * 4));
-    API_TRY(segment_heads(c->ws, c->ev_key.as<uint32_t>(), nE, c->t_list.as<int32_t>(), c->t_seg.as<int32_t>(),
-                          &dc->v[C_NT], s));
+    const int passes = (c->id_bits + kRadixBits - 1) / kRadixBits;
+#define INK_SMALL_GROUP(T, I)                                                                                      \
+  hipLaunchKernelGGL((k_small_group<T, I>), dim3(1), dim3(T), 0, s, (const int32_t *)c->del_src,                    \
+                     (const int32_t *)c->del_dst, (const int32_t *)c->ins_src, (const int32_t *)c->ins_dst,        \
+                     (int)n_del, (int)n_ins, F, (int)nF, (const int32_t *)c->f_pref.as<int32_t>(), (int)n_chg,     \
+                     (const int64_t *)c->gout.off, (const int32_t *)c->gout.ids, c->is_select ? 0 : 1, passes, key, \
+                     val, c->t_list.as<int32_t>(), c->t_seg.as<int32_t>(), dc)
+    if (nE <= 256) INK_SMALL_GROUP(256, 1);
+    else if (nE <= 1024) INK_SMALL_GROUP(256, 4);
+    else INK_SMALL_GROUP(1024, 4);
+#undef INK_SMALL_GROUP
+    API_TRY(hipGetLastError());
+  } else {
+    {
+      Prof p(c, INK_T_EVENTS);
+      if (n_seed > 0)
+        hipLaunchKernelGGL(k_seed_events, grid1(n_seed), dim3(256), 0, s, (const int32_t *)c->del_src,
+                           (const int32_t *)c->del_dst, (const int32_t *)c->ins_src, (const int32_t *)c->ins_dst,
+                           (int)n_del, (int)n_ins, key, val);
+      if (n_chg > 0)
+        hipLaunchKernelGGL(k_expand_events, grid1(n_chg), dim3(256), 0, s, F, (int)nF,
+                           (const int32_t *)c->f_pref.as<int32_t>(), (int)n_chg, (const int64_t *)c->gout.off,
+                           (const int32_t *)c->gout.ids, key + n_seed, val + n_seed, c->is_select ? 0 : 1);
+      API_TRY(hipGetLastError());
+    }
+    Prof p(c, INK_T_GROUP);
+    API_TRY(radix_sort_pairs(c->ws, key, val, nE, c->id_bits, s));
+    API_TRY(segment_heads(c->ws, key, nE, c->t_list.as<int32_t>(), c->t_seg.as<int32_t>(), &dc->v[C_NT], s));
     if (nE > kNoSyncEvents) {
       API_TRY(read_counters(c));
       nT = c->h_cnt->v[C_NT];
@@ -765,18 +878,32 @@ static ink_status emit_changed(ink_ctx *c, int64_t nC, int nxt, bool keep_old, i
   Prof p(c, INK_T_COMPACT);
   Counters *dc = c->d_cnt;
   *nF2 = 0; *n_chg = 0;
-  API_TRY(compact_flags_u8(c->ws, c->c_flag.as<uint8_t>(), nC, c->c_idx.as<int32_t>(), &dc->v[C_NEXT], s));
   API_TRY(c->f_list[nxt].reserve((size_t)nC * 4));
-  hipLaunchKernelGGL(k_gather_i32, grid1(nC), dim3(256), 0, s, (const int32_t *)c->c_list.as<int32_t>(),
-                     (const int32_t *)c->c_idx.as<int32_t>(), 0, (const int32_t *)&dc->v[C_NEXT],
-                     c->f_list[nxt].as<int32_t>());
+  const bool small = nC <= kSmallLayer;
+  if (small) {
+    if (want_events) API_TRY(c->f_pref.reserve((size_t)(nC + 1) * 4));
+#define INK_SMALL_EMIT(T, I)                                                                                       \
+  hipLaunchKernelGGL((k_small_emit<T, I>), dim3(1), dim3(T), 0, s, (const uint8_t *)c->c_flag.as<uint8_t>(),        \
+                     (const int32_t *)c->c_list.as<int32_t>(), (int)nC, c->c_idx.as<int32_t>(),                    \
+                     c->f_list[nxt].as<int32_t>(), want_events ? 1 : 0, (const int32_t *)c->gout.deg,              \
+                     (const int32_t *)c->new_out, c->f_pref.as<int32_t>(), dc)
+    if (nC <= 256) INK_SMALL_EMIT(256, 1);
+    else if (nC <= 1024) INK_SMALL_EMIT(256, 4);
+    else INK_SMALL_EMIT(1024, 4);
+#undef INK_SMALL_EMIT
+  } else {
+    API_TRY(compact_flags_u8(c->ws, c->c_flag.as<uint8_t>(), nC, c->c_idx.as<int32_t>(), &dc->v[C_NEXT], s));
+    hipLaunchKernelGGL(k_gather_i32, grid1(nC), dim3(256), 0, s, (const int32_t *)c->c_list.as<int32_t>(),
+                       (const int32_t *)c->c_idx.as<int32_t>(), 0, (const int32_t *)&dc->v[C_NEXT],
+                       c->f_list[nxt].as<int32_t>());
+  }
   if (keep_old) {
     API_TRY(c->f_old[nxt].reserve((size_t)nC * ld * 4));
     hipLaunchKernelGGL(k_gather_rows_ld, grid1(nC * (ld / 4)), dim3(256), 0, s, (const float *)c->c_old.as<float>(), ld,
                        (const int32_t *)c->c_idx.as<int32_t>(), (int64_t)0, (const int32_t *)&dc->v[C_NEXT],
                        c->f_old[nxt].as<float>());
   }
-  if (want_events) {
+  if (want_events && !small) {
     API_TRY(c->f_pref.reserve((size_t)(nC + 1) * 4));
     API_TRY(tile_scan(c->ws, KeptOutDeg{c->f_list[nxt].as<int32_t>(), c->gout.deg, c->new_out, &dc->v[C_NEXT]},
                       StorePref{c->f_pref.as<int32_t>()}, nC, &dc->v[C_NEV], s));
