@@ -121,6 +121,59 @@ __global__ __launch_bounds__(THREADS) void k_small_group(const int32_t *del_s, c
   if (threadIdx.x == 0) { t_seg[nT] = nE; cnt->v[C_NT] = nT; }
 }
 
+// The rows a layer with few events has to transform, in one workgroup: the targets whose bit the
+// aggregation set in the bitmap (the bits are cleared on the way), the sources F (self term) and
+// the nodes D whose in-degree changed, sorted and made unique -> rows[], their number -> C_NC.
+// Also clears the first n_flags bytes of flag (the transform sets the flags of changed rows).
+// n_t_bound + nF + nD is at most THREADS * ITEMS.
+template <int THREADS, int ITEMS>
+__global__ __launch_bounds__(THREADS) void k_small_collect(const int32_t *t_list, const int32_t *n_t_dev, int n_t_bound,
+                                                           unsigned long long *bm, const int32_t *F, int nF,
+                                                           const int32_t *D, int nD, int passes, int32_t *rows,
+                                                           uint8_t *flag, int n_flags, Counters *cnt) {
+  __shared__ SmallSortLds<THREADS, ITEMS> S;
+  __shared__ int sm[THREADS / kWave + 1];
+  for (int i = threadIdx.x; i < n_flags; i += THREADS) flag[i] = 0;
+  const int nT = n_t_bound > 0 ? min(*n_t_dev, n_t_bound) : 0;
+  const int M = n_t_bound + nF + nD;
+  const int t0 = threadIdx.x * ITEMS;
+  int id[ITEMS], c = 0;
+#pragma unroll
+  for (int k = 0; k < ITEMS; k++) {
+    int i = t0 + k;
+    id[k] = -1;
+    if (i < n_t_bound) {
+      if (i < nT) {
+        int v = t_list[i];
+        unsigned long long bit = 1ull << (v & 63);
+        if (atomicAnd(&bm[v >> 6], ~bit) & bit) id[k] = v;
+      }
+    } else if (i < n_t_bound + nF) id[k] = F[i - n_t_bound];
+    else if (i < M) id[k] = D[i - n_t_bound - nF];
+    c += id[k] >= 0;
+  }
+  int m;
+  int ex = block_excl_scan<THREADS>(c, sm, &m);
+#pragma unroll
+  for (int k = 0; k < ITEMS; k++)
+    if (id[k] >= 0) { S.sk[ex] = (uint32_t)id[k]; S.sv[ex] = 0; ex++; }
+  small_sort_lds<THREADS, ITEMS>(S, m, passes);
+  int h[ITEMS];
+  c = 0;
+#pragma unroll
+  for (int k = 0; k < ITEMS; k++) {
+    int i = t0 + k;
+    h[k] = i < m && (i == 0 || S.sk[i] != S.sk[i - 1]);
+    c += h[k];
+  }
+  int nC;
+  ex = block_excl_scan<THREADS>(c, sm, &nC);
+#pragma unroll
+  for (int k = 0; k < ITEMS; k++)
+    if (h[k]) rows[ex++] = (int32_t)S.sk[t0 + k];
+  if (threadIdx.x == 0) cnt->v[C_NC] = nC;
+}
+
 // The emission of a layer with few transformed rows (at most THREADS * ITEMS) in one workgroup:
 // rows whose flag is set -> their positions (idx) and ids (f_list), the count, and, with
 // want_events, the exclusive prefix of their kept out-degrees and its total.
@@ -726,6 +779,7 @@ extern "C" ink_status ink_full_infer(ink_ctx *c) {
 // f_old holds their previous message rows (sum-type only).  Marks targets whose aggregate changed
 // in c->bm_a.  Counters are read back by the caller's next synchronisation.
 constexpr int64_t kSmallLayer = 4096;           // events / rows up to which a layer's bookkeeping runs in one workgroup
+constexpr int64_t kBitmapOneLaunch = 16384;     // nodes up to which the bitmap scan is a single launch
 constexpr int64_t kNoSyncEvents = 1 << 18;     // below this the target count stays on the device
 
 static ink_status layer_aggregate(ink_ctx *c, int l, const int32_t *F, int64_t nF, int64_t n_chg, const float *f_old,
@@ -849,15 +903,37 @@ static void layer_stats_from_counters(ink_ctx *c, int l) {
 }
 
 // bitmap (plus extra id lists) -> ascending row list in c->c_list; returns the count, or, with
-// bound >= 0, that upper bound without waiting for the device (the count stays in C_NC)
+// bound >= 0, that upper bound without waiting for the device (the count stays in C_NC).
+// n_t_bound >= 0 says that only the first *C_NT (at most n_t_bound) entries of c->t_list can have
+// their bit set; a short candidate list is then collected in one workgroup, which also clears
+// the row flags (*flags_cleared), unless the graph is so small that scanning the whole bitmap is
+// one launch as well (then sorting the candidates costs more than the scan).
 static ink_status collect_rows(ink_ctx *c, const int32_t *extra0, int64_t n0, const int32_t *extra1, int64_t n1,
-                               int64_t *nC, int64_t bound = -1) {
+                               int64_t *nC, int64_t bound = -1, int64_t n_t_bound = -1, bool *flags_cleared = nullptr) {
   hipStream_t s = c->stream;
   Prof p(c, INK_T_COMPACT);
-  if (n0 > 0) hipLaunchKernelGGL(k_mark_nodes, grid1(n0), dim3(256), 0, s, extra0, (int)n0, c->bm_a);
-  if (n1 > 0) hipLaunchKernelGGL(k_mark_nodes, grid1(n1), dim3(256), 0, s, extra1, (int)n1, c->bm_a);
   API_TRY(c->c_list.reserve((size_t)c->n * 4));
-  API_TRY(bitmap_to_list(c->ws, c->bm_a, c->n, c->c_list.as<int32_t>(), &c->d_cnt->v[C_NC], 1, s));
+  const int64_t M = n_t_bound + n0 + n1;
+  if (n_t_bound >= 0 && M <= kSmallLayer && c->n > kBitmapOneLaunch) {
+    const int64_t n_flags = std::min<int64_t>(M, c->n);
+    API_TRY(c->c_flag.reserve((size_t)n_flags + 64));
+    const int passes = (c->id_bits + kRadixBits - 1) / kRadixBits;
+#define INK_SMALL_COLLECT(T, I)                                                                                    \
+  hipLaunchKernelGGL((k_small_collect<T, I>), dim3(1), dim3(T), 0, s, (const int32_t *)c->t_list.as<int32_t>(),     \
+                     (const int32_t *)&c->d_cnt->v[C_NT], (int)n_t_bound, (unsigned long long *)c->bm_a, extra0,   \
+                     (int)n0, extra1, (int)n1, passes, c->c_list.as<int32_t>(), c->c_flag.as<uint8_t>(),           \
+                     (int)n_flags, c->d_cnt)
+    if (M <= 256) INK_SMALL_COLLECT(256, 1);
+    else if (M <= 1024) INK_SMALL_COLLECT(256, 4);
+    else INK_SMALL_COLLECT(1024, 4);
+#undef INK_SMALL_COLLECT
+    API_TRY(hipGetLastError());
+    if (flags_cleared) *flags_cleared = true;
+  } else {
+    if (n0 > 0) hipLaunchKernelGGL(k_mark_nodes, grid1(n0), dim3(256), 0, s, extra0, (int)n0, c->bm_a);
+    if (n1 > 0) hipLaunchKernelGGL(k_mark_nodes, grid1(n1), dim3(256), 0, s, extra1, (int)n1, c->bm_a);
+    API_TRY(bitmap_to_list(c->ws, c->bm_a, c->n, c->c_list.as<int32_t>(), &c->d_cnt->v[C_NC], 1, s));
+  }
   if (bound >= 0) { *nC = bound; return INK_OK; }
   API_TRY(read_counters(c));
   *nC = c->h_cnt->v[C_NC];
@@ -944,7 +1020,10 @@ static ink_status propagate_layers(ink_ctx *c, int64_t nF, int64_t n_chg, int cu
     int64_t nC = 0;
     const bool lazy = !gcn && !S.dense && !c->affected_mode && S.n_events <= kNoSyncEvents;
     const int64_t bound = lazy ? std::min<int64_t>(std::min<int64_t>(S.n_events, c->n) + nF + nD, c->n) : -1;
-    st = collect_rows(c, F, nF, D, nD, &nC, bound);
+    // without the dense fallback and the baseline only grouped targets can have changed aggregates
+    const int64_t n_t_bound = (S.dense || c->affected_mode) ? -1 : (S.n_events > 0 ? std::min<int64_t>(S.n_events, c->n) : 0);
+    bool flags_cleared = false;
+    st = collect_rows(c, F, nF, D, nD, &nC, bound, n_t_bound, &flags_cleared);
     if (st != INK_OK) return st;
     const int32_t *nC_dev = lazy ? &c->d_cnt->v[C_NC] : nullptr;
     if (!lazy) { S.n_transformed = nC; layer_stats_from_counters(c, l); }
@@ -963,10 +1042,10 @@ static ink_status propagate_layers(ink_ctx *c, int64_t nF, int64_t n_chg, int cu
         const int32_t *rows = c->c_list.as<int32_t>();
         float *old_rows = want_old ? c->c_old.as<float>() : nullptr;
         if (!gcn) {
-          if (lazy) API_TRY(hipMemsetAsync(c->c_flag.p, 0, (size_t)nC, s));   // flags past the count stay 0
+          if (lazy && !flags_cleared) API_TRY(hipMemsetAsync(c->c_flag.p, 0, (size_t)nC, s));   // flags past the count stay 0
           API_TRY(run_transform(c, l, rows, nC, c->c_flag.as<uint8_t>(), old_rows, nC_dev));
         } else {
-          API_TRY(hipMemsetAsync(c->c_flag.p, 0, (size_t)nC, s));
+          if (!flags_cleared) API_TRY(hipMemsetAsync(c->c_flag.p, 0, (size_t)nC, s));
           if (!last) API_TRY(gcn_next_messages(c, l, rows, nC, c->c_flag.as<uint8_t>(), old_rows));
           else API_TRY(gcn_final(c, rows, nC, c->c_flag.as<uint8_t>()));
         }

@@ -119,3 +119,32 @@ def test_blocks_and_pools_grow_in_both_forms(limit):
         h.check_graph()
     h.check_state()
     h.ink.close()
+
+
+@pytest.mark.parametrize("kind,agg,exact", [("sage", "max", True), ("gin", "min", True), ("gin", "sum", False),
+                                            ("gcn", "gcn_sym", False), ("sage", "mean", False)])
+def test_short_layers_on_a_graph_with_a_long_bitmap(kind, agg, exact):
+    """Above 16 384 nodes a layer with few events collects its rows from the grouped targets, the
+    sources and the degree-changed nodes instead of scanning the changed-row bitmap: small edge
+    batches and feature updates, three layers, so that layers of every size class occur."""
+    dims = (8, 8, 8, 6)
+    n = 20000
+    cfg = synth.WorkloadConfig(8, "t", kind, agg, n, 60000, False, dims, 12, 50, False)
+    src, dst = synth.make_graph(cfg)
+    rng = np.random.default_rng(41)
+    X = rng.integers(-3, 4, size=(n, dims[0])).astype(np.float32)
+    h = Harness(cfg=cfg, graph=(n, src, dst), X=X, model=tiny_model(kind, agg, dims, seed=5, hidden=8),
+                precision="f32" if exact else "f64", slack=0.05, profile=True)
+    small_layers = 0
+    for size in (1, 3, 20, 90, 300, 700):
+        op, s, d = messy_batch(rng, n, h.keys, size)
+        h.step(op, s, d, exact=exact, tol=1e-5)
+        small_layers += sum(1 for L in h.ink.stats()["layers"] if 0 < L["n_events"] <= 4096)
+        ids = rng.choice(n, size=min(size, 40), replace=False)
+        h.feature_step(ids, rng.integers(-3, 4, size=(ids.size, dims[0])).astype(np.float32), exact=exact, tol=1e-5)
+    assert small_layers >= 6
+    h.check_graph()
+    h.check_state(exact=exact, tol=1e-5)
+    if exact:
+        h.check_bound()
+    h.ink.close()
