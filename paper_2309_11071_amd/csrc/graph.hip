@@ -601,7 +601,8 @@ __global__ __launch_bounds__(THREADS) void k_small_in(const RawUpdate *raw, int 
   }
   __syncthreads();
   if (threadIdx.x == 0) cnt->v[C_NOPS] = n_ops;
-  small_heads_and_chunks<THREADS, ITEMS>(S, s_src, sm, n_ops, deg, o.uniq, o.seg, o.chunk_pref, &cnt->v[C_TMP0], &cnt->v[C_TMP1]);
+  // the permutation in sv is used up: its space serves as scratch
+  small_heads_and_chunks<THREADS, ITEMS>(S, (int *)S.sv, sm, n_ops, deg, o.uniq, o.seg, o.chunk_pref, &cnt->v[C_TMP0], &cnt->v[C_TMP1]);
 }
 
 // Out side, after the in side's k_effect: the effective ops become Delta E (inserted and removed
@@ -612,7 +613,6 @@ __global__ __launch_bounds__(THREADS) void k_small_out(SmallSide in, int passes,
                                                              int32_t *del_s, int32_t *del_d, SmallSide o,
                                                              const int32_t *deg, Counters *cnt) {
   __shared__ SmallSortLds<THREADS, ITEMS> S;
-  __shared__ int s_u[THREADS * ITEMS];
   __shared__ int sm[THREADS / kWave + 1];
   const int n_ops = cnt->v[C_NOPS];
   const int t0 = threadIdx.x * ITEMS;
@@ -643,7 +643,8 @@ __global__ __launch_bounds__(THREADS) void k_small_out(SmallSide in, int passes,
     o.node[p] = S.sk[p]; o.other[p] = (int)in.node[j]; o.op[p] = in.eff[j] == 2 ? 1 : 0; o.pos[p] = -1;
   }
   if (threadIdx.x == 0) { cnt->v[C_TMP2] = n_ins; cnt->v[C_TMP3] = n_del; }
-  small_heads_and_chunks<THREADS, ITEMS>(S, s_u, sm, m, deg, o.uniq, o.seg, o.chunk_pref, &cnt->v[C_OT], &cnt->v[C_OCH]);
+  __syncthreads();            // sv has been read by everyone: its space serves as scratch
+  small_heads_and_chunks<THREADS, ITEMS>(S, (int *)S.sv, sm, m, deg, o.uniq, o.seg, o.chunk_pref, &cnt->v[C_OT], &cnt->v[C_OCH]);
 }
 
 static ink_status graph_apply_small(ink_ctx *c, int64_t n, int64_t *n_ins_out, int64_t *n_del_out) {

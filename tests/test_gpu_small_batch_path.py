@@ -26,7 +26,7 @@ def pair(kind, agg, exact, n=5000, e=40000, dims=(8, 8, 6), slack=0.05, **kw):
 def test_both_forms_agree_and_match_the_oracle(kind, agg, exact):
     a, b = pair(kind, agg, exact)
     rng = np.random.default_rng(31)
-    for size in (1, 2, 63, 64, 65, 255, 257, 1000, 1024, 1025, 3000, 4095, 4096, 4097):
+    for size in (1, 2, 63, 64, 65, 255, 257, 1000, 1024, 1025, 3000, 4095, 4096, 4097, 9000, 16383, 16384, 16385):
         op, s, d = messy_batch(rng, a.n, a.keys, size)
         ra, _ = a.step(op, s, d, exact=exact, tol=1e-5)
         rb, _ = b.step(op, s, d, exact=exact, tol=1e-5)
@@ -69,8 +69,8 @@ def test_degenerate_short_batches():
     a.ink.close(); b.ink.close()
 
 
-@pytest.mark.parametrize("limit", [0, -1])
-def test_malformed_device_batches_are_dropped_whole(limit):
+@pytest.mark.parametrize("limit,size", [(0, 300), (0, 3000), (-1, 300), (-1, 10000)])
+def test_malformed_device_batches_are_dropped_whole(limit, size):
     """A device-resident batch is validated by the first kernel of the graph stage: one bad entry
     drops the batch before any block is touched, and the next batch is served as usual."""
     import torch
@@ -82,7 +82,7 @@ def test_malformed_device_batches_are_dropped_whole(limit):
     dev.full_infer()
     before = dev.get_layer(2, 0).copy()
     rng = np.random.default_rng(3)
-    op, s, d = messy_batch(rng, h.n, h.keys, 300)
+    op, s, d = messy_batch(rng, h.n, h.keys, size)
     for pos, (bo, bs, bd, code) in enumerate([(0, h.n, 1, 5), (0, 2, -1, 5), (9, 1, 2, 1)]):
         o2, s2, d2 = op.copy(), s.copy(), d.copy()
         o2[17 + pos], s2[17 + pos], d2[17 + pos] = bo, bs, bd
@@ -136,7 +136,7 @@ def test_short_layers_on_a_graph_with_a_long_bitmap(kind, agg, exact):
     h = Harness(cfg=cfg, graph=(n, src, dst), X=X, model=tiny_model(kind, agg, dims, seed=5, hidden=8),
                 precision="f32" if exact else "f64", slack=0.05, profile=True)
     small_layers = 0
-    for size in (1, 3, 20, 90, 300, 700):
+    for size in (1, 3, 20, 90, 300, 700, 2500):
         op, s, d = messy_batch(rng, n, h.keys, size)
         h.step(op, s, d, exact=exact, tol=1e-5)
         small_layers += sum(1 for L in h.ink.stats()["layers"] if 0 < L["n_events"] <= 4096)
