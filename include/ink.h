@@ -24,6 +24,8 @@
  *   - Node ids are int32 in [0, n_nodes); the graph is a simple directed graph without self
  *     loops; n_nodes is fixed for the life of the context (the paper updates edges only,
  *     Sec. 2.1).  Edge (u -> v) makes u an in-neighbour of v: v aggregates m_u.
+ *   - At most 2^31 - 2^30 - 1 edges (event offsets are 32-bit); a batch that could take the graph
+ *     past that is refused.
  *   - All matrices are row-major float32.  Layer outputs are at most INK_MAX_OUT_DIM wide, layer
  *     inputs (the feature width in particular) at most INK_MAX_IN_DIM.
  */

@@ -491,6 +491,10 @@ static hipError_t run_transform(ink_ctx *c, int l, const int32_t *rows, int64_t 
 }
 
 // ------------------------------------------------------------------------------------ create
+// Event records of a layer are addressed with 32-bit offsets: at most one per edge plus one per
+// list entry of the batch (below 2^30), so the edge count is held below 2^31 - 2^30.
+constexpr int64_t kMaxEdges = (1ll << 31) - (1ll << 30) - 1;
+
 static ink_status validate_model(const ink_model *m, int feat_dim, std::string &why) {
   if (m->n_layers < 1 || m->n_layers > INK_MAX_LAYERS || !m->layers) { why = "n_layers out of range or layers NULL"; return INK_E_ARG; }
   if (m->kind != INK_MODEL_SAGE && m->kind != INK_MODEL_GIN && m->kind != INK_MODEL_GCN) { why = "unknown model kind"; return INK_E_ARG; }
@@ -525,6 +529,7 @@ extern "C" ink_status ink_create(const ink_csr *g, const float *features, int32_
   const bool dev = opts && opts->mem == INK_MEM_DEVICE;
   const int n = g->n_nodes;
   const int64_t E = g->n_edges;
+  if (E > kMaxEdges) return fail(nullptr, INK_E_ARG, "ink_create: more than 2^31 - 2^30 edges (event offsets are 32-bit)");
   // graph to the host (validation and block layout are host work)
   std::vector<int64_t> rowptr((size_t)n + 1);
   std::vector<int32_t> col((size_t)E);
@@ -1099,6 +1104,7 @@ static ink_status apply_updates_impl(ink_ctx *c, const ink_edge_update *upd, int
   if (!out || n < 0 || (n > 0 && !upd)) return fail(c, INK_E_ARG, "ink_apply_updates: NULL argument or negative n");
   if (!c->inferred) return fail(c, INK_E_STATE, "ink_apply_updates: call ink_full_infer first");
   if (n >= (1ll << 30)) return fail(c, INK_E_ARG, "ink_apply_updates: batch too large");
+  if (c->n_edges_now + n > kMaxEdges) return fail(c, INK_E_ARG, "ink_apply_updates: the graph would exceed the edge limit");
   auto t0 = std::chrono::steady_clock::now();
   memset(out, 0, sizeof(*out));
   hipStream_t s = c->stream;
