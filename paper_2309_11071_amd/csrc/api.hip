@@ -427,10 +427,39 @@ static void prof_collect(ink_ctx *c) {
   c->ev_pending.clear();
 }
 
-static hipError_t read_counters(ink_ctx *c) {
-  hipError_t e = hipMemcpyAsync(c->h_cnt, c->d_cnt, sizeof(Counters), hipMemcpyDeviceToHost, c->stream);
+// The counters reach the host through a kernel that writes them into pinned host memory and then
+// a sequence number; the host polls that number.  A blocking stream synchronisation costs an
+// interrupt round trip (15-25 us here) per read-back, and a short batch has four of them.  After
+// a short spin the host falls back to the blocking wait (long kernels ahead of the read-back).
+__global__ __launch_bounds__(64) void k_publish(const Counters *d, HostCounters *h, uint32_t *h_seq, uint32_t seq) {
+  const int l = threadIdx.x;
+  if (l < 32) h->v[l] = d->v[l];
+#pragma unroll
+  for (int w = 0; w < ST_N; w++) {
+    unsigned long long t = d->stripe[l][w];       // kStripes == 64 == one per lane
+    for (int o = 32; o > 0; o >>= 1) t += __shfl_xor(t, o, kWave);
+    if (l == 0) h->total[w] = t;
+  }
+  __threadfence_system();
+  if (l == 0) __hip_atomic_store(h_seq, seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+static_assert(kStripes == kWave, "one stripe per lane");
+
+hipError_t ink::read_counters(ink_ctx *c) {
+  const uint32_t seq = ++c->pub_seq;
+  hipLaunchKernelGGL(k_publish, dim3(1), dim3(64), 0, c->stream, (const Counters *)c->d_cnt, c->h_cnt, c->h_seq, seq);
+  hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  return hipStreamSynchronize(c->stream);
+  const auto t0 = std::chrono::steady_clock::now();
+  for (int spin = 0;; spin++) {
+    if (__atomic_load_n(c->h_seq, __ATOMIC_ACQUIRE) == seq) return hipSuccess;
+    if ((spin & 63) == 63 &&
+        std::chrono::duration<double, std::micro>(std::chrono::steady_clock::now() - t0).count() > 150.0)
+      break;
+  }
+  e = hipStreamSynchronize(c->stream);
+  if (e != hipSuccess) return e;
+  return __atomic_load_n(c->h_seq, __ATOMIC_ACQUIRE) == seq ? hipSuccess : hipErrorUnknown;
 }
 
 static const Table &msg_table(ink_ctx *c, int l) {   // m_l: h_{l-1} (aggregate first) or GCN's scaled h_{l-1} W_l
@@ -580,7 +609,9 @@ extern "C" ink_status ink_create(const ink_csr *g, const float *features, int32_
   CREATE_TRY(hipMemset(c->new_out, 0, (size_t)nc * 4));
   CREATE_TRY(hipMalloc(&c->d_cnt, sizeof(Counters)));
   CREATE_TRY(hipMemset(c->d_cnt, 0, sizeof(Counters)));
-  CREATE_TRY(hipHostMalloc((void **)&c->h_cnt, sizeof(Counters)));
+  CREATE_TRY(hipHostMalloc((void **)&c->h_cnt, sizeof(HostCounters) + 64, hipHostMallocCoherent));
+  memset(c->h_cnt, 0, sizeof(HostCounters) + 64);
+  c->h_seq = reinterpret_cast<uint32_t *>(reinterpret_cast<char *>(c->h_cnt) + sizeof(HostCounters));
   size_t bmw = ((size_t)nc + 63) / 64;
   CREATE_TRY(hipMalloc(&c->bm_a, bmw * 8));
   CREATE_TRY(hipMemset(c->bm_a, 0, bmw * 8));

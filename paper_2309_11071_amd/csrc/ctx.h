@@ -86,6 +86,12 @@ struct Counters {            // device-written, host-read through pinned memory
     return t;
   }
 };
+// what the host sees of them: the slots and the stripe totals (192 bytes through pinned memory)
+struct HostCounters {
+  int32_t v[32];
+  unsigned long long total[ST_N];
+  unsigned long long sum(int which) const { return total[which]; }
+};
 // slots of Counters::v: event count of the next layer, unique targets, long rows listed, rows to
 // transform, rows changed, chunks of long rows, distinct ops of a batch, scratch of the graph stage,
 // touched nodes and block chunks of the out side (single-workgroup graph stage), and two 64-bit
@@ -122,8 +128,9 @@ struct ink_ctx {
 
   ink::PrimWorkspace ws;
   ink::Counters *d_cnt = nullptr;    // device counters
-  ink::Counters *h_cnt = nullptr;    // pinned host mirror
-  unsigned long long h_top = 0, h_top2 = 0;   // staging for the device copies of the pool tops
+  ink::HostCounters *h_cnt = nullptr;   // pinned host mirror, written by the publish kernel
+  uint32_t *h_seq = nullptr;         // (same allocation) sequence number of the last published copy
+  uint32_t pub_seq = 0;
   int64_t small_batch = 4096;        // batches up to this size take the single-workgroup graph stage
   uint64_t *bm_a = nullptr;          // node bitmaps (n bits each)
 
@@ -162,6 +169,7 @@ hipError_t graph_build(ink_ctx *c, const int64_t *rowptr_h, const int32_t *col_h
 // applies a validated batch already on the device in c->b_raw; fills Delta E lists and counts
 ink_status graph_apply_batch(ink_ctx *c, int64_t n, int64_t *n_ins, int64_t *n_del);
 ink_status graph_add_nodes(ink_ctx *c, int64_t n_new);   // empty edge blocks for nodes n .. n + n_new - 1 (before n grows)
+hipError_t read_counters(ink_ctx *c);        // device counters -> c->h_cnt, waits for them
 hipError_t graph_end_batch(ink_ctx *c);     // clears per-batch marks (new_out)
 hipError_t graph_export(ink_ctx *c, int64_t *rowptr_h, int32_t *col_h);
 

@@ -236,8 +236,9 @@ __global__ __launch_bounds__(256) void k_effect(const int32_t *nodes, const int3
 __global__ __launch_bounds__(256) void k_apply(const int32_t *nodes, const int32_t *seg, const int32_t *other,
                                                const uint8_t *eff, const int32_t *pos, const int32_t *nd_ins,
                                                const int32_t *nd_del, int64_t *off, int32_t *deg, int32_t *cap,
-                                               int32_t *ids, unsigned long long *pool_top, float slack,
-                                               int32_t *fill, int32_t *new_cnt, uint8_t *asc) {
+                                               int32_t *ids, unsigned long long *pool_used,
+                                               unsigned long long pool_base, float slack, int32_t *fill,
+                                               int32_t *new_cnt, uint8_t *asc) {
   __shared__ int sm[kScanThreads / kWave + 1];
   __shared__ long long s_newoff;
   const int i = blockIdx.x;
@@ -282,7 +283,7 @@ __global__ __launch_bounds__(256) void k_apply(const int32_t *nodes, const int32
       if (extra < 4) extra = 4;
       if (want < d2 + extra) want = d2 + extra;
       want = (want + 3) & ~3ll;
-      s_newoff = (long long)atomicAdd(pool_top, (unsigned long long)want);
+      s_newoff = (long long)(pool_base + atomicAdd(pool_used, (unsigned long long)want));
       cap[v] = (int32_t)want;
       off[v] = s_newoff;
     }
@@ -457,8 +458,7 @@ static ink_status apply_side(ink_ctx *c, GraphSide &g, SideBufs &b, int64_t n_op
                      (const int32_t *)&dc->v[C_TMP0], (const int32_t *)b.seg, (const uint8_t *)b.op,
                      (const int32_t *)b.pos, b.eff, (const int32_t *)g.deg, (const int32_t *)g.cap, b.nd_ins, b.nd_del,
                      c->slack, dc, (int)ST_REGATHER, (int)ST_EXPOSED, (int)ST_ACHG);
-  INK_TRYS(hipMemcpyAsync(c->h_cnt, dc, sizeof(Counters), hipMemcpyDeviceToHost, s));
-  INK_TRYS(hipStreamSynchronize(s));
+  INK_TRYS(read_counters(c));
   if (c->h_cnt->v[C_ERR]) return batch_error(c);
   int n_touched = c->h_cnt->v[C_TMP0];
   *n_touched_out = n_touched;
@@ -471,14 +471,13 @@ static ink_status apply_side(ink_ctx *c, GraphSide &g, SideBufs &b, int64_t n_op
     if (e == hipErrorOutOfMemory) { c->err = "out of device memory while growing the edge pool"; return INK_E_OOM; }
     INK_TRYS(e);
   }
-  // device copy of the pool top lives in the counter block (64-bit slot)
-  unsigned long long *d_top = (unsigned long long *)&dc->v[C_TOP64];
-  c->h_top = (unsigned long long)g.pool_top;
-  INK_TRYS(hipMemcpyAsync(d_top, &c->h_top, sizeof(unsigned long long), hipMemcpyHostToDevice, s));
+  // blocks that move take their space at the pool's top: base by value, the amount handed out so
+  // far in a 64-bit slot of the counter block (zero since the fill above)
+  unsigned long long *d_used = (unsigned long long *)&dc->v[C_TOP64];
   hipLaunchKernelGGL(k_apply, dim3(n_touched), dim3(256), 0, s, (const int32_t *)b.uniq, (const int32_t *)b.seg,
                      (const int32_t *)b.other, (const uint8_t *)b.eff, (const int32_t *)b.pos,
-                     (const int32_t *)b.nd_ins, (const int32_t *)b.nd_del, g.off, g.deg, g.cap, g.ids, d_top,
-                     c->slack, b.fill, new_cnt, g.asc);
+                     (const int32_t *)b.nd_ins, (const int32_t *)b.nd_del, g.off, g.deg, g.cap, g.ids, d_used,
+                     (unsigned long long)g.pool_top, c->slack, b.fill, new_cnt, g.asc);
   INK_TRYS(hipGetLastError());
   g.pool_top += need;      // exact: the apply kernel allocates precisely what k_effect summed
   return INK_OK;
@@ -698,8 +697,7 @@ static ink_status graph_apply_small(ink_ctx *c, int64_t n, int64_t *n_ins_out, i
                        (const int32_t *)b.pos, b.eff, (const int32_t *)g.deg, (const int32_t *)g.cap, b.nd_ins, b.nd_del,
                        c->slack, dc, st[k][0], st[k][1], st[k][2]);
   }
-  INK_TRYS(hipMemcpyAsync(c->h_cnt, dc, sizeof(Counters), hipMemcpyDeviceToHost, s));
-  INK_TRYS(hipStreamSynchronize(s));
+  INK_TRYS(read_counters(c));
   if (c->h_cnt->v[C_ERR]) return batch_error(c);
   const int64_t ti = (int64_t)c->h_cnt->sum(st[0][1]), td = (int64_t)c->h_cnt->sum(st[0][2]);
   if ((int64_t)c->h_cnt->sum(st[1][1]) != ti || (int64_t)c->h_cnt->sum(st[1][2]) != td) {
@@ -711,7 +709,6 @@ static ink_status graph_apply_small(ink_ctx *c, int64_t n, int64_t *n_ins_out, i
   c->n_touched_in = c->h_cnt->v[C_TMP0];
   c->n_touched_src = c->h_cnt->v[C_OT];
   if (ti + td == 0) { c->n_touched_src = 0; return INK_OK; }
-  unsigned long long *h_top[2] = {&c->h_top, &c->h_top2};
   const int slot_top[2] = {C_TOP64, C_TOP64B};
   for (int k = 0; k < 2; k++) {
     SmallSide &b = sd[k];
@@ -723,13 +720,12 @@ static ink_status graph_apply_small(ink_ctx *c, int64_t n, int64_t *n_ins_out, i
       if (e == hipErrorOutOfMemory) { c->err = "out of device memory while growing the edge pool"; return INK_E_OOM; }
       INK_TRYS(e);
     }
-    unsigned long long *d_top = (unsigned long long *)&dc->v[slot_top[k]];
-    *h_top[k] = (unsigned long long)g.pool_top;
-    INK_TRYS(hipMemcpyAsync(d_top, h_top[k], sizeof(unsigned long long), hipMemcpyHostToDevice, s));
-    hipLaunchKernelGGL(k_apply, dim3(n_touched), dim3(256), 0, s, (const int32_t *)b.uniq, (const int32_t *)b.seg,
-                       (const int32_t *)b.other, (const uint8_t *)b.eff, (const int32_t *)b.pos,
-                       (const int32_t *)b.nd_ins, (const int32_t *)b.nd_del, g.off, g.deg, g.cap, g.ids, d_top,
-                       c->slack, b.fill, k == 1 ? c->new_out : nullptr, g.asc);
+    unsigned long long *d_used = (unsigned long long *)&dc->v[slot_top[k]];     // zero since k_small_in
+    if (n_touched > 0)
+      hipLaunchKernelGGL(k_apply, dim3(n_touched), dim3(256), 0, s, (const int32_t *)b.uniq, (const int32_t *)b.seg,
+                         (const int32_t *)b.other, (const uint8_t *)b.eff, (const int32_t *)b.pos,
+                         (const int32_t *)b.nd_ins, (const int32_t *)b.nd_del, g.off, g.deg, g.cap, g.ids, d_used,
+                         (unsigned long long)g.pool_top, c->slack, b.fill, k == 1 ? c->new_out : nullptr, g.asc);
     INK_TRYS(hipGetLastError());
     g.pool_top += need;
   }
