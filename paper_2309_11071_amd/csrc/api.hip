@@ -77,6 +77,28 @@ __global__ void k_expand_events(const int32_t *F, int nF, const int32_t *pref, i
   if (e < n_ev) expand_event((int)e, F, nF, pref, off, ids, payload_index, &key[e], &val[e]);
 }
 
+// The counters reach the host through pinned host memory: one wave writes the slots and the
+// stripe totals, then a sequence number that the host polls.  A blocking stream synchronisation
+// costs an interrupt round trip per read-back, and a short batch has four of them.  The loads
+// bypass the L1 so that a workgroup may publish what its own threads stored before a barrier.
+__device__ __forceinline__ void publish_wave(const Counters *d, HostCounters *h, uint32_t *h_seq, uint32_t seq) {
+  const int l = lane_id();
+  if (l < 32) h->v[l] = __hip_atomic_load(&d->v[l], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+  for (int w = 0; w < ST_N; w++) {
+    unsigned long long t = __hip_atomic_load(&d->stripe[l][w], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    for (int o = 32; o > 0; o >>= 1) t += __shfl_xor(t, o, kWave);
+    if (l == 0) h->total[w] = t;
+  }
+  __threadfence_system();
+  if (l == 0) __hip_atomic_store(h_seq, seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+static_assert(kStripes == kWave, "one stripe per lane");
+
+__global__ __launch_bounds__(64) void k_publish(const Counters *d, HostCounters *h, uint32_t *h_seq, uint32_t seq) {
+  publish_wave(d, h, h_seq, seq);
+}
+
 // A layer with few events (at most THREADS * ITEMS): clearing the counters, creating the events,
 // grouping them by target (stable, so deletions stay ahead of insertions ahead of changes) and
 // the segment heads in one workgroup.  Output as from the separate kernels: val in grouped
@@ -180,7 +202,8 @@ __global__ __launch_bounds__(THREADS) void k_small_collect(const int32_t *t_list
 template <int THREADS, int ITEMS>
 __global__ __launch_bounds__(THREADS) void k_small_emit(const uint8_t *flag, const int32_t *rows, int nC, int32_t *idx,
                                                         int32_t *f_list, int want_events, const int32_t *deg,
-                                                        const int32_t *new_out, int32_t *f_pref, Counters *cnt) {
+                                                        const int32_t *new_out, int32_t *f_pref, Counters *cnt,
+                                                        HostCounters *h, uint32_t *h_seq, uint32_t seq) {
   __shared__ int s_f[THREADS * ITEMS];
   __shared__ int sm[THREADS / kWave + 1];
   const int t0 = threadIdx.x * ITEMS;
@@ -197,7 +220,12 @@ __global__ __launch_bounds__(THREADS) void k_small_emit(const uint8_t *flag, con
   for (int k = 0; k < ITEMS; k++)
     if (f[k]) { int u = rows[t0 + k]; idx[ex] = t0 + k; f_list[ex] = u; s_f[ex] = u; ex++; }
   if (threadIdx.x == 0) cnt->v[C_NEXT] = nF;
-  if (!want_events) return;
+  if (!want_events) {
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x < kWave) publish_wave(cnt, h, h_seq, seq);
+    return;
+  }
   __syncthreads();
   int kd[ITEMS];
   c = 0;
@@ -215,6 +243,9 @@ __global__ __launch_bounds__(THREADS) void k_small_emit(const uint8_t *flag, con
     ex += kd[k];
   }
   if (threadIdx.x == 0) cnt->v[C_NEV] = n_ev;
+  __threadfence();
+  __syncthreads();
+  if (threadIdx.x < kWave) publish_wave(cnt, h, h_seq, seq);
 }
 
 __global__ void k_mark_nodes(const int32_t *list, int n, uint64_t *bm) {
@@ -368,6 +399,8 @@ static ink_status fail(ink_ctx *c, ink_status st, const std::string &msg) {
   return st;
 }
 
+static hipError_t wait_published(ink_ctx *c, uint32_t seq);
+
 static hipError_t alloc_table(Table &t, int64_t n, int d) {
   t.d = d;
   t.ld = round_up(d, 4);
@@ -427,29 +460,17 @@ static void prof_collect(ink_ctx *c) {
   c->ev_pending.clear();
 }
 
-// The counters reach the host through a kernel that writes them into pinned host memory and then
-// a sequence number; the host polls that number.  A blocking stream synchronisation costs an
-// interrupt round trip (15-25 us here) per read-back, and a short batch has four of them.  After
-// a short spin the host falls back to the blocking wait (long kernels ahead of the read-back).
-__global__ __launch_bounds__(64) void k_publish(const Counters *d, HostCounters *h, uint32_t *h_seq, uint32_t seq) {
-  const int l = threadIdx.x;
-  if (l < 32) h->v[l] = d->v[l];
-#pragma unroll
-  for (int w = 0; w < ST_N; w++) {
-    unsigned long long t = d->stripe[l][w];       // kStripes == 64 == one per lane
-    for (int o = 32; o > 0; o >>= 1) t += __shfl_xor(t, o, kWave);
-    if (l == 0) h->total[w] = t;
-  }
-  __threadfence_system();
-  if (l == 0) __hip_atomic_store(h_seq, seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
-}
-static_assert(kStripes == kWave, "one stripe per lane");
-
 hipError_t ink::read_counters(ink_ctx *c) {
   const uint32_t seq = ++c->pub_seq;
   hipLaunchKernelGGL(k_publish, dim3(1), dim3(64), 0, c->stream, (const Counters *)c->d_cnt, c->h_cnt, c->h_seq, seq);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
+  return wait_published(c, seq);
+}
+
+// waits until the record with this sequence number has arrived: a short spin, then the blocking wait
+static hipError_t wait_published(ink_ctx *c, uint32_t seq) {
+  hipError_t e;
   const auto t0 = std::chrono::steady_clock::now();
   for (int spin = 0;; spin++) {
     if (__atomic_load_n(c->h_seq, __ATOMIC_ACQUIRE) == seq) return hipSuccess;
@@ -992,13 +1013,16 @@ static ink_status emit_changed(ink_ctx *c, int64_t nC, int nxt, bool keep_old, i
   *nF2 = 0; *n_chg = 0;
   API_TRY(c->f_list[nxt].reserve((size_t)nC * 4));
   const bool small = nC <= kSmallLayer;
+  uint32_t published = 0;
   if (small) {
     if (want_events) API_TRY(c->f_pref.reserve((size_t)(nC + 1) * 4));
 #define INK_SMALL_EMIT(T, I)                                                                                       \
   hipLaunchKernelGGL((k_small_emit<T, I>), dim3(1), dim3(T), 0, s, (const uint8_t *)c->c_flag.as<uint8_t>(),        \
                      (const int32_t *)c->c_list.as<int32_t>(), (int)nC, c->c_idx.as<int32_t>(),                    \
                      c->f_list[nxt].as<int32_t>(), want_events ? 1 : 0, (const int32_t *)c->gout.deg,              \
-                     (const int32_t *)c->new_out, c->f_pref.as<int32_t>(), dc)
+                     (const int32_t *)c->new_out, c->f_pref.as<int32_t>(), dc, c->h_cnt, c->h_seq, seq)
+    const uint32_t seq = ++c->pub_seq;       // the kernel publishes the counters itself
+    published = seq;
     if (nC <= 256) INK_SMALL_EMIT(256, 1);
     else if (nC <= 1024) INK_SMALL_EMIT(256, 4);
     else INK_SMALL_EMIT(1024, 4);
@@ -1028,7 +1052,8 @@ static ink_status emit_changed(ink_ctx *c, int64_t nC, int nxt, bool keep_old, i
     *result_done = true;
   }
   API_TRY(hipGetLastError());
-  API_TRY(read_counters(c));
+  if (small) API_TRY(wait_published(c, published));
+  else API_TRY(read_counters(c));
   *nF2 = c->h_cnt->v[C_NEXT];
   if (want_events) *n_chg = (uint32_t)c->h_cnt->v[C_NEV];
   return INK_OK;
