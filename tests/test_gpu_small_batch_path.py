@@ -148,3 +148,42 @@ def test_short_layers_on_a_graph_with_a_long_bitmap(kind, agg, exact):
     if exact:
         h.check_bound()
     h.ink.close()
+
+
+@pytest.mark.parametrize("kind,agg,exact", [("sage", "max", True), ("gin", "sum", False), ("gcn", "gcn_sym", False)])
+def test_mixed_stream_of_every_kind_of_call(kind, agg, exact):
+    """Edge batches of both forms, feature updates and node arrivals in random order on one
+    context (20 000 nodes, three layers); every call is checked against the oracle."""
+    from test_gpu_add_nodes import edges_touching
+    dims = (8, 8, 8, 6)
+    n = 20000
+    cfg = synth.WorkloadConfig(8, "t", kind, agg, n, 60000, False, dims, 12, 50, False)
+    src, dst = synth.make_graph(cfg)
+    rng = np.random.default_rng(77)
+    X = rng.integers(-3, 4, size=(n, dims[0])).astype(np.float32)
+    h = Harness(cfg=cfg, graph=(n, src, dst), X=X, model=tiny_model(kind, agg, dims, seed=9, hidden=8),
+                precision="f32" if exact else "f64", slack=0.05, node_capacity=n + 200)
+    for it in range(24):
+        what = int(rng.integers(0, 5))
+        if what == 0:
+            op, s, d = messy_batch(rng, h.n, h.keys, int(rng.integers(1, 60)))
+            h.step(op, s, d, exact=exact, tol=1e-5)
+        elif what == 1:
+            op, s, d = messy_batch(rng, h.n, h.keys, int(rng.integers(300, 4000)))
+            h.step(op, s, d, exact=exact, tol=1e-5)
+        elif what == 2:
+            op, s, d = messy_batch(rng, h.n, h.keys, int(rng.integers(4097, 9000)))
+            h.step(op, s, d, exact=exact, tol=1e-5)
+        elif what == 3:
+            ids = rng.choice(h.n, size=int(rng.integers(1, 80)), replace=False)
+            h.feature_step(ids, rng.integers(-3, 4, size=(ids.size, dims[0])).astype(np.float32), exact=exact, tol=1e-5)
+        elif h.n + 8 <= n + 200:
+            lo = h.n
+            h.add_nodes(rng.integers(-3, 4, size=(int(rng.integers(1, 8)), dims[0])).astype(np.float32), exact=exact)
+            op, s, d = edges_touching(rng, h, lo, 30)
+            h.step(op, s, d, exact=exact, tol=1e-5)
+    h.check_graph()
+    h.check_state(exact=exact, tol=1e-5)
+    if exact:
+        h.check_bound()
+    h.ink.close()
