@@ -15,12 +15,26 @@ struct S4 { float v[4]; };
 
 __device__ __forceinline__ float4 ldf4(const float *p) { return *reinterpret_cast<const float4 *>(p); }
 
+// Lanes per row: 16 / 32 / 64 (64 / LPR groups fill the wave) or 12 (five groups, lanes 60-63 idle:
+// rows of at most 48 floats, five of them per load instead of four).
 template <int LPR> __device__ __forceinline__ void sum_groups(S4 &a) {
+  if constexpr ((LPR & (LPR - 1)) == 0) {
 #pragma unroll
-  for (int off = LPR; off < kWave; off <<= 1)
+    for (int off = LPR; off < kWave; off <<= 1)
 #pragma unroll
-    for (int c = 0; c < 4; c++) a.v[c] = __fadd_rn(a.v[c], __shfl_xor(a.v[c], off, kWave));
+      for (int c = 0; c < 4; c++) a.v[c] = __fadd_rn(a.v[c], __shfl_xor(a.v[c], off, kWave));
+  } else {       // group 0 + group 1 + ... in that order; valid in the lanes of group 0
+    constexpr int G = kWave / LPR;
+    const int q = lane_id() % LPR;
+    S4 r = a;
+#pragma unroll
+    for (int g = 1; g < G; g++)
+#pragma unroll
+      for (int c = 0; c < 4; c++) r.v[c] = __fadd_rn(r.v[c], __shfl(a.v[c], q + g * LPR, kWave));
+    a = r;
+  }
 }
+template <int LPR> __device__ __forceinline__ bool lane_in_groups() { return lane_id() < (kWave / LPR) * LPR; }
 
 // sum of rows M[ids[j]] for j in [j0, j1): group g takes j0 + g, j0 + g + G, ... in order
 template <int LPR>
@@ -35,7 +49,7 @@ __device__ __forceinline__ void sum_range(const int32_t *ids, int64_t j0, int64_
     int64_t jj = jb + l;
     int myid = jj < j1 ? ids[jj] : -1;
     int cnt = (int)((j1 - jb) < kWave ? (j1 - jb) : kWave);
-    constexpr int U = LPR == 16 ? INK_U_SUM16 : (LPR == 32 ? INK_U_SUM32 : INK_U_SUM64);
+    constexpr int U = LPR <= 16 ? INK_U_SUM16 : (LPR == 32 ? INK_U_SUM32 : INK_U_SUM64);
     for (int it = 0; it < cnt; it += G * U) {
       int id[U];
       float4 row[U];
@@ -88,7 +102,7 @@ __global__ __launch_bounds__(256) void k_sum_full(AggArgs a, const int32_t *targ
                                                   int32_t *big_list, int32_t *n_big, int compare, Counters *cnt) {
   const int l = lane_id();
   const int q = l % LPR;
-  const bool lane_on = 4 * q < a.wd;
+  const bool lane_on = 4 * q < a.wd && lane_in_groups<LPR>();
   int64_t wid = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kWave;
   if (wid >= n_targets) return;
   int v = targets ? targets[wid] : (int)wid;
@@ -110,7 +124,7 @@ __global__ __launch_bounds__(INK_BIG_LB) void k_sum_big_partial(AggArgs a, const
   __shared__ float sv[kBigMaxWaves][kWave * 4];
   const int l = lane_id(), w = threadIdx.x / kWave, nw = blockDim.x / kWave;
   const int q = l % LPR;
-  const bool lane_on = 4 * q < a.wd;
+  const bool lane_on = 4 * q < a.wd && lane_in_groups<LPR>();
   const int total = *total_p, n_big = *n_big_p;
   for (int cg = blockIdx.x; cg < total; cg += gridDim.x) {
     int i, v;
@@ -255,6 +269,8 @@ __global__ __launch_bounds__(256) void k_sum_events(AggArgs a, const int32_t *ta
 }
 
 static int lanes_per_row(int ld) { return ld <= 64 ? 16 : (ld <= 128 ? 32 : 64); }
+// full re-aggregation only: narrow rows take 12 lanes (config 2, layer 2: 4.5 % less aggregation time)
+static int lanes_per_row_full(int ld) { return ld <= 48 ? 12 : lanes_per_row(ld); }
 
 template <int LPR>
 static hipError_t sum_full_t(ink_ctx *c, const AggArgs &a_in, const int32_t *targets, int64_t n_targets,
@@ -291,7 +307,8 @@ static hipError_t sum_events_t(ink_ctx *c, const AggArgs &a, const int32_t *targ
 }
 
 hipError_t agg_sum_full(ink_ctx *c, const AggArgs &a, const int32_t *targets, int64_t n_targets, uint64_t *chg) {
-  switch (lanes_per_row(a.wd)) {
+  switch (lanes_per_row_full(a.wd)) {
+    case 12: return sum_full_t<12>(c, a, targets, n_targets, chg);
     case 16: return sum_full_t<16>(c, a, targets, n_targets, chg);
     case 32: return sum_full_t<32>(c, a, targets, n_targets, chg);
     default: return sum_full_t<64>(c, a, targets, n_targets, chg);

@@ -402,8 +402,11 @@ static ink_status fail(ink_ctx *c, ink_status st, const std::string &msg) {
 static hipError_t wait_published(ink_ctx *c, uint32_t seq);
 
 static hipError_t alloc_table(Table &t, int64_t n, int d) {
+  // rows start on 64-byte boundaries: a gathered row then touches the fewest cache lines (config 2,
+  // 41-wide rows: 176 -> 192 bytes per row and 5 % less aggregation time; 128-byte alignment loses
+  // that again to the larger table)
   t.d = d;
-  t.ld = round_up(d, 4);
+  t.ld = round_up(d, 16);
   size_t bytes = (size_t)n * t.ld * 4;
   hipError_t e = hipMalloc(&t.p, bytes);
   if (e != hipSuccess) return e;
