@@ -25,7 +25,7 @@ namespace ink {
 #define INK_U_SEL64 4
 #endif
 #ifndef INK_U_SUM16
-#define INK_U_SUM16 4
+#define INK_U_SUM16 8       // narrow rows are cheap in registers: 8 loads in flight measured 3.5 % faster than 4
 #endif
 #ifndef INK_U_SUM32
 #define INK_U_SUM32 4
