@@ -86,10 +86,17 @@ __device__ __forceinline__ void fetch_x4(const XformArgs &x, int64_t row, int k,
       ld4v(x.A + row * x.lda + k, a);
       ld4v(x.Hp + row * x.ldh + k, h);
       float cv = x.cnorm[row];
+      float b[4] = {0.f, 0.f, 0.f, 0.f};
+      if (x.in_bias) {       // one 16-byte load when the group lies inside the bias vector
+        if (k + 3 < x.d_in) ld4v(x.in_bias + k, b);
+        else
+#pragma unroll
+          for (int i = 0; i < 4; i++) if (k + i < x.d_in) b[i] = x.in_bias[k + i];
+      }
 #pragma unroll
       for (int i = 0; i < 4; i++) {
         float v = __fmul_rn(cv, __fadd_rn(a[i], h[i]));
-        if (x.in_bias && k + i < x.d_in) v = __fadd_rn(v, x.in_bias[k + i]);
+        if (x.in_bias && k + i < x.d_in) v = __fadd_rn(v, b[i]);
         if (x.in_relu) v = v > 0.f ? v : 0.f;
         out[i] = k + i < x.d_in ? v : 0.f;
       }
