@@ -48,6 +48,8 @@ int main(void) {
          sizeof(ink_stats));
   printf("%zu %zu %zu %zu\n", offsetof(ink_options, pool_reserve), offsetof(ink_layer, act),
          offsetof(ink_stats, ms), offsetof(ink_edge_update, src));
+  printf("%zu %zu %zu %zu\n", offsetof(ink_options, small_batch_limit), offsetof(ink_options, node_capacity),
+         offsetof(ink_options, batch_mem), offsetof(ink_update_result, n_applied_ins));
   return 0;
 }
 '''
@@ -67,6 +69,10 @@ int main(void) {
     assert b._Layer.act.offset == offs[1]
     assert b._Stats.ms.offset == offs[2]
     assert b.EDGE_UPDATE_DTYPE.fields["src"][1] == offs[3]
+    assert b._Options.small_batch_limit.offset == offs[4]
+    assert b._Options.node_capacity.offset == offs[5]
+    assert b._Options.batch_mem.offset == offs[6]
+    assert b._Result.n_applied_ins.offset == offs[7]
 
 
 def test_binding_refuses_to_run_without_the_library(monkeypatch, tmp_path):
