@@ -205,8 +205,42 @@ __global__ __launch_bounds__(NW * 64) void k_xform(XformArgs x) {
       for (int kk = 0; kk < KPT; kk += 4) fetch_x4<MODE>(x, xrow, k0 + xks + kk, xv + kk);
     }
   };
-  fetch_chunk(0);
+  // GCN rows whose width is a multiple of the chunk: the loads of the next chunk are issued a
+  // whole iteration before their values are scaled, biased, stored as h and staged, so the
+  // gather latency overlaps the barriers, the weight staging and the MFMAs of the chunk between
+  const bool raw3 = MODE == 3 && x.d_in == x.Kp && x.lda >= x.Kp && x.ldh >= x.Kp && (!x.h_store || x.ld_hs >= x.Kp);
+  float ra[KPT], rh[KPT], rb[KPT];
+  const float cv3 = (raw3 && xrow >= 0) ? x.cnorm[xrow] : 0.f;
+  auto issue3 = [&](int k0) {
+    if (xrow < 0) return;
+#pragma unroll
+    for (int kk = 0; kk < KPT; kk += 4) {
+      int k = k0 + xks + kk;
+      ld4v(x.A + xrow * x.lda + k, ra + kk);
+      ld4v(x.Hp + xrow * x.ldh + k, rh + kk);
+      if (x.in_bias) ld4v(x.in_bias + k, rb + kk);
+    }
+  };
+  auto finish3 = [&](int k0) {
+#pragma unroll
+    for (int kk = 0; kk < KPT; kk++) xv[kk] = 0.f;
+    if (xrow < 0) return;
+#pragma unroll
+    for (int kk = 0; kk < KPT; kk++) {
+      float v = __fmul_rn(cv3, __fadd_rn(ra[kk], rh[kk]));
+      if (x.in_bias) v = __fadd_rn(v, rb[kk]);
+      if (x.in_relu) v = v > 0.f ? v : 0.f;
+      xv[kk] = v;
+    }
+    if (x.h_store) {
+#pragma unroll
+      for (int kk = 0; kk < KPT; kk += 4)
+        *reinterpret_cast<float4 *>(x.h_store + xrow * x.ld_hs + k0 + xks + kk) = make_float4(xv[kk], xv[kk + 1], xv[kk + 2], xv[kk + 3]);
+    }
+  };
+  if (raw3) issue3(0); else fetch_chunk(0);
   for (int k0 = 0; k0 < x.Kp; k0 += KT) {
+    if (raw3) finish3(k0);
     if (xstage) {   // even k first, then odd k
       float *xp = Xs + xr * XS + (xks >> 1);
       if constexpr (KPT == 8) {
@@ -223,8 +257,9 @@ __global__ __launch_bounds__(NW * 64) void k_xform(XformArgs x) {
 #pragma unroll
       for (int i = t; i < n4; i += NTHR) *reinterpret_cast<float4 *>(Ws + (i >> 3) * XS + (i & 7) * 4) = src[i];
     }
+    if (raw3 && k0 + KT < x.Kp) issue3(k0 + KT);
     __syncthreads();
-    if (k0 + KT < x.Kp) fetch_chunk(k0 + KT);
+    if (!raw3 && k0 + KT < x.Kp) fetch_chunk(k0 + KT);
     // this wave owns TPW column tiles, or one fewer when the last one would lie past NT
     if (ct0 + (TPW - 1) * CS < NT) mfma_chunk<TPW, CS>(Xs, Ws, rt, ct0, l, acc);
     else if (TPW > 1) mfma_chunk<(TPW > 1 ? TPW - 1 : 1), CS>(Xs, Ws, rt, ct0, l, acc);
