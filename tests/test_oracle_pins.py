@@ -386,3 +386,16 @@ def test_isolated_new_node_has_the_closed_form_embedding(kind, agg):
         h = post["h"][l + 1][n:].astype(np.float64)
     if agg in ("max", "min"):
         assert (post["arg"][1][n:] == -1).all() and (post["alpha"][1][n:] == 0).all()
+
+
+def test_rows_differ_is_bitwise():
+    """The changed-node sets compare bit patterns (the reading of Sec. 2.5.2's "equal" that both
+    sides use): +0 and -0 differ, a NaN equals itself, and one differing element marks the row."""
+    a = np.array([[0.0, 1.0], [np.nan, 2.0], [3.0, 4.0], [5.0, 6.0]], np.float32)
+    b = np.array([[-0.0, 1.0], [np.nan, 2.0], [3.0, 4.0], [5.0, np.nextafter(np.float32(6.0), np.float32(7.0))]], np.float32)
+    assert oracle.rows_differ(a, b).tolist() == [True, False, False, True]
+    pre = dict(h=[a, a])
+    post = dict(h=[a, b])
+    ch = oracle.changed_nodes(pre, post)
+    assert ch[0].size == 0 and ch[1].tolist() == [0, 3] and ch[1].dtype == np.int32
+
