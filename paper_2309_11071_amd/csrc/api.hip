@@ -1192,7 +1192,6 @@ static ink_status apply_updates_impl(ink_ctx *c, const ink_edge_update *upd, int
   c->n_edges_now += n_ins - n_del;
   const int64_t n_seed = n_ins + n_del;
   const bool gcn = c->kind == INK_MODEL_GCN;
-  const bool keep_old = !c->is_select && !c->affected_mode;   // delta updates subtract the old message rows
   // nodes whose in-degree may have changed: their normalisation (GCN, mean) changes row-locally
   const int32_t *D = (const int32_t *)c->b_touch_in.p;
   const int64_t nD = (n_seed > 0 && (gcn || c->agg == INK_AGG_MEAN)) ? c->n_touched_in : 0;

@@ -738,7 +738,7 @@ ink_status graph_apply_batch(ink_ctx *c, int64_t n, int64_t *n_ins_out, int64_t 
   c->n_ins = c->n_del = 0;
   c->n_touched_in = 0;
   if (n == 0) return INK_OK;
-  if (n <= c->small_batch) return graph_apply_small(c, n, n_ins_out, n_del_out);
+  if (n <= c->small_batch && n <= kSmallBatch) return graph_apply_small(c, n, n_ins_out, n_del_out);
   const RawUpdate *raw = c->b_raw.as<RawUpdate>();
   size_t per = ((size_t)(n + 64) * 4 + 255) & ~(size_t)255;
   INK_TRYS(c->b_misc.reserve(per * 28));
