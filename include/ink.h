@@ -18,12 +18,17 @@
  *     needs.  Buffers returned by the library are library-owned DEVICE memory, valid until
  *     the next ink_apply_updates / ink_full_infer / ink_destroy on the same context.
  *   - Every call returns an ink_status.  On an argument / range / state error nothing in
- *     the context has been modified.  ink_last_error() gives a readable message.
+ *     the context has been modified.  INK_E_OOM or INK_E_DEVICE from a call that updates the
+ *     context (ink_apply_updates, ink_apply_updates_affected, ink_update_features,
+ *     ink_add_nodes) may leave the graph store or the cache half-written: the context is then
+ *     unusable, every later call on it returns INK_E_STATE, and it must be destroyed.
+ *     ink_last_error() gives a readable message.
  *   - One context = one HIP stream; calls on one context must not overlap.  All calls are
  *     synchronous: on return the work is complete.
  *   - Node ids are int32 in [0, n_nodes); the graph is a simple directed graph without self
- *     loops; n_nodes is fixed for the life of the context (the paper updates edges only,
- *     Sec. 2.1).  Edge (u -> v) makes u an in-neighbour of v: v aggregates m_u.
+ *     loops.  Edge batches never change n_nodes (the paper's update stream holds edges only,
+ *     Sec. 2.1); it grows only through ink_add_nodes, up to ink_options.node_capacity.
+ *     Edge (u -> v) makes u an in-neighbour of v: v aggregates m_u.
  *   - At most 2^31 - 2^30 - 1 edges (event offsets are 32-bit); a batch that could take the graph
  *     past that is refused.
  *   - All matrices are row-major float32.  Layer outputs are at most INK_MAX_OUT_DIM wide, layer
@@ -49,7 +54,7 @@ typedef enum {
   INK_OK = 0,
   INK_E_ARG = 1,    /* null pointer, bad dimension, malformed CSR, unsupported combination */
   INK_E_STATE = 2,  /* ink_apply_updates / ink_get_layer before ink_full_infer */
-  INK_E_OOM = 3,    /* device or host allocation failed */
+  INK_E_OOM = 3,    /* device or host allocation failed; from an updating call: destroy the context */
   INK_E_DEVICE = 4, /* a HIP call failed; the context must be destroyed */
   INK_E_RANGE = 5   /* node id or layer index out of range */
 } ink_status;
@@ -150,7 +155,10 @@ typedef struct {
   int64_t n_transformed; /* rows through the dense combination                              */
   int64_t n_changed;     /* rows whose layer output changed: next layer's sources           */
   /* MAX / MIN only: how the targets that were NOT recomputed split over the conditions of
-   * Sec. 2.5.1 (the distribution of Sec. 5.2); together with n_exposed they sum to n_targets */
+   * Sec. 2.5.1 (the distribution of Sec. 5.2); together with n_exposed they sum to n_targets.
+   * Aggregated rows wider than 256 columns are processed in 256-column blocks: the condition
+   * counters, n_exposed and n_alpha_changed then describe the first block of each target,
+   * n_regather_nb counts the neighbour rows of every block. */
   int64_t n_no_deletion;        /* only additions arrived                                    */
   int64_t n_deletion_no_effect; /* something was cancelled but no dimension needed a reset   */
   int64_t n_covered;            /* resets, all covered by added messages                     */
@@ -171,9 +179,8 @@ typedef struct {
 } ink_stats;
 
 /* Builds a context: copies graph, features ([n_nodes][feat_dim]) and weights to the device and
- * builds the device graph store (per-node in- and out-edge blocks with slack).  The paper's
- * method starts from "the result of an initial full graph inference" (Sec. 2): call
- * ink_full_infer next.  Errors: INK_E_ARG (malformed input), INK_E_RANGE (column id outside
+ * builds the device graph store (per-node in- and out-edge blocks with slack).  The method's
+ * input is a completed full inference of the initial snapshot (Sec. 2): call ink_full_infer next.  Errors: INK_E_ARG (malformed input), INK_E_RANGE (column id outside
  * [0, n)), INK_E_OOM. */
 ink_status ink_create(const ink_csr *graph, const float *features, int32_t feat_dim,
                       const ink_model *model, const ink_options *opts, ink_ctx **out);

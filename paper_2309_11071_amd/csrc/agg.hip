@@ -317,7 +317,7 @@ __global__ __launch_bounds__(64) void k_big_final(AggArgs a, const int32_t *big_
     bool ch = store_row<LPR>(o, v, lane_on, q, bv, bi, s2, j2, false, dum, dumi);
     if (compare && ch && chg && l == 0) {
       mark_bit(chg, v);
-      atomicAdd(&cnt->stripe[blockIdx.x % kStripes][ST_ACHG], 1ull);
+      if (a.count_cond) atomicAdd(&cnt->stripe[blockIdx.x % kStripes][ST_ACHG], 1ull);
     }
   }
 }
@@ -459,7 +459,7 @@ __device__ __forceinline__ void agg_events_one(const AggArgs &a, int v, int e0, 
     bool rs = (reset[0] || reset[1] || reset[2] || reset[3]) && lane_on;
     bool any_reset = __ballot(rs) != 0ull;
     bool dl = __ballot(any_del) != 0ull;
-    if (l == 0 && !exposed) {
+    if (l == 0 && !exposed && a.count_cond) {
       int which = !dl ? ST_NODEL : (!any_reset ? ST_NOEFFECT : ST_COVERED);
       atomicAdd(&cnt->stripe[blockIdx.x % kStripes][which], 1ull);
     }
@@ -467,7 +467,7 @@ __device__ __forceinline__ void agg_events_one(const AggArgs &a, int v, int e0, 
   if (exposed) {
     int deg = a.in_deg[v];
     if (l == 0) {
-      atomicAdd(&cnt->stripe[blockIdx.x % kStripes][ST_EXPOSED], 1ull);
+      if (a.count_cond) atomicAdd(&cnt->stripe[blockIdx.x % kStripes][ST_EXPOSED], 1ull);
       atomicAdd(&cnt->stripe[blockIdx.x % kStripes][ST_REGATHER], (unsigned long long)deg);
     }
     if (deg > a.big_deg) {
@@ -479,7 +479,7 @@ __device__ __forceinline__ void agg_events_one(const AggArgs &a, int v, int e0, 
   }
   RowOut o{a.A, a.ARG, a.UB, a.ARG2, a.ld, a.d};
   bool ch = store_row<LPR>(o, v, lane_on, q, nv, ni, nu, n2, true, ov, oi);
-  if (ch && l == 0) { mark_bit(chg, v); atomicAdd(&cnt->stripe[blockIdx.x % kStripes][ST_ACHG], 1ull); }
+  if (ch && l == 0) { mark_bit(chg, v); if (a.count_cond) atomicAdd(&cnt->stripe[blockIdx.x % kStripes][ST_ACHG], 1ull); }
 }
 
 // The grid is sized to what the chip holds at once; every wave walks the target list with the

@@ -265,7 +265,7 @@ __global__ __launch_bounds__(256) void k_sum_events(AggArgs a, const int32_t *ta
     nv.v[2] = __fadd_rn(o.z, acc.v[2]); nv.v[3] = __fadd_rn(o.w, acc.v[3]);
   }
   bool ch = store_sum<LPR>(a.A, a.ld, a.d, v, lane_on, q, nv, true);
-  if (ch && l == 0) { mark_bit_s(chg, v); atomicAdd(&cnt->stripe[blockIdx.x % kStripes][ST_ACHG], 1ull); }
+  if (ch && l == 0) { mark_bit_s(chg, v); if (a.count_cond) atomicAdd(&cnt->stripe[blockIdx.x % kStripes][ST_ACHG], 1ull); }
 }
 
 static int lanes_per_row(int ld) { return ld <= 64 ? 16 : (ld <= 128 ? 32 : 64); }

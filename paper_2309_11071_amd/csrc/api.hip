@@ -313,6 +313,12 @@ __global__ void k_any_adjacent_equal(const uint32_t *keys, int64_t n, int32_t *f
   if (i + 1 < n && keys[i] == keys[i + 1]) *flag = 1;
 }
 
+// any id outside [0, n_nodes) (a negative id is a huge unsigned one) -> *flag = 1
+__global__ void k_any_out_of_range(const uint32_t *ids, int64_t n, uint32_t n_nodes, int32_t *flag) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n && ids[i] >= n_nodes) *flag = 1;
+}
+
 // New input features for the nodes ids[i] (ascending); the caller's row of ids[i] is rows[perm[i]].
 // Writes the feature table with compare-and-emit: flag[i] = 1 if the row changed bitwise,
 // old_rows[i] = the previous row (optional), dense[i] = the new row padded to ld (optional).
@@ -398,6 +404,15 @@ static ink_status fail(ink_ctx *c, ink_status st, const std::string &msg) {
   if (c) c->err = msg; else g_create_err = msg;
   return st;
 }
+
+// An updating call that fails on the device side (allocation or HIP error) may have rewritten part of
+// the graph store or of the cache: the context is then marked unusable and every later call but
+// ink_last_error / ink_destroy returns INK_E_STATE.
+static ink_status seal(ink_ctx *c, ink_status st) {
+  if (st == INK_E_OOM || st == INK_E_DEVICE) c->broken = true;
+  return st;
+}
+static const char *kBrokenMsg = "the context is unusable after a failed update (INK_E_OOM / INK_E_DEVICE): destroy it";
 
 static hipError_t wait_published(ink_ctx *c, uint32_t seq);
 
@@ -503,6 +518,7 @@ static AggArgs agg_args(ink_ctx *c, int l) {       // layer l in 1..k
   a.is_min = c->is_min;
   a.big_deg = kBigDeg;
   a.big_grid = 2 * c->big_hint[l] + 1024;
+  a.count_cond = 1;
   return a;
 }
 
@@ -746,6 +762,7 @@ static AggArgs agg_block(const AggArgs &a, int b) {
   if (r.ARG) { r.ARG += c0; r.UB += c0; r.ARG2 += c0; }
   r.d = std::min(kAggBlock, a.d - c0);
   r.wd = round_up(r.d, 4);
+  r.count_cond = b == 0;      // a target's condition is tallied once, for its first block
   return r;
 }
 
@@ -796,6 +813,7 @@ static hipError_t gcn_final(ink_ctx *c, const int32_t *rows, int64_t n_rows, uin
 
 extern "C" ink_status ink_full_infer(ink_ctx *c) {
   if (!c) return INK_E_ARG;
+  if (c->broken) return fail(c, INK_E_STATE, kBrokenMsg);
   auto t0 = std::chrono::steady_clock::now();
   memset(&c->stats, 0, sizeof(c->stats));
   c->stats.n_layers = c->n_layers;
@@ -1146,17 +1164,19 @@ static ink_status apply_updates_impl(ink_ctx *c, const ink_edge_update *upd, int
 
 extern "C" ink_status ink_apply_updates(ink_ctx *c, const ink_edge_update *upd, int64_t n, ink_update_result *out) {
   if (!c) return INK_E_ARG;
+  if (c->broken) return fail(c, INK_E_STATE, kBrokenMsg);
   c->affected_mode = false;
-  return apply_updates_impl(c, upd, n, out);
+  return seal(c, apply_updates_impl(c, upd, n, out));
 }
 
 extern "C" ink_status ink_apply_updates_affected(ink_ctx *c, const ink_edge_update *upd, int64_t n,
                                                  ink_update_result *out) {
   if (!c) return INK_E_ARG;
+  if (c->broken) return fail(c, INK_E_STATE, kBrokenMsg);
   c->affected_mode = true;
   ink_status st = apply_updates_impl(c, upd, n, out);
   c->affected_mode = false;
-  return st;
+  return seal(c, st);
 }
 
 static ink_status apply_updates_impl(ink_ctx *c, const ink_edge_update *upd, int64_t n, ink_update_result *out) {
@@ -1228,9 +1248,17 @@ static ink_status apply_updates_impl(ink_ctx *c, const ink_edge_update *upd, int
 }
 
 // ------------------------------------------------------------------------------------ feature updates
+static ink_status update_features_impl(ink_ctx *c, const int32_t *node_ids, const float *rows, int64_t n,
+                                       ink_update_result *out);
 extern "C" ink_status ink_update_features(ink_ctx *c, const int32_t *node_ids, const float *rows, int64_t n,
                                           ink_update_result *out) {
   if (!c) return INK_E_ARG;
+  if (c->broken) return fail(c, INK_E_STATE, kBrokenMsg);
+  return seal(c, update_features_impl(c, node_ids, rows, n, out));
+}
+
+static ink_status update_features_impl(ink_ctx *c, const int32_t *node_ids, const float *rows, int64_t n,
+                                       ink_update_result *out) {
   if (!out || n < 0 || (n > 0 && (!node_ids || !rows))) return fail(c, INK_E_ARG, "ink_update_features: NULL argument or negative n");
   if (!c->inferred) return fail(c, INK_E_STATE, "ink_update_features: call ink_full_infer first");
   if (n > c->n) return fail(c, INK_E_ARG, "ink_update_features: more rows than nodes (ids must be distinct)");
@@ -1239,16 +1267,11 @@ extern "C" ink_status ink_update_features(ink_ctx *c, const int32_t *node_ids, c
   hipStream_t s = c->stream;
   c->affected_mode = false;
   const int d0 = c->H[0].d, ld0 = c->H[0].ld;
-  // validation before anything is touched: range on the host, distinctness on the sorted device copy
-  std::vector<int32_t> staged;
-  const int32_t *h = node_ids;
-  if (c->batch_dev && n > 0) {
-    staged.resize((size_t)n);
-    API_TRY(hipMemcpy(staged.data(), node_ids, (size_t)n * 4, hipMemcpyDeviceToHost));
-    h = staged.data();
-  }
-  for (int64_t i = 0; i < n; i++)
-    if (h[i] < 0 || h[i] >= c->n) return fail(c, INK_E_RANGE, "ink_update_features: node id out of range");
+  // validation before anything is touched: host-resident ids are range-checked here, device-resident
+  // ones by a kernel; distinctness is checked on the sorted device copy (one read-back for both)
+  if (!c->batch_dev)
+    for (int64_t i = 0; i < n; i++)
+      if (node_ids[i] < 0 || node_ids[i] >= c->n) return fail(c, INK_E_RANGE, "ink_update_features: node id out of range");
   memset(&c->stats, 0, sizeof(c->stats));
   c->stats.n_layers = c->n_layers;
   if (n == 0) return INK_OK;
@@ -1274,8 +1297,11 @@ extern "C" ink_status ink_update_features(ink_ctx *c, const int32_t *node_ids, c
     API_TRY(radix_sort_pairs(c->ws, ids, perm, n, c->id_bits, s));
     API_TRY(hipMemsetAsync(dc, 0, sizeof(Counters), s));
     hipLaunchKernelGGL(k_any_adjacent_equal, grid1(n), dim3(256), 0, s, (const uint32_t *)ids, n, &dc->v[C_TMP0]);
+    if (c->batch_dev)
+      hipLaunchKernelGGL(k_any_out_of_range, grid1(n), dim3(256), 0, s, (const uint32_t *)ids, n, (uint32_t)c->n, &dc->v[C_TMP1]);
     API_TRY(hipGetLastError());
     API_TRY(read_counters(c));
+    if (c->h_cnt->v[C_TMP1]) return fail(c, INK_E_RANGE, "ink_update_features: node id out of range");
     if (c->h_cnt->v[C_TMP0]) return fail(c, INK_E_ARG, "ink_update_features: a node id appears more than once");
     API_TRY(c->c_flag.reserve((size_t)n + 64));
     API_TRY(c->c_idx.reserve((size_t)n * 4));
@@ -1331,8 +1357,14 @@ __global__ void k_unpack_rows_at(const float *in, int d, int ld, int64_t row0, i
   table[(row0 + i) * ld + k] = k < d ? in[i * d + k] : 0.f;
 }
 
+static ink_status add_nodes_impl(ink_ctx *c, const float *features, int64_t n_new, ink_update_result *out);
 extern "C" ink_status ink_add_nodes(ink_ctx *c, const float *features, int64_t n_new, ink_update_result *out) {
   if (!c) return INK_E_ARG;
+  if (c->broken) return fail(c, INK_E_STATE, kBrokenMsg);
+  return seal(c, add_nodes_impl(c, features, n_new, out));
+}
+
+static ink_status add_nodes_impl(ink_ctx *c, const float *features, int64_t n_new, ink_update_result *out) {
   if (!out || n_new < 0 || (n_new > 0 && !features)) return fail(c, INK_E_ARG, "ink_add_nodes: NULL argument or negative n_new");
   if (!c->inferred) return fail(c, INK_E_STATE, "ink_add_nodes: call ink_full_infer first");
   if ((int64_t)c->n + n_new > c->n_cap) return fail(c, INK_E_RANGE, "ink_add_nodes: beyond ink_options.node_capacity");
@@ -1410,6 +1442,7 @@ extern "C" ink_status ink_add_nodes(ink_ctx *c, const float *features, int64_t n
 extern "C" ink_status ink_get_layer(ink_ctx *c, int32_t layer, int32_t which, int64_t row0, int64_t nrows, void *dst,
                                     int32_t dst_mem, int32_t *width_out) {
   if (!c) return INK_E_ARG;
+  if (c->broken) return fail(c, INK_E_STATE, kBrokenMsg);
   if (!c->inferred) return fail(c, INK_E_STATE, "ink_get_layer: call ink_full_infer first");
   if (layer < 0 || layer > c->n_layers || which < 0 || which > 4 || (which > 0 && layer == 0))
     return fail(c, INK_E_RANGE, "ink_get_layer: layer / which out of range");
@@ -1433,6 +1466,7 @@ extern "C" ink_status ink_get_layer(ink_ctx *c, int32_t layer, int32_t which, in
 
 extern "C" ink_status ink_get_graph(ink_ctx *c, int64_t *rowptr, int32_t *col) {
   if (!c || !rowptr) return INK_E_ARG;
+  if (c->broken) return fail(c, INK_E_STATE, kBrokenMsg);
   API_TRY(hipStreamSynchronize(c->stream));
   API_TRY(graph_export(c, rowptr, col));
   return INK_OK;

@@ -114,6 +114,7 @@ struct ink_ctx {
   bool batch_dev = false;
   bool affected_mode = false;        // current call is the affected-area recompute baseline
   bool is_select = true, is_min = false, inferred = false, own_stream = false;
+  bool broken = false;               // an updating call failed on the device side: state may be half-written
   hipStream_t stream = nullptr;
   std::string err;
 
@@ -187,6 +188,7 @@ struct AggArgs {
   bool is_min;
   int big_deg;                      // rows with more in-neighbours go to the chunked cooperative path
   int64_t big_grid;                 // workgroups to launch for the chunk kernel (it strides if there are more chunks)
+  int count_cond;                   // tally the per-target condition counters (only the first 256-column block of a wide row does)
 };
 // full re-aggregation of every node (targets == nullptr) or of a target list; flags rows whose
 // alpha changed in bitmap `chg` (may be null); big rows go through the cooperative path

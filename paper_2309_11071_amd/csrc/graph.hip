@@ -240,15 +240,22 @@ __global__ __launch_bounds__(256) void k_apply(const int32_t *nodes, const int32
                                                unsigned long long pool_base, float slack, int32_t *fill,
                                                int32_t *new_cnt, uint8_t *asc) {
   __shared__ int sm[kScanThreads / kWave + 1];
-  __shared__ long long s_newoff;
+  __shared__ long long s_off, s_newoff;
+  __shared__ int s_deg, s_cap;
   const int i = blockIdx.x;
   const int v = nodes[i];
   const int s0 = seg[i], s1 = seg[i + 1];
   const int ni = nd_ins[i], nd = nd_del[i];
   if (ni == 0 && nd == 0) return;
-  const int d0 = deg[v];
+  // The block's descriptor is read once, by one thread, and handed to the others through LDS;
+  // it is written back only after the last barrier.  (Every wave reading off / cap from global
+  // memory raced with the relocation below, which rewrites both.)
+  if (threadIdx.x == 0) { s_off = off[v]; s_deg = deg[v]; s_cap = cap[v]; }
+  __syncthreads();
+  const int d0 = s_deg;
+  const int cap0 = s_cap;
   const int d1 = d0 - nd;             // survivors of the old block
-  int64_t base = off[v];
+  int64_t base = s_off;
   if (nd > 0) {
     // survivors in the tail [d1, d0), in slot order -> fill[s0 ...]
     int carry = 0;
@@ -275,18 +282,16 @@ __global__ __launch_bounds__(256) void k_apply(const int32_t *nodes, const int32
       __syncthreads();
     }
   }
-  int d2 = d1 + ni;
-  if (d2 > cap[v]) {
-    if (threadIdx.x == 0) {
-      long long want = 2ll * cap[v];
-      long long extra = (long long)(d2 * (double)slack + 0.999);
-      if (extra < 4) extra = 4;
-      if (want < d2 + extra) want = d2 + extra;
-      want = (want + 3) & ~3ll;
-      s_newoff = (long long)(pool_base + atomicAdd(pool_used, (unsigned long long)want));
-      cap[v] = (int32_t)want;
-      off[v] = s_newoff;
-    }
+  const int d2 = d1 + ni;
+  const bool move = d2 > cap0;        // workgroup-uniform: taken from the LDS copy
+  long long want = cap0;
+  if (move) {
+    want = 2ll * cap0;
+    long long extra = (long long)(d2 * (double)slack + 0.999);
+    if (extra < 4) extra = 4;
+    if (want < d2 + extra) want = d2 + extra;
+    want = (want + 3) & ~3ll;
+    if (threadIdx.x == 0) s_newoff = (long long)(pool_base + atomicAdd(pool_used, (unsigned long long)want));
     __syncthreads();
     int64_t nb = s_newoff;
     for (int p = threadIdx.x; p < d1; p += blockDim.x) ids[nb + p] = ids[base + p];
@@ -306,6 +311,7 @@ __global__ __launch_bounds__(256) void k_apply(const int32_t *nodes, const int32
     }
   }
   if (threadIdx.x == 0) {
+    if (move) { cap[v] = (int32_t)want; off[v] = base; }
     deg[v] = d2;
     asc[v] = 0;              // holes were refilled from the tail / ids appended: order no longer known
     if (new_cnt) new_cnt[v] = ni;

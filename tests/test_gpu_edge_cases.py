@@ -273,3 +273,46 @@ def test_widest_feature_rows():
         h.step(op, bs, bd)
     h.check_state()
     h.ink.close()
+
+
+@pytest.mark.parametrize("small_batch_limit", [0, -1])
+def test_many_blocks_relocate_in_one_batch(small_batch_limit):
+    """Hundreds of nodes outgrow their edge block in the same batch, with insertions only: every
+    workgroup of the apply kernel takes the relocation branch without any earlier barrier, which
+    is the case in which the waves of a workgroup must agree on the block's old place and size."""
+    n, d = 4000, 4
+    rng = np.random.default_rng(5)
+    X = rng.standard_normal((n, d)).astype(np.float32)
+    src, dst = arr([1, 2, 3]), arr([0, 0, 0])
+    h = Harness(graph=(n, src, dst), X=X, model=tiny_model("sage", "max", (d, 4, 4)), slack=0.01,
+                small_batch_limit=small_batch_limit)
+    for r in range(3):
+        # 500 destinations and 500 sources gain 7 edges each: far more than the 4 spare slots of a block
+        ops = []
+        for v in range(100, 600):
+            for j in range(7):
+                ops.append((INS, 1000 + (v * 7 + j + 53 * r) % 2900, v))
+        ops = [o for o in dict.fromkeys(ops) if o[1] != o[2]]
+        run(h, ops[:3900] if small_batch_limit == 0 else ops)
+        h.check_graph()
+        h.check_state()
+    h.ink.close()
+
+
+def test_condition_counters_of_rows_wider_than_one_block():
+    """Aggregated rows of 300 columns are processed as two column blocks; a target's condition
+    is tallied once, so the four classes still partition the targets (Sec. 5.2)."""
+    dims = (300, 16, 8)
+    cfg = synth.WorkloadConfig(6, "t", "sage", "max", 500, 6000, False, dims, 8, 80, True)
+    src, dst = synth.make_graph(cfg)
+    X = np.random.default_rng(11).standard_normal((cfg.n_nodes, dims[0])).astype(np.float32)
+    h = Harness(cfg=cfg, graph=(cfg.n_nodes, src, dst), X=X, model=tiny_model("sage", "max", dims, seed=4))
+    for b in range(3):
+        op, bs, bd = h.sampler.next_batch()
+        h.step(op, bs, bd)
+        L = h.ink.stats()["layers"][0]
+        assert L["n_targets"] > 0
+        assert L["n_no_deletion"] + L["n_deletion_no_effect"] + L["n_covered"] + L["n_exposed"] == L["n_targets"]
+        assert L["n_alpha_changed"] <= L["n_targets"]
+    h.check_state()
+    h.ink.close()
