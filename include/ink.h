@@ -190,6 +190,23 @@ ink_status ink_create(const ink_csr *graph, const float *features, int32_t feat_
  * rebuild the cache from the current graph. */
 ink_status ink_full_infer(ink_ctx *ctx);
 
+/* ink_full_infer for callers that cannot allocate device memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid it): same arguments, same result, bit for bit, but
+ * the call makes no hipMalloc / hipFree (nor any other allocating call).  The work memory that
+ * ink_full_infer takes from the allocator -- the list of long rows, the plan and the partial
+ * rows of their chunks, GIN's staging rows -- lies in one static device array of
+ * INK_NOALLOC_SCRATCH_BYTES bytes per GPU, which that GPU holds until the process ends; the
+ * per-kernel-class timing of ink_stats is off during the call.  Every context on a GPU shares
+ * the array: calls of this entry point that overlap on one GPU race (calls on one context never
+ * overlap anyway).  Nothing in the array is expected to be zero between calls.
+ * Errors: INK_E_RANGE if the graph and model need more than the array holds -- the need is
+ * 4 (R + 1) + 4 (R + 2) + p w (E / 1024 + R) 4 bytes plus, for GIN, 4 n_nodes hidden, with
+ * E the edge count, R = min(node capacity, max(E / 256, 8192)) + 1 the bound on long rows, w the
+ * widest aggregated row (at most 256) and p = 4 tables for MAX / MIN, 1 otherwise; then use
+ * ink_full_infer.  Otherwise as ink_full_infer. */
+#define INK_NOALLOC_SCRATCH_BYTES (64u << 20)
+ink_status ink_full_infer_noalloc(ink_ctx *ctx);
+
 /* Applies an ordered list of n updates and incrementally refreshes every layer (Sec. 2.3).
  * The post-update snapshot is the net effect of the list on the edge set.  `updates` is a host
  * or device array according to ink_options.mem.  n = 0 is allowed (empty result).

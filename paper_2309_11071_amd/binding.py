@@ -95,6 +95,8 @@ def load_library():
     lib.ink_create.restype = C.c_int
     lib.ink_full_infer.argtypes = [vp]
     lib.ink_full_infer.restype = C.c_int
+    lib.ink_full_infer_noalloc.argtypes = [vp]
+    lib.ink_full_infer_noalloc.restype = C.c_int
     lib.ink_apply_updates.argtypes = [vp, vp, C.c_int64, C.POINTER(_Result)]
     lib.ink_apply_updates.restype = C.c_int
     lib.ink_apply_updates_affected.argtypes = [vp, vp, C.c_int64, C.POINTER(_Result)]
@@ -180,6 +182,9 @@ class Ink:
 
     def full_infer(self):
         self._check(self._lib.ink_full_infer(self._h))
+
+    def full_infer_noalloc(self):
+        self._check(self._lib.ink_full_infer_noalloc(self._h))
 
     def apply_updates(self, updates, fetch=True, affected=False):
         """updates: structured array (EDGE_UPDATE_DTYPE).  Returns dict; with fetch the changed ids

@@ -5,10 +5,12 @@
 #include <algorithm>
 #include <chrono>
 #include <cstring>
+#include <cstdio>
+#include <mutex>
 #include <new>
 #include <vector>
 
-#include "ctx.h"
+#include "bigrows.h"
 
 using namespace ink;
 
@@ -559,6 +561,38 @@ static hipError_t run_transform(ink_ctx *c, int l, const int32_t *rows, int64_t 
   return xform_run(c, y);
 }
 
+// ------------------------------------------------------------------------------------ static work memory
+// Work memory of ink_full_infer_noalloc: the list of long rows, its chunk prefix, the partial rows
+// of the chunks, the block sums of the scan that plans them and GIN's staging rows.  One array per
+// GPU for the life of the process, shared by every call on that GPU.  Nothing in it has to start
+// from zero: every part is written by the launch that reads it afterwards.
+static __device__ __align__(256) unsigned char scratch[INK_NOALLOC_SCRATCH_BYTES];
+
+// device address of `scratch` per GPU, looked up once with that GPU current (ink_create does it);
+// host code uses these pointers, never the array's name
+constexpr int kMaxDevices = 64;
+static void *g_scratch_ptr[kMaxDevices];
+static std::mutex g_scratch_mu;
+
+static hipError_t scratch_lookup(int *dev_out, void **ptr_out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void *p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    g_scratch_ptr[dev] = p;
+  }
+  if (dev_out) *dev_out = dev;
+  if (ptr_out) *ptr_out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
+
+static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
 // ------------------------------------------------------------------------------------ create
 // Event records of a layer are addressed with 32-bit offsets: at most one per edge plus one per
 // list entry of the batch (below 2^30), so the edge count is held below 2^31 - 2^30.
@@ -643,6 +677,7 @@ extern "C" ink_status ink_create(const ink_csr *g, const float *features, int32_
   } while (0)
   if (opts && opts->hip_stream) c->stream = (hipStream_t)opts->hip_stream;
   else { CREATE_TRY(hipStreamCreate(&c->stream)); c->own_stream = true; }
+  CREATE_TRY(scratch_lookup(&c->device, &c->scratch));
   CREATE_TRY(graph_build(c, rowptr.data(), col.data()));
   const int64_t nc = c->n_cap;     // every per-node array is allocated for the capacity
   CREATE_TRY(hipMalloc(&c->new_out, (size_t)nc * 4));
@@ -811,9 +846,7 @@ static hipError_t gcn_final(ink_ctx *c, const int32_t *rows, int64_t n_rows, uin
   return hipGetLastError();
 }
 
-extern "C" ink_status ink_full_infer(ink_ctx *c) {
-  if (!c) return INK_E_ARG;
-  if (c->broken) return fail(c, INK_E_STATE, kBrokenMsg);
+static ink_status full_infer_impl(ink_ctx *c) {
   auto t0 = std::chrono::steady_clock::now();
   memset(&c->stats, 0, sizeof(c->stats));
   c->stats.n_layers = c->n_layers;
@@ -849,6 +882,60 @@ extern "C" ink_status ink_full_infer(ink_ctx *c) {
   c->inferred = true;
   c->stats.ms_total = std::chrono::duration<float, std::milli>(std::chrono::steady_clock::now() - t0).count();
   return INK_OK;
+}
+
+extern "C" ink_status ink_full_infer(ink_ctx *c) {
+  if (!c) return INK_E_ARG;
+  if (c->broken) return fail(c, INK_E_STATE, kBrokenMsg);
+  return seal(c, full_infer_impl(c));
+}
+
+// ------------------------------------------------------------------------------------ full inference without allocation
+extern "C" ink_status ink_full_infer_noalloc(ink_ctx *c) {
+  if (!c) return INK_E_ARG;
+  if (c->broken) return fail(c, INK_E_STATE, kBrokenMsg);
+  void *base = c->scratch;
+  if (!base) return fail(c, INK_E_DEVICE, "ink_full_infer_noalloc: the scratch array's address was not found at ink_create");
+  // what the full inference reserves, from the same bounds its kernels' launchers use
+  int wd_max = 0, n1p_max = 0;
+  for (int l = 1; l <= c->n_layers; l++) {
+    wd_max = std::max(wd_max, std::min(round_up(c->A[l].d, 4), kAggBlock));
+    if (c->kind == INK_MODEL_GIN) n1p_max = std::max(n1p_max, c->layers[l - 1].N1p);
+  }
+  const size_t list_b = align256((size_t)big_rows_capacity(c) * 4);
+  const size_t pref_b = align256((list_b / 4 + 1) * 4);
+  const size_t part_b = align256((size_t)big_chunk_capacity(c) * wd_max * 4);
+  const int n_part = c->is_select ? 4 : 1;
+  const size_t blk_b = align256((size_t)nblocks((int64_t)(list_b / 4), kScanTile) * 4);
+  const size_t stage_b = align256((size_t)c->n * n1p_max * 4);
+  const size_t need = list_b + pref_b + (size_t)n_part * part_b + blk_b + stage_b;
+  if (need > (size_t)INK_NOALLOC_SCRATCH_BYTES) {
+    char msg[256];
+    snprintf(msg, sizeof(msg), "ink_full_infer_noalloc: this graph and model need %zu bytes of work memory, the static "
+             "scratch holds %zu: use ink_full_infer", need, (size_t)INK_NOALLOC_SCRATCH_BYTES);
+    return fail(c, INK_E_RANGE, msg);
+  }
+  // lend the carve-outs to the buffers the kernels' launchers use, run, and put the owners back
+  DevBuf *bufs[] = {&c->big_list, &c->big_pref, &c->big_part_v, &c->big_part_i, &c->big_part_s, &c->big_part_j,
+                    &c->ws.blk, &c->stage0};
+  const size_t sizes[] = {list_b, pref_b, part_b, c->is_select ? part_b : 0, c->is_select ? part_b : 0,
+                          c->is_select ? part_b : 0, blk_b, stage_b};
+  constexpr int NB = sizeof(bufs) / sizeof(bufs[0]);
+  DevBuf saved[NB];
+  size_t used = 0;
+  for (int i = 0; i < NB; i++) {
+    saved[i] = *bufs[i];
+    bufs[i]->p = sizes[i] ? (char *)base + used : nullptr;
+    bufs[i]->cap = sizes[i];
+    bufs[i]->fixed = true;
+    used += sizes[i];
+  }
+  const int profile = c->profile;
+  c->profile = 0;                    // HIP events are created on demand: not in this call
+  ink_status st = full_infer_impl(c);
+  c->profile = profile;
+  for (int i = 0; i < NB; i++) *bufs[i] = saved[i];
+  return seal(c, st);
 }
 
 // ------------------------------------------------------------------------------------ updates

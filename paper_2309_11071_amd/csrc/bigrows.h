@@ -14,10 +14,21 @@ namespace ink {
 
 constexpr int kBigGrid = 4096;             // workgroups of the per-row combine kernel
 
-// upper bound of the chunks any launch can need: every long row has at most deg / chunk + 1
+// Few targets (small batches): latency matters more than throughput, so rows are handed to the
+// cooperative path much earlier and each chunk is shared by 16 waves instead of 4.
+constexpr int kLatencyTargets = 8192;
+
+// upper bound of the long rows one launch can list: with at most kLatencyTargets targets every
+// target may be one, otherwise a long row has more than kBigDeg in-neighbours; never more than nodes
+inline int64_t big_rows_capacity(const ink_ctx *c) {
+  int64_t e = c->n_edges_now > c->n_edges ? c->n_edges_now : c->n_edges;
+  int64_t r = e / kBigDeg > kLatencyTargets ? e / kBigDeg : kLatencyTargets;
+  return (r < c->n_cap ? r : c->n_cap) + 1;
+}
+// ... and of their chunks: a row of deg neighbours has at most deg / chunk + 1
 inline int64_t big_chunk_capacity(const ink_ctx *c) {
   int64_t e = c->n_edges_now > c->n_edges ? c->n_edges_now : c->n_edges;
-  return e / kBigChunk + e / kBigDeg + 32768;
+  return e / kBigChunk + big_rows_capacity(c);
 }
 
 // one workgroup per expected chunk (the hardware balances them); never fewer than fill the chip
@@ -30,9 +41,7 @@ inline unsigned big_partial_grid(const ink_ctx *c, int64_t want, int block_threa
 
 // buffers of the long-row path; call before the kernel that fills the list (growing drops contents)
 inline hipError_t ensure_big_buffers(ink_ctx *c, int ld, bool with_ids) {
-  int64_t e = c->n_edges_now > c->n_edges ? c->n_edges_now : c->n_edges;
-  int64_t rows = e / kBigDeg + 32768;
-  INK_TRY(c->big_list.reserve((size_t)rows * 4));
+  INK_TRY(c->big_list.reserve((size_t)big_rows_capacity(c) * 4));
   INK_TRY(c->big_pref.reserve((size_t)(c->big_list.cap / 4 + 1) * 4));
   int64_t cap = big_chunk_capacity(c);
   INK_TRY(c->big_part_v.reserve((size_t)cap * ld * sizeof(float)));
@@ -44,9 +53,6 @@ inline hipError_t ensure_big_buffers(ink_ctx *c, int ld, bool with_ids) {
   return hipSuccess;
 }
 
-// Few targets (small batches): latency matters more than throughput, so rows are handed to the
-// cooperative path much earlier and each chunk is shared by 16 waves instead of 4.
-constexpr int kLatencyTargets = 8192;
 inline bool latency_mode(int64_t n_targets) { return n_targets <= kLatencyTargets; }
 inline int big_threshold(int64_t n_targets, int lanes_per_row, int throughput_deg) {
   return latency_mode(n_targets) ? 32 * (kWave / lanes_per_row) : throughput_deg;

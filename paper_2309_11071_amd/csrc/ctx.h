@@ -116,6 +116,8 @@ struct ink_ctx {
   bool is_select = true, is_min = false, inferred = false, own_stream = false;
   bool broken = false;               // an updating call failed on the device side: state may be half-written
   hipStream_t stream = nullptr;
+  int device = 0;                    // HIP device the context lives on
+  void *scratch = nullptr;           // that device's copy of the static work array of ink_full_infer_noalloc
   std::string err;
 
   ink::GraphSide gin, gout;

@@ -15,8 +15,10 @@ constexpr int kScanTile = kScanThreads * kScanItems;   // items per workgroup
 struct DevBuf {            // grow-only device buffer (contents are NOT kept across growth)
   void *p = nullptr;
   size_t cap = 0;
+  bool fixed = false;      // p is borrowed memory of exactly cap bytes: never freed, never grown
   hipError_t reserve(size_t bytes) {
     if (bytes <= cap) return hipSuccess;
+    if (fixed) return hipErrorOutOfMemory;
     if (p) { hipError_t e = hipFree(p); p = nullptr; cap = 0; if (e != hipSuccess) return e; }
     size_t want = bytes + bytes / 4 + 256;
     hipError_t e = hipMalloc(&p, want);
@@ -24,7 +26,7 @@ struct DevBuf {            // grow-only device buffer (contents are NOT kept acr
     cap = want;
     return hipSuccess;
   }
-  void release() { if (p) (void)hipFree(p); p = nullptr; cap = 0; }
+  void release() { if (p && !fixed) (void)hipFree(p); p = nullptr; cap = 0; fixed = false; }
   template <class T> T *as() const { return reinterpret_cast<T *>(p); }
 };
 
