@@ -93,29 +93,36 @@ void orc_agg_gcn_sym(int64_t n, const int64_t *rowptr, const int32_t *col, const
  * mode 1: float accumulator starting at +0, one fused multiply-add per k in ascending order,
  *         then a float add of the bias: the fp32 evaluation order used when an integer decision
  *         (changed set, argmax) downstream must be taken in the same precision as fp32 hardware.
+ *         The loop over the outputs j is the inner one here (each y[r][j] is its own accumulator
+ *         and still receives k = 0, 1, 2, ... in that order), so that the compiler may work on
+ *         several outputs at once: the full-size parity runs push 10^10 such chains through it.
  * relu: x > 0 ? x : +0. */
 void orc_linear(int64_t rows, int32_t din, int32_t dout, const float *x, const float *W,
                 const float *bias, int32_t relu, int32_t mode, float *y)
 {
 #pragma omp parallel for schedule(static)
     for (int64_t r = 0; r < rows; r++) {
-        for (int32_t j = 0; j < dout; j++) {
-            float out;
-            if (mode == 0) {
+        if (mode == 0) {
+            for (int32_t j = 0; j < dout; j++) {
                 double acc = 0.0;
                 for (int32_t k = 0; k < din; k++)
                     acc += (double)x[r * din + k] * (double)W[(int64_t)k * dout + j];
                 if (bias) acc += (double)bias[j];
-                out = (float)acc;
-            } else {
-                float acc = 0.0f;
-                for (int32_t k = 0; k < din; k++)
-                    acc = fmaf(x[r * din + k], W[(int64_t)k * dout + j], acc);
-                if (bias) acc = acc + bias[j];
-                out = acc;
+                y[r * dout + j] = (float)acc;
             }
-            if (relu) out = out > 0.0f ? out : 0.0f;
-            y[r * dout + j] = out;
+        } else {
+            float *acc = y + r * dout;
+            for (int32_t j = 0; j < dout; j++) acc[j] = 0.0f;
+            for (int32_t k = 0; k < din; k++) {
+                const float xv = x[r * din + k];
+                const float *w = W + (int64_t)k * dout;
+                for (int32_t j = 0; j < dout; j++) acc[j] = fmaf(xv, w[j], acc[j]);
+            }
+            if (bias)
+                for (int32_t j = 0; j < dout; j++) acc[j] = acc[j] + bias[j];
         }
+        if (relu)
+            for (int32_t j = 0; j < dout; j++)
+                y[r * dout + j] = y[r * dout + j] > 0.0f ? y[r * dout + j] : 0.0f;
     }
 }
