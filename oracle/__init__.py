@@ -95,8 +95,24 @@ def aggregate(rowptr, col, m, agg):
     raise ValueError(agg)
 
 
-def transform(model, l, alpha, h_prev, precision="f64"):
-    """Combination + activation of layer l (0-based): h_l = act(T(alpha_l, h_{l-1})) (Sec. 2.2 item 2)."""
+def transform(model, l, alpha, h_prev, precision="f64", user=None):
+    """Combination + activation of layer l (0-based): h_l = act(T(alpha_l, h_{l-1})) (Sec. 2.2 item 2).
+
+    user: optional [n][out_dim] term of user-defined events (Sec. 2.6; Sec. 3.2 shows the use: a
+    user_apply step adds a user-supplied per-node term to the tensor between the linear map and the
+    activation): h_l = act(T(alpha_l, h_{l-1}) + user).  It is added to the rounded result of the
+    linear map, in fp64 (precision "f64") or as one fp32 addition ("f32"), before the activation."""
+    if user is not None:
+        L = model["layers"][l]
+        lin = dict(model, layers=[dict(x, act="none") if i == l else x for i, x in enumerate(model["layers"])])
+        y = transform(lin, l, alpha, h_prev, precision)
+        if precision == "f64":
+            y = (y.astype(np.float64) + np.asarray(user, np.float64)).astype(np.float32)
+        else:
+            y = y + np.asarray(user, np.float32)
+        if L["act"] == "relu":
+            y = np.where(y > 0, y, np.float32(0.0)).astype(np.float32)
+        return y
     L = model["layers"][l]
     relu = L["act"] == "relu"
     kind = model["kind"]
@@ -117,16 +133,46 @@ def transform(model, l, alpha, h_prev, precision="f64"):
     raise ValueError(kind)
 
 
-def full_infer(rowptr, col, X, model, precision="f64"):
-    """Plain inference.  Returns dict with lists h[0..k], alpha[1..k] (index 0 unused), arg[1..k]."""
+def full_infer(rowptr, col, X, model, precision="f64", user_terms=None):
+    """Plain inference.  Returns dict with lists h[0..k], alpha[1..k] (index 0 unused), arg[1..k].
+    user_terms: optional list, entry l - 1 = the [n][out_dim_l] term of layer l or None (see transform)."""
     h = [np.ascontiguousarray(X, dtype=np.float32)]
     alpha, arg = [None], [None]
     for l in range(len(model["layers"])):
         a, g = aggregate(rowptr, col, h[l], model["agg"])      # m_{l+1} = h_l (aggregate first)
         alpha.append(a)
         arg.append(g)
-        h.append(transform(model, l, a, h[l], precision))
+        u = None if user_terms is None else user_terms[l]
+        h.append(transform(model, l, a, h[l], precision) if u is None else transform(model, l, a, h[l], precision, user=u))
     return dict(h=h, alpha=alpha, arg=arg)
+
+
+USER_SET, USER_ADD, USER_CLEAR = 0, 1, 2
+
+
+def apply_user_events(user_terms, widths, n, events, rows):
+    """Net effect of an ordered list of user-defined events (Sec. 2.6) on the per-layer user terms.
+
+    events: iterable of (layer 1..k, target, op); rows[i] = the event's row (its first width_l
+    entries count).  Events are grouped by (layer, target) and applied in list order to that node's
+    term: set replaces it, add adds to it (one fp32 addition per event), clear zeroes it.  Returns
+    a new list of terms (a layer never touched stays None)."""
+    out = [None if t is None else t.copy() for t in user_terms]
+    for (layer, target, op), row in zip(events, rows):
+        w = widths[layer - 1]
+        if out[layer - 1] is None:
+            out[layer - 1] = np.zeros((n, w), np.float32)
+        t = out[layer - 1]
+        r = np.asarray(row, np.float32)[:w]
+        if op == USER_SET:
+            t[target] = r
+        elif op == USER_ADD:
+            t[target] = t[target] + r
+        elif op == USER_CLEAR:
+            t[target] = 0.0
+        else:
+            raise ValueError(op)
+    return out
 
 
 def rows_differ(a, b):

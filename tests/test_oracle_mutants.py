@@ -8,7 +8,8 @@ import oracle
 import test_oracle_pins as pins
 
 REAL = {name: getattr(oracle, name) for name in
-        ("agg_select", "agg_sum", "agg_gcn_sym", "linear", "transform", "apply_batch", "rows_differ")}
+        ("agg_select", "agg_sum", "agg_gcn_sym", "linear", "transform", "apply_batch", "rows_differ",
+         "apply_user_events")}
 
 
 def _nb_lists(rowptr, col):
@@ -163,6 +164,25 @@ def rows_differ_by_value(a, b):
     return (np.asarray(a, np.float32) != np.asarray(b, np.float32)).any(axis=1)
 
 
+def transform_user_term_after_the_activation(model, l, alpha, h_prev, precision="f64", user=None):
+    y = REAL["transform"](model, l, alpha, h_prev, precision)
+    return y if user is None else (y + np.asarray(user, np.float32)).astype(np.float32)
+
+
+def transform_ignores_the_user_term(model, l, alpha, h_prev, precision="f64", user=None):
+    return REAL["transform"](model, l, alpha, h_prev, precision)
+
+
+def user_events_add_acts_as_set(user_terms, widths, n, events, rows):
+    events = [(l, t, oracle.USER_SET if op == oracle.USER_ADD else op) for l, t, op in events]
+    return REAL["apply_user_events"](user_terms, widths, n, events, rows)
+
+
+def user_events_ignore_the_layer(user_terms, widths, n, events, rows):
+    events = [(1, t, op) for l, t, op in events]
+    return REAL["apply_user_events"](user_terms, widths, n, events, rows)
+
+
 def _call(fn, *args):
     return lambda: fn(*args)
 
@@ -180,6 +200,10 @@ ALL_MODEL = [pins.test_full_infer_sage_against_dense_formula, pins.test_full_inf
              pins.test_full_infer_gcn_against_dense_formula,
              pins.test_one_layer_model_is_one_aggregation_and_one_linear_map]
 ALL_BATCH = [pins.test_apply_batch_net_effect]
+ALL_USER = [_call(pins.test_user_term_is_added_before_the_activation, "sage", "max"),
+            _call(pins.test_user_term_is_added_before_the_activation, "gin", "sum"),
+            pins.test_user_events_group_by_layer_and_target_in_list_order,
+            pins.test_a_user_event_stays_in_the_out_neighbourhood]
 ALL_DIFF = [_call(pins.test_update_invariants, "sage", "max"), pins.test_rows_differ_is_bitwise]
 
 MUTANTS = [
@@ -201,6 +225,10 @@ MUTANTS = [
     ("transform", transform_no_relu_on_hidden_layers, ALL_MODEL),
     ("transform", transform_gin_eps_sign, ALL_MODEL),
     ("transform", transform_gin_forgets_inner_relu, ALL_MODEL),
+    ("transform", transform_user_term_after_the_activation, ALL_USER),
+    ("transform", transform_ignores_the_user_term, ALL_USER),
+    ("apply_user_events", user_events_add_acts_as_set, ALL_USER),
+    ("apply_user_events", user_events_ignore_the_layer, ALL_USER),
     ("apply_batch", batch_first_op_wins, ALL_BATCH),
     ("apply_batch", batch_accepts_self_loops, ALL_BATCH),
     ("rows_differ", rows_differ_by_value, ALL_DIFF),

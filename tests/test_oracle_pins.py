@@ -399,3 +399,72 @@ def test_rows_differ_is_bitwise():
     ch = oracle.changed_nodes(pre, post)
     assert ch[0].size == 0 and ch[1].tolist() == [0, 3] and ch[1].dtype == np.int32
 
+
+
+# ---- user-defined events (Sec. 2.6): a per-node term added between the linear map and the activation
+def _user_case(kind, agg, seed=0):
+    rng = np.random.default_rng(seed)
+    n, dims = 30, (5, 6, 4)
+    cfg = synth.WorkloadConfig(9, "t", kind, agg, n, 120, False, dims, 7, 4, False)
+    src, dst = synth.make_graph(cfg)
+    rp, col = synth.in_csr_from_edges(n, src, dst)
+    X = rng.standard_normal((n, dims[0])).astype(np.float32)
+    model = synth.make_model(cfg, bias_scale=0.3)
+    return n, dims, rp, col, X, model, rng
+
+
+@pytest.mark.parametrize("kind,agg", [("sage", "max"), ("gin", "sum")])
+def test_user_term_is_added_before_the_activation(kind, agg):
+    n, dims, rp, col, X, model, rng = _user_case(kind, agg)
+    base = oracle.full_infer(rp, col, X, model, "f64")
+    none = oracle.full_infer(rp, col, X, model, "f64", [None, None])
+    zero = oracle.full_infer(rp, col, X, model, "f64", [np.zeros((n, dims[1]), np.float32), None])
+    for a, b, c in zip(base["h"], none["h"], zero["h"]):
+        assert np.array_equal(a, b) and np.array_equal(a, c)
+    # last layer has no activation: its term shifts the output by exactly that term (up to the final rounding)
+    u2 = rng.standard_normal((n, dims[2])).astype(np.float32)
+    out = oracle.full_infer(rp, col, X, model, "f64", [None, u2])
+    assert np.array_equal(out["h"][1], base["h"][1])
+    want = base["h"][2].astype(np.float64) + u2
+    assert np.allclose(out["h"][2], want, rtol=0, atol=2e-6 * np.abs(want).max())
+    # hidden layer: the activation comes after the term -- a very negative term zeroes the row, and the
+    # dense closed form act(lin + u) holds with a library matmul
+    u1 = np.zeros((n, dims[1]), np.float32)
+    u1[3] = -1e6
+    u1[7] = rng.standard_normal(dims[1])
+    out = oracle.full_infer(rp, col, X, model, "f64", [u1, None])
+    assert np.all(out["h"][1][3] == 0.0)
+    lin = dict(model, layers=[dict(model["layers"][0], act="none"), model["layers"][1]])
+    pre = oracle.transform(lin, 0, base["alpha"][1], X, "f64").astype(np.float64)
+    assert np.allclose(out["h"][1], np.maximum(pre + u1, 0.0), rtol=0, atol=1e-5)
+    others = np.ones(n, bool); others[[3, 7]] = False
+    assert np.array_equal(out["h"][1][others], base["h"][1][others])
+
+
+def test_user_events_group_by_layer_and_target_in_list_order():
+    widths, n = (3, 2), 5
+    r = lambda *x: np.array(x + (9.0,) * (3 - len(x)), np.float32)
+    ev = [(1, 2, oracle.USER_SET), (2, 2, oracle.USER_ADD), (1, 2, oracle.USER_ADD), (1, 4, oracle.USER_ADD),
+          (1, 4, oracle.USER_CLEAR), (1, 4, oracle.USER_ADD), (2, 0, oracle.USER_SET), (2, 0, oracle.USER_CLEAR)]
+    rows = [r(1, 2, 3), r(5, 6), r(10, 20, 30), r(1, 1, 1), r(0, 0, 0), r(7, 8, 9), r(4, 4), r(0, 0)]
+    out = oracle.apply_user_events([None, None], widths, n, ev, rows)
+    want1 = np.zeros((5, 3), np.float32); want1[2] = (11, 22, 33); want1[4] = (7, 8, 9)
+    want2 = np.zeros((5, 2), np.float32); want2[2] = (5, 6)            # only the first width_l entries of a row count
+    assert np.array_equal(out[0], want1) and np.array_equal(out[1], want2)
+    again = oracle.apply_user_events(out, widths, n, [(1, 2, oracle.USER_CLEAR), (1, 4, oracle.USER_CLEAR), (2, 2, oracle.USER_CLEAR)],
+                                     [r(0), r(0), r(0)])
+    assert not again[0].any() and not again[1].any()
+    assert np.array_equal(out[0], want1)                                # the input terms are not modified
+
+
+def test_a_user_event_stays_in_the_out_neighbourhood():
+    n, dims, rp, col, X, model, rng = _user_case("sage", "max", seed=4)
+    base = oracle.full_infer(rp, col, X, model, "f32")
+    u1 = np.zeros((n, dims[1]), np.float32)
+    u1[5] = rng.standard_normal(dims[1]) * 3
+    out = oracle.full_infer(rp, col, X, model, "f32", [u1, None])
+    ch1 = np.nonzero(oracle.rows_differ(base["h"][1], out["h"][1]))[0]
+    assert set(ch1.tolist()) <= {5}
+    outn = {5} | {v for v in range(n) if 5 in col[rp[v]:rp[v + 1]].tolist()}      # 5 and the nodes that aggregate it
+    ch2 = np.nonzero(oracle.rows_differ(base["h"][2], out["h"][2]))[0]
+    assert set(ch2.tolist()) <= outn
