@@ -226,3 +226,47 @@ def csr_from_keys(n, keys):
     rowptr = np.zeros(n + 1, dtype=np.int64)
     np.cumsum(np.bincount(dst, minlength=n), out=rowptr[1:])
     return rowptr, (keys & 0xFFFFFFFF).astype(np.int32)
+
+
+def affected_area(n, out_rowptr, out_col, changed_dst, k):
+    """Theoretical affected area of a batch (Sec. 1, Fig. "Inference on a streaming graph" (b);
+    Sec. 4.1 "Affected"): layer 1 can change only at the destinations of the changed edges; layer l
+    at those of layer l - 1, at their out-neighbours, and again at the changed destinations.
+    out_rowptr / out_col: out-neighbour CSR of the NEW snapshot.  Returns k ascending id arrays."""
+    seed = np.unique(np.asarray(changed_dst, np.int64))
+    areas, cur = [], seed
+    for l in range(k):
+        if l > 0:
+            nb = [out_col[out_rowptr[v]:out_rowptr[v + 1]] for v in cur.tolist()]
+            cur = np.unique(np.concatenate([cur, seed] + [x.astype(np.int64) for x in nb])) if nb else seed
+        areas.append(cur.astype(np.int32))
+    return areas
+
+
+def affected_infer(rowptr, col, X, model, prev, areas, precision="f64"):
+    """The "Affected" baseline (Sec. 4.1): inference on the theoretically affected area only.  Every
+    node of areas[l] is recomputed at layer l + 1 from its whole neighbourhood in the new snapshot
+    (rowptr, col) whether or not anything it reads changed; every other row is taken from `prev`,
+    the inference of the previous snapshot.  Not for the degree-normalised aggregator, whose
+    affected area also holds the out-neighbours of every node whose degree changed."""
+    if model["agg"] == "gcn_sym":
+        raise ValueError("affected_infer: gcn_sym not supported")
+    h = [np.ascontiguousarray(X, dtype=np.float32)]
+    alpha, arg = [None], [None]
+    for l in range(len(model["layers"])):
+        rows = areas[l].astype(np.int64)
+        sub_rp = np.zeros(rows.size + 1, np.int64)
+        np.cumsum(rowptr[rows + 1] - rowptr[rows], out=sub_rp[1:])
+        sub_col = np.concatenate([col[rowptr[v]:rowptr[v + 1]] for v in rows.tolist()]) if rows.size else np.zeros(0, np.int32)
+        a, g = aggregate(sub_rp, sub_col, h[l], model["agg"])
+        al = prev["alpha"][l + 1].copy()
+        al[rows] = a
+        gl = None
+        if g is not None:
+            gl = prev["arg"][l + 1].copy()
+            gl[rows] = g
+        hl = prev["h"][l + 1].copy()
+        if rows.size:
+            hl[rows] = transform(model, l, a, h[l][rows], precision)
+        alpha.append(al); arg.append(gl); h.append(hl)
+    return dict(h=h, alpha=alpha, arg=arg)

@@ -468,3 +468,40 @@ def test_a_user_event_stays_in_the_out_neighbourhood():
     outn = {5} | {v for v in range(n) if 5 in col[rp[v]:rp[v + 1]].tolist()}      # 5 and the nodes that aggregate it
     ch2 = np.nonzero(oracle.rows_differ(base["h"][2], out["h"][2]))[0]
     assert set(ch2.tolist()) <= outn
+
+
+# ---- the "Affected" baseline (Sec. 4.1): recomputing the theoretical affected area gives the full result
+@pytest.mark.parametrize("kind,agg", [("sage", "max"), ("gin", "sum"), ("sage", "mean")])
+def test_affected_area_recompute_equals_full_inference(kind, agg):
+    rng = np.random.default_rng(12)
+    n, dims = 300, (6, 5, 5, 4)
+    cfg = synth.WorkloadConfig(9, "t", kind, agg, n, 1500, False, dims, 6, 12, False)
+    src, dst = synth.make_graph(cfg)
+    X = rng.standard_normal((n, dims[0])).astype(np.float32)
+    model = synth.make_model(cfg, bias_scale=0.2)
+    keys = np.unique(synth.edge_keys(src, dst))
+    pre = oracle.full_infer(*oracle.csr_from_keys(n, keys), X, model, "f32")
+    sampler = synth.BatchSampler(cfg, src, dst)
+    op, bs, bd = sampler.next_batch()
+    keys2, _, _, _ = oracle.apply_batch(keys, op, bs, bd)
+    rp2, col2 = oracle.csr_from_keys(n, keys2)
+    s2, d2 = (keys2 & 0xFFFFFFFF).astype(np.int32), (keys2 >> 32).astype(np.int32)
+    orp, ocol = synth.in_csr_from_edges(n, d2, s2)            # roles swapped: out-neighbour lists
+    areas = oracle.affected_area(n, orp, ocol, bd, 3)
+    # hand check of the area: layer 1 = changed destinations, layer 2 adds their out-neighbours
+    assert np.array_equal(areas[0], np.unique(bd))
+    want2 = set(np.unique(bd).tolist())
+    for v in np.unique(bd).tolist():
+        want2 |= set(d2[s2 == v].tolist())
+    assert set(areas[1].tolist()) == want2 and set(areas[1].tolist()) <= set(areas[2].tolist())
+    got = oracle.affected_infer(rp2, col2, X, model, pre, areas, "f32")
+    full = oracle.full_infer(rp2, col2, X, model, "f32")
+    for l in range(1, 4):
+        assert np.array_equal(got["h"][l].view(np.uint32), full["h"][l].view(np.uint32))
+        assert np.array_equal(got["alpha"][l].view(np.uint32), full["alpha"][l].view(np.uint32))
+        if full["arg"][l] is not None:
+            assert np.array_equal(got["arg"][l], full["arg"][l])
+    # and the area is needed: leaving the out-neighbours out of layer 2 must show (the pin is sharp)
+    short = [areas[0], areas[0], areas[0]]
+    bad = oracle.affected_infer(rp2, col2, X, model, pre, short, "f32")
+    assert not np.array_equal(bad["h"][3].view(np.uint32), full["h"][3].view(np.uint32))
