@@ -144,6 +144,15 @@ typedef struct {
                      edge, self loop, or an insert/delete pair that cancels within the batch */
 } ink_update_result;
 
+/* Kernels of a layer that are timed one by one (ink_layer_stats.ms_kernel). */
+enum { INK_K_AGG_EVENTS = 0, /* incremental aggregation over the grouped events (Sec. 2.5)          */
+       INK_K_AGG_EXPOSED,    /* recompute of the exposed rows of moderate length, one wave per row  */
+       INK_K_AGG_LONG,       /* recompute of long rows: plan, chunk partials, combine               */
+       INK_K_AGG_FULL,       /* recompute of every row (full inference, dense fallback), short rows */
+       INK_K_SORT,           /* grouping: radix sort of the events by target                        */
+       INK_K_XFORM,          /* dense combination (all linear maps of the layer)                    */
+       INK_K_NKERNEL = 8 };
+
 /* Per-layer counters and timings of the LAST ink_apply_updates (or ink_full_infer). */
 typedef struct {
   int64_t n_sources;     /* |F_l|: nodes whose message m_l changed                         */
@@ -164,6 +173,8 @@ typedef struct {
   int64_t n_covered;            /* resets, all covered by added messages                     */
   int32_t dense;         /* 1 if the layer fell back to re-aggregating every node           */
   int32_t pad_;
+  int64_t n_regather_nb_long; /* the part of n_regather_nb fetched by the chunked long-row kernels */
+  float ms_kernel[INK_K_NKERNEL]; /* GPU time of single kernels of this layer, HIP events (profile != 0) */
 } ink_layer_stats;
 
 enum { INK_T_GRAPH = 0, INK_T_EVENTS, INK_T_GROUP, INK_T_AGG, INK_T_COMPACT, INK_T_TRANSFORM,
@@ -238,6 +249,38 @@ ink_status ink_apply_updates_affected(ink_ctx *ctx, const ink_edge_update *updat
 ink_status ink_update_features(ink_ctx *ctx, const int32_t *node_ids, const float *rows, int64_t n,
                                ink_update_result *out);
 
+/* User-defined events (Sec. 2.6: callers may create, group and apply events of their own next
+ * to the built-in ones, and these are managed apart from them; Sec. 3.2 shows the use: a user_apply
+ * step adds a caller-supplied per-node term to the tensor between the linear map and the
+ * activation).  Every layer l has a user term u_l[v] of out_dim_l floats per node, zero until an
+ * event touches it, and the layer computes h_l[v] = act(T_l(alpha_l[v], h_{l-1}[v]) + u_l[v])
+ * (added to the fp32 result of the linear map and its bias, before the activation).  An event
+ * names a layer (1 .. n_layers), a target node and an operation on that node's term. */
+typedef enum { INK_USER_SET = 0,   /* u <- row          */
+               INK_USER_ADD = 1,   /* u <- u + row, one fp32 addition per event */
+               INK_USER_CLEAR = 2  /* u <- 0 (row ignored) */ } ink_user_op;
+typedef struct {
+  int32_t layer, target;
+  int32_t op;      /* ink_user_op */
+  int32_t pad_;
+} ink_user_event;
+
+/* Applies an ordered list of n user events: they are grouped by (layer, target), each group is
+ * applied in list order to its node's term, and every node whose term changed bitwise is
+ * re-transformed at its layer and, if its embedding changed, propagates to the deeper layers
+ * like any changed node (Sec. 2.4.2).  The graph is unchanged; the terms stay in force for every
+ * later call, ink_full_infer included.
+ *   events : HOST array [n]
+ *   rows   : HOST array [n][row_stride]; the first out_dim_layer floats of row i belong to event i
+ * (both always host memory: user events are control input, not a data stream).  The first event
+ * on a layer allocates that layer's term table (n_nodes capacity x out_dim floats).
+ * The result has the layout of ink_apply_updates' (n_applied_* are 0).  GCN_SYM is not supported.
+ * Errors: INK_E_STATE before ink_full_infer; INK_E_RANGE for a layer outside 1 .. n_layers or a
+ * target outside [0, n_nodes); INK_E_ARG for an unknown op, row_stride below the width of a named
+ * layer, n < 0, NULL arrays or a GCN model.  On these errors nothing is changed. */
+ink_status ink_apply_user_events(ink_ctx *ctx, const ink_user_event *events, const float *rows, int32_t row_stride,
+                                 int64_t n, ink_update_result *out);
+
 /* Node arrival (Sec. 1 names newly arriving nodes as one source of change; Sec. 2.1 defines the
  * update stream over edges only, so a node arrives without edges and its edges follow through
  * ink_apply_updates).  Appends n_new nodes with ids n_nodes .. n_nodes + n_new - 1 and the given
@@ -263,6 +306,7 @@ ink_status ink_add_nodes(ink_ctx *ctx, const float *features, int64_t n_new, ink
  *              exact after a recompute and may be loose afterwards; it never affects results.
  *   which = 4: MAX / MIN only, int32: the neighbour other than the holder that has exactly the
  *              value of which = 3 (the lowest such id), or -1 where that is not known.
+ *   which = 5: the user term u_layer of ink_apply_user_events (INK_E_ARG if no event ever named the layer).
  * width is returned in *width_out if not NULL. */
 ink_status ink_get_layer(ink_ctx *ctx, int32_t layer, int32_t which, int64_t row0, int64_t nrows,
                          void *dst, int32_t dst_mem, int32_t *width_out);

@@ -12,11 +12,15 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 INK_MAX_LAYERS = 8
 INK_T_NCLASS = 6
 TIME_CLASSES = ["graph", "events", "group", "agg", "compact", "transform"]
+INK_K_NKERNEL = 8
+KERNEL_SLOTS = ["agg_events", "agg_exposed", "agg_long", "agg_full", "sort", "xform"]
 STATUS_NAMES = {0: "INK_OK", 1: "INK_E_ARG", 2: "INK_E_STATE", 3: "INK_E_OOM", 4: "INK_E_DEVICE",
                 5: "INK_E_RANGE"}
 MODEL_KINDS = {"sage": 0, "gcn": 1, "gin": 2}
 AGGS = {"max": 0, "min": 1, "sum": 2, "mean": 3, "gcn_sym": 4}
 
+USER_EVENT_DTYPE = np.dtype([("layer", np.int32), ("target", np.int32), ("op", np.int32), ("pad", np.int32)])
+USER_SET, USER_ADD, USER_CLEAR = 0, 1, 2
 EDGE_UPDATE_DTYPE = np.dtype([("op", np.uint8), ("pad", np.uint8, (3,)), ("src", np.int32),
                               ("dst", np.int32)])
 assert EDGE_UPDATE_DTYPE.itemsize == 12
@@ -59,7 +63,9 @@ class _LayerStats(C.Structure):
     _fields_ = [(k, C.c_int64) for k in ("n_sources", "n_events", "n_targets", "n_exposed",
                                          "n_regather_nb", "n_alpha_changed", "n_transformed",
                                          "n_changed", "n_no_deletion", "n_deletion_no_effect",
-                                         "n_covered")] + [("dense", C.c_int32), ("pad_", C.c_int32)]
+                                         "n_covered")] + [("dense", C.c_int32), ("pad_", C.c_int32),
+                                                          ("n_regather_nb_long", C.c_int64),
+                                                          ("ms_kernel", C.c_float * INK_K_NKERNEL)]
 
 
 class _Stats(C.Structure):
@@ -103,6 +109,8 @@ def load_library():
     lib.ink_apply_updates_affected.restype = C.c_int
     lib.ink_update_features.argtypes = [vp, vp, vp, C.c_int64, C.POINTER(_Result)]
     lib.ink_update_features.restype = C.c_int
+    lib.ink_apply_user_events.argtypes = [vp, vp, vp, C.c_int32, C.c_int64, C.POINTER(_Result)]
+    lib.ink_apply_user_events.restype = C.c_int
     lib.ink_add_nodes.argtypes = [vp, vp, C.c_int64, C.POINTER(_Result)]
     lib.ink_add_nodes.restype = C.c_int
     lib.ink_get_layer.argtypes = [vp, C.c_int32, C.c_int32, C.c_int64, C.c_int64, vp, C.c_int32,
@@ -137,7 +145,8 @@ class Ink:
     """One context.  `model` is the dict layout of synth.make_model (host numpy weights)."""
 
     def __init__(self, rowptr, col, features, model, slack_factor=0.25, profile=False, stream=None,
-                 dense_threshold=0.0, pool_reserve=0, batch_device=False, node_capacity=0, small_batch_limit=0):
+                 dense_threshold=0.0, pool_reserve=0, batch_device=False, node_capacity=0, small_batch_limit=0,
+                 max_batch=0):
         self._lib = load_library()
         self._h = C.c_void_p()
         rowptr = np.ascontiguousarray(rowptr, np.int64)
@@ -159,7 +168,7 @@ class Ink:
         m = _Model(MODEL_KINDS[model["kind"]], AGGS[model["agg"]], float(model.get("gin_eps", 0.0)),
                    len(model["layers"]), layers)
         g = _Csr(rowptr.size - 1, col.size, rowptr.ctypes.data, col.ctypes.data if col.size else None)
-        o = _Options(0, stream, slack_factor, 0, int(bool(profile)), dense_threshold,
+        o = _Options(0, stream, slack_factor, int(max_batch), int(bool(profile)), dense_threshold,
                      1 if batch_device else 0, small_batch_limit, pool_reserve, node_capacity)
         st = self._lib.ink_create(C.byref(g), features.ctypes.data, features.shape[1], C.byref(m), C.byref(o),
                                   C.byref(self._h))
@@ -238,6 +247,31 @@ class Ink:
             out["changed_ids"], out["embeddings"] = ids, emb
         return out
 
+    def apply_user_events(self, events, rows, fetch=True):
+        """events: list of (layer, target, op) or a USER_EVENT_DTYPE array; rows: [n][stride] float32
+        (row i belongs to event i).  Host arrays; same result dict as apply_updates."""
+        if not isinstance(events, np.ndarray) or events.dtype != USER_EVENT_DTYPE:
+            ev = np.zeros(len(events), dtype=USER_EVENT_DTYPE)
+            for i, (layer, target, op) in enumerate(events):
+                ev[i] = (layer, target, op, 0)
+            events = ev
+        events = np.ascontiguousarray(events)
+        rows = np.ascontiguousarray(rows, dtype=np.float32).reshape(events.size, -1) if events.size else np.zeros((0, 1), np.float32)
+        r = _Result()
+        self._check(self._lib.ink_apply_user_events(self._h, events.ctypes.data if events.size else None,
+                                                    rows.ctypes.data if events.size else None, rows.shape[1],
+                                                    events.size, C.byref(r)))
+        out = dict(n_changed=r.n_changed, n_applied_ins=r.n_applied_ins, n_applied_del=r.n_applied_del,
+                   n_noop=r.n_noop, changed_ids_ptr=r.changed_ids, embeddings_ptr=r.embeddings)
+        if fetch:
+            ids = np.empty(r.n_changed, np.int32)
+            emb = np.empty((r.n_changed, self.out_dim), np.float32)
+            if r.n_changed:
+                _dtoh(ids, r.changed_ids)
+                _dtoh(emb, r.embeddings)
+            out["changed_ids"], out["embeddings"] = ids, emb
+        return out
+
     def add_nodes(self, features, fetch=True):
         """Appends len(features) nodes without edges; returns their ids and final embeddings."""
         assert not self.batch_device, "context expects device batches"
@@ -268,7 +302,7 @@ class Ink:
         nrows = self.n - row0 if nrows is None else nrows
         w = C.c_int32()
         self._check(self._lib.ink_get_layer(self._h, layer, which, 0, 0, None, 0, C.byref(w)))
-        out = np.empty((nrows, w.value), np.int32 if which in (2, 4) else np.float32)
+        out = np.empty((nrows, w.value), np.int32 if which in (2, 4) else np.float32)   # 5: user term, float
         self._check(self._lib.ink_get_layer(self._h, layer, which, row0, nrows, out.ctypes.data, 0, None))
         return out
 
@@ -285,8 +319,10 @@ class Ink:
     def stats(self):
         s = _Stats()
         self._check(self._lib.ink_get_stats(self._h, C.byref(s), C.sizeof(s)))
-        layers = [{k: getattr(s.layer[i], k) for k, _ in _LayerStats._fields_ if k != "pad_"}
+        layers = [{k: getattr(s.layer[i], k) for k, _ in _LayerStats._fields_ if k not in ("pad_", "ms_kernel")}
                   for i in range(s.n_layers)]
+        for i, L in enumerate(layers):
+            L["ms_kernel"] = {name: s.layer[i].ms_kernel[j] for j, name in enumerate(KERNEL_SLOTS)}
         return dict(layers=layers, ms={TIME_CLASSES[i]: s.ms[i] for i in range(INK_T_NCLASS)},
                     launches={TIME_CLASSES[i]: s.launches[i] for i in range(INK_T_NCLASS)},
                     ms_total=s.ms_total)

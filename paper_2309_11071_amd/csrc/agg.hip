@@ -203,40 +203,55 @@ __device__ __forceinline__ void mark_bit(uint64_t *bm, int v) {
 }
 
 // ------------------------------------------------------------------ full re-aggregation
+// what a recompute launch does besides storing the rows
+enum { FULL_COMPARE = 1,        // compare with the cached row: store and mark only what changed
+       FULL_COUNT_GATHER = 2,   // tally the neighbour rows fetched
+       FULL_COUNT_CHANGED = 4 };// tally the rows whose value changed
+
+// One wave per row, the grid strides over the rows; n_targets_dev (optional) is the device-side
+// row count, n_targets then only bounds it.
 template <bool IS_MIN, int LPR>
 __global__ __launch_bounds__(256) void k_agg_full(AggArgs a, const int32_t *targets, int64_t n_targets,
-                                                  uint64_t *chg, int32_t *big_list, int32_t *n_big, int compare,
-                                                  Counters *cnt) {
+                                                  const int32_t *n_targets_dev, uint64_t *chg, int32_t *big_list,
+                                                  int32_t *n_big, int flags, Counters *cnt) {
   const int l = lane_id();
   const int q = l % LPR;
   const bool lane_on = 4 * q < a.wd;
-  int64_t wid = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kWave;
-  if (wid >= n_targets) return;
-  int v = targets ? targets[wid] : (int)wid;
-  int deg = a.in_deg[v];
-  if (targets && l == 0) atomicAdd(&cnt->stripe[blockIdx.x % kStripes][ST_REGATHER], (unsigned long long)deg);
-  if (deg > a.big_deg) {
-    if (l == 0) big_list[atomicAdd(n_big, 1)] = v;
-    return;
-  }
-  int64_t off = a.in_off[v];
-  F4 bv; I4 bi; F4 sv; I4 si;
-  gather_range<IS_MIN, LPR>(a.in_ids + off, 0, deg, a.M, a.ldm, lane_on, q, a.in_asc[v] != 0, bv, bi, sv, si);
-  finish_empty<IS_MIN>(bv, bi, sv, si);
-  RowOut o{a.A, a.ARG, a.UB, a.ARG2, a.ld, a.d};
-  F4 dum; I4 dumi;
-  bool ch;
-  if (compare) ch = store_row<LPR>(o, v, lane_on, q, bv, bi, sv, si, false, dum, dumi);
-  else {
-    if (lane_on && l < LPR) {
-      *reinterpret_cast<float4 *>(a.A + (int64_t)v * a.ld + 4 * q) = make_float4(bv.v[0], bv.v[1], bv.v[2], bv.v[3]);
-      *reinterpret_cast<int4 *>(a.ARG + (int64_t)v * a.ld + 4 * q) = make_int4(bi.v[0], bi.v[1], bi.v[2], bi.v[3]);
-      *reinterpret_cast<float4 *>(a.UB + (int64_t)v * a.ld + 4 * q) = make_float4(sv.v[0], sv.v[1], sv.v[2], sv.v[3]);
-      *reinterpret_cast<int4 *>(a.ARG2 + (int64_t)v * a.ld + 4 * q) = make_int4(si.v[0], si.v[1], si.v[2], si.v[3]);
+  if (n_targets_dev) { int64_t nd = *n_targets_dev; n_targets = nd < n_targets ? nd : n_targets; }
+  const int64_t stride = (int64_t)gridDim.x * (blockDim.x / kWave);
+  for (int64_t wid = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kWave; wid < n_targets; wid += stride) {
+    int v = targets ? targets[wid] : (int)wid;
+    int deg = a.in_deg[v];
+    if ((flags & FULL_COUNT_GATHER) && l == 0) {
+      atomicAdd(&cnt->stripe[blockIdx.x % kStripes][ST_REGATHER], (unsigned long long)deg);
+      if (deg > a.big_deg) atomicAdd(&cnt->stripe[blockIdx.x % kStripes][ST_REGATHER_LONG], (unsigned long long)deg);
     }
-    ch = false;
+    if (deg > a.big_deg) {
+      if (l == 0) big_list[atomicAdd(n_big, 1)] = v;
+      continue;
+    }
+    int64_t off = a.in_off[v];
+    F4 bv; I4 bi; F4 sv; I4 si;
+    gather_range<IS_MIN, LPR>(a.in_ids + off, 0, deg, a.M, a.ldm, lane_on, q, a.in_asc[v] != 0, bv, bi, sv, si);
+    finish_empty<IS_MIN>(bv, bi, sv, si);
+    RowOut o{a.A, a.ARG, a.UB, a.ARG2, a.ld, a.d};
+    F4 dum; I4 dumi;
+    bool ch;
+    if (flags & FULL_COMPARE) ch = store_row<LPR>(o, v, lane_on, q, bv, bi, sv, si, false, dum, dumi);
+    else {
+      if (lane_on && l < LPR) {
+        *reinterpret_cast<float4 *>(a.A + (int64_t)v * a.ld + 4 * q) = make_float4(bv.v[0], bv.v[1], bv.v[2], bv.v[3]);
+        *reinterpret_cast<int4 *>(a.ARG + (int64_t)v * a.ld + 4 * q) = make_int4(bi.v[0], bi.v[1], bi.v[2], bi.v[3]);
+        *reinterpret_cast<float4 *>(a.UB + (int64_t)v * a.ld + 4 * q) = make_float4(sv.v[0], sv.v[1], sv.v[2], sv.v[3]);
+        *reinterpret_cast<int4 *>(a.ARG2 + (int64_t)v * a.ld + 4 * q) = make_int4(si.v[0], si.v[1], si.v[2], si.v[3]);
+      }
+      ch = false;
+    }
+    if (ch && chg && l == 0) {
+      mark_bit(chg, v);
+      if ((flags & FULL_COUNT_CHANGED) && a.count_cond) atomicAdd(&cnt->stripe[blockIdx.x % kStripes][ST_ACHG], 1ull);
+    }
   }
-  if (ch && chg && l == 0) mark_bit(chg, v);
 }
 
 // cooperative path for rows with more than kBigDeg in-neighbours: a workgroup per chunk of
@@ -330,77 +345,112 @@ __global__ __launch_bounds__(64) void k_big_final(AggArgs a, const int32_t *big_
 //        its value got worse the dimension needs a reset, if equal nothing happened there
 // A reset dimension is covered when the best candidate strictly beats the old value, otherwise
 // the row is exposed and recomputed from its whole current neighbourhood.
-template <bool IS_MIN, int LPR>
-__device__ __forceinline__ void agg_events_one(const AggArgs &a, int v, int e0, int e1, const uint32_t *ev, uint64_t *chg,
-                                               int32_t *big_list, Counters *cnt) {
-  constexpr int G = kWave / LPR;
-  const int l = lane_id();
-  const int q = l % LPR, g = l / LPR;
-  const bool lane_on = 4 * q < a.wd;
-  F4 ov; I4 oi; F4 ou; I4 o2;   // cached value, holder, bound on the other neighbours, runner-up id or -1
+//
+// A target has a handful of events, and what bounds the kernel is the traffic of its random row
+// accesses (one source row per event, four cached rows per target, up to four written back), not
+// the latency of one target's chain: keeping the next targets' rows in flight across targets
+// (register double-buffering, event words staged in LDS) was measured and bought nothing, so the
+// loop is the plain one.
+
+#ifndef INK_EV_U
+#define INK_EV_U 2                 // source rows in flight per lane group and batch
+#endif
+#ifndef INK_EV_BLOCK
+#define INK_EV_BLOCK 8             // consecutive targets per wave visit (at most 62)
+#endif
+constexpr int kEvBlock = INK_EV_BLOCK;
+constexpr uint32_t kEvNone = 0xFFFFFFFFu;     // no event: its kind bits name no kind
+
+template <bool IS_MIN> struct Cached {        // this lane's four dimensions of a target's cached row
+  F4 ov; I4 oi; F4 ou; I4 o2;                 // value, holder, bound on the other neighbours, runner-up id or -1
+};
+template <bool IS_MIN>
+__device__ __forceinline__ void load_cached(const AggArgs &a, int v, bool lane_on, int q, Cached<IS_MIN> &k) {
 #pragma unroll
-  for (int c = 0; c < 4; c++) { ov.v[c] = 0.f; oi.v[c] = -1; ou.v[c] = worst<IS_MIN>(); o2.v[c] = -1; }
+  for (int c = 0; c < 4; c++) { k.ov.v[c] = 0.f; k.oi.v[c] = -1; k.ou.v[c] = worst<IS_MIN>(); k.o2.v[c] = -1; }
   if (lane_on) {
-    float4 x = ld4(a.A + (int64_t)v * a.ld + 4 * q);
-    int4 y = *reinterpret_cast<const int4 *>(a.ARG + (int64_t)v * a.ld + 4 * q);
-    float4 z = ld4(a.UB + (int64_t)v * a.ld + 4 * q);
-    int4 y2 = *reinterpret_cast<const int4 *>(a.ARG2 + (int64_t)v * a.ld + 4 * q);
-    ov.v[0] = x.x; ov.v[1] = x.y; ov.v[2] = x.z; ov.v[3] = x.w;
-    oi.v[0] = y.x; oi.v[1] = y.y; oi.v[2] = y.z; oi.v[3] = y.w;
-    ou.v[0] = z.x; ou.v[1] = z.y; ou.v[2] = z.z; ou.v[3] = z.w;
-    o2.v[0] = y2.x; o2.v[1] = y2.y; o2.v[2] = y2.z; o2.v[3] = y2.w;
+    const int64_t o = (int64_t)v * a.ld + 4 * q;
+    const float4 x = ld4(a.A + o);
+    const int4 y = *reinterpret_cast<const int4 *>(a.ARG + o);
+    const float4 z = ld4(a.UB + o);
+    const int4 y2 = *reinterpret_cast<const int4 *>(a.ARG2 + o);
+    k.ov.v[0] = x.x; k.ov.v[1] = x.y; k.ov.v[2] = x.z; k.ov.v[3] = x.w;
+    k.oi.v[0] = y.x; k.oi.v[1] = y.y; k.oi.v[2] = y.z; k.oi.v[3] = y.w;
+    k.ou.v[0] = z.x; k.ou.v[1] = z.y; k.ou.v[2] = z.z; k.ou.v[3] = z.w;
+    k.o2.v[0] = y2.x; k.o2.v[1] = y2.y; k.o2.v[2] = y2.z; k.o2.v[3] = y2.w;
   }
+}
+
+// U events per lane group: their words and, unless they are deletions, their sources' message rows
+template <int U> struct EvBatch { uint32_t code[U]; float4 row[U]; };
+
+// events it + u G + g (u < U) of the window `mine` (lane j holds event j, cntw of them are real)
+template <int LPR, int U>
+__device__ __forceinline__ void issue_batch(const AggArgs &a, uint32_t mine, int it, int cntw, bool lane_on, int q,
+                                            EvBatch<U> &b) {
+  constexpr int G = kWave / LPR;
+  const int g = lane_id() / LPR;
+#pragma unroll
+  for (int u = 0; u < U; u++) {
+    const int k = it + u * G + g;
+    const uint32_t x = __shfl(mine, k < kWave ? k : 0, kWave);
+    const bool valid = k < cntw && lane_on;
+    b.code[u] = valid ? x : kEvNone;
+    if (valid && (x >> kEvKindShift) != EV_DEL) b.row[u] = ld4(a.M + (int64_t)(x & kEvIdMask) * a.ldm + 4 * q);
+  }
+}
+
+template <bool IS_MIN> struct EvAcc {
   F4 cv; I4 ci; F4 cs;       // best candidate, its source, runner-up candidate value
   // per dimension c: bit c = reset (the holder left or got worse), bit 4 + c = the recorded
   // runner-up left or changed its message (one register instead of eight flags)
-  unsigned fl = 0u;
-  bool any_del = false;      // the segment cancels something: a removed edge or a changed source
+  unsigned fl;
+  bool any_del;              // the segment cancels something: a removed edge or a changed source
+  __device__ __forceinline__ void init() {
+    fl = 0u; any_del = false;
 #pragma unroll
-  for (int c = 0; c < 4; c++) { cv.v[c] = worst<IS_MIN>(); ci.v[c] = 0x7fffffff; cs.v[c] = worst<IS_MIN>(); }
-  for (int eb = e0; eb < e1; eb += kWave) {
-    int ee = eb + l;
-    uint32_t mine = ee < e1 ? ev[ee] : 0xFFFFFFFFu;
-    int cntw = (e1 - eb) < kWave ? (e1 - eb) : kWave;
-    constexpr int U = 4;       // events in flight per lane group
-    for (int it = 0; it < cntw; it += G * U) {
-      int src[U];                // source id, bit 30 set for a changed source (ids stay below 2^30)
-      float4 r4[U];
+    for (int c = 0; c < 4; c++) { cv.v[c] = worst<IS_MIN>(); ci.v[c] = 0x7fffffff; cs.v[c] = worst<IS_MIN>(); }
+  }
+};
+
+template <bool IS_MIN, int U>
+__device__ __forceinline__ void consume_batch(const EvBatch<U> &b, const Cached<IS_MIN> &k, EvAcc<IS_MIN> &s) {
 #pragma unroll
-      for (int u = 0; u < U; u++) {
-        int k = it + u * G + g;
-        uint32_t x = __shfl(mine, k < kWave ? k : 0, kWave);
-        src[u] = -1;
-        if (k < cntw && lane_on) {
-          uint32_t kind = x >> kEvKindShift;
-          int uu = (int)(x & kEvIdMask);
-          any_del |= kind != EV_ADD;
-          if (kind != EV_ADD) {
+  for (int u = 0; u < U; u++) {
+    const uint32_t x = b.code[u];
+    if (x == kEvNone) continue;
+    const uint32_t kind = x >> kEvKindShift;
+    const int id = (int)(x & kEvIdMask);
+    s.any_del |= kind != EV_ADD;
+    if (kind != EV_ADD) {
 #pragma unroll
-            for (int c = 0; c < 4; c++) fl |= (unsigned)(o2.v[c] == uu) << (4 + c);
-          }
-          if (kind == EV_DEL) {
+      for (int c = 0; c < 4; c++) s.fl |= (unsigned)(k.o2.v[c] == id) << (4 + c);
+    }
+    if (kind == EV_DEL) {
 #pragma unroll
-            for (int c = 0; c < 4; c++) fl |= (unsigned)(oi.v[c] == uu) << c;
-          } else {
-            src[u] = uu | (kind == EV_CHG ? (1 << 30) : 0);
-            r4[u] = ld4(a.M + (int64_t)uu * a.ldm + 4 * q);
-          }
-        }
-      }
+      for (int c = 0; c < 4; c++) s.fl |= (unsigned)(k.oi.v[c] == id) << c;
+    } else {
+      const bool changed = kind == EV_CHG;
+      const float r[4] = {b.row[u].x, b.row[u].y, b.row[u].z, b.row[u].w};
 #pragma unroll
-      for (int u = 0; u < U; u++) {
-        if (src[u] < 0) continue;
-        const bool changed = (src[u] >> 30) & 1;
-        const int id = src[u] & kEvIdMask;
-        float r[4] = {r4[u].x, r4[u].y, r4[u].z, r4[u].w};
-#pragma unroll
-        for (int c = 0; c < 4; c++) {
-          fl |= (unsigned)(changed && oi.v[c] == id && better<IS_MIN>(ov.v[c], r[c])) << c;
-          take2<IS_MIN>(r[c], id, cv.v[c], ci.v[c], cs.v[c]);
-        }
+      for (int c = 0; c < 4; c++) {
+        s.fl |= (unsigned)(changed && k.oi.v[c] == id && better<IS_MIN>(k.ov.v[c], r[c])) << c;
+        take2<IS_MIN>(r[c], id, s.cv.v[c], s.ci.v[c], s.cs.v[c]);
       }
     }
   }
+}
+
+// The decision for target v once its events are reduced (the lane groups still hold partial
+// results), the recompute of an exposed row of moderate length, and the store.
+template <bool IS_MIN, int LPR>
+__device__ __forceinline__ void finish_target(const AggArgs &a, int v, const Cached<IS_MIN> &k, EvAcc<IS_MIN> &s,
+                                              bool lane_on, int q, uint64_t *chg, int32_t *big_list, int32_t *exp_list,
+                                              Counters *cnt) {
+  const int l = lane_id();
+  const F4 &ov = k.ov; const I4 &oi = k.oi; const F4 &ou = k.ou; const I4 &o2 = k.o2;
+  F4 &cv = s.cv; I4 &ci = s.ci; F4 &cs = s.cs;
+  unsigned fl = s.fl;
   // combine the lane groups
 #pragma unroll
   for (int off = LPR; off < kWave; off <<= 1) fl |= (unsigned)__shfl_xor((int)fl, off, kWave);
@@ -455,11 +505,11 @@ __device__ __forceinline__ void agg_events_one(const AggArgs &a, int v, int e0, 
     }
   }
   exposed = __ballot(exposed && lane_on) != 0ull;
-  {   // condition of this target (Sec. 2.5.1; the distribution shown in Sec. 5.2)
+  if (a.count_cond) {   // condition of this target (Sec. 2.5.1; the distribution shown in Sec. 5.2)
     bool rs = (reset[0] || reset[1] || reset[2] || reset[3]) && lane_on;
     bool any_reset = __ballot(rs) != 0ull;
-    bool dl = __ballot(any_del) != 0ull;
-    if (l == 0 && !exposed && a.count_cond) {
+    bool dl = __ballot(s.any_del) != 0ull;
+    if (l == 0 && !exposed) {
       int which = !dl ? ST_NODEL : (!any_reset ? ST_NOEFFECT : ST_COVERED);
       atomicAdd(&cnt->stripe[blockIdx.x % kStripes][which], 1ull);
     }
@@ -470,29 +520,90 @@ __device__ __forceinline__ void agg_events_one(const AggArgs &a, int v, int e0, 
       if (a.count_cond) atomicAdd(&cnt->stripe[blockIdx.x % kStripes][ST_EXPOSED], 1ull);
       atomicAdd(&cnt->stripe[blockIdx.x % kStripes][ST_REGATHER], (unsigned long long)deg);
     }
-    if (deg > a.big_deg) {
-      if (l == 0) big_list[atomicAdd(&cnt->v[C_NBIG], 1)] = v;
-      return;
+    // recomputed by the kernels that follow: long rows chunk by chunk, the others one wave per row
+    if (l == 0) {
+      if (deg > a.big_deg) {
+        big_list[atomicAdd(&cnt->v[C_NBIG], 1)] = v;
+        atomicAdd(&cnt->stripe[blockIdx.x % kStripes][ST_REGATHER_LONG], (unsigned long long)deg);
+      } else {
+        exp_list[atomicAdd(&cnt->v[C_NEXP], 1)] = v;
+      }
     }
-    gather_range<IS_MIN, LPR>(a.in_ids + a.in_off[v], 0, deg, a.M, a.ldm, lane_on, q, a.in_asc[v] != 0, nv, ni, nu, n2);
-    finish_empty<IS_MIN>(nv, ni, nu, n2);
+    return;
   }
-  RowOut o{a.A, a.ARG, a.UB, a.ARG2, a.ld, a.d};
-  bool ch = store_row<LPR>(o, v, lane_on, q, nv, ni, nu, n2, true, ov, oi);
+  // each half of the cached row is rewritten only if it changed: most targets keep their bound and
+  // runner-up, many keep value and holder
+  const bool writer = lane_on && l < LPR;
+  bool vchg = false;
+  if (writer) {
+    bool ichg = false, uchg = false;
+#pragma unroll
+    for (int c = 0; c < 4; c++) {
+      if (4 * q + c < a.d) vchg |= __float_as_uint(ov.v[c]) != __float_as_uint(nv.v[c]);
+      ichg |= oi.v[c] != ni.v[c];
+      uchg |= __float_as_uint(ou.v[c]) != __float_as_uint(nu.v[c]) || o2.v[c] != n2.v[c];
+    }
+    if (vchg || ichg) {
+      *reinterpret_cast<float4 *>(a.A + (int64_t)v * a.ld + 4 * q) = make_float4(nv.v[0], nv.v[1], nv.v[2], nv.v[3]);
+      *reinterpret_cast<int4 *>(a.ARG + (int64_t)v * a.ld + 4 * q) = make_int4(ni.v[0], ni.v[1], ni.v[2], ni.v[3]);
+    }
+    if (uchg) {
+      *reinterpret_cast<float4 *>(a.UB + (int64_t)v * a.ld + 4 * q) = make_float4(nu.v[0], nu.v[1], nu.v[2], nu.v[3]);
+      *reinterpret_cast<int4 *>(a.ARG2 + (int64_t)v * a.ld + 4 * q) = make_int4(n2.v[0], n2.v[1], n2.v[2], n2.v[3]);
+    }
+  }
+  const bool ch = __ballot(vchg) != 0ull;
   if (ch && l == 0) { mark_bit(chg, v); if (a.count_cond) atomicAdd(&cnt->stripe[blockIdx.x % kStripes][ST_ACHG], 1ull); }
 }
 
-// The grid is sized to what the chip holds at once; every wave walks the target list with the
-// grid's wave count as stride (a wave per target costs more in wave launches than in work when
-// a target has a handful of events).
+// The grid is sized to what the chip holds at once; every wave walks blocks of kEvBlock consecutive
+// targets with the grid's wave count as stride.  One load per block brings the targets' ids and
+// segment bounds (lane j holds those of target j), so a target's own chain is: cached row and event
+// words (issued together), then the source rows.
+#ifdef INK_EV_MIN_WAVES
+#define INK_EV_ATTR __attribute__((amdgpu_waves_per_eu(INK_EV_MIN_WAVES)))
+#else
+#define INK_EV_ATTR
+#endif
 template <bool IS_MIN, int LPR>
-__global__ __launch_bounds__(256) void k_agg_events(AggArgs a, const int32_t *targets, const int32_t *seg,
+__global__ __launch_bounds__(256) INK_EV_ATTR void k_agg_events(AggArgs a, const int32_t *targets, const int32_t *seg,
                                                     const int32_t *n_targets_p, const uint32_t *ev, uint64_t *chg,
-                                                    int32_t *big_list, Counters *cnt) {
-  const int64_t n = *n_targets_p;
-  const int64_t stride = (int64_t)gridDim.x * (blockDim.x / kWave);
-  for (int64_t wid = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kWave; wid < n; wid += stride)
-    agg_events_one<IS_MIN, LPR>(a, targets[wid], seg[wid], seg[wid + 1], ev, chg, big_list, cnt);
+                                                    int32_t *big_list, int32_t *exp_list, Counters *cnt) {
+  constexpr int G = kWave / LPR;
+  constexpr int U = INK_EV_U;
+  static_assert(kEvBlock + 2 <= kWave, "a lane per target and bound of the block");
+  const int l = lane_id();
+  const int q = l % LPR;
+  const bool lane_on = 4 * q < a.wd;
+  const int n = *n_targets_p;
+  const int n_blk = (n + kEvBlock - 1) / kEvBlock;
+  const int n_waves = (int)gridDim.x * (int)(blockDim.x / kWave);
+  const int wave0 = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave));
+  for (int blk = wave0; blk < n_blk; blk += n_waves) {
+    const int w0 = blk * kEvBlock;
+    const int kt = n - w0 < kEvBlock ? n - w0 : kEvBlock;
+    const int my_t = targets[w0 + (l < kt ? l : kt - 1)];
+    const int my_s = seg[w0 + (l <= kt ? l : kt)];
+    for (int t = 0; t < kt; t++) {
+      const int v = __builtin_amdgcn_readlane(my_t, t);
+      const int e0 = __builtin_amdgcn_readlane(my_s, t), e1 = __builtin_amdgcn_readlane(my_s, t + 1);
+      Cached<IS_MIN> c;
+      load_cached<IS_MIN>(a, v, lane_on, q, c);
+      EvAcc<IS_MIN> s;
+      s.init();
+      for (int eb = e0; eb < e1; eb += kWave) {
+        const int ee = eb + l;
+        const uint32_t mine = ee < e1 ? ev[ee] : kEvNone;
+        const int cntw = e1 - eb < kWave ? e1 - eb : kWave;
+        for (int it = 0; it < cntw; it += G * U) {
+          EvBatch<U> bx;
+          issue_batch<LPR, U>(a, mine, it, cntw, lane_on, q, bx);
+          consume_batch<IS_MIN, U>(bx, c, s);
+        }
+      }
+      finish_target<IS_MIN, LPR>(a, v, c, s, lane_on, q, chg, big_list, exp_list, cnt);
+    }
+  }
 }
 
 // ------------------------------------------------------------------ host side
@@ -521,6 +632,8 @@ static hipError_t run_big(ink_ctx *c, const AggArgs &a, uint64_t *chg, int compa
   return hipGetLastError();
 }
 
+constexpr int64_t kFullGrid = 1 << 20;     // workgroups of a recompute launch (4 rows each per stride)
+
 template <bool IS_MIN, int LPR>
 static hipError_t full_t(ink_ctx *c, const AggArgs &a_in, const int32_t *targets, int64_t n_targets, uint64_t *chg) {
   if (n_targets <= 0) return hipSuccess;
@@ -529,14 +642,20 @@ static hipError_t full_t(ink_ctx *c, const AggArgs &a_in, const int32_t *targets
   int compare = chg != nullptr;
   INK_TRY(ensure_big_buffers(c, a.wd, true));
   INK_TRY(hipMemsetAsync(&c->d_cnt->v[C_NBIG], 0, sizeof(int32_t), c->stream));
-  int64_t blocks = (n_targets + 3) / 4;
-  hipLaunchKernelGGL((k_agg_full<IS_MIN, LPR>), dim3((unsigned)blocks), dim3(256), 0, c->stream, a, targets, n_targets,
-                     chg, c->big_list.as<int32_t>(), &c->d_cnt->v[C_NBIG], compare, c->d_cnt);
-  INK_TRY(hipGetLastError());
+  int64_t blocks = std::min<int64_t>((n_targets + 3) / 4, kFullGrid);
+  {
+    KernelTimer kt(c, a.layer, INK_K_AGG_FULL);
+    hipLaunchKernelGGL((k_agg_full<IS_MIN, LPR>), dim3((unsigned)blocks), dim3(256), 0, c->stream, a, targets, n_targets,
+                       (const int32_t *)nullptr, chg, c->big_list.as<int32_t>(), &c->d_cnt->v[C_NBIG],
+                       (compare ? FULL_COMPARE : 0) | (targets ? FULL_COUNT_GATHER : 0), c->d_cnt);
+    INK_TRY(hipGetLastError());
+  }
+  KernelTimer kt(c, a.layer, INK_K_AGG_LONG);
   return run_big<IS_MIN, LPR>(c, a, chg, compare, big_block_threads(n_targets), n_targets);
 }
 
-// n_targets may be an upper bound: the kernel stops at the device-side count n_targets_dev
+// n_targets may be an upper bound: the kernel stops at the device-side count n_targets_dev.
+// Exposed rows are listed by the event kernel and recomputed by the two launches after it.
 template <bool IS_MIN, int LPR>
 static hipError_t events_t(ink_ctx *c, const AggArgs &a_in, const int32_t *targets, const int32_t *seg,
                            int64_t n_targets, const int32_t *n_targets_dev, const uint32_t *ev, uint64_t *chg) {
@@ -544,10 +663,23 @@ static hipError_t events_t(ink_ctx *c, const AggArgs &a_in, const int32_t *targe
   AggArgs a = a_in;
   a.big_deg = big_threshold(n_targets, LPR, kBigDeg);
   INK_TRY(ensure_big_buffers(c, a.wd, true));
-  int64_t blocks = std::min<int64_t>((n_targets + 3) / 4, INK_EVENT_GRID);
-  hipLaunchKernelGGL((k_agg_events<IS_MIN, LPR>), dim3((unsigned)blocks), dim3(256), 0, c->stream, a, targets, seg,
-                     n_targets_dev, ev, chg, c->big_list.as<int32_t>(), c->d_cnt);
-  INK_TRY(hipGetLastError());
+  INK_TRY(c->exp_list.reserve((size_t)n_targets * 4));
+  int64_t blocks = std::min<int64_t>(((n_targets + kEvBlock - 1) / kEvBlock + 3) / 4, INK_EVENT_GRID);
+  {
+    KernelTimer kt(c, a.layer, INK_K_AGG_EVENTS);
+    hipLaunchKernelGGL((k_agg_events<IS_MIN, LPR>), dim3((unsigned)blocks), dim3(256), 0, c->stream, a, targets, seg,
+                       n_targets_dev, ev, chg, c->big_list.as<int32_t>(), c->exp_list.as<int32_t>(), c->d_cnt);
+    INK_TRY(hipGetLastError());
+  }
+  {
+    KernelTimer kt(c, a.layer, INK_K_AGG_EXPOSED);
+    int64_t rb = std::min<int64_t>((n_targets + 3) / 4, latency_mode(n_targets) ? 2048 : 16384);
+    hipLaunchKernelGGL((k_agg_full<IS_MIN, LPR>), dim3((unsigned)rb), dim3(256), 0, c->stream, a,
+                       (const int32_t *)c->exp_list.as<int32_t>(), n_targets, (const int32_t *)&c->d_cnt->v[C_NEXP], chg,
+                       c->big_list.as<int32_t>(), &c->d_cnt->v[C_NBIG], FULL_COMPARE | FULL_COUNT_CHANGED, c->d_cnt);
+    INK_TRY(hipGetLastError());
+  }
+  KernelTimer kt(c, a.layer, INK_K_AGG_LONG);
   return run_big<IS_MIN, LPR>(c, a, chg, 1, big_block_threads(n_targets), n_targets);
 }
 

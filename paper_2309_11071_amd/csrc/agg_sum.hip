@@ -107,7 +107,10 @@ __global__ __launch_bounds__(256) void k_sum_full(AggArgs a, const int32_t *targ
   if (wid >= n_targets) return;
   int v = targets ? targets[wid] : (int)wid;
   int deg = a.in_deg[v];
-  if (targets && l == 0) atomicAdd(&cnt->stripe[blockIdx.x % kStripes][ST_REGATHER], (unsigned long long)deg);
+  if (targets && l == 0) {
+    atomicAdd(&cnt->stripe[blockIdx.x % kStripes][ST_REGATHER], (unsigned long long)deg);
+    if (deg > a.big_deg) atomicAdd(&cnt->stripe[blockIdx.x % kStripes][ST_REGATHER_LONG], (unsigned long long)deg);
+  }
   if (deg > a.big_deg) {
     if (l == 0) big_list[atomicAdd(n_big, 1)] = v;
     return;
@@ -281,9 +284,13 @@ static hipError_t sum_full_t(ink_ctx *c, const AggArgs &a_in, const int32_t *tar
   int compare = chg != nullptr;
   INK_TRY(ensure_big_buffers(c, a.wd, false));
   INK_TRY(hipMemsetAsync(&c->d_cnt->v[C_NBIG], 0, sizeof(int32_t), c->stream));
-  hipLaunchKernelGGL((k_sum_full<LPR>), dim3((unsigned)((n_targets + 3) / 4)), dim3(256), 0, c->stream, a, targets,
-                     n_targets, chg, c->big_list.as<int32_t>(), &c->d_cnt->v[C_NBIG], compare, c->d_cnt);
-  INK_TRY(hipGetLastError());
+  {
+    KernelTimer kt(c, a.layer, INK_K_AGG_FULL);
+    hipLaunchKernelGGL((k_sum_full<LPR>), dim3((unsigned)((n_targets + 3) / 4)), dim3(256), 0, c->stream, a, targets,
+                       n_targets, chg, c->big_list.as<int32_t>(), &c->d_cnt->v[C_NBIG], compare, c->d_cnt);
+    INK_TRY(hipGetLastError());
+  }
+  KernelTimer kt(c, a.layer, INK_K_AGG_LONG);
   const int32_t *list = c->big_list.as<int32_t>();
   int32_t *pref = c->big_pref.as<int32_t>();
   int32_t *n_big = &c->d_cnt->v[C_NBIG], *total = &c->d_cnt->v[C_NCHUNK];
@@ -301,6 +308,7 @@ static hipError_t sum_events_t(ink_ctx *c, const AggArgs &a, const int32_t *targ
                                int64_t n_targets, const int32_t *n_targets_dev, const uint32_t *ev, const int32_t *F,
                                int nF, const float *f_old, const float *f_delta, int ld_old, uint64_t *chg) {
   if (n_targets <= 0) return hipSuccess;
+  KernelTimer kt(c, a.layer, INK_K_AGG_EVENTS);
   hipLaunchKernelGGL((k_sum_events<LPR>), dim3((unsigned)((n_targets + 3) / 4)), dim3(256), 0, c->stream, a, targets,
                      seg, n_targets_dev, ev, F, nF, f_old, f_delta, ld_old, chg, c->d_cnt);
   return hipGetLastError();

@@ -454,27 +454,13 @@ static hipError_t upload_vec(const float *src, int n, float **dst, bool src_dev)
   return hipMemcpy(*dst, src, (size_t)n * 4, src_dev ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice);
 }
 
-struct Prof {
-  ink_ctx *c; int cls; hipEvent_t a = nullptr, b = nullptr;
-  Prof(ink_ctx *c_, int cls_) : c(c_), cls(cls_) {
-    c->stats.launches[cls]++;
-    if (!c->profile) return;
-    if (c->ev_free.size() < 2) { hipEvent_t e; (void)hipEventCreate(&e); c->ev_free.push_back(e); (void)hipEventCreate(&e); c->ev_free.push_back(e); }
-    a = c->ev_free.back(); c->ev_free.pop_back();
-    b = c->ev_free.back(); c->ev_free.pop_back();
-    (void)hipEventRecord(a, c->stream);
-  }
-  ~Prof() {
-    if (!c->profile) return;
-    (void)hipEventRecord(b, c->stream);
-    c->ev_pending.push_back({cls, a, b});
-  }
-};
-
 static void prof_collect(ink_ctx *c) {
   for (auto &p : c->ev_pending) {
     float ms = 0.f;
-    if (hipEventElapsedTime(&ms, p.a, p.b) == hipSuccess) c->stats.ms[p.cls] += ms;
+    if (hipEventElapsedTime(&ms, p.a, p.b) == hipSuccess) {
+      if (p.cls >= 0) c->stats.ms[p.cls] += ms;
+      if (p.kern >= 0 && p.layer >= 1 && p.layer <= INK_MAX_LAYERS) c->stats.layer[p.layer - 1].ms_kernel[p.kern] += ms;
+    }
     c->ev_free.push_back(p.a); c->ev_free.push_back(p.b);
   }
   c->ev_pending.clear();
@@ -521,6 +507,7 @@ static AggArgs agg_args(ink_ctx *c, int l) {       // layer l in 1..k
   a.big_deg = kBigDeg;
   a.big_grid = 2 * c->big_hint[l] + 1024;
   a.count_cond = 1;
+  a.layer = l;
   return a;
 }
 
@@ -541,6 +528,7 @@ static hipError_t run_transform(ink_ctx *c, int l, const int32_t *rows, int64_t 
     x.mode = 0;
     x.W = L.W1; x.Kp = L.K1p; x.Np = L.N1p; x.bias = L.b1; x.n_out = L.out_dim; x.relu = L.act == INK_ACT_RELU;
     x.out = c->H[l].f(); x.ld_out = c->H[l].ld; x.to_table = 1; x.row_changed = flags;
+    x.user = c->USER[l].f(); x.ld_user = c->USER[l].ld;
     return xform_run(c, x);
   }
   // GIN: two linear maps through a staging buffer
@@ -558,6 +546,7 @@ static hipError_t run_transform(ink_ctx *c, int l, const int32_t *rows, int64_t 
   y.W = L.W2; y.Kp = L.K2p; y.Np = L.N2p; y.bias = L.b2; y.n_out = L.out_dim; y.relu = L.act == INK_ACT_RELU;
   y.out = c->H[l].f(); y.ld_out = c->H[l].ld; y.to_table = 1; y.row_changed = flags; y.out_rows = rows;
   y.old_rows = old_rows; y.ld_old = c->H[l].ld;
+  y.user = c->USER[l].f(); y.ld_user = c->USER[l].ld;
   return xform_run(c, y);
 }
 
@@ -692,13 +681,16 @@ extern "C" ink_status ink_create(const ink_csr *g, const float *features, int32_
   CREATE_TRY(hipMemset(c->bm_a, 0, bmw * 8));
   if (opts && opts->max_batch > 0) {       // size the batch staging up front
     CREATE_TRY(c->b_raw.reserve((size_t)opts->max_batch * sizeof(ink_edge_update)));
-    CREATE_TRY(c->b_misc.reserve((((size_t)opts->max_batch + 64) * 4 + 255) / 256 * 256 * 28));
+    const size_t per = (((size_t)opts->max_batch + 64) * 4 + 255) / 256 * 256;
+    CREATE_TRY(c->b_misc.reserve(per * 28));
+    for (DevBuf *b : {&c->b_del_s, &c->b_del_d, &c->b_ins_s, &c->b_ins_d, &c->b_touch_in, &c->b_uniq}) CREATE_TRY(b->reserve(per));
+    CREATE_TRY(c->c_list.reserve((size_t)nc * 4));
   }
   CREATE_TRY(c->big_list.reserve((size_t)(c->gin.pool_cap / kBigDeg + 4096) * 4));
   // tables
   c->H.resize(c->n_layers + 1); c->A.resize(c->n_layers + 1); c->ARG.resize(c->n_layers + 1);
   c->UB.resize(c->n_layers + 1); c->ARG2.resize(c->n_layers + 1);
-  c->XW.resize(c->n_layers + 1); c->Msc.resize(c->n_layers + 1);
+  c->XW.resize(c->n_layers + 1); c->Msc.resize(c->n_layers + 1); c->USER.resize(c->n_layers + 1);
   if (c->kind == INK_MODEL_GCN) CREATE_TRY(hipMalloc(&c->cnorm, (size_t)nc * 4));
   CREATE_TRY(alloc_table(c->H[0], nc, feat_dim));
   {
@@ -766,7 +758,7 @@ extern "C" void ink_destroy(ink_ctx *c) {
   }
   if (c->new_out) (void)hipFree(c->new_out);
   for (auto &L : c->layers) for (float *p : {L.W1, L.b1, L.W2, L.b2}) if (p) (void)hipFree(p);
-  for (auto *vec : {&c->H, &c->A, &c->ARG, &c->UB, &c->ARG2, &c->XW, &c->Msc}) for (auto &t : *vec) if (t.p) (void)hipFree(t.p);
+  for (auto *vec : {&c->H, &c->A, &c->ARG, &c->UB, &c->ARG2, &c->XW, &c->Msc, &c->USER}) for (auto &t : *vec) if (t.p) (void)hipFree(t.p);
   if (c->cnorm) (void)hipFree(c->cnorm);
   if (c->d_cnt) (void)hipFree(c->d_cnt);
   if (c->h_cnt) (void)hipHostFree(c->h_cnt);
@@ -775,7 +767,7 @@ extern "C" void ink_destroy(ink_ctx *c) {
                     &c->b_del_d, &c->b_ins_s, &c->b_ins_d, &c->f_list[0], &c->f_list[1], &c->f_old[0], &c->f_old[1],
                     &c->f_pref, &c->ev_key, &c->ev_val, &c->t_list, &c->t_seg, &c->c_list, &c->c_flag, &c->c_idx, &c->c_old,
                     &c->b_touch_in,
-                    &c->big_list, &c->big_part_v, &c->big_part_i, &c->big_part_s, &c->big_part_j, &c->big_pref, &c->f_delta, &c->stage0, &c->stage1, &c->res_ids, &c->res_emb})
+                    &c->u_ev, &c->u_rows, &c->u_key, &c->u_val, &c->u_uniq, &c->u_seg, &c->u_flag, &c->u_idx, &c->u_list, &c->exp_list, &c->big_list, &c->big_part_v, &c->big_part_i, &c->big_part_s, &c->big_part_j, &c->big_pref, &c->f_delta, &c->stage0, &c->stage1, &c->res_ids, &c->res_emb})
     b->release();
   for (auto e : c->ev_free) (void)hipEventDestroy(e);
   for (auto &p : c->ev_pending) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
@@ -869,7 +861,7 @@ static ink_status full_infer_impl(ink_ctx *c) {
     AggArgs a = agg_args(c, l);
     { Prof p(c, INK_T_AGG); API_TRY(agg_full_any(c, a, nullptr)); }
     {
-      Prof p(c, INK_T_TRANSFORM);
+      Prof p(c, INK_T_TRANSFORM, l, INK_K_XFORM);
       if (c->kind != INK_MODEL_GCN) API_TRY(run_transform(c, l, nullptr, c->n, nullptr));
       else if (l < c->n_layers) API_TRY(gcn_next_messages(c, l, nullptr, c->n, nullptr, nullptr));
       else API_TRY(gcn_final(c, nullptr, c->n, nullptr));
@@ -1004,7 +996,7 @@ static ink_status layer_aggregate(ink_ctx *c, int l, const int32_t *F, int64_t n
       API_TRY(hipGetLastError());
     }
     Prof p(c, INK_T_GROUP);
-    API_TRY(radix_sort_pairs(c->ws, key, val, nE, c->id_bits, s));
+    { KernelTimer kt(c, l, INK_K_SORT); API_TRY(radix_sort_pairs(c->ws, key, val, nE, c->id_bits, s)); }
     API_TRY(segment_heads(c->ws, key, nE, c->t_list.as<int32_t>(), c->t_seg.as<int32_t>(), &dc->v[C_NT], s));
     if (nE > kNoSyncEvents) {
       API_TRY(read_counters(c));
@@ -1033,7 +1025,7 @@ static ink_status layer_aggregate(ink_ctx *c, int l, const int32_t *F, int64_t n
     for (int b = 0; b < agg_blocks(a); b++) {
       AggArgs ab = agg_block(a, b);
       int c0 = b * kAggBlock;
-      if (b > 0) API_TRY(hipMemsetAsync(&dc->v[C_NBIG], 0, sizeof(int32_t), s));
+      if (b > 0) API_TRY(hipMemsetAsync(&dc->v[C_NBIG], 0, 2 * sizeof(int32_t), s));   // long and exposed row lists
       if (c->is_select)
         API_TRY(agg_select_events(c, ab, c->t_list.as<int32_t>(), c->t_seg.as<int32_t>(), nT, &dc->v[C_NT],
                                   c->ev_val.as<uint32_t>(), bm));
@@ -1061,6 +1053,7 @@ static void layer_stats_from_counters(ink_ctx *c, int l) {
   }
   S.n_exposed = (int64_t)c->h_cnt->sum(ST_EXPOSED);
   S.n_regather_nb = (int64_t)c->h_cnt->sum(ST_REGATHER);
+  S.n_regather_nb_long = (int64_t)c->h_cnt->sum(ST_REGATHER_LONG);
   S.n_alpha_changed = (int64_t)c->h_cnt->sum(ST_ACHG);
   S.n_no_deletion = (int64_t)c->h_cnt->sum(ST_NODEL);
   S.n_deletion_no_effect = (int64_t)c->h_cnt->sum(ST_NOEFFECT);
@@ -1170,14 +1163,29 @@ static ink_status emit_changed(ink_ctx *c, int64_t nC, int nxt, bool keep_old, i
 // Layers 1..k for the sources F_1 = f_list[cur] (nF ids whose layer-1 message changed, n_chg events
 // along their kept out-edges) and the applied edge changes; D (nD ids) are nodes whose in-degree
 // changed (normalised aggregators).  Fills the result for layer k.
+// Rows that have to be re-transformed at a layer for a reason of their own (their user term changed):
+// asked for at the start of every layer up to `last_layer`.
+struct LayerRows {
+  int last_layer;
+  ink_status (*rows_of)(ink_ctx *c, int l, void *state, const int32_t **rows, int64_t *n);
+  void *state;
+};
+
 static ink_status propagate_layers(ink_ctx *c, int64_t nF, int64_t n_chg, int cur, int64_t n_ins, int64_t n_del,
-                                   const int32_t *D, int64_t nD, ink_update_result *out) {
+                                   const int32_t *D_all, int64_t nD_all, ink_update_result *out,
+                                   const LayerRows *own = nullptr) {
   hipStream_t s = c->stream;
   const int64_t n_seed = n_ins + n_del;
   const bool gcn = c->kind == INK_MODEL_GCN;
   const bool keep_old = !c->is_select && !c->affected_mode;   // delta updates subtract the old message rows
-  for (int l = 1; l <= c->n_layers && (n_seed > 0 || nF > 0); l++) {
+  for (int l = 1; l <= c->n_layers && (n_seed > 0 || nF > 0 || (own && l <= own->last_layer)); l++) {
     ink_layer_stats &S = c->stats.layer[l - 1];
+    const int32_t *D = D_all;
+    int64_t nD = nD_all;
+    if (own) {
+      ink_status st_own = own->rows_of(c, l, own->state, &D, &nD);
+      if (st_own != INK_OK) return st_own;
+    }
     const int32_t *F = c->f_list[cur].as<int32_t>();
     int ld_msg = msg_table(c, l).ld;
     ink_status st = layer_aggregate(c, l, F, nF, n_chg, keep_old ? c->f_old[cur].as<float>() : nullptr, ld_msg,
@@ -1207,7 +1215,7 @@ static ink_status propagate_layers(ink_ctx *c, int64_t nF, int64_t n_chg, int cu
       bool want_old = keep_old && !last;
       if (want_old) API_TRY(c->c_old.reserve((size_t)nC * ld_next * 4));
       {
-        Prof p(c, INK_T_TRANSFORM);
+        Prof p(c, INK_T_TRANSFORM, l, INK_K_XFORM);
         const int32_t *rows = c->c_list.as<int32_t>();
         float *old_rows = want_old ? c->c_old.as<float>() : nullptr;
         if (!gcn) {
@@ -1430,6 +1438,133 @@ static ink_status update_features_impl(ink_ctx *c, const int32_t *node_ids, cons
   return INK_OK;
 }
 
+// ------------------------------------------------------------------------------------ user-defined events
+// key of event i for the pass over layer l: its target, or n_nodes (sorts behind every node) if it
+// belongs to another layer; value = its position in the list
+__global__ void k_user_keys(const ink_user_event *ev, int64_t n, int layer, uint32_t n_nodes, uint32_t *key, uint32_t *val) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  key[i] = ev[i].layer == layer ? (uint32_t)ev[i].target : n_nodes;
+  val[i] = (uint32_t)i;
+}
+
+// One wave per target: its events (positions pos[seg[j] .. seg[j + 1]) of the list, in list order)
+// are applied to the node's term; flag[j] = 1 if the term changed bitwise.
+__global__ __launch_bounds__(256) void k_user_apply(const int32_t *uniq, const int32_t *seg, const int32_t *n_uniq,
+                                                    const uint32_t *pos, const ink_user_event *ev, const float *rows,
+                                                    int stride, float *U, int ld, int d, uint8_t *flag) {
+  const int l = lane_id();
+  int64_t j = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kWave;
+  if (j >= *n_uniq) return;
+  const int64_t v = uniq[j];
+  const int e0 = seg[j], e1 = seg[j + 1];
+  bool chg = false;
+  for (int k = l; k < d; k += kWave) {
+    const float old = U[v * ld + k];
+    float u = old;
+    for (int e = e0; e < e1; e++) {
+      const uint32_t i = pos[e];
+      const int op = ev[i].op;
+      const float r = rows[(int64_t)i * stride + k];
+      u = op == INK_USER_SET ? r : (op == INK_USER_ADD ? __fadd_rn(u, r) : 0.f);
+    }
+    if (__float_as_uint(u) != __float_as_uint(old)) { U[v * ld + k] = u; chg = true; }
+  }
+  const bool any = __ballot(chg) != 0ull;
+  if (l == 0) flag[j] = any ? 1 : 0;
+}
+
+struct UserState {
+  int64_t n;                       // events in the list
+  int row_stride;                  // floats between the rows of two events
+  int64_t per_layer[INK_MAX_LAYERS + 1];   // events that name each layer
+};
+
+// the nodes whose term of layer l changed -> ascending list (the rows this layer re-transforms for its own reasons)
+static ink_status user_rows_of(ink_ctx *c, int l, void *state, const int32_t **rows, int64_t *n_rows) {
+  const UserState *u = (const UserState *)state;
+  *rows = nullptr; *n_rows = 0;
+  const int64_t m = u->per_layer[l];
+  if (m == 0) return INK_OK;
+  hipStream_t s = c->stream;
+  Prof p(c, INK_T_EVENTS);
+  uint32_t *key = c->u_key.as<uint32_t>(), *val = c->u_val.as<uint32_t>();
+  hipLaunchKernelGGL(k_user_keys, grid1(u->n), dim3(256), 0, s, (const ink_user_event *)c->u_ev.p, u->n, l, (uint32_t)c->n, key, val);
+  API_TRY(hipGetLastError());
+  // stable: the layer's events come first, grouped by target, each group in list order
+  API_TRY(radix_sort_pairs(c->ws, key, val, u->n, c->id_bits + 1, s));
+  int32_t *n_uniq = &c->d_cnt->v[C_TMP0], *n_chg = &c->d_cnt->v[C_TMP1];
+  API_TRY(segment_heads(c->ws, key, m, c->u_uniq.as<int32_t>(), c->u_seg.as<int32_t>(), n_uniq, s));
+  hipLaunchKernelGGL(k_user_apply, grid1(m * kWave), dim3(256), 0, s, (const int32_t *)c->u_uniq.as<int32_t>(),
+                     (const int32_t *)c->u_seg.as<int32_t>(), (const int32_t *)n_uniq, (const uint32_t *)val,
+                     (const ink_user_event *)c->u_ev.p, (const float *)c->u_rows.p, u->row_stride,
+                     c->USER[l].f(), c->USER[l].ld, c->USER[l].d, c->u_flag.as<uint8_t>());
+  API_TRY(hipGetLastError());
+  API_TRY(read_counters(c));
+  const int64_t nu = c->h_cnt->v[C_TMP0];
+  API_TRY(compact_flags_u8(c->ws, c->u_flag.as<uint8_t>(), nu, c->u_idx.as<int32_t>(), n_chg, s));
+  hipLaunchKernelGGL(k_gather_i32, grid1(nu), dim3(256), 0, s, (const int32_t *)c->u_uniq.as<int32_t>(),
+                     (const int32_t *)c->u_idx.as<int32_t>(), 0, (const int32_t *)n_chg, c->u_list.as<int32_t>());
+  API_TRY(hipGetLastError());
+  API_TRY(read_counters(c));
+  *rows = c->u_list.as<int32_t>();
+  *n_rows = c->h_cnt->v[C_TMP1];
+  return INK_OK;
+}
+
+static ink_status apply_user_events_impl(ink_ctx *c, const ink_user_event *events, const float *rows, int32_t row_stride,
+                                         int64_t n, ink_update_result *out) {
+  if (!out || n < 0 || (n > 0 && (!events || !rows))) return fail(c, INK_E_ARG, "ink_apply_user_events: NULL argument or negative n");
+  if (!c->inferred) return fail(c, INK_E_STATE, "ink_apply_user_events: call ink_full_infer first");
+  if (c->kind == INK_MODEL_GCN) return fail(c, INK_E_ARG, "ink_apply_user_events: not supported for INK_AGG_GCN_SYM");
+  if (n >= (1ll << 30)) return fail(c, INK_E_ARG, "ink_apply_user_events: too many events");
+  UserState u;
+  memset(&u, 0, sizeof(u));
+  u.n = n;
+  u.row_stride = row_stride;
+  int last = 0;
+  for (int64_t i = 0; i < n; i++) {
+    const ink_user_event &e = events[i];
+    if (e.layer < 1 || e.layer > c->n_layers) return fail(c, INK_E_RANGE, "ink_apply_user_events: layer out of range");
+    if (e.target < 0 || e.target >= c->n) return fail(c, INK_E_RANGE, "ink_apply_user_events: node id out of range");
+    if (e.op < INK_USER_SET || e.op > INK_USER_CLEAR) return fail(c, INK_E_ARG, "ink_apply_user_events: unknown op");
+    if (row_stride < c->H[e.layer].d) return fail(c, INK_E_ARG, "ink_apply_user_events: row_stride below the layer's width");
+    u.per_layer[e.layer]++;
+    last = std::max(last, (int)e.layer);
+  }
+  auto t0 = std::chrono::steady_clock::now();
+  memset(out, 0, sizeof(*out));
+  memset(&c->stats, 0, sizeof(c->stats));
+  c->stats.n_layers = c->n_layers;
+  if (n == 0) return INK_OK;
+  c->affected_mode = false;
+  hipStream_t s = c->stream;
+  // everything that can fail for lack of memory comes before the first term is touched
+  for (int l = 1; l <= last; l++)
+    if (u.per_layer[l] > 0 && !c->USER[l].p) API_TRY(alloc_table(c->USER[l], c->n_cap, c->H[l].d));
+  API_TRY(c->u_ev.reserve((size_t)n * sizeof(ink_user_event)));
+  API_TRY(c->u_rows.reserve((size_t)n * row_stride * 4));
+  for (DevBuf *b : {&c->u_key, &c->u_val, &c->u_uniq, &c->u_seg, &c->u_idx, &c->u_list}) API_TRY(b->reserve((size_t)(n + 2) * 4));
+  API_TRY(c->u_flag.reserve((size_t)n + 64));
+  API_TRY(c->c_list.reserve((size_t)c->n * 4));
+  API_TRY(hipMemcpyAsync(c->u_ev.p, events, (size_t)n * sizeof(ink_user_event), hipMemcpyHostToDevice, s));
+  API_TRY(hipMemcpyAsync(c->u_rows.p, rows, (size_t)n * row_stride * 4, hipMemcpyHostToDevice, s));
+  LayerRows own{last, user_rows_of, &u};
+  ink_status st = propagate_layers(c, 0, 0, 0, 0, 0, nullptr, 0, out, &own);
+  if (st != INK_OK) return st;
+  API_TRY(hipStreamSynchronize(s));
+  prof_collect(c);
+  c->stats.ms_total = std::chrono::duration<float, std::milli>(std::chrono::steady_clock::now() - t0).count();
+  return INK_OK;
+}
+
+extern "C" ink_status ink_apply_user_events(ink_ctx *c, const ink_user_event *events, const float *rows,
+                                            int32_t row_stride, int64_t n, ink_update_result *out) {
+  if (!c) return INK_E_ARG;
+  if (c->broken) return fail(c, INK_E_STATE, kBrokenMsg);
+  return seal(c, apply_user_events_impl(c, events, rows, row_stride, n, out));
+}
+
 // ------------------------------------------------------------------------------------ node arrival
 __global__ void k_iota_i32(int32_t *out, int64_t n, int32_t first) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -1531,11 +1666,11 @@ extern "C" ink_status ink_get_layer(ink_ctx *c, int32_t layer, int32_t which, in
   if (!c) return INK_E_ARG;
   if (c->broken) return fail(c, INK_E_STATE, kBrokenMsg);
   if (!c->inferred) return fail(c, INK_E_STATE, "ink_get_layer: call ink_full_infer first");
-  if (layer < 0 || layer > c->n_layers || which < 0 || which > 4 || (which > 0 && layer == 0))
+  if (layer < 0 || layer > c->n_layers || which < 0 || which > 5 || (which > 0 && layer == 0))
     return fail(c, INK_E_RANGE, "ink_get_layer: layer / which out of range");
   if (row0 < 0 || nrows < 0 || row0 + nrows > c->n) return fail(c, INK_E_RANGE, "ink_get_layer: rows out of range");
-  if (which >= 2 && !c->is_select) return fail(c, INK_E_ARG, "ink_get_layer: no argument table for sum-type aggregators");
-  const Table &t = which == 0 ? c->H[layer] : (which == 1 ? c->A[layer] : (which == 2 ? c->ARG[layer] : (which == 3 ? c->UB[layer] : c->ARG2[layer])));
+  if (which >= 2 && which <= 4 && !c->is_select) return fail(c, INK_E_ARG, "ink_get_layer: no argument table for sum-type aggregators");
+  const Table &t = which == 0 ? c->H[layer] : (which == 1 ? c->A[layer] : (which == 2 ? c->ARG[layer] : (which == 3 ? c->UB[layer] : (which == 4 ? c->ARG2[layer] : c->USER[layer]))));
   if (!t.p) return fail(c, INK_E_ARG, "ink_get_layer: table not kept for this model");
   if (width_out) *width_out = t.d;
   if (nrows == 0) return INK_OK;

@@ -75,7 +75,7 @@ struct DevLayer {
 };
 
 constexpr int kStripes = 64;
-enum { ST_EXPOSED = 0, ST_REGATHER, ST_ACHG, ST_NODEL, ST_NOEFFECT, ST_COVERED, ST_PAD6, ST_PAD7, ST_N };
+enum { ST_EXPOSED = 0, ST_REGATHER, ST_ACHG, ST_NODEL, ST_NOEFFECT, ST_COVERED, ST_REGATHER_LONG, ST_PAD7, ST_N };
 struct Counters {            // device-written, host-read through pinned memory
   int32_t v[32];
   // statistics that many waves bump: striped by workgroup so that no single address is contended
@@ -94,9 +94,10 @@ struct HostCounters {
 };
 // slots of Counters::v: event count of the next layer, unique targets, long rows listed, rows to
 // transform, rows changed, chunks of long rows, distinct ops of a batch, scratch of the graph stage,
+// (C_NEXP: exposed rows of moderate length listed for the recompute, next to the long ones in C_NBIG)
 // touched nodes and block chunks of the out side (single-workgroup graph stage), and two 64-bit
 // slots (pool tops handed to the apply kernels).  Slot 0 flags a malformed update batch.
-enum { C_ERR = 0, C_NEV = 1, C_NT, C_NBIG, C_NC, C_NEXT, C_NCHUNK, C_NOPS, C_TMP0, C_TMP1, C_TMP2, C_TMP3,
+enum { C_ERR = 0, C_NEV = 1, C_NT, C_NBIG, C_NEXP, C_NC, C_NEXT, C_NCHUNK, C_NOPS, C_TMP0, C_TMP1, C_TMP2, C_TMP3,
        C_OT, C_OCH, C_TOP64 = 16, C_TOP64B = 18 };
 
 }  // namespace ink
@@ -128,6 +129,8 @@ struct ink_ctx {
   // GCN only: XW[l] = unscaled transformed messages h_{l-1} W_l, H-like scaled copies live in Msc[l]
   std::vector<ink::Table> XW, Msc;
   float *cnorm = nullptr;            // GCN: (indeg + 1)^(-1/2) per node
+  std::vector<ink::Table> USER;      // per layer: the term of user-defined events (allocated by the first event of the layer)
+  ink::DevBuf u_ev, u_rows, u_key, u_val, u_uniq, u_seg, u_flag, u_idx, u_list;   // work buffers of ink_apply_user_events
 
   ink::PrimWorkspace ws;
   ink::Counters *d_cnt = nullptr;    // device counters
@@ -155,17 +158,41 @@ struct ink_ctx {
   ink::DevBuf c_old;                 // previous table rows of the transformed rows (sum-type)
   ink::DevBuf b_touch_in;            // destinations touched by the current batch
   int64_t n_touched_in = 0;
+  ink::DevBuf exp_list;              // exposed rows of moderate length, listed by the event kernel
   ink::DevBuf big_list, big_part_v, big_part_i, big_part_s, big_part_j, big_pref;   // cooperative re-gather of long rows
   ink::DevBuf stage0, stage1;        // transform staging
   ink::DevBuf res_ids, res_emb;      // result of the last batch
 
   ink_stats stats;
-  struct Pending { int cls; hipEvent_t a, b; };
+  struct Pending { int cls, layer, kern; hipEvent_t a, b; };
   std::vector<hipEvent_t> ev_free;
   std::vector<Pending> ev_pending;
 };
 
 namespace ink {
+
+// Times what is launched during its life with a pair of HIP events on the context's stream (only
+// while profiling is on): into the class total `cls` (>= 0) and / or into kernel slot `kern` of
+// layer `layer` (1-based).  Launch counts per class are always kept.
+struct Prof {
+  ink_ctx *c; int cls, layer, kern; hipEvent_t a = nullptr, b = nullptr;
+  Prof(ink_ctx *c_, int cls_, int layer_ = 0, int kern_ = -1) : c(c_), cls(cls_), layer(layer_), kern(kern_) {
+    if (cls >= 0) c->stats.launches[cls]++;
+    if (!c->profile) return;
+    while (c->ev_free.size() < 2) { hipEvent_t e; if (hipEventCreate(&e) != hipSuccess) return; c->ev_free.push_back(e); }
+    a = c->ev_free.back(); c->ev_free.pop_back();
+    b = c->ev_free.back(); c->ev_free.pop_back();
+    (void)hipEventRecord(a, c->stream);
+  }
+  ~Prof() {
+    if (!a) return;
+    (void)hipEventRecord(b, c->stream);
+    c->ev_pending.push_back({cls, layer, kern, a, b});
+  }
+};
+struct KernelTimer : Prof {
+  KernelTimer(ink_ctx *c_, int layer_, int kern_) : Prof(c_, -1, layer_, kern_) {}
+};
 
 // ---- graph store (graph.hip)
 hipError_t graph_build(ink_ctx *c, const int64_t *rowptr_h, const int32_t *col_h);
@@ -190,6 +217,7 @@ struct AggArgs {
   bool is_min;
   int big_deg;                      // rows with more in-neighbours go to the chunked cooperative path
   int64_t big_grid;                 // workgroups to launch for the chunk kernel (it strides if there are more chunks)
+  int layer;                        // 1-based layer the launch belongs to (per-kernel timing)
   int count_cond;                   // tally the per-target condition counters (only the first 256-column block of a wide row does)
 };
 // full re-aggregation of every node (targets == nullptr) or of a target list; flags rows whose
@@ -231,6 +259,7 @@ struct XformArgs {
   const float *in_bias; int in_relu;   // mode 3
   float *h_store; int ld_hs;           // mode 3: where x (= h_l) is written, one row per node
   const float *out_scale;   // per-node factor applied to the output row (after bias), null: none
+  const float *user; int ld_user;      // per-node term added after the bias, before the activation (to_table only), null: none
 };
 hipError_t xform_run(ink_ctx *c, const XformArgs &x);
 // position of W[k][col] in the padded device copy: k-chunks of 32, inside a chunk one row of 32 per

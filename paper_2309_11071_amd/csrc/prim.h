@@ -20,7 +20,7 @@ struct DevBuf {            // grow-only device buffer (contents are NOT kept acr
     if (bytes <= cap) return hipSuccess;
     if (fixed) return hipErrorOutOfMemory;
     if (p) { hipError_t e = hipFree(p); p = nullptr; cap = 0; if (e != hipSuccess) return e; }
-    size_t want = bytes + bytes / 4 + 256;
+    size_t want = 2 * bytes + 256;       // generous: a buffer that grows again stalls the stream (free + allocate)
     hipError_t e = hipMalloc(&p, want);
     if (e != hipSuccess) { p = nullptr; return e; }
     cap = want;

@@ -288,6 +288,7 @@ __global__ __launch_bounds__(NW * 64) void k_xform(XformArgs x) {
       if (row < 0) continue;
       float v = acc[i][r];
       if (x.bias) v = __fadd_rn(v, bias);
+      if (x.user) v = __fadd_rn(v, x.user[sout[rl] * x.ld_user + col]);
       if (x.out_scale) v = __fmul_rn(v, x.out_scale[sout[rl]]);
       if (x.relu) v = v > 0.f ? v : 0.f;
       int64_t j = r0 + rl;

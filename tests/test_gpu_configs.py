@@ -1,6 +1,6 @@
-"""Parity at the benchmark's sizes: configs 2 and 3 at full size (the oracle needs 10-20 s per
-full inference there), configs 4 and 5 on 1/16-scale replicas and, at their full size of 20 M
-nodes, on sampled rows that the oracle checks layer by layer.  State after a sequence of batches
+"""Parity at the benchmark's sizes: configs 2, 3 and 5 at full size against complete, independent
+oracle inferences; config 4 on a 1/16-scale replica and, at its full size of 20 M nodes, on
+sampled rows that the oracle checks layer by layer.  State after a sequence of batches
 is compared table by table with a fresh oracle inference of the final snapshot: an error made by
 any earlier batch would persist in the cache."""
 import numpy as np
@@ -8,7 +8,7 @@ import pytest
 
 import oracle
 import synth
-from util import Harness, scaled_rel_err
+from util import Harness, check_accumulated, chain_lengths, magnitude_inference
 
 pytestmark = pytest.mark.gpu
 
@@ -36,21 +36,29 @@ def test_config3_full_size_exact():
 
 
 def test_config2_full_size_within_tolerance():
+    """Config 2 at its full size against the fp64 oracle: the whole cache after the full inference,
+    again after two batches, then the third batch's changed set and rows and the cache once more.
+    Every accumulated table is held to the stated per-row metric (util.check_accumulated)."""
     cfg = synth.get_config(2)
     h = Harness(cfg, precision="f64")
+    h.check_state(exact=False)
     from paper_2309_11071_amd.binding import make_updates
-    for b in range(3):
+    for b in range(2):
         op, bs, bd = h.sampler.next_batch()
         res = h.ink.apply_updates(make_updates(op, bs, bd))
         h.keys, n_ins, n_del, n_noop = oracle.apply_batch(h.keys, op, bs, bd)
         assert (res["n_applied_ins"], res["n_applied_del"], res["n_noop"]) == (n_ins, n_del, n_noop)
         assert res["n_changed"] > 1000
-    post = oracle.full_infer(*oracle.csr_from_keys(h.n, h.keys), h.X, h.model, "f64")
-    for l in (1, 2):
-        err = scaled_rel_err(h.ink.get_layer(l, 0), post["h"][l])
-        assert err <= 1e-5, (l, err)
+    h.ref = oracle.full_infer(*oracle.csr_from_keys(h.n, h.keys), h.X, h.model, "f64")
+    h.check_state(exact=False)
+    op, bs, bd = h.sampler.next_batch()
+    res, want = h.step(op, bs, bd, exact=False)            # changed set and returned rows of the third batch
+    assert want.size > 1000
+    h.check_state(exact=False)
     ids = res["changed_ids"]
     assert np.array_equal(h.ink.get_layer(2, 0)[ids].view(np.uint32), res["embeddings"].view(np.uint32))
+    # the relative bar is met outright by all but a sliver of the rows
+    assert all(r["rows_beyond_strict"] <= r["rows"] // 1000 for r in h.reports), h.reports
     h.ink.close()
 
 
@@ -102,18 +110,74 @@ def _rows_of(ink, layer, which, rows):
     return np.concatenate([ink.get_layer(layer, which, int(v), 1) for v in rows], axis=0)
 
 
-@pytest.mark.parametrize("cfg_id", [5, 4])
-def test_configs_4_and_5_full_size_sampled_rows(cfg_id):
-    """20 M nodes / 400 M edges, batches of 10 000 as bench.py runs them.  A full oracle inference
-    takes minutes there, so a sample of rows (random nodes, the highest in-degrees, destinations of
-    the last batch) is checked layer by layer: the oracle aggregates the library's own message
-    table over the row's neighbour list (kept on the oracle's side from the initial graph and the
-    ops) and combines it; both must reproduce the library's cached row — bit for bit for max, to
-    1e-5 for the accumulated sums."""
+def _assert_table_equal(ink, layer, which, ref, what, chunk=2_000_000):
+    """A cached table of the library against the oracle's, bit for bit, fetched chunk by chunk."""
+    n = ref.shape[0]
+    for r0 in range(0, n, chunk):
+        got = ink.get_layer(layer, which, r0, min(chunk, n - r0))
+        want = ref[r0:r0 + got.shape[0]]
+        if not np.array_equal(got.view(np.uint32), want.view(np.uint32)):
+            bad = np.nonzero((got.view(np.uint32) != want.view(np.uint32)).any(axis=1))[0]
+            raise AssertionError("%s differs in %d rows of [%d, %d), first %d" % (what, bad.size, r0, r0 + got.shape[0], r0 + bad[0]))
+
+
+def test_config5_full_size_whole_state_exact():
+    """Config 5 as bench.py runs it (20 M nodes, 400 M edges, batches of 10 000): after the first
+    batch and again after the second, EVERY row of every cached table (aggregate, holder ids, layer
+    output; three layers) is compared bit for bit with an independent oracle inference of that
+    snapshot, which streams one layer at a time from its own previous layer.  The second batch's
+    changed-node set and returned rows are compared with the difference of the two inferences."""
     from paper_2309_11071_amd import Ink
     from paper_2309_11071_amd.binding import make_updates
-    cfg = synth.get_config(cfg_id)
-    exact = cfg.agg in ("max", "min")
+    cfg = synth.get_config(5)
+    src, dst = synth.make_graph(cfg)
+    n = cfg.n_nodes
+    rp, col = synth.in_csr_from_edges(n, src, dst, assume_sorted=True)
+    X = synth.make_features(cfg)
+    model = synth.make_model(cfg)
+    ink = Ink(rp, col, X, model)
+    ink.full_infer()
+    sampler = synth.BatchSampler(cfg, src, dst)
+    keys = synth.edge_keys(src, dst)
+    del src, dst, rp, col
+    k = len(model["layers"])
+    final = []
+    for b in range(2):
+        op, bs, bd = sampler.next_batch()
+        res = ink.apply_updates(make_updates(op, bs, bd))
+        keys, n_ins, n_del, n_noop = oracle.apply_batch(keys, op, bs, bd)
+        assert (res["n_applied_ins"], res["n_applied_del"], res["n_noop"]) == (n_ins, n_del, n_noop)
+        rp2, col2 = oracle.csr_from_keys(n, keys)
+        h_prev = X
+        for l in range(1, k + 1):
+            a_ref, g_ref = oracle.agg_select(rp2, col2, h_prev)
+            _assert_table_equal(ink, l, 1, a_ref, "batch %d: alpha_%d" % (b, l))
+            _assert_table_equal(ink, l, 2, g_ref, "batch %d: holder ids of layer %d" % (b, l))
+            del g_ref
+            h_ref = oracle.transform(model, l - 1, a_ref, h_prev, "f32")
+            del a_ref
+            _assert_table_equal(ink, l, 0, h_ref, "batch %d: h_%d" % (b, l))
+            h_prev = h_ref
+        final.append(h_prev)
+        del rp2, col2
+    want = np.nonzero(oracle.rows_differ(final[0], final[1]))[0].astype(np.int32)
+    assert want.size > 100000
+    assert np.array_equal(res["changed_ids"], want), "changed-node set of the second batch differs"
+    assert np.array_equal(res["embeddings"].view(np.uint32), final[1][want].view(np.uint32))
+    ink.close()
+
+
+def test_config4_full_size_sampled_rows():
+    """Config 4 at its full size (20 M nodes / 400 M edges, batches of 10 000).  An independent fp64
+    oracle inference of this snapshot would take a quarter of an hour, so this is a sampled,
+    layer-wise check (parity at this size is otherwise unpinned): for random nodes, the highest
+    in-degrees and destinations of the last batch the oracle sums the library's own message table
+    over the row's neighbour list -- kept on the oracle's side from the initial graph and the ops --
+    and combines it; both must reproduce the library's cached row under the stated per-row metric.
+    The complete comparison of this model runs at 1/16 scale (test_configs_4_and_5_at_one_sixteenth)."""
+    from paper_2309_11071_amd import Ink
+    from paper_2309_11071_amd.binding import make_updates
+    cfg = synth.get_config(4)
     src, dst = synth.make_graph(cfg)
     n = cfg.n_nodes
     rp, col = synth.in_csr_from_edges(n, src, dst, assume_sorted=True)
@@ -137,24 +201,25 @@ def test_configs_4_and_5_full_size_sampled_rows(cfg_id):
                                      rng.choice(batches[-1][2], size=400, replace=False)])).astype(np.int64)
     rp_s, col_s = _neighbour_lists(rp, col, rows, batches)
     assert rp_s[-1] > 100000
+    deg_s = np.diff(rp_s)
     k = len(model["layers"])
-    prec = "f32" if exact else "f64"
+    k_lin = chain_lengths(model)
+    absw = lambda w: None if w is None else np.abs(w)
     for l in range(1, k + 1):
         M = X if l == 1 else ink.get_layer(l - 1, 0)              # the library's own m_l = h_{l-1}
         if l == 1:
             assert np.array_equal(_rows_of(ink, 0, 0, rows[:50]), X[rows[:50]])
+        L = model["layers"][l - 1]
         a_gpu = _rows_of(ink, l, 1, rows)
         h_gpu = _rows_of(ink, l, 0, rows)
-        if exact:
-            a_ref, g_ref = oracle.agg_select(rp_s, col_s, M, is_min=cfg.agg == "min")
-            assert np.array_equal(a_gpu.view(np.uint32), a_ref.view(np.uint32)), "alpha_%d" % l
-            assert np.array_equal(_rows_of(ink, l, 2, rows), g_ref), "argmax_%d" % l
-            h_ref = oracle.transform(model, l - 1, a_gpu, M[rows], prec)
-            assert np.array_equal(h_gpu.view(np.uint32), h_ref.view(np.uint32)), "h_%d" % l
-        else:
-            a_ref = oracle.agg_sum(rp_s, col_s, M)
-            assert scaled_rel_err(a_gpu, a_ref) <= 1e-5, "sum_%d" % l
-            h_ref = oracle.transform(model, l - 1, a_ref, M[rows], prec)
-            assert scaled_rel_err(h_gpu, h_ref) <= 1e-5, "h_%d" % l
+        a_ref = oracle.agg_sum(rp_s, col_s, M)
+        a_mag = oracle.agg_sum(rp_s, col_s, np.abs(M))
+        rep = check_accumulated(a_gpu, a_ref, a_mag, deg_s, 0, 1, 1e-5, "sum_%d" % l)
+        h_ref = oracle.transform(model, l - 1, a_ref, M[rows], "f64")
+        x_mag = (np.abs(M[rows]).astype(np.float64) + a_mag).astype(np.float32)
+        z_mag = oracle.linear(x_mag, np.abs(L["W_neigh"]), absw(L.get("bias")), False, "f64")
+        h_mag = oracle.linear(z_mag, np.abs(L["W_mlp2"]), absw(L.get("bias_mlp2")), False, "f64")
+        rep2 = check_accumulated(h_gpu, h_ref, h_mag, deg_s, k_lin[l - 1], 1, 1e-5, "h_%d" % l)
+        print("config 4 sampled rows, layer %d: %s ; %s" % (l, rep, rep2))
         del M
     ink.close()
