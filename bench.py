@@ -235,6 +235,7 @@ def main():
             "as_designed_GBs": designed / 1e9 / (avg_ms / 1e3),
             "traffic": traffic, "traffic_source": traffic_src,
             "measured_copy_GBs": copy_gbs,
+            "measured_random_row_gather_GBs": measured_gather_rate(torch, ink.agg_widths[li]),
             "share_of_step": kern_ms[(li, kern)] / args.steps / (total / args.steps * 1e3),
             "units_per_launch": {"targets": L["n_targets"], "events": L["n_events"], "distinct_sources": L["n_sources"],
                                  "row_floats": d},
@@ -367,6 +368,28 @@ def measured_copy_rate(torch):
         e1.record()
         torch.cuda.synchronize()
         return 5 * 2 * a.numel() * 4 / 1e9 / (e0.elapsed_time(e1) / 1e3)
+    except RuntimeError:
+        return None
+
+
+def measured_gather_rate(torch, row_floats):
+    """What a plain gather kernel reaches on random rows of the dominant kernel's width (bytes of the
+    rows read + written per second): 2^23 random rows out of a 4 GiB table, far larger than L2 and MALL."""
+    try:
+        rows = (1 << 30) // row_floats
+        table = torch.empty(rows * row_floats, dtype=torch.float32, device="cuda").normal_().view(rows, row_floats)
+        g = torch.Generator(device="cuda")
+        g.manual_seed(11)
+        idx = torch.randint(0, rows, (1 << 23,), device="cuda", generator=g)
+        out = torch.index_select(table, 0, idx)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(3):
+            torch.index_select(table, 0, idx, out=out)
+        e1.record()
+        torch.cuda.synchronize()
+        return 3 * 2 * idx.numel() * row_floats * 4 / 1e9 / (e0.elapsed_time(e1) / 1e3)
     except RuntimeError:
         return None
 

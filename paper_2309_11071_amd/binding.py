@@ -78,7 +78,8 @@ _lib = None
 
 
 def lib_path():
-    return os.path.join(HERE, "libink.so")
+    """libink.so next to this file, or the build named by INK_LIBRARY (to compare builds)."""
+    return os.environ.get("INK_LIBRARY") or os.path.join(HERE, "libink.so")
 
 
 def load_library():

@@ -75,6 +75,7 @@ __device__ __forceinline__ void merge2i(float ov, int oi, float os, int osi, flo
 
 __device__ __forceinline__ float4 ld4(const float *p) { return *reinterpret_cast<const float4 *>(p); }
 
+
 // Reduce (bv, bi) over the lane groups of a wave (groups are LPR lanes wide); every lane ends
 // with the result for its 4 dimensions.
 template <bool IS_MIN, int LPR> __device__ __forceinline__ void reduce_groups(F4 &bv, I4 &bi, F4 &sv) {
@@ -396,47 +397,51 @@ __device__ __forceinline__ void issue_batch(const AggArgs &a, uint32_t mine, int
     const uint32_t x = __shfl(mine, k < kWave ? k : 0, kWave);
     const bool valid = k < cntw && lane_on;
     b.code[u] = valid ? x : kEvNone;
+    b.row[u] = make_float4(0.f, 0.f, 0.f, 0.f);
     if (valid && (x >> kEvKindShift) != EV_DEL) b.row[u] = ld4(a.M + (int64_t)(x & kEvIdMask) * a.ldm + 4 * q);
   }
 }
 
 template <bool IS_MIN> struct EvAcc {
   F4 cv; I4 ci; F4 cs;       // best candidate, its source, runner-up candidate value
-  // per dimension c: bit c = reset (the holder left or got worse), bit 4 + c = the recorded
-  // runner-up left or changed its message (one register instead of eight flags)
-  unsigned fl;
+  bool reset[4];             // per dimension: the holder left or got worse
+  bool inv2[4];              // per dimension: the recorded runner-up left or changed its message
   bool any_del;              // the segment cancels something: a removed edge or a changed source
   __device__ __forceinline__ void init() {
-    fl = 0u; any_del = false;
+    any_del = false;
 #pragma unroll
-    for (int c = 0; c < 4; c++) { cv.v[c] = worst<IS_MIN>(); ci.v[c] = 0x7fffffff; cs.v[c] = worst<IS_MIN>(); }
+    for (int c = 0; c < 4; c++) {
+      cv.v[c] = worst<IS_MIN>(); ci.v[c] = 0x7fffffff; cs.v[c] = worst<IS_MIN>();
+      reset[c] = false; inv2[c] = false;
+    }
   }
 };
 
+// Written without branches: the per-lane conditions become wave masks in scalar registers and the
+// updates selects, a fraction of the instructions the branching form compiles to (this loop runs
+// once per event and lane group and is half of the kernel's vector instructions).
 template <bool IS_MIN, int U>
 __device__ __forceinline__ void consume_batch(const EvBatch<U> &b, const Cached<IS_MIN> &k, EvAcc<IS_MIN> &s) {
 #pragma unroll
   for (int u = 0; u < U; u++) {
     const uint32_t x = b.code[u];
-    if (x == kEvNone) continue;
-    const uint32_t kind = x >> kEvKindShift;
+    const uint32_t kind = x >> kEvKindShift;           // 3 for "no event"
     const int id = (int)(x & kEvIdMask);
-    s.any_del |= kind != EV_ADD;
-    if (kind != EV_ADD) {
+    const bool is_del = kind == EV_DEL, is_add = kind == EV_ADD, is_chg = kind == EV_CHG;
+    const bool cancels = is_del | is_chg, has_row = is_add | is_chg;
+    s.any_del |= cancels;
+    const float r[4] = {b.row[u].x, b.row[u].y, b.row[u].z, b.row[u].w};
 #pragma unroll
-      for (int c = 0; c < 4; c++) s.fl |= (unsigned)(k.o2.v[c] == id) << (4 + c);
-    }
-    if (kind == EV_DEL) {
-#pragma unroll
-      for (int c = 0; c < 4; c++) s.fl |= (unsigned)(k.oi.v[c] == id) << c;
-    } else {
-      const bool changed = kind == EV_CHG;
-      const float r[4] = {b.row[u].x, b.row[u].y, b.row[u].z, b.row[u].w};
-#pragma unroll
-      for (int c = 0; c < 4; c++) {
-        s.fl |= (unsigned)(changed && k.oi.v[c] == id && better<IS_MIN>(k.ov.v[c], r[c])) << c;
-        take2<IS_MIN>(r[c], id, s.cv.v[c], s.ci.v[c], s.cs.v[c]);
-      }
+    for (int c = 0; c < 4; c++) {      // & and | on purpose: no short-circuit, no branch
+      const bool holds = k.oi.v[c] == id;
+      s.inv2[c] |= cancels & (k.o2.v[c] == id);
+      s.reset[c] |= holds & (is_del | (is_chg & better<IS_MIN>(k.ov.v[c], r[c])));
+      // take2, applied only where the event carries a row
+      const bool first = has_row & (better<IS_MIN>(r[c], s.cv.v[c]) | ((r[c] == s.cv.v[c]) & (id < s.ci.v[c])));
+      const bool second = has_row & !first & better<IS_MIN>(r[c], s.cs.v[c]);
+      s.cs.v[c] = first ? s.cv.v[c] : (second ? r[c] : s.cs.v[c]);
+      s.cv.v[c] = first ? r[c] : s.cv.v[c];
+      s.ci.v[c] = first ? id : s.ci.v[c];
     }
   }
 }
@@ -450,8 +455,10 @@ __device__ __forceinline__ void finish_target(const AggArgs &a, int v, const Cac
   const int l = lane_id();
   const F4 &ov = k.ov; const I4 &oi = k.oi; const F4 &ou = k.ou; const I4 &o2 = k.o2;
   F4 &cv = s.cv; I4 &ci = s.ci; F4 &cs = s.cs;
-  unsigned fl = s.fl;
-  // combine the lane groups
+  // combine the lane groups: the flags travel packed in one register
+  unsigned fl = 0u;
+#pragma unroll
+  for (int c = 0; c < 4; c++) fl |= ((unsigned)s.reset[c] << c) | ((unsigned)s.inv2[c] << (4 + c));
 #pragma unroll
   for (int off = LPR; off < kWave; off <<= 1) fl |= (unsigned)__shfl_xor((int)fl, off, kWave);
   bool reset[4], inv2[4];

@@ -82,7 +82,7 @@ def test_user_event_errors_change_nothing():
     res = h.ink.apply_user_events([], np.zeros((0, 16), np.float32))
     assert res["n_changed"] == 0
     h.ink.close()
-    g = Harness(synth.get_config(2, 512), precision="f64")
+    g = Harness(synth.get_config(2, 64), precision="f64")
     with pytest.raises(InkError) as e:
         g.ink.apply_user_events([(1, 0, SET)], np.zeros((1, 256), np.float32))
     assert e.value.status == 1
