@@ -186,7 +186,7 @@ def main():
     for i in range(args.warmup):
         ink.apply_updates_device(batches[i].data_ptr(), cfg.batch, affected=aff)
     lat, changed = [], 0
-    per_class, kern_ms, kern_n = {}, {}, {}
+    per_class, kern_ms, kern_n, kern_each = {}, {}, {}, {}
     layer_tot, layer_src = None, None
     torch.cuda.synchronize()
     t_start = time.perf_counter()
@@ -203,6 +203,7 @@ def main():
                 if v > 0:
                     kern_ms[(li, k_)] = kern_ms.get((li, k_), 0.0) + v
                     kern_n[(li, k_)] = kern_n.get((li, k_), 0) + 1
+                    kern_each.setdefault((li, k_), []).append(v)
         if layer_tot is None:
             layer_tot = [dict(L) for L in st["layers"]]
         else:
@@ -230,6 +231,7 @@ def main():
             "achieved": ach, "frac": ach / HBM_PEAK_GBS,
             "kernel": "%s, layer %d" % (KERNEL_NAMES[kern], li + 1),
             "launches": launches, "avg_launch_ms": avg_ms,
+            "median_launch_ms": float(np.median(kern_each[(li, kern)])),
             "algorithmic_bytes_per_launch": alg,
             "as_designed_bytes_per_launch": designed,
             "as_designed_GBs": designed / 1e9 / (avg_ms / 1e3),
@@ -239,6 +241,7 @@ def main():
             "share_of_step": kern_ms[(li, kern)] / args.steps / (total / args.steps * 1e3),
             "units_per_launch": {"targets": L["n_targets"], "events": L["n_events"], "distinct_sources": L["n_sources"],
                                  "row_floats": d},
+            "above_hbm_peak": bool(ach > HBM_PEAK_GBS),     # then the launch re-reads rows that L2 / MALL serve: see traffic
             "note": "achieved = bytes the method must move for this launch (each distinct source row once, value and "
                     "holder row of each target read and written) / HIP-event time of this kernel; as_designed adds the "
                     "per-event source-row reads that the caches serve and the two runner-up tables"})

@@ -207,7 +207,8 @@ __device__ __forceinline__ void mark_bit(uint64_t *bm, int v) {
 // what a recompute launch does besides storing the rows
 enum { FULL_COMPARE = 1,        // compare with the cached row: store and mark only what changed
        FULL_COUNT_GATHER = 2,   // tally the neighbour rows fetched
-       FULL_COUNT_CHANGED = 4 };// tally the rows whose value changed
+       FULL_COUNT_CHANGED = 4,  // tally the rows whose value changed
+       FULL_COUNT_LONG = 8 };   // tally the neighbour rows that go to the long-row path
 
 // One wave per row, the grid strides over the rows; n_targets_dev (optional) is the device-side
 // row count, n_targets then only bounds it.
@@ -223,10 +224,10 @@ __global__ __launch_bounds__(256) void k_agg_full(AggArgs a, const int32_t *targ
   for (int64_t wid = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kWave; wid < n_targets; wid += stride) {
     int v = targets ? targets[wid] : (int)wid;
     int deg = a.in_deg[v];
-    if ((flags & FULL_COUNT_GATHER) && l == 0) {
+    if ((flags & FULL_COUNT_GATHER) && l == 0)
       atomicAdd(&cnt->stripe[blockIdx.x % kStripes][ST_REGATHER], (unsigned long long)deg);
-      if (deg > a.big_deg) atomicAdd(&cnt->stripe[blockIdx.x % kStripes][ST_REGATHER_LONG], (unsigned long long)deg);
-    }
+    if ((flags & FULL_COUNT_LONG) && deg > a.big_deg && l == 0)     // few rows: also tallied when every row is recomputed
+      atomicAdd(&cnt->stripe[blockIdx.x % kStripes][ST_REGATHER_LONG], (unsigned long long)deg);
     if (deg > a.big_deg) {
       if (l == 0) big_list[atomicAdd(n_big, 1)] = v;
       continue;
@@ -654,7 +655,7 @@ static hipError_t full_t(ink_ctx *c, const AggArgs &a_in, const int32_t *targets
     KernelTimer kt(c, a.layer, INK_K_AGG_FULL);
     hipLaunchKernelGGL((k_agg_full<IS_MIN, LPR>), dim3((unsigned)blocks), dim3(256), 0, c->stream, a, targets, n_targets,
                        (const int32_t *)nullptr, chg, c->big_list.as<int32_t>(), &c->d_cnt->v[C_NBIG],
-                       (compare ? FULL_COMPARE : 0) | (targets ? FULL_COUNT_GATHER : 0), c->d_cnt);
+                       (compare ? FULL_COMPARE : 0) | (targets ? FULL_COUNT_GATHER : 0) | FULL_COUNT_LONG, c->d_cnt);
     INK_TRY(hipGetLastError());
   }
   KernelTimer kt(c, a.layer, INK_K_AGG_LONG);

@@ -107,10 +107,9 @@ __global__ __launch_bounds__(256) void k_sum_full(AggArgs a, const int32_t *targ
   if (wid >= n_targets) return;
   int v = targets ? targets[wid] : (int)wid;
   int deg = a.in_deg[v];
-  if (targets && l == 0) {
-    atomicAdd(&cnt->stripe[blockIdx.x % kStripes][ST_REGATHER], (unsigned long long)deg);
-    if (deg > a.big_deg) atomicAdd(&cnt->stripe[blockIdx.x % kStripes][ST_REGATHER_LONG], (unsigned long long)deg);
-  }
+  if (targets && l == 0) atomicAdd(&cnt->stripe[blockIdx.x % kStripes][ST_REGATHER], (unsigned long long)deg);
+  if (deg > a.big_deg && l == 0)      // few rows: also tallied when every row is recomputed
+    atomicAdd(&cnt->stripe[blockIdx.x % kStripes][ST_REGATHER_LONG], (unsigned long long)deg);
   if (deg > a.big_deg) {
     if (l == 0) big_list[atomicAdd(n_big, 1)] = v;
     return;

@@ -1043,6 +1043,7 @@ static void layer_stats_from_counters(ink_ctx *c, int l) {
   ink_layer_stats &S = c->stats.layer[l - 1];
   if (S.dense) {
     S.n_targets = c->n; S.n_exposed = c->n; S.n_regather_nb = c->n_edges_now;
+    S.n_regather_nb_long = (int64_t)c->h_cnt->sum(ST_REGATHER_LONG);
     return;
   }
   c->big_hint[l] = c->h_cnt->v[C_NCHUNK];

@@ -3,7 +3,9 @@
     python -m paper_2309_11071_amd.profile_summary --kernel 'k_agg_events<false, 32>' \
         [--stats DIR_OR_CSV] [--pmc DIR_OR_CSV ...] [--top-frac 0.5]
 
---stats : output of `rocprofv3 --kernel-trace --stats` (the *_kernel_stats.csv file or its folder)
+--stats : output of `rocprofv3 --kernel-trace --stats` (the *_kernel_stats.csv file or its folder);
+          if the per-dispatch *_kernel_trace.csv lies there too, the durations of the LARGE launches
+          (see below) are listed as well
 --pmc   : output of `rocprofv3 --pmc ...` runs (*_counter_collection.csv or folders), any number
 
 Prints markdown: the duration table of the kernels that match --kernel, then per counter the
@@ -66,6 +68,16 @@ def main():
                     r["Name"].split("(")[0][:90], r["Calls"], float(r["TotalDurationNs"]) / 1e6,
                     float(r["AverageNs"]) / 1e3, float(r["MinNs"]) / 1e3, float(r["MaxNs"]) / 1e3))
         out.append("")
+        durs = []
+        for f in find(args.stats, "*kernel_trace.csv"):
+            for r in csv.DictReader(open(f)):
+                if args.kernel in r["Kernel_Name"]:
+                    durs.append((int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e6)
+        if durs:
+            big = sorted(d for d in durs if d >= args.top_frac * max(durs))
+            out.append("large launches (at least %.2f of the longest): %d of %d; average %.3f ms, median %.3f ms, min %.3f ms, max %.3f ms"
+                       % (args.top_frac, len(big), len(durs), sum(big) / len(big), big[len(big) // 2], big[0], big[-1]))
+            out.append("")
     for path in args.pmc:
         rows = load_pmc(path)
         per = collections.defaultdict(list)              # counter -> values of the matching kernel
@@ -96,7 +108,7 @@ def main():
                     out.append("calibration, elementwise copy (1 GiB read, 1 GiB written): %s = %.0f KiB -> factor %.3f"
                                % (cn, v, known / (v * KIB) if v else float("nan")))
             else:
-                for w, v in zip(CAL_WIDTHS, vals[-len(CAL_WIDTHS):]):
+                for w, v in zip(CAL_WIDTHS, vals[:len(CAL_WIDTHS)]):      # the calibration gathers come first in a run
                     known = float(CAL_GATHER_ROWS * w * 4)
                     out.append("calibration, gather of 2^21 rows of %d B (%s side %.0f MiB known): %s = %.0f KiB -> factor %.3f"
                                % (w * 4, "read" if cn == "FETCH_SIZE" else "write", known / (1 << 20), cn, v,
