@@ -5,7 +5,10 @@
 
 --stats : output of `rocprofv3 --kernel-trace --stats` (the *_kernel_stats.csv file or its folder);
           if the per-dispatch *_kernel_trace.csv lies there too, the durations of the LARGE launches
-          (see below) are listed as well
+          (see below) are listed as well, and with --window W K those of K large launches after
+          the first W alone (bench.py runs its warm-up steps, then its timed steps, then other
+          legs: W = --warmup and K = --steps select the launches whose HIP-event average bench.py
+          prints as avg_launch_ms)
 --pmc   : output of `rocprofv3 --pmc ...` runs (*_counter_collection.csv or folders), any number
 
 Prints markdown: the duration table of the kernels that match --kernel, then per counter the
@@ -57,6 +60,8 @@ def main():
     ap.add_argument("--stats", default=None)
     ap.add_argument("--pmc", nargs="*", default=[])
     ap.add_argument("--top-frac", type=float, default=0.2)
+    ap.add_argument("--window", type=int, nargs=2, default=None, metavar=("SKIP", "COUNT"),
+                    help="also average COUNT large launches of the kernel trace after the first SKIP")
     args = ap.parse_args()
     out = []
     if args.stats:
@@ -72,11 +77,19 @@ def main():
         for f in find(args.stats, "*kernel_trace.csv"):
             for r in csv.DictReader(open(f)):
                 if args.kernel in r["Kernel_Name"]:
-                    durs.append((int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e6)
+                    durs.append((int(r["Start_Timestamp"]), (int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e6))
         if durs:
-            big = sorted(d for d in durs if d >= args.top_frac * max(durs))
+            durs.sort()
+            longest = max(d for _, d in durs)
+            in_order = [d for _, d in durs if d >= args.top_frac * longest]
+            big = sorted(in_order)
             out.append("large launches (at least %.2f of the longest): %d of %d; average %.3f ms, median %.3f ms, min %.3f ms, max %.3f ms"
                        % (args.top_frac, len(big), len(durs), sum(big) / len(big), big[len(big) // 2], big[0], big[-1]))
+            if args.window:
+                part = in_order[args.window[0]:args.window[0] + args.window[1]]
+                if part:
+                    out.append("large launches %d .. %d in launch order (the timed steps): average %.3f ms, median %.3f ms"
+                               % (args.window[0] + 1, args.window[0] + len(part), sum(part) / len(part), sorted(part)[len(part) // 2]))
             out.append("")
     for path in args.pmc:
         rows = load_pmc(path)

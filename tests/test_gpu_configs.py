@@ -32,6 +32,8 @@ def test_config3_full_size_exact():
     assert st[1]["n_exposed"] > 0 and st[0]["n_events"] == cfg.batch
     h.check_state(exact=True)
     h.check_graph()
+    reps = h.check_against_f64(1e-5)           # accuracy after the updates, end to end, against fp64
+    assert all(r["rows_beyond_strict"] <= r["rows"] // 1000 for r in reps), reps
     h.ink.close()
 
 
@@ -72,6 +74,9 @@ def test_configs_4_and_5_at_one_sixteenth(cfg_id, exact):
         h.step(op, bs, bd, exact=exact)
     h.check_state(exact=exact)
     h.check_graph()
+    if exact:
+        reps = h.check_against_f64(1e-5)
+        assert all(r["rows_beyond_strict"] <= r["rows"] // 1000 for r in reps), reps
     h.ink.close()
 
 

@@ -64,8 +64,9 @@ def check_accumulated(got, ref, mag, deg, k_lin, depth, tol=1e-5, what=""):
     metric <= tol.  A row beyond it passes only if every element lies within the rounding bound of
     its own summands, depth * (deg + K + 2) * 2^-24 * magnitude (depth layers of a (deg + K)-term
     fp32 evaluation; magnitude from magnitude_inference), i.e. if the row's true value cancels so
-    far below its summands that no fp32 evaluation could meet the relative bar.  Returns the
-    strict maximum and how many rows needed the second bound."""
+    far below its summands that no fp32 evaluation could meet the relative bar.  mag and deg may be
+    callables, evaluated only if some row is beyond the strict bar.  Returns the strict maximum and
+    how many rows needed the second bound."""
     got = np.asarray(got, np.float64)
     ref = np.asarray(ref, np.float64)
     if got.size == 0:
@@ -75,6 +76,8 @@ def check_accumulated(got, ref, mag, deg, k_lin, depth, tol=1e-5, what=""):
     strict = err.max(axis=1) / rmax
     beyond = np.nonzero(strict > tol)[0]
     if beyond.size:
+        mag = mag() if callable(mag) else mag
+        deg = deg() if callable(deg) else deg
         bound = (depth * (np.asarray(deg, np.float64)[beyond] + k_lin + 2) * U32)[:, None] * np.asarray(mag, np.float64)[beyond]
         ok = err[beyond] <= np.maximum(bound, tol * rmax[beyond][:, None])
         worst = int(beyond[np.argmin(ok.all(axis=1))])
@@ -114,16 +117,18 @@ class Harness:
         self.reports = []          # one entry per accumulated table checked (strict maximum, rows beyond it)
         self.last_set_mismatch = 0
         self._mag_keys = None
+        self.k_lin = chain_lengths(self.model)
 
     def _magnitudes(self):
         """Summand magnitudes and in-degrees of the current snapshot (for check_accumulated)."""
         if self._mag_keys is self.keys and self._mag_X is self.X and self._mag_user is self.user_terms:
-            return
+            return self
         rp, col = oracle.csr_from_keys(self.n, self.keys)
         self.mag = magnitude_inference(rp, col, self.X, self.model, self.user_terms)
         self.deg = np.diff(rp)
         self.k_lin = chain_lengths(self.model)
         self._mag_keys, self._mag_X, self._mag_user = self.keys, self.X, self.user_terms
+        return self
 
     def check_state(self, exact=True, tol=1e-5):
         k = len(self.model["layers"])
@@ -133,8 +138,8 @@ class Harness:
             if exact:
                 assert np.array_equal(h.view(np.uint32), self.ref["h"][l].view(np.uint32)), "h_%d differs" % l
             else:
-                self._magnitudes()
-                rep = check_accumulated(h, self.ref["h"][l], self.mag[l], self.deg, self.k_lin[l - 1], l, tol, "h_%d" % l)
+                rep = check_accumulated(h, self.ref["h"][l], lambda: self._magnitudes().mag[l], lambda: self._magnitudes().deg,
+                                        self.k_lin[l - 1], l, tol, "h_%d" % l)
                 self.reports.append(rep)
                 print("parity %s: strict max %.3g, %d of %d rows beyond the strict bar (within their rounding bound)"
                       % (rep["what"], rep["strict_max"], rep["rows_beyond_strict"], rep["rows"]))
@@ -144,6 +149,20 @@ class Harness:
                 if exact:
                     assert np.array_equal(a.view(np.uint32), self.ref["alpha"][l].view(np.uint32)), "alpha_%d" % l
                     assert np.array_equal(g, self.ref["arg"][l]), "argmax_%d differs" % l
+
+    def check_against_f64(self, tol=1e-5):
+        """End-to-end accuracy of the cached embeddings (whatever sequence of updates produced them)
+        against an fp64 inference of the current snapshot, under the stated per-row metric; for
+        the models whose primary bar is bit-exactness against the fp32-chain oracle."""
+        ref64 = oracle.full_infer(*oracle.csr_from_keys(self.n, self.keys), self.X, self.model, "f64", user_terms=self.user_terms)
+        out = []
+        for l in range(1, len(self.model["layers"]) + 1):
+            rep = check_accumulated(self.ink.get_layer(l, 0), ref64["h"][l], lambda: self._magnitudes().mag[l],
+                                    lambda: self._magnitudes().deg, self.k_lin[l - 1], l, tol, "h_%d vs fp64" % l)
+            print("parity %s: strict max %.3g, %d of %d rows beyond the strict bar (within their rounding bound)"
+                  % (rep["what"], rep["strict_max"], rep["rows_beyond_strict"], rep["rows"]))
+            out.append(rep)
+        return out
 
     def check_bound(self, exact=False, max_nodes=4000):
         """The cached bound on the runner-up value (get_layer which=3) must dominate the best value
@@ -206,19 +225,27 @@ class Harness:
             assert np.all(np.diff(got) > 0)
             hk_pre, hk_post = self.ref["h"][-1], post["h"][-1]
             k = len(self.model["layers"])
-            rp2, col2 = oracle.csr_from_keys(n_post, keys_post)
-            mag = magnitude_inference(rp2, col2, X_post, self.model, user_post)[k]
-            deg = np.diff(rp2)
+            memo = {}
+
+            def magnitudes():                      # of the new snapshot; computed only if a row needs its rounding bound
+                if not memo:
+                    rp2, col2 = oracle.csr_from_keys(n_post, keys_post)
+                    memo["mag"] = magnitude_inference(rp2, col2, X_post, self.model, user_post)[k]
+                    memo["deg"] = np.diff(rp2)
+                return memo
             k_lin = chain_lengths(self.model)[k - 1]
             sym = np.setxor1d(got, want)
             if sym.size:
                 delta = row_err(hk_pre[sym], hk_post[sym])
-                bound = (k * (deg[sym] + k_lin + 2) * U32)[:, None] * mag[sym].astype(np.float64)
-                small = np.abs(hk_post[sym].astype(np.float64) - hk_pre[sym]) <= bound
-                assert np.all((delta <= tol) | small.all(axis=1)), "changed sets differ in a row that really changed"
+                if np.any(delta > tol):
+                    m = magnitudes()
+                    bound = (k * (m["deg"][sym] + k_lin + 2) * U32)[:, None] * m["mag"][sym].astype(np.float64)
+                    small = np.abs(hk_post[sym].astype(np.float64) - hk_pre[sym]) <= bound
+                    assert np.all((delta <= tol) | small.all(axis=1)), "changed sets differ in a row that really changed"
             self.last_set_mismatch = int(sym.size)
             assert sym.size <= max(8, (got.size + want.size) // 100), "changed sets differ in %d rows" % sym.size
-            rep = check_accumulated(res["embeddings"], hk_post[got], mag[got], deg[got], k_lin, k, tol, "returned rows")
+            rep = check_accumulated(res["embeddings"], hk_post[got], lambda: magnitudes()["mag"][got],
+                                    lambda: magnitudes()["deg"][got], k_lin, k, tol, "returned rows")
             rep["set_mismatch"] = int(sym.size)
             self.reports.append(rep)
             print("parity returned rows: strict max %.3g, %d of %d rows beyond the strict bar; changed sets differ in %d rows"
