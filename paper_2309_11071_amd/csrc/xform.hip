@@ -149,6 +149,53 @@ __device__ __forceinline__ void mfma_chunk(const float *Xs, const float *Ws, int
   }
 }
 
+// Epilogue of a workgroup's tile: bias, user term, output scale, activation, then either a plain
+// store or compare-and-emit against the cached table row.  A lane holds rows
+// 8*(r/4) + 4*(l/32) + r%4 of its row tile, column l % 32 of each of its column tiles.
+template <int TPW, int CS, int NT, int BM>
+__device__ __forceinline__ void xform_epilogue(const XformArgs &x, const f16v *acc, const int64_t *srow, const int64_t *sout,
+                                               int *schg, int rt, int ct0, int l, int t, int64_t r0) {
+#pragma unroll
+  for (int i = 0; i < TPW; i++) {
+    int ct = ct0 + CS * i;
+    if (ct >= NT) continue;
+    int col = ct * 32 + (l & 31);
+    if (col >= x.n_out) continue;
+    float bias = x.bias ? x.bias[col] : 0.f;
+    float oldv[16];
+    if (x.to_table) {      // all loads of the cached values first, then compare and store
+#pragma unroll
+      for (int r = 0; r < 16; r++) {
+        int rl = rt * 32 + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3);
+        oldv[r] = srow[rl] >= 0 ? x.out[sout[rl] * x.ld_out + col] : 0.f;
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < 16; r++) {
+      int rl = rt * 32 + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3);
+      int64_t row = srow[rl];
+      if (row < 0) continue;
+      float v = acc[i][r];
+      if (x.bias) v = __fadd_rn(v, bias);
+      if (x.user) v = __fadd_rn(v, x.user[sout[rl] * x.ld_user + col]);
+      if (x.out_scale) v = __fmul_rn(v, x.out_scale[sout[rl]]);
+      if (x.relu) v = v > 0.f ? v : 0.f;
+      int64_t j = r0 + rl;
+      if (x.to_table) {
+        float old = oldv[r];
+        if (x.old_rows) x.old_rows[j * x.ld_old + col] = old;
+        if (__float_as_uint(old) != __float_as_uint(v)) { x.out[sout[rl] * x.ld_out + col] = v; schg[rl] = 1; }
+      } else {
+        x.out[j * x.ld_out + col] = v;
+      }
+    }
+  }
+  if (x.to_table && x.row_changed) {
+    __syncthreads();
+    if (t < BM && srow[t] >= 0) x.row_changed[r0 + t] = (uint8_t)schg[t];
+  }
+}
+
 // BM = rows per workgroup (64 or 128), NT = number of 32-column tiles (Np / 32), NW = waves per
 // workgroup.  With RT = BM / 32 row tiles, wave w works on row tile w % RT and on the column tiles
 // w / RT, w / RT + NW / RT, ...
@@ -265,46 +312,7 @@ __global__ __launch_bounds__(NW * 64) void k_xform(XformArgs x) {
     else if (TPW > 1) mfma_chunk<(TPW > 1 ? TPW - 1 : 1), CS>(Xs, Ws, rt, ct0, l, acc);
     __syncthreads();
   }
-  // epilogue: lane holds rows 8*(r/4) + 4*(l/32) + r%4 of its row tile, column l % 32 of each tile
-#pragma unroll
-  for (int i = 0; i < TPW; i++) {
-    int ct = ct0 + CS * i;
-    if (ct >= NT) continue;
-    int col = ct * 32 + (l & 31);
-    if (col >= x.n_out) continue;
-    float bias = x.bias ? x.bias[col] : 0.f;
-    float oldv[16];
-    if (x.to_table) {      // all loads of the cached values first, then compare and store
-#pragma unroll
-      for (int r = 0; r < 16; r++) {
-        int rl = rt * 32 + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3);
-        oldv[r] = srow[rl] >= 0 ? x.out[sout[rl] * x.ld_out + col] : 0.f;
-      }
-    }
-#pragma unroll
-    for (int r = 0; r < 16; r++) {
-      int rl = rt * 32 + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3);
-      int64_t row = srow[rl];
-      if (row < 0) continue;
-      float v = acc[i][r];
-      if (x.bias) v = __fadd_rn(v, bias);
-      if (x.user) v = __fadd_rn(v, x.user[sout[rl] * x.ld_user + col]);
-      if (x.out_scale) v = __fmul_rn(v, x.out_scale[sout[rl]]);
-      if (x.relu) v = v > 0.f ? v : 0.f;
-      int64_t j = r0 + rl;
-      if (x.to_table) {
-        float old = oldv[r];
-        if (x.old_rows) x.old_rows[j * x.ld_old + col] = old;
-        if (__float_as_uint(old) != __float_as_uint(v)) { x.out[sout[rl] * x.ld_out + col] = v; schg[rl] = 1; }
-      } else {
-        x.out[j * x.ld_out + col] = v;
-      }
-    }
-  }
-  if (x.to_table && x.row_changed) {
-    __syncthreads();
-    if (t < BM && srow[t] >= 0) x.row_changed[r0 + t] = (uint8_t)schg[t];
-  }
+  xform_epilogue<TPW, CS, NT, BM>(x, acc, srow, sout, schg, rt, ct0, l, t, r0);
 }
 
 #ifndef INK_XF_WIDE_FROM

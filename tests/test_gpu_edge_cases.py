@@ -126,6 +126,9 @@ def test_first_and_last_edge_of_a_node():
     ("gin", "max", (300, 40, 6)),
     ("sage", "max", (12, 7)),             # a single layer
     ("sage", "max", (6,) * 9),            # the largest layer count the library takes
+    ("sage", "max", (176, 33, 5)),        # narrow outputs, inputs of 11 k-chunks
+    ("sage", "max", (48, 64, 40)),        # 3 and 4 k-chunks, one and two column tiles
+    ("sage", "min", (256, 8, 8)),         # 16 k-chunks
 ])
 def test_random_sequences(kind, agg, dims):
     cfg = synth.WorkloadConfig(6, "t", kind, agg, 3000, 20000, False, tuple(dims), 24, 300, True)

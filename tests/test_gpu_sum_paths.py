@@ -24,6 +24,10 @@ TOL = 1e-5
     ("gin", "sum", (12, 9)),               # a single layer
     ("gcn", "gcn_sym", (12, 9)),
     ("gin", "sum", (6,) * 9),              # the largest layer count the library takes
+    ("gcn", "gcn_sym", (20, 64, 7)),       # narrow outputs over whole rows of 2 and 5 k-chunks
+    ("gcn", "gcn_sym", (12, 160, 40)),
+    ("sage", "mean", (176, 33, 5)),        # mean over 11 k-chunks
+    ("sage", "sum", (80, 64, 8)),
 ])
 def test_random_sequences(kind, agg, dims):
     cfg = synth.WorkloadConfig(6, "t", kind, agg, 3000, 20000, False, tuple(dims), 24, 200, False)
