@@ -39,7 +39,7 @@ KERNEL_NAMES = {"agg_events": "k_agg_events (incremental aggregation over groupe
                 "agg_full": "k_agg_full / k_sum_full (recompute of every row)"}
 
 
-def kernel_bytes(kern, L, d, select, sources):
+def kernel_bytes(kern, L, d, select, sources, inline_exposed=False):
     """Bytes one launch of an aggregation kernel must move, from the layer's counters.
 
     The accounting per layer is: every event record read once (4 B, plus 8 B per target for its id
@@ -49,15 +49,17 @@ def kernel_bytes(kern, L, d, select, sources):
     a recomputed row reads, per neighbour, one id and one message row (4 + 4 d B).
     Returns (bytes by that accounting, bytes as designed).  As designed adds what this
     implementation moves on top: one source row per non-delete event (mostly cache hits) and the
-    two runner-up tables of max / min (another 2 * 2 * 4 d per target)."""
+    two runner-up tables of max / min (another 2 * 2 * 4 d per target).  inline_exposed: the event
+    kernel itself recomputed the exposed rows of moderate length (no follow-up launch ran), so their
+    neighbour rows count for it."""
     t, e = L["n_targets"], L["n_events"]
     row = 4 * d
     rw = 2 * row * (2 if select else 1)
-    if kern == "agg_events":
-        alg = e * 4 + t * 8 + sources * row + t * rw
-        return alg, alg + max(e - sources, 0) * row + (t * rw if select else 0)
     nb_long = L["n_regather_nb_long"]
     nb = L["n_regather_nb"]
+    if kern == "agg_events":
+        alg = e * 4 + t * 8 + sources * row + t * rw + ((nb - nb_long) * (4 + row) if inline_exposed else 0)
+        return alg, alg + max(e - sources, 0) * row + (t * rw if select else 0)
     if kern == "agg_long":
         return nb_long * (4 + row), nb_long * (4 + row)
     rows = L["n_exposed"] if kern == "agg_exposed" else L["n_targets"]
@@ -223,7 +225,8 @@ def main():
         launches = kern_n[(li, kern)]
         L = {k_: v / args.steps for k_, v in layer_tot[li].items()}         # per-step averages of that layer
         d = ink.agg_widths[li]
-        alg, designed = kernel_bytes(kern, L, d, select, L["n_sources"])
+        inline_exposed = kern == "agg_events" and L["n_exposed"] > 0 and kern_n.get((li, "agg_exposed"), 0) == 0
+        alg, designed = kernel_bytes(kern, L, d, select, L["n_sources"], inline_exposed)
         avg_ms = kern_ms[(li, kern)] / launches
         ach = alg / 1e9 / (avg_ms / 1e3)
         traffic, traffic_src = read_traffic(cfg.name, kern)
@@ -240,7 +243,8 @@ def main():
             "measured_random_row_gather_GBs": measured_gather_rate(torch, ink.agg_widths[li]),
             "share_of_step": kern_ms[(li, kern)] / args.steps / (total / args.steps * 1e3),
             "units_per_launch": {"targets": L["n_targets"], "events": L["n_events"], "distinct_sources": L["n_sources"],
-                                 "row_floats": d},
+                                 "row_floats": d, "exposed_rows_recomputed_inside": bool(inline_exposed),
+                                 "neighbour_rows_of_those": (L["n_regather_nb"] - L["n_regather_nb_long"]) if inline_exposed else 0},
             "above_hbm_peak": bool(ach > HBM_PEAK_GBS),     # then the launch re-reads rows that L2 / MALL serve: see traffic
             "note": "achieved = bytes the method must move for this launch (each distinct source row once, value and "
                     "holder row of each target read and written) / HIP-event time of this kernel; as_designed adds the "

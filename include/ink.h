@@ -274,10 +274,11 @@ typedef struct {
  *   rows   : HOST array [n][row_stride]; the first out_dim_layer floats of row i belong to event i
  * (both always host memory: user events are control input, not a data stream).  The first event
  * on a layer allocates that layer's term table (n_nodes capacity x out_dim floats).
- * The result has the layout of ink_apply_updates' (n_applied_* are 0).  GCN_SYM is not supported.
+ * The result has the layout of ink_apply_updates' (n_applied_* are 0).  Every model kind takes
+ * them; for GCN the term joins the bias: h_l = act(normalised sum of layer l + b_l + u_l).
  * Errors: INK_E_STATE before ink_full_infer; INK_E_RANGE for a layer outside 1 .. n_layers or a
  * target outside [0, n_nodes); INK_E_ARG for an unknown op, row_stride below the width of a named
- * layer, n < 0, NULL arrays or a GCN model.  On these errors nothing is changed. */
+ * layer, n < 0 or NULL arrays.  On these errors nothing is changed. */
 ink_status ink_apply_user_events(ink_ctx *ctx, const ink_user_event *events, const float *rows, int32_t row_stride,
                                  int64_t n, ink_update_result *out);
 

@@ -73,10 +73,31 @@ __device__ __forceinline__ void expand_event(int e, const int32_t *F, int nF, co
   *val = (EV_CHG << kEvKindShift) | (uint32_t)(payload_index ? lo : u);
 }
 
-__global__ void k_expand_events(const int32_t *F, int nF, const int32_t *pref, int n_ev, const int64_t *off,
-                                const int32_t *ids, uint32_t *key, uint32_t *val, int payload_index) {
-  int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (e < n_ev) expand_event((int)e, F, nF, pref, off, ids, payload_index, &key[e], &val[e]);
+// A wave creates kExpandPerWave consecutive events.  It finds the sources of its first and last
+// event with two wave-wide searches (64 probes per round); a lane then looks for the source of each
+// of its events only between those two, usually one or two candidates, instead of searching the
+// whole prefix array once per event.
+constexpr int kExpandPerWave = 4 * kWave;
+__global__ __launch_bounds__(256) void k_expand_events(const int32_t *F, int nF, const int32_t *pref, int n_ev,
+                                                       const int64_t *off, const int32_t *ids, uint32_t *key,
+                                                       uint32_t *val, int payload_index) {
+  const int l = lane_id();
+  const int64_t wv = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kWave;
+  const int64_t e_base = wv * kExpandPerWave;
+  if (e_base >= n_ev) return;
+  const int e_end = (int)(e_base + kExpandPerWave < n_ev ? e_base + kExpandPerWave : n_ev);
+  const int lo = wave_last_le(pref, nF, (int)e_base);                      // pref[0] = 0 <= every event
+  const int hi = lo + wave_last_le(pref + lo, nF - lo, e_end - 1);         // pref[lo] <= e_base <= e_end - 1
+  for (int e = (int)e_base + l; e < e_end; e += kWave) {
+    int a = lo, b = hi;
+    while (a < b) {
+      int mid = (a + b + 1) >> 1;
+      if (pref[mid] <= e) a = mid; else b = mid - 1;
+    }
+    const int u = F[a];
+    key[e] = (uint32_t)ids[off[u] + (e - pref[a])];
+    val[e] = (EV_CHG << kEvKindShift) | (uint32_t)(payload_index ? a : u);
+  }
 }
 
 // The counters reach the host through pinned host memory: one wave writes the slots and the
@@ -385,7 +406,8 @@ __global__ void k_gcn_rescale(const int32_t *nodes, int64_t n, const int32_t *de
 
 // last GCN layer: h = act(c_v (S + own scaled message) + b) for the listed rows, compare-and-emit
 __global__ void k_gcn_final(const int32_t *rows, int64_t n, const float *S, const float *Msc, const float *cnorm,
-                            const float *bias, int relu, float *H, int ld, int d, uint8_t *flag) {
+                            const float *bias, const float *user, int ld_user, int relu, float *H, int ld, int d,
+                            uint8_t *flag) {
   int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   int64_t i = t / ld;
   int k = (int)(t % ld);
@@ -393,6 +415,7 @@ __global__ void k_gcn_final(const int32_t *rows, int64_t n, const float *S, cons
   int64_t v = rows ? rows[i] : i;
   float x = __fmul_rn(cnorm[v], __fadd_rn(S[v * ld + k], Msc[v * ld + k]));
   if (bias) x = __fadd_rn(x, bias[k]);
+  if (user) x = __fadd_rn(x, user[v * ld_user + k]);
   if (relu) x = x > 0.f ? x : 0.f;
   float o = H[v * ld + k];
   if (__float_as_uint(o) != __float_as_uint(x)) {
@@ -820,6 +843,7 @@ static hipError_t gcn_next_messages(ink_ctx *c, int l, const int32_t *rows, int6
   x.mode = 3; x.rows = rows; x.n_rows = n_rows;
   x.A = c->A[l].f(); x.lda = c->A[l].ld; x.Hp = c->Msc[l].f(); x.ldh = c->Msc[l].ld; x.d_in = L.out_dim;
   x.cnorm = c->cnorm; x.in_bias = L.b1; x.in_relu = L.act == INK_ACT_RELU;
+  x.in_user = c->USER[l].f(); x.ld_in_user = c->USER[l].ld;
   x.h_store = c->H[l].f(); x.ld_hs = c->H[l].ld;
   x.W = Ln.W1; x.Kp = Ln.K1p; x.Np = Ln.N1p; x.bias = nullptr; x.n_out = Ln.out_dim; x.relu = 0;
   x.out_scale = c->cnorm;
@@ -834,7 +858,8 @@ static hipError_t gcn_final(ink_ctx *c, const int32_t *rows, int64_t n_rows, uin
   if (n_rows <= 0) return hipSuccess;
   hipLaunchKernelGGL(k_gcn_final, grid1(n_rows * c->H[k].ld), dim3(256), 0, c->stream, rows, n_rows,
                      (const float *)c->A[k].f(), (const float *)c->Msc[k].f(), (const float *)c->cnorm,
-                     (const float *)L.b1, (int)(L.act == INK_ACT_RELU), c->H[k].f(), c->H[k].ld, c->H[k].d, flags);
+                     (const float *)L.b1, (const float *)c->USER[k].f(), c->USER[k].ld, (int)(L.act == INK_ACT_RELU),
+                     c->H[k].f(), c->H[k].ld, c->H[k].d, flags);
   return hipGetLastError();
 }
 
@@ -990,7 +1015,7 @@ static ink_status layer_aggregate(ink_ctx *c, int l, const int32_t *F, int64_t n
                            (const int32_t *)c->del_dst, (const int32_t *)c->ins_src, (const int32_t *)c->ins_dst,
                            (int)n_del, (int)n_ins, key, val);
       if (n_chg > 0)
-        hipLaunchKernelGGL(k_expand_events, grid1(n_chg), dim3(256), 0, s, F, (int)nF,
+        hipLaunchKernelGGL(k_expand_events, grid1(n_chg, 256 / kWave * kExpandPerWave), dim3(256), 0, s, F, (int)nF,
                            (const int32_t *)c->f_pref.as<int32_t>(), (int)n_chg, (const int64_t *)c->gout.off,
                            (const int32_t *)c->gout.ids, key + n_seed, val + n_seed, c->is_select ? 0 : 1);
       API_TRY(hipGetLastError());
@@ -1517,7 +1542,6 @@ static ink_status apply_user_events_impl(ink_ctx *c, const ink_user_event *event
                                          int64_t n, ink_update_result *out) {
   if (!out || n < 0 || (n > 0 && (!events || !rows))) return fail(c, INK_E_ARG, "ink_apply_user_events: NULL argument or negative n");
   if (!c->inferred) return fail(c, INK_E_STATE, "ink_apply_user_events: call ink_full_infer first");
-  if (c->kind == INK_MODEL_GCN) return fail(c, INK_E_ARG, "ink_apply_user_events: not supported for INK_AGG_GCN_SYM");
   if (n >= (1ll << 30)) return fail(c, INK_E_ARG, "ink_apply_user_events: too many events");
   UserState u;
   memset(&u, 0, sizeof(u));

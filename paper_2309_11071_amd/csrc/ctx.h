@@ -257,6 +257,7 @@ struct XformArgs {
   const int32_t *mean_deg;  // modes 0/1 with mean aggregation: A is divided by max(deg, 1)
   const float *cnorm;       // mode 3: per-node c_v
   const float *in_bias; int in_relu;   // mode 3
+  const float *in_user; int ld_in_user;   // mode 3: per-node term added after in_bias, before the activation; null: none
   float *h_store; int ld_hs;           // mode 3: where x (= h_l) is written, one row per node
   const float *out_scale;   // per-node factor applied to the output row (after bias), null: none
   const float *user; int ld_user;      // per-node term added after the bias, before the activation (to_table only), null: none

@@ -33,6 +33,7 @@ __device__ __forceinline__ float fetch_x(const XformArgs &x, int64_t row, int k)
     if (k >= x.d_in) return 0.f;
     float v = __fmul_rn(x.cnorm[row], __fadd_rn(x.A[row * x.lda + k], x.Hp[row * x.ldh + k]));
     if (x.in_bias) v = __fadd_rn(v, x.in_bias[k]);
+    if (x.in_user) v = __fadd_rn(v, x.in_user[row * x.ld_in_user + k]);
     if (x.in_relu) v = v > 0.f ? v : 0.f;
     if (x.h_store) x.h_store[row * x.ld_hs + k] = v;
     return v;
@@ -81,7 +82,7 @@ __device__ __forceinline__ void fetch_x4(const XformArgs &x, int64_t row, int k,
       return;
     }
   } else if (MODE == 3) {
-    if (k + 3 < x.lda && k + 3 < x.ldh) {
+    if (k + 3 < x.lda && k + 3 < x.ldh && !x.in_user) {      // rows with a user term take the element-wise path
       float a[4], h[4];
       ld4v(x.A + row * x.lda + k, a);
       ld4v(x.Hp + row * x.ldh + k, h);
@@ -255,7 +256,7 @@ __global__ __launch_bounds__(NW * 64) void k_xform(XformArgs x) {
   // GCN rows whose width is a multiple of the chunk: the loads of the next chunk are issued a
   // whole iteration before their values are scaled, biased, stored as h and staged, so the
   // gather latency overlaps the barriers, the weight staging and the MFMAs of the chunk between
-  const bool raw3 = MODE == 3 && x.d_in == x.Kp && x.lda >= x.Kp && x.ldh >= x.Kp && (!x.h_store || x.ld_hs >= x.Kp);
+  const bool raw3 = MODE == 3 && x.d_in == x.Kp && x.lda >= x.Kp && x.ldh >= x.Kp && (!x.h_store || x.ld_hs >= x.Kp) && !x.in_user;
   float ra[KPT], rh[KPT], rb[KPT];
   const float cv3 = (raw3 && xrow >= 0) ? x.cnorm[xrow] : 0.f;
   auto issue3 = [&](int k0) {

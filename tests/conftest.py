@@ -27,3 +27,19 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture
+def progress(request):
+    """Long tests say where they are on the real stdout (output capture is suspended for the line),
+    so that whoever watches the run sees it advance during minutes of CPU-side oracle work."""
+    capman = request.config.pluginmanager.getplugin("capturemanager")
+
+    def say(msg):
+        line = "\n[%s] %s" % (request.node.name, msg)
+        if capman is None:
+            print(line, flush=True)
+            return
+        with capman.global_and_fixture_disabled():
+            print(line, flush=True)
+    return say

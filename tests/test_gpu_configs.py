@@ -13,9 +13,10 @@ from util import Harness, check_accumulated, chain_lengths, magnitude_inference
 pytestmark = pytest.mark.gpu
 
 
-def test_config3_full_size_exact():
+def test_config3_full_size_exact(progress):
     cfg = synth.get_config(3)
     h = Harness(cfg, precision="f32")
+    progress("graph, context and oracle inference ready")
     h.check_state(exact=True)
     from paper_2309_11071_amd.binding import make_updates
     for b in range(2):                      # no oracle in between: only the key set is tracked
@@ -25,8 +26,10 @@ def test_config3_full_size_exact():
         assert (res["n_applied_ins"], res["n_applied_del"], res["n_noop"]) == (n_ins, n_del, n_noop)
     h.ref = oracle.full_infer(*oracle.csr_from_keys(h.n, h.keys), h.X, h.model, "f32")
     h.check_state(exact=True)
+    progress("state after two batches compared")
     op, bs, bd = h.sampler.next_batch()      # third batch: changed set and embeddings, exactly
     res, want = h.step(op, bs, bd, exact=True)
+    progress("third batch compared")
     assert want.size > 1000
     st = h.ink.stats()["layers"]
     assert st[1]["n_exposed"] > 0 and st[0]["n_events"] == cfg.batch
@@ -37,12 +40,13 @@ def test_config3_full_size_exact():
     h.ink.close()
 
 
-def test_config2_full_size_within_tolerance():
+def test_config2_full_size_within_tolerance(progress):
     """Config 2 at its full size against the fp64 oracle: the whole cache after the full inference,
     again after two batches, then the third batch's changed set and rows and the cache once more.
     Every accumulated table is held to the stated per-row metric (util.check_accumulated)."""
     cfg = synth.get_config(2)
     h = Harness(cfg, precision="f64")
+    progress("graph, context and oracle inference ready")
     h.check_state(exact=False)
     from paper_2309_11071_amd.binding import make_updates
     for b in range(2):
@@ -53,8 +57,10 @@ def test_config2_full_size_within_tolerance():
         assert res["n_changed"] > 1000
     h.ref = oracle.full_infer(*oracle.csr_from_keys(h.n, h.keys), h.X, h.model, "f64")
     h.check_state(exact=False)
+    progress("state after two batches compared")
     op, bs, bd = h.sampler.next_batch()
     res, want = h.step(op, bs, bd, exact=False)            # changed set and returned rows of the third batch
+    progress("third batch compared")
     assert want.size > 1000
     h.check_state(exact=False)
     ids = res["changed_ids"]
@@ -65,13 +71,14 @@ def test_config2_full_size_within_tolerance():
 
 
 @pytest.mark.parametrize("cfg_id,exact", [(4, False), (5, True)])
-def test_configs_4_and_5_at_one_sixteenth(cfg_id, exact):
+def test_configs_4_and_5_at_one_sixteenth(cfg_id, exact, progress):
     cfg = synth.get_config(cfg_id, 16)
     h = Harness(cfg, precision="f32" if exact else "f64")
     h.check_state(exact=exact)
     for b in range(3):
         op, bs, bd = h.sampler.next_batch()
         h.step(op, bs, bd, exact=exact)
+        progress("batch %d compared" % b)
     h.check_state(exact=exact)
     h.check_graph()
     if exact:
@@ -126,7 +133,7 @@ def _assert_table_equal(ink, layer, which, ref, what, chunk=2_000_000):
             raise AssertionError("%s differs in %d rows of [%d, %d), first %d" % (what, bad.size, r0, r0 + got.shape[0], r0 + bad[0]))
 
 
-def test_config5_full_size_whole_state_exact():
+def test_config5_full_size_whole_state_exact(progress):
     """Config 5 as bench.py runs it (20 M nodes, 400 M edges, batches of 10 000): after the first
     batch and again after the second, EVERY row of every cached table (aggregate, holder ids, layer
     output; three layers) is compared bit for bit with an independent oracle inference of that
@@ -140,11 +147,13 @@ def test_config5_full_size_whole_state_exact():
     rp, col = synth.in_csr_from_edges(n, src, dst, assume_sorted=True)
     X = synth.make_features(cfg)
     model = synth.make_model(cfg)
+    progress("graph generated")
     ink = Ink(rp, col, X, model)
     ink.full_infer()
     sampler = synth.BatchSampler(cfg, src, dst)
     keys = synth.edge_keys(src, dst)
     del src, dst, rp, col
+    progress("context created, full inference done")
     k = len(model["layers"])
     final = []
     for b in range(2):
@@ -163,6 +172,7 @@ def test_config5_full_size_whole_state_exact():
             del a_ref
             _assert_table_equal(ink, l, 0, h_ref, "batch %d: h_%d" % (b, l))
             h_prev = h_ref
+            progress("batch %d, layer %d compared" % (b, l))
         final.append(h_prev)
         del rp2, col2
     want = np.nonzero(oracle.rows_differ(final[0], final[1]))[0].astype(np.int32)
@@ -172,7 +182,7 @@ def test_config5_full_size_whole_state_exact():
     ink.close()
 
 
-def test_config4_full_size_sampled_rows():
+def test_config4_full_size_sampled_rows(progress):
     """Config 4 at its full size (20 M nodes / 400 M edges, batches of 10 000).  An independent fp64
     oracle inference of this snapshot would take a quarter of an hour, so this is a sampled,
     layer-wise check (parity at this size is otherwise unpinned): for random nodes, the highest
@@ -188,10 +198,12 @@ def test_config4_full_size_sampled_rows():
     rp, col = synth.in_csr_from_edges(n, src, dst, assume_sorted=True)
     X = synth.make_features(cfg)
     model = synth.make_model(cfg)
+    progress("graph generated")
     ink = Ink(rp, col, X, model)
     ink.full_infer()
     sampler = synth.BatchSampler(cfg, src, dst)
     del src, dst
+    progress("context created, full inference done")
     batches = []
     for b in range(2):
         op, bs, bd = sampler.next_batch()
@@ -225,6 +237,6 @@ def test_config4_full_size_sampled_rows():
         z_mag = oracle.linear(x_mag, np.abs(L["W_neigh"]), absw(L.get("bias")), False, "f64")
         h_mag = oracle.linear(z_mag, np.abs(L["W_mlp2"]), absw(L.get("bias_mlp2")), False, "f64")
         rep2 = check_accumulated(h_gpu, h_ref, h_mag, deg_s, k_lin[l - 1], 1, 1e-5, "h_%d" % l)
-        print("config 4 sampled rows, layer %d: %s ; %s" % (l, rep, rep2))
+        progress("config 4 sampled rows, layer %d: %s ; %s" % (l, rep, rep2))
         del M
     ink.close()

@@ -23,7 +23,7 @@ def _harness(kind, agg, exact, n=3000, dims=(12, 16, 8), seed=3):
 
 
 @pytest.mark.parametrize("kind,agg,exact", [("sage", "max", True), ("sage", "min", True), ("gin", "sum", False),
-                                            ("sage", "mean", False), ("gin", "max", True)])
+                                            ("sage", "mean", False), ("gin", "max", True), ("gcn", "gcn_sym", False)])
 def test_user_events_match_the_oracle(kind, agg, exact):
     h, rng = _harness(kind, agg, exact)
     n, stride = h.n, 16
@@ -82,8 +82,3 @@ def test_user_event_errors_change_nothing():
     res = h.ink.apply_user_events([], np.zeros((0, 16), np.float32))
     assert res["n_changed"] == 0
     h.ink.close()
-    g = Harness(synth.get_config(2, 64), precision="f64")
-    with pytest.raises(InkError) as e:
-        g.ink.apply_user_events([(1, 0, SET)], np.zeros((1, 256), np.float32))
-    assert e.value.status == 1
-    g.ink.close()

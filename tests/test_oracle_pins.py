@@ -413,7 +413,7 @@ def _user_case(kind, agg, seed=0):
     return n, dims, rp, col, X, model, rng
 
 
-@pytest.mark.parametrize("kind,agg", [("sage", "max"), ("gin", "sum")])
+@pytest.mark.parametrize("kind,agg", [("sage", "max"), ("gin", "sum"), ("gcn", "gcn_sym")])
 def test_user_term_is_added_before_the_activation(kind, agg):
     n, dims, rp, col, X, model, rng = _user_case(kind, agg)
     base = oracle.full_infer(rp, col, X, model, "f64")
