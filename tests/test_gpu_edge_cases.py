@@ -319,3 +319,43 @@ def test_condition_counters_of_rows_wider_than_one_block():
         assert L["n_alpha_changed"] <= L["n_targets"]
     h.check_state()
     h.ink.close()
+
+
+@pytest.mark.parametrize("kind,agg,exact", [("sage", "max", True), ("gin", "min", True), ("gin", "sum", False),
+                                            ("gcn", "gcn_sym", False)])
+def test_insert_then_delete_restores_the_cache(kind, agg, exact):
+    """Inserting a set of edges and deleting the same edges again leaves the edge set as it was: the
+    selecting aggregators must return to the very same values, holder ids and embeddings (a selection
+    has no memory), the accumulating ones to within the stated tolerance (Sec. 7: the delta method
+    may lose precision)."""
+    from util import row_rel_err
+    dims = (16, 24, 8)
+    cfg = synth.WorkloadConfig(6, "t", kind, agg, 2000, 16000, False, dims, 12, 200, False)
+    src, dst = synth.make_graph(cfg)
+    rng = np.random.default_rng(21)
+    X = rng.standard_normal((cfg.n_nodes, dims[0])).astype(np.float32)
+    h = Harness(cfg=cfg, graph=(cfg.n_nodes, src, dst), X=X, model=tiny_model(kind, agg, dims, seed=2, hidden=12),
+                precision="f32" if exact else "f64")
+    which = (0, 1, 2) if exact else (0, 1)
+    before = {(l, w): h.ink.get_layer(l, w) for l in (1, 2) for w in which}
+    have = set(h.keys.tolist())
+    s = rng.integers(0, cfg.n_nodes, size=600).astype(np.int32)
+    d = rng.integers(0, cfg.n_nodes, size=600).astype(np.int32)
+    new = np.array([a != b and int(k) not in have for a, b, k in zip(s, d, synth.edge_keys(s, d))])
+    _, first = np.unique(synth.edge_keys(s, d), return_index=True)
+    keep = np.zeros(s.size, bool); keep[first] = True
+    s, d = s[new & keep], d[new & keep]
+    assert s.size > 400
+    res, want = h.step(np.zeros(s.size, np.uint8), s, d, exact=exact)
+    assert res["n_applied_ins"] == s.size and want.size > 0
+    res, want = h.step(np.ones(s.size, np.uint8), s, d, exact=exact)
+    assert res["n_applied_del"] == s.size
+    if exact:
+        for (l, w), old in before.items():
+            assert np.array_equal(h.ink.get_layer(l, w).view(np.uint32), old.view(np.uint32)), (l, w)
+    else:       # against the oracle's inference of the restored snapshot, under the metric of the accumulated tables
+        h.check_state(exact=False)
+        print("restored to within", max(row_rel_err(h.ink.get_layer(l, w), old) for (l, w), old in before.items()))
+    h.check_graph()
+    h.check_bound()
+    h.ink.close()
