@@ -582,18 +582,13 @@ __device__ __forceinline__ void finish_target(const AggArgs &a, int v, const Cac
 // targets with the grid's wave count as stride.  One load per block brings the targets' ids and
 // segment bounds (lane j holds those of target j), so a target's own chain is: cached row and event
 // words (issued together), then the source rows.
-#ifdef INK_EV_MIN_WAVES
-#define INK_EV_ATTR __attribute__((amdgpu_waves_per_eu(INK_EV_MIN_WAVES)))
-#else
-#define INK_EV_ATTR
-#endif
 // INLINE: exposed rows of moderate length are recomputed by the wave that finds them instead of
 // being listed for a follow-up launch.  Measured: on large launches over 128-float rows the listing
 // form is 3 % faster (waves that recompute leave their neighbours in the block waiting), on rows of
 // 256 floats the inline form saves 0.1 of 0.9 ms of aggregation, and on short launches it saves a
 // launch.  The launcher picks per call.
 template <bool IS_MIN, int LPR, bool INLINE>
-__global__ __launch_bounds__(256) INK_EV_ATTR void k_agg_events(AggArgs a, const int32_t *targets, const int32_t *seg,
+__global__ __launch_bounds__(256) void k_agg_events(AggArgs a, const int32_t *targets, const int32_t *seg,
                                                     const int32_t *n_targets_p, const uint32_t *ev, uint64_t *chg,
                                                     int32_t *big_list, int32_t *exp_list, Counters *cnt) {
   constexpr int G = kWave / LPR;
