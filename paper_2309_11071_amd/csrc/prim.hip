@@ -96,15 +96,23 @@ __global__ __launch_bounds__(kSortThreads) void k_radix_hist(const uint32_t *key
 }
 
 // Each wave owns a contiguous run of kSortItems * 64 keys of the tile and walks it in rounds of
-// 64 consecutive keys, so ranks follow the input order (stability).
+// 64 consecutive keys, so ranks follow the input order (stability).  The pairs are first put in
+// digit order inside LDS and written out from there, so that neighbouring lanes store to
+// neighbouring addresses (runs of one digit) instead of 64 unrelated ones per instruction.
 __global__ __launch_bounds__(kSortThreads) void k_radix_scatter(const uint32_t *keys, const uint32_t *vals,
                                                                  uint32_t *okeys, uint32_t *ovals, int64_t n,
                                                                  int shift, const int32_t *hist_scanned, int nb) {
-  __shared__ int cnt[kSortWaves][kRadix];      // per-wave running digit counts
+  static_assert(kSortThreads == kRadix, "one thread per digit");
+  __shared__ int cnt[kSortWaves][kRadix];      // per-wave digit counts, then the wave's first slot of the digit in the tile
+  __shared__ int tile_first[kRadix];           // first slot of the digit in the tile
+  __shared__ int64_t out_first[kRadix];        // first position of the tile's keys of the digit in the output
+  __shared__ uint32_t skey[kSortTile], sval[kSortTile];
+  __shared__ int sm[kSortWaves + 1];
   int w = threadIdx.x / kWave, l = lane_id();
   for (int i = threadIdx.x; i < kSortWaves * kRadix; i += kSortThreads) (&cnt[0][0])[i] = 0;
   __syncthreads();
-  int64_t wbase = (int64_t)blockIdx.x * kSortTile + (int64_t)w * (kSortItems * kWave);
+  const int64_t tbase = (int64_t)blockIdx.x * kSortTile;
+  int64_t wbase = tbase + (int64_t)w * (kSortItems * kWave);
   uint32_t key[kSortItems], val[kSortItems];
   int rank[kSortItems];
 #pragma unroll
@@ -131,10 +139,17 @@ __global__ __launch_bounds__(kSortThreads) void k_radix_scatter(const uint32_t *
     if (leader) cnt[w][dg] = prev + before + 1;
   }
   __syncthreads();
-  // prefix over waves for each digit; thread t handles digit t
+  // thread t handles digit t: its total in the tile, the exclusive prefix over digits, the waves' slots
   {
-    int d = threadIdx.x;
-    int run = hist_scanned[(int64_t)d * nb + blockIdx.x];
+    const int d = threadIdx.x;
+    int tot = 0;
+#pragma unroll
+    for (int i = 0; i < kSortWaves; i++) tot += cnt[i][d];
+    int all;
+    int first = block_excl_scan<kSortThreads>(tot, sm, &all);
+    tile_first[d] = first;
+    out_first[d] = (int64_t)hist_scanned[(int64_t)d * nb + blockIdx.x];
+    int run = first;
 #pragma unroll
     for (int i = 0; i < kSortWaves; i++) {
       int c = cnt[i][d];
@@ -148,10 +163,19 @@ __global__ __launch_bounds__(kSortThreads) void k_radix_scatter(const uint32_t *
     int64_t i = wbase + k * kWave + l;
     if (i < n) {
       int dg = (key[k] >> shift) & (kRadix - 1);
-      int64_t pos = (int64_t)cnt[w][dg] + rank[k];
-      okeys[pos] = key[k];
-      ovals[pos] = val[k];
+      int slot = cnt[w][dg] + rank[k];
+      skey[slot] = key[k];
+      sval[slot] = val[k];
     }
+  }
+  __syncthreads();
+  const int in_tile = (int)(n - tbase < kSortTile ? n - tbase : kSortTile);
+  for (int s = threadIdx.x; s < in_tile; s += kSortThreads) {
+    uint32_t kk = skey[s];
+    int dg = (kk >> shift) & (kRadix - 1);
+    int64_t pos = out_first[dg] + (s - tile_first[dg]);
+    okeys[pos] = kk;
+    ovals[pos] = sval[s];
   }
 }
 
