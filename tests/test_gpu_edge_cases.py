@@ -359,3 +359,26 @@ def test_insert_then_delete_restores_the_cache(kind, agg, exact):
     h.check_graph()
     h.check_bound()
     h.ink.close()
+
+
+def test_expansion_over_sources_with_one_or_no_out_edge():
+    """Thousands of changed sources that have one out-edge or none: a wave of the expansion kernel
+    then covers hundreds of sources, runs of equal offsets included (sources without out-edges)."""
+    n, d = 20000, 8
+    ids = np.arange(n - 1, dtype=np.int32)
+    chain = ids[ids % 3 != 0]                                  # i -> i + 1, every third node has no out-edge
+    src = np.concatenate([chain, arr([n - 1, n - 1])])
+    dst = np.concatenate([chain + 1, arr([0, 1])])
+    rng = np.random.default_rng(13)
+    X = rng.standard_normal((n, d)).astype(np.float32)
+    h = Harness(graph=(n, src, dst), X=X, model=tiny_model("sage", "max", (d, 8, 8), seed=6))
+    h.check_state()
+    targets = rng.choice(np.arange(2, n - 1), size=9000, replace=False).astype(np.int32)
+    res, want = h.step(np.zeros(targets.size, np.uint8), np.full(targets.size, n - 1, np.int32), targets)
+    st = h.ink.stats()["layers"]
+    assert st[1]["n_sources"] > 5000 and st[1]["n_events"] > 9000 + 3000
+    h.check_state()
+    res, want = h.step(np.ones(targets.size, np.uint8), np.full(targets.size, n - 1, np.int32), targets)
+    h.check_state()
+    h.check_graph()
+    h.ink.close()
