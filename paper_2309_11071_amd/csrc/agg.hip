@@ -390,10 +390,11 @@ __device__ __forceinline__ void load_cached(const AggArgs &a, int v, bool lane_o
 template <int U> struct EvBatch { uint32_t code[U]; float4 row[U]; };
 
 // events it + u G + g (u < U) of the window `mine` (lane j holds event j, cntw of them are real)
-template <int LPR, int U>
+template <bool IS_MIN, int LPR, int U>
 __device__ __forceinline__ void issue_batch(const AggArgs &a, uint32_t mine, int it, int cntw, bool lane_on, int q,
                                             EvBatch<U> &b) {
   constexpr int G = kWave / LPR;
+  const float W = worst<IS_MIN>();
   const int g = lane_id() / LPR;
 #pragma unroll
   for (int u = 0; u < U; u++) {
@@ -401,7 +402,7 @@ __device__ __forceinline__ void issue_batch(const AggArgs &a, uint32_t mine, int
     const uint32_t x = __shfl(mine, k < kWave ? k : 0, kWave);
     const bool valid = k < cntw && lane_on;
     b.code[u] = valid ? x : kEvNone;
-    b.row[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+    b.row[u] = make_float4(W, W, W, W);        // an event without a row offers the worst value: it never wins
     if (valid && (x >> kEvKindShift) != EV_DEL) b.row[u] = ld4(a.M + (int64_t)(x & kEvIdMask) * a.ldm + 4 * q);
   }
 }
@@ -410,7 +411,7 @@ template <bool IS_MIN> struct EvAcc {
   F4 cv; I4 ci; F4 cs;       // best candidate, its source, runner-up candidate value
   bool reset[4];             // per dimension: the holder left or got worse
   bool inv2[4];              // per dimension: the recorded runner-up left or changed its message
-  bool any_del;              // the segment cancels something: a removed edge or a changed source
+  bool any_del;              // wave-uniform: the segment cancels something (a removed edge or a changed source)
   __device__ __forceinline__ void init() {
     any_del = false;
 #pragma unroll
@@ -422,30 +423,49 @@ template <bool IS_MIN> struct EvAcc {
 };
 
 // Written without branches: the per-lane conditions become wave masks in scalar registers and the
-// updates selects, a fraction of the instructions the branching form compiles to (this loop runs
-// once per event and lane group and is half of the kernel's vector instructions).
+// updates selects and min / max (this loop runs once per event and lane group and is half of the
+// kernel's vector instructions, and the kernel's time follows their number).  What keeps it short:
+//  * an event without a row (a removed edge, an empty slot) carries the worst value, so it needs no
+//    mask of its own: it never becomes a candidate, and as "new value of the holder" it is a reset;
+//  * an inserted edge cannot name the old holder or runner-up (it was no neighbour), so the id
+//    tests need no kind;
+//  * the runner-up among the candidates is max(cs, min(r, cv)) (mirrored for min) whichever of the
+//    two wins;
+//  * TIES false (wave-uniform): the candidates so far are changed sources in ascending id order (the order the
+//    events are created in), so on equal values the earlier one keeps the dimension and the id
+//    comparison is skipped.  The caller sets TIES from a target's first inserted edge on.
+// v_max_f32 / v_min_f32 as they are: the library forms first canonicalise both operands (two more
+// instructions each), which matters in a loop whose time follows its instruction count.  No NaN
+// reaches them (inputs are finite, the sentinels are infinities).
+__device__ __forceinline__ float vmax(float a, float b) { float d; asm("v_max_f32 %0, %1, %2" : "=v"(d) : "v"(a), "v"(b)); return d; }
+__device__ __forceinline__ float vmin(float a, float b) { float d; asm("v_min_f32 %0, %1, %2" : "=v"(d) : "v"(a), "v"(b)); return d; }
+
 template <bool IS_MIN, int U>
-__device__ __forceinline__ void consume_batch(const EvBatch<U> &b, const Cached<IS_MIN> &k, EvAcc<IS_MIN> &s) {
+__device__ __forceinline__ void consume_batch(const EvBatch<U> &b, const Cached<IS_MIN> &k, EvAcc<IS_MIN> &s, bool TIES) {
 #pragma unroll
   for (int u = 0; u < U; u++) {
     const uint32_t x = b.code[u];
-    const uint32_t kind = x >> kEvKindShift;           // 3 for "no event"
-    const int id = (int)(x & kEvIdMask);
-    const bool is_del = kind == EV_DEL, is_add = kind == EV_ADD, is_chg = kind == EV_CHG;
-    const bool cancels = is_del | is_chg, has_row = is_add | is_chg;
-    s.any_del |= cancels;
+    const int id = (int)(x & kEvIdMask);               // "no event": an id no node has
     const float r[4] = {b.row[u].x, b.row[u].y, b.row[u].z, b.row[u].w};
+    bool first[4];
 #pragma unroll
     for (int c = 0; c < 4; c++) {      // & and | on purpose: no short-circuit, no branch
-      const bool holds = k.oi.v[c] == id;
-      s.inv2[c] |= cancels & (k.o2.v[c] == id);
-      s.reset[c] |= holds & (is_del | (is_chg & better<IS_MIN>(k.ov.v[c], r[c])));
-      // take2, applied only where the event carries a row
-      const bool first = has_row & (better<IS_MIN>(r[c], s.cv.v[c]) | ((r[c] == s.cv.v[c]) & (id < s.ci.v[c])));
-      const bool second = has_row & !first & better<IS_MIN>(r[c], s.cs.v[c]);
-      s.cs.v[c] = first ? s.cv.v[c] : (second ? r[c] : s.cs.v[c]);
-      s.cv.v[c] = first ? r[c] : s.cv.v[c];
-      s.ci.v[c] = first ? id : s.ci.v[c];
+      s.inv2[c] |= k.o2.v[c] == id;
+      s.reset[c] |= (k.oi.v[c] == id) & better<IS_MIN>(k.ov.v[c], r[c]);
+      first[c] = better<IS_MIN>(r[c], s.cv.v[c]);
+    }
+    if (TIES) {
+      asm volatile("");                // keeps this a (wave-uniform) branch: only targets with an inserted edge pay for it
+      const uint32_t kind = x >> kEvKindShift;
+      const bool has_row = (kind == EV_ADD) | (kind == EV_CHG);
+#pragma unroll
+      for (int c = 0; c < 4; c++) first[c] |= has_row & (r[c] == s.cv.v[c]) & (id < s.ci.v[c]);
+    }
+#pragma unroll
+    for (int c = 0; c < 4; c++) {
+      s.cs.v[c] = IS_MIN ? vmin(s.cs.v[c], vmax(r[c], s.cv.v[c])) : vmax(s.cs.v[c], vmin(r[c], s.cv.v[c]));
+      s.cv.v[c] = first[c] ? r[c] : s.cv.v[c];
+      s.ci.v[c] = first[c] ? id : s.ci.v[c];
     }
   }
 }
@@ -475,6 +495,7 @@ __device__ __forceinline__ void finish_target(const AggArgs &a, int v, const Cac
   // covers be settled by promotion instead of a recompute, once per dimension between recomputes.
   F4 nv = ov; I4 ni = oi; F4 nu = ou; I4 n2;
   bool exposed = false;
+  bool vchg = false, ichg = false, uchg = false;      // what of the cached row changes (short live ranges: per dimension)
 #pragma unroll
   for (int c = 0; c < 4; c++) {
     const bool has_cand = ci.v[c] != 0x7fffffff;
@@ -514,12 +535,15 @@ __device__ __forceinline__ void finish_target(const AggArgs &a, int v, const Cac
         n2.v[c] = better<IS_MIN>(ou.v[c], cv.v[c]) ? r2 : -1;
       }
     }
+    vchg |= (4 * q + c < a.d) & (__float_as_uint(ov.v[c]) != __float_as_uint(nv.v[c]));
+    ichg |= oi.v[c] != ni.v[c];
+    uchg |= (__float_as_uint(ou.v[c]) != __float_as_uint(nu.v[c])) | (o2.v[c] != n2.v[c]);
   }
   exposed = __ballot(exposed && lane_on) != 0ull;
   if (a.count_cond) {   // condition of this target (Sec. 2.5.1; the distribution shown in Sec. 5.2)
     bool rs = (reset[0] || reset[1] || reset[2] || reset[3]) && lane_on;
     bool any_reset = __ballot(rs) != 0ull;
-    bool dl = __ballot(s.any_del) != 0ull;
+    bool dl = s.any_del;
     if (l == 0 && !exposed) {
       int which = !dl ? ST_NODEL : (!any_reset ? ST_NOEFFECT : ST_COVERED);
       atomicAdd(&cnt->stripe[blockIdx.x % kStripes][which], 1ull);
@@ -556,15 +580,8 @@ __device__ __forceinline__ void finish_target(const AggArgs &a, int v, const Cac
   // each half of the cached row is rewritten only if it changed: most targets keep their bound and
   // runner-up, many keep value and holder
   const bool writer = lane_on && l < LPR;
-  bool vchg = false;
+  vchg &= writer;
   if (writer) {
-    bool ichg = false, uchg = false;
-#pragma unroll
-    for (int c = 0; c < 4; c++) {
-      if (4 * q + c < a.d) vchg |= __float_as_uint(ov.v[c]) != __float_as_uint(nv.v[c]);
-      ichg |= oi.v[c] != ni.v[c];
-      uchg |= __float_as_uint(ou.v[c]) != __float_as_uint(nu.v[c]) || o2.v[c] != n2.v[c];
-    }
     if (vchg || ichg) {
       *reinterpret_cast<float4 *>(a.A + (int64_t)v * a.ld + 4 * q) = make_float4(nv.v[0], nv.v[1], nv.v[2], nv.v[3]);
       *reinterpret_cast<int4 *>(a.ARG + (int64_t)v * a.ld + 4 * q) = make_int4(ni.v[0], ni.v[1], ni.v[2], ni.v[3]);
@@ -613,14 +630,20 @@ __global__ __launch_bounds__(256) void k_agg_events(AggArgs a, const int32_t *ta
       load_cached<IS_MIN>(a, v, lane_on, q, c);
       EvAcc<IS_MIN> s;
       s.init();
+      bool ties = false;
       for (int eb = e0; eb < e1; eb += kWave) {
         const int ee = eb + l;
         const uint32_t mine = ee < e1 ? ev[ee] : kEvNone;
         const int cntw = e1 - eb < kWave ? e1 - eb : kWave;
+        // wave-uniform: from the first inserted edge of the window on, equal values are settled by id
+        const uint64_t adds = __ballot(ee < e1 && (mine >> kEvKindShift) == EV_ADD);
+        s.any_del |= __ballot(ee < e1 && (mine >> kEvKindShift) != EV_ADD) != 0ull;
+        const int first_add = adds ? __builtin_ctzll(adds) : kWave;
         for (int it = 0; it < cntw; it += G * U) {
           EvBatch<U> bx;
-          issue_batch<LPR, U>(a, mine, it, cntw, lane_on, q, bx);
-          consume_batch<IS_MIN, U>(bx, c, s);
+          issue_batch<IS_MIN, LPR, U>(a, mine, it, cntw, lane_on, q, bx);
+          ties |= it + G * U > first_add;
+          consume_batch<IS_MIN, U>(bx, c, s, ties);
         }
       }
       finish_target<IS_MIN, LPR, INLINE>(a, v, c, s, lane_on, q, chg, big_list, exp_list, cnt);

@@ -29,7 +29,12 @@ static inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
 static inline dim3 grid1(int64_t n, int per = 256) { return dim3((unsigned)std::max<int64_t>(1, (n + per - 1) / per)); }
 
 // ------------------------------------------------------------------------------------ kernels
-// event i of the applied edge changes: deletions first, then insertions; key = target
+// The events of a layer are created in this order: removed edges, changed sources (by ascending
+// source, each over its kept out-edges), inserted edges.  The grouping is stable, so every target
+// sees its events in that order: among the events that carry a row, the changed sources come first
+// and in ascending id order, which is what lets the max / min kernel drop the id comparison of ties
+// until the first inserted edge shows up (consume_batch in agg.hip).
+// seed i of the applied edge changes: deletions first, then insertions; key = target
 __device__ __forceinline__ void seed_event(int i, const int32_t *del_s, const int32_t *del_d, const int32_t *ins_s,
                                            const int32_t *ins_d, int n_del, uint32_t *key, uint32_t *val) {
   if (i < n_del) { *key = (uint32_t)del_d[i]; *val = (EV_DEL << kEvKindShift) | (uint32_t)del_s[i]; }
@@ -39,10 +44,13 @@ __device__ __forceinline__ void seed_event(int i, const int32_t *del_s, const in
   }
 }
 
+// deletions go to [0, n_del), insertions behind the n_chg events of the changed sources
 __global__ void k_seed_events(const int32_t *del_s, const int32_t *del_d, const int32_t *ins_s, const int32_t *ins_d,
-                              int n_del, int n_ins, uint32_t *key, uint32_t *val) {
+                              int n_del, int n_ins, int64_t n_chg, uint32_t *key, uint32_t *val) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n_del + n_ins) seed_event((int)i, del_s, del_d, ins_s, ins_d, n_del, &key[i], &val[i]);
+  if (i >= n_del + n_ins) return;
+  const int64_t p = i < n_del ? i : i + n_chg;
+  seed_event((int)i, del_s, del_d, ins_s, ins_d, n_del, &key[p], &val[p]);
 }
 
 // out-edges of a changed source that exist in both snapshots: the block minus the ids appended
@@ -123,7 +131,7 @@ __global__ __launch_bounds__(64) void k_publish(const Counters *d, HostCounters 
 }
 
 // A layer with few events (at most THREADS * ITEMS): clearing the counters, creating the events,
-// grouping them by target (stable, so deletions stay ahead of insertions ahead of changes) and
+// grouping them by target (stable, so deletions stay ahead of changes ahead of insertions) and
 // the segment heads in one workgroup.  Output as from the separate kernels: val in grouped
 // order, the distinct targets, the start of each target's events plus the closing offset, and
 // the target count in the counter block.
@@ -144,8 +152,9 @@ __global__ __launch_bounds__(THREADS) void k_small_group(const int32_t *del_s, c
   const int n_seed = n_del + n_ins, nE = n_seed + n_chg;
   for (int e = threadIdx.x; e < nE; e += THREADS) {
     uint32_t k, v;
-    if (e < n_seed) seed_event(e, del_s, del_d, ins_s, ins_d, n_del, &k, &v);
-    else expand_event(e - n_seed, F, nF, pref, off, ids, payload_index, &k, &v);
+    if (e < n_del) seed_event(e, del_s, del_d, ins_s, ins_d, n_del, &k, &v);
+    else if (e < n_del + n_chg) expand_event(e - n_del, F, nF, pref, off, ids, payload_index, &k, &v);
+    else seed_event(e - n_chg, del_s, del_d, ins_s, ins_d, n_del, &k, &v);
     S.sk[e] = k; S.sv[e] = v;
   }
   small_sort_lds<THREADS, ITEMS>(S, nE, passes);
@@ -1013,11 +1022,11 @@ static ink_status layer_aggregate(ink_ctx *c, int l, const int32_t *F, int64_t n
       if (n_seed > 0)
         hipLaunchKernelGGL(k_seed_events, grid1(n_seed), dim3(256), 0, s, (const int32_t *)c->del_src,
                            (const int32_t *)c->del_dst, (const int32_t *)c->ins_src, (const int32_t *)c->ins_dst,
-                           (int)n_del, (int)n_ins, key, val);
+                           (int)n_del, (int)n_ins, (int64_t)n_chg, key, val);
       if (n_chg > 0)
         hipLaunchKernelGGL(k_expand_events, grid1(n_chg, 256 / kWave * kExpandPerWave), dim3(256), 0, s, F, (int)nF,
                            (const int32_t *)c->f_pref.as<int32_t>(), (int)n_chg, (const int64_t *)c->gout.off,
-                           (const int32_t *)c->gout.ids, key + n_seed, val + n_seed, c->is_select ? 0 : 1);
+                           (const int32_t *)c->gout.ids, key + n_del, val + n_del, c->is_select ? 0 : 1);
       API_TRY(hipGetLastError());
     }
     Prof p(c, INK_T_GROUP);
