@@ -607,7 +607,7 @@ __device__ __forceinline__ void finish_target(const AggArgs &a, int v, const Cac
 template <bool IS_MIN, int LPR, bool INLINE>
 __global__ __launch_bounds__(256) void k_agg_events(AggArgs a, const int32_t *targets, const int32_t *seg,
                                                     const int32_t *n_targets_p, const uint32_t *ev, uint64_t *chg,
-                                                    int32_t *big_list, int32_t *exp_list, Counters *cnt) {
+                                                    int32_t *big_list, int32_t *exp_list, Counters *cnt, int ev_block) {
   constexpr int G = kWave / LPR;
   constexpr int U = INK_EV_U;
   static_assert(kEvBlock + 2 <= kWave, "a lane per target and bound of the block");
@@ -615,12 +615,12 @@ __global__ __launch_bounds__(256) void k_agg_events(AggArgs a, const int32_t *ta
   const int q = l % LPR;
   const bool lane_on = 4 * q < a.wd;
   const int n = *n_targets_p;
-  const int n_blk = (n + kEvBlock - 1) / kEvBlock;
+  const int n_blk = (n + ev_block - 1) / ev_block;      // ev_block <= kEvBlock: 1 for short launches, whose targets should not queue behind each other in one wave
   const int n_waves = (int)gridDim.x * (int)(blockDim.x / kWave);
   const int wave0 = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave));
   for (int blk = wave0; blk < n_blk; blk += n_waves) {
-    const int w0 = blk * kEvBlock;
-    const int kt = n - w0 < kEvBlock ? n - w0 : kEvBlock;
+    const int w0 = blk * ev_block;
+    const int kt = n - w0 < ev_block ? n - w0 : ev_block;
     const int my_t = targets[w0 + (l < kt ? l : kt - 1)];
     const int my_s = seg[w0 + (l <= kt ? l : kt)];
     for (int t = 0; t < kt; t++) {
@@ -709,16 +709,17 @@ static hipError_t events_t(ink_ctx *c, const AggArgs &a_in, const int32_t *targe
   a.big_deg = big_threshold(n_targets, LPR, kBigDeg);
   INK_TRY(ensure_big_buffers(c, a.wd, true));
   INK_TRY(c->exp_list.reserve((size_t)n_targets * 4));
-  int64_t blocks = std::min<int64_t>(((n_targets + kEvBlock - 1) / kEvBlock + 3) / 4, INK_EVENT_GRID);
+  const int ev_block = latency_mode(n_targets) ? 1 : kEvBlock;
+  int64_t blocks = std::min<int64_t>(((n_targets + ev_block - 1) / ev_block + 3) / 4, INK_EVENT_GRID);
   const bool inline_exposed = INK_EV_INLINE_WIDE == 0 ? false : (LPR >= (INK_EV_INLINE_WIDE == 1 ? 64 : (INK_EV_INLINE_WIDE == 2 ? 32 : 16)) || latency_mode(n_targets));
   {
     KernelTimer kt(c, a.layer, INK_K_AGG_EVENTS);
     if (inline_exposed)
       hipLaunchKernelGGL((k_agg_events<IS_MIN, LPR, true>), dim3((unsigned)blocks), dim3(256), 0, c->stream, a, targets, seg,
-                         n_targets_dev, ev, chg, c->big_list.as<int32_t>(), c->exp_list.as<int32_t>(), c->d_cnt);
+                         n_targets_dev, ev, chg, c->big_list.as<int32_t>(), c->exp_list.as<int32_t>(), c->d_cnt, ev_block);
     else
       hipLaunchKernelGGL((k_agg_events<IS_MIN, LPR, false>), dim3((unsigned)blocks), dim3(256), 0, c->stream, a, targets, seg,
-                         n_targets_dev, ev, chg, c->big_list.as<int32_t>(), c->exp_list.as<int32_t>(), c->d_cnt);
+                         n_targets_dev, ev, chg, c->big_list.as<int32_t>(), c->exp_list.as<int32_t>(), c->d_cnt, ev_block);
     INK_TRY(hipGetLastError());
   }
   if (!inline_exposed) {
